@@ -1,0 +1,303 @@
+"""Pins for the cluster-quantization half of the CPU oracle (paper: "Cluster Based Quantization
+for Optimizer States", Eq. qmap-distance, the S/b definition, Eq. decluster, the size analysis,
+Algorithm 2).  Every reference value below comes from the paper (tests/golden), from a closed
+form, from a numpy/stdlib routine that is the textbook form of one step, or from brute force.
+"""
+import math
+import statistics
+from decimal import Decimal, getcontext
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2511_12376_amd import synth
+
+
+# ---------------------------------------------------------------------------------------------
+# step 2: normal quantiles
+# ---------------------------------------------------------------------------------------------
+def _quantile_decimal(k, m):
+    """Phi^{-1}(k/m) to ~60 digits: Taylor series of erf plus Newton, all in Decimal."""
+    getcontext().prec = 70
+    pi = Decimal("3.14159265358979323846264338327950288419716939937510582097494459230781640628620899862803")
+    p = Decimal(k) / Decimal(m)
+
+    def cdf(z):
+        x = z / Decimal(2).sqrt()
+        s, term, n = Decimal(0), x, 0
+        while True:
+            t = term / (2 * n + 1)
+            s += t
+            if abs(t) < Decimal(10) ** -65:
+                break
+            n += 1
+            term = -term * x * x / n
+        return (1 + 2 * s / pi.sqrt()) / 2
+
+    z = Decimal(0)
+    for _ in range(100):
+        dz = (cdf(z) - p) * (2 * pi).sqrt() / (-(z * z) / 2).exp()
+        z -= dz
+        if abs(dz) < Decimal(10) ** -60:
+            break
+    return z
+
+
+@pytest.mark.parametrize("m", [2, 3, 4, 7, 16])
+def test_quantiles_are_correctly_rounded(m):
+    nd = statistics.NormalDist()
+    for k in range(1, m):
+        z = oracle.norm_quantile(k, m)
+        assert z == float(_quantile_decimal(k, m))            # nearest double to the exact value
+        assert z == pytest.approx(nd.inv_cdf(k / m), abs=1e-15)
+        assert z == -oracle.norm_quantile(m - k, m)
+    assert [oracle.norm_quantile(k, m) for k in range(1, m)] == sorted(oracle.norm_quantile(k, m) for k in range(1, m))
+
+
+def test_equal_probability_edges():
+    # each of the m intervals carries probability 1/m under N(mu, sigma)
+    nd = statistics.NormalDist(0.25, 3.0)
+    e = oracle.cluster_edges(0.25, 3.0, 16).astype(np.float64)
+    cdf = np.array([0.0] + [nd.cdf(v) for v in e] + [1.0])
+    assert np.allclose(np.diff(cdf), 1 / 16, atol=1e-7)
+    assert e[7] == 0.25                                         # the middle edge is the mean
+
+
+# ---------------------------------------------------------------------------------------------
+# step 1: mean and standard deviation
+# ---------------------------------------------------------------------------------------------
+def test_fit_exact_on_integers():
+    x = np.array([1, 2, 3, 4, 5, 6, 7, 8], np.float32)        # mean 4.5, population variance 5.25
+    mu, sg = oracle.cluster_fit(x)
+    assert mu == np.float32(4.5)
+    assert sg == np.float32(math.sqrt(5.25))                    # a sample (n-1) deviation would give sqrt(6)
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_fit_against_exact_summation(seed):
+    rng = np.random.default_rng(seed)
+    x = (rng.standard_normal(4096) * 10.0 ** rng.integers(-6, 3) + rng.standard_normal() * 1e-3).astype(np.float32)
+    mu, sg = oracle.cluster_fit(x)
+    xs = [float(v) for v in x]
+    mean = math.fsum(xs) / len(xs)
+    var = math.fsum((v - mean) ** 2 for v in xs) / len(xs)
+    ulp = lambda v: float(np.spacing(np.float32(abs(v))))
+    assert abs(float(mu) - mean) <= 0.5 * ulp(mean) * 1.001 + 1e-300
+    assert abs(float(sg) - math.sqrt(var)) <= 0.5 * ulp(math.sqrt(var)) * 1.001
+    assert float(sg) == pytest.approx(float(np.std(x.astype(np.float64))), rel=1e-7)
+
+
+# ---------------------------------------------------------------------------------------------
+# step 3: labels
+# ---------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("m", [1, 2, 3, 5, 16])
+def test_labels_equal_searchsorted(m):
+    rng = np.random.default_rng(m)
+    x = (rng.standard_normal(5000) * 2 + 1).astype(np.float32)
+    q = oracle.quantize_cluster(x, G=0, m=m)
+    edges = q["fit"][0, 2:]
+    assert edges.size == m - 1
+    x[: m - 1] = edges                                          # values exactly on an edge go to the upper cluster
+    q = oracle.quantize_cluster(x, G=0, m=m, fit_in=q["fit"][:, :2])
+    lab = oracle.unpack_labels(q["labels"], x.size)
+    assert np.array_equal(lab, np.searchsorted(edges, x, side="right"))
+    assert lab.max() <= m - 1
+    # labels are monotone in x
+    order = np.argsort(x, kind="stable")
+    assert np.all(np.diff(lab[order].astype(int)) >= 0)
+
+
+def test_clusters_balanced_on_normal_data():
+    rng = np.random.default_rng(5)
+    n = 1 << 20
+    x = (rng.standard_normal(n) * 3e-4 + 1e-5).astype(np.float32)
+    q = oracle.quantize_cluster(x, G=0, m=16)
+    cnt = np.bincount(oracle.unpack_labels(q["labels"], n), minlength=16)
+    assert np.all(np.abs(cnt - n / 16) < 4 * math.sqrt(n / 16))
+
+
+# ---------------------------------------------------------------------------------------------
+# step 4: S and b; steps 5-6: codes; dequantisation
+# ---------------------------------------------------------------------------------------------
+def _per_cluster_minmax(x, lab, m):
+    S = np.zeros(m, np.float32)
+    b = np.zeros(m, np.float32)
+    for c in range(m):
+        sel = x[lab == c]
+        if sel.size:
+            b[c] = sel.min()
+            S[c] = np.float32(sel.max()) - np.float32(sel.min())
+    return S, b
+
+
+@pytest.mark.parametrize("G", [0, 4096, 1000])
+def test_params_are_cluster_min_and_range(G):
+    rng = np.random.default_rng(11)
+    n = 3 * 4096 + 123
+    x = (rng.standard_normal(n) * 1e-4).astype(np.float32)
+    q = oracle.quantize_cluster(x, G=G, m=16)
+    g_size = n if G == 0 else G
+    for g in range(oracle.n_groups(n, G)):
+        xs = x[g * g_size:(g + 1) * g_size]
+        lab = np.searchsorted(q["fit"][g, 2:], xs, side="right")
+        S, b = _per_cluster_minmax(xs, lab, 16)
+        assert np.array_equal(q["params"][g, :, 0], S)
+        assert np.array_equal(q["params"][g, :, 1], b)
+
+
+def test_error_bound_endpoints_and_monotone_codes():
+    rng = np.random.default_rng(3)
+    n = 8 * 4096
+    for x in [(rng.standard_normal(n) * 1e-4).astype(np.float32),
+              (rng.standard_normal(n).astype(np.float32) ** 2 * np.exp(rng.standard_normal(n)).astype(np.float32) * 1e-8)]:
+        q = oracle.quantize_cluster(x, G=4096, m=16)
+        xh = oracle.dequantize_cluster(q["codes"], q["labels"], q["params"], n, 4096, 16)
+        lab = oracle.unpack_labels(q["labels"], n)
+        grp = np.arange(n) // 4096
+        S = q["params"][grp, lab, 0].astype(np.float64)
+        b = q["params"][grp, lab, 1].astype(np.float64)
+        ulp = np.spacing(np.abs(x)).astype(np.float64)
+        # half the spacing of the 256 levels inside the element's own cluster
+        assert np.all(np.abs(x.astype(np.float64) - xh) <= S / 510 * (1 + 1e-5) + 2 * ulp)
+        # code 0 is the cluster minimum (exactly), code 255 the maximum (to an ulp)
+        lo = q["codes"] == 0
+        assert np.array_equal(xh[lo], q["params"][grp, lab, 1][lo])
+        hi = (q["codes"] == 255)
+        assert np.all(np.abs(xh[hi] - (b + S)[hi]) <= 2 * np.spacing(np.abs((b + S)[hi]).astype(np.float32)))
+        # every non-empty cluster with S > 0 uses both end codes
+        for g in range(n // 4096):
+            for c in range(16):
+                sel = (grp == g) & (lab == c)
+                if sel.any() and q["params"][g, c, 0] > 0:
+                    assert q["codes"][sel].min() == 0 and q["codes"][sel].max() == 255
+        # inside a cluster, codes do not decrease with x
+        key = (grp.astype(np.int64) * 16 + lab) * 2.0 ** 40
+        order = np.lexsort((x, key))
+        same = np.diff(key[order]) == 0
+        assert np.all(np.diff(q["codes"][order].astype(int))[same] >= 0)
+
+
+@pytest.mark.parametrize("m", [1, 2, 4, 16])
+def test_codes_against_bruteforce_argmin(m):
+    """Eq. qmap-distance by exhaustive search, n <= 64."""
+    rng = np.random.default_rng(100 + m)
+    for trial in range(20):
+        n = int(rng.integers(1, 65))
+        x = (rng.standard_normal(n) * 10.0 ** rng.integers(-8, 2)).astype(np.float32)
+        q = oracle.quantize_cluster(x, G=0, m=m)
+        lab = oracle.unpack_labels(q["labels"], n)
+        S, b = q["params"][0, :, 0], q["params"][0, :, 1]
+        # (a) own-cluster argmin over the 256 levels, in fp64
+        for i in range(n):
+            j, gap = oracle.code_bruteforce(x[i], b[lab[i]], S[lab[i]])
+            t = (float(x[i]) - float(b[lab[i]])) / float(S[lab[i]]) * 255 if S[lab[i]] > 0 else 0.0
+            if q["codes"][i] != j:
+                assert abs(int(q["codes"][i]) - j) == 1 and gap < 1e-4 / 255, (x[i], j, q["codes"][i], t)
+        # (b) the (label, code) pair is the nearest of all m*256 centroids b_c + j*S_c/255
+        cent = b.astype(np.float64)[:, None] + np.arange(256)[None, :] * (S.astype(np.float64)[:, None] / 255)
+        used = np.zeros(m, bool)
+        used[np.unique(lab)] = True
+        cent[~used] = np.inf                                     # empty clusters hold no centroid
+        d_all = np.abs(cent[None, :, :] - x.astype(np.float64)[:, None, None]).reshape(n, -1).min(axis=1)
+        d_own = np.abs(cent[lab, q["codes"]] - x.astype(np.float64))
+        assert np.all(d_own <= d_all + 1e-4 * np.maximum(S[lab], 1e-45) / 255 + np.spacing(np.abs(x)).astype(np.float64))
+
+
+def test_one_cluster_is_plain_minmax_uint8():
+    """m = 1 is the per-tensor [0,255] packing the paper calls naive 8-bit quantisation."""
+    rng = np.random.default_rng(9)
+    x = (rng.standard_normal(10000) * 1e-3).astype(np.float32)
+    q = oracle.quantize_cluster(x, G=0, m=1)
+    mn, mx = float(x.min()), float(x.max())
+    ref = (x.astype(np.float64) - mn) / (mx - mn) * 255
+    code = np.rint(ref)
+    diff = q["codes"].astype(np.int64) - code.astype(np.int64)
+    near_tie = np.abs(ref - np.floor(ref) - 0.5) < 1e-4
+    assert np.all((diff == 0) | (near_tie & (np.abs(diff) == 1)))
+    assert np.count_nonzero(diff) <= 3
+    assert q["params"][0, 0, 0] == np.float32(mx) - np.float32(mn) and q["params"][0, 0, 1] == np.float32(mn)
+    assert np.all(q["labels"] == 0)
+    xh = oracle.dequantize_cluster(q["codes"], q["labels"], q["params"], x.size, 0, 1)
+    assert np.allclose(xh, mn + code / 255 * (mx - mn), rtol=0, atol=(mx - mn) / 255 * 1.001)
+
+
+def test_dequantize_formula():
+    # Q(j) * S + b on hand-made inputs: 2 clusters, group of 4
+    params = np.array([[[2.55, -1.0], [510.0, 100.0]]], np.float32)       # (S, b)
+    codes = np.array([0, 100, 255, 1], np.uint8)
+    labels = np.array([0 | (0 << 4), 1 | (1 << 4)], np.uint8)               # elements 0,1 -> cluster 0; 2,3 -> cluster 1
+    out = oracle.dequantize_cluster(codes, labels, params, 4, 0, 2)
+    want = [-1.0, -1.0 + 100 * (2.55 / 255), 100.0 + 510.0, 100.0 + 2.0]
+    assert np.allclose(out, want, rtol=1e-6)
+    assert out[0] == np.float32(-1.0) and out[2] == np.float32(610.0) and out[3] == np.float32(102.0)
+
+
+def test_stored_size_formula(golden):
+    n, m = 1 << 16, 16
+    x = np.random.default_rng(1).standard_normal(n).astype(np.float32)
+    q = oracle.quantize_cluster(x, G=0, m=m)
+    stored = q["codes"].nbytes + q["labels"].nbytes + q["params"].nbytes + 8     # + 8 for the 2-D shape
+    assert stored == golden["quant_bytes_slope"] * n + golden["quant_bytes_const"]
+    assert q["params"].nbytes == 8 * m and q["labels"].nbytes == n // 2
+    assert 4 * n / stored == pytest.approx(golden["quant_ratio"], abs=0.01)
+    assert oracle.unpack_labels(q["labels"], n).max() < golden["quant_clusters_max"]
+    # grouped variant: 128 bytes of (S, b) per 4096-element group
+    q = oracle.quantize_cluster(x, G=4096, m=m)
+    assert q["params"].nbytes == 128 * (n // 4096)
+
+
+# ---------------------------------------------------------------------------------------------
+# degenerate inputs
+# ---------------------------------------------------------------------------------------------
+def test_degenerate_groups():
+    # constant group: sigma = 0, every edge equals mu, every element lands in the top cluster
+    x = np.full(4096, 3.25, np.float32)
+    q = oracle.quantize_cluster(x, G=4096, m=16)
+    assert q["fit"][0, 1] == 0 and np.all(q["fit"][0, 2:] == np.float32(3.25))
+    assert np.all(oracle.unpack_labels(q["labels"], 4096) == 15) and np.all(q["codes"] == 0)
+    assert q["params"][0, 15].tolist() == [0.0, 3.25] and np.all(q["params"][0, :15] == 0)
+    assert np.array_equal(oracle.dequantize_cluster(q["codes"], q["labels"], q["params"], 4096), x)
+    # single element
+    q = oracle.quantize_cluster(np.array([-7.5], np.float32), G=4096, m=16)
+    assert q["labels"].tolist() == [15] and q["codes"].tolist() == [0]
+    assert oracle.dequantize_cluster(q["codes"], q["labels"], q["params"], 1).tolist() == [-7.5]
+    # one outlier: it sits alone in an end cluster and is reproduced exactly
+    rng = np.random.default_rng(2)
+    x = (rng.standard_normal(4096) * 1e-4).astype(np.float32)
+    x[1234] = 5.0
+    q = oracle.quantize_cluster(x, G=4096, m=16)
+    xh = oracle.dequantize_cluster(q["codes"], q["labels"], q["params"], 4096)
+    assert xh[1234] == np.float32(5.0)
+    # odd n: the unused high nibble of the last label byte is zero; short last group has its own fit
+    n = 4096 + 37
+    x = (rng.standard_normal(n)).astype(np.float32)
+    q = oracle.quantize_cluster(x, G=4096, m=16)
+    assert q["labels"].size == (n + 1) // 2 and (q["labels"][-1] >> 4) == 0
+    mu, sg = oracle.cluster_fit(x[4096:])
+    assert q["fit"][1, 0] == mu and q["fit"][1, 1] == sg
+    # a range so small that 255/S overflows: codes are 0, S is still stored
+    tiny = np.float32(1e-40)
+    x = np.array([0.0, tiny], np.float32)
+    q = oracle.quantize_cluster(x, G=0, m=1)
+    assert q["codes"].tolist() == [0, 0] and q["params"][0, 0, 0] == tiny
+
+
+def test_fit_injection_and_adam_second_moment_occupancy():
+    d = synth.make_tensor_np(synth.config(0), 2)
+    v = d["v"][: 16 * 4096]
+    q = oracle.quantize_cluster(v, G=4096, m=16)
+    q2 = oracle.quantize_cluster(v, G=4096, m=16, fit_in=q["fit"][:, :2])
+    for k in ("codes", "labels", "params", "fit"):
+        assert np.array_equal(q[k], q2[k])
+    # a one-sided heavy-tailed state leaves the lowest clusters empty; the error bound still holds per cluster
+    lab = oracle.unpack_labels(q["labels"], v.size)
+    assert lab.min() > 0
+    xh = oracle.dequantize_cluster(q["codes"], q["labels"], q["params"], v.size)
+    S = q["params"][np.arange(v.size) // 4096, lab, 0].astype(np.float64)
+    assert np.all(np.abs(xh.astype(np.float64) - v) <= S / 510 * (1 + 1e-5) + 2 * np.spacing(v).astype(np.float64))
+    # shifted fit -> different edges -> different labels somewhere
+    fit = q["fit"][:, :2].copy()
+    fit[:, 0] += fit[:, 1]
+    q3 = oracle.quantize_cluster(v, G=4096, m=16, fit_in=fit)
+    assert not np.array_equal(q3["labels"], q["labels"])

@@ -1,0 +1,92 @@
+"""Are the oracle's pins sharp?  Plant one plausible mistake at a time in a COPY of the oracle
+source (CPU only), build it, point the ctypes wrapper at it, and require that at least one pin
+from test_oracle_sparse / test_oracle_cluster fails.  The oracle itself is never modified.
+"""
+import ctypes
+import os
+import subprocess
+
+import pytest
+
+import oracle
+import conftest
+import test_oracle_cluster as tc
+import test_oracle_sparse as ts
+
+SRC = os.path.join(os.path.dirname(oracle.__file__), "bitsnap_oracle.c")
+
+# (name, text to find, replacement, occurrence index)
+MUTANTS = [
+    ("mask_msb_first", "(1u << (i & 7))", "(0x80u >> (i & 7))", 0),
+    ("payload_takes_base", "payload[nc] = cur[i];", "payload[nc] = base[i];", 0),
+    ("payload_stores_difference", "payload[nc] = cur[i];", "payload[nc] = (uint16_t)(cur[i] - base[i]);", 0),
+    ("offsets_inclusive", "off[t] = run;", "off[t] = run + 1;", 0),
+    ("sample_std", "sqrt(q / (double)len)", "sqrt(q / (double)(len - 1))", 0),
+    ("mean_not_subtracted", "double d = (double)x[i] - mean;", "double d = (double)x[i];", 0),
+    ("edge_sign", "double e = (double)mu + prod;", "double e = (double)mu - prod;", 0),
+    ("edge_strict_compare", "if (edges[k - 1] <= x)", "if (edges[k - 1] < x)", 0),
+    ("quantile_k_plus_1", "long double p = (long double)k / (long double)m;", "long double p = (long double)(k + 1) / (long double)(m + 2);", 0),
+    ("scale_is_max", "seen[c] ? (mx[c] - mn[c]) : 0.0f;", "seen[c] ? mx[c] : 0.0f;", 0),
+    ("offset_is_max", "seen[c] ? mn[c] : 0.0f;", "seen[c] ? mx[c] : 0.0f;", 0),
+    ("params_swapped", "pg[2 * l + 1], pg[2 * l + 0]);", "pg[2 * l + 0], pg[2 * l + 1]);", 0),
+    ("code_without_offset", "float d = x - b;", "float d = x;", 0),
+    ("code_floor", "float r = rintf(y);", "float r = floorf(y);", 0),
+    ("code_256_levels", "float inv = 255.0f / S;", "float inv = 256.0f / S;", 0),
+    ("label_nibbles_swapped", "(l << ((idx & 1) * 4))", "(l << ((1 - (idx & 1)) * 4))", 0),
+    ("dequant_drops_offset", "out[i] = t + b;", "out[i] = t;", 0),
+    ("dequant_wrong_group", "int64_t g = i / G;", "int64_t g = 0;", 0),
+]
+
+
+def _pins(golden):
+    yield lambda: ts.test_roundtrip_lossless(4097, 0.06)
+    yield lambda: ts.test_roundtrip_lossless(65, 1.0)
+    yield lambda: ts.test_space_formula_and_ratios(golden)
+    yield lambda: ts.test_mask_payload_offsets_against_library_routines(4097)
+    yield lambda: ts.test_naive_mask_and_coo_crossovers(golden)
+    yield ts.test_decode_uses_payload_in_order
+    yield lambda: tc.test_quantiles_are_correctly_rounded(16)
+    yield tc.test_equal_probability_edges
+    yield tc.test_fit_exact_on_integers
+    yield lambda: tc.test_fit_against_exact_summation(0)
+    yield lambda: tc.test_labels_equal_searchsorted(16)
+    yield lambda: tc.test_params_are_cluster_min_and_range(4096)
+    yield tc.test_error_bound_endpoints_and_monotone_codes
+    yield lambda: tc.test_codes_against_bruteforce_argmin(4)
+    yield tc.test_one_cluster_is_plain_minmax_uint8
+    yield tc.test_dequantize_formula
+    yield lambda: tc.test_stored_size_formula(golden)
+    yield tc.test_degenerate_groups
+
+
+@pytest.mark.parametrize("name,find,repl,occ", MUTANTS, ids=[m[0] for m in MUTANTS])
+def test_planted_mistake_is_caught(tmp_path, name, find, repl, occ):
+    golden = conftest.load_golden("paper_closed_forms.txt")
+    text = open(SRC).read()
+    parts = text.split(find)
+    assert len(parts) > occ + 1, f"mutation site for {name} not found: the oracle changed, update this list"
+    text = find.join(parts[: occ + 1]) + repl + find.join(parts[occ + 1:])
+    src = tmp_path / "mutant.c"
+    lib = tmp_path / "libmutant.so"
+    src.write_text(text)
+    subprocess.run(["gcc", "-std=c11", "-O2", "-fPIC", "-shared", "-ffp-contract=off", "-o", str(lib), str(src), "-lm"],
+                   check=True)
+    good = oracle._load()
+    mut = ctypes.CDLL(str(lib))
+    for sym in ("oracle_encode_sparse", "oracle_encode_sparse_naive", "oracle_tile_offsets", "oracle_decode_sparse",
+                "oracle_norm_quantile", "oracle_cluster_fit", "oracle_cluster_edges", "oracle_quantize_cluster",
+                "oracle_dequantize_cluster", "oracle_code_bruteforce"):
+        getattr(mut, sym).argtypes = getattr(good, sym).argtypes
+        getattr(mut, sym).restype = getattr(good, sym).restype
+    oracle._lib = mut
+    try:
+        caught = False
+        for pin in _pins(golden):
+            try:
+                pin()
+            except AssertionError:
+                caught = True
+                break
+        assert caught, f"no pin noticed the planted mistake '{name}'"
+    finally:
+        oracle._lib = good

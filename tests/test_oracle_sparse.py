@@ -1,0 +1,153 @@
+"""Pins for the sparse half of the CPU oracle (paper: "Bitmask Based Sparsification for Model
+States", Eq. bitmask-required-space, Eq. improved-bitmask, Algorithm 1).
+
+Each check compares the oracle with something that is not the oracle: a number the paper
+prints (tests/golden), a closed form, a library routine that is the textbook form of one step,
+or the generator's own bookkeeping.
+"""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2511_12376_amd import synth
+
+SIZES = [0, 1, 7, 8, 9, 15, 16, 17, 63, 64, 65, 511, 512, 513, 4095, 4096, 4097, 8191, 8192, 8193, 20001]
+
+
+def _pair(n, p, seed):
+    rng = np.random.default_rng(seed)
+    base = rng.integers(0, 1 << 16, n, dtype=np.uint16)
+    cur = base.copy()
+    sel = rng.random(n) < p
+    cur[sel] ^= rng.integers(1, 1 << 16, n, dtype=np.uint16)[sel]   # xor with non-zero: always differs
+    return cur, base, int(sel.sum())
+
+
+# P1 ------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("n", SIZES)
+@pytest.mark.parametrize("p", [0.0, 0.06, 0.5, 1.0])
+def test_roundtrip_lossless(n, p):
+    cur, base, nsel = _pair(n, p, 1000 + n)
+    mask, payload, nc = oracle.encode_sparse(cur, base)
+    assert nc == nsel
+    out = oracle.decode_sparse(base, mask, payload)
+    assert out.dtype == np.uint16 and np.array_equal(out, cur)
+
+
+def test_roundtrip_signed_zero_and_nan_patterns():
+    # bf16 patterns: +0, -0, two NaNs with different payloads, +inf, a denormal
+    pats = np.array([0x0000, 0x8000, 0x7FC1, 0x7FC2, 0x7F80, 0x0001], np.uint16)
+    base = np.repeat(pats, len(pats))
+    cur = np.tile(pats, len(pats))
+    mask, payload, nc = oracle.encode_sparse(cur, base)
+    # +0 -> -0 is a change, NaN -> the same NaN is not, NaN -> other NaN is
+    assert nc == len(pats) * (len(pats) - 1)
+    assert np.array_equal(oracle.decode_sparse(base, mask, payload), cur)
+
+
+# P2 ------------------------------------------------------------------------------------------
+def test_space_formula_and_ratios(golden):
+    n = 1 << 16
+    for p in [0.0, 0.01, 0.06, 0.15, 0.2, 1 / 16, 15 / 16, 1.0]:
+        nsel = int(round(p * n))
+        base = np.arange(n, dtype=np.uint16)
+        cur = base.copy()
+        cur[:nsel] ^= np.uint16(0x0100)
+        mask, payload, nc = oracle.encode_sparse(cur, base)
+        stored = mask.nbytes + payload.nbytes
+        assert stored == (n + 7) // 8 + 2 * nc          # n/8 + 2 n_c
+        ratio = 2 * n / stored
+        assert ratio == pytest.approx(16 / (1 + 16 * nc / n), rel=1e-12)
+        if p == 0.0:
+            assert ratio == golden["sparse_ratio_max"]
+        if p == 0.15:
+            assert golden["sparse_ratio_at_15pct_floor"] < ratio < golden["sparse_ratio_at_15pct_ceil"]
+            assert ratio == pytest.approx(4.71, abs=0.01)
+        if p == 1 / 16:
+            assert ratio == pytest.approx(8.0)
+        if p == 15 / 16:
+            assert ratio == pytest.approx(1.0)              # break-even point of Eq. improved-bitmask
+            assert nc / n == golden["sparse_breakeven_fraction"]
+        if p == 1.0:
+            assert ratio < 1.0
+
+
+def test_config1_sweep_ratios():
+    # GPT-2-XL-shaped tensor (truncated), change fractions of the sweep
+    for p, want in [(0.01, 13.79), (0.06, 8.16), (0.2, 3.81)]:
+        cfg = synth.config(1, p=p)
+        d = synth.make_tensor_np(cfg, 4, n_limit=1_000_003)
+        mask, payload, nc = oracle.encode_sparse(d["cur"], d["base"])
+        n = d["cur"].size
+        assert nc == d["n_changed"]
+        assert abs(nc / n - p) < 4 * np.sqrt(p * (1 - p) / n)
+        assert 2 * n / (mask.nbytes + payload.nbytes) == pytest.approx(want, rel=0.02)
+
+
+# P3 / P5 -------------------------------------------------------------------------------------
+@pytest.mark.parametrize("n", [1, 9, 65, 4097, 100003])
+def test_mask_payload_offsets_against_library_routines(n):
+    cur, base, nsel = _pair(n, 0.3, 77 + n)
+    mask, payload, nc = oracle.encode_sparse(cur, base)
+    changed = cur != base
+    assert nc == int(changed.sum()) == nsel
+    # packed mask == numpy.packbits, least significant bit first; padding bits are zero
+    assert np.array_equal(mask, np.packbits(changed, bitorder="little"))
+    assert int(np.unpackbits(mask, bitorder="little")[n:].sum()) == 0
+    assert int(np.unpackbits(mask).sum()) == nc                      # popcount(mask) == n_c
+    # payload == boolean-mask selection, order preserved
+    assert np.array_equal(payload, cur[changed])
+    for tile in (8, 64, 4096):
+        off = oracle.tile_offsets(mask, n, tile)
+        cs = np.concatenate([[0], np.cumsum(changed, dtype=np.uint64)])
+        idx = np.minimum(np.arange(off.size, dtype=np.int64) * tile, n)
+        assert np.array_equal(off, cs[idx])
+        assert off[-1] == nc
+
+
+def test_generator_bookkeeping_matches_mask():
+    for ci, t in [(0, 0), (0, 2), (0, 3), (3, 8)]:
+        cfg = synth.config(ci)
+        d = synth.make_tensor_np(cfg, t, n_limit=300_000)
+        mask, payload, nc = oracle.encode_sparse(d["cur"], d["base"])
+        assert nc == d["n_changed"]
+        if cfg.recipe == "runs":
+            # whole 4096-element runs change together
+            bits = np.unpackbits(mask, bitorder="little")[: d["cur"].size]
+            runs = bits[: bits.size // 4096 * 4096].reshape(-1, 4096)
+            assert set(np.unique(runs.sum(axis=1))) <= {0, 4096}
+
+
+# P4 ------------------------------------------------------------------------------------------
+def test_naive_mask_and_coo_crossovers(golden):
+    n = 4096
+    for nsel in [0, 100, n // 2 - 1, n // 2, n // 2 + 1, n]:
+        base = np.zeros(n, np.uint16)
+        cur = base.copy()
+        cur[:nsel] = 1
+        flags, payload, nc = oracle.encode_sparse_naive(cur, base)
+        assert set(np.unique(flags)) <= {0, 1} and flags.sum() == nc == nsel
+        naive_bytes = flags.nbytes + payload.nbytes                  # n + 2 n_c
+        assert naive_bytes == n + 2 * nc
+        assert (naive_bytes < 2 * n) == (nc / n < golden["naive_breakeven_fraction"])
+        mask, payload2, nc2 = oracle.encode_sparse(cur, base)
+        assert np.array_equal(payload, payload2)
+        assert np.array_equal(np.packbits(flags, bitorder="little"), mask)
+    # packed mask vs a COO delta holding a 4-byte coordinate next to each 2-byte value
+    for nsel in [n // 32 - 1, n // 32, n // 32 + 1]:
+        base = np.zeros(n, np.uint16)
+        cur = base.copy()
+        cur[:nsel] = 1
+        mask, payload, nc = oracle.encode_sparse(cur, base)
+        bitmask_bytes = mask.nbytes + payload.nbytes
+        coo_bytes = (4 + 2) * nc
+        assert (bitmask_bytes < coo_bytes) == (nc / n > golden["coo_crossover_fraction"])
+
+
+def test_decode_uses_payload_in_order():
+    # a decoder that indexed payload by element index, or ranked from the wrong end, fails here
+    base = np.array([10, 11, 12, 13, 14, 15, 16, 17, 18, 19], np.uint16)
+    mask = np.array([0b10010010, 0b00000010], np.uint8)               # elements 1, 4, 7, 9
+    payload = np.array([100, 200, 300, 400], np.uint16)
+    out = oracle.decode_sparse(base, mask, payload)
+    assert out.tolist() == [10, 100, 12, 13, 200, 15, 16, 300, 18, 400]
