@@ -1,0 +1,168 @@
+/*
+ * bitsnap.h - C ABI of libbitsnap: the per-tensor checkpoint codecs of BitSnap
+ * (arXiv 2511.12376) as hand-written HIP kernels for gfx950 (MI355X).
+ *
+ *   encode_sparse / decode_sparse          bitmask-based delta sparsification of 16-bit model
+ *                                          states against a base checkpoint (lossless)
+ *   quantize_cluster / dequantize_cluster  cluster-based 8-bit quantisation of fp32 optimizer
+ *                                          states (lossy, error bounded per cluster)
+ *
+ * Conventions for every call
+ *   - Pointers are DEVICE pointers unless a parameter says "host".  The caller owns all
+ *     buffers; the library never allocates or frees device memory.
+ *   - Work is enqueued on `stream` (a hipStream_t passed as void*, NULL = the default stream)
+ *     and the call returns without waiting.  Outputs are valid once the stream has passed it.
+ *   - Return value: BITSNAP_OK or a negative BITSNAP_E_* code.  Errors are found on the host
+ *     before anything is launched; a rejected call has touched no buffer.
+ *   - Tensors are flat and contiguous.  Pointers named below as "aligned" must be multiples
+ *     of 16 bytes.
+ *   - Two calls that share a workspace must not overlap in time.
+ */
+#ifndef BITSNAP_H
+#define BITSNAP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef void *bitsnap_stream_t;
+
+enum {
+    BITSNAP_OK = 0,
+    BITSNAP_E_NULL = -1,        /* a required pointer is NULL                              */
+    BITSNAP_E_SIZE = -2,        /* n < 0, unsupported elem_bytes / m / group, n too large  */
+    BITSNAP_E_ALIGN = -3,       /* a pointer that must be 16-byte aligned is not           */
+    BITSNAP_E_WORKSPACE = -4,   /* workspace missing or smaller than *_workspace_bytes()   */
+    BITSNAP_E_OFFSETS = -5,     /* tile_offsets requested but n >= 2^32                    */
+    BITSNAP_E_LAUNCH = -6       /* the HIP runtime refused the launch                      */
+};
+
+/* Library version, major*10000 + minor*100 + patch. */
+int bitsnap_version(void);
+
+/* Static, NUL-terminated text for a return code (host pointer, never freed). */
+const char *bitsnap_error_string(int code);
+
+/* ------------------------------------------------------------------------------------------
+ * Sparse path.  Paper: "Bitmask Based Sparsification for Model States" (improved bitmask,
+ * space n/8 + 2 n_c, Eq. improved-bitmask) and Algorithm 1.
+ *
+ * Format of one encoded tensor of n 16-bit elements (fp16 and bf16 are the same to the codec):
+ *   mask     bit i (byte i/8, bit position i%8, least significant first) is 1 iff the 16-bit
+ *            pattern of cur[i] differs from base[i]; padding bits are 0.  ceil(n/8) bytes count
+ *            as stored data.
+ *   payload  the changed elements of cur (the new values, not differences), in index order:
+ *            n_c elements of 2 bytes.
+ * ---------------------------------------------------------------------------------------- */
+
+/* Number of elements covered by one entry of `tile_offsets`. */
+size_t bitsnap_sparse_tile_elems(void);
+
+/* Bytes the caller must provide for `mask`: ceil(n/8) rounded up to a multiple of 16.  The
+ * bytes after ceil(n/8) are written as 0. */
+size_t bitsnap_sparse_mask_bytes(int64_t n);
+
+/* Bytes of workspace encode_sparse / decode_sparse need for a tensor of n elements.  The
+ * workspace holds the cross-workgroup scan state.  It must contain zeros the first time it is
+ * used (any means: hipMemset, torch.zeros); afterwards the kernels leave it ready for the next
+ * call, of any size that fits, so one workspace serves a whole checkpoint. */
+size_t bitsnap_sparse_workspace_bytes(int64_t n);
+
+/* Algorithm 1, steps 1-5, for one tensor.
+ *   cur, base        [n] 16-bit elements, aligned
+ *   elem_bytes       must be 2
+ *   mask             [bitsnap_sparse_mask_bytes(n)] out, aligned
+ *   payload          [payload_capacity_elems] 16-bit out, aligned.  If more than
+ *                    payload_capacity_elems elements changed, only the first
+ *                    payload_capacity_elems are written; mask and n_changed are still complete,
+ *                    so the caller can see the overflow (n_changed > capacity) and keep the
+ *                    full tensor instead - the paper's own rule once n_c >= 15n/16.
+ *   tile_offsets     nullable; [ceil(n/tile_elems)] out: number of changed elements before
+ *                    each tile (the compaction offset of the tile)
+ *   n_changed        [1] out, 8-byte aligned: n_c.  UINT64_MAX reports that the scan gave up
+ *                    waiting (see bitsnap_debug_set_spin_limit); outputs are then unspecified
+ *                    but every access stayed in bounds and the workspace is reusable.
+ *   workspace        see bitsnap_sparse_workspace_bytes
+ * n == 0 is legal and writes n_changed = 0. */
+int bitsnap_encode_sparse(const void *cur, const void *base, int64_t n, int elem_bytes,
+                          uint8_t *mask, void *payload, int64_t payload_capacity_elems,
+                          uint32_t *tile_offsets, uint64_t *n_changed,
+                          void *workspace, size_t workspace_bytes, bitsnap_stream_t stream);
+
+/* Inverse of encode_sparse: out[i] = bit i of mask ? next payload element : base[i].
+ *   base             [n] 16-bit, aligned
+ *   mask             [ceil(n/8)] bytes, aligned; bits at or beyond n are ignored
+ *   payload          [payload_elems] 16-bit, aligned.  Never read at or beyond payload_elems;
+ *                    if the mask has more set bits than that, the surplus elements decode to 0.
+ *   out              [n] 16-bit, aligned; may be the same buffer as base (in-place patch)
+ *   n_changed        nullable, [1] out: the number of set mask bits below n (UINT64_MAX: as in
+ *                    encode_sparse)
+ */
+int bitsnap_decode_sparse(const void *base, const uint8_t *mask, const void *payload,
+                          int64_t payload_elems, int64_t n, int elem_bytes, void *out,
+                          uint64_t *n_changed,
+                          void *workspace, size_t workspace_bytes, bitsnap_stream_t stream);
+
+/* Host-side knob for tests of the give-up path: the number of polls a workgroup spends waiting
+ * for a predecessor's scan state before it reports failure through n_changed.  0 restores the
+ * default (large enough never to trigger in normal operation). */
+void bitsnap_debug_set_spin_limit(uint32_t polls);
+
+/* ------------------------------------------------------------------------------------------
+ * Cluster path.  Paper: "Cluster Based Quantization for Optimizer States" (Eq. qmap-distance,
+ * S = max - min and b = min per cluster, Eq. decluster, size analysis) and Algorithm 2.
+ *
+ * The flat fp32 tensor is cut into groups of `group` consecutive elements (the last one may be
+ * short); group == 0 means one group spanning the tensor, the paper's own formulation.  Each
+ * group gets its own fit: mean and standard deviation -> m clusters bounded by the normal
+ * quantiles mu + sigma * Phi^-1(k/m) -> label (uint4) per element -> per-cluster (S, b) ->
+ * uint8 code = nearest of the 256 levels b + j*S/255.
+ *
+ *   codes   [n] uint8, element order
+ *   labels  [ceil(n/2)] bytes, element 2i in the low nibble of byte i, element 2i+1 in the high
+ *   params  [groups][m][2] fp32: (S, b) per cluster; (0, 0) for a cluster without members
+ *   fit     [groups][2 + (m-1)] fp32: mu, sigma, e_1 .. e_{m-1}
+ * Stored size per group: group + group/2 + 8m bytes (1.5 n + 128 per 4096 elements at m = 16).
+ * ---------------------------------------------------------------------------------------- */
+
+size_t bitsnap_cluster_groups(int64_t n, int64_t group);
+size_t bitsnap_cluster_param_bytes(int64_t n, int64_t group, int m);
+size_t bitsnap_cluster_label_bytes(int64_t n);
+size_t bitsnap_cluster_fit_floats(int64_t n, int64_t group, int m);
+size_t bitsnap_cluster_workspace_bytes(int64_t n, int64_t group, int m);
+
+/* Host: the standard-normal quantile Phi^-1(k/m) the kernels use for edge k (0 < k < m <= 16);
+ * 0.0 outside that range. */
+double bitsnap_cluster_z(int k, int m);
+
+/* Algorithm 2 for one tensor.
+ *   x          [n] fp32, aligned
+ *   group      0 (whole tensor) or the group length
+ *   m          clusters, 1..16
+ *   codes      [n] out, aligned;  labels [ceil(n/2)] out, aligned;  params out, aligned
+ *   fit_out    nullable, [bitsnap_cluster_fit_floats] out
+ *   fit_in     nullable, [groups][2]: use these (mu, sigma) instead of computing them
+ *              (everything after step 1 of Algorithm 2 is a function of these two numbers)
+ *   status     nullable, [1] uint32: bit 0 is OR-ed in when a group's mean or deviation is not
+ *              finite (NaN/Inf in the input); that group's output is unspecified, in bounds
+ *   workspace  [bitsnap_cluster_workspace_bytes]; may be NULL when that size is 0
+ */
+int bitsnap_quantize_cluster(const float *x, int64_t n, int64_t group, int m,
+                             uint8_t *codes, uint8_t *labels, float *params,
+                             float *fit_out, const float *fit_in, uint32_t *status,
+                             void *workspace, size_t workspace_bytes, bitsnap_stream_t stream);
+
+/* Dequantisation and "decluster": out[i] = (codes[i] * (S/255)) + b with (S, b) of the cluster
+ * labels[i] names in element i's group; values return to their original positions because
+ * codes are kept in element order.   out [n] fp32, aligned. */
+int bitsnap_dequantize_cluster(const uint8_t *codes, const uint8_t *labels, const float *params,
+                               int64_t n, int64_t group, int m, float *out,
+                               bitsnap_stream_t stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BITSNAP_H */

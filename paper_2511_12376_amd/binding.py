@@ -1,0 +1,243 @@
+"""ctypes binding of libbitsnap.so: same names as the C ABI (include/bitsnap.h), argument
+marshalling only.  Tensors are torch tensors on the MI355X; torch supplies device memory and the
+current HIP stream, every step of the codecs runs in the library's kernels.
+
+There is no fallback: if the library has not been built (``python -m paper_2511_12376_amd.build``)
+or cannot be loaded, every entry point raises ``BitsnapError``.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from types import SimpleNamespace
+from typing import Optional
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libbitsnap.so")
+
+SYMBOLS = (
+    "bitsnap_version", "bitsnap_error_string",
+    "bitsnap_sparse_tile_elems", "bitsnap_sparse_mask_bytes", "bitsnap_sparse_workspace_bytes",
+    "bitsnap_encode_sparse", "bitsnap_decode_sparse", "bitsnap_debug_set_spin_limit",
+    "bitsnap_cluster_groups", "bitsnap_cluster_param_bytes", "bitsnap_cluster_label_bytes",
+    "bitsnap_cluster_fit_floats", "bitsnap_cluster_workspace_bytes", "bitsnap_cluster_z",
+    "bitsnap_quantize_cluster", "bitsnap_dequantize_cluster",
+)
+
+
+class BitsnapError(RuntimeError):
+    pass
+
+
+_lib = None
+
+
+def lib():
+    """The loaded library.  Raises BitsnapError when it is missing."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise BitsnapError(f"{LIB_PATH} not found: build it with `python -m paper_2511_12376_amd.build`")
+    try:
+        L = C.CDLL(LIB_PATH)
+    except OSError as e:  # e.g. no HIP runtime on this machine
+        raise BitsnapError(f"cannot load {LIB_PATH}: {e}") from e
+    p, i64, sz, i = C.c_void_p, C.c_int64, C.c_size_t, C.c_int
+    L.bitsnap_version.argtypes, L.bitsnap_version.restype = [], i
+    L.bitsnap_error_string.argtypes, L.bitsnap_error_string.restype = [i], C.c_char_p
+    L.bitsnap_sparse_tile_elems.argtypes, L.bitsnap_sparse_tile_elems.restype = [], sz
+    L.bitsnap_sparse_mask_bytes.argtypes, L.bitsnap_sparse_mask_bytes.restype = [i64], sz
+    L.bitsnap_sparse_workspace_bytes.argtypes, L.bitsnap_sparse_workspace_bytes.restype = [i64], sz
+    L.bitsnap_encode_sparse.argtypes = [p, p, i64, i, p, p, i64, p, p, p, sz, p]
+    L.bitsnap_encode_sparse.restype = i
+    L.bitsnap_decode_sparse.argtypes = [p, p, p, i64, i64, i, p, p, p, sz, p]
+    L.bitsnap_decode_sparse.restype = i
+    L.bitsnap_debug_set_spin_limit.argtypes, L.bitsnap_debug_set_spin_limit.restype = [C.c_uint32], None
+    L.bitsnap_cluster_groups.argtypes, L.bitsnap_cluster_groups.restype = [i64, i64], sz
+    L.bitsnap_cluster_param_bytes.argtypes, L.bitsnap_cluster_param_bytes.restype = [i64, i64, i], sz
+    L.bitsnap_cluster_label_bytes.argtypes, L.bitsnap_cluster_label_bytes.restype = [i64], sz
+    L.bitsnap_cluster_fit_floats.argtypes, L.bitsnap_cluster_fit_floats.restype = [i64, i64, i], sz
+    L.bitsnap_cluster_workspace_bytes.argtypes, L.bitsnap_cluster_workspace_bytes.restype = [i64, i64, i], sz
+    L.bitsnap_cluster_z.argtypes, L.bitsnap_cluster_z.restype = [i, i], C.c_double
+    L.bitsnap_quantize_cluster.argtypes = [p, i64, i64, i, p, p, p, p, p, p, p, sz, p]
+    L.bitsnap_quantize_cluster.restype = i
+    L.bitsnap_dequantize_cluster.argtypes = [p, p, p, i64, i64, i, p, p]
+    L.bitsnap_dequantize_cluster.restype = i
+    _lib = L
+    return L
+
+
+def _check(rc: int, what: str):
+    if rc != 0:
+        raise BitsnapError(f"{what}: {lib().bitsnap_error_string(rc).decode()} ({rc})")
+
+
+def _ptr(t) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _stream(stream) -> Optional[int]:
+    import torch
+    s = torch.cuda.current_stream() if stream is None else stream
+    return s.cuda_stream or None
+
+
+# ----------------------------------------------------------------------------------------------
+# size helpers (host)
+# ----------------------------------------------------------------------------------------------
+def version() -> int:
+    return lib().bitsnap_version()
+
+
+def sparse_tile_elems() -> int:
+    return lib().bitsnap_sparse_tile_elems()
+
+
+def sparse_mask_bytes(n: int) -> int:
+    return lib().bitsnap_sparse_mask_bytes(n)
+
+
+def sparse_workspace_bytes(n: int) -> int:
+    return lib().bitsnap_sparse_workspace_bytes(n)
+
+
+def cluster_groups(n: int, group: int) -> int:
+    return lib().bitsnap_cluster_groups(n, group)
+
+
+def cluster_param_bytes(n: int, group: int, m: int) -> int:
+    return lib().bitsnap_cluster_param_bytes(n, group, m)
+
+
+def cluster_label_bytes(n: int) -> int:
+    return lib().bitsnap_cluster_label_bytes(n)
+
+
+def cluster_fit_floats(n: int, group: int, m: int) -> int:
+    return lib().bitsnap_cluster_fit_floats(n, group, m)
+
+
+def cluster_workspace_bytes(n: int, group: int, m: int) -> int:
+    return lib().bitsnap_cluster_workspace_bytes(n, group, m)
+
+
+def cluster_z(k: int, m: int) -> float:
+    return lib().bitsnap_cluster_z(k, m)
+
+
+def debug_set_spin_limit(polls: int) -> None:
+    lib().bitsnap_debug_set_spin_limit(polls)
+
+
+def new_sparse_workspace(n: int, device):
+    """A zeroed workspace good for tensors of up to n elements (reusable across calls)."""
+    import torch
+    return torch.zeros(sparse_workspace_bytes(n), dtype=torch.uint8, device=device)
+
+
+# ----------------------------------------------------------------------------------------------
+# the four codecs.  Raw forms take every buffer; the caller allocates.
+# ----------------------------------------------------------------------------------------------
+def encode_sparse_raw(cur, base, n: int, mask, payload, payload_capacity: int, tile_offsets, n_changed,
+                      workspace, stream=None) -> None:
+    rc = lib().bitsnap_encode_sparse(_ptr(cur), _ptr(base), n, 2, _ptr(mask), _ptr(payload), payload_capacity,
+                                     _ptr(tile_offsets), _ptr(n_changed), _ptr(workspace),
+                                     workspace.numel() * workspace.element_size(), _stream(stream))
+    _check(rc, "bitsnap_encode_sparse")
+
+
+def decode_sparse_raw(base, mask, payload, payload_elems: int, n: int, out, n_changed, workspace, stream=None) -> None:
+    rc = lib().bitsnap_decode_sparse(_ptr(base), _ptr(mask), _ptr(payload), payload_elems, n, 2, _ptr(out),
+                                     _ptr(n_changed), _ptr(workspace),
+                                     workspace.numel() * workspace.element_size(), _stream(stream))
+    _check(rc, "bitsnap_decode_sparse")
+
+
+def quantize_cluster_raw(x, n: int, group: int, m: int, codes, labels, params, fit_out=None, fit_in=None,
+                         status=None, workspace=None, stream=None) -> None:
+    wb = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    rc = lib().bitsnap_quantize_cluster(_ptr(x), n, group, m, _ptr(codes), _ptr(labels), _ptr(params),
+                                        _ptr(fit_out), _ptr(fit_in), _ptr(status), _ptr(workspace), wb,
+                                        _stream(stream))
+    _check(rc, "bitsnap_quantize_cluster")
+
+
+def dequantize_cluster_raw(codes, labels, params, n: int, group: int, m: int, out, stream=None) -> None:
+    rc = lib().bitsnap_dequantize_cluster(_ptr(codes), _ptr(labels), _ptr(params), n, group, m, _ptr(out),
+                                          _stream(stream))
+    _check(rc, "bitsnap_dequantize_cluster")
+
+
+# ----------------------------------------------------------------------------------------------
+# convenience forms: allocate the outputs with torch, then call the raw form
+# ----------------------------------------------------------------------------------------------
+def _flat16(t):
+    import torch
+    assert t.is_cuda and t.is_contiguous() and t.element_size() == 2, "need a contiguous 16-bit device tensor"
+    return t.reshape(-1)
+
+
+def encode_sparse(cur, base, *, capacity: Optional[int] = None, want_offsets: bool = False, workspace=None,
+                  stream=None):
+    """-> namespace(mask uint8[mask_bytes], payload int16[capacity], n_changed uint64-as-int64[1] (device),
+    tile_offsets int32[tiles] or None, workspace).  Nothing is synchronised."""
+    import torch
+    cur, base = _flat16(cur), _flat16(base)
+    n = cur.numel()
+    assert base.numel() == n
+    dev = cur.device
+    capacity = n if capacity is None else capacity
+    mask = torch.empty(sparse_mask_bytes(n), dtype=torch.uint8, device=dev)
+    payload = torch.empty(max(capacity, 1), dtype=torch.int16, device=dev)
+    n_changed = torch.empty(1, dtype=torch.int64, device=dev)
+    tiles = (n + sparse_tile_elems() - 1) // sparse_tile_elems()
+    offs = torch.empty(max(tiles, 1), dtype=torch.int32, device=dev) if want_offsets else None
+    if workspace is None:
+        workspace = new_sparse_workspace(n, dev)
+    encode_sparse_raw(cur, base, n, mask, payload, capacity, offs, n_changed, workspace, stream)
+    return SimpleNamespace(mask=mask, payload=payload, n_changed=n_changed, tile_offsets=offs, workspace=workspace,
+                           n=n, capacity=capacity)
+
+
+def decode_sparse(base, mask, payload, payload_elems: int, *, out=None, workspace=None, stream=None):
+    """-> (out, n_changed[1] device).  ``out`` defaults to a new tensor like ``base``."""
+    import torch
+    base_f = _flat16(base)
+    n = base_f.numel()
+    if out is None:
+        out = torch.empty_like(base)
+    out_f = _flat16(out)
+    n_changed = torch.empty(1, dtype=torch.int64, device=base.device)
+    if workspace is None:
+        workspace = new_sparse_workspace(n, base.device)
+    decode_sparse_raw(base_f, mask, payload, payload_elems, n, out_f, n_changed, workspace, stream)
+    return out, n_changed
+
+
+def quantize_cluster(x, group: int = 4096, m: int = 16, *, fit_in=None, want_fit: bool = True, stream=None):
+    """-> namespace(codes uint8[n], labels uint8[ceil(n/2)], params f32[groups,m,2], fit f32[groups,m+1] or None,
+    status int32[1])."""
+    import torch
+    assert x.is_cuda and x.is_contiguous() and x.dtype == torch.float32
+    xf = x.reshape(-1)
+    n = xf.numel()
+    dev = x.device
+    g = cluster_groups(n, group)
+    codes = torch.empty(max(n, 1), dtype=torch.uint8, device=dev)[:n]
+    labels = torch.empty(max(cluster_label_bytes(n), 1), dtype=torch.uint8, device=dev)[:cluster_label_bytes(n)]
+    params = torch.empty((max(g, 1), m, 2), dtype=torch.float32, device=dev)[:g]
+    fit = torch.empty((max(g, 1), m + 1), dtype=torch.float32, device=dev)[:g] if want_fit else None
+    status = torch.zeros(1, dtype=torch.int32, device=dev)
+    wsb = cluster_workspace_bytes(n, group, m)
+    ws = torch.zeros(wsb, dtype=torch.uint8, device=dev) if wsb else None
+    quantize_cluster_raw(xf, n, group, m, codes, labels, params, fit, fit_in, status, ws, stream)
+    return SimpleNamespace(codes=codes, labels=labels, params=params, fit=fit, status=status, n=n, group=group, m=m)
+
+
+def dequantize_cluster(codes, labels, params, n: int, group: int = 4096, m: int = 16, *, out=None, stream=None):
+    import torch
+    if out is None:
+        out = torch.empty(max(n, 1), dtype=torch.float32, device=codes.device)[:n]
+    dequantize_cluster_raw(codes, labels, params, n, group, m, out, stream)
+    return out

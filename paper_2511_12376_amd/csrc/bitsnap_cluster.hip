@@ -1,0 +1,422 @@
+// quantize_cluster / dequantize_cluster: cluster-based 8-bit quantisation of fp32 optimizer
+// states (paper: "Cluster Based Quantization for Optimizer States", Eq. qmap-distance, S and b
+// per cluster, Eq. decluster; Algorithm 2).
+//
+// One wavefront owns one group of G = 256*K elements and keeps it in registers (K float4 per
+// lane), so HBM is read once.  Nothing in the kernel crosses waves: no workgroup barrier.
+//   step 1  mean / deviation: fp64 partial sums per lane, DPP tree across the wave
+//   step 2  the 15 edges mu + sigma*z_k, laid out in LDS as an implicit binary search tree
+//   step 3  label = 4 tree steps (compare, shift-in the result)
+//   step 4  per-cluster min/max: every lane owns a private column of a [32][64] LDS table
+//           (bank = lane mod 32, so the read-modify-writes never conflict), reduced at the end
+//   step 5-6  code = rint((x-b) * (255/S)) with (b, 255/S) fetched from a 16-entry LDS table
+#include <hip/hip_runtime.h>
+#include <math.h>
+#include <stdint.h>
+
+#include "../../include/bitsnap.h"
+#include "host_util.hpp"
+#include "wave.hpp"
+
+namespace bitsnap {
+
+static const double kZHost[17][16] = {
+#include "z_table.inc"
+};
+__constant__ double kZDev[17][16] = {
+#include "z_table.inc"
+};
+
+constexpr int kQBlock = 256;
+constexpr int kQWaves = kQBlock / kWave;
+constexpr int kMaxClusters = 16;
+
+struct alignas(16) WaveShared {
+    float tab[2 * kMaxClusters][kWave];  // rows 0..15: running min per cluster, rows 16..31: running max
+    float tree[kMaxClusters];            // node i of the edge search tree (node 1 = root), [0] unused
+    float2 coder[kMaxClusters];          // (b, 255/S) for quantize, (S/255, b) for dequantize
+};
+
+// Orders this wave's LDS writes before its later LDS reads (lanes exchange data through LDS).
+__device__ __forceinline__ void wave_lds_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+__device__ __forceinline__ float comp(const float4 &v, int j) { return j == 0 ? v.x : j == 1 ? v.y : j == 2 ? v.z : v.w; }
+
+// Algorithm 2 step 3 for one value: number of edges <= x, by descending the search tree.
+__device__ __forceinline__ uint32_t label_of(const float *tree, float x)
+{
+    uint32_t node = 1;
+#pragma unroll
+    for (int s = 0; s < 4; ++s)
+        node = 2u * node + (x >= tree[node] ? 1u : 0u);
+    return node - 16u;
+}
+
+template <int K, bool kFull>
+__device__ __forceinline__ void quantize_group(const float *__restrict__ x, int64_t lo, int len, int m, int64_t g,
+                                               uint8_t *__restrict__ codes, uint8_t *__restrict__ labels,
+                                               float *__restrict__ params, float *__restrict__ fit_out,
+                                               const float *__restrict__ fit_in, uint32_t *__restrict__ status,
+                                               WaveShared &ws, int lane)
+{
+    // ---- load: lane owns elements lo + k*256 + lane*4 + {0..3}
+    float4 v[K];
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        const int off = k * 256 + lane * 4;
+        if (kFull) {
+            v[k] = *reinterpret_cast<const float4 *>(x + lo + off);
+        } else {
+            v[k].x = off + 0 < len ? x[lo + off + 0] : 0.0f;
+            v[k].y = off + 1 < len ? x[lo + off + 1] : 0.0f;
+            v[k].z = off + 2 < len ? x[lo + off + 2] : 0.0f;
+            v[k].w = off + 3 < len ? x[lo + off + 3] : 0.0f;
+        }
+    }
+    // running min/max table: this lane's column
+#pragma unroll
+    for (int c = 0; c < kMaxClusters; ++c) {
+        ws.tab[c][lane] = INFINITY;
+        ws.tab[kMaxClusters + c][lane] = -INFINITY;
+    }
+
+    // ---- step 1: mean and population standard deviation, fp64
+    double s = 0.0;
+#pragma unroll
+    for (int k = 0; k < K; ++k)
+        s += ((double)v[k].x + (double)v[k].y) + ((double)v[k].z + (double)v[k].w);  // padding adds 0
+    s = wave_sum(s);
+    const double mean = s / (double)len;
+    double q = 0.0;
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            if (kFull || k * 256 + lane * 4 + j < len) {
+                const double d = (double)comp(v[k], j) - mean;
+                q = fma(d, d, q);
+            }
+        }
+    }
+    q = wave_sum(q);
+    float mu = (float)mean;
+    float sigma = (float)sqrt(q / (double)len);
+    if (fit_in) {
+        mu = fit_in[2 * g];
+        sigma = fit_in[2 * g + 1];
+    }
+    if (status && lane == 0 && !(isfinite(mu) && isfinite(sigma)))
+        atomicOr(status, 1u);
+
+    // ---- step 2: edges e_k = fl32(mu + sigma * z_k), product and sum rounded separately in fp64
+    if (lane >= 1 && lane < kMaxClusters) {
+        float e = INFINITY;  // edges that do not exist (m < 16) are never <= x
+        if (lane < m)
+            e = (float)__dadd_rn((double)mu, __dmul_rn((double)sigma, kZDev[m][lane]));
+        const int tz = __ffs(lane) - 1;
+        ws.tree[(1 << (3 - tz)) + (lane >> (tz + 1))] = e;
+        if (fit_out && lane < m)
+            fit_out[g * (m + 1) + 1 + lane] = e;
+    }
+    if (fit_out && lane == 0) {
+        fit_out[g * (m + 1) + 0] = mu;
+        fit_out[g * (m + 1) + 1] = sigma;
+    }
+    wave_lds_sync();
+
+    // ---- steps 3-4: labels, per-cluster min and max
+    uint32_t packed[(K + 1) / 2];
+#pragma unroll
+    for (int i = 0; i < (K + 1) / 2; ++i)
+        packed[i] = 0;
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        uint32_t l4 = 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            if (kFull || k * 256 + lane * 4 + j < len) {
+                const float xv = comp(v[k], j);
+                const uint32_t l = label_of(ws.tree, xv);
+                float *pmin = &ws.tab[l][lane];
+                float *pmax = &ws.tab[kMaxClusters + l][lane];
+                *pmin = fminf(*pmin, xv);
+                *pmax = fmaxf(*pmax, xv);
+                l4 |= l << (4 * j);
+            }
+        }
+        packed[k >> 1] |= l4 << (16 * (k & 1));
+        // labels: two per byte, even element in the low nibble
+        const int off = k * 256 + lane * 4;
+        uint8_t *lp = labels + ((lo + off) >> 1);
+        if (kFull || off + 3 < len) {
+            *reinterpret_cast<uint16_t *>(lp) = (uint16_t)l4;
+        } else {
+            if (off < len)
+                lp[0] = (uint8_t)l4;
+            if (off + 2 < len)
+                lp[1] = (uint8_t)(l4 >> 8);
+        }
+    }
+    wave_lds_sync();
+
+    // ---- reduce the table over its 64 columns: lane handles row (lane & 31), half (lane >> 5)
+    {
+        const int row = lane & 31, half = lane >> 5;
+        float mn = INFINITY, mx = -INFINITY;
+#pragma unroll 8
+        for (int j = 0; j < 32; ++j) {
+            const float t = ws.tab[row][half * 32 + ((j + lane) & 31)];
+            mn = fminf(mn, t);
+            mx = fmaxf(mx, t);
+        }
+        float r = row < kMaxClusters ? mn : mx;
+        const float o = __shfl_xor(r, 32, kWave);
+        r = row < kMaxClusters ? fminf(r, o) : fmaxf(r, o);
+        const float hi = __shfl_down(r, kMaxClusters, kWave);  // lane c receives max of cluster c
+        if (lane < kMaxClusters) {
+            float S = 0.0f, b = 0.0f, inv = 0.0f;
+            if (r <= hi) {  // the cluster has members
+                b = r;
+                S = __fsub_rn(hi, r);
+                if (S > 0.0f) {
+                    inv = __fdiv_rn(255.0f, S);
+                    if (!isfinite(inv))
+                        inv = 0.0f;
+                }
+            }
+            ws.coder[lane] = make_float2(b, inv);
+            if (lane < m)
+                *reinterpret_cast<float2 *>(params + (g * m + lane) * 2) = make_float2(S, b);
+        }
+    }
+    wave_lds_sync();
+
+    // ---- steps 5-6: nearest of the 256 levels inside the element's cluster
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        const uint32_t l4 = (packed[k >> 1] >> (16 * (k & 1))) & 0xFFFFu;
+        uint32_t c4 = 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const float2 bi = ws.coder[(l4 >> (4 * j)) & 15u];
+            const float y = __fmul_rn(__fsub_rn(comp(v[k], j), bi.x), bi.y);
+            const float r = rintf(y);
+            uint32_t c = (uint32_t)r;  // saturating: negative and NaN give 0
+            c = c > 255u ? 255u : c;
+            c4 |= c << (8 * j);
+        }
+        const int off = k * 256 + lane * 4;
+        uint8_t *cp = codes + lo + off;
+        if (kFull || off + 3 < len) {
+            *reinterpret_cast<uint32_t *>(cp) = c4;
+        } else {
+            for (int j = 0; j < 4; ++j)
+                if (off + j < len)
+                    cp[j] = (uint8_t)(c4 >> (8 * j));
+        }
+    }
+}
+
+template <int K>
+__global__ __launch_bounds__(kQBlock) void quantize_cluster_kernel(
+    const float *__restrict__ x, int64_t n, int64_t groups, int m, uint8_t *__restrict__ codes,
+    uint8_t *__restrict__ labels, float *__restrict__ params, float *__restrict__ fit_out,
+    const float *__restrict__ fit_in, uint32_t *__restrict__ status)
+{
+    __shared__ WaveShared shared[kQWaves];
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
+    const int64_t g = (int64_t)blockIdx.x * kQWaves + wave;
+    if (g >= groups)
+        return;  // whole wave leaves; the kernel has no workgroup barrier
+    constexpr int G = 256 * K;
+    const int64_t lo = g * G;
+    const int64_t rest = n - lo;
+    if (rest >= G)
+        quantize_group<K, true>(x, lo, G, m, g, codes, labels, params, fit_out, fit_in, status, shared[wave], lane);
+    else
+        quantize_group<K, false>(x, lo, (int)rest, m, g, codes, labels, params, fit_out, fit_in, status, shared[wave], lane);
+}
+
+template <int K>
+__global__ __launch_bounds__(kQBlock) void dequantize_cluster_kernel(
+    const uint8_t *__restrict__ codes, const uint8_t *__restrict__ labels, const float *__restrict__ params,
+    int64_t n, int64_t groups, int m, float *__restrict__ out)
+{
+    __shared__ float2 coder[kQWaves][kMaxClusters];
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
+    const int64_t g = (int64_t)blockIdx.x * kQWaves + wave;
+    if (g >= groups)
+        return;
+    constexpr int G = 256 * K;
+    const int64_t lo = g * G;
+    const int64_t rest = n - lo;
+    const int len = rest >= G ? G : (int)rest;
+    if (lane < kMaxClusters) {
+        float2 sb = make_float2(0.0f, 0.0f);
+        if (lane < m)
+            sb = *reinterpret_cast<const float2 *>(params + (g * m + lane) * 2);
+        coder[wave][lane] = make_float2(__fdiv_rn(sb.x, 255.0f), sb.y);  // (S/255, b)
+    }
+    wave_lds_sync();
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        const int off = k * 256 + lane * 4;
+        if (off >= len)
+            break;
+        const bool full = off + 3 < len;
+        uint32_t c4 = 0, l4 = 0;
+        if (full) {
+            c4 = *reinterpret_cast<const uint32_t *>(codes + lo + off);
+            l4 = *reinterpret_cast<const uint16_t *>(labels + ((lo + off) >> 1));
+        } else {
+            for (int j = 0; j < 4; ++j)
+                if (off + j < len) {
+                    c4 |= (uint32_t)codes[lo + off + j] << (8 * j);
+                    l4 |= (uint32_t)((labels[(lo + off + j) >> 1] >> (4 * (j & 1))) & 15u) << (4 * j);
+                }
+        }
+        float r[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const float2 sb = coder[wave][(l4 >> (4 * j)) & 15u];
+            r[j] = __fadd_rn(__fmul_rn((float)((c4 >> (8 * j)) & 255u), sb.x), sb.y);
+        }
+        if (full) {
+            *reinterpret_cast<float4 *>(out + lo + off) = make_float4(r[0], r[1], r[2], r[3]);
+        } else {
+            for (int j = 0; j < 4; ++j)
+                if (off + j < len)
+                    out[lo + off + j] = r[j];
+        }
+    }
+}
+
+static int group_k(int64_t n, int64_t group)
+{
+    (void)n;
+    switch (group) {
+    case 256: return 1;
+    case 512: return 2;
+    case 1024: return 4;
+    case 2048: return 8;
+    case 4096: return 16;
+    default: return 0;
+    }
+}
+
+}  // namespace bitsnap
+
+using namespace bitsnap;
+
+extern "C" size_t bitsnap_cluster_groups(int64_t n, int64_t group)
+{
+    if (n <= 0)
+        return 0;
+    if (group <= 0 || group > n)
+        group = n;
+    return (size_t)((n + group - 1) / group);
+}
+
+extern "C" size_t bitsnap_cluster_param_bytes(int64_t n, int64_t group, int m)
+{
+    return bitsnap_cluster_groups(n, group) * (size_t)(m > 0 ? m : 0) * 2 * sizeof(float);
+}
+
+extern "C" size_t bitsnap_cluster_label_bytes(int64_t n) { return n <= 0 ? 0 : (size_t)((n + 1) / 2); }
+
+extern "C" size_t bitsnap_cluster_fit_floats(int64_t n, int64_t group, int m)
+{
+    return bitsnap_cluster_groups(n, group) * (size_t)(m > 0 ? m + 1 : 0);
+}
+
+extern "C" size_t bitsnap_cluster_workspace_bytes(int64_t n, int64_t group, int m)
+{
+    (void)n;
+    (void)group;
+    (void)m;
+    return 0;
+}
+
+extern "C" double bitsnap_cluster_z(int k, int m)
+{
+    if (m < 2 || m > kMaxClusters || k < 1 || k >= m)
+        return 0.0;
+    return kZHost[m][k];
+}
+
+extern "C" int bitsnap_quantize_cluster(const float *x, int64_t n, int64_t group, int m, uint8_t *codes,
+                                        uint8_t *labels, float *params, float *fit_out, const float *fit_in,
+                                        uint32_t *status, void *workspace, size_t workspace_bytes,
+                                        bitsnap_stream_t stream)
+{
+    (void)workspace;
+    (void)workspace_bytes;
+    if (n < 0 || m < 1 || m > kMaxClusters || group < 0)
+        return BITSNAP_E_SIZE;
+    if (n == 0)
+        return BITSNAP_OK;
+    const int K = group_k(n, group);
+    if (K == 0)
+        return BITSNAP_E_SIZE;
+    if (!x || !codes || !labels || !params)
+        return BITSNAP_E_NULL;
+    if (!aligned16(x) || !aligned16(codes) || !aligned16(labels) || !aligned16(params) || ((uintptr_t)fit_out & 3u) ||
+        ((uintptr_t)fit_in & 3u) || ((uintptr_t)status & 3u))
+        return BITSNAP_E_ALIGN;
+    const int64_t groups = (int64_t)bitsnap_cluster_groups(n, group);
+    const int64_t blocks = (groups + kQWaves - 1) / kQWaves;
+    if (blocks > 0x7FFFFFFF)
+        return BITSNAP_E_SIZE;
+    const dim3 grid((unsigned)blocks), block(kQBlock);
+    hipStream_t s = (hipStream_t)stream;
+#define BITSNAP_LAUNCH_Q(KK)                                                                                          \
+    hipLaunchKernelGGL(quantize_cluster_kernel<KK>, grid, block, 0, s, x, n, groups, m, codes, labels, params, fit_out, \
+                       fit_in, status)
+    switch (K) {
+    case 1: BITSNAP_LAUNCH_Q(1); break;
+    case 2: BITSNAP_LAUNCH_Q(2); break;
+    case 4: BITSNAP_LAUNCH_Q(4); break;
+    case 8: BITSNAP_LAUNCH_Q(8); break;
+    default: BITSNAP_LAUNCH_Q(16); break;
+    }
+#undef BITSNAP_LAUNCH_Q
+    return launch_status();
+}
+
+extern "C" int bitsnap_dequantize_cluster(const uint8_t *codes, const uint8_t *labels, const float *params, int64_t n,
+                                          int64_t group, int m, float *out, bitsnap_stream_t stream)
+{
+    if (n < 0 || m < 1 || m > kMaxClusters || group < 0)
+        return BITSNAP_E_SIZE;
+    if (n == 0)
+        return BITSNAP_OK;
+    const int K = group_k(n, group);
+    if (K == 0)
+        return BITSNAP_E_SIZE;
+    if (!codes || !labels || !params || !out)
+        return BITSNAP_E_NULL;
+    if (!aligned16(codes) || !aligned16(labels) || !aligned16(params) || !aligned16(out))
+        return BITSNAP_E_ALIGN;
+    const int64_t groups = (int64_t)bitsnap_cluster_groups(n, group);
+    const int64_t blocks = (groups + kQWaves - 1) / kQWaves;
+    if (blocks > 0x7FFFFFFF)
+        return BITSNAP_E_SIZE;
+    const dim3 grid((unsigned)blocks), block(kQBlock);
+    hipStream_t s = (hipStream_t)stream;
+#define BITSNAP_LAUNCH_D(KK) \
+    hipLaunchKernelGGL(dequantize_cluster_kernel<KK>, grid, block, 0, s, codes, labels, params, n, groups, m, out)
+    switch (K) {
+    case 1: BITSNAP_LAUNCH_D(1); break;
+    case 2: BITSNAP_LAUNCH_D(2); break;
+    case 4: BITSNAP_LAUNCH_D(4); break;
+    case 8: BITSNAP_LAUNCH_D(8); break;
+    default: BITSNAP_LAUNCH_D(16); break;
+    }
+#undef BITSNAP_LAUNCH_D
+    return launch_status();
+}

@@ -1,0 +1,409 @@
+// encode_sparse / decode_sparse: bitmask-based delta sparsification of 16-bit model states
+// (paper: "Bitmask Based Sparsification for Model States", improved bitmask; Algorithm 1) and
+// its inverse.  One kernel launch per call, one pass over HBM.
+//
+// A tile is 4096 consecutive elements and is processed by one 256-thread workgroup.  Inside a
+// tile a lane owns 8 consecutive elements per 16-byte load (one mask byte), a wavefront owns two
+// consecutive 512-element chunks.  Per-lane popcounts are scanned with DPP inside the wave,
+// through LDS across the four waves, and with the decoupled look-back of scan_state.hpp across
+// tiles.  Changed values are staged in LDS so that the payload leaves (encode) or enters
+// (decode) HBM as 16-byte accesses aligned on the payload buffer, whatever the tile's offset.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/bitsnap.h"
+#include "host_util.hpp"
+#include "scan_state.hpp"
+#include "wave.hpp"
+
+namespace bitsnap {
+
+constexpr int kBlock = 256;
+constexpr int kWaves = kBlock / kWave;
+constexpr int kChunksPerWave = 2;
+constexpr int kLaneElems = 8;                                     // one 16-byte load of 16-bit elements
+constexpr int kChunkElems = kWave * kLaneElems;                   // 512
+constexpr int kTileElems = kWaves * kChunksPerWave * kChunkElems; // 4096
+constexpr int kStageElems = kTileElems + 8;                       // + alignment shift
+
+struct TileShared {
+    alignas(16) uint16_t stage[kStageElems];
+    uint32_t wave_total[kWaves];
+    uint64_t excl;
+    int64_t next_tile;
+    int aborted;
+};
+
+// 8 elements of a 16-bit array starting at element e0 (e0 is a multiple of 8); elements at or
+// beyond n read as 0.
+__device__ __forceinline__ uint4 load8(const uint16_t *p, int64_t e0, int64_t n)
+{
+    if (e0 + kLaneElems <= n)
+        return *reinterpret_cast<const uint4 *>(p + e0);
+    uint32_t w[4] = {0, 0, 0, 0};
+    for (int t = 0; t < kLaneElems; ++t)
+        if (e0 + t < n)
+            w[t >> 1] |= (uint32_t)p[e0 + t] << ((t & 1) * 16);
+    return make_uint4(w[0], w[1], w[2], w[3]);
+}
+
+__device__ __forceinline__ void store8(uint16_t *p, int64_t e0, int64_t n, uint4 v)
+{
+    if (e0 + kLaneElems <= n) {
+        *reinterpret_cast<uint4 *>(p + e0) = v;
+        return;
+    }
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+    for (int t = 0; t < kLaneElems; ++t)
+        if (e0 + t < n)
+            p[e0 + t] = (uint16_t)(w[t >> 1] >> ((t & 1) * 16));
+}
+
+// bit t = 1 iff 16-bit element t of a differs from element t of b (Algorithm 1 steps 1-2)
+__device__ __forceinline__ uint32_t diff_bits(uint4 a, uint4 b)
+{
+    const uint32_t x[4] = {a.x ^ b.x, a.y ^ b.y, a.z ^ b.z, a.w ^ b.w};
+    uint32_t m = 0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        m |= ((x[j] & 0xFFFFu) != 0u ? 1u : 0u) << (2 * j);
+        m |= ((x[j] >> 16) != 0u ? 1u : 0u) << (2 * j + 1);
+    }
+    return m;
+}
+
+__device__ __forceinline__ uint16_t elem16(const uint4 &v, int t)
+{
+    const uint32_t w = (t >> 1) == 0 ? v.x : (t >> 1) == 1 ? v.y : (t >> 1) == 2 ? v.z : v.w;
+    return (uint16_t)(w >> ((t & 1) * 16));
+}
+
+// Per-lane counts of two chunks -> this lane's exclusive ranks inside the tile and the tile
+// total.  Contains one __syncthreads.
+__device__ __forceinline__ void tile_ranks(TileShared &sh, uint32_t c0, uint32_t c1, int lane, int wave,
+                                           uint32_t &rank0, uint32_t &rank1, uint32_t &tile_total)
+{
+    const uint32_t pk = c0 | (c1 << 16);
+    const uint32_t incl = wave_inclusive_add(pk);
+    const uint32_t tot = read_lane(incl, 63);
+    const uint32_t ex = incl - pk;
+    const uint32_t t0 = tot & 0xFFFFu;
+    if (lane == 0)
+        sh.wave_total[wave] = t0 + (tot >> 16);
+    __syncthreads();
+    uint32_t before = 0, all = 0;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) {
+        const uint32_t v = sh.wave_total[w];
+        before += (w < wave) ? v : 0u;
+        all += v;
+    }
+    rank0 = before + (ex & 0xFFFFu);
+    rank1 = before + t0 + (ex >> 16);
+    tile_total = all;
+}
+
+// Wave 0: publish the tile's count, find the count of everything before it, publish the
+// inclusive value; the result reaches the other waves through sh.excl / sh.aborted.
+__device__ __forceinline__ void tile_prefix(TileShared &sh, ScanHeader *hdr, uint64_t *status, int64_t tile,
+                                            uint32_t epoch, uint32_t spin_limit, uint32_t tile_total, int lane)
+{
+    uint64_t excl = 0;
+    bool aborted = false;
+    if (tile == 0) {
+        if (lane == 0)
+            publish(status, 0, make_status(kFlagInclusive, epoch, tile_total));
+    } else {
+        if (lane == 0)
+            publish(status, tile, make_status(kFlagAggregate, epoch, tile_total));
+        excl = look_back(status, hdr, tile, epoch, spin_limit, aborted);
+        if (lane == 0)
+            publish(status, tile, aborted ? make_status(kFlagAbort, epoch, 0)
+                                          : make_status(kFlagInclusive, epoch, excl + tile_total));
+    }
+    if (lane == 0) {
+        sh.excl = excl;
+        sh.aborted = aborted ? 1 : 0;
+    }
+}
+
+__global__ __launch_bounds__(kBlock) void encode_sparse_kernel(
+    const uint16_t *__restrict__ cur, const uint16_t *__restrict__ base, int64_t n, uint8_t *__restrict__ mask,
+    int64_t mask_bytes, uint16_t *__restrict__ payload, int64_t capacity, uint32_t *__restrict__ tile_offsets,
+    uint64_t *__restrict__ n_changed, ScanHeader *hdr, uint64_t *status, int64_t status_cap, int64_t num_tiles,
+    uint32_t spin_limit)
+{
+    __shared__ TileShared sh;
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
+    const uint32_t epoch = hdr->epoch;
+    bool aborted = false;
+
+    if (tid == 0)
+        sh.next_tile = (int64_t)atomicAdd(&hdr->ticket, 1u);
+    __syncthreads();
+    int64_t tile = sh.next_tile;
+
+    while (tile < num_tiles) {
+        uint32_t next_ticket = 0;
+        if (tid == 0)
+            next_ticket = atomicAdd(&hdr->ticket, 1u);  // claimed now, consumed at the end of this tile
+
+        const int64_t chunk0 = tile * (kTileElems / kChunkElems) + wave * kChunksPerWave;
+        const int64_t e0 = chunk0 * kChunkElems + lane * kLaneElems, e1 = e0 + kChunkElems;
+        const uint4 c0 = load8(cur, e0, n), b0 = load8(base, e0, n);
+        const uint4 c1 = load8(cur, e1, n), b1 = load8(base, e1, n);
+        const uint32_t m0 = diff_bits(c0, b0), m1 = diff_bits(c1, b1);
+
+        // Algorithm 1 steps 3-4: one mask byte per lane; bytes past ceil(n/8) come out as 0
+        const int64_t mb0 = chunk0 * kWave + lane, mb1 = mb0 + kWave;
+        if (mb0 < mask_bytes)
+            mask[mb0] = (uint8_t)m0;
+        if (mb1 < mask_bytes)
+            mask[mb1] = (uint8_t)m1;
+
+        uint32_t r0, r1, total;
+        tile_ranks(sh, __popc(m0), __popc(m1), lane, wave, r0, r1, total);
+        if (wave == 0) {
+            tile_prefix(sh, hdr, status, tile, epoch, spin_limit, total, lane);
+            if (lane == 0)
+                sh.next_tile = (int64_t)next_ticket;
+        }
+        __syncthreads();
+        const uint64_t excl = sh.excl;
+        if (sh.aborted) {
+            aborted = true;
+            break;
+        }
+        if (tid == 0) {
+            if (tile_offsets)
+                tile_offsets[tile] = (uint32_t)excl;
+            if (tile == num_tiles - 1)
+                *n_changed = excl + total;
+        }
+
+        // Algorithm 1 step 5: changed values, in index order.  Staged at (offset mod 8) so that
+        // 16-byte pieces of LDS line up with 16-byte pieces of the payload buffer.
+        const uint32_t shift = (uint32_t)(excl & 7u);
+        uint32_t p0 = shift + r0, p1 = shift + r1;
+#pragma unroll
+        for (int t = 0; t < kLaneElems; ++t) {
+            if ((m0 >> t) & 1u)
+                sh.stage[p0++] = elem16(c0, t);
+        }
+#pragma unroll
+        for (int t = 0; t < kLaneElems; ++t) {
+            if ((m1 >> t) & 1u)
+                sh.stage[p1++] = elem16(c1, t);
+        }
+        __syncthreads();
+        const uint32_t first = shift, last = shift + total;  // valid staged range [first, last)
+        const int64_t dst0 = (int64_t)(excl - shift);         // payload element of stage[0], multiple of 8
+        const uint32_t pieces = (last + 7u) >> 3;
+        for (uint32_t q = tid; q < pieces; q += kBlock) {
+            const uint32_t lo = q * 8u;
+            const int64_t d = dst0 + lo;
+            if (lo >= first && lo + 8u <= last && d + 8 <= capacity) {
+                *reinterpret_cast<uint4 *>(payload + d) = *reinterpret_cast<const uint4 *>(&sh.stage[lo]);
+            } else {
+                for (uint32_t t = 0; t < 8u; ++t) {
+                    const uint32_t i = lo + t;
+                    if (i >= first && i < last && d + t < capacity)
+                        payload[d + t] = sh.stage[i];
+                }
+            }
+        }
+        tile = sh.next_tile;  // written before the barrier above
+        // the next iteration's first write to sh.stage comes after two more barriers
+    }
+    scan_epilogue(hdr, status, status_cap, epoch, aborted, num_tiles, n_changed);
+}
+
+__global__ __launch_bounds__(kBlock) void decode_sparse_kernel(
+    const uint16_t *base, const uint8_t *__restrict__ mask, const uint16_t *__restrict__ payload,
+    int64_t payload_elems, int64_t n, uint16_t *out, uint64_t *__restrict__ n_changed, ScanHeader *hdr,
+    uint64_t *status, int64_t status_cap, int64_t num_tiles, uint32_t spin_limit)
+{
+    __shared__ TileShared sh;
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
+    const uint32_t epoch = hdr->epoch;
+    const int64_t mask_bytes = (n + 7) >> 3;
+    bool aborted = false;
+
+    if (tid == 0)
+        sh.next_tile = (int64_t)atomicAdd(&hdr->ticket, 1u);
+    __syncthreads();
+    int64_t tile = sh.next_tile;
+
+    while (tile < num_tiles) {
+        uint32_t next_ticket = 0;
+        if (tid == 0)
+            next_ticket = atomicAdd(&hdr->ticket, 1u);
+
+        const int64_t chunk0 = tile * (kTileElems / kChunkElems) + wave * kChunksPerWave;
+        const int64_t e0 = chunk0 * kChunkElems + lane * kLaneElems, e1 = e0 + kChunkElems;
+        const int64_t mb0 = chunk0 * kWave + lane, mb1 = mb0 + kWave;
+        uint32_t m0 = (mb0 < mask_bytes) ? mask[mb0] : 0u;
+        uint32_t m1 = (mb1 < mask_bytes) ? mask[mb1] : 0u;
+        // bits at or beyond n carry no element
+        if (e0 + kLaneElems > n)
+            m0 &= (e0 < n) ? ((1u << (uint32_t)(n - e0)) - 1u) : 0u;
+        if (e1 + kLaneElems > n)
+            m1 &= (e1 < n) ? ((1u << (uint32_t)(n - e1)) - 1u) : 0u;
+        uint4 v0 = load8(base, e0, n), v1 = load8(base, e1, n);  // in flight during the scan
+
+        uint32_t r0, r1, total;
+        tile_ranks(sh, __popc(m0), __popc(m1), lane, wave, r0, r1, total);
+        if (wave == 0) {
+            tile_prefix(sh, hdr, status, tile, epoch, spin_limit, total, lane);
+            if (lane == 0)
+                sh.next_tile = (int64_t)next_ticket;
+        }
+        __syncthreads();
+        const uint64_t excl = sh.excl;
+        if (sh.aborted) {
+            aborted = true;
+            break;
+        }
+        if (tid == 0 && n_changed && tile == num_tiles - 1)
+            *n_changed = excl + total;
+
+        // the tile's payload segment [excl, excl+total) -> LDS, as aligned 16-byte pieces
+        const uint32_t shift = (uint32_t)(excl & 7u);
+        const uint32_t last = shift + total;
+        const int64_t src0 = (int64_t)(excl - shift);
+        const uint32_t pieces = (last + 7u) >> 3;
+        for (uint32_t q = tid; q < pieces; q += kBlock) {
+            const uint32_t lo = q * 8u;
+            const int64_t s = src0 + lo;
+            uint4 v = make_uint4(0, 0, 0, 0);
+            if (s + 8 <= payload_elems) {
+                v = *reinterpret_cast<const uint4 *>(payload + s);
+            } else {
+                uint32_t w[4] = {0, 0, 0, 0};
+                for (int t = 0; t < 8; ++t)
+                    if (s + t < payload_elems)
+                        w[t >> 1] |= (uint32_t)payload[s + t] << ((t & 1) * 16);
+                v = make_uint4(w[0], w[1], w[2], w[3]);
+            }
+            *reinterpret_cast<uint4 *>(&sh.stage[lo]) = v;
+        }
+        __syncthreads();
+
+        uint32_t p0 = shift + r0, p1 = shift + r1;
+        uint32_t w0[4] = {v0.x, v0.y, v0.z, v0.w}, w1[4] = {v1.x, v1.y, v1.z, v1.w};
+#pragma unroll
+        for (int t = 0; t < kLaneElems; ++t) {
+            if ((m0 >> t) & 1u) {
+                const uint32_t s = sh.stage[p0++];
+                w0[t >> 1] = (t & 1) ? ((w0[t >> 1] & 0x0000FFFFu) | (s << 16)) : ((w0[t >> 1] & 0xFFFF0000u) | s);
+            }
+        }
+#pragma unroll
+        for (int t = 0; t < kLaneElems; ++t) {
+            if ((m1 >> t) & 1u) {
+                const uint32_t s = sh.stage[p1++];
+                w1[t >> 1] = (t & 1) ? ((w1[t >> 1] & 0x0000FFFFu) | (s << 16)) : ((w1[t >> 1] & 0xFFFF0000u) | s);
+            }
+        }
+        store8(out, e0, n, make_uint4(w0[0], w0[1], w0[2], w0[3]));
+        store8(out, e1, n, make_uint4(w1[0], w1[1], w1[2], w1[3]));
+        tile = sh.next_tile;
+        __syncthreads();  // sh.stage is refilled right after the next scan; keep readers ahead of it
+    }
+    scan_epilogue(hdr, status, status_cap, epoch, aborted, num_tiles, n_changed);
+}
+
+static uint32_t g_spin_limit = kDefaultSpinLimit;
+
+static int sparse_grid(const void *kernel, int64_t num_tiles)
+{
+    const DeviceInfo &di = device_info();
+    int per_cu = occupancy_blocks_per_cu(kernel, kBlock);
+    int64_t resident = (int64_t)di.cu_count * per_cu;
+    int64_t g = num_tiles < resident ? num_tiles : resident;
+    return (int)(g < 1 ? 1 : g);
+}
+
+static int check_workspace(void *workspace, size_t workspace_bytes, int64_t n)
+{
+    if (!workspace)
+        return BITSNAP_E_NULL;
+    if (!aligned16(workspace))
+        return BITSNAP_E_ALIGN;
+    if (workspace_bytes < bitsnap_sparse_workspace_bytes(n))
+        return BITSNAP_E_WORKSPACE;
+    return BITSNAP_OK;
+}
+
+}  // namespace bitsnap
+
+using namespace bitsnap;
+
+extern "C" size_t bitsnap_sparse_tile_elems(void) { return (size_t)kTileElems; }
+
+extern "C" size_t bitsnap_sparse_mask_bytes(int64_t n)
+{
+    if (n <= 0)
+        return 0;
+    return (size_t)((((n + 7) / 8) + 15) / 16 * 16);
+}
+
+extern "C" size_t bitsnap_sparse_workspace_bytes(int64_t n)
+{
+    const int64_t tiles = n <= 0 ? 0 : (n + kTileElems - 1) / kTileElems;
+    const size_t bytes = kScanHeaderBytes + (size_t)tiles * sizeof(uint64_t);
+    return (bytes + 255) / 256 * 256;
+}
+
+extern "C" void bitsnap_debug_set_spin_limit(uint32_t polls) { g_spin_limit = polls ? polls : kDefaultSpinLimit; }
+
+extern "C" int bitsnap_encode_sparse(const void *cur, const void *base, int64_t n, int elem_bytes, uint8_t *mask,
+                                     void *payload, int64_t payload_capacity_elems, uint32_t *tile_offsets,
+                                     uint64_t *n_changed, void *workspace, size_t workspace_bytes,
+                                     bitsnap_stream_t stream)
+{
+    if (n < 0 || elem_bytes != 2 || payload_capacity_elems < 0 || n >= (int64_t)1 << kValueBits)
+        return BITSNAP_E_SIZE;
+    if (!n_changed || (n > 0 && (!cur || !base || !mask)) || (payload_capacity_elems > 0 && !payload))
+        return BITSNAP_E_NULL;
+    if (!aligned16(cur) || !aligned16(base) || !aligned16(mask) || !aligned16(payload) ||
+        ((uintptr_t)n_changed & 7u) || ((uintptr_t)tile_offsets & 3u))
+        return BITSNAP_E_ALIGN;
+    if (int rc = check_workspace(workspace, workspace_bytes, n))
+        return rc;
+    if (tile_offsets && n >= (int64_t)1 << 32)
+        return BITSNAP_E_OFFSETS;
+    const int64_t num_tiles = (n + kTileElems - 1) / kTileElems;
+    ScanHeader *hdr = reinterpret_cast<ScanHeader *>(workspace);
+    uint64_t *status = reinterpret_cast<uint64_t *>(reinterpret_cast<char *>(workspace) + kScanHeaderBytes);
+    const int64_t status_cap = (int64_t)((workspace_bytes - kScanHeaderBytes) / sizeof(uint64_t));
+    const int grid = sparse_grid(reinterpret_cast<const void *>(&encode_sparse_kernel), num_tiles);
+    hipLaunchKernelGGL(encode_sparse_kernel, dim3(grid), dim3(kBlock), 0, (hipStream_t)stream,
+                       (const uint16_t *)cur, (const uint16_t *)base, n, mask, (int64_t)bitsnap_sparse_mask_bytes(n),
+                       (uint16_t *)payload, payload_capacity_elems, tile_offsets, n_changed, hdr, status, status_cap,
+                       num_tiles, g_spin_limit);
+    return launch_status();
+}
+
+extern "C" int bitsnap_decode_sparse(const void *base, const uint8_t *mask, const void *payload, int64_t payload_elems,
+                                     int64_t n, int elem_bytes, void *out, uint64_t *n_changed, void *workspace,
+                                     size_t workspace_bytes, bitsnap_stream_t stream)
+{
+    if (n < 0 || elem_bytes != 2 || payload_elems < 0 || n >= (int64_t)1 << kValueBits)
+        return BITSNAP_E_SIZE;
+    if ((n > 0 && (!base || !mask || !out)) || (payload_elems > 0 && !payload))
+        return BITSNAP_E_NULL;
+    if (!aligned16(base) || !aligned16(mask) || !aligned16(payload) || !aligned16(out) || ((uintptr_t)n_changed & 7u))
+        return BITSNAP_E_ALIGN;
+    if (int rc = check_workspace(workspace, workspace_bytes, n))
+        return rc;
+    const int64_t num_tiles = (n + kTileElems - 1) / kTileElems;
+    ScanHeader *hdr = reinterpret_cast<ScanHeader *>(workspace);
+    uint64_t *status = reinterpret_cast<uint64_t *>(reinterpret_cast<char *>(workspace) + kScanHeaderBytes);
+    const int64_t status_cap = (int64_t)((workspace_bytes - kScanHeaderBytes) / sizeof(uint64_t));
+    const int grid = sparse_grid(reinterpret_cast<const void *>(&decode_sparse_kernel), num_tiles);
+    hipLaunchKernelGGL(decode_sparse_kernel, dim3(grid), dim3(kBlock), 0, (hipStream_t)stream,
+                       (const uint16_t *)base, mask, (const uint16_t *)payload, payload_elems, n, (uint16_t *)out,
+                       n_changed, hdr, status, status_cap, num_tiles, g_spin_limit);
+    return launch_status();
+}

@@ -1,0 +1,151 @@
+// Cross-workgroup exclusive scan of per-tile counts: single pass, decoupled look-back.
+//
+// Workspace layout: a 256-byte header, then one 64-bit status word per tile.
+//   word = [63:62] flag | [61:40] epoch tag | [39:0] value
+// A word only counts if its epoch tag equals the header's epoch, so the words a previous call
+// left behind read as "not yet written" and nothing has to be cleared between calls.  The
+// workgroup that finishes last advances the epoch and resets the counters; when the 22-bit tag
+// is about to wrap it clears every status word the workspace can hold, so a stale word can never
+// be taken for a fresh one.
+//
+// Tiles are handed out through an atomic ticket, so a tile only ever waits for tiles that a
+// running workgroup has already claimed: forward progress does not depend on the order in which
+// the hardware dispatches workgroups.  Every wait is bounded: after `spin_limit` polls a
+// workgroup marks its tile aborted, raises header.error, and leaves; the others see either the
+// aborted word or the error flag and leave too, so every wave reaches the end of the kernel.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "wave.hpp"
+
+namespace bitsnap {
+
+constexpr uint32_t kFlagAggregate = 1;  // value = the tile's own count
+constexpr uint32_t kFlagInclusive = 2;  // value = count of this tile and all before it
+constexpr uint32_t kFlagAbort = 3;      // the tile's workgroup gave up
+constexpr int kEpochBits = 22;
+constexpr uint32_t kEpochMask = (1u << kEpochBits) - 1;
+constexpr int kValueBits = 40;
+constexpr uint64_t kValueMask = (1ull << kValueBits) - 1;
+constexpr size_t kScanHeaderBytes = 256;
+constexpr uint32_t kDefaultSpinLimit = 1u << 22;
+
+struct ScanHeader {
+    uint32_t ticket;  // next tile to hand out
+    uint32_t done;    // workgroups that have finished
+    uint32_t epoch;   // tag of the call in flight
+    uint32_t error;   // non-zero once a workgroup has given up
+};
+
+__device__ __forceinline__ uint64_t make_status(uint32_t flag, uint32_t epoch, uint64_t value)
+{
+    return ((uint64_t)((flag << kEpochBits) | epoch) << kValueBits) | (value & kValueMask);
+}
+
+__device__ __forceinline__ void publish(uint64_t *status, int64_t tile, uint64_t word)
+{
+    __hip_atomic_store(&status[tile], word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Number of counted items in tiles [0, tile).  Called by one full wavefront.  On give-up sets
+// `aborted` and returns 0.
+__device__ __forceinline__ uint64_t look_back(uint64_t *status, ScanHeader *hdr, int64_t tile, uint32_t epoch,
+                                              uint32_t spin_limit, bool &aborted)
+{
+    const int lane = lane_id();
+    uint64_t excl = 0;
+    int64_t look = tile - 1;  // nearest predecessor not yet accounted for
+    uint32_t polls = 0;
+    aborted = false;
+    for (;;) {
+        const int64_t idx = look - lane;  // lane 0 looks at the nearest tile
+        uint64_t w;
+        uint32_t flag;
+        for (;;) {
+            // tiles before the first one: a virtual inclusive prefix of 0
+            w = (idx >= 0) ? __hip_atomic_load(&status[idx], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
+                           : make_status(kFlagInclusive, epoch, 0);
+            const uint32_t tag = (uint32_t)(w >> kValueBits);
+            flag = ((tag & kEpochMask) == epoch) ? (tag >> kEpochBits) : 0u;
+            const uint64_t okm = __ballot(flag != 0);
+            const uint64_t incm = __ballot(flag == kFlagInclusive || flag == kFlagAbort);
+            // enough: every lane up to and including the nearest inclusive word is written
+            uint64_t need = ~0ull;
+            if (incm) {
+                const int first = __ffsll((long long)incm) - 1;
+                need = (first == 63) ? ~0ull : ((1ull << (first + 1)) - 1);
+            }
+            if ((okm & need) == need)
+                break;
+            ++polls;
+            if (polls > spin_limit ||
+                ((polls & 63u) == 0 && __hip_atomic_load(&hdr->error, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))) {
+                aborted = true;
+                return 0;
+            }
+            __builtin_amdgcn_s_sleep(1);
+        }
+        const uint64_t incm = __ballot(flag == kFlagInclusive || flag == kFlagAbort);
+        const uint64_t val = w & kValueMask;
+        if (incm) {
+            const int first = __ffsll((long long)incm) - 1;
+            if (__ballot(flag == kFlagAbort) & (1ull << first)) {
+                aborted = true;
+                return 0;
+            }
+            excl += wave_sum_u64(lane <= first ? val : 0ull);
+            return excl;
+        }
+        excl += wave_sum_u64(val);
+        look -= kWave;
+    }
+}
+
+// Last step of every workgroup of a scan kernel (called by all threads, uniformly).  The
+// workgroup that arrives last resets the header for the next call.
+//   aborted        this workgroup gave up
+//   status_cap     number of status words the workspace holds
+//   n_out          nullable: receives UINT64_MAX when any workgroup gave up, `empty_value` when
+//                  there were no tiles at all
+__device__ __forceinline__ void scan_epilogue(ScanHeader *hdr, uint64_t *status, int64_t status_cap, uint32_t epoch,
+                                              bool aborted, int64_t num_tiles, uint64_t *n_out)
+{
+    __shared__ int s_wrap;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int wrap = 0;
+        if (aborted)
+            __hip_atomic_store(&hdr->error, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __threadfence();
+        const uint32_t prev = atomicAdd(&hdr->done, 1u);
+        if (prev == gridDim.x - 1) {
+            __threadfence();
+            const uint32_t err = __hip_atomic_load(&hdr->error, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (n_out) {
+                if (err)
+                    *n_out = ~0ull;
+                else if (num_tiles == 0)
+                    *n_out = 0;
+            }
+            hdr->done = 0;
+            hdr->ticket = 0;
+            hdr->error = 0;
+            if (epoch == kEpochMask)
+                wrap = 1;
+            else
+                hdr->epoch = epoch + 1;
+        }
+        s_wrap = wrap;
+    }
+    __syncthreads();
+    if (s_wrap) {
+        for (int64_t i = threadIdx.x; i < status_cap; i += blockDim.x)
+            status[i] = 0;
+        __syncthreads();
+        if (threadIdx.x == 0)
+            hdr->epoch = 0;
+    }
+}
+
+}  // namespace bitsnap

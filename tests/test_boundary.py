@@ -1,0 +1,94 @@
+"""Host-side checks of the C-ABI boundary: the library loads, exports every symbol the header
+declares, its size helpers follow the stored-size formulas of the paper, and bad arguments are
+rejected on the host before anything is launched (no GPU needed for any of this)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import oracle
+from paper_2511_12376_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "bitsnap.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(bitsnap_[a-z_0-9]+)\s*\(", header))
+    assert declared == set(B.SYMBOLS)
+    L = B.lib()
+    for name in declared:
+        assert getattr(L, name) is not None
+    assert B.version() >= 100
+    assert B.lib().bitsnap_error_string(0) == b"ok"
+    for rc in range(-6, 0):
+        assert b"unknown" not in B.lib().bitsnap_error_string(rc)
+
+
+def test_sparse_size_helpers():
+    T = B.sparse_tile_elems()
+    assert T == 4096
+    for n in [0, 1, 8, 9, 127, 128, 129, 4096, 10**6 + 3]:
+        mb = B.sparse_mask_bytes(n)
+        assert mb % 16 == 0 and mb >= (n + 7) // 8 and mb < (n + 7) // 8 + 16
+        assert B.sparse_workspace_bytes(n) >= 256 + 8 * ((n + T - 1) // T)
+    assert B.sparse_mask_bytes(0) == 0
+
+
+def test_cluster_size_helpers_follow_size_analysis():
+    # per whole-tensor fit: 8m bytes of (S, b) + n/2 label bytes + n code bytes (+8 for the shape = 1.5n + 136)
+    n, m = 1 << 20, 16
+    assert B.cluster_groups(n, 0) == 1 and B.cluster_param_bytes(n, 0, m) == 8 * m
+    assert B.cluster_label_bytes(n) == n // 2 and B.cluster_label_bytes(7) == 4
+    assert n + B.cluster_label_bytes(n) + B.cluster_param_bytes(n, 0, m) + 8 == 1.5 * n + 136
+    assert B.cluster_groups(n, 4096) == 256 and B.cluster_param_bytes(n, 4096, m) == 128 * 256
+    assert B.cluster_groups(4097, 4096) == 2 and B.cluster_groups(100, 4096) == 1 and B.cluster_groups(0, 4096) == 0
+    assert B.cluster_fit_floats(n, 4096, m) == 256 * 17
+
+
+def test_quantile_table_matches_oracle_bit_for_bit():
+    for m in range(2, 17):
+        for k in range(1, m):
+            assert B.cluster_z(k, m) == oracle.norm_quantile(k, m)
+    assert B.cluster_z(0, 16) == 0.0 and B.cluster_z(16, 16) == 0.0 and B.cluster_z(1, 17) == 0.0
+
+
+def test_bad_arguments_are_rejected_on_the_host():
+    L = B.lib()
+    buf = ctypes.create_string_buffer(1 << 16)
+    a = (ctypes.addressof(buf) + 255) // 256 * 256          # an aligned, non-NULL (host) address: never dereferenced
+    ws_bytes = B.sparse_workspace_bytes(4096)
+    enc = lambda cur, base, n, eb, mask, pay, cap, offs, nch, ws, wsb: L.bitsnap_encode_sparse(
+        cur, base, n, eb, mask, pay, cap, offs, nch, ws, wsb, None)
+    assert enc(a, a, -1, 2, a, a, 0, None, a, a, ws_bytes) == -2          # n < 0
+    assert enc(a, a, 4096, 4, a, a, 4096, None, a, a, ws_bytes) == -2     # element width
+    assert enc(None, a, 4096, 2, a, a, 4096, None, a, a, ws_bytes) == -1  # NULL input
+    assert enc(a, a, 4096, 2, a, a, 4096, None, None, a, ws_bytes) == -1  # NULL n_changed
+    assert enc(a + 2, a, 4096, 2, a, a, 4096, None, a, a, ws_bytes) == -3  # misaligned
+    assert enc(a, a, 4096, 2, a, a, 4096, None, a, None, ws_bytes) == -1  # no workspace
+    assert enc(a, a, 4096, 2, a, a, 4096, None, a, a, 16) == -4           # workspace too small
+    assert enc(a, a, 1 << 33, 2, a, a, 0, a, a, a, B.sparse_workspace_bytes(1 << 33)) == -5  # offsets need n < 2^32
+    dec = lambda base, mask, pay, pe, n, eb, out, nch, ws, wsb: L.bitsnap_decode_sparse(
+        base, mask, pay, pe, n, eb, out, nch, ws, wsb, None)
+    assert dec(a, a, a, 0, -5, 2, a, None, a, ws_bytes) == -2
+    assert dec(a, None, a, 0, 4096, 2, a, None, a, ws_bytes) == -1
+    assert dec(a, a, a, 0, 4096, 2, a + 8, None, a, ws_bytes) == -3
+    assert dec(a, a, a, 0, 4096, 2, a, None, a, 100) == -4
+    q = lambda x, n, g, m, codes, labels, params: L.bitsnap_quantize_cluster(
+        x, n, g, m, codes, labels, params, None, None, None, None, 0, None)
+    assert q(a, 4096, 4096, 0, a, a, a) == -2 and q(a, 4096, 4096, 17, a, a, a) == -2
+    assert q(a, -1, 4096, 16, a, a, a) == -2 and q(a, 4096, 1000, 16, a, a, a) == -2
+    assert q(None, 4096, 4096, 16, a, a, a) == -1 and q(a, 4096, 4096, 16, a + 4, a, a) == -3
+    assert q(None, 0, 4096, 16, None, None, None) == 0                     # empty tensor: nothing to do
+    d = lambda codes, labels, params, n, g, m, out: L.bitsnap_dequantize_cluster(codes, labels, params, n, g, m, out, None)
+    assert d(a, a, a, 4096, 4096, 16, None) == -1 and d(a, a, a, 4096, 4096, 16, a + 4) == -3
+    assert d(a, a, a, 4096, 4096, 0, a) == -2 and d(None, None, None, 0, 4096, 16, None) == 0
+
+
+def test_missing_library_fails_loudly(monkeypatch):
+    monkeypatch.setattr(B, "_lib", None)
+    monkeypatch.setattr(B, "LIB_PATH", os.path.join(ROOT, "no_such_dir", "libbitsnap.so"))
+    with pytest.raises(B.BitsnapError):
+        B.version()

@@ -1,0 +1,180 @@
+"""GPU parity: quantize_cluster / dequantize_cluster through the C ABI against the CPU oracle.
+
+Protocol.  The mean and deviation of a group are floating reductions, so the GPU's (mu, sigma)
+may differ from the oracle's in the last bit on rare groups; they are compared at 1e-6 relative.
+Everything after that is a function of the two fp32 numbers, so edges, (S, b), labels and codes
+must be bit-exact: directly where the two fits are bit-identical, and against the oracle re-run
+with the GPU's fit where they are not.  Feeding the oracle's fit to the GPU (fit_in) must be
+bit-exact everywhere.  Dequantised values are compared bit-exactly too (the tolerance the benchmark spec
+allows, 1e-6 of the cluster's magnitude, is asserted as well, separately).
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from gpu_util import DEV, announce, f32_to_dev, to_np
+from paper_2511_12376_amd import binding as B
+from paper_2511_12376_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+def _gpu_quantize(x, G, m, fit_in=None):
+    q = B.quantize_cluster(f32_to_dev(x), G, m, fit_in=None if fit_in is None else f32_to_dev(fit_in.reshape(-1)))
+    torch.cuda.synchronize()
+    return dict(codes=to_np(q.codes), labels=to_np(q.labels), params=to_np(q.params), fit=to_np(q.fit),
+                status=int(q.status.item())), q
+
+
+def _compare(x, G, m):
+    n = x.size
+    o = oracle.quantize_cluster(x, G, m)
+    g, q = _gpu_quantize(x, G, m)
+    assert g["status"] == 0
+    groups = oracle.n_groups(n, G)
+    # (i) fit within 1e-6
+    mu_o, sg_o = o["fit"][:, 0].astype(np.float64), o["fit"][:, 1].astype(np.float64)
+    mu_g, sg_g = g["fit"][:, 0].astype(np.float64), g["fit"][:, 1].astype(np.float64)
+    assert np.all(np.abs(sg_g - sg_o) <= 1e-6 * sg_o)
+    assert np.all(np.abs(mu_g - mu_o) <= 1e-6 * np.maximum(np.abs(mu_o), sg_o))
+    same = (o["fit"][:, 0] == g["fit"][:, 0]) & (o["fit"][:, 1] == g["fit"][:, 1])
+    # (ii)/(iii) everything downstream bit-exact, given the same fit
+    ref = o if same.all() else oracle.quantize_cluster(x, G, m, fit_in=g["fit"][:, :2])
+    for k in ("fit", "params", "labels", "codes"):
+        assert np.array_equal(g[k], ref[k]), k
+    # (iv) oracle's fit injected into the GPU
+    gi, _ = _gpu_quantize(x, G, m, fit_in=o["fit"][:, :2].copy())
+    for k in ("fit", "params", "labels", "codes"):
+        assert np.array_equal(gi[k], o[k]), "fit_in " + k
+    # dequantise: GPU on its own output vs oracle on the same bytes
+    xh = to_np(B.dequantize_cluster(q.codes, q.labels, q.params, n, G, m))
+    torch.cuda.synchronize()
+    xo = oracle.dequantize_cluster(g["codes"], g["labels"], g["params"], n, G, m)
+    assert np.array_equal(xh, xo)
+    lab = oracle.unpack_labels(g["labels"], n)
+    grp = np.arange(n) // (G if 0 < G <= n else n)
+    S = g["params"][grp, lab, 0].astype(np.float64)
+    b = g["params"][grp, lab, 1].astype(np.float64)
+    scale = np.maximum(np.abs(b), np.abs(b + S))
+    assert np.all(np.abs(xh.astype(np.float64) - xo) <= 1e-6 * scale)
+    # and the quantisation error bound of the method itself
+    with np.errstate(divide="ignore", over="ignore"):
+        coded = np.isfinite(np.float32(255.0) / g["params"][grp, lab, 0])     # a range too small to code keeps b only
+    bound = np.where(coded, S / 510 * (1 + 1e-5), S)
+    assert np.all(np.abs(xh.astype(np.float64) - x) <= bound + 2 * np.spacing(np.abs(x)).astype(np.float64))
+    return int((~same).sum()), groups
+
+
+SIZES = [1, 5, 255, 256, 257, 4095, 4096, 4097, 3 * 4096 + 123, 1_000_003]
+
+
+@pytest.mark.parametrize("n", SIZES)
+@pytest.mark.parametrize("G,m", [(4096, 16), (256, 16), (1024, 5), (4096, 1), (2048, 2), (512, 16)])
+def test_quantize_dequantize_match_oracle(n, G, m):
+    announce("cluster", n, G, m)
+    rng = np.random.default_rng(n * 7 + G + m)
+    x = (rng.standard_normal(n) * 10.0 ** rng.integers(-6, 1) + rng.standard_normal() * 1e-4).astype(np.float32)
+    _compare(x, G, m)
+
+
+def test_config0_optimizer_states():
+    cfg = synth.config(0)
+    differing = total = 0
+    for t in (0, 1, 4, 10, 12):
+        d = synth.make_tensor_np(cfg, t)
+        for key in ("master", "m", "v"):
+            announce("cluster config0", t, key)
+            a, b = _compare(d[key], 4096, 16)
+            differing += a
+            total += b
+    print(f"groups whose fp32 (mu, sigma) differ between GPU and oracle: {differing} of {total}")
+    assert differing <= max(1, total // 1000)
+
+
+def test_adam_simulated_states_config2_recipe():
+    announce("cluster adam recipe")
+    d = synth.make_tensor_np(synth.config(2), 2, n_limit=64 * 4096 + 5, adam_steps=20)
+    for key in ("master", "m", "v"):
+        _compare(d[key], 4096, 16)
+
+
+def test_degenerate_groups():
+    announce("cluster degenerate")
+    rng = np.random.default_rng(4)
+    x = (rng.standard_normal(5 * 4096) * 1e-4).astype(np.float32)
+    x[:4096] = 3.25                                               # constant group
+    x[4096 + 100] = 5.0                                           # one outlier
+    x[2 * 4096:3 * 4096] = np.where(np.arange(4096) % 2 == 0, 1.0, 1.0 + 1e-7).astype(np.float32)  # two values
+    x[3 * 4096:4 * 4096] = 0.0                                    # all zero
+    x[4 * 4096:4 * 4096 + 2] = [0.0, 1e-40]                       # denormal range inside a group
+    _compare(x, 4096, 16)
+    # sub-normal spread only: 255/S overflows, codes must be 0, S kept
+    y = np.zeros(256, np.float32)
+    y[1::2] = 1e-40
+    _compare(y, 256, 1)
+
+
+def test_non_finite_input_sets_status_and_stays_in_bounds():
+    announce("cluster non-finite")
+    x = np.random.default_rng(1).standard_normal(3 * 4096).astype(np.float32)
+    x[5000] = np.inf
+    x[9000] = np.nan
+    g, q = _gpu_quantize(x, 4096, 16)
+    assert g["status"] & 1
+    o = oracle.quantize_cluster(x[:4096].copy(), 4096, 16)        # the clean group is unaffected
+    assert np.array_equal(g["codes"][:4096], o["codes"]) and np.array_equal(g["params"][0], o["params"][0])
+    out = B.dequantize_cluster(q.codes, q.labels, q.params, x.size, 4096, 16)
+    torch.cuda.synchronize()
+    assert out.shape[0] == x.size
+
+
+def test_dequantize_oracle_bytes():
+    """GPU dequantise fed with the ORACLE's compressed bytes reproduces the oracle's output."""
+    announce("cluster dequantize oracle bytes")
+    rng = np.random.default_rng(8)
+    n = 7 * 4096 + 1001
+    x = (rng.standard_normal(n) ** 2 * 1e-8).astype(np.float32)
+    o = oracle.quantize_cluster(x, 4096, 16)
+    codes = torch.from_numpy(o["codes"]).to(DEV)
+    labels = torch.from_numpy(o["labels"]).to(DEV)
+    params = torch.from_numpy(o["params"]).to(DEV)
+    xh = to_np(B.dequantize_cluster(codes, labels, params, n, 4096, 16))
+    assert np.array_equal(xh, oracle.dequantize_cluster(o["codes"], o["labels"], o["params"], n, 4096, 16))
+
+
+def test_full_size_tensor_sampled_groups():
+    """Llama-2-7B's largest tensor (32000 x 4096 fp32) in the benchmark's launch configuration;
+    the oracle recomputes sampled groups one by one."""
+    announce("cluster full size sampled")
+    n = 32000 * 4096
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(synth.seed_for(2, 0))
+    x = torch.randn(n, device=DEV, generator=gen).mul_(2e-4)
+    q = B.quantize_cluster(x, 4096, 16)
+    xh = B.dequantize_cluster(q.codes, q.labels, q.params, n, 4096, 16)
+    torch.cuda.synchronize()
+    assert int(q.status.item()) == 0
+    groups = n // 4096
+    rng = np.random.default_rng(3)
+    differ = 0
+    for g in [0, 1, groups - 1] + list(rng.integers(0, groups, 60)):
+        lo, hi = g * 4096, (g + 1) * 4096
+        xs = to_np(x[lo:hi])
+        fit_g = to_np(q.fit[g])
+        o = oracle.quantize_cluster(xs, 4096, 16)
+        assert abs(float(fit_g[1]) - float(o["fit"][0, 1])) <= 1e-6 * float(o["fit"][0, 1])
+        if not np.array_equal(fit_g[:2], o["fit"][0, :2]):
+            differ += 1
+            o = oracle.quantize_cluster(xs, 4096, 16, fit_in=fit_g[:2].copy())
+        assert np.array_equal(fit_g, o["fit"][0])
+        assert np.array_equal(to_np(q.params[g]), o["params"][0])
+        assert np.array_equal(to_np(q.codes[lo:hi]), o["codes"])
+        assert np.array_equal(to_np(q.labels[lo // 2:hi // 2]), o["labels"])
+        assert np.array_equal(to_np(xh[lo:hi]), oracle.dequantize_cluster(o["codes"], o["labels"], o["params"], 4096, 4096, 16))
+    assert differ <= 1
+    # a property that holds at any size: the error bound, checked on the whole tensor on the device
+    lab = torch.stack([q.labels & 15, q.labels >> 4], dim=1).reshape(-1).long()
+    S = q.params[:, :, 0].reshape(-1)[torch.arange(n, device=DEV) // 4096 * 16 + lab]
+    err = (xh.double() - x.double()).abs()
+    assert bool((err <= S.double() / 510 + 5e-7 * (x.abs().double() + S.double())).all())   # + fp32 rounding of q*step + b

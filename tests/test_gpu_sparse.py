@@ -1,0 +1,199 @@
+"""GPU parity: encode_sparse / decode_sparse through the C ABI against the CPU oracle, element by
+element, bit-exact (masks, offsets, payloads, counts, round trips)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from gpu_util import DEV, announce, dev_to_u16, to_np, u16_to_dev
+from paper_2511_12376_amd import binding as B
+from paper_2511_12376_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+T = 4096
+SIZES = [0, 1, 7, 8, 9, 63, 64, 65, 511, 512, 513, T - 1, T, T + 1, 2 * T - 1, 2 * T, 3 * T + 777, 1_000_003]
+
+
+def _pair(n, p, seed):
+    rng = np.random.default_rng(seed)
+    base = rng.integers(0, 1 << 16, n, dtype=np.uint16)
+    cur = base.copy()
+    sel = rng.random(n) < p
+    cur[sel] ^= rng.integers(1, 1 << 16, n, dtype=np.uint16)[sel]
+    return cur, base
+
+
+def _check_encode(cur, base, ws=None, capacity=None):
+    n = cur.size
+    o_mask, o_pay, o_nc = oracle.encode_sparse(cur, base)
+    enc = B.encode_sparse(u16_to_dev(cur), u16_to_dev(base), want_offsets=True, workspace=ws, capacity=capacity)
+    torch.cuda.synchronize()
+    nc = int(enc.n_changed.item())
+    assert nc == o_nc
+    mask = to_np(enc.mask)
+    nb = (n + 7) // 8
+    assert np.array_equal(mask[:nb], o_mask)
+    assert not mask[nb:].any()                                    # padding bytes are zero
+    cap = n if capacity is None else capacity
+    k = min(nc, cap)
+    assert np.array_equal(to_np(enc.payload).view(np.uint16)[:k], o_pay[:k])
+    ntiles = (n + T - 1) // T
+    offs = oracle.tile_offsets(o_mask, n, T)
+    assert np.array_equal(to_np(enc.tile_offsets).view(np.uint32)[:ntiles], offs[:ntiles].astype(np.uint32))
+    return enc, o_mask, o_pay, o_nc
+
+
+@pytest.mark.parametrize("n", SIZES)
+@pytest.mark.parametrize("p", [0.0, 0.06, 0.5, 1.0])
+def test_encode_decode_match_oracle(n, p):
+    announce("sparse", n, p)
+    cur, base = _pair(n, p, 31 * n + int(100 * p))
+    enc, o_mask, o_pay, o_nc = _check_encode(cur, base)
+    # decode the GPU's own output and the oracle's output; both must give cur back
+    out, nch = B.decode_sparse(u16_to_dev(base), enc.mask, enc.payload, o_nc)
+    torch.cuda.synchronize()
+    assert int(nch.item()) == o_nc
+    assert np.array_equal(dev_to_u16(out), cur)
+    o_out = oracle.decode_sparse(base, o_mask, o_pay)
+    mask_d = torch.zeros(max(B.sparse_mask_bytes(n), 16), dtype=torch.uint8, device=DEV)
+    mask_d[: o_mask.size] = torch.from_numpy(o_mask).to(DEV)
+    pay_d = torch.from_numpy(np.concatenate([o_pay, np.zeros(8, np.uint16)]).view(np.int16)).to(DEV)
+    out2, _ = B.decode_sparse(u16_to_dev(base), mask_d, pay_d, o_nc)
+    torch.cuda.synchronize()
+    assert np.array_equal(dev_to_u16(out2), o_out)
+
+
+def test_decode_in_place_and_special_patterns():
+    announce("sparse in-place / -0 / NaN")
+    pats = np.array([0x0000, 0x8000, 0x7FC1, 0x7FC2, 0x7F80, 0x0001], np.uint16)
+    base = np.tile(np.repeat(pats, len(pats)), 300)
+    cur = np.tile(np.tile(pats, len(pats)), 300)
+    enc, _, _, nc = _check_encode(cur, base)
+    assert nc == 300 * len(pats) * (len(pats) - 1)
+    buf = u16_to_dev(base)
+    B.decode_sparse(buf, enc.mask, enc.payload, nc, out=buf)     # patch the base in place
+    torch.cuda.synchronize()
+    assert np.array_equal(dev_to_u16(buf), cur)
+
+
+def test_config0_every_tensor_with_one_workspace():
+    cfg = synth.config(0)
+    ws = B.new_sparse_workspace(max(np.prod(s) for _, s in cfg.tensors), DEV)
+    for t in range(len(cfg.tensors)):
+        announce("sparse config0 tensor", t)
+        d = synth.make_tensor_np(cfg, t)
+        enc, _, _, nc = _check_encode(d["cur"], d["base"], ws=ws)
+        assert nc == d["n_changed"]
+        out, _ = B.decode_sparse(u16_to_dev(d["base"]), enc.mask, enc.payload, nc, workspace=ws)
+        torch.cuda.synchronize()
+        assert np.array_equal(dev_to_u16(out), d["cur"])
+
+
+def test_clustered_runs_config3_shape():
+    announce("sparse config3 runs")
+    d = synth.make_tensor_np(synth.config(3), 2, n_limit=5_000_000 + 13)
+    enc, _, _, nc = _check_encode(d["cur"], d["base"])
+    out, _ = B.decode_sparse(u16_to_dev(d["base"]), enc.mask, enc.payload, nc)
+    torch.cuda.synchronize()
+    assert np.array_equal(dev_to_u16(out), d["cur"])
+
+
+def test_payload_capacity_overflow_is_reported_not_written():
+    announce("sparse capacity overflow")
+    n = 3 * T + 100
+    cur, base = _pair(n, 0.5, 5)
+    cap = 1000
+    o_mask, o_pay, o_nc = oracle.encode_sparse(cur, base)
+    assert o_nc > cap
+    guard = torch.full((cap + 64,), 0x5A5A, dtype=torch.int16, device=DEV)
+    mask = torch.empty(B.sparse_mask_bytes(n), dtype=torch.uint8, device=DEV)
+    nch = torch.zeros(1, dtype=torch.int64, device=DEV)
+    ws = B.new_sparse_workspace(n, DEV)
+    B.encode_sparse_raw(u16_to_dev(cur), u16_to_dev(base), n, mask, guard, cap, None, nch, ws)
+    torch.cuda.synchronize()
+    assert int(nch.item()) == o_nc                                # the true count: overflow is visible
+    g = to_np(guard).view(np.uint16)
+    assert np.array_equal(g[:cap], o_pay[:cap]) and np.all(g[cap:] == 0x5A5A)
+    assert np.array_equal(to_np(mask)[: o_mask.size], o_mask)
+    # decode with too few payload elements stays in bounds: surplus elements read as 0
+    out, _ = B.decode_sparse(u16_to_dev(base), mask, guard, cap, workspace=ws)
+    torch.cuda.synchronize()
+    got = dev_to_u16(out)
+    bits = np.unpackbits(o_mask, bitorder="little")[:n].astype(bool)
+    rank = np.cumsum(bits) - 1
+    ok = ~bits | (rank < cap)
+    assert np.array_equal(got[ok], cur[ok]) and not got[~ok].any()
+
+
+def test_workspace_reuse_and_epoch_wrap():
+    announce("sparse workspace reuse / epoch wrap")
+    nmax = 40 * T
+    ws = B.new_sparse_workspace(nmax, DEV)
+    hdr = ws[:16].view(torch.int32)
+    rng = np.random.default_rng(0)
+    for it in range(12):
+        if it == 4:
+            torch.cuda.synchronize()
+            hdr[2] = (1 << 22) - 3                                 # two calls before the 22-bit tag wraps
+            torch.cuda.synchronize()
+        n = int(rng.integers(1, nmax))
+        cur, base = _pair(n, 0.3, 900 + it)
+        _check_encode(cur, base, ws=ws)
+    torch.cuda.synchronize()
+    h = to_np(hdr)
+    assert h[0] == 0 and h[1] == 0 and h[3] == 0                   # ticket, done, error are reset
+    assert 0 < h[2] < 16                                           # the tag wrapped and started again
+
+
+def test_give_up_path_reports_and_recovers():
+    """With a spin limit of one poll, workgroups that have to wait give up.  The call must still
+    finish, report the failure through n_changed, and leave the workspace usable."""
+    announce("sparse give-up path")
+    n = 2000 * T
+    cur, base = _pair(n, 0.2, 77)
+    ws = B.new_sparse_workspace(n, DEV)
+    cur_d, base_d = u16_to_dev(cur), u16_to_dev(base)
+    try:
+        B.debug_set_spin_limit(1)
+        enc = B.encode_sparse(cur_d, base_d, workspace=ws)
+        torch.cuda.synchronize()
+        nc = int(enc.n_changed.item())
+    finally:
+        B.debug_set_spin_limit(0)
+    o_mask, o_pay, o_nc = oracle.encode_sparse(cur, base)
+    assert nc == o_nc or nc == -1                                  # UINT64_MAX read as int64
+    enc = B.encode_sparse(cur_d, base_d, workspace=ws)             # the same workspace, normal limit
+    torch.cuda.synchronize()
+    assert int(enc.n_changed.item()) == o_nc
+    assert np.array_equal(to_np(enc.payload).view(np.uint16)[:o_nc], o_pay)
+
+
+def test_full_size_tensor_sampled_tiles():
+    """Llama-2-7B's largest tensor shape (32000 x 4096), in the launch configuration the benchmark
+    times.  The oracle recomputes sampled tiles one by one; totals are checked through properties
+    that hold at any size."""
+    announce("sparse full size sampled")
+    cfg = synth.config(1, p=0.06)                                  # Bernoulli recipe, cheap to generate
+    n = 32000 * 4096
+    d = synth.make_tensor_torch(synth.Config(9, "big", "bernoulli", 0.06, 0, (("w", (n,)),)), 0, DEV, want=("base", "cur"))
+    enc = B.encode_sparse(d["cur"], d["base"], want_offsets=True)
+    out, nch = B.decode_sparse(d["base"], enc.mask, enc.payload, n, workspace=enc.workspace)
+    torch.cuda.synchronize()
+    nc = int(enc.n_changed.item())
+    changed = d["cur"].view(torch.int16) != d["base"].view(torch.int16)
+    assert nc == int(changed.sum().item()) == int(nch.item())
+    assert torch.equal(out.view(torch.int16), d["cur"].view(torch.int16))
+    offs = to_np(enc.tile_offsets).view(np.uint32).astype(np.int64)
+    ntiles = n // T
+    per_tile = changed.view(ntiles, T).sum(dim=1).cpu().numpy()
+    assert np.array_equal(offs, np.concatenate([[0], np.cumsum(per_tile)[:-1]]))
+    rng = np.random.default_rng(1)
+    cur16, base16 = d["cur"].view(torch.int16), d["base"].view(torch.int16)
+    for t in [0, 1, ntiles - 1] + list(rng.integers(0, ntiles, 40)):
+        lo = t * T
+        c = cur16[lo:lo + T].cpu().numpy().view(np.uint16)
+        b = base16[lo:lo + T].cpu().numpy().view(np.uint16)
+        o_mask, o_pay, o_nc = oracle.encode_sparse(c, b)
+        assert np.array_equal(to_np(enc.mask[lo // 8:(lo + T) // 8]), o_mask)
+        assert np.array_equal(to_np(enc.payload[offs[t]:offs[t] + o_nc]).view(np.uint16), o_pay)
