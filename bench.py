@@ -1,0 +1,250 @@
+#!/usr/bin/env python3
+"""Benchmark of the BitSnap codec hot path on one MI355X.
+
+A step is one pass of the whole hot path over one synthetic checkpoint that is already resident
+in HBM: encode_sparse of every bf16 weight tensor against its base, quantize_cluster of the fp32
+master weights and both Adam moments, then decode_sparse and dequantize_cluster of everything
+that was just produced.  The default workload is the Llama-2-7B-shaped checkpoint (291 tensors,
+6.74 G parameters, 14 bytes of state per parameter) whose next checkpoint comes from 100
+simulated Adam steps.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2] [--limit-tensors N]
+                    [--no-cpu-baseline]
+
+Prints ONE JSON line.  `value` is GB/s of input state: (bytes encoded + bytes decoded) / time.
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes as C
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+GROUP, M = 4096, 16
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--config", type=int, default=2)
+    ap.add_argument("--p", type=float, default=None, help="change fraction for the Bernoulli configs")
+    ap.add_argument("--limit-tensors", type=int, default=0, help="only the first N tensors (debugging)")
+    ap.add_argument("--adam-steps", type=int, default=None)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-tensors", type=int, default=4)
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (every tensor is an independent unit; a multi-GPU job runs "
+              "one such process per rank on its own shard, with no communication).  Use --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    from paper_2511_12376_amd import binding as B
+    from paper_2511_12376_amd import synth
+
+    L = B.lib()                      # raises if the HIP library is not built
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    cfg = synth.config(args.config, p=args.p)
+    tensors = list(range(len(cfg.tensors)))
+    if args.limit_tensors:
+        tensors = tensors[: args.limit_tensors]
+    sizes = [math.prod(cfg.tensors[t][1]) for t in tensors]
+    n_total, n_max = sum(sizes), max(sizes)
+
+    # ------------------------------------------------------------------ inputs, resident in HBM
+    t0 = time.time()
+    inputs = []
+    for t in tensors:
+        d = synth.make_tensor_torch(cfg, t, dev, adam_steps=args.adam_steps)
+        inputs.append(d)
+    torch.cuda.synchronize()
+    gen_s = time.time() - t0
+
+    # ------------------------------------------------------------------ outputs
+    u8, i16, f32, i64 = torch.uint8, torch.int16, torch.float32, torch.int64
+    ws = B.new_sparse_workspace(n_max, dev)
+    enc = []
+    for n in sizes:
+        g = B.cluster_groups(n, GROUP)
+        e = dict(mask=torch.empty(B.sparse_mask_bytes(n), dtype=u8, device=dev),
+                 payload=torch.empty(n, dtype=i16, device=dev),
+                 n_changed=torch.zeros(1, dtype=i64, device=dev),
+                 q=[dict(codes=torch.empty(n, dtype=u8, device=dev),
+                         labels=torch.empty((n + 1) // 2, dtype=u8, device=dev),
+                         params=torch.empty(g * M * 2, dtype=f32, device=dev)) for _ in range(3)])
+        enc.append(e)
+    RING = 4
+    dec_ring = [torch.empty(n_max, dtype=torch.bfloat16, device=dev) for _ in range(RING)]
+    deq_ring = [torch.empty(n_max, dtype=f32, device=dev) for _ in range(RING)]
+    status = torch.zeros(1, dtype=torch.int32, device=dev)
+    dec_count = torch.zeros(1, dtype=i64, device=dev)
+
+    stream = torch.cuda.current_stream()
+    sp = stream.cuda_stream or None
+    ws_bytes = ws.numel()
+
+    # pre-marshalled argument lists: the timed loop is nothing but the C-ABI calls
+    calls = {"encode_sparse": [], "quantize_cluster": [], "decode_sparse": [], "dequantize_cluster": []}
+    for i, (d, e, n) in enumerate(zip(inputs, enc, sizes)):
+        calls["encode_sparse"].append((d["cur"].data_ptr(), d["base"].data_ptr(), n, 2, e["mask"].data_ptr(),
+                                       e["payload"].data_ptr(), n, None, e["n_changed"].data_ptr(), ws.data_ptr(),
+                                       ws_bytes, sp))
+        calls["decode_sparse"].append((d["base"].data_ptr(), e["mask"].data_ptr(), e["payload"].data_ptr(), n, n, 2,
+                                       dec_ring[i % RING].data_ptr(), dec_count.data_ptr(), ws.data_ptr(), ws_bytes, sp))
+        for j, key in enumerate(("master", "m", "v")):
+            q = e["q"][j]
+            calls["quantize_cluster"].append((d[key].data_ptr(), n, GROUP, M, q["codes"].data_ptr(),
+                                              q["labels"].data_ptr(), q["params"].data_ptr(), None, None,
+                                              status.data_ptr(), None, 0, sp))
+            calls["dequantize_cluster"].append((q["codes"].data_ptr(), q["labels"].data_ptr(), q["params"].data_ptr(),
+                                                n, GROUP, M, deq_ring[(3 * i + j) % RING].data_ptr(), sp))
+    fns = {"encode_sparse": L.bitsnap_encode_sparse, "quantize_cluster": L.bitsnap_quantize_cluster,
+           "decode_sparse": L.bitsnap_decode_sparse, "dequantize_cluster": L.bitsnap_dequantize_cluster}
+    order = ["encode_sparse", "quantize_cluster", "decode_sparse", "dequantize_cluster"]
+
+    def run_step(events=None):
+        for k, op in enumerate(order):
+            if events is not None:
+                events[k].record(stream)
+            fn = fns[op]
+            for a in calls[op]:
+                rc = fn(*a)
+                if rc != 0:
+                    raise RuntimeError(f"{op}: {L.bitsnap_error_string(rc).decode()}")
+        if events is not None:
+            events[len(order)].record(stream)
+
+    for _ in range(args.warmup):
+        run_step()
+    torch.cuda.synchronize()
+
+    # the timed region: exactly --steps steps between two synchronisations
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(len(order) + 1)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(args.steps):
+        run_step(ev[s])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / args.steps
+
+    # ------------------------------------------------------------------ accounting
+    n_changed = sum(int(e["n_changed"].item()) for e in enc)
+    assert int(status.item()) == 0
+    p = n_changed / n_total
+    groups = sum(B.cluster_groups(n, GROUP) for n in sizes)
+    state_bytes = {"encode_sparse": 2 * n_total, "decode_sparse": 2 * n_total,
+                   "quantize_cluster": 12 * n_total, "dequantize_cluster": 12 * n_total}
+    mask_bytes = sum((n + 7) // 8 for n in sizes)
+    sparse_alg = 4 * n_total + mask_bytes + 2 * n_changed           # cur + base (or base + out) + mask + payload
+    cluster_alg = 3 * (4 * n_total + n_total + (n_total + 1) // 2 + groups * M * 8)
+    alg_bytes = {"encode_sparse": sparse_alg, "decode_sparse": sparse_alg,
+                 "quantize_cluster": cluster_alg, "dequantize_cluster": cluster_alg}
+    op_ms = {op: sum(ev[s][k].elapsed_time(ev[s][k + 1]) for s in range(args.steps)) / args.steps
+             for k, op in enumerate(order)}
+    ops = {}
+    for op in order:
+        sec = op_ms[op] * 1e-3
+        ops[op] = {"ms": round(op_ms[op], 3), "launches": len(calls[op]),
+                   "state_GBps": round(state_bytes[op] / sec / 1e9, 1),
+                   "hbm_GBps": round(alg_bytes[op] / sec / 1e9, 1),
+                   "hbm_frac": round(alg_bytes[op] / sec / 1e9 / HBM_PEAK_GBS, 4)}
+    total_state = sum(state_bytes.values())
+    value = total_state / (ms_per_step * 1e-3) / 1e9
+
+    dominant = max(order, key=lambda op: op_ms[op])
+    kernel_name = {"encode_sparse": "encode_sparse_kernel", "decode_sparse": "decode_sparse_kernel",
+                   "quantize_cluster": "quantize_cluster_kernel<16>", "dequantize_cluster": "dequantize_cluster_kernel<16>"}
+    launches = len(calls[dominant])
+    roofline = {"bound": "hbm", "kernel": kernel_name[dominant],
+                "achieved": round(alg_bytes[dominant] / (op_ms[dominant] * 1e-3) / 1e9, 1),
+                "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(alg_bytes[dominant] / (op_ms[dominant] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                "traffic": read_traffic(kernel_name[dominant]),
+                "launches_per_step": launches,
+                "avg_launch_us": round(op_ms[dominant] * 1e3 / launches, 2),
+                "algorithmic_bytes_per_launch": round(alg_bytes[dominant] / launches)}
+
+    out = {"metric": "checkpoint encode/decode GB/s (input state) and % of HBM peak",
+           "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+           "ms_per_step": round(ms_per_step, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+           "dtype": "u16 compare + f32 (f64 group statistics)", "data": "synthetic",
+           "config": {"workload": f"configs[{cfg.index}] {cfg.name}-shaped checkpoint: {len(tensors)} tensors, "
+                                  f"{n_total} params, bf16 weights vs base + fp32 master/m/v, tensor by tensor",
+                      "recipe": cfg.recipe, "changed_fraction": round(p, 4), "group": GROUP, "clusters": M,
+                      "state_bytes_per_step": total_state, "generation_s": round(gen_s, 1)},
+           "hbm_frac_of_peak": {op: ops[op]["hbm_frac"] for op in order},
+           "ops": ops, "roofline": roofline}
+
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(inputs, sizes, args.cpu_sample_tensors, cfg)
+    print(json.dumps(out), flush=True)
+
+
+def read_traffic(kernel):
+    """HBM bytes per launch of the dominant kernel from the committed counter summary, if present:
+    a line 'traffic_bytes_per_launch <kernel> <bytes>' in profiles/hbm_traffic_llama2_7b.txt."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic_llama2_7b.txt")
+    try:
+        with open(path) as f:
+            for line in f:
+                w = line.split()
+                if len(w) == 3 and w[0] == "traffic_bytes_per_launch" and w[1] == kernel:
+                    return float(w[2])
+    except OSError:
+        pass
+    return None
+
+
+def cpu_baseline(inputs, sizes, k, cfg):
+    """The CPU oracle, as it stands, single thread, on a bounded sample of the same workload: the
+    same four operations on the first `k` 2-D tensors after the embeddings."""
+    import numpy as np
+    import torch
+
+    import oracle
+
+    pick = [i for i, n in enumerate(sizes) if 4_000_000 <= n <= 20_000_000][:k]
+    if not pick:
+        pick = list(range(min(k, len(sizes))))
+    host = []
+    for i in pick:
+        d = inputs[i]
+        host.append(dict(cur=d["cur"].view(torch.int16).cpu().numpy().view(np.uint16),
+                         base=d["base"].view(torch.int16).cpu().numpy().view(np.uint16),
+                         states=[d[key].cpu().numpy() for key in ("master", "m", "v")]))
+    state = 0
+    t0 = time.perf_counter()
+    for h in host:
+        n = h["cur"].size
+        mask, payload, nc = oracle.encode_sparse(h["cur"], h["base"])
+        oracle.decode_sparse(h["base"], mask, payload)
+        for x in h["states"]:
+            q = oracle.quantize_cluster(x, GROUP, M)
+            oracle.dequantize_cluster(q["codes"], q["labels"], q["params"], n, GROUP, M)
+        state += 2 * 14 * n
+    sec = time.perf_counter() - t0
+    return {"value": round(state / sec / 1e9, 4), "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "sample": f"{len(pick)} tensors of configs[{cfg.index}] ({sum(sizes[i] for i in pick)} params: "
+                      f"{', '.join(cfg.tensors[i][0] for i in pick)}), all four operations, {round(sec, 1)} s"}
+
+
+if __name__ == "__main__":
+    main()
