@@ -47,14 +47,26 @@ __device__ __forceinline__ void wave_lds_sync()
 
 __device__ __forceinline__ float comp(const float4 &v, int j) { return j == 0 ? v.x : j == 1 ? v.y : j == 2 ? v.z : v.w; }
 
-// Algorithm 2 step 3 for one value: number of edges <= x, by descending the search tree.
-__device__ __forceinline__ uint32_t label_of(const float *tree, float x)
+typedef float float4v __attribute__((ext_vector_type(4)));
+#define BITSNAP_LDS __attribute__((address_space(3)))
+
+// Byte address of an LDS object, and LDS accesses by byte address.  The label search and the
+// min/max table below carry addresses, not indices, so that one shift-add per step does both the
+// tree descent and the address arithmetic.
+__device__ __forceinline__ uint32_t lds_addr(const void *p) { return (uint32_t)(uintptr_t)(const BITSNAP_LDS void *)p; }
+__device__ __forceinline__ float lds_read_f32(uint32_t a) { return *(const BITSNAP_LDS float *)(uintptr_t)a; }
+__device__ __forceinline__ float2 lds_read_f32x2(uint32_t a)
 {
-    uint32_t node = 1;
-#pragma unroll
-    for (int s = 0; s < 4; ++s)
-        node = 2u * node + (x >= tree[node] ? 1u : 0u);
-    return node - 16u;
+    typedef float float2v __attribute__((ext_vector_type(2)));
+    const float2v t = *(const BITSNAP_LDS float2v *)(uintptr_t)a;
+    return make_float2(t.x, t.y);
+}
+
+// streaming 16-byte load: the data is used once, keep it out of the way of everything else
+__device__ __forceinline__ float4 load_stream(const float *p)
+{
+    const float4v t = __builtin_nontemporal_load(reinterpret_cast<const float4v *>(p));
+    return make_float4(t.x, t.y, t.z, t.w);
 }
 
 template <int K, bool kFull>
@@ -70,7 +82,7 @@ __device__ __forceinline__ void quantize_group(const float *__restrict__ x, int6
     for (int k = 0; k < K; ++k) {
         const int off = k * 256 + lane * 4;
         if (kFull) {
-            v[k] = *reinterpret_cast<const float4 *>(x + lo + off);
+            v[k] = load_stream(x + lo + off);
         } else {
             v[k].x = off + 0 < len ? x[lo + off + 0] : 0.0f;
             v[k].y = off + 1 < len ? x[lo + off + 1] : 0.0f;
@@ -92,6 +104,11 @@ __device__ __forceinline__ void quantize_group(const float *__restrict__ x, int6
         s += ((double)v[k].x + (double)v[k].y) + ((double)v[k].z + (double)v[k].w);  // padding adds 0
     s = wave_sum(s);
     const double mean = s / (double)len;
+    // Keep the group as fp32 in registers: without this the compiler holds on to the fp64 copies
+    // made for the sum above, which doubles the register footprint and halves the occupancy.
+#pragma unroll
+    for (int k = 0; k < K; ++k)
+        asm volatile("" : "+v"(v[k].x), "+v"(v[k].y), "+v"(v[k].z), "+v"(v[k].w));
     double q = 0.0;
 #pragma unroll
     for (int k = 0; k < K; ++k) {
@@ -114,52 +131,91 @@ __device__ __forceinline__ void quantize_group(const float *__restrict__ x, int6
         atomicOr(status, 1u);
 
     // ---- step 2: edges e_k = fl32(mu + sigma * z_k), product and sum rounded separately in fp64
+    float edge = INFINITY;  // edges that do not exist (m < 16) are never <= x
+    if (lane >= 1 && lane < m)
+        edge = (float)__dadd_rn((double)mu, __dmul_rn((double)sigma, kZDev[m][lane]));
     if (lane >= 1 && lane < kMaxClusters) {
-        float e = INFINITY;  // edges that do not exist (m < 16) are never <= x
-        if (lane < m)
-            e = (float)__dadd_rn((double)mu, __dmul_rn((double)sigma, kZDev[m][lane]));
         const int tz = __ffs(lane) - 1;
-        ws.tree[(1 << (3 - tz)) + (lane >> (tz + 1))] = e;
+        ws.tree[(1 << (3 - tz)) + (lane >> (tz + 1))] = edge;
         if (fit_out && lane < m)
-            fit_out[g * (m + 1) + 1 + lane] = e;
+            fit_out[g * (m + 1) + 1 + lane] = edge;
     }
     if (fit_out && lane == 0) {
         fit_out[g * (m + 1) + 0] = mu;
         fit_out[g * (m + 1) + 1] = sigma;
     }
+    const float root = read_lane(edge, 8);  // the middle edge, e_8: first step of every search
     wave_lds_sync();
 
-    // ---- steps 3-4: labels, per-cluster min and max
+    // ---- steps 3-4: labels, per-cluster min and max.
+    // Search state a = byte address of tree node `node`: a = T + 4*node, so the step
+    // node' = 2*node + c is a' = 2a + (c ? 4 - T : -T).  The last step also subtracts T + 64,
+    // which leaves 4*label.
+    const uint32_t T = lds_addr(&ws.tree[0]);
+    const uint32_t a_lo = T + 8u, a_hi = T + 12u;                  // nodes 2 and 3
+    const uint32_t k0 = 0u - T, k1 = 4u - T;
+    const uint32_t k0_last = 0u - 2u * T - 64u, k1_last = 4u - 2u * T - 64u;
+    const uint32_t tab0 = lds_addr(&ws.tab[0][lane]);              // + 256*label: this lane's min of the cluster
+    // The searches run in batches of kBatch float4 (4*kBatch elements): all LDS reads of one tree
+    // level are issued together and waited for once.  Left to itself the compiler's scheduler
+    // finishes one element's read-compare-step chain before starting the next, which exposes
+    // the LDS latency once per element and level; the scheduling barriers keep the batches intact.
+    constexpr int kBatch = K >= 2 ? 2 : 1;
+    constexpr int kB = 4 * kBatch;
     uint32_t packed[(K + 1) / 2];
 #pragma unroll
     for (int i = 0; i < (K + 1) / 2; ++i)
         packed[i] = 0;
 #pragma unroll
-    for (int k = 0; k < K; ++k) {
-        uint32_t l4 = 0;
+    for (int kb = 0; kb < K; kb += kBatch) {
+        float xs[kB];
+        uint32_t a[kB];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            if (kFull || k * 256 + lane * 4 + j < len) {
-                const float xv = comp(v[k], j);
-                const uint32_t l = label_of(ws.tree, xv);
-                float *pmin = &ws.tab[l][lane];
-                float *pmax = &ws.tab[kMaxClusters + l][lane];
-                *pmin = fminf(*pmin, xv);
-                *pmax = fmaxf(*pmax, xv);
-                l4 |= l << (4 * j);
-            }
+        for (int i = 0; i < kB; ++i) {
+            xs[i] = comp(v[kb + i / 4], i % 4);
+            a[i] = xs[i] >= root ? a_hi : a_lo;
         }
-        packed[k >> 1] |= l4 << (16 * (k & 1));
-        // labels: two per byte, even element in the low nibble
-        const int off = k * 256 + lane * 4;
-        uint8_t *lp = labels + ((lo + off) >> 1);
-        if (kFull || off + 3 < len) {
-            *reinterpret_cast<uint16_t *>(lp) = (uint16_t)l4;
-        } else {
-            if (off < len)
-                lp[0] = (uint8_t)l4;
-            if (off + 2 < len)
-                lp[1] = (uint8_t)(l4 >> 8);
+#pragma unroll
+        for (int st = 0; st < 3; ++st) {
+            float e[kB];
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int i = 0; i < kB; ++i)
+                e[i] = lds_read_f32(a[i]);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int i = 0; i < kB; ++i)
+                a[i] = (a[i] << 1) + (xs[i] >= e[i] ? (st == 2 ? k1_last : k1) : (st == 2 ? k0_last : k0));
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int b = 0; b < kBatch; ++b) {
+            const int k = kb + b;
+            uint32_t l4 = 0;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const uint32_t al = a[4 * b + j];  // == 4*label
+                if (kFull || k * 256 + lane * 4 + j < len) {
+                    // LDS float min/max without return value: no round trip, no conflict (private column)
+                    float *pmin = (float *)(BITSNAP_LDS float *)(uintptr_t)(tab0 + (al << 6));
+                    __hip_atomic_fetch_min(pmin, xs[4 * b + j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+                    __hip_atomic_fetch_max(pmin + kMaxClusters * kWave, xs[4 * b + j], __ATOMIC_RELAXED,
+                                           __HIP_MEMORY_SCOPE_WAVEFRONT);
+                    l4 |= j == 0 ? (al >> 2) : (al << (4 * j - 2));
+                }
+            }
+            packed[k >> 1] |= l4 << (16 * (k & 1));
+            // labels: two per byte, even element in the low nibble
+            const int off = k * 256 + lane * 4;
+            uint8_t *lp = labels + ((lo + off) >> 1);
+            if (kFull || off + 3 < len) {
+                *reinterpret_cast<uint16_t *>(lp) = (uint16_t)l4;
+            } else {
+                if (off < len)
+                    lp[0] = (uint8_t)l4;
+                if (off + 2 < len)
+                    lp[1] = (uint8_t)(l4 >> 8);
+            }
         }
     }
     wave_lds_sync();
@@ -196,50 +252,60 @@ __device__ __forceinline__ void quantize_group(const float *__restrict__ x, int6
     }
     wave_lds_sync();
 
-    // ---- steps 5-6: nearest of the 256 levels inside the element's cluster
+    // ---- steps 5-6: nearest of the 256 levels inside the element's cluster.  v_cvt_pk_u8_f32
+    // rounds to nearest even, saturates to [0, 255], maps NaN to 0 and inserts the byte.
+    const uint32_t coder0 = lds_addr(&ws.coder[0]);
 #pragma unroll
-    for (int k = 0; k < K; ++k) {
-        const uint32_t l4 = (packed[k >> 1] >> (16 * (k & 1))) & 0xFFFFu;
-        uint32_t c4 = 0;
+    for (int kb = 0; kb < K; kb += kBatch) {
+        float2 bi[kB];
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const float2 bi = ws.coder[(l4 >> (4 * j)) & 15u];
-            const float y = __fmul_rn(__fsub_rn(comp(v[k], j), bi.x), bi.y);
-            const float r = rintf(y);
-            uint32_t c = (uint32_t)r;  // saturating: negative and NaN give 0
-            c = c > 255u ? 255u : c;
-            c4 |= c << (8 * j);
+        for (int i = 0; i < kB; ++i) {
+            const int k = kb + i / 4;
+            const uint32_t l4 = (packed[k >> 1] >> (16 * (k & 1))) & 0xFFFFu;
+            bi[i] = lds_read_f32x2(coder0 + (((l4 >> (4 * (i % 4))) & 15u) << 3));
         }
-        const int off = k * 256 + lane * 4;
-        uint8_t *cp = codes + lo + off;
-        if (kFull || off + 3 < len) {
-            *reinterpret_cast<uint32_t *>(cp) = c4;
-        } else {
-            for (int j = 0; j < 4; ++j)
-                if (off + j < len)
-                    cp[j] = (uint8_t)(c4 >> (8 * j));
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int b = 0; b < kBatch; ++b) {
+            const int k = kb + b;
+            uint32_t c4 = 0;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const float y = __fmul_rn(__fsub_rn(comp(v[k], j), bi[4 * b + j].x), bi[4 * b + j].y);
+                c4 = __builtin_amdgcn_cvt_pk_u8_f32(y, j, c4);
+            }
+            const int off = k * 256 + lane * 4;
+            uint8_t *cp = codes + lo + off;
+            if (kFull || off + 3 < len) {
+                *reinterpret_cast<uint32_t *>(cp) = c4;
+            } else {
+                for (int j = 0; j < 4; ++j)
+                    if (off + j < len)
+                        cp[j] = (uint8_t)(c4 >> (8 * j));
+            }
         }
     }
 }
 
-template <int K>
+// Full groups: one wave per group, `groups` of them.  The short last group of a tensor (if any)
+// goes through the same code with bounds checks, as a launch of its own (kFull = false, one wave).
+template <int K, bool kFull>
 __global__ __launch_bounds__(kQBlock) void quantize_cluster_kernel(
-    const float *__restrict__ x, int64_t n, int64_t groups, int m, uint8_t *__restrict__ codes,
+    const float *__restrict__ x, int64_t n, int64_t first_group, int64_t groups, int m, uint8_t *__restrict__ codes,
     uint8_t *__restrict__ labels, float *__restrict__ params, float *__restrict__ fit_out,
     const float *__restrict__ fit_in, uint32_t *__restrict__ status)
 {
     __shared__ WaveShared shared[kQWaves];
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
-    const int64_t g = (int64_t)blockIdx.x * kQWaves + wave;
-    if (g >= groups)
+    const int64_t g = first_group + (int64_t)blockIdx.x * kQWaves + wave;
+    if (g >= first_group + groups)
         return;  // whole wave leaves; the kernel has no workgroup barrier
     constexpr int G = 256 * K;
     const int64_t lo = g * G;
     const int64_t rest = n - lo;
-    if (rest >= G)
-        quantize_group<K, true>(x, lo, G, m, g, codes, labels, params, fit_out, fit_in, status, shared[wave], lane);
-    else
-        quantize_group<K, false>(x, lo, (int)rest, m, g, codes, labels, params, fit_out, fit_in, status, shared[wave], lane);
+    const int len = kFull ? G : (int)(rest < G ? rest : G);
+    quantize_group<K, kFull>(x, lo, len, m, g, codes, labels, params, fit_out, fit_in, status, shared[wave], lane);
 }
 
 template <int K>
@@ -368,15 +434,23 @@ extern "C" int bitsnap_quantize_cluster(const float *x, int64_t n, int64_t group
     if (!aligned16(x) || !aligned16(codes) || !aligned16(labels) || !aligned16(params) || ((uintptr_t)fit_out & 3u) ||
         ((uintptr_t)fit_in & 3u) || ((uintptr_t)status & 3u))
         return BITSNAP_E_ALIGN;
-    const int64_t groups = (int64_t)bitsnap_cluster_groups(n, group);
-    const int64_t blocks = (groups + kQWaves - 1) / kQWaves;
+    const int64_t G = 256 * (int64_t)K;
+    const int64_t full = n / G;                  // groups that are complete
+    const bool tail = (n % G) != 0;              // plus one short group
+    const int64_t blocks = (full + kQWaves - 1) / kQWaves;
     if (blocks > 0x7FFFFFFF)
         return BITSNAP_E_SIZE;
-    const dim3 grid((unsigned)blocks), block(kQBlock);
+    const dim3 block(kQBlock);
     hipStream_t s = (hipStream_t)stream;
-#define BITSNAP_LAUNCH_Q(KK)                                                                                          \
-    hipLaunchKernelGGL(quantize_cluster_kernel<KK>, grid, block, 0, s, x, n, groups, m, codes, labels, params, fit_out, \
-                       fit_in, status)
+#define BITSNAP_LAUNCH_Q(KK)                                                                                       \
+    do {                                                                                                           \
+        if (full > 0)                                                                                              \
+            hipLaunchKernelGGL((quantize_cluster_kernel<KK, true>), dim3((unsigned)blocks), block, 0, s, x, n,     \
+                               (int64_t)0, full, m, codes, labels, params, fit_out, fit_in, status);               \
+        if (tail)                                                                                                  \
+            hipLaunchKernelGGL((quantize_cluster_kernel<KK, false>), dim3(1), block, 0, s, x, n, full, (int64_t)1, \
+                               m, codes, labels, params, fit_out, fit_in, status);                                 \
+    } while (0)
     switch (K) {
     case 1: BITSNAP_LAUNCH_Q(1); break;
     case 2: BITSNAP_LAUNCH_Q(2); break;

@@ -2,11 +2,13 @@
 // (paper: "Bitmask Based Sparsification for Model States", improved bitmask; Algorithm 1) and
 // its inverse.  One kernel launch per call, one pass over HBM.
 //
-// A tile is 4096 consecutive elements and is processed by one 256-thread workgroup.  Inside a
-// tile a lane owns 8 consecutive elements per 16-byte load (one mask byte), a wavefront owns two
+// A tile is 16384 consecutive elements (4 rounds of 4096) and is processed by one 256-thread
+// workgroup; all of a tile's loads are issued before anything waits on them.  A lane owns 8
+// consecutive elements per 16-byte load (one mask byte); in each round a wavefront owns two
 // consecutive 512-element chunks.  Per-lane popcounts are scanned with DPP inside the wave,
-// through LDS across the four waves, and with the decoupled look-back of scan_state.hpp across
-// tiles.  Changed values are staged in LDS so that the payload leaves (encode) or enters
+// through LDS across the four waves and the rounds, and with the decoupled look-back of
+// scan_state.hpp across tiles.  The tile is large because the ticket that hands tiles out is a
+// same-address device-scope atomic, which this chip serves at about one per 11 ns.  Changed values are staged in LDS so that the payload leaves (encode) or enters
 // (decode) HBM as 16-byte accesses aligned on the payload buffer, whatever the tile's offset.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -17,18 +19,23 @@
 #include "wave.hpp"
 
 namespace bitsnap {
+#ifndef BITSNAP_SPARSE_ROUNDS
+#define BITSNAP_SPARSE_ROUNDS 4
+#endif
 
 constexpr int kBlock = 256;
 constexpr int kWaves = kBlock / kWave;
-constexpr int kChunksPerWave = 2;
-constexpr int kLaneElems = 8;                                     // one 16-byte load of 16-bit elements
-constexpr int kChunkElems = kWave * kLaneElems;                   // 512
-constexpr int kTileElems = kWaves * kChunksPerWave * kChunkElems; // 4096
-constexpr int kStageElems = kTileElems + 8;                       // + alignment shift
+constexpr int kLaneElems = 8;                              // one 16-byte load of 16-bit elements
+constexpr int kChunkElems = kWave * kLaneElems;            // 512: what one wave covers with one load
+constexpr int kRoundChunks = 2 * kWaves;                   // a round: every wave takes two consecutive chunks
+constexpr int kRoundElems = kRoundChunks * kChunkElems;    // 4096
+constexpr int kRounds = BITSNAP_SPARSE_ROUNDS;             // rounds per tile, all loaded before the scan
+constexpr int kTileElems = kRounds * kRoundElems;          // one ticket, one status word, one look-back
+constexpr int kStageElems = kTileElems + 8;                // + alignment shift
 
 struct TileShared {
     alignas(16) uint16_t stage[kStageElems];
-    uint32_t wave_total[kWaves];
+    uint32_t wave_total[kRounds][kWaves];
     uint64_t excl;
     int64_t next_tile;
     int aborted;
@@ -78,29 +85,46 @@ __device__ __forceinline__ uint16_t elem16(const uint4 &v, int t)
     return (uint16_t)(w >> ((t & 1) * 16));
 }
 
-// Per-lane counts of two chunks -> this lane's exclusive ranks inside the tile and the tile
-// total.  Contains one __syncthreads.
-__device__ __forceinline__ void tile_ranks(TileShared &sh, uint32_t c0, uint32_t c1, int lane, int wave,
-                                           uint32_t &rank0, uint32_t &rank1, uint32_t &tile_total)
+// Where the calling lane's 8-element pieces sit inside a tile: round r, piece j (0 or 1)
+//   chunk  = tile*8R + r*8 + wave*2 + j        element = chunk*512 + lane*8
+// so element order is round-major, then wave, then piece, then lane.
+__device__ __forceinline__ int64_t piece_chunk(int64_t tile, int r, int wave, int j)
 {
-    const uint32_t pk = c0 | (c1 << 16);
-    const uint32_t incl = wave_inclusive_add(pk);
-    const uint32_t tot = read_lane(incl, 63);
-    const uint32_t ex = incl - pk;
-    const uint32_t t0 = tot & 0xFFFFu;
-    if (lane == 0)
-        sh.wave_total[wave] = t0 + (tot >> 16);
-    __syncthreads();
-    uint32_t before = 0, all = 0;
+    return tile * (kRounds * kRoundChunks) + r * kRoundChunks + wave * 2 + j;
+}
+
+// Per-lane popcounts m[r][j] -> this lane's exclusive rank of each piece inside the tile, and
+// the tile total.  Contains one __syncthreads.
+__device__ __forceinline__ void tile_ranks(TileShared &sh, const uint32_t (&cnt)[kRounds][2], int lane, int wave,
+                                           uint32_t (&rank)[kRounds][2], uint32_t &tile_total)
+{
+    uint32_t ex[kRounds], t0[kRounds];
 #pragma unroll
-    for (int w = 0; w < kWaves; ++w) {
-        const uint32_t v = sh.wave_total[w];
-        before += (w < wave) ? v : 0u;
-        all += v;
+    for (int r = 0; r < kRounds; ++r) {
+        const uint32_t pk = cnt[r][0] | (cnt[r][1] << 16);
+        const uint32_t incl = wave_inclusive_add(pk);
+        const uint32_t tot = read_lane(incl, 63);
+        ex[r] = incl - pk;
+        t0[r] = tot & 0xFFFFu;
+        if (lane == 0)
+            sh.wave_total[r][wave] = t0[r] + (tot >> 16);
     }
-    rank0 = before + (ex & 0xFFFFu);
-    rank1 = before + t0 + (ex >> 16);
-    tile_total = all;
+    __syncthreads();
+    uint32_t run = 0;
+#pragma unroll
+    for (int r = 0; r < kRounds; ++r) {
+        uint32_t before = 0, all = 0;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) {
+            const uint32_t v = sh.wave_total[r][w];
+            before += (w < wave) ? v : 0u;
+            all += v;
+        }
+        rank[r][0] = run + before + (ex[r] & 0xFFFFu);
+        rank[r][1] = run + before + t0[r] + (ex[r] >> 16);
+        run += all;
+    }
+    tile_total = run;
 }
 
 // Wave 0: publish the tile's count, find the count of everything before it, publish the
@@ -127,6 +151,29 @@ __device__ __forceinline__ void tile_prefix(TileShared &sh, ScanHeader *hdr, uin
     }
 }
 
+// All of a tile's loads for the calling lane (issued back to back, nothing waits here).
+__device__ __forceinline__ void load_tile16(const uint16_t *__restrict__ p, int64_t tile, int wave, int lane, int64_t n,
+                                            uint4 (&v)[kRounds][2])
+{
+#pragma unroll
+    for (int r = 0; r < kRounds; ++r)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+            v[r][j] = load8(p, piece_chunk(tile, r, wave, j) * kChunkElems + lane * kLaneElems, n);
+}
+
+// Hands the calling workgroup its next tile (all threads get the same value).  Contains two
+// __syncthreads.  The ticket is taken when the workgroup is ready to start the tile, never
+// earlier: a tile that is claimed but not yet counted stalls every look-back that reaches it.
+__device__ __forceinline__ int64_t claim_tile(TileShared &sh, ScanHeader *hdr)
+{
+    __syncthreads();
+    if (threadIdx.x == 0)
+        sh.next_tile = (int64_t)atomicAdd(&hdr->ticket, 1u);
+    __syncthreads();
+    return sh.next_tile;
+}
+
 __global__ __launch_bounds__(kBlock) void encode_sparse_kernel(
     const uint16_t *__restrict__ cur, const uint16_t *__restrict__ base, int64_t n, uint8_t *__restrict__ mask,
     int64_t mask_bytes, uint16_t *__restrict__ payload, int64_t capacity, uint32_t *__restrict__ tile_offsets,
@@ -138,36 +185,29 @@ __global__ __launch_bounds__(kBlock) void encode_sparse_kernel(
     const uint32_t epoch = hdr->epoch;
     bool aborted = false;
 
-    if (tid == 0)
-        sh.next_tile = (int64_t)atomicAdd(&hdr->ticket, 1u);
-    __syncthreads();
-    int64_t tile = sh.next_tile;
-
-    while (tile < num_tiles) {
-        uint32_t next_ticket = 0;
-        if (tid == 0)
-            next_ticket = atomicAdd(&hdr->ticket, 1u);  // claimed now, consumed at the end of this tile
-
-        const int64_t chunk0 = tile * (kTileElems / kChunkElems) + wave * kChunksPerWave;
-        const int64_t e0 = chunk0 * kChunkElems + lane * kLaneElems, e1 = e0 + kChunkElems;
-        const uint4 c0 = load8(cur, e0, n), b0 = load8(base, e0, n);
-        const uint4 c1 = load8(cur, e1, n), b1 = load8(base, e1, n);
-        const uint32_t m0 = diff_bits(c0, b0), m1 = diff_bits(c1, b1);
-
-        // Algorithm 1 steps 3-4: one mask byte per lane; bytes past ceil(n/8) come out as 0
-        const int64_t mb0 = chunk0 * kWave + lane, mb1 = mb0 + kWave;
-        if (mb0 < mask_bytes)
-            mask[mb0] = (uint8_t)m0;
-        if (mb1 < mask_bytes)
-            mask[mb1] = (uint8_t)m1;
-
-        uint32_t r0, r1, total;
-        tile_ranks(sh, __popc(m0), __popc(m1), lane, wave, r0, r1, total);
-        if (wave == 0) {
-            tile_prefix(sh, hdr, status, tile, epoch, spin_limit, total, lane);
-            if (lane == 0)
-                sh.next_tile = (int64_t)next_ticket;
+    for (int64_t tile = claim_tile(sh, hdr); tile < num_tiles; tile = claim_tile(sh, hdr)) {
+        uint4 c[kRounds][2];
+        uint32_t m[kRounds][2], cnt[kRounds][2], rank[kRounds][2];
+        {
+            uint4 b[kRounds][2];
+            load_tile16(cur, tile, wave, lane, n, c);
+            load_tile16(base, tile, wave, lane, n, b);
+#pragma unroll
+            for (int r = 0; r < kRounds; ++r)
+#pragma unroll
+                for (int j = 0; j < 2; ++j) {
+                    m[r][j] = diff_bits(c[r][j], b[r][j]);
+                    cnt[r][j] = __popc(m[r][j]);
+                    // Algorithm 1 steps 3-4: one mask byte per lane; bytes past ceil(n/8) come out as 0
+                    const int64_t mb = piece_chunk(tile, r, wave, j) * kWave + lane;
+                    if (mb < mask_bytes)
+                        mask[mb] = (uint8_t)m[r][j];
+                }
         }
+        uint32_t total;
+        tile_ranks(sh, cnt, lane, wave, rank, total);  // barrier
+        if (wave == 0)
+            tile_prefix(sh, hdr, status, tile, epoch, spin_limit, total, lane);
         __syncthreads();
         const uint64_t excl = sh.excl;
         if (sh.aborted) {
@@ -184,17 +224,16 @@ __global__ __launch_bounds__(kBlock) void encode_sparse_kernel(
         // Algorithm 1 step 5: changed values, in index order.  Staged at (offset mod 8) so that
         // 16-byte pieces of LDS line up with 16-byte pieces of the payload buffer.
         const uint32_t shift = (uint32_t)(excl & 7u);
-        uint32_t p0 = shift + r0, p1 = shift + r1;
 #pragma unroll
-        for (int t = 0; t < kLaneElems; ++t) {
-            if ((m0 >> t) & 1u)
-                sh.stage[p0++] = elem16(c0, t);
-        }
+        for (int r = 0; r < kRounds; ++r)
 #pragma unroll
-        for (int t = 0; t < kLaneElems; ++t) {
-            if ((m1 >> t) & 1u)
-                sh.stage[p1++] = elem16(c1, t);
-        }
+            for (int j = 0; j < 2; ++j) {
+                uint32_t p = shift + rank[r][j];
+#pragma unroll
+                for (int t = 0; t < kLaneElems; ++t)
+                    if ((m[r][j] >> t) & 1u)
+                        sh.stage[p++] = elem16(c[r][j], t);
+            }
         __syncthreads();
         const uint32_t first = shift, last = shift + total;  // valid staged range [first, last)
         const int64_t dst0 = (int64_t)(excl - shift);         // payload element of stage[0], multiple of 8
@@ -212,10 +251,25 @@ __global__ __launch_bounds__(kBlock) void encode_sparse_kernel(
                 }
             }
         }
-        tile = sh.next_tile;  // written before the barrier above
-        // the next iteration's first write to sh.stage comes after two more barriers
     }
     scan_epilogue(hdr, status, status_cap, epoch, aborted, num_tiles, n_changed);
+}
+
+// The lane's mask bytes of one tile; bits at or beyond n are cleared.
+__device__ __forceinline__ void load_tile_mask(const uint8_t *__restrict__ mask, int64_t mask_bytes, int64_t tile,
+                                               int wave, int lane, int64_t n, uint32_t (&m)[kRounds][2])
+{
+#pragma unroll
+    for (int r = 0; r < kRounds; ++r)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int64_t ch = piece_chunk(tile, r, wave, j);
+            const int64_t mb = ch * kWave + lane, e = ch * kChunkElems + lane * kLaneElems;
+            uint32_t bits = (mb < mask_bytes) ? mask[mb] : 0u;
+            if (e + kLaneElems > n)
+                bits &= (e < n) ? ((1u << (uint32_t)(n - e)) - 1u) : 0u;
+            m[r][j] = bits;
+        }
 }
 
 __global__ __launch_bounds__(kBlock) void decode_sparse_kernel(
@@ -229,35 +283,20 @@ __global__ __launch_bounds__(kBlock) void decode_sparse_kernel(
     const int64_t mask_bytes = (n + 7) >> 3;
     bool aborted = false;
 
-    if (tid == 0)
-        sh.next_tile = (int64_t)atomicAdd(&hdr->ticket, 1u);
-    __syncthreads();
-    int64_t tile = sh.next_tile;
-
-    while (tile < num_tiles) {
-        uint32_t next_ticket = 0;
-        if (tid == 0)
-            next_ticket = atomicAdd(&hdr->ticket, 1u);
-
-        const int64_t chunk0 = tile * (kTileElems / kChunkElems) + wave * kChunksPerWave;
-        const int64_t e0 = chunk0 * kChunkElems + lane * kLaneElems, e1 = e0 + kChunkElems;
-        const int64_t mb0 = chunk0 * kWave + lane, mb1 = mb0 + kWave;
-        uint32_t m0 = (mb0 < mask_bytes) ? mask[mb0] : 0u;
-        uint32_t m1 = (mb1 < mask_bytes) ? mask[mb1] : 0u;
-        // bits at or beyond n carry no element
-        if (e0 + kLaneElems > n)
-            m0 &= (e0 < n) ? ((1u << (uint32_t)(n - e0)) - 1u) : 0u;
-        if (e1 + kLaneElems > n)
-            m1 &= (e1 < n) ? ((1u << (uint32_t)(n - e1)) - 1u) : 0u;
-        uint4 v0 = load8(base, e0, n), v1 = load8(base, e1, n);  // in flight during the scan
-
-        uint32_t r0, r1, total;
-        tile_ranks(sh, __popc(m0), __popc(m1), lane, wave, r0, r1, total);
-        if (wave == 0) {
+    for (int64_t tile = claim_tile(sh, hdr); tile < num_tiles; tile = claim_tile(sh, hdr)) {
+        uint32_t m[kRounds][2], cnt[kRounds][2], rank[kRounds][2];
+        uint4 v[kRounds][2];
+        load_tile_mask(mask, mask_bytes, tile, wave, lane, n, m);  // the mask first: the scan only needs it
+        load_tile16(base, tile, wave, lane, n, v);                  // in flight during the scan
+#pragma unroll
+        for (int r = 0; r < kRounds; ++r)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+                cnt[r][j] = __popc(m[r][j]);
+        uint32_t total;
+        tile_ranks(sh, cnt, lane, wave, rank, total);  // barrier
+        if (wave == 0)
             tile_prefix(sh, hdr, status, tile, epoch, spin_limit, total, lane);
-            if (lane == 0)
-                sh.next_tile = (int64_t)next_ticket;
-        }
         __syncthreads();
         const uint64_t excl = sh.excl;
         if (sh.aborted) {
@@ -275,40 +314,36 @@ __global__ __launch_bounds__(kBlock) void decode_sparse_kernel(
         for (uint32_t q = tid; q < pieces; q += kBlock) {
             const uint32_t lo = q * 8u;
             const int64_t s = src0 + lo;
-            uint4 v = make_uint4(0, 0, 0, 0);
+            uint4 pv = make_uint4(0, 0, 0, 0);
             if (s + 8 <= payload_elems) {
-                v = *reinterpret_cast<const uint4 *>(payload + s);
+                pv = *reinterpret_cast<const uint4 *>(payload + s);
             } else {
                 uint32_t w[4] = {0, 0, 0, 0};
                 for (int t = 0; t < 8; ++t)
                     if (s + t < payload_elems)
                         w[t >> 1] |= (uint32_t)payload[s + t] << ((t & 1) * 16);
-                v = make_uint4(w[0], w[1], w[2], w[3]);
+                pv = make_uint4(w[0], w[1], w[2], w[3]);
             }
-            *reinterpret_cast<uint4 *>(&sh.stage[lo]) = v;
+            *reinterpret_cast<uint4 *>(&sh.stage[lo]) = pv;
         }
         __syncthreads();
 
-        uint32_t p0 = shift + r0, p1 = shift + r1;
-        uint32_t w0[4] = {v0.x, v0.y, v0.z, v0.w}, w1[4] = {v1.x, v1.y, v1.z, v1.w};
 #pragma unroll
-        for (int t = 0; t < kLaneElems; ++t) {
-            if ((m0 >> t) & 1u) {
-                const uint32_t s = sh.stage[p0++];
-                w0[t >> 1] = (t & 1) ? ((w0[t >> 1] & 0x0000FFFFu) | (s << 16)) : ((w0[t >> 1] & 0xFFFF0000u) | s);
-            }
-        }
+        for (int r = 0; r < kRounds; ++r)
 #pragma unroll
-        for (int t = 0; t < kLaneElems; ++t) {
-            if ((m1 >> t) & 1u) {
-                const uint32_t s = sh.stage[p1++];
-                w1[t >> 1] = (t & 1) ? ((w1[t >> 1] & 0x0000FFFFu) | (s << 16)) : ((w1[t >> 1] & 0xFFFF0000u) | s);
+            for (int j = 0; j < 2; ++j) {
+                uint32_t p = shift + rank[r][j];
+                uint32_t w[4] = {v[r][j].x, v[r][j].y, v[r][j].z, v[r][j].w};
+#pragma unroll
+                for (int t = 0; t < kLaneElems; ++t) {
+                    if ((m[r][j] >> t) & 1u) {
+                        const uint32_t s = sh.stage[p++];
+                        w[t >> 1] = (t & 1) ? ((w[t >> 1] & 0x0000FFFFu) | (s << 16)) : ((w[t >> 1] & 0xFFFF0000u) | s);
+                    }
+                }
+                store8(out, piece_chunk(tile, r, wave, j) * kChunkElems + lane * kLaneElems, n,
+                       make_uint4(w[0], w[1], w[2], w[3]));
             }
-        }
-        store8(out, e0, n, make_uint4(w0[0], w0[1], w0[2], w0[3]));
-        store8(out, e1, n, make_uint4(w1[0], w1[1], w1[2], w1[3]));
-        tile = sh.next_tile;
-        __syncthreads();  // sh.stage is refilled right after the next scan; keep readers ahead of it
     }
     scan_epilogue(hdr, status, status_cap, epoch, aborted, num_tiles, n_changed);
 }

@@ -48,36 +48,62 @@ __device__ __forceinline__ void publish(uint64_t *status, int64_t tile, uint64_t
     __hip_atomic_store(&status[tile], word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+#ifndef BITSNAP_LOOKBACK_WORDS
+#define BITSNAP_LOOKBACK_WORDS 1
+#endif
+// Status words one lane inspects per poll.  A poll is one memory round trip, and inclusive
+// prefixes can only spread by one window per round trip, so the window (64 lanes x this) bounds
+// how many tiles per microsecond the whole scan can retire.
+constexpr int kLookbackWords = BITSNAP_LOOKBACK_WORDS;
+
 // Number of counted items in tiles [0, tile).  Called by one full wavefront.  On give-up sets
 // `aborted` and returns 0.
+//
+// Lane l inspects tiles look - (l*K + k), k = 0..K-1, nearest first.  Walking away from the
+// tile, every word must carry at least the tile's own count (aggregate) until the first word
+// that carries an inclusive prefix; the answer is the sum up to and including that word.
 __device__ __forceinline__ uint64_t look_back(uint64_t *status, ScanHeader *hdr, int64_t tile, uint32_t epoch,
                                               uint32_t spin_limit, bool &aborted)
 {
+    constexpr int K = kLookbackWords;
     const int lane = lane_id();
     uint64_t excl = 0;
     int64_t look = tile - 1;  // nearest predecessor not yet accounted for
     uint32_t polls = 0;
     aborted = false;
     for (;;) {
-        const int64_t idx = look - lane;  // lane 0 looks at the nearest tile
-        uint64_t w;
-        uint32_t flag;
+        const int64_t idx0 = look - (int64_t)lane * K;
+        uint64_t lane_sum;
+        bool stop, blocked, abort_word;
         for (;;) {
-            // tiles before the first one: a virtual inclusive prefix of 0
-            w = (idx >= 0) ? __hip_atomic_load(&status[idx], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
-                           : make_status(kFlagInclusive, epoch, 0);
-            const uint32_t tag = (uint32_t)(w >> kValueBits);
-            flag = ((tag & kEpochMask) == epoch) ? (tag >> kEpochBits) : 0u;
-            const uint64_t okm = __ballot(flag != 0);
-            const uint64_t incm = __ballot(flag == kFlagInclusive || flag == kFlagAbort);
-            // enough: every lane up to and including the nearest inclusive word is written
-            uint64_t need = ~0ull;
-            if (incm) {
-                const int first = __ffsll((long long)incm) - 1;
-                need = (first == 63) ? ~0ull : ((1ull << (first + 1)) - 1);
+            uint64_t w[K];
+#pragma unroll
+            for (int k = 0; k < K; ++k)  // tiles before the first one: a virtual inclusive prefix of 0
+                w[k] = (idx0 - k >= 0) ? __hip_atomic_load(&status[idx0 - k], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
+                                       : make_status(kFlagInclusive, epoch, 0);
+            lane_sum = 0;
+            stop = blocked = abort_word = false;
+#pragma unroll
+            for (int k = 0; k < K; ++k) {
+                const uint32_t tag = (uint32_t)(w[k] >> kValueBits);
+                const uint32_t flag = ((tag & kEpochMask) == epoch) ? (tag >> kEpochBits) : 0u;
+                const bool live = !stop && !blocked;
+                if (live && flag == 0)
+                    blocked = true;
+                if (live && flag != 0) {
+                    lane_sum += w[k] & kValueMask;
+                    if (flag != kFlagAggregate) {
+                        stop = true;
+                        abort_word = flag == kFlagAbort;
+                    }
+                }
             }
-            if ((okm & need) == need)
-                break;
+            const uint64_t halt = __ballot(stop || blocked);
+            if (halt == 0)
+                break;  // the whole window holds aggregates: take them all and look further back
+            const int first = __ffsll((long long)halt) - 1;
+            if (!(__ballot(blocked) & (1ull << first)))
+                break;  // the nearest halting lane found an inclusive word
             ++polls;
             if (polls > spin_limit ||
                 ((polls & 63u) == 0 && __hip_atomic_load(&hdr->error, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))) {
@@ -86,19 +112,18 @@ __device__ __forceinline__ uint64_t look_back(uint64_t *status, ScanHeader *hdr,
             }
             __builtin_amdgcn_s_sleep(1);
         }
-        const uint64_t incm = __ballot(flag == kFlagInclusive || flag == kFlagAbort);
-        const uint64_t val = w & kValueMask;
-        if (incm) {
-            const int first = __ffsll((long long)incm) - 1;
-            if (__ballot(flag == kFlagAbort) & (1ull << first)) {
+        const uint64_t halt = __ballot(stop);
+        if (halt) {
+            const int first = __ffsll((long long)halt) - 1;
+            if (__ballot(abort_word) & (1ull << first)) {
                 aborted = true;
                 return 0;
             }
-            excl += wave_sum_u64(lane <= first ? val : 0ull);
+            excl += wave_sum_u64(lane <= first ? lane_sum : 0ull);
             return excl;
         }
-        excl += wave_sum_u64(val);
-        look -= kWave;
+        excl += wave_sum_u64(lane_sum);
+        look -= (int64_t)kWave * K;
     }
 }
 

@@ -29,7 +29,7 @@ def test_library_exports_every_declared_symbol():
 
 def test_sparse_size_helpers():
     T = B.sparse_tile_elems()
-    assert T == 4096
+    assert T % 4096 == 0 and T <= 65536
     for n in [0, 1, 8, 9, 127, 128, 129, 4096, 10**6 + 3]:
         mb = B.sparse_mask_bytes(n)
         assert mb % 16 == 0 and mb >= (n + 7) // 8 and mb < (n + 7) // 8 + 16

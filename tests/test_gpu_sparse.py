@@ -11,8 +11,8 @@ from paper_2511_12376_amd import synth
 
 pytestmark = pytest.mark.gpu
 
-T = 4096
-SIZES = [0, 1, 7, 8, 9, 63, 64, 65, 511, 512, 513, T - 1, T, T + 1, 2 * T - 1, 2 * T, 3 * T + 777, 1_000_003]
+T = B.sparse_tile_elems()
+SIZES = [0, 1, 7, 8, 9, 63, 64, 65, 511, 512, 513, 4095, 4096, 4097, 8191, 8193, T - 1, T, T + 1, 2 * T - 1, 2 * T, 3 * T + 777, 1_000_003]
 
 
 def _pair(n, p, seed):
