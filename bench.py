@@ -145,6 +145,22 @@ def main():
     wall = time.perf_counter() - t0
     ms_per_step = wall * 1e3 / args.steps
 
+    # what a dependency-free streaming copy sustains on this machine (context for the fractions below,
+    # and the kernel the HBM byte counters are calibrated against: it reads and writes cal_bytes)
+    cal_bytes = min(1 << 30, n_max * 4) // (1 << 20) * (1 << 20)
+    copy_gbps = None
+    if cal_bytes > 0:
+        cal_src = deq_ring[0].view(torch.uint8)[:cal_bytes]
+        cal_dst = deq_ring[1].view(torch.uint8)[:cal_bytes]
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        for it in range(2):
+            e0.record(stream)
+            for _ in range(5):
+                B.debug_stream_copy(cal_dst, cal_src)
+            e1.record(stream)
+            torch.cuda.synchronize()
+        copy_gbps = 5 * 2 * cal_bytes / (e0.elapsed_time(e1) * 1e-3) / 1e9
+
     # ------------------------------------------------------------------ accounting
     n_changed = sum(int(e["n_changed"].item()) for e in enc)
     assert int(status.item()) == 0
@@ -191,6 +207,7 @@ def main():
                       "recipe": cfg.recipe, "changed_fraction": round(p, 4), "group": GROUP, "clusters": M,
                       "state_bytes_per_step": total_state, "generation_s": round(gen_s, 1)},
            "hbm_frac_of_peak": {op: ops[op]["hbm_frac"] for op in order},
+           "copy_kernel_GBps": None if copy_gbps is None else round(copy_gbps, 1), "copy_kernel_bytes_each_way": cal_bytes,
            "ops": ops, "roofline": roofline}
 
     if not args.no_cpu_baseline:

@@ -46,6 +46,11 @@ int bitsnap_version(void);
 /* Static, NUL-terminated text for a return code (host pointer, never freed). */
 const char *bitsnap_error_string(int code);
 
+/* Diagnostic: a plain 16-byte-per-lane streaming copy of `bytes` (a multiple of 16) from src to
+ * dst, both aligned.  It moves exactly `bytes` in and `bytes` out, which makes it the yardstick
+ * for HBM byte counters and for what a kernel without dependencies sustains on the same device. */
+int bitsnap_debug_stream_copy(void *dst, const void *src, int64_t bytes, bitsnap_stream_t stream);
+
 /* ------------------------------------------------------------------------------------------
  * Sparse path.  Paper: "Bitmask Based Sparsification for Model States" (improved bitmask,
  * space n/8 + 2 n_c, Eq. improved-bitmask) and Algorithm 1.

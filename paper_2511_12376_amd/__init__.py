@@ -10,7 +10,7 @@ _BINDING_NAMES = (
     "encode_sparse", "decode_sparse", "quantize_cluster", "dequantize_cluster",
     "sparse_mask_bytes", "sparse_tile_elems", "sparse_workspace_bytes",
     "cluster_param_bytes", "cluster_label_bytes", "cluster_fit_floats", "cluster_workspace_bytes",
-    "cluster_z", "version", "lib", "BitsnapError",
+    "cluster_z", "version", "lib", "BitsnapError", "debug_stream_copy",
 )
 
 

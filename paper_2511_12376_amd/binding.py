@@ -16,7 +16,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libbitsnap.so")
 
 SYMBOLS = (
-    "bitsnap_version", "bitsnap_error_string",
+    "bitsnap_version", "bitsnap_error_string", "bitsnap_debug_stream_copy",
     "bitsnap_sparse_tile_elems", "bitsnap_sparse_mask_bytes", "bitsnap_sparse_workspace_bytes",
     "bitsnap_encode_sparse", "bitsnap_decode_sparse", "bitsnap_debug_set_spin_limit",
     "bitsnap_cluster_groups", "bitsnap_cluster_param_bytes", "bitsnap_cluster_label_bytes",
@@ -46,6 +46,7 @@ def lib():
     p, i64, sz, i = C.c_void_p, C.c_int64, C.c_size_t, C.c_int
     L.bitsnap_version.argtypes, L.bitsnap_version.restype = [], i
     L.bitsnap_error_string.argtypes, L.bitsnap_error_string.restype = [i], C.c_char_p
+    L.bitsnap_debug_stream_copy.argtypes, L.bitsnap_debug_stream_copy.restype = [p, p, i64, p], i
     L.bitsnap_sparse_tile_elems.argtypes, L.bitsnap_sparse_tile_elems.restype = [], sz
     L.bitsnap_sparse_mask_bytes.argtypes, L.bitsnap_sparse_mask_bytes.restype = [i64], sz
     L.bitsnap_sparse_workspace_bytes.argtypes, L.bitsnap_sparse_workspace_bytes.restype = [i64], sz
@@ -128,6 +129,13 @@ def cluster_z(k: int, m: int) -> float:
 
 def debug_set_spin_limit(polls: int) -> None:
     lib().bitsnap_debug_set_spin_limit(polls)
+
+
+def debug_stream_copy(dst, src, stream=None) -> None:
+    """dst <- src with the library's plain copy kernel (same byte size, multiple of 16)."""
+    nbytes = src.numel() * src.element_size()
+    assert dst.numel() * dst.element_size() == nbytes
+    _check(lib().bitsnap_debug_stream_copy(_ptr(dst), _ptr(src), nbytes, _stream(stream)), "bitsnap_debug_stream_copy")
 
 
 def new_sparse_workspace(n: int, device):
