@@ -15,6 +15,7 @@
 #include <stdint.h>
 
 #include "../../include/bitsnap.h"
+#include "cluster_general.hpp"
 #include "host_util.hpp"
 #include "wave.hpp"
 
@@ -27,6 +28,12 @@ __constant__ double kZDev[17][16] = {
 #include "z_table.inc"
 };
 
+#ifdef EXP_TIMING
+__device__ unsigned long long *g_qdbg;
+#define QSTAMP(k) do { if (lane == 0 && g_qdbg) g_qdbg[g * 4 + (k)] = __builtin_amdgcn_s_memrealtime(); } while (0)
+#else
+#define QSTAMP(k) do {} while (0)
+#endif
 constexpr int kQBlock = 256;
 constexpr int kQWaves = kQBlock / kWave;
 constexpr int kMaxClusters = 16;
@@ -77,6 +84,7 @@ __device__ __forceinline__ void quantize_group(const float *__restrict__ x, int6
                                                WaveShared &ws, int lane)
 {
     // ---- load: lane owns elements lo + k*256 + lane*4 + {0..3}
+    QSTAMP(0);
     float4 v[K];
 #pragma unroll
     for (int k = 0; k < K; ++k) {
@@ -103,6 +111,7 @@ __device__ __forceinline__ void quantize_group(const float *__restrict__ x, int6
     for (int k = 0; k < K; ++k)
         s += ((double)v[k].x + (double)v[k].y) + ((double)v[k].z + (double)v[k].w);  // padding adds 0
     s = wave_sum(s);
+    QSTAMP(1);
     const double mean = s / (double)len;
     // Keep the group as fp32 in registers: without this the compiler holds on to the fp64 copies
     // made for the sum above, which doubles the register footprint and halves the occupancy.
@@ -254,6 +263,7 @@ __device__ __forceinline__ void quantize_group(const float *__restrict__ x, int6
 
     // ---- steps 5-6: nearest of the 256 levels inside the element's cluster.  v_cvt_pk_u8_f32
     // rounds to nearest even, saturates to [0, 255], maps NaN to 0 and inserts the byte.
+    QSTAMP(2);
     const uint32_t coder0 = lds_addr(&ws.coder[0]);
 #pragma unroll
     for (int kb = 0; kb < K; kb += kBatch) {
@@ -286,6 +296,7 @@ __device__ __forceinline__ void quantize_group(const float *__restrict__ x, int6
             }
         }
     }
+    QSTAMP(3);
 }
 
 // Full groups: one wave per group, `groups` of them.  The short last group of a tensor (if any)
@@ -362,6 +373,8 @@ __global__ __launch_bounds__(kQBlock) void dequantize_cluster_kernel(
     }
 }
 
+// K (float4 per lane) of the one-wave-per-group kernels, or 0 when the group length needs the
+// multi-pass path
 static int group_k(int64_t n, int64_t group)
 {
     (void)n;
@@ -402,10 +415,10 @@ extern "C" size_t bitsnap_cluster_fit_floats(int64_t n, int64_t group, int m)
 
 extern "C" size_t bitsnap_cluster_workspace_bytes(int64_t n, int64_t group, int m)
 {
-    (void)n;
-    (void)group;
     (void)m;
-    return 0;
+    if (n <= 0 || group_k(n, group) != 0)
+        return 0;
+    return cluster_general_workspace_bytes(n, group);
 }
 
 extern "C" double bitsnap_cluster_z(int k, int m)
@@ -420,20 +433,28 @@ extern "C" int bitsnap_quantize_cluster(const float *x, int64_t n, int64_t group
                                         uint32_t *status, void *workspace, size_t workspace_bytes,
                                         bitsnap_stream_t stream)
 {
-    (void)workspace;
-    (void)workspace_bytes;
     if (n < 0 || m < 1 || m > kMaxClusters || group < 0)
         return BITSNAP_E_SIZE;
     if (n == 0)
         return BITSNAP_OK;
     const int K = group_k(n, group);
-    if (K == 0)
+    if (K == 0 && !cluster_general_supported(n, group))
         return BITSNAP_E_SIZE;
     if (!x || !codes || !labels || !params)
         return BITSNAP_E_NULL;
     if (!aligned16(x) || !aligned16(codes) || !aligned16(labels) || !aligned16(params) || ((uintptr_t)fit_out & 3u) ||
         ((uintptr_t)fit_in & 3u) || ((uintptr_t)status & 3u))
         return BITSNAP_E_ALIGN;
+    if (K == 0) {
+        if (!workspace)
+            return BITSNAP_E_NULL;
+        if (!aligned16(workspace))
+            return BITSNAP_E_ALIGN;
+        if (workspace_bytes < cluster_general_workspace_bytes(n, group))
+            return BITSNAP_E_WORKSPACE;
+        return cluster_general_quantize(x, n, group, m, codes, labels, params, fit_out, fit_in, status, workspace,
+                                        (hipStream_t)stream);
+    }
     const int64_t G = 256 * (int64_t)K;
     const int64_t full = n / G;                  // groups that are complete
     const bool tail = (n % G) != 0;              // plus one short group
@@ -470,12 +491,14 @@ extern "C" int bitsnap_dequantize_cluster(const uint8_t *codes, const uint8_t *l
     if (n == 0)
         return BITSNAP_OK;
     const int K = group_k(n, group);
-    if (K == 0)
+    if (K == 0 && !cluster_general_supported(n, group))
         return BITSNAP_E_SIZE;
     if (!codes || !labels || !params || !out)
         return BITSNAP_E_NULL;
     if (!aligned16(codes) || !aligned16(labels) || !aligned16(params) || !aligned16(out))
         return BITSNAP_E_ALIGN;
+    if (K == 0)
+        return cluster_general_dequantize(codes, labels, params, n, group, m, out, (hipStream_t)stream);
     const int64_t groups = (int64_t)bitsnap_cluster_groups(n, group);
     const int64_t blocks = (groups + kQWaves - 1) / kQWaves;
     if (blocks > 0x7FFFFFFF)

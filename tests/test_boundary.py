@@ -79,7 +79,11 @@ def test_bad_arguments_are_rejected_on_the_host():
     q = lambda x, n, g, m, codes, labels, params: L.bitsnap_quantize_cluster(
         x, n, g, m, codes, labels, params, None, None, None, None, 0, None)
     assert q(a, 4096, 4096, 0, a, a, a) == -2 and q(a, 4096, 4096, 17, a, a, a) == -2
-    assert q(a, -1, 4096, 16, a, a, a) == -2 and q(a, 4096, 1000, 16, a, a, a) == -2
+    assert q(a, -1, 4096, 16, a, a, a) == -2
+    assert q(a, 8192, 1001, 16, a, a, a) == -2                            # odd group length: a label byte would straddle groups
+    assert q(a, 8192, 1000, 16, a, a, a) == -1                            # multi-pass group lengths need a workspace
+    assert B.cluster_workspace_bytes(8192, 4096, 16) == 0 and B.cluster_workspace_bytes(8192, 1000, 16) > 0
+    assert L.bitsnap_quantize_cluster(a, 8192, 0, 16, a, a, a, None, None, None, a, 16, None) == -4
     assert q(None, 4096, 4096, 16, a, a, a) == -1 and q(a, 4096, 4096, 16, a + 4, a, a) == -3
     assert q(None, 0, 4096, 16, None, None, None) == 0                     # empty tensor: nothing to do
     d = lambda codes, labels, params, n, g, m, out: L.bitsnap_dequantize_cluster(codes, labels, params, n, g, m, out, None)

@@ -62,7 +62,7 @@ def _compare(x, G, m):
     with np.errstate(divide="ignore", over="ignore"):
         coded = np.isfinite(np.float32(255.0) / g["params"][grp, lab, 0])     # a range too small to code keeps b only
     bound = np.where(coded, S / 510 * (1 + 1e-5), S)
-    assert np.all(np.abs(xh.astype(np.float64) - x) <= bound + 2 * np.spacing(np.abs(x)).astype(np.float64))
+    assert np.all(np.abs(xh.astype(np.float64) - x) <= bound + 2 * np.spacing(scale.astype(np.float32)).astype(np.float64))  # fp32 rounding of q*step + b
     return int((~same).sum()), groups
 
 
@@ -76,6 +76,26 @@ def test_quantize_dequantize_match_oracle(n, G, m):
     rng = np.random.default_rng(n * 7 + G + m)
     x = (rng.standard_normal(n) * 10.0 ** rng.integers(-6, 1) + rng.standard_normal() * 1e-4).astype(np.float32)
     _compare(x, G, m)
+
+
+@pytest.mark.parametrize("n", [1, 7, 1000, 4097, 50_001, 300_000])
+@pytest.mark.parametrize("G,m", [(0, 16), (1000, 16), (6000, 7), (2, 16), (10_000, 16), (0, 1)])
+def test_other_group_lengths_and_whole_tensor(n, G, m):
+    """Group lengths outside the one-wave-per-group kernels, and G = 0: one fit for the whole
+    tensor, which is how the paper states Algorithm 2."""
+    announce("cluster general", n, G, m)
+    rng = np.random.default_rng(n + 13 * G + m)
+    x = (rng.standard_normal(n) * 3e-4 + 1e-5).astype(np.float32)
+    _compare(x, G, m)
+
+
+def test_whole_tensor_fit_on_config0():
+    cfg = synth.config(0)
+    for t in (2, 4, 27):
+        d = synth.make_tensor_np(cfg, t)
+        for key in ("m", "v"):
+            announce("cluster whole-tensor config0", t, key)
+            _compare(d[key], 0, 16)
 
 
 def test_config0_optimizer_states():
