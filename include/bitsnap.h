@@ -167,6 +167,59 @@ int bitsnap_dequantize_cluster(const uint8_t *codes, const uint8_t *labels, cons
                                int64_t n, int64_t group, int m, float *out,
                                bitsnap_stream_t stream);
 
+/* ------------------------------------------------------------------------------------------
+ * Batched forms: one launch for a whole list of tensors.  The paper compresses an entire
+ * state_dict per checkpoint ("process the state_dict", section "Details of Modifications"); a
+ * launch per tensor leaves the device ramping up and draining a few thousand groups at a time.
+ * Results are identical to calling the single-tensor entry point on every item.
+ *
+ * `items` is a DEVICE array written by the caller; its contents cannot be checked on the host:
+ * every pointer in an item must meet the requirements of the single-tensor call, n must be > 0,
+ * and first_group must be the number of groups, ceil(n/group), of all earlier items.
+ * ---------------------------------------------------------------------------------------- */
+
+typedef struct bitsnap_cluster_item {
+    void *values;          /* quantize: const float* x [n] in;   dequantize: float* out [n]        */
+    uint8_t *codes;        /* [n]          quantize: out, dequantize: in                            */
+    uint8_t *labels;       /* [ceil(n/2)]  quantize: out, dequantize: in                            */
+    float *params;         /* [groups][m][2]  quantize: out, dequantize: in                         */
+    float *fit_out;        /* quantize only, nullable: [groups][m+1]                                */
+    const float *fit_in;   /* quantize only, nullable: [groups][2]                                  */
+    int64_t n;             /* elements                                                              */
+    int64_t first_group;   /* index of this tensor's first group in the list-wide numbering         */
+} bitsnap_cluster_item;
+
+typedef struct bitsnap_sparse_item {
+    const void *src;         /* encode: cur [n] in;                 decode: unused                      */
+    const void *base;        /* [n] in                                                                  */
+    uint8_t *mask;           /* encode: [bitsnap_sparse_mask_bytes(n)] out;   decode: [ceil(n/8)] in    */
+    void *payload;           /* encode: [capacity] out;             decode: [capacity] in               */
+    void *out;               /* decode: [n] out (may equal base);   encode: unused                      */
+    uint64_t *n_changed;     /* [1] out; required for encode, nullable for decode                       */
+    uint32_t *tile_offsets;  /* encode: nullable, [ceil(n/tile_elems)] out;   decode: unused            */
+    int64_t n;               /* elements, > 0                                                           */
+    int64_t capacity;        /* encode: payload capacity in elements;   decode: payload elements        */
+    int64_t first_tile;      /* sum of ceil(n/tile_elems) over all earlier items                        */
+} bitsnap_sparse_item;
+
+/* Workspace for a batched sparse call over total_tiles = sum of ceil(n/tile_elems); same rules as
+ * bitsnap_sparse_workspace_bytes (zero once, then self-maintaining; a workspace of this size
+ * also serves single-tensor calls of up to total_tiles tiles). */
+size_t bitsnap_sparse_batch_workspace_bytes(int64_t total_tiles);
+
+/* The scan restarts at every tensor: each item gets its own mask, payload and n_changed exactly
+ * as from the single-tensor call.  If the scan gives up, every item's n_changed reads UINT64_MAX. */
+int bitsnap_encode_sparse_batched(const bitsnap_sparse_item *items, int64_t count, int64_t total_tiles,
+                                  void *workspace, size_t workspace_bytes, bitsnap_stream_t stream);
+int bitsnap_decode_sparse_batched(const bitsnap_sparse_item *items, int64_t count, int64_t total_tiles,
+                                  void *workspace, size_t workspace_bytes, bitsnap_stream_t stream);
+
+/* group must be one of 256, 512, 1024, 2048, 4096; total_groups = sum of ceil(n/group). */
+int bitsnap_quantize_cluster_batched(const bitsnap_cluster_item *items, int64_t count, int64_t total_groups,
+                                     int64_t group, int m, uint32_t *status, bitsnap_stream_t stream);
+int bitsnap_dequantize_cluster_batched(const bitsnap_cluster_item *items, int64_t count, int64_t total_groups,
+                                       int64_t group, int m, bitsnap_stream_t stream);
+
 #ifdef __cplusplus
 }
 #endif

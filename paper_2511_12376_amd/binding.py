@@ -22,6 +22,8 @@ SYMBOLS = (
     "bitsnap_cluster_groups", "bitsnap_cluster_param_bytes", "bitsnap_cluster_label_bytes",
     "bitsnap_cluster_fit_floats", "bitsnap_cluster_workspace_bytes", "bitsnap_cluster_z",
     "bitsnap_quantize_cluster", "bitsnap_dequantize_cluster",
+    "bitsnap_quantize_cluster_batched", "bitsnap_dequantize_cluster_batched",
+    "bitsnap_sparse_batch_workspace_bytes", "bitsnap_encode_sparse_batched", "bitsnap_decode_sparse_batched",
 )
 
 
@@ -65,6 +67,15 @@ def lib():
     L.bitsnap_quantize_cluster.restype = i
     L.bitsnap_dequantize_cluster.argtypes = [p, p, p, i64, i64, i, p, p]
     L.bitsnap_dequantize_cluster.restype = i
+    L.bitsnap_sparse_batch_workspace_bytes.argtypes, L.bitsnap_sparse_batch_workspace_bytes.restype = [i64], sz
+    L.bitsnap_encode_sparse_batched.argtypes = [p, i64, i64, p, sz, p]
+    L.bitsnap_encode_sparse_batched.restype = i
+    L.bitsnap_decode_sparse_batched.argtypes = [p, i64, i64, p, sz, p]
+    L.bitsnap_decode_sparse_batched.restype = i
+    L.bitsnap_quantize_cluster_batched.argtypes = [p, i64, i64, i64, i, p, p]
+    L.bitsnap_quantize_cluster_batched.restype = i
+    L.bitsnap_dequantize_cluster_batched.argtypes = [p, i64, i64, i64, i, p]
+    L.bitsnap_dequantize_cluster_batched.restype = i
     _lib = L
     return L
 
@@ -249,3 +260,66 @@ def dequantize_cluster(codes, labels, params, n: int, group: int = 4096, m: int 
         out = torch.empty(max(n, 1), dtype=torch.float32, device=codes.device)[:n]
     dequantize_cluster_raw(codes, labels, params, n, group, m, out, stream)
     return out
+
+
+# ----------------------------------------------------------------------------------------------
+# batched forms: the caller-side list of tensors becomes a device array of items
+# ----------------------------------------------------------------------------------------------
+def cluster_items(values, codes, labels, params, group: int, fit_out=None, fit_in=None):
+    """Device array of bitsnap_cluster_item (8 x int64 per tensor) for lists of torch tensors.
+    ``values`` holds x (quantize) or out (dequantize).  -> (items int64[count, 8], total_groups)."""
+    import torch
+    rows, first = [], 0
+    for k, v in enumerate(values):
+        n = v.numel()
+        assert n > 0
+        rows.append([v.data_ptr(), codes[k].data_ptr(), labels[k].data_ptr(), params[k].data_ptr(),
+                     0 if fit_out is None else fit_out[k].data_ptr(), 0 if fit_in is None else fit_in[k].data_ptr(),
+                     n, first])
+        first += cluster_groups(n, group)
+    items = torch.tensor(rows, dtype=torch.int64).to(values[0].device)
+    return items, first
+
+
+def quantize_cluster_batched(items, total_groups: int, group: int, m: int, status=None, stream=None) -> None:
+    rc = lib().bitsnap_quantize_cluster_batched(_ptr(items), items.shape[0], total_groups, group, m, _ptr(status),
+                                                _stream(stream))
+    _check(rc, "bitsnap_quantize_cluster_batched")
+
+
+def dequantize_cluster_batched(items, total_groups: int, group: int, m: int, stream=None) -> None:
+    rc = lib().bitsnap_dequantize_cluster_batched(_ptr(items), items.shape[0], total_groups, group, m, _stream(stream))
+    _check(rc, "bitsnap_dequantize_cluster_batched")
+
+
+def sparse_batch_workspace_bytes(total_tiles: int) -> int:
+    return lib().bitsnap_sparse_batch_workspace_bytes(total_tiles)
+
+
+def sparse_items(n_list, *, src=None, base=None, mask=None, payload=None, out=None, n_changed=None,
+                 tile_offsets=None, capacity=None):
+    """Device array of bitsnap_sparse_item (10 x int64 per tensor) from parallel lists of torch tensors
+    (None where a field is unused).  -> (items int64[count, 10], total_tiles)."""
+    import torch
+    T = sparse_tile_elems()
+    rows, first = [], 0
+    ptr = lambda lst, k: 0 if lst is None or lst[k] is None else lst[k].data_ptr()
+    for k, n in enumerate(n_list):
+        assert n > 0
+        rows.append([ptr(src, k), ptr(base, k), ptr(mask, k), ptr(payload, k), ptr(out, k), ptr(n_changed, k),
+                     ptr(tile_offsets, k), n, n if capacity is None else capacity[k], first])
+        first += (n + T - 1) // T
+    dev = next(l[0].device for l in (src, base, mask, payload, out) if l is not None)
+    return torch.tensor(rows, dtype=torch.int64).to(dev), first
+
+
+def encode_sparse_batched(items, total_tiles: int, workspace, stream=None) -> None:
+    rc = lib().bitsnap_encode_sparse_batched(_ptr(items), items.shape[0], total_tiles, _ptr(workspace),
+                                             workspace.numel() * workspace.element_size(), _stream(stream))
+    _check(rc, "bitsnap_encode_sparse_batched")
+
+
+def decode_sparse_batched(items, total_tiles: int, workspace, stream=None) -> None:
+    rc = lib().bitsnap_decode_sparse_batched(_ptr(items), items.shape[0], total_tiles, _ptr(workspace),
+                                             workspace.numel() * workspace.element_size(), _stream(stream))
+    _check(rc, "bitsnap_decode_sparse_batched")

@@ -28,12 +28,6 @@ __constant__ double kZDev[17][16] = {
 #include "z_table.inc"
 };
 
-#ifdef EXP_TIMING
-__device__ unsigned long long *g_qdbg;
-#define QSTAMP(k) do { if (lane == 0 && g_qdbg) g_qdbg[g * 4 + (k)] = __builtin_amdgcn_s_memrealtime(); } while (0)
-#else
-#define QSTAMP(k) do {} while (0)
-#endif
 constexpr int kQBlock = 256;
 constexpr int kQWaves = kQBlock / kWave;
 constexpr int kMaxClusters = 16;
@@ -84,7 +78,6 @@ __device__ __forceinline__ void quantize_group(const float *__restrict__ x, int6
                                                WaveShared &ws, int lane)
 {
     // ---- load: lane owns elements lo + k*256 + lane*4 + {0..3}
-    QSTAMP(0);
     float4 v[K];
 #pragma unroll
     for (int k = 0; k < K; ++k) {
@@ -111,7 +104,6 @@ __device__ __forceinline__ void quantize_group(const float *__restrict__ x, int6
     for (int k = 0; k < K; ++k)
         s += ((double)v[k].x + (double)v[k].y) + ((double)v[k].z + (double)v[k].w);  // padding adds 0
     s = wave_sum(s);
-    QSTAMP(1);
     const double mean = s / (double)len;
     // Keep the group as fp32 in registers: without this the compiler holds on to the fp64 copies
     // made for the sum above, which doubles the register footprint and halves the occupancy.
@@ -263,7 +255,6 @@ __device__ __forceinline__ void quantize_group(const float *__restrict__ x, int6
 
     // ---- steps 5-6: nearest of the 256 levels inside the element's cluster.  v_cvt_pk_u8_f32
     // rounds to nearest even, saturates to [0, 255], maps NaN to 0 and inserts the byte.
-    QSTAMP(2);
     const uint32_t coder0 = lds_addr(&ws.coder[0]);
 #pragma unroll
     for (int kb = 0; kb < K; kb += kBatch) {
@@ -296,7 +287,7 @@ __device__ __forceinline__ void quantize_group(const float *__restrict__ x, int6
             }
         }
     }
-    QSTAMP(3);
+    wave_lds_sync();  // this wave may start its next group and rewrite the tables
 }
 
 // Full groups: one wave per group, `groups` of them.  The short last group of a tensor (if any)
@@ -319,25 +310,17 @@ __global__ __launch_bounds__(kQBlock) void quantize_cluster_kernel(
     quantize_group<K, kFull>(x, lo, len, m, g, codes, labels, params, fit_out, fit_in, status, shared[wave], lane);
 }
 
+// Dequantisation of one group by one wave: codes[lo..lo+len) -> out[lo..lo+len).
 template <int K>
-__global__ __launch_bounds__(kQBlock) void dequantize_cluster_kernel(
-    const uint8_t *__restrict__ codes, const uint8_t *__restrict__ labels, const float *__restrict__ params,
-    int64_t n, int64_t groups, int m, float *__restrict__ out)
+__device__ __forceinline__ void dequantize_group(const uint8_t *__restrict__ codes, const uint8_t *__restrict__ labels,
+                                                 const float *__restrict__ params, int64_t lo, int len, int m, int64_t g,
+                                                 float *__restrict__ out, float2 *coder, int lane)
 {
-    __shared__ float2 coder[kQWaves][kMaxClusters];
-    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
-    const int64_t g = (int64_t)blockIdx.x * kQWaves + wave;
-    if (g >= groups)
-        return;
-    constexpr int G = 256 * K;
-    const int64_t lo = g * G;
-    const int64_t rest = n - lo;
-    const int len = rest >= G ? G : (int)rest;
     if (lane < kMaxClusters) {
         float2 sb = make_float2(0.0f, 0.0f);
         if (lane < m)
             sb = *reinterpret_cast<const float2 *>(params + (g * m + lane) * 2);
-        coder[wave][lane] = make_float2(__fdiv_rn(sb.x, 255.0f), sb.y);  // (S/255, b)
+        coder[lane] = make_float2(__fdiv_rn(sb.x, 255.0f), sb.y);  // (S/255, b)
     }
     wave_lds_sync();
 #pragma unroll
@@ -360,7 +343,7 @@ __global__ __launch_bounds__(kQBlock) void dequantize_cluster_kernel(
         float r[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            const float2 sb = coder[wave][(l4 >> (4 * j)) & 15u];
+            const float2 sb = coder[(l4 >> (4 * j)) & 15u];
             r[j] = __fadd_rn(__fmul_rn((float)((c4 >> (8 * j)) & 255u), sb.x), sb.y);
         }
         if (full) {
@@ -370,6 +353,99 @@ __global__ __launch_bounds__(kQBlock) void dequantize_cluster_kernel(
                 if (off + j < len)
                     out[lo + off + j] = r[j];
         }
+    }
+    wave_lds_sync();  // the coder table may be rewritten by this wave's next group
+}
+
+template <int K>
+__global__ __launch_bounds__(kQBlock) void dequantize_cluster_kernel(
+    const uint8_t *__restrict__ codes, const uint8_t *__restrict__ labels, const float *__restrict__ params,
+    int64_t n, int64_t groups, int m, float *__restrict__ out)
+{
+    __shared__ float2 coder[kQWaves][kMaxClusters];
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
+    const int64_t g = (int64_t)blockIdx.x * kQWaves + wave;
+    if (g >= groups)
+        return;
+    constexpr int G = 256 * K;
+    const int64_t lo = g * G;
+    const int64_t rest = n - lo;
+    dequantize_group<K>(codes, labels, params, lo, rest >= G ? G : (int)rest, m, g, out, coder[wave], lane);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Batched forms: one launch for a list of tensors.  Groups are numbered across the list
+// (item.first_group = groups of all earlier items); a persistent grid of waves strides over that
+// numbering, so the load, compute and store phases of different waves drift apart and overlap,
+// which a single tensor of a few thousand groups (one group per wave slot) cannot do.
+// ---------------------------------------------------------------------------------------------
+
+// Advance `t` until item t holds group g (items are ordered; g only ever grows for a wave).
+__device__ __forceinline__ void seek_item(const bitsnap_cluster_item *__restrict__ items, int64_t count, int64_t g,
+                                          int64_t &t, bitsnap_cluster_item &it, int64_t &next_first)
+{
+    while (t + 1 < count && g >= next_first) {
+        ++t;
+        it = items[t];
+        next_first = (t + 1 < count) ? items[t + 1].first_group : INT64_MAX;
+    }
+}
+
+template <int K, bool kFull>
+__global__ __launch_bounds__(kQBlock, 4) void quantize_cluster_batched_kernel(
+    const bitsnap_cluster_item *__restrict__ items, int64_t count, int64_t total_groups, int m,
+    uint32_t *__restrict__ status)
+{
+    __shared__ WaveShared shared[kQWaves];
+    // the wave index as a scalar: group and item bookkeeping then lives in SGPRs
+    const int lane = threadIdx.x & (kWave - 1), wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    constexpr int G = 256 * K;
+    if (kFull) {
+        int64_t t = 0;
+        bitsnap_cluster_item it = items[0];
+        int64_t next_first = count > 1 ? items[1].first_group : INT64_MAX;
+        const int64_t stride = (int64_t)gridDim.x * kQWaves;
+        for (int64_t gg = (int64_t)blockIdx.x * kQWaves + wave; gg < total_groups; gg += stride) {
+            seek_item(items, count, gg, t, it, next_first);
+            const int64_t g = gg - it.first_group;
+            const int64_t lo = g * G;
+            if (it.n - lo >= G)  // a short last group is left to the tail launch
+                quantize_group<K, true>((const float *)it.values, lo, G, m, g, it.codes, it.labels, it.params,
+                                        it.fit_out, it.fit_in, status, shared[wave], lane);
+        }
+    } else {
+        // one wave per tensor: its short last group, if it has one
+        const int64_t t = (int64_t)blockIdx.x * kQWaves + wave;
+        if (t >= count)
+            return;
+        const bitsnap_cluster_item it = items[t];
+        const int64_t g = it.n / G;
+        const int rest = (int)(it.n - g * G);
+        if (rest > 0)
+            quantize_group<K, false>((const float *)it.values, g * G, rest, m, g, it.codes, it.labels, it.params,
+                                     it.fit_out, it.fit_in, status, shared[wave], lane);
+    }
+}
+
+template <int K>
+__global__ __launch_bounds__(kQBlock) void dequantize_cluster_batched_kernel(
+    const bitsnap_cluster_item *__restrict__ items, int64_t count, int64_t total_groups, int m)
+{
+    __shared__ float2 coder[kQWaves][kMaxClusters];
+    const int lane = threadIdx.x & (kWave - 1), wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    constexpr int G = 256 * K;
+    int64_t t = 0;
+    bitsnap_cluster_item it = items[0];
+    int64_t next_first = count > 1 ? items[1].first_group : INT64_MAX;
+    const int64_t stride = (int64_t)gridDim.x * kQWaves;
+    for (int64_t gg = (int64_t)blockIdx.x * kQWaves + wave; gg < total_groups; gg += stride) {
+        seek_item(items, count, gg, t, it, next_first);
+        const int64_t g = gg - it.first_group;
+        const int64_t lo = g * G;
+        const int64_t rest = it.n - lo;
+        if (rest > 0)
+            dequantize_group<K>(it.codes, it.labels, it.params, lo, rest >= G ? G : (int)rest, m, g, (float *)it.values,
+                                coder[wave], lane);
     }
 }
 
@@ -515,5 +591,75 @@ extern "C" int bitsnap_dequantize_cluster(const uint8_t *codes, const uint8_t *l
     default: BITSNAP_LAUNCH_D(16); break;
     }
 #undef BITSNAP_LAUNCH_D
+    return launch_status();
+}
+
+static int batched_grid(int64_t total_groups)
+{
+    const int64_t blocks = (total_groups + kQWaves - 1) / kQWaves;
+    const int64_t cap = (int64_t)device_info().cu_count * 4;  // 16 waves per CU stay resident
+    return (int)(blocks < 1 ? 1 : (blocks < cap ? blocks : cap));
+}
+
+extern "C" int bitsnap_quantize_cluster_batched(const bitsnap_cluster_item *items, int64_t count, int64_t total_groups,
+                                                int64_t group, int m, uint32_t *status, bitsnap_stream_t stream)
+{
+    if (count < 0 || total_groups < 0 || m < 1 || m > kMaxClusters)
+        return BITSNAP_E_SIZE;
+    const int K = group_k(0, group);
+    if (K == 0)
+        return BITSNAP_E_SIZE;  // the batched form exists for the one-wave-per-group lengths only
+    if (count == 0 || total_groups == 0)
+        return BITSNAP_OK;
+    if (!items)
+        return BITSNAP_E_NULL;
+    if (((uintptr_t)items & 7u) || ((uintptr_t)status & 3u))
+        return BITSNAP_E_ALIGN;
+    const dim3 block(kQBlock), grid(batched_grid(total_groups)), tgrid((unsigned)((count + kQWaves - 1) / kQWaves));
+    hipStream_t s = (hipStream_t)stream;
+#define BITSNAP_LAUNCH_QB(KK)                                                                                     \
+    do {                                                                                                          \
+        hipLaunchKernelGGL((quantize_cluster_batched_kernel<KK, true>), grid, block, 0, s, items, count,          \
+                           total_groups, m, status);                                                              \
+        hipLaunchKernelGGL((quantize_cluster_batched_kernel<KK, false>), tgrid, block, 0, s, items, count,        \
+                           total_groups, m, status);                                                              \
+    } while (0)
+    switch (K) {
+    case 1: BITSNAP_LAUNCH_QB(1); break;
+    case 2: BITSNAP_LAUNCH_QB(2); break;
+    case 4: BITSNAP_LAUNCH_QB(4); break;
+    case 8: BITSNAP_LAUNCH_QB(8); break;
+    default: BITSNAP_LAUNCH_QB(16); break;
+    }
+#undef BITSNAP_LAUNCH_QB
+    return launch_status();
+}
+
+extern "C" int bitsnap_dequantize_cluster_batched(const bitsnap_cluster_item *items, int64_t count,
+                                                  int64_t total_groups, int64_t group, int m, bitsnap_stream_t stream)
+{
+    if (count < 0 || total_groups < 0 || m < 1 || m > kMaxClusters)
+        return BITSNAP_E_SIZE;
+    const int K = group_k(0, group);
+    if (K == 0)
+        return BITSNAP_E_SIZE;
+    if (count == 0 || total_groups == 0)
+        return BITSNAP_OK;
+    if (!items)
+        return BITSNAP_E_NULL;
+    if ((uintptr_t)items & 7u)
+        return BITSNAP_E_ALIGN;
+    const dim3 block(kQBlock), grid(batched_grid(total_groups));
+    hipStream_t s = (hipStream_t)stream;
+#define BITSNAP_LAUNCH_DB(KK) \
+    hipLaunchKernelGGL(dequantize_cluster_batched_kernel<KK>, grid, block, 0, s, items, count, total_groups, m)
+    switch (K) {
+    case 1: BITSNAP_LAUNCH_DB(1); break;
+    case 2: BITSNAP_LAUNCH_DB(2); break;
+    case 4: BITSNAP_LAUNCH_DB(4); break;
+    case 8: BITSNAP_LAUNCH_DB(8); break;
+    default: BITSNAP_LAUNCH_DB(16); break;
+    }
+#undef BITSNAP_LAUNCH_DB
     return launch_status();
 }

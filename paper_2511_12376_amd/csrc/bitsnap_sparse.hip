@@ -127,20 +127,22 @@ __device__ __forceinline__ void tile_ranks(TileShared &sh, const uint32_t (&cnt)
     tile_total = run;
 }
 
-// Wave 0: publish the tile's count, find the count of everything before it, publish the
-// inclusive value; the result reaches the other waves through sh.excl / sh.aborted.
+// Wave 0: publish the tile's count, find the count of everything before it in the same tensor,
+// publish the inclusive value; the result reaches the other waves through sh.excl / sh.aborted.
+// `tile` and `first_tile` (the tensor's first tile) are in the launch-wide numbering.
 __device__ __forceinline__ void tile_prefix(TileShared &sh, ScanHeader *hdr, uint64_t *status, int64_t tile,
-                                            uint32_t epoch, uint32_t spin_limit, uint32_t tile_total, int lane)
+                                            int64_t first_tile, uint32_t epoch, uint32_t spin_limit,
+                                            uint32_t tile_total, int lane)
 {
     uint64_t excl = 0;
     bool aborted = false;
-    if (tile == 0) {
+    if (tile == first_tile) {
         if (lane == 0)
-            publish(status, 0, make_status(kFlagInclusive, epoch, tile_total));
+            publish(status, tile, make_status(kFlagInclusive, epoch, tile_total));
     } else {
         if (lane == 0)
             publish(status, tile, make_status(kFlagAggregate, epoch, tile_total));
-        excl = look_back(status, hdr, tile, epoch, spin_limit, aborted);
+        excl = look_back(status, hdr, tile, first_tile, epoch, spin_limit, aborted);
         if (lane == 0)
             publish(status, tile, aborted ? make_status(kFlagAbort, epoch, 0)
                                           : make_status(kFlagInclusive, epoch, excl + tile_total));
@@ -162,30 +164,89 @@ __device__ __forceinline__ void load_tile16(const uint16_t *__restrict__ p, int6
             v[r][j] = load8(p, piece_chunk(tile, r, wave, j) * kChunkElems + lane * kLaneElems, n);
 }
 
-// Hands the calling workgroup its next tile (all threads get the same value).  Contains two
-// __syncthreads.  The ticket is taken when the workgroup is ready to start the tile, never
-// earlier: a tile that is claimed but not yet counted stalls every look-back that reaches it.
+// Hands the calling workgroup its next tile (all threads get the same value, as a scalar).
+// Contains two __syncthreads.  The ticket is taken when the workgroup is ready to start the tile,
+// never earlier: a tile that is claimed but not yet counted stalls every look-back that reaches it.
 __device__ __forceinline__ int64_t claim_tile(TileShared &sh, ScanHeader *hdr)
 {
     __syncthreads();
     if (threadIdx.x == 0)
         sh.next_tile = (int64_t)atomicAdd(&hdr->ticket, 1u);
     __syncthreads();
-    return sh.next_tile;
+    const uint64_t t = (uint64_t)sh.next_tile;
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)t), hi = __builtin_amdgcn_readfirstlane((uint32_t)(t >> 32));
+    return (int64_t)(((uint64_t)hi << 32) | lo);
 }
 
-__global__ __launch_bounds__(kBlock) void encode_sparse_kernel(
-    const uint16_t *__restrict__ cur, const uint16_t *__restrict__ base, int64_t n, uint8_t *__restrict__ mask,
-    int64_t mask_bytes, uint16_t *__restrict__ payload, int64_t capacity, uint32_t *__restrict__ tile_offsets,
-    uint64_t *__restrict__ n_changed, ScanHeader *hdr, uint64_t *status, int64_t status_cap, int64_t num_tiles,
-    uint32_t spin_limit)
+// The tensor a launch-wide tile number belongs to.  Tickets only grow, so a workgroup walks the
+// item list forwards.  With kBatched == false there is one tensor, passed by value.
+template <bool kBatched>
+struct ItemCursor {
+    const bitsnap_sparse_item *items;
+    int64_t count, t, next_first;
+    bitsnap_sparse_item it;
+
+    __device__ __forceinline__ ItemCursor(const bitsnap_sparse_item &single, const bitsnap_sparse_item *list, int64_t n)
+        : items(list), count(n), t(0), next_first(INT64_MAX), it(single)
+    {
+        if (kBatched) {
+            it = items[0];
+            next_first = count > 1 ? items[1].first_tile : INT64_MAX;
+        }
+    }
+    __device__ __forceinline__ void seek(int64_t tile)
+    {
+        if (kBatched) {
+            while (t + 1 < count && tile >= next_first) {
+                ++t;
+                it = items[t];
+                next_first = (t + 1 < count) ? items[t + 1].first_tile : INT64_MAX;
+            }
+        }
+    }
+};
+
+// After the scan: what only the workgroup that finished last may write.
+__device__ __forceinline__ void report_failures(int epilogue, const bitsnap_sparse_item &single,
+                                                const bitsnap_sparse_item *items, int64_t count, bool batched,
+                                                int64_t num_tiles)
+{
+    if (!(epilogue & kEpilogueLast))
+        return;
+    if (epilogue & kEpilogueError) {  // some workgroup gave up waiting: every count of this launch is void
+        if (batched) {
+            for (int64_t t = threadIdx.x; t < count; t += blockDim.x)
+                if (items[t].n_changed)
+                    *items[t].n_changed = ~0ull;
+        } else if (threadIdx.x == 0 && single.n_changed) {
+            *single.n_changed = ~0ull;
+        }
+    } else if (!batched && num_tiles == 0 && threadIdx.x == 0 && single.n_changed) {
+        *single.n_changed = 0;  // an empty tensor has no tile that could report its count
+    }
+}
+
+template <bool kBatched>
+__global__ __launch_bounds__(kBlock) void encode_sparse_kernel(bitsnap_sparse_item single,
+                                                               const bitsnap_sparse_item *__restrict__ items,
+                                                               int64_t count, ScanHeader *hdr, uint64_t *status,
+                                                               int64_t status_cap, int64_t num_tiles, uint32_t spin_limit)
 {
     __shared__ TileShared sh;
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
     const uint32_t epoch = hdr->epoch;
     bool aborted = false;
+    ItemCursor<kBatched> cursor(single, items, count);
 
-    for (int64_t tile = claim_tile(sh, hdr); tile < num_tiles; tile = claim_tile(sh, hdr)) {
+    for (int64_t gtile = claim_tile(sh, hdr); gtile < num_tiles; gtile = claim_tile(sh, hdr)) {
+        cursor.seek(gtile);
+        const bitsnap_sparse_item &it = cursor.it;
+        const uint16_t *__restrict__ cur = (const uint16_t *)it.src, *__restrict__ base = (const uint16_t *)it.base;
+        uint8_t *__restrict__ mask = it.mask;
+        uint16_t *__restrict__ payload = (uint16_t *)it.payload;
+        const int64_t n = it.n, capacity = it.capacity, tile = gtile - it.first_tile;
+        const int64_t mask_bytes = (((n + 7) >> 3) + 15) & ~(int64_t)15;
+
         uint4 c[kRounds][2];
         uint32_t m[kRounds][2], cnt[kRounds][2], rank[kRounds][2];
         {
@@ -207,7 +268,7 @@ __global__ __launch_bounds__(kBlock) void encode_sparse_kernel(
         uint32_t total;
         tile_ranks(sh, cnt, lane, wave, rank, total);  // barrier
         if (wave == 0)
-            tile_prefix(sh, hdr, status, tile, epoch, spin_limit, total, lane);
+            tile_prefix(sh, hdr, status, gtile, it.first_tile, epoch, spin_limit, total, lane);
         __syncthreads();
         const uint64_t excl = sh.excl;
         if (sh.aborted) {
@@ -215,10 +276,10 @@ __global__ __launch_bounds__(kBlock) void encode_sparse_kernel(
             break;
         }
         if (tid == 0) {
-            if (tile_offsets)
-                tile_offsets[tile] = (uint32_t)excl;
-            if (tile == num_tiles - 1)
-                *n_changed = excl + total;
+            if (it.tile_offsets)
+                it.tile_offsets[tile] = (uint32_t)excl;
+            if ((tile + 1) * kTileElems >= n)  // the tensor's last tile knows the total
+                *it.n_changed = excl + total;
         }
 
         // Algorithm 1 step 5: changed values, in index order.  Staged at (offset mod 8) so that
@@ -252,7 +313,8 @@ __global__ __launch_bounds__(kBlock) void encode_sparse_kernel(
             }
         }
     }
-    scan_epilogue(hdr, status, status_cap, epoch, aborted, num_tiles, n_changed);
+    const int epilogue = scan_epilogue(hdr, status, status_cap, epoch, aborted);
+    report_failures(epilogue, single, items, count, kBatched, num_tiles);
 }
 
 // The lane's mask bytes of one tile; bits at or beyond n are cleared.
@@ -272,18 +334,28 @@ __device__ __forceinline__ void load_tile_mask(const uint8_t *__restrict__ mask,
         }
 }
 
-__global__ __launch_bounds__(kBlock) void decode_sparse_kernel(
-    const uint16_t *base, const uint8_t *__restrict__ mask, const uint16_t *__restrict__ payload,
-    int64_t payload_elems, int64_t n, uint16_t *out, uint64_t *__restrict__ n_changed, ScanHeader *hdr,
-    uint64_t *status, int64_t status_cap, int64_t num_tiles, uint32_t spin_limit)
+template <bool kBatched>
+__global__ __launch_bounds__(kBlock) void decode_sparse_kernel(bitsnap_sparse_item single,
+                                                               const bitsnap_sparse_item *__restrict__ items,
+                                                               int64_t count, ScanHeader *hdr, uint64_t *status,
+                                                               int64_t status_cap, int64_t num_tiles, uint32_t spin_limit)
 {
     __shared__ TileShared sh;
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
     const uint32_t epoch = hdr->epoch;
-    const int64_t mask_bytes = (n + 7) >> 3;
     bool aborted = false;
+    ItemCursor<kBatched> cursor(single, items, count);
 
-    for (int64_t tile = claim_tile(sh, hdr); tile < num_tiles; tile = claim_tile(sh, hdr)) {
+    for (int64_t gtile = claim_tile(sh, hdr); gtile < num_tiles; gtile = claim_tile(sh, hdr)) {
+        cursor.seek(gtile);
+        const bitsnap_sparse_item &it = cursor.it;
+        const uint16_t *base = (const uint16_t *)it.base;  // may alias out
+        const uint8_t *__restrict__ mask = it.mask;
+        const uint16_t *__restrict__ payload = (const uint16_t *)it.payload;
+        uint16_t *out = (uint16_t *)it.out;
+        const int64_t n = it.n, payload_elems = it.capacity, tile = gtile - it.first_tile;
+        const int64_t mask_bytes = (n + 7) >> 3;
+
         uint32_t m[kRounds][2], cnt[kRounds][2], rank[kRounds][2];
         uint4 v[kRounds][2];
         load_tile_mask(mask, mask_bytes, tile, wave, lane, n, m);  // the mask first: the scan only needs it
@@ -296,15 +368,15 @@ __global__ __launch_bounds__(kBlock) void decode_sparse_kernel(
         uint32_t total;
         tile_ranks(sh, cnt, lane, wave, rank, total);  // barrier
         if (wave == 0)
-            tile_prefix(sh, hdr, status, tile, epoch, spin_limit, total, lane);
+            tile_prefix(sh, hdr, status, gtile, it.first_tile, epoch, spin_limit, total, lane);
         __syncthreads();
         const uint64_t excl = sh.excl;
         if (sh.aborted) {
             aborted = true;
             break;
         }
-        if (tid == 0 && n_changed && tile == num_tiles - 1)
-            *n_changed = excl + total;
+        if (tid == 0 && it.n_changed && (tile + 1) * kTileElems >= n)
+            *it.n_changed = excl + total;
 
         // the tile's payload segment [excl, excl+total) -> LDS, as aligned 16-byte pieces
         const uint32_t shift = (uint32_t)(excl & 7u);
@@ -345,7 +417,8 @@ __global__ __launch_bounds__(kBlock) void decode_sparse_kernel(
                        make_uint4(w[0], w[1], w[2], w[3]));
             }
     }
-    scan_epilogue(hdr, status, status_cap, epoch, aborted, num_tiles, n_changed);
+    const int epilogue = scan_epilogue(hdr, status, status_cap, epoch, aborted);
+    report_failures(epilogue, single, items, count, kBatched, num_tiles);
 }
 
 static uint32_t g_spin_limit = kDefaultSpinLimit;
@@ -392,6 +465,32 @@ extern "C" size_t bitsnap_sparse_workspace_bytes(int64_t n)
 
 extern "C" void bitsnap_debug_set_spin_limit(uint32_t polls) { g_spin_limit = polls ? polls : kDefaultSpinLimit; }
 
+static int64_t tiles_of(int64_t n) { return n <= 0 ? 0 : (n + kTileElems - 1) / kTileElems; }
+
+template <typename Kernel>
+static int launch_scan(Kernel kernel, const bitsnap_sparse_item &single, const bitsnap_sparse_item *items, int64_t count,
+                       int64_t num_tiles, void *workspace, size_t workspace_bytes, bitsnap_stream_t stream)
+{
+    ScanHeader *hdr = reinterpret_cast<ScanHeader *>(workspace);
+    uint64_t *status = reinterpret_cast<uint64_t *>(reinterpret_cast<char *>(workspace) + kScanHeaderBytes);
+    const int64_t status_cap = (int64_t)((workspace_bytes - kScanHeaderBytes) / sizeof(uint64_t));
+    const int grid = sparse_grid(reinterpret_cast<const void *>(kernel), num_tiles);
+    hipLaunchKernelGGL(kernel, dim3(grid), dim3(kBlock), 0, (hipStream_t)stream, single, items, count, hdr, status,
+                       status_cap, num_tiles, g_spin_limit);
+    return launch_status();
+}
+
+static int check_scan_workspace(void *workspace, size_t workspace_bytes, int64_t num_tiles)
+{
+    if (!workspace)
+        return BITSNAP_E_NULL;
+    if (!aligned16(workspace))
+        return BITSNAP_E_ALIGN;
+    if (workspace_bytes < kScanHeaderBytes + (size_t)num_tiles * sizeof(uint64_t))
+        return BITSNAP_E_WORKSPACE;
+    return BITSNAP_OK;
+}
+
 extern "C" int bitsnap_encode_sparse(const void *cur, const void *base, int64_t n, int elem_bytes, uint8_t *mask,
                                      void *payload, int64_t payload_capacity_elems, uint32_t *tile_offsets,
                                      uint64_t *n_changed, void *workspace, size_t workspace_bytes,
@@ -408,16 +507,16 @@ extern "C" int bitsnap_encode_sparse(const void *cur, const void *base, int64_t 
         return rc;
     if (tile_offsets && n >= (int64_t)1 << 32)
         return BITSNAP_E_OFFSETS;
-    const int64_t num_tiles = (n + kTileElems - 1) / kTileElems;
-    ScanHeader *hdr = reinterpret_cast<ScanHeader *>(workspace);
-    uint64_t *status = reinterpret_cast<uint64_t *>(reinterpret_cast<char *>(workspace) + kScanHeaderBytes);
-    const int64_t status_cap = (int64_t)((workspace_bytes - kScanHeaderBytes) / sizeof(uint64_t));
-    const int grid = sparse_grid(reinterpret_cast<const void *>(&encode_sparse_kernel), num_tiles);
-    hipLaunchKernelGGL(encode_sparse_kernel, dim3(grid), dim3(kBlock), 0, (hipStream_t)stream,
-                       (const uint16_t *)cur, (const uint16_t *)base, n, mask, (int64_t)bitsnap_sparse_mask_bytes(n),
-                       (uint16_t *)payload, payload_capacity_elems, tile_offsets, n_changed, hdr, status, status_cap,
-                       num_tiles, g_spin_limit);
-    return launch_status();
+    bitsnap_sparse_item it = {};
+    it.src = cur;
+    it.base = base;
+    it.mask = mask;
+    it.payload = payload;
+    it.n_changed = n_changed;
+    it.tile_offsets = tile_offsets;
+    it.n = n;
+    it.capacity = payload_capacity_elems;
+    return launch_scan(&encode_sparse_kernel<false>, it, nullptr, 1, tiles_of(n), workspace, workspace_bytes, stream);
 }
 
 extern "C" int bitsnap_decode_sparse(const void *base, const uint8_t *mask, const void *payload, int64_t payload_elems,
@@ -432,13 +531,53 @@ extern "C" int bitsnap_decode_sparse(const void *base, const uint8_t *mask, cons
         return BITSNAP_E_ALIGN;
     if (int rc = check_workspace(workspace, workspace_bytes, n))
         return rc;
-    const int64_t num_tiles = (n + kTileElems - 1) / kTileElems;
-    ScanHeader *hdr = reinterpret_cast<ScanHeader *>(workspace);
-    uint64_t *status = reinterpret_cast<uint64_t *>(reinterpret_cast<char *>(workspace) + kScanHeaderBytes);
-    const int64_t status_cap = (int64_t)((workspace_bytes - kScanHeaderBytes) / sizeof(uint64_t));
-    const int grid = sparse_grid(reinterpret_cast<const void *>(&decode_sparse_kernel), num_tiles);
-    hipLaunchKernelGGL(decode_sparse_kernel, dim3(grid), dim3(kBlock), 0, (hipStream_t)stream,
-                       (const uint16_t *)base, mask, (const uint16_t *)payload, payload_elems, n, (uint16_t *)out,
-                       n_changed, hdr, status, status_cap, num_tiles, g_spin_limit);
-    return launch_status();
+    bitsnap_sparse_item it = {};
+    it.base = base;
+    it.mask = const_cast<uint8_t *>(mask);
+    it.payload = const_cast<void *>(payload);
+    it.out = out;
+    it.n_changed = n_changed;
+    it.n = n;
+    it.capacity = payload_elems;
+    return launch_scan(&decode_sparse_kernel<false>, it, nullptr, 1, tiles_of(n), workspace, workspace_bytes, stream);
+}
+
+extern "C" size_t bitsnap_sparse_batch_workspace_bytes(int64_t total_tiles)
+{
+    const size_t bytes = kScanHeaderBytes + (size_t)(total_tiles < 0 ? 0 : total_tiles) * sizeof(uint64_t);
+    return (bytes + 255) / 256 * 256;
+}
+
+static int check_batch(const bitsnap_sparse_item *items, int64_t count, int64_t total_tiles, void *workspace,
+                       size_t workspace_bytes)
+{
+    if (count < 0 || total_tiles < 0 || total_tiles >= (int64_t)1 << 32)
+        return BITSNAP_E_SIZE;
+    if (count > 0 && !items)
+        return BITSNAP_E_NULL;
+    if ((uintptr_t)items & 7u)
+        return BITSNAP_E_ALIGN;
+    return check_scan_workspace(workspace, workspace_bytes, total_tiles);
+}
+
+extern "C" int bitsnap_encode_sparse_batched(const bitsnap_sparse_item *items, int64_t count, int64_t total_tiles,
+                                             void *workspace, size_t workspace_bytes, bitsnap_stream_t stream)
+{
+    if (int rc = check_batch(items, count, total_tiles, workspace, workspace_bytes))
+        return rc;
+    if (count == 0 || total_tiles == 0)
+        return BITSNAP_OK;
+    return launch_scan(&encode_sparse_kernel<true>, bitsnap_sparse_item{}, items, count, total_tiles, workspace,
+                       workspace_bytes, stream);
+}
+
+extern "C" int bitsnap_decode_sparse_batched(const bitsnap_sparse_item *items, int64_t count, int64_t total_tiles,
+                                             void *workspace, size_t workspace_bytes, bitsnap_stream_t stream)
+{
+    if (int rc = check_batch(items, count, total_tiles, workspace, workspace_bytes))
+        return rc;
+    if (count == 0 || total_tiles == 0)
+        return BITSNAP_OK;
+    return launch_scan(&decode_sparse_kernel<true>, bitsnap_sparse_item{}, items, count, total_tiles, workspace,
+                       workspace_bytes, stream);
 }

@@ -56,14 +56,15 @@ __device__ __forceinline__ void publish(uint64_t *status, int64_t tile, uint64_t
 // how many tiles per microsecond the whole scan can retire.
 constexpr int kLookbackWords = BITSNAP_LOOKBACK_WORDS;
 
-// Number of counted items in tiles [0, tile).  Called by one full wavefront.  On give-up sets
+// Number of counted items in tiles [first_tile, tile): the scan restarts at first_tile (the first
+// tile of the tensor this tile belongs to).  Called by one full wavefront.  On give-up sets
 // `aborted` and returns 0.
 //
 // Lane l inspects tiles look - (l*K + k), k = 0..K-1, nearest first.  Walking away from the
 // tile, every word must carry at least the tile's own count (aggregate) until the first word
 // that carries an inclusive prefix; the answer is the sum up to and including that word.
-__device__ __forceinline__ uint64_t look_back(uint64_t *status, ScanHeader *hdr, int64_t tile, uint32_t epoch,
-                                              uint32_t spin_limit, bool &aborted)
+__device__ __forceinline__ uint64_t look_back(uint64_t *status, ScanHeader *hdr, int64_t tile, int64_t first_tile,
+                                              uint32_t epoch, uint32_t spin_limit, bool &aborted)
 {
     constexpr int K = kLookbackWords;
     const int lane = lane_id();
@@ -79,7 +80,7 @@ __device__ __forceinline__ uint64_t look_back(uint64_t *status, ScanHeader *hdr,
             uint64_t w[K];
 #pragma unroll
             for (int k = 0; k < K; ++k)  // tiles before the first one: a virtual inclusive prefix of 0
-                w[k] = (idx0 - k >= 0) ? __hip_atomic_load(&status[idx0 - k], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
+                w[k] = (idx0 - k >= first_tile) ? __hip_atomic_load(&status[idx0 - k], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
                                        : make_status(kFlagInclusive, epoch, 0);
             lane_sum = 0;
             stop = blocked = abort_word = false;
@@ -127,32 +128,31 @@ __device__ __forceinline__ uint64_t look_back(uint64_t *status, ScanHeader *hdr,
     }
 }
 
+constexpr int kEpilogueLast = 1;   // this workgroup finished last
+constexpr int kEpilogueError = 2;  // ... and some workgroup had given up
+
 // Last step of every workgroup of a scan kernel (called by all threads, uniformly).  The
-// workgroup that arrives last resets the header for the next call.
+// workgroup that arrives last resets the header for the next call.  Returns, to every thread of
+// the workgroup, kEpilogueLast (| kEpilogueError) in the last workgroup and 0 elsewhere, so that
+// the caller can write what only the last workgroup may write.
 //   aborted        this workgroup gave up
 //   status_cap     number of status words the workspace holds
-//   n_out          nullable: receives UINT64_MAX when any workgroup gave up, `empty_value` when
-//                  there were no tiles at all
-__device__ __forceinline__ void scan_epilogue(ScanHeader *hdr, uint64_t *status, int64_t status_cap, uint32_t epoch,
-                                              bool aborted, int64_t num_tiles, uint64_t *n_out)
+__device__ __forceinline__ int scan_epilogue(ScanHeader *hdr, uint64_t *status, int64_t status_cap, uint32_t epoch,
+                                             bool aborted)
 {
-    __shared__ int s_wrap;
+    __shared__ int s_wrap, s_result;
     __syncthreads();
     if (threadIdx.x == 0) {
-        int wrap = 0;
+        int wrap = 0, result = 0;
         if (aborted)
             __hip_atomic_store(&hdr->error, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         __threadfence();
         const uint32_t prev = atomicAdd(&hdr->done, 1u);
         if (prev == gridDim.x - 1) {
             __threadfence();
-            const uint32_t err = __hip_atomic_load(&hdr->error, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            if (n_out) {
-                if (err)
-                    *n_out = ~0ull;
-                else if (num_tiles == 0)
-                    *n_out = 0;
-            }
+            result = kEpilogueLast;
+            if (__hip_atomic_load(&hdr->error, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))
+                result |= kEpilogueError;
             hdr->done = 0;
             hdr->ticket = 0;
             hdr->error = 0;
@@ -162,6 +162,7 @@ __device__ __forceinline__ void scan_epilogue(ScanHeader *hdr, uint64_t *status,
                 hdr->epoch = epoch + 1;
         }
         s_wrap = wrap;
+        s_result = result;
     }
     __syncthreads();
     if (s_wrap) {
@@ -171,6 +172,7 @@ __device__ __forceinline__ void scan_epilogue(ScanHeader *hdr, uint64_t *status,
         if (threadIdx.x == 0)
             hdr->epoch = 0;
     }
+    return s_result;
 }
 
 }  // namespace bitsnap

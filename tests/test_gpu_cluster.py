@@ -198,3 +198,38 @@ def test_full_size_tensor_sampled_groups():
     S = q.params[:, :, 0].reshape(-1)[torch.arange(n, device=DEV) // 4096 * 16 + lab]
     err = (xh.double() - x.double()).abs()
     assert bool((err <= S.double() / 510 + 5e-7 * (x.abs().double() + S.double())).all())   # + fp32 rounding of q*step + b
+
+
+def test_batched_equals_single_tensor_calls():
+    """One launch over a list of tensors (ragged sizes, short last groups, a one-element tensor) gives
+    exactly what the per-tensor entry point gives, which the tests above tie to the oracle; a few
+    items are also compared with the oracle directly."""
+    announce("cluster batched")
+    rng = np.random.default_rng(21)
+    sizes = [4096, 1, 4097, 3 * 4096 + 123, 300_000, 4096 * 50, 77, 8192, 1_000_003, 4095]
+    for G, m in [(4096, 16), (1024, 5)]:
+        xs = [f32_to_dev((rng.standard_normal(n) * 10.0 ** rng.integers(-5, 0)).astype(np.float32)) for n in sizes]
+        single = [B.quantize_cluster(x, G, m) for x in xs]
+        codes = [torch.zeros_like(q.codes) for q in single]
+        labels = [torch.zeros_like(q.labels) for q in single]
+        params = [torch.zeros_like(q.params) for q in single]
+        fits = [torch.zeros_like(q.fit) for q in single]
+        status = torch.zeros(1, dtype=torch.int32, device=DEV)
+        items, total = B.cluster_items(xs, codes, labels, params, G, fit_out=fits)
+        assert total == sum(B.cluster_groups(n, G) for n in sizes)
+        B.quantize_cluster_batched(items, total, G, m, status)
+        outs = [torch.zeros(n, dtype=torch.float32, device=DEV) for n in sizes]
+        ditems, _ = B.cluster_items(outs, codes, labels, params, G)
+        B.dequantize_cluster_batched(ditems, total, G, m)
+        torch.cuda.synchronize()
+        assert int(status.item()) == 0
+        for k, q in enumerate(single):
+            assert torch.equal(codes[k], q.codes) and torch.equal(labels[k], q.labels)
+            assert torch.equal(params[k], q.params) and torch.equal(fits[k], q.fit)
+            ref = B.dequantize_cluster(q.codes, q.labels, q.params, sizes[k], G, m)
+            assert torch.equal(outs[k], ref)
+        for k in (1, 3, 6):
+            o = oracle.quantize_cluster(to_np(xs[k]), G, m, fit_in=to_np(fits[k])[:, :2].copy())
+            assert np.array_equal(to_np(codes[k]), o["codes"]) and np.array_equal(to_np(labels[k]), o["labels"])
+            assert np.array_equal(to_np(params[k]), o["params"])
+            assert np.array_equal(to_np(outs[k]), oracle.dequantize_cluster(o["codes"], o["labels"], o["params"], sizes[k], G, m))

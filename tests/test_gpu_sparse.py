@@ -197,3 +197,41 @@ def test_full_size_tensor_sampled_tiles():
         o_mask, o_pay, o_nc = oracle.encode_sparse(c, b)
         assert np.array_equal(to_np(enc.mask[lo // 8:(lo + T) // 8]), o_mask)
         assert np.array_equal(to_np(enc.payload[offs[t]:offs[t] + o_nc]).view(np.uint16), o_pay)
+
+
+def test_batched_equals_oracle_per_tensor():
+    """One launch over a list of tensors: the scan restarts at each tensor, every item gets exactly
+    the oracle's mask, payload, count and offsets, and the batched decode gives every tensor back."""
+    announce("sparse batched")
+    sizes = [1, T, T + 1, 5 * T + 77, 9, 3 * T, 200_003, 8, 40 * T - 1, 65]
+    ps = [1.0, 0.06, 0.5, 0.7, 0.0, 1.0, 0.06, 0.5, 0.3, 0.2]
+    pairs = [_pair(n, p, 4000 + i) for i, (n, p) in enumerate(zip(sizes, ps))]
+    cur = [u16_to_dev(c) for c, _ in pairs]
+    base = [u16_to_dev(b) for _, b in pairs]
+    mask = [torch.full((B.sparse_mask_bytes(n),), 0xEE, dtype=torch.uint8, device=DEV) for n in sizes]
+    payload = [torch.zeros(n + 8, dtype=torch.int16, device=DEV) for n in sizes]
+    counts = [torch.zeros(1, dtype=torch.int64, device=DEV) for _ in sizes]
+    offs = [torch.zeros((n + T - 1) // T, dtype=torch.int32, device=DEV) for n in sizes]
+    items, total = B.sparse_items(sizes, src=cur, base=base, mask=mask, payload=payload, n_changed=counts, tile_offsets=offs)
+    ws = torch.zeros(B.sparse_batch_workspace_bytes(total), dtype=torch.uint8, device=DEV)
+    for rep in range(2):                                           # twice: the workspace must come back clean
+        B.encode_sparse_batched(items, total, ws)
+    out = [torch.zeros(n, dtype=torch.bfloat16, device=DEV) for n in sizes]
+    dcounts = [torch.zeros(1, dtype=torch.int64, device=DEV) for _ in sizes]
+    ditems, dtotal = B.sparse_items(sizes, base=base, mask=mask, payload=payload, out=out, n_changed=dcounts)
+    assert dtotal == total
+    B.decode_sparse_batched(ditems, total, ws)
+    torch.cuda.synchronize()
+    for k, (c, b) in enumerate(pairs):
+        o_mask, o_pay, o_nc = oracle.encode_sparse(c, b)
+        assert int(counts[k].item()) == o_nc == int(dcounts[k].item())
+        m = to_np(mask[k])
+        assert np.array_equal(m[: o_mask.size], o_mask) and not m[o_mask.size:].any()
+        assert np.array_equal(to_np(payload[k]).view(np.uint16)[:o_nc], o_pay)
+        o_off = oracle.tile_offsets(o_mask, sizes[k], T)
+        assert np.array_equal(to_np(offs[k]).view(np.uint32), o_off[:-1].astype(np.uint32))
+        assert np.array_equal(dev_to_u16(out[k]), c)
+    # the same workspace still serves a single-tensor call
+    enc = B.encode_sparse(cur[3], base[3], workspace=ws)
+    torch.cuda.synchronize()
+    assert int(enc.n_changed.item()) == int(counts[3].item())
