@@ -4,7 +4,9 @@
 A step is one pass of the whole hot path over one synthetic checkpoint that is already resident
 in HBM: encode_sparse of every bf16 weight tensor against its base, quantize_cluster of the fp32
 master weights and both Adam moments, then decode_sparse and dequantize_cluster of everything
-that was just produced.  The default workload is the Llama-2-7B-shaped checkpoint (291 tensors,
+that was just produced.  Two ways of issuing it are timed: "batched" (the *_batched entry points:
+one launch per operation and state, 8 launches per step) and "per-tensor" (one call per tensor,
+2328 launches per step).  --mode picks the one reported as `value`; the other is listed beside it.  The default workload is the Llama-2-7B-shaped checkpoint (291 tensors,
 6.74 G parameters, 14 bytes of state per parameter) whose next checkpoint comes from 100
 simulated Adam steps.
 
@@ -40,6 +42,8 @@ def parse():
     ap.add_argument("--p", type=float, default=None, help="change fraction for the Bernoulli configs")
     ap.add_argument("--limit-tensors", type=int, default=0, help="only the first N tensors (debugging)")
     ap.add_argument("--adam-steps", type=int, default=None)
+    ap.add_argument("--mode", choices=["batched", "per-tensor"], default="batched",
+                    help="which entry points the reported step uses; the other mode is timed too and reported beside it")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tensors", type=int, default=4)
     return ap.parse_args()
@@ -115,35 +119,80 @@ def main():
                                               status.data_ptr(), None, 0, sp))
             calls["dequantize_cluster"].append((q["codes"].data_ptr(), q["labels"].data_ptr(), q["params"].data_ptr(),
                                                 n, GROUP, M, deq_ring[(3 * i + j) % RING].data_ptr(), sp))
+    # batched form: device item arrays; decoded outputs go to arenas that the three states share
+    T = B.sparse_tile_elems()
+    dec_arena = torch.empty(n_total, dtype=torch.bfloat16, device=dev)
+    deq_arena = torch.empty(n_total, dtype=f32, device=dev)
+    starts = [0]
+    for n in sizes:
+        starts.append(starts[-1] + n)
+    dec_out = [dec_arena[starts[i]:starts[i + 1]] for i in range(len(sizes))]
+    deq_out = [deq_arena[starts[i]:starts[i + 1]] for i in range(len(sizes))]
+    enc_items, total_tiles = B.sparse_items(sizes, src=[d["cur"] for d in inputs], base=[d["base"] for d in inputs],
+                                            mask=[e["mask"] for e in enc], payload=[e["payload"] for e in enc],
+                                            n_changed=[e["n_changed"] for e in enc])
+    dec_items, _ = B.sparse_items(sizes, base=[d["base"] for d in inputs], mask=[e["mask"] for e in enc],
+                                  payload=[e["payload"] for e in enc], out=dec_out)
+    bws = torch.zeros(B.sparse_batch_workspace_bytes(total_tiles), dtype=u8, device=dev)
+    q_items, dq_items, total_groups = [], [], 0
+    for j, key in enumerate(("master", "m", "v")):
+        qi, total_groups = B.cluster_items([d[key] for d in inputs], [e["q"][j]["codes"] for e in enc],
+                                           [e["q"][j]["labels"] for e in enc], [e["q"][j]["params"] for e in enc], GROUP)
+        di, _ = B.cluster_items(deq_out, [e["q"][j]["codes"] for e in enc], [e["q"][j]["labels"] for e in enc],
+                                [e["q"][j]["params"] for e in enc], GROUP)
+        q_items.append(qi)
+        dq_items.append(di)
+    bcalls = {
+        "encode_sparse": [(L.bitsnap_encode_sparse_batched, (enc_items.data_ptr(), len(sizes), total_tiles, bws.data_ptr(), bws.numel(), sp))],
+        "quantize_cluster": [(L.bitsnap_quantize_cluster_batched, (qi.data_ptr(), len(sizes), total_groups, GROUP, M, status.data_ptr(), sp)) for qi in q_items],
+        "decode_sparse": [(L.bitsnap_decode_sparse_batched, (dec_items.data_ptr(), len(sizes), total_tiles, bws.data_ptr(), bws.numel(), sp))],
+        "dequantize_cluster": [(L.bitsnap_dequantize_cluster_batched, (di.data_ptr(), len(sizes), total_groups, GROUP, M, sp)) for di in dq_items],
+    }
+
     fns = {"encode_sparse": L.bitsnap_encode_sparse, "quantize_cluster": L.bitsnap_quantize_cluster,
            "decode_sparse": L.bitsnap_decode_sparse, "dequantize_cluster": L.bitsnap_dequantize_cluster}
     order = ["encode_sparse", "quantize_cluster", "decode_sparse", "dequantize_cluster"]
 
-    def run_step(events=None):
+    def run_step(mode, events=None):
         for k, op in enumerate(order):
             if events is not None:
                 events[k].record(stream)
-            fn = fns[op]
-            for a in calls[op]:
-                rc = fn(*a)
-                if rc != 0:
-                    raise RuntimeError(f"{op}: {L.bitsnap_error_string(rc).decode()}")
+            if mode == "batched":
+                for fn, a in bcalls[op]:
+                    rc = fn(*a)
+                    if rc != 0:
+                        raise RuntimeError(f"{op} (batched): {L.bitsnap_error_string(rc).decode()}")
+            else:
+                fn = fns[op]
+                for a in calls[op]:
+                    rc = fn(*a)
+                    if rc != 0:
+                        raise RuntimeError(f"{op}: {L.bitsnap_error_string(rc).decode()}")
         if events is not None:
             events[len(order)].record(stream)
 
-    for _ in range(args.warmup):
-        run_step()
-    torch.cuda.synchronize()
+    def time_mode(mode):
+        for _ in range(args.warmup):
+            run_step(mode)
+        torch.cuda.synchronize()
+        # the timed region: exactly --steps steps between two synchronisations
+        ev = [[torch.cuda.Event(enable_timing=True) for _ in range(len(order) + 1)] for _ in range(args.steps)]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for s_ in range(args.steps):
+            run_step(mode, ev[s_])
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        op_ms = {op: sum(ev[s_][k].elapsed_time(ev[s_][k + 1]) for s_ in range(args.steps)) / args.steps
+                 for k, op in enumerate(order)}
+        return wall * 1e3 / args.steps, op_ms
 
-    # the timed region: exactly --steps steps between two synchronisations
-    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(len(order) + 1)] for _ in range(args.steps)]
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for s in range(args.steps):
-        run_step(ev[s])
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-    ms_per_step = wall * 1e3 / args.steps
+    other = "per-tensor" if args.mode == "batched" else "batched"
+    other_ms, other_op_ms = time_mode(other)
+    ms_per_step, op_ms = time_mode(args.mode)
+    n_launch = {op: (len(bcalls[op]) if args.mode == "batched" else len(calls[op])) for op in order}
+    if args.mode == "batched":   # the cluster quantiser's batched form adds one launch for short last groups
+        n_launch["quantize_cluster"] *= 2
 
     # what a dependency-free streaming copy sustains on this machine (context for the fractions below,
     # and the kernel the HBM byte counters are calibrated against: it reads and writes cal_bytes)
@@ -173,12 +222,10 @@ def main():
     cluster_alg = 3 * (4 * n_total + n_total + (n_total + 1) // 2 + groups * M * 8)
     alg_bytes = {"encode_sparse": sparse_alg, "decode_sparse": sparse_alg,
                  "quantize_cluster": cluster_alg, "dequantize_cluster": cluster_alg}
-    op_ms = {op: sum(ev[s][k].elapsed_time(ev[s][k + 1]) for s in range(args.steps)) / args.steps
-             for k, op in enumerate(order)}
     ops = {}
     for op in order:
         sec = op_ms[op] * 1e-3
-        ops[op] = {"ms": round(op_ms[op], 3), "launches": len(calls[op]),
+        ops[op] = {"ms": round(op_ms[op], 3), "launches": n_launch[op],
                    "state_GBps": round(state_bytes[op] / sec / 1e9, 1),
                    "hbm_GBps": round(alg_bytes[op] / sec / 1e9, 1),
                    "hbm_frac": round(alg_bytes[op] / sec / 1e9 / HBM_PEAK_GBS, 4)}
@@ -186,9 +233,11 @@ def main():
     value = total_state / (ms_per_step * 1e-3) / 1e9
 
     dominant = max(order, key=lambda op: op_ms[op])
+    bt = "_batched" if args.mode == "batched" else ""
     kernel_name = {"encode_sparse": "encode_sparse_kernel", "decode_sparse": "decode_sparse_kernel",
-                   "quantize_cluster": "quantize_cluster_kernel<16>", "dequantize_cluster": "dequantize_cluster_kernel<16>"}
-    launches = len(calls[dominant])
+                   "quantize_cluster": f"quantize_cluster{bt}_kernel<16>",
+                   "dequantize_cluster": f"dequantize_cluster{bt}_kernel<16>"}
+    launches = len(bcalls[dominant]) if args.mode == "batched" else len(calls[dominant])
     roofline = {"bound": "hbm", "kernel": kernel_name[dominant],
                 "achieved": round(alg_bytes[dominant] / (op_ms[dominant] * 1e-3) / 1e9, 1),
                 "peak": HBM_PEAK_GBS, "unit": "GB/s",
@@ -202,6 +251,10 @@ def main():
            "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
            "ms_per_step": round(ms_per_step, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
            "dtype": "u16 compare + f32 (f64 group statistics)", "data": "synthetic",
+           "mode": args.mode,
+           "other_mode": {"mode": other, "ms_per_step": round(other_ms, 3),
+                          "value": round(total_state / (other_ms * 1e-3) / 1e9, 1),
+                          "op_ms": {op: round(other_op_ms[op], 3) for op in order}},
            "config": {"workload": f"configs[{cfg.index}] {cfg.name}-shaped checkpoint: {len(tensors)} tensors, "
                                   f"{n_total} params, bf16 weights vs base + fp32 master/m/v, tensor by tensor",
                       "recipe": cfg.recipe, "changed_fraction": round(p, 4), "group": GROUP, "clusters": M,

@@ -375,24 +375,36 @@ __global__ __launch_bounds__(kQBlock) void dequantize_cluster_kernel(
 
 // ---------------------------------------------------------------------------------------------
 // Batched forms: one launch for a list of tensors.  Groups are numbered across the list
-// (item.first_group = groups of all earlier items); a persistent grid of waves strides over that
-// numbering, so the load, compute and store phases of different waves drift apart and overlap,
-// which a single tensor of a few thousand groups (one group per wave slot) cannot do.
+// (item.first_group = groups of all earlier items) and the grid has one wave per group of the
+// whole list, so the device works through many rounds of waves whose load, compute and store
+// phases overlap; a single tensor of a few thousand groups is one round (one group per wave slot)
+// whose phases cannot overlap.
 // ---------------------------------------------------------------------------------------------
 
-// Advance `t` until item t holds group g (items are ordered; g only ever grows for a wave).
-__device__ __forceinline__ void seek_item(const bitsnap_cluster_item *__restrict__ items, int64_t count, int64_t g,
-                                          int64_t &t, bitsnap_cluster_item &it, int64_t &next_first)
+// The item that holds list-wide group gg: the last one whose first_group <= gg (binary search;
+// every operand is wave-uniform, so this runs on the scalar unit).
+__device__ __forceinline__ int64_t find_item(const bitsnap_cluster_item *__restrict__ items, int64_t count, int64_t gg)
 {
-    while (t + 1 < count && g >= next_first) {
-        ++t;
-        it = items[t];
-        next_first = (t + 1 < count) ? items[t + 1].first_group : INT64_MAX;
+    int64_t lo = 0, hi = count - 1;
+    while (lo < hi) {
+        const int64_t mid = (lo + hi + 1) >> 1;
+        if (items[mid].first_group <= gg)
+            lo = mid;
+        else
+            hi = mid - 1;
     }
+    return lo;
+}
+
+__device__ __forceinline__ int64_t uniform_i64(int64_t v)
+{
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)(uint64_t)v);
+    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)((uint64_t)v >> 32));
+    return (int64_t)(((uint64_t)hi << 32) | lo);
 }
 
 template <int K, bool kFull>
-__global__ __launch_bounds__(kQBlock, 4) void quantize_cluster_batched_kernel(
+__global__ __launch_bounds__(kQBlock) void quantize_cluster_batched_kernel(
     const bitsnap_cluster_item *__restrict__ items, int64_t count, int64_t total_groups, int m,
     uint32_t *__restrict__ status)
 {
@@ -401,24 +413,21 @@ __global__ __launch_bounds__(kQBlock, 4) void quantize_cluster_batched_kernel(
     const int lane = threadIdx.x & (kWave - 1), wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     constexpr int G = 256 * K;
     if (kFull) {
-        int64_t t = 0;
-        bitsnap_cluster_item it = items[0];
-        int64_t next_first = count > 1 ? items[1].first_group : INT64_MAX;
-        const int64_t stride = (int64_t)gridDim.x * kQWaves;
-        for (int64_t gg = (int64_t)blockIdx.x * kQWaves + wave; gg < total_groups; gg += stride) {
-            seek_item(items, count, gg, t, it, next_first);
-            const int64_t g = gg - it.first_group;
-            const int64_t lo = g * G;
-            if (it.n - lo >= G)  // a short last group is left to the tail launch
-                quantize_group<K, true>((const float *)it.values, lo, G, m, g, it.codes, it.labels, it.params,
-                                        it.fit_out, it.fit_in, status, shared[wave], lane);
-        }
+        const int64_t gg = (int64_t)blockIdx.x * kQWaves + wave;
+        if (gg >= total_groups)
+            return;
+        const bitsnap_cluster_item &it = items[find_item(items, count, gg)];
+        const int64_t g = gg - it.first_group;
+        const int64_t lo = g * G;
+        if (it.n - lo >= G)  // a short last group is left to the tail launch
+            quantize_group<K, true>((const float *)it.values, lo, G, m, g, it.codes, it.labels, it.params, it.fit_out,
+                                    it.fit_in, status, shared[wave], lane);
     } else {
         // one wave per tensor: its short last group, if it has one
         const int64_t t = (int64_t)blockIdx.x * kQWaves + wave;
         if (t >= count)
             return;
-        const bitsnap_cluster_item it = items[t];
+        const bitsnap_cluster_item &it = items[t];
         const int64_t g = it.n / G;
         const int rest = (int)(it.n - g * G);
         if (rest > 0)
@@ -434,19 +443,16 @@ __global__ __launch_bounds__(kQBlock) void dequantize_cluster_batched_kernel(
     __shared__ float2 coder[kQWaves][kMaxClusters];
     const int lane = threadIdx.x & (kWave - 1), wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     constexpr int G = 256 * K;
-    int64_t t = 0;
-    bitsnap_cluster_item it = items[0];
-    int64_t next_first = count > 1 ? items[1].first_group : INT64_MAX;
-    const int64_t stride = (int64_t)gridDim.x * kQWaves;
-    for (int64_t gg = (int64_t)blockIdx.x * kQWaves + wave; gg < total_groups; gg += stride) {
-        seek_item(items, count, gg, t, it, next_first);
-        const int64_t g = gg - it.first_group;
-        const int64_t lo = g * G;
-        const int64_t rest = it.n - lo;
-        if (rest > 0)
-            dequantize_group<K>(it.codes, it.labels, it.params, lo, rest >= G ? G : (int)rest, m, g, (float *)it.values,
-                                coder[wave], lane);
-    }
+    const int64_t gg = (int64_t)blockIdx.x * kQWaves + wave;
+    if (gg >= total_groups)
+        return;
+    const bitsnap_cluster_item &it = items[find_item(items, count, gg)];
+    const int64_t g = gg - it.first_group;
+    const int64_t lo = g * G;
+    const int64_t rest = it.n - lo;
+    if (rest > 0)
+        dequantize_group<K>(it.codes, it.labels, it.params, lo, rest >= G ? G : (int)rest, m, g, (float *)it.values,
+                            coder[wave], lane);
 }
 
 // K (float4 per lane) of the one-wave-per-group kernels, or 0 when the group length needs the
@@ -594,12 +600,7 @@ extern "C" int bitsnap_dequantize_cluster(const uint8_t *codes, const uint8_t *l
     return launch_status();
 }
 
-static int batched_grid(int64_t total_groups)
-{
-    const int64_t blocks = (total_groups + kQWaves - 1) / kQWaves;
-    const int64_t cap = (int64_t)device_info().cu_count * 4;  // 16 waves per CU stay resident
-    return (int)(blocks < 1 ? 1 : (blocks < cap ? blocks : cap));
-}
+static int64_t batched_blocks(int64_t total_groups) { return (total_groups + kQWaves - 1) / kQWaves; }
 
 extern "C" int bitsnap_quantize_cluster_batched(const bitsnap_cluster_item *items, int64_t count, int64_t total_groups,
                                                 int64_t group, int m, uint32_t *status, bitsnap_stream_t stream)
@@ -615,7 +616,9 @@ extern "C" int bitsnap_quantize_cluster_batched(const bitsnap_cluster_item *item
         return BITSNAP_E_NULL;
     if (((uintptr_t)items & 7u) || ((uintptr_t)status & 3u))
         return BITSNAP_E_ALIGN;
-    const dim3 block(kQBlock), grid(batched_grid(total_groups)), tgrid((unsigned)((count + kQWaves - 1) / kQWaves));
+    if (batched_blocks(total_groups) > 0x7FFFFFFF)
+        return BITSNAP_E_SIZE;
+    const dim3 block(kQBlock), grid((unsigned)batched_blocks(total_groups)), tgrid((unsigned)((count + kQWaves - 1) / kQWaves));
     hipStream_t s = (hipStream_t)stream;
 #define BITSNAP_LAUNCH_QB(KK)                                                                                     \
     do {                                                                                                          \
@@ -649,7 +652,9 @@ extern "C" int bitsnap_dequantize_cluster_batched(const bitsnap_cluster_item *it
         return BITSNAP_E_NULL;
     if ((uintptr_t)items & 7u)
         return BITSNAP_E_ALIGN;
-    const dim3 block(kQBlock), grid(batched_grid(total_groups));
+    if (batched_blocks(total_groups) > 0x7FFFFFFF)
+        return BITSNAP_E_SIZE;
+    const dim3 block(kQBlock), grid((unsigned)batched_blocks(total_groups));
     hipStream_t s = (hipStream_t)stream;
 #define BITSNAP_LAUNCH_DB(KK) \
     hipLaunchKernelGGL(dequantize_cluster_batched_kernel<KK>, grid, block, 0, s, items, count, total_groups, m)
