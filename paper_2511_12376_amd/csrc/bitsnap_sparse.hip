@@ -334,92 +334,183 @@ __device__ __forceinline__ void load_tile_mask(const uint8_t *__restrict__ mask,
         }
 }
 
+// ---------------------------------------------------------------------------------------------
+// decode_sparse.  The ranks of the inverse only depend on the mask, which is 1/33 of the data, so
+// the decoder does not scan while it streams: a first kernel counts the set bits of every tile,
+// a second turns the counts into per-tile payload offsets (one workgroup per tensor), and the
+// third, which moves all the bytes, has no dependency between workgroups at all.
+// ---------------------------------------------------------------------------------------------
+
+// The item that holds launch-wide tile gt (binary search on wave-uniform operands).
+__device__ __forceinline__ int64_t find_sparse_item(const bitsnap_sparse_item *__restrict__ items, int64_t count, int64_t gt)
+{
+    int64_t lo = 0, hi = count - 1;
+    while (lo < hi) {
+        const int64_t mid = (lo + hi + 1) >> 1;
+        if (items[mid].first_tile <= gt)
+            lo = mid;
+        else
+            hi = mid - 1;
+    }
+    return lo;
+}
+
+// One wave per tile: popcount of the tile's 2 KB of mask (bits at or beyond n do not count).
 template <bool kBatched>
-__global__ __launch_bounds__(kBlock) void decode_sparse_kernel(bitsnap_sparse_item single,
-                                                               const bitsnap_sparse_item *__restrict__ items,
-                                                               int64_t count, ScanHeader *hdr, uint64_t *status,
-                                                               int64_t status_cap, int64_t num_tiles, uint32_t spin_limit)
+__global__ __launch_bounds__(kBlock) void decode_count_kernel(bitsnap_sparse_item single,
+                                                              const bitsnap_sparse_item *__restrict__ items,
+                                                              int64_t count, int64_t num_tiles,
+                                                              uint32_t *__restrict__ tile_count)
+{
+    const int lane = threadIdx.x & (kWave - 1), wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int64_t gt = (int64_t)blockIdx.x * kWaves + wave;
+    if (gt >= num_tiles)
+        return;
+    const bitsnap_sparse_item &it = kBatched ? items[find_sparse_item(items, count, gt)] : single;
+    const int64_t tile = gt - it.first_tile, n = it.n;
+    const int64_t mask_bytes = (n + 7) >> 3;
+    constexpr int kTileMaskBytes = kTileElems / 8, kPerLane = kTileMaskBytes / kWave;  // 2048, 32
+    static_assert(kPerLane % 16 == 0, "a lane reads whole 16-byte pieces of the mask");
+    uint32_t c = 0;
+#pragma unroll
+    for (int q = 0; q < kPerLane / 16; ++q) {
+        const int64_t b0 = tile * kTileMaskBytes + (int64_t)(q * kWave + lane) * 16;  // byte offset, 16-aligned
+        uint32_t w[4] = {0, 0, 0, 0};
+        if (b0 + 16 <= mask_bytes) {
+            const uint4 v = *reinterpret_cast<const uint4 *>(it.mask + b0);
+            w[0] = v.x, w[1] = v.y, w[2] = v.z, w[3] = v.w;
+        } else {
+            for (int t = 0; t < 16; ++t)
+                if (b0 + t < mask_bytes)
+                    w[t >> 2] |= (uint32_t)it.mask[b0 + t] << ((t & 3) * 8);
+        }
+        // bits at or beyond n carry no element
+        const int64_t e0 = b0 * 8;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int64_t ek = e0 + 32 * k;
+            if (ek + 32 > n)
+                w[k] &= (ek < n) ? ((1u << (uint32_t)(n - ek)) - 1u) : 0u;
+            c += __popc(w[k]);
+        }
+    }
+    c = wave_inclusive_add(c);
+    if (lane == kWave - 1)
+        tile_count[gt] = c;
+}
+
+// One workgroup per tensor: exclusive scan of its tiles' counts -> payload offset of every tile,
+// and the tensor's total.
+template <bool kBatched>
+__global__ __launch_bounds__(kBlock) void decode_scan_kernel(bitsnap_sparse_item single,
+                                                             const bitsnap_sparse_item *__restrict__ items,
+                                                             const uint32_t *__restrict__ tile_count,
+                                                             uint64_t *__restrict__ tile_offset)
+{
+    __shared__ uint64_t wave_sum_s[kWaves];
+    __shared__ uint64_t carry_s;
+    const bitsnap_sparse_item &it = kBatched ? items[blockIdx.x] : single;
+    const int64_t ntiles = (it.n + kTileElems - 1) / kTileElems, first = it.first_tile;
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
+    if (tid == 0)
+        carry_s = 0;
+    __syncthreads();
+    for (int64_t base = 0; base < ntiles; base += kBlock) {
+        const int64_t i = base + tid;
+        const uint32_t c = i < ntiles ? tile_count[first + i] : 0u;
+        const uint32_t incl = wave_inclusive_add(c);  // a wave covers 64 tiles: at most 2^20 elements
+        if (lane == kWave - 1)
+            wave_sum_s[wave] = incl;
+        __syncthreads();
+        uint64_t before = carry_s;
+        for (int w = 0; w < wave; ++w)
+            before += wave_sum_s[w];
+        if (i < ntiles)
+            tile_offset[first + i] = before + incl - c;
+        __syncthreads();
+        if (tid == kBlock - 1)
+            carry_s = before + incl;
+        __syncthreads();
+    }
+    if (tid == 0 && it.n_changed)
+        *it.n_changed = carry_s;
+}
+
+// One workgroup per tile: out = bit ? next payload element : base.
+template <bool kBatched>
+__global__ __launch_bounds__(kBlock) void decode_merge_kernel(bitsnap_sparse_item single,
+                                                              const bitsnap_sparse_item *__restrict__ items,
+                                                              int64_t count, const uint64_t *__restrict__ tile_offset)
 {
     __shared__ TileShared sh;
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
-    const uint32_t epoch = hdr->epoch;
-    bool aborted = false;
-    ItemCursor<kBatched> cursor(single, items, count);
+    const int64_t gtile = blockIdx.x;
+    const bitsnap_sparse_item &it = kBatched ? items[find_sparse_item(items, count, gtile)] : single;
+    const uint16_t *base = (const uint16_t *)it.base;  // may alias out
+    const uint8_t *__restrict__ mask = it.mask;
+    const uint16_t *__restrict__ payload = (const uint16_t *)it.payload;
+    uint16_t *out = (uint16_t *)it.out;
+    const int64_t n = it.n, payload_elems = it.capacity, tile = gtile - it.first_tile;
+    const int64_t mask_bytes = (n + 7) >> 3;
 
-    for (int64_t gtile = claim_tile(sh, hdr); gtile < num_tiles; gtile = claim_tile(sh, hdr)) {
-        cursor.seek(gtile);
-        const bitsnap_sparse_item &it = cursor.it;
-        const uint16_t *base = (const uint16_t *)it.base;  // may alias out
-        const uint8_t *__restrict__ mask = it.mask;
-        const uint16_t *__restrict__ payload = (const uint16_t *)it.payload;
-        uint16_t *out = (uint16_t *)it.out;
-        const int64_t n = it.n, payload_elems = it.capacity, tile = gtile - it.first_tile;
-        const int64_t mask_bytes = (n + 7) >> 3;
+    const uint64_t excl = tile_offset[gtile];
+    uint32_t m[kRounds][2], cnt[kRounds][2], rank[kRounds][2];
+    uint4 v[kRounds][2];
+    load_tile_mask(mask, mask_bytes, tile, wave, lane, n, m);
+    load_tile16(base, tile, wave, lane, n, v);
+#pragma unroll
+    for (int r = 0; r < kRounds; ++r)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+            cnt[r][j] = __popc(m[r][j]);
+    uint32_t total;
+    tile_ranks(sh, cnt, lane, wave, rank, total);  // barrier
 
-        uint32_t m[kRounds][2], cnt[kRounds][2], rank[kRounds][2];
-        uint4 v[kRounds][2];
-        load_tile_mask(mask, mask_bytes, tile, wave, lane, n, m);  // the mask first: the scan only needs it
-        load_tile16(base, tile, wave, lane, n, v);                  // in flight during the scan
-#pragma unroll
-        for (int r = 0; r < kRounds; ++r)
-#pragma unroll
-            for (int j = 0; j < 2; ++j)
-                cnt[r][j] = __popc(m[r][j]);
-        uint32_t total;
-        tile_ranks(sh, cnt, lane, wave, rank, total);  // barrier
-        if (wave == 0)
-            tile_prefix(sh, hdr, status, gtile, it.first_tile, epoch, spin_limit, total, lane);
-        __syncthreads();
-        const uint64_t excl = sh.excl;
-        if (sh.aborted) {
-            aborted = true;
-            break;
+    // the tile's payload segment [excl, excl+total) -> LDS, as aligned 16-byte pieces
+    const uint32_t shift = (uint32_t)(excl & 7u);
+    const uint32_t last = shift + total;
+    const int64_t src0 = (int64_t)(excl - shift);
+    const uint32_t pieces = (last + 7u) >> 3;
+    for (uint32_t q = tid; q < pieces; q += kBlock) {
+        const uint32_t lo = q * 8u;
+        const int64_t s = src0 + lo;
+        uint4 pv = make_uint4(0, 0, 0, 0);
+        if (s + 8 <= payload_elems) {
+            pv = *reinterpret_cast<const uint4 *>(payload + s);
+        } else {
+            uint32_t w[4] = {0, 0, 0, 0};
+            for (int t = 0; t < 8; ++t)
+                if (s + t < payload_elems)
+                    w[t >> 1] |= (uint32_t)payload[s + t] << ((t & 1) * 16);
+            pv = make_uint4(w[0], w[1], w[2], w[3]);
         }
-        if (tid == 0 && it.n_changed && (tile + 1) * kTileElems >= n)
-            *it.n_changed = excl + total;
-
-        // the tile's payload segment [excl, excl+total) -> LDS, as aligned 16-byte pieces
-        const uint32_t shift = (uint32_t)(excl & 7u);
-        const uint32_t last = shift + total;
-        const int64_t src0 = (int64_t)(excl - shift);
-        const uint32_t pieces = (last + 7u) >> 3;
-        for (uint32_t q = tid; q < pieces; q += kBlock) {
-            const uint32_t lo = q * 8u;
-            const int64_t s = src0 + lo;
-            uint4 pv = make_uint4(0, 0, 0, 0);
-            if (s + 8 <= payload_elems) {
-                pv = *reinterpret_cast<const uint4 *>(payload + s);
-            } else {
-                uint32_t w[4] = {0, 0, 0, 0};
-                for (int t = 0; t < 8; ++t)
-                    if (s + t < payload_elems)
-                        w[t >> 1] |= (uint32_t)payload[s + t] << ((t & 1) * 16);
-                pv = make_uint4(w[0], w[1], w[2], w[3]);
-            }
-            *reinterpret_cast<uint4 *>(&sh.stage[lo]) = pv;
-        }
-        __syncthreads();
-
-#pragma unroll
-        for (int r = 0; r < kRounds; ++r)
-#pragma unroll
-            for (int j = 0; j < 2; ++j) {
-                uint32_t p = shift + rank[r][j];
-                uint32_t w[4] = {v[r][j].x, v[r][j].y, v[r][j].z, v[r][j].w};
-#pragma unroll
-                for (int t = 0; t < kLaneElems; ++t) {
-                    if ((m[r][j] >> t) & 1u) {
-                        const uint32_t s = sh.stage[p++];
-                        w[t >> 1] = (t & 1) ? ((w[t >> 1] & 0x0000FFFFu) | (s << 16)) : ((w[t >> 1] & 0xFFFF0000u) | s);
-                    }
-                }
-                store8(out, piece_chunk(tile, r, wave, j) * kChunkElems + lane * kLaneElems, n,
-                       make_uint4(w[0], w[1], w[2], w[3]));
-            }
+        *reinterpret_cast<uint4 *>(&sh.stage[lo]) = pv;
     }
-    const int epilogue = scan_epilogue(hdr, status, status_cap, epoch, aborted);
-    report_failures(epilogue, single, items, count, kBatched, num_tiles);
+    __syncthreads();
+
+#pragma unroll
+    for (int r = 0; r < kRounds; ++r)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            uint32_t p = shift + rank[r][j];
+            uint32_t w[4] = {v[r][j].x, v[r][j].y, v[r][j].z, v[r][j].w};
+#pragma unroll
+            for (int t = 0; t < kLaneElems; ++t) {
+                if ((m[r][j] >> t) & 1u) {
+                    const uint32_t s = sh.stage[p++];
+                    w[t >> 1] = (t & 1) ? ((w[t >> 1] & 0x0000FFFFu) | (s << 16)) : ((w[t >> 1] & 0xFFFF0000u) | s);
+                }
+            }
+            store8(out, piece_chunk(tile, r, wave, j) * kChunkElems + lane * kLaneElems, n,
+                   make_uint4(w[0], w[1], w[2], w[3]));
+        }
 }
+
+// Workspace after the header: encode keeps one 8-byte scan word per tile there; decode keeps the
+// tiles' payload offsets (8 bytes each, in the same place) followed by their counts (4 bytes each).
+// A raw offset is below 2^40, so as a scan word its flag bits read "not written": a decode never
+// confuses a later encode.
+constexpr size_t kWorkspaceBytesPerTile = 16;
 
 static uint32_t g_spin_limit = kDefaultSpinLimit;
 
@@ -459,7 +550,7 @@ extern "C" size_t bitsnap_sparse_mask_bytes(int64_t n)
 extern "C" size_t bitsnap_sparse_workspace_bytes(int64_t n)
 {
     const int64_t tiles = n <= 0 ? 0 : (n + kTileElems - 1) / kTileElems;
-    const size_t bytes = kScanHeaderBytes + (size_t)tiles * sizeof(uint64_t);
+    const size_t bytes = kScanHeaderBytes + (size_t)tiles * kWorkspaceBytesPerTile;
     return (bytes + 255) / 256 * 256;
 }
 
@@ -486,9 +577,31 @@ static int check_scan_workspace(void *workspace, size_t workspace_bytes, int64_t
         return BITSNAP_E_NULL;
     if (!aligned16(workspace))
         return BITSNAP_E_ALIGN;
-    if (workspace_bytes < kScanHeaderBytes + (size_t)num_tiles * sizeof(uint64_t))
+    if (workspace_bytes < kScanHeaderBytes + (size_t)num_tiles * kWorkspaceBytesPerTile)
         return BITSNAP_E_WORKSPACE;
     return BITSNAP_OK;
+}
+
+template <bool kBatched>
+static int launch_decode(const bitsnap_sparse_item &single, const bitsnap_sparse_item *items, int64_t count,
+                         int64_t num_tiles, void *workspace, bitsnap_stream_t stream)
+{
+    uint64_t *tile_offset = reinterpret_cast<uint64_t *>(reinterpret_cast<char *>(workspace) + kScanHeaderBytes);
+    uint32_t *tile_count = reinterpret_cast<uint32_t *>(tile_offset + num_tiles);
+    hipStream_t s = (hipStream_t)stream;
+    if (num_tiles > 0) {
+        if ((num_tiles + kWaves - 1) / kWaves > 0x7FFFFFFF || num_tiles > 0x7FFFFFFF)
+            return BITSNAP_E_SIZE;
+        hipLaunchKernelGGL(decode_count_kernel<kBatched>, dim3((unsigned)((num_tiles + kWaves - 1) / kWaves)), dim3(kBlock),
+                           0, s, single, items, count, num_tiles, tile_count);
+    }
+    // the scan also reports n_changed, for an empty tensor too
+    hipLaunchKernelGGL(decode_scan_kernel<kBatched>, dim3((unsigned)(kBatched ? count : 1)), dim3(kBlock), 0, s, single,
+                       items, tile_count, tile_offset);
+    if (num_tiles > 0)
+        hipLaunchKernelGGL(decode_merge_kernel<kBatched>, dim3((unsigned)num_tiles), dim3(kBlock), 0, s, single, items,
+                           count, tile_offset);
+    return launch_status();
 }
 
 extern "C" int bitsnap_encode_sparse(const void *cur, const void *base, int64_t n, int elem_bytes, uint8_t *mask,
@@ -539,12 +652,12 @@ extern "C" int bitsnap_decode_sparse(const void *base, const uint8_t *mask, cons
     it.n_changed = n_changed;
     it.n = n;
     it.capacity = payload_elems;
-    return launch_scan(&decode_sparse_kernel<false>, it, nullptr, 1, tiles_of(n), workspace, workspace_bytes, stream);
+    return launch_decode<false>(it, nullptr, 1, tiles_of(n), workspace, stream);
 }
 
 extern "C" size_t bitsnap_sparse_batch_workspace_bytes(int64_t total_tiles)
 {
-    const size_t bytes = kScanHeaderBytes + (size_t)(total_tiles < 0 ? 0 : total_tiles) * sizeof(uint64_t);
+    const size_t bytes = kScanHeaderBytes + (size_t)(total_tiles < 0 ? 0 : total_tiles) * kWorkspaceBytesPerTile;
     return (bytes + 255) / 256 * 256;
 }
 
@@ -578,6 +691,5 @@ extern "C" int bitsnap_decode_sparse_batched(const bitsnap_sparse_item *items, i
         return rc;
     if (count == 0 || total_tiles == 0)
         return BITSNAP_OK;
-    return launch_scan(&decode_sparse_kernel<true>, bitsnap_sparse_item{}, items, count, total_tiles, workspace,
-                       workspace_bytes, stream);
+    return launch_decode<true>(bitsnap_sparse_item{}, items, count, total_tiles, workspace, stream);
 }
