@@ -70,10 +70,11 @@ size_t bitsnap_sparse_tile_elems(void);
  * bytes after ceil(n/8) are written as 0. */
 size_t bitsnap_sparse_mask_bytes(int64_t n);
 
-/* Bytes of workspace encode_sparse / decode_sparse need for a tensor of n elements.  The
- * workspace holds the cross-workgroup scan state.  It must contain zeros the first time it is
- * used (any means: hipMemset, torch.zeros); afterwards the kernels leave it ready for the next
- * call, of any size that fits, so one workspace serves a whole checkpoint. */
+/* Bytes of workspace encode_sparse / decode_sparse need for a tensor of n elements (256 bytes
+ * plus 16 per tile).  encode keeps its cross-workgroup scan state there, decode the payload
+ * offset and count of every tile.  It must contain zeros the first time it is used (any means:
+ * hipMemset, torch.zeros); afterwards the kernels leave it ready for the next call, encode or
+ * decode, of any size that fits, so one workspace serves a whole checkpoint. */
 size_t bitsnap_sparse_workspace_bytes(int64_t n);
 
 /* Algorithm 1, steps 1-5, for one tensor.
@@ -103,9 +104,9 @@ int bitsnap_encode_sparse(const void *cur, const void *base, int64_t n, int elem
  *   payload          [payload_elems] 16-bit, aligned.  Never read at or beyond payload_elems;
  *                    if the mask has more set bits than that, the surplus elements decode to 0.
  *   out              [n] 16-bit, aligned; may be the same buffer as base (in-place patch)
- *   n_changed        nullable, [1] out: the number of set mask bits below n (UINT64_MAX: as in
- *                    encode_sparse)
- */
+ *   n_changed        nullable, [1] out: the number of set mask bits below n
+ * Three launches: set bits per tile, payload offset per tile, then the merge, which has no
+ * dependency between workgroups (nothing in decode waits, so it cannot give up). */
 int bitsnap_decode_sparse(const void *base, const uint8_t *mask, const void *payload,
                           int64_t payload_elems, int64_t n, int elem_bytes, void *out,
                           uint64_t *n_changed,
@@ -208,7 +209,8 @@ typedef struct bitsnap_sparse_item {
 size_t bitsnap_sparse_batch_workspace_bytes(int64_t total_tiles);
 
 /* The scan restarts at every tensor: each item gets its own mask, payload and n_changed exactly
- * as from the single-tensor call.  If the scan gives up, every item's n_changed reads UINT64_MAX. */
+ * as from the single-tensor call.  If encode's scan gives up, every item's n_changed reads
+ * UINT64_MAX. */
 int bitsnap_encode_sparse_batched(const bitsnap_sparse_item *items, int64_t count, int64_t total_tiles,
                                   void *workspace, size_t workspace_bytes, bitsnap_stream_t stream);
 int bitsnap_decode_sparse_batched(const bitsnap_sparse_item *items, int64_t count, int64_t total_tiles,

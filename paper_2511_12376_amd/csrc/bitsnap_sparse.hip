@@ -31,7 +31,9 @@ constexpr int kRoundChunks = 2 * kWaves;                   // a round: every wav
 constexpr int kRoundElems = kRoundChunks * kChunkElems;    // 4096
 constexpr int kRounds = BITSNAP_SPARSE_ROUNDS;             // rounds per tile, all loaded before the scan
 constexpr int kTileElems = kRounds * kRoundElems;          // one ticket, one status word, one look-back
-constexpr int kStageElems = kTileElems + 8;                // + alignment shift
+constexpr int kPhases = (kRounds % 2 == 0) ? 2 : 1;         // the payload passes through LDS in this many parts
+constexpr int kPhaseRounds = kRounds / kPhases;
+constexpr int kStageElems = kPhaseRounds * kRoundElems + 8; // one part + alignment shift
 
 struct TileShared {
     alignas(16) uint16_t stage[kStageElems];
@@ -93,10 +95,11 @@ __device__ __forceinline__ int64_t piece_chunk(int64_t tile, int r, int wave, in
     return tile * (kRounds * kRoundChunks) + r * kRoundChunks + wave * 2 + j;
 }
 
-// Per-lane popcounts m[r][j] -> this lane's exclusive rank of each piece inside the tile, and
-// the tile total.  Contains one __syncthreads.
+// Per-lane popcounts m[r][j] -> this lane's exclusive rank of each piece inside the tile, and the
+// rank at which each staging phase starts (the last entry is the tile total).  Contains one
+// __syncthreads.
 __device__ __forceinline__ void tile_ranks(TileShared &sh, const uint32_t (&cnt)[kRounds][2], int lane, int wave,
-                                           uint32_t (&rank)[kRounds][2], uint32_t &tile_total)
+                                           uint32_t (&rank)[kRounds][2], uint32_t (&phase_start)[kPhases + 1])
 {
     uint32_t ex[kRounds], t0[kRounds];
 #pragma unroll
@@ -113,6 +116,8 @@ __device__ __forceinline__ void tile_ranks(TileShared &sh, const uint32_t (&cnt)
     uint32_t run = 0;
 #pragma unroll
     for (int r = 0; r < kRounds; ++r) {
+        if (r % kPhaseRounds == 0)
+            phase_start[r / kPhaseRounds] = run;
         uint32_t before = 0, all = 0;
 #pragma unroll
         for (int w = 0; w < kWaves; ++w) {
@@ -124,7 +129,7 @@ __device__ __forceinline__ void tile_ranks(TileShared &sh, const uint32_t (&cnt)
         rank[r][1] = run + before + t0[r] + (ex[r] >> 16);
         run += all;
     }
-    tile_total = run;
+    phase_start[kPhases] = run;  // the tile total
 }
 
 // Wave 0: publish the tile's count, find the count of everything before it in the same tensor,
@@ -265,8 +270,9 @@ __global__ __launch_bounds__(kBlock) void encode_sparse_kernel(bitsnap_sparse_it
                         mask[mb] = (uint8_t)m[r][j];
                 }
         }
-        uint32_t total;
-        tile_ranks(sh, cnt, lane, wave, rank, total);  // barrier
+        uint32_t phase_start[kPhases + 1];
+        tile_ranks(sh, cnt, lane, wave, rank, phase_start);  // barrier
+        const uint32_t total = phase_start[kPhases];
         if (wave == 0)
             tile_prefix(sh, hdr, status, gtile, it.first_tile, epoch, spin_limit, total, lane);
         __syncthreads();
@@ -282,33 +288,42 @@ __global__ __launch_bounds__(kBlock) void encode_sparse_kernel(bitsnap_sparse_it
                 *it.n_changed = excl + total;
         }
 
-        // Algorithm 1 step 5: changed values, in index order.  Staged at (offset mod 8) so that
-        // 16-byte pieces of LDS line up with 16-byte pieces of the payload buffer.
-        const uint32_t shift = (uint32_t)(excl & 7u);
+        // Algorithm 1 step 5: changed values, in index order, in kPhases parts (rounds are
+        // consecutive in rank, so a part is a contiguous piece of the payload).  Each part is
+        // staged in LDS at (its offset mod 8), so that 16-byte pieces of LDS line up with 16-byte
+        // pieces of the payload buffer; the ragged ends of a part go out element by element.
 #pragma unroll
-        for (int r = 0; r < kRounds; ++r)
+        for (int ph = 0; ph < kPhases; ++ph) {
+            const uint64_t part_off = excl + phase_start[ph];
+            const uint32_t part_len = phase_start[ph + 1] - phase_start[ph];
+            const uint32_t shift = (uint32_t)(part_off & 7u);
+            if (ph > 0)
+                __syncthreads();  // the previous part has left the stage
 #pragma unroll
-            for (int j = 0; j < 2; ++j) {
-                uint32_t p = shift + rank[r][j];
+            for (int r = ph * kPhaseRounds; r < (ph + 1) * kPhaseRounds; ++r)
 #pragma unroll
-                for (int t = 0; t < kLaneElems; ++t)
-                    if ((m[r][j] >> t) & 1u)
-                        sh.stage[p++] = elem16(c[r][j], t);
-            }
-        __syncthreads();
-        const uint32_t first = shift, last = shift + total;  // valid staged range [first, last)
-        const int64_t dst0 = (int64_t)(excl - shift);         // payload element of stage[0], multiple of 8
-        const uint32_t pieces = (last + 7u) >> 3;
-        for (uint32_t q = tid; q < pieces; q += kBlock) {
-            const uint32_t lo = q * 8u;
-            const int64_t d = dst0 + lo;
-            if (lo >= first && lo + 8u <= last && d + 8 <= capacity) {
-                *reinterpret_cast<uint4 *>(payload + d) = *reinterpret_cast<const uint4 *>(&sh.stage[lo]);
-            } else {
-                for (uint32_t t = 0; t < 8u; ++t) {
-                    const uint32_t i = lo + t;
-                    if (i >= first && i < last && d + t < capacity)
-                        payload[d + t] = sh.stage[i];
+                for (int j = 0; j < 2; ++j) {
+                    uint32_t p = shift + rank[r][j] - phase_start[ph];
+#pragma unroll
+                    for (int t = 0; t < kLaneElems; ++t)
+                        if ((m[r][j] >> t) & 1u)
+                            sh.stage[p++] = elem16(c[r][j], t);
+                }
+            __syncthreads();
+            const uint32_t first = shift, last = shift + part_len;  // valid staged range [first, last)
+            const int64_t dst0 = (int64_t)(part_off - shift);        // payload element of stage[0], multiple of 8
+            const uint32_t pieces = (last + 7u) >> 3;
+            for (uint32_t q = tid; q < pieces; q += kBlock) {
+                const uint32_t lo = q * 8u;
+                const int64_t d = dst0 + lo;
+                if (lo >= first && lo + 8u <= last && d + 8 <= capacity) {
+                    *reinterpret_cast<uint4 *>(payload + d) = *reinterpret_cast<const uint4 *>(&sh.stage[lo]);
+                } else {
+                    for (uint32_t t = 0; t < 8u; ++t) {
+                        const uint32_t i = lo + t;
+                        if (i >= first && i < last && d + t < capacity)
+                            payload[d + t] = sh.stage[i];
+                    }
                 }
             }
         }
@@ -369,25 +384,25 @@ __global__ __launch_bounds__(kBlock) void decode_count_kernel(bitsnap_sparse_ite
     const bitsnap_sparse_item &it = kBatched ? items[find_sparse_item(items, count, gt)] : single;
     const int64_t tile = gt - it.first_tile, n = it.n;
     const int64_t mask_bytes = (n + 7) >> 3;
-    constexpr int kTileMaskBytes = kTileElems / 8, kPerLane = kTileMaskBytes / kWave;  // 2048, 32
-    static_assert(kPerLane % 16 == 0, "a lane reads whole 16-byte pieces of the mask");
+    constexpr int kTileMaskBytes = kTileElems / 8, kPerLane = kTileMaskBytes / kWave;  // 2048 and 32 at 4 rounds
+    static_assert(kPerLane % 8 == 0, "a lane reads whole 8-byte pieces of the mask");
     uint32_t c = 0;
 #pragma unroll
-    for (int q = 0; q < kPerLane / 16; ++q) {
-        const int64_t b0 = tile * kTileMaskBytes + (int64_t)(q * kWave + lane) * 16;  // byte offset, 16-aligned
-        uint32_t w[4] = {0, 0, 0, 0};
-        if (b0 + 16 <= mask_bytes) {
-            const uint4 v = *reinterpret_cast<const uint4 *>(it.mask + b0);
-            w[0] = v.x, w[1] = v.y, w[2] = v.z, w[3] = v.w;
+    for (int q = 0; q < kPerLane / 8; ++q) {
+        const int64_t b0 = tile * kTileMaskBytes + (int64_t)(q * kWave + lane) * 8;  // byte offset, 8-aligned
+        uint32_t w[2] = {0, 0};
+        if (b0 + 8 <= mask_bytes) {
+            const uint2 v = *reinterpret_cast<const uint2 *>(it.mask + b0);
+            w[0] = v.x, w[1] = v.y;
         } else {
-            for (int t = 0; t < 16; ++t)
+            for (int t = 0; t < 8; ++t)
                 if (b0 + t < mask_bytes)
                     w[t >> 2] |= (uint32_t)it.mask[b0 + t] << ((t & 3) * 8);
         }
         // bits at or beyond n carry no element
         const int64_t e0 = b0 * 8;
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
+        for (int k = 0; k < 2; ++k) {
             const int64_t ek = e0 + 32 * k;
             if (ek + 32 > n)
                 w[k] &= (ek < n) ? ((1u << (uint32_t)(n - ek)) - 1u) : 0u;
@@ -463,47 +478,53 @@ __global__ __launch_bounds__(kBlock) void decode_merge_kernel(bitsnap_sparse_ite
 #pragma unroll
         for (int j = 0; j < 2; ++j)
             cnt[r][j] = __popc(m[r][j]);
-    uint32_t total;
-    tile_ranks(sh, cnt, lane, wave, rank, total);  // barrier
+    uint32_t phase_start[kPhases + 1];
+    tile_ranks(sh, cnt, lane, wave, rank, phase_start);  // barrier
 
-    // the tile's payload segment [excl, excl+total) -> LDS, as aligned 16-byte pieces
-    const uint32_t shift = (uint32_t)(excl & 7u);
-    const uint32_t last = shift + total;
-    const int64_t src0 = (int64_t)(excl - shift);
-    const uint32_t pieces = (last + 7u) >> 3;
-    for (uint32_t q = tid; q < pieces; q += kBlock) {
-        const uint32_t lo = q * 8u;
-        const int64_t s = src0 + lo;
-        uint4 pv = make_uint4(0, 0, 0, 0);
-        if (s + 8 <= payload_elems) {
-            pv = *reinterpret_cast<const uint4 *>(payload + s);
-        } else {
-            uint32_t w[4] = {0, 0, 0, 0};
-            for (int t = 0; t < 8; ++t)
-                if (s + t < payload_elems)
-                    w[t >> 1] |= (uint32_t)payload[s + t] << ((t & 1) * 16);
-            pv = make_uint4(w[0], w[1], w[2], w[3]);
-        }
-        *reinterpret_cast<uint4 *>(&sh.stage[lo]) = pv;
-    }
-    __syncthreads();
-
+    // the tile's payload segment, in kPhases contiguous parts -> LDS as aligned 16-byte pieces
 #pragma unroll
-    for (int r = 0; r < kRounds; ++r)
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            uint32_t p = shift + rank[r][j];
-            uint32_t w[4] = {v[r][j].x, v[r][j].y, v[r][j].z, v[r][j].w};
-#pragma unroll
-            for (int t = 0; t < kLaneElems; ++t) {
-                if ((m[r][j] >> t) & 1u) {
-                    const uint32_t s = sh.stage[p++];
-                    w[t >> 1] = (t & 1) ? ((w[t >> 1] & 0x0000FFFFu) | (s << 16)) : ((w[t >> 1] & 0xFFFF0000u) | s);
-                }
+    for (int ph = 0; ph < kPhases; ++ph) {
+        const uint64_t part_off = excl + phase_start[ph];
+        const uint32_t part_len = phase_start[ph + 1] - phase_start[ph];
+        const uint32_t shift = (uint32_t)(part_off & 7u);
+        const uint32_t last = shift + part_len;
+        const int64_t src0 = (int64_t)(part_off - shift);
+        const uint32_t pieces = (last + 7u) >> 3;
+        if (ph > 0)
+            __syncthreads();  // the previous part has been consumed
+        for (uint32_t q = tid; q < pieces; q += kBlock) {
+            const uint32_t lo = q * 8u;
+            const int64_t s = src0 + lo;
+            uint4 pv = make_uint4(0, 0, 0, 0);
+            if (s + 8 <= payload_elems) {
+                pv = *reinterpret_cast<const uint4 *>(payload + s);
+            } else {
+                uint32_t w[4] = {0, 0, 0, 0};
+                for (int t = 0; t < 8; ++t)
+                    if (s + t < payload_elems)
+                        w[t >> 1] |= (uint32_t)payload[s + t] << ((t & 1) * 16);
+                pv = make_uint4(w[0], w[1], w[2], w[3]);
             }
-            store8(out, piece_chunk(tile, r, wave, j) * kChunkElems + lane * kLaneElems, n,
-                   make_uint4(w[0], w[1], w[2], w[3]));
+            *reinterpret_cast<uint4 *>(&sh.stage[lo]) = pv;
         }
+        __syncthreads();
+#pragma unroll
+        for (int r = ph * kPhaseRounds; r < (ph + 1) * kPhaseRounds; ++r)
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                uint32_t p = shift + rank[r][j] - phase_start[ph];
+                uint32_t w[4] = {v[r][j].x, v[r][j].y, v[r][j].z, v[r][j].w};
+#pragma unroll
+                for (int t = 0; t < kLaneElems; ++t) {
+                    if ((m[r][j] >> t) & 1u) {
+                        const uint32_t s = sh.stage[p++];
+                        w[t >> 1] = (t & 1) ? ((w[t >> 1] & 0x0000FFFFu) | (s << 16)) : ((w[t >> 1] & 0xFFFF0000u) | s);
+                    }
+                }
+                store8(out, piece_chunk(tile, r, wave, j) * kChunkElems + lane * kLaneElems, n,
+                       make_uint4(w[0], w[1], w[2], w[3]));
+            }
+    }
 }
 
 // Workspace after the header: encode keeps one 8-byte scan word per tile there; decode keeps the
@@ -514,10 +535,15 @@ constexpr size_t kWorkspaceBytesPerTile = 16;
 
 static uint32_t g_spin_limit = kDefaultSpinLimit;
 
+// Persistent grid of the scan kernel.  Tiles are handed out by ticket, so nothing depends on every
+// workgroup being resident: a workgroup that only starts after others have finished finds no tile
+// left and exits.  Four per CU measured best (the occupancy query is conservative on this chip).
 static int sparse_grid(const void *kernel, int64_t num_tiles)
 {
     const DeviceInfo &di = device_info();
     int per_cu = occupancy_blocks_per_cu(kernel, kBlock);
+    if (per_cu < 4)
+        per_cu = 4;
     int64_t resident = (int64_t)di.cu_count * per_cu;
     int64_t g = num_tiles < resident ? num_tiles : resident;
     return (int)(g < 1 ? 1 : g);
