@@ -191,8 +191,6 @@ def main():
     other_ms, other_op_ms = time_mode(other)
     ms_per_step, op_ms = time_mode(args.mode)
     n_launch = {op: (len(bcalls[op]) if args.mode == "batched" else len(calls[op])) for op in order}
-    if args.mode == "batched":   # the cluster quantiser's batched form adds one launch for short last groups
-        n_launch["quantize_cluster"] *= 2
 
     # what a dependency-free streaming copy sustains on this machine (context for the fractions below,
     # and the kernel the HBM byte counters are calibrated against: it reads and writes cal_bytes)
@@ -225,7 +223,7 @@ def main():
     ops = {}
     for op in order:
         sec = op_ms[op] * 1e-3
-        ops[op] = {"ms": round(op_ms[op], 3), "launches": n_launch[op],
+        ops[op] = {"ms": round(op_ms[op], 3), "api_calls": n_launch[op],
                    "state_GBps": round(state_bytes[op] / sec / 1e9, 1),
                    "hbm_GBps": round(alg_bytes[op] / sec / 1e9, 1),
                    "hbm_frac": round(alg_bytes[op] / sec / 1e9 / HBM_PEAK_GBS, 4)}

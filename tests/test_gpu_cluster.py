@@ -135,6 +135,22 @@ def test_degenerate_groups():
     _compare(y, 256, 1)
 
 
+@pytest.mark.parametrize("scale", [1.0, 2.0 ** -10, 2.0 ** 7])
+def test_exact_ties_round_to_the_even_code(scale):
+    """Scaled positions exactly half-way between two codes: the hardware conversion must round to the even code
+    like the oracle's rint (closed form: b = 0, S = 255*scale, every operation exact)."""
+    announce("cluster exact ties", scale)
+    j = np.arange(255, dtype=np.float64)
+    x = (np.concatenate([j + 0.5, j, [255.0, 0.0]]) * scale).astype(np.float32)
+    want = np.concatenate([2 * np.floor((j + 1) / 2), j, [255, 0]]).astype(np.uint8)
+    g, _ = _gpu_quantize(x, 512, 1)
+    assert np.array_equal(g["codes"], want)
+    _compare(x, 512, 1)
+    # the same values inside 16 clusters of a 4096-element group: whatever the clusters are, GPU == oracle
+    big = np.tile(x, 8)
+    _compare(big, 4096, 16)
+
+
 def test_non_finite_input_sets_status_and_stays_in_bounds():
     announce("cluster non-finite")
     x = np.random.default_rng(1).standard_normal(3 * 4096).astype(np.float32)

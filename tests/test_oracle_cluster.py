@@ -222,6 +222,26 @@ def test_one_cluster_is_plain_minmax_uint8():
     assert np.allclose(xh, mn + code / 255 * (mx - mn), rtol=0, atol=(mx - mn) / 255 * 1.001)
 
 
+def _tie_group(scale):
+    """512 values whose scaled position (x-b)*255/S is exactly j or j + 1/2: b = 0 and S = 255*scale with scale a
+    power of two, so every step of the code's arithmetic is exact and the code has a closed form."""
+    j = np.arange(255, dtype=np.float64)
+    x = np.concatenate([j + 0.5, j, [255.0, 0.0]]) * scale
+    want = np.concatenate([2 * np.floor((j + 1) / 2), j, [255, 0]]).astype(np.uint8)   # half-way cases go to the even code
+    return x.astype(np.float32), want
+
+
+@pytest.mark.parametrize("scale", [1.0, 2.0 ** -10, 2.0 ** 7])
+def test_exact_ties_round_to_the_even_code(scale):
+    """The rounding rule for half-way positions (closest 8-bit level, ties to even), on exact ties."""
+    x, want = _tie_group(scale)
+    assert x.size == 512
+    q = oracle.quantize_cluster(x, G=512, m=1)
+    assert q["params"][0, 0, 0] == np.float32(255 * scale) and q["params"][0, 0, 1] == 0
+    assert np.array_equal(q["codes"], want)
+    assert np.all(want[:255] % 2 == 0)
+
+
 def test_dequantize_formula():
     # Q(j) * S + b on hand-made inputs: 2 clusters, group of 4
     params = np.array([[[2.55, -1.0], [510.0, 100.0]]], np.float32)       # (S, b)

@@ -31,6 +31,7 @@ MUTANTS = [
     ("params_swapped", "pg[2 * l + 1], pg[2 * l + 0]);", "pg[2 * l + 0], pg[2 * l + 1]);", 0),
     ("code_without_offset", "float d = x - b;", "float d = x;", 0),
     ("code_floor", "float r = rintf(y);", "float r = floorf(y);", 0),
+    ("code_ties_away_from_zero", "float r = rintf(y);", "float r = roundf(y);", 0),
     ("code_256_levels", "float inv = 255.0f / S;", "float inv = 256.0f / S;", 0),
     ("label_nibbles_swapped", "(l << ((idx & 1) * 4))", "(l << ((1 - (idx & 1)) * 4))", 0),
     ("dequant_drops_offset", "out[i] = t + b;", "out[i] = t;", 0),
@@ -54,6 +55,7 @@ def _pins(golden):
     yield tc.test_error_bound_endpoints_and_monotone_codes
     yield lambda: tc.test_codes_against_bruteforce_argmin(4)
     yield tc.test_one_cluster_is_plain_minmax_uint8
+    yield lambda: tc.test_exact_ties_round_to_the_even_code(1.0)
     yield tc.test_dequantize_formula
     yield lambda: tc.test_stored_size_formula(golden)
     yield tc.test_degenerate_groups
