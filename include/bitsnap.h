@@ -63,7 +63,7 @@ int bitsnap_debug_stream_copy(void *dst, const void *src, int64_t bytes, bitsnap
  *            n_c elements of 2 bytes.
  * ---------------------------------------------------------------------------------------- */
 
-/* Number of elements covered by one entry of `tile_offsets`. */
+/* Number of elements covered by one entry of `tile_offsets` (32768). */
 size_t bitsnap_sparse_tile_elems(void);
 
 /* Bytes the caller must provide for `mask`: ceil(n/8) rounded up to a multiple of 16.  The
@@ -71,8 +71,9 @@ size_t bitsnap_sparse_tile_elems(void);
 size_t bitsnap_sparse_mask_bytes(int64_t n);
 
 /* Bytes of workspace encode_sparse / decode_sparse need for a tensor of n elements (256 bytes
- * plus 16 per tile).  encode keeps its cross-workgroup scan state there, decode the payload
- * offset and count of every tile.  It must contain zeros the first time it is used (any means:
+ * plus 128 per tile).  encode keeps its cross-workgroup scan state there, one cache line per
+ * tile because all workgroups poll the same few lines; decode the payload offset and count of
+ * every tile.  It must contain zeros the first time it is used (any means:
  * hipMemset, torch.zeros); afterwards the kernels leave it ready for the next call, encode or
  * decode, of any size that fits, so one workspace serves a whole checkpoint. */
 size_t bitsnap_sparse_workspace_bytes(int64_t n);

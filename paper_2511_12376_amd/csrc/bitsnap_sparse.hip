@@ -1,15 +1,18 @@
 // encode_sparse / decode_sparse: bitmask-based delta sparsification of 16-bit model states
 // (paper: "Bitmask Based Sparsification for Model States", improved bitmask; Algorithm 1) and
-// its inverse.  One kernel launch per call, one pass over HBM.
+// its inverse.  Encode is one kernel and one pass over HBM; decode is three kernels, of which
+// only the last touches more than the mask.
 //
-// A tile is 16384 consecutive elements (4 rounds of 4096) and is processed by one 256-thread
+// A tile is 32768 consecutive elements (4 rounds of 8192) and is processed by one 512-thread
 // workgroup; all of a tile's loads are issued before anything waits on them.  A lane owns 8
 // consecutive elements per 16-byte load (one mask byte); in each round a wavefront owns two
 // consecutive 512-element chunks.  Per-lane popcounts are scanned with DPP inside the wave,
-// through LDS across the four waves and the rounds, and with the decoupled look-back of
-// scan_state.hpp across tiles.  The tile is large because the ticket that hands tiles out is a
-// same-address device-scope atomic, which this chip serves at about one per 11 ns.  Changed values are staged in LDS so that the payload leaves (encode) or enters
-// (decode) HBM as 16-byte accesses aligned on the payload buffer, whatever the tile's offset.
+// through LDS across the eight waves and the rounds, and (encode) with the decoupled look-back
+// of scan_state.hpp across tiles.  The tile is large because every tile costs the machine one
+// same-address atomic (the ticket) and a handful of polls of its predecessors' scan words, and
+// both are served far more slowly than streaming traffic.  Changed values are staged in LDS so
+// that the payload leaves (encode) or enters (decode) HBM as 16-byte accesses aligned on the
+// payload buffer, whatever the tile's offset.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -19,53 +22,65 @@
 #include "wave.hpp"
 
 namespace bitsnap {
-#ifndef BITSNAP_SPARSE_ROUNDS
-#define BITSNAP_SPARSE_ROUNDS 4
-#endif
 
-constexpr int kBlock = 256;
+constexpr int kBlock = 512;
 constexpr int kWaves = kBlock / kWave;
 constexpr int kLaneElems = 8;                              // one 16-byte load of 16-bit elements
 constexpr int kChunkElems = kWave * kLaneElems;            // 512: what one wave covers with one load
 constexpr int kRoundChunks = 2 * kWaves;                   // a round: every wave takes two consecutive chunks
 constexpr int kRoundElems = kRoundChunks * kChunkElems;    // 4096
-constexpr int kRounds = BITSNAP_SPARSE_ROUNDS;             // rounds per tile, all loaded before the scan
+constexpr int kRounds = 4;                                 // rounds per tile, all loaded before the scan
 constexpr int kTileElems = kRounds * kRoundElems;          // one ticket, one status word, one look-back
 constexpr int kPhases = (kRounds % 2 == 0) ? 2 : 1;         // the payload passes through LDS in this many parts
 constexpr int kPhaseRounds = kRounds / kPhases;
 constexpr int kStageElems = kPhaseRounds * kRoundElems + 8; // one part + alignment shift
 
+// decode: the payload passes through LDS in kPhases parts
 struct TileShared {
     alignas(16) uint16_t stage[kStageElems];
+    uint32_t wave_total[kRounds][kWaves];
+};
+
+// encode: the whole tile's changed values are staged at their rank inside the tile, before the
+// tile's place in the payload is known
+struct EncodeShared {
+    alignas(16) uint16_t stage[kTileElems + 8];  // + the dword pair a realigning read may touch
     uint32_t wave_total[kRounds][kWaves];
     uint64_t excl;
     int64_t next_tile;
     int aborted;
 };
 
-// 8 elements of a 16-bit array starting at element e0 (e0 is a multiple of 8); elements at or
-// beyond n read as 0.
-__device__ __forceinline__ uint4 load8(const uint16_t *p, int64_t e0, int64_t n)
+// Device buffers are addressed as global memory explicitly: a generic (flat) access would also
+// count as an LDS operation in flight, and every wait for LDS would then wait for HBM.
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(1))) u32x4 global_u32x4;
+typedef __attribute__((address_space(1))) uint16_t global_u16;
+typedef __attribute__((address_space(1))) uint8_t global_u8;
+
+__device__ __forceinline__ uint4 load_global16(const void *p)
 {
-    if (e0 + kLaneElems <= n)
-        return *reinterpret_cast<const uint4 *>(p + e0);
-    uint32_t w[4] = {0, 0, 0, 0};
-    for (int t = 0; t < kLaneElems; ++t)
-        if (e0 + t < n)
-            w[t >> 1] |= (uint32_t)p[e0 + t] << ((t & 1) * 16);
-    return make_uint4(w[0], w[1], w[2], w[3]);
+    const u32x4 v = *(const global_u32x4 *)p;
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ void store_global16(void *p, uint4 v)
+{
+    u32x4 t;
+    t.x = v.x, t.y = v.y, t.z = v.z, t.w = v.w;
+    *(global_u32x4 *)p = t;
 }
 
+// 8 elements to p[e0 .. e0+8) (e0 a multiple of 8), clipped at n
 __device__ __forceinline__ void store8(uint16_t *p, int64_t e0, int64_t n, uint4 v)
 {
     if (e0 + kLaneElems <= n) {
-        *reinterpret_cast<uint4 *>(p + e0) = v;
+        store_global16(p + e0, v);
         return;
     }
     const uint32_t w[4] = {v.x, v.y, v.z, v.w};
     for (int t = 0; t < kLaneElems; ++t)
         if (e0 + t < n)
-            p[e0 + t] = (uint16_t)(w[t >> 1] >> ((t & 1) * 16));
+            ((global_u16 *)p)[e0 + t] = (uint16_t)(w[t >> 1] >> ((t & 1) * 16));
 }
 
 // bit t = 1 iff 16-bit element t of a differs from element t of b (Algorithm 1 steps 1-2)
@@ -98,7 +113,8 @@ __device__ __forceinline__ int64_t piece_chunk(int64_t tile, int r, int wave, in
 // Per-lane popcounts m[r][j] -> this lane's exclusive rank of each piece inside the tile, and the
 // rank at which each staging phase starts (the last entry is the tile total).  Contains one
 // __syncthreads.
-__device__ __forceinline__ void tile_ranks(TileShared &sh, const uint32_t (&cnt)[kRounds][2], int lane, int wave,
+template <class Shared>
+__device__ __forceinline__ void tile_ranks(Shared &sh, const uint32_t (&cnt)[kRounds][2], int lane, int wave,
                                            uint32_t (&rank)[kRounds][2], uint32_t (&phase_start)[kPhases + 1])
 {
     uint32_t ex[kRounds], t0[kRounds];
@@ -132,21 +148,17 @@ __device__ __forceinline__ void tile_ranks(TileShared &sh, const uint32_t (&cnt)
     phase_start[kPhases] = run;  // the tile total
 }
 
-// Wave 0: publish the tile's count, find the count of everything before it in the same tensor,
-// publish the inclusive value; the result reaches the other waves through sh.excl / sh.aborted.
-// `tile` and `first_tile` (the tensor's first tile) are in the launch-wide numbering.
-__device__ __forceinline__ void tile_prefix(TileShared &sh, ScanHeader *hdr, uint64_t *status, int64_t tile,
-                                            int64_t first_tile, uint32_t epoch, uint32_t spin_limit,
-                                            uint32_t tile_total, int lane)
+// Wave 0, after the tile's count has been published: the count of everything before the tile in
+// the same tensor; publishes the inclusive value; the result reaches the other waves through
+// sh.excl / sh.aborted.  `tile` and `first_tile` (the tensor's first tile) are in the launch-wide
+// numbering.
+__device__ __forceinline__ void tile_look_back(EncodeShared &sh, ScanHeader *hdr, uint64_t *status, int64_t tile,
+                                               int64_t first_tile, uint32_t epoch, uint32_t spin_limit,
+                                               uint32_t tile_total, int lane)
 {
     uint64_t excl = 0;
     bool aborted = false;
-    if (tile == first_tile) {
-        if (lane == 0)
-            publish(status, tile, make_status(kFlagInclusive, epoch, tile_total));
-    } else {
-        if (lane == 0)
-            publish(status, tile, make_status(kFlagAggregate, epoch, tile_total));
+    if (tile != first_tile) {
         excl = look_back(status, hdr, tile, first_tile, epoch, spin_limit, aborted);
         if (lane == 0)
             publish(status, tile, aborted ? make_status(kFlagAbort, epoch, 0)
@@ -158,30 +170,43 @@ __device__ __forceinline__ void tile_prefix(TileShared &sh, ScanHeader *hdr, uin
     }
 }
 
-// All of a tile's loads for the calling lane (issued back to back, nothing waits here).
+// All of a tile's loads for the calling lane (issued back to back, nothing waits here): a
+// wave-uniform tile base plus a 32-bit offset each.  A piece that starts at or beyond the end of
+// the tensor reads the tile's first piece instead, and a piece that straddles the end is read
+// whole: the buffer is 16-byte aligned, so an aligned 16-byte piece never leaves the page its
+// first element is in.  The caller ignores what lies at or beyond n (piece_valid_bits).
 __device__ __forceinline__ void load_tile16(const uint16_t *__restrict__ p, int64_t tile, int wave, int lane, int64_t n,
                                             uint4 (&v)[kRounds][2])
 {
+    const int64_t t0 = tile * kTileElems;
+    const uint16_t *__restrict__ tp = p + t0;  // wave-uniform
+    const uint32_t rem = n - t0 >= kTileElems ? (uint32_t)kTileElems : (uint32_t)(n - t0);
+    const uint32_t e0 = (uint32_t)(wave * (2 * kChunkElems) + lane * kLaneElems);
 #pragma unroll
     for (int r = 0; r < kRounds; ++r)
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
-            v[r][j] = load8(p, piece_chunk(tile, r, wave, j) * kChunkElems + lane * kLaneElems, n);
+        for (int j = 0; j < 2; ++j) {
+            const uint32_t e = e0 + (uint32_t)((r * kRoundChunks + j) * kChunkElems);
+            v[r][j] = load_global16(tp + (e < rem ? e : 0u));
+        }
 }
 
-// Hands the calling workgroup its next tile (all threads get the same value, as a scalar).
-// Contains two __syncthreads.  The ticket is taken when the workgroup is ready to start the tile,
-// never earlier: a tile that is claimed but not yet counted stalls every look-back that reaches it.
-__device__ __forceinline__ int64_t claim_tile(TileShared &sh, ScanHeader *hdr)
+// Which of the 8 elements of the lane's piece (r, j) exist, in a tile that holds `rem` elements.
+__device__ __forceinline__ uint32_t piece_valid_bits(int r, int j, int wave, int lane, uint32_t rem)
 {
-    __syncthreads();
-    if (threadIdx.x == 0)
-        sh.next_tile = (int64_t)atomicAdd(&hdr->ticket, 1u);
-    __syncthreads();
-    const uint64_t t = (uint64_t)sh.next_tile;
-    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)t), hi = __builtin_amdgcn_readfirstlane((uint32_t)(t >> 32));
-    return (int64_t)(((uint64_t)hi << 32) | lo);
+    const int32_t left = (int32_t)rem - (r * kRoundChunks + wave * 2 + j) * kChunkElems - lane * kLaneElems;
+    return left >= kLaneElems ? 0xFFu : left > 0 ? (1u << left) - 1u : 0u;
 }
+
+// A value every lane holds alike, moved to scalar registers.
+__device__ __forceinline__ uint64_t uniform64(uint64_t t)
+{
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)t), hi = __builtin_amdgcn_readfirstlane((uint32_t)(t >> 32));
+    return ((uint64_t)hi << 32) | lo;
+}
+
+// The value thread 0 left in sh.next_tile, as a scalar in every thread (call after a barrier).
+__device__ __forceinline__ int64_t claimed_tile(const EncodeShared &sh) { return (int64_t)uniform64((uint64_t)sh.next_tile); }
 
 // The tensor a launch-wide tile number belongs to.  Tickets only grow, so a workgroup walks the
 // item list forwards.  With kBatched == false there is one tensor, passed by value.
@@ -231,102 +256,161 @@ __device__ __forceinline__ void report_failures(int epilogue, const bitsnap_spar
     }
 }
 
+// Algorithm 1 step 5, second half: payload[excl + i] = stage[i], i < total.  Payload element
+// excl - shift is 16-byte aligned; piece q covers payload elements [dst0 + 8q, dst0 + 8q + 8), i.e.
+// stage elements from 8q - shift, read as five dwords and shifted by one element when shift is
+// odd.  The ragged ends of the tile's segment, and whatever would cross the payload capacity, go
+// out element by element.
+__device__ __forceinline__ void copy_out_stage(const EncodeShared &sh, uint16_t *__restrict__ payload, int64_t capacity,
+                                               uint64_t excl, uint32_t total, int tid)
+{
+    const uint32_t shift = (uint32_t)(excl & 7u);
+    const uint32_t first = shift, last = shift + total;
+    const int64_t dst0 = (int64_t)(excl - shift);
+    const uint32_t pieces = (last + 7u) >> 3;
+    const uint32_t odd_bytes = (shift & 1u) * 2u;
+    const uint32_t *stage32 = reinterpret_cast<const uint32_t *>(sh.stage);
+    uint64_t base_bits = (uint64_t)payload;
+    asm volatile("" : "+s"(base_bits));                              // stays in scalar registers
+    uint16_t *__restrict__ dst = (uint16_t *)base_bits + dst0;       // wave-uniform, 16-byte aligned
+    const int64_t room = capacity - dst0;                            // elements of dst that may be written
+    const uint32_t fits = room >= (int64_t)(kTileElems + 8) ? (uint32_t)(kTileElems + 8) : room > 0 ? (uint32_t)room : 0u;
+    for (uint32_t q = tid; q < pieces; q += kBlock) {
+        const uint32_t lo = q * 8u;
+        if (lo >= first && lo + 8u <= last && lo + 8u <= fits) {
+            const uint32_t w0 = (lo - shift) >> 1;
+            uint32_t w[5];
+#pragma unroll
+            for (int k = 0; k < 5; ++k)
+                w[k] = stage32[w0 + k];
+            uint4 v;
+            v.x = __builtin_amdgcn_alignbyte(w[1], w[0], odd_bytes);
+            v.y = __builtin_amdgcn_alignbyte(w[2], w[1], odd_bytes);
+            v.z = __builtin_amdgcn_alignbyte(w[3], w[2], odd_bytes);
+            v.w = __builtin_amdgcn_alignbyte(w[4], w[3], odd_bytes);
+            store_global16(dst + lo, v);
+        } else {
+            for (uint32_t t = 0; t < 8u; ++t) {
+                const uint32_t i = lo + t;
+                if (i >= first && i < last && i < fits)
+                    ((global_u16 *)dst)[i] = sh.stage[i - shift];
+            }
+        }
+    }
+}
+
+// Order of work in one turn of the loop:
+//   the tile's loads are issued -> the previous tile's staged values go out as 16-byte stores
+//   aligned on the payload buffer, realigned on the way out of LDS -> mask bytes and counts ->
+//   ranks inside the tile -> the tile's count is published -> changed values are scattered into
+//   LDS at their rank inside the tile (this needs nothing from other tiles, so it runs while the
+//   preceding tiles are still publishing) -> look-back (wave 0) -> ticket for the next tile.
+// So HBM reads of a tile overlap the copy-out of the tile before it.  The ticket is requested
+// only after the look-back: between the ticket and the published count of a tile then lies one
+// load latency and nothing that waits on other workgroups.  (With the ticket requested earlier,
+// to hide its round trip, a slow look-back delays the count of the workgroup's next tile, which
+// slows the look-backs of the tiles after that one, and so on: measured at half the throughput.)
+// launch_bounds: 4 waves per SIMD, i.e. two 512-thread workgroups per CU (128 registers per lane).
 template <bool kBatched>
-__global__ __launch_bounds__(kBlock) void encode_sparse_kernel(bitsnap_sparse_item single,
+__global__ __launch_bounds__(kBlock, 4) void encode_sparse_kernel(bitsnap_sparse_item single,
                                                                const bitsnap_sparse_item *__restrict__ items,
                                                                int64_t count, ScanHeader *hdr, uint64_t *status,
                                                                int64_t status_cap, int64_t num_tiles, uint32_t spin_limit)
 {
-    __shared__ TileShared sh;
-    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
+    __shared__ EncodeShared sh;
+    const int tid0 = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid0 >> 6);
     const uint32_t epoch = hdr->epoch;
     bool aborted = false;
     ItemCursor<kBatched> cursor(single, items, count);
 
-    for (int64_t gtile = claim_tile(sh, hdr); gtile < num_tiles; gtile = claim_tile(sh, hdr)) {
-        cursor.seek(gtile);
-        const bitsnap_sparse_item &it = cursor.it;
-        const uint16_t *__restrict__ cur = (const uint16_t *)it.src, *__restrict__ base = (const uint16_t *)it.base;
-        uint8_t *__restrict__ mask = it.mask;
-        uint16_t *__restrict__ payload = (uint16_t *)it.payload;
-        const int64_t n = it.n, capacity = it.capacity, tile = gtile - it.first_tile;
-        const int64_t mask_bytes = (((n + 7) >> 3) + 15) & ~(int64_t)15;
-
-        uint4 c[kRounds][2];
-        uint32_t m[kRounds][2], cnt[kRounds][2], rank[kRounds][2];
-        {
-            uint4 b[kRounds][2];
-            load_tile16(cur, tile, wave, lane, n, c);
-            load_tile16(base, tile, wave, lane, n, b);
-#pragma unroll
-            for (int r = 0; r < kRounds; ++r)
-#pragma unroll
-                for (int j = 0; j < 2; ++j) {
-                    m[r][j] = diff_bits(c[r][j], b[r][j]);
-                    cnt[r][j] = __popc(m[r][j]);
-                    // Algorithm 1 steps 3-4: one mask byte per lane; bytes past ceil(n/8) come out as 0
-                    const int64_t mb = piece_chunk(tile, r, wave, j) * kWave + lane;
-                    if (mb < mask_bytes)
-                        mask[mb] = (uint8_t)m[r][j];
-                }
+    if (tid0 == 0)
+        sh.next_tile = (int64_t)atomicAdd(&hdr->ticket, 1u);
+    __syncthreads();
+    // the previous tile of this workgroup: staged in LDS, still to be copied out
+    bool staged = false;
+    uint16_t *__restrict__ staged_payload = nullptr;
+    int64_t staged_capacity = 0;
+    uint64_t staged_excl = 0;
+    uint32_t staged_total = 0;
+    for (;;) {
+        // The thread's index is made opaque once per turn: otherwise every per-piece offset derived
+        // from it counts as loop-invariant and is kept in (or spilled from) a register of its own.
+        int tid = tid0;
+        asm volatile("" : "+v"(tid));
+        const int lane = tid & (kWave - 1);
+        const int64_t gtile = claimed_tile(sh);
+        const bool valid = gtile < num_tiles;
+        uint4 c[kRounds][2], b[kRounds][2];
+        if (valid) {  // this tile's loads fly while the previous tile's values leave
+            cursor.seek(gtile);
+            load_tile16((const uint16_t *)cursor.it.src, gtile - cursor.it.first_tile, wave, lane, cursor.it.n, c);
+            load_tile16((const uint16_t *)cursor.it.base, gtile - cursor.it.first_tile, wave, lane, cursor.it.n, b);
         }
+        if (staged)
+            copy_out_stage(sh, staged_payload, staged_capacity, staged_excl, staged_total, tid);
+        if (!valid)
+            break;
+        __syncthreads();  // the stage has been read
+
+        const bitsnap_sparse_item &it = cursor.it;
+        const int64_t n = it.n, tile = gtile - it.first_tile;
+        const int64_t mask_bytes = (((n + 7) >> 3) + 15) & ~(int64_t)15;
+        uint8_t *__restrict__ wave_mask = it.mask + tile * (kTileElems / 8) + wave * (2 * kWave);
+        const bool full_tile = (tile + 1) * kTileElems <= n;
+        const int32_t wave_mask_bytes =
+            (full_tile ? (int32_t)(kTileElems / 8) : (int32_t)(mask_bytes - tile * (kTileElems / 8))) - wave * (2 * kWave);
+        const uint32_t tile_elems = full_tile ? (uint32_t)kTileElems : (uint32_t)(n - tile * kTileElems);
+
+        uint32_t m[kRounds][2], cnt[kRounds][2], rank[kRounds][2];
+#pragma unroll
+        for (int r = 0; r < kRounds; ++r)
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                m[r][j] = diff_bits(c[r][j], b[r][j]) & piece_valid_bits(r, j, wave, lane, tile_elems);
+                cnt[r][j] = __popc(m[r][j]);
+                // Algorithm 1 steps 3-4: one mask byte per lane; bytes past ceil(n/8) come out as 0
+                const int32_t mb = (r * kRoundChunks + j) * kWave;  // + lane, in this wave's part of the tile's mask
+                if (mb + lane < wave_mask_bytes)
+                    ((global_u8 *)(wave_mask + mb))[(uint32_t)lane] = (uint8_t)m[r][j];
+            }
         uint32_t phase_start[kPhases + 1];
         tile_ranks(sh, cnt, lane, wave, rank, phase_start);  // barrier
         const uint32_t total = phase_start[kPhases];
+        if (tid == 0)
+            publish(status, gtile, make_status(tile == 0 ? kFlagInclusive : kFlagAggregate, epoch, total));
+
+        // Algorithm 1 step 5, first half: changed values in index order, at their rank inside the tile
+#pragma unroll
+        for (int r = 0; r < kRounds; ++r)
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                uint32_t p = rank[r][j];
+#pragma unroll
+                for (int t = 0; t < kLaneElems; ++t)
+                    if ((m[r][j] >> t) & 1u)
+                        sh.stage[p++] = elem16(c[r][j], t);
+            }
+        __syncthreads();  // the stage is complete
         if (wave == 0)
-            tile_prefix(sh, hdr, status, gtile, it.first_tile, epoch, spin_limit, total, lane);
-        __syncthreads();
-        const uint64_t excl = sh.excl;
+            tile_look_back(sh, hdr, status, gtile, it.first_tile, epoch, spin_limit, total, lane);
+        __syncthreads();  // sh.excl / sh.aborted are set
         if (sh.aborted) {
             aborted = true;
             break;
         }
+        staged = true;
+        staged_payload = (uint16_t *)it.payload;
+        staged_capacity = it.capacity;
+        staged_excl = uniform64(sh.excl);
+        staged_total = __builtin_amdgcn_readfirstlane(total);
         if (tid == 0) {
             if (it.tile_offsets)
-                it.tile_offsets[tile] = (uint32_t)excl;
+                it.tile_offsets[tile] = (uint32_t)staged_excl;
             if ((tile + 1) * kTileElems >= n)  // the tensor's last tile knows the total
-                *it.n_changed = excl + total;
+                *it.n_changed = staged_excl + total;
+            sh.next_tile = (int64_t)atomicAdd(&hdr->ticket, 1u);
         }
-
-        // Algorithm 1 step 5: changed values, in index order, in kPhases parts (rounds are
-        // consecutive in rank, so a part is a contiguous piece of the payload).  Each part is
-        // staged in LDS at (its offset mod 8), so that 16-byte pieces of LDS line up with 16-byte
-        // pieces of the payload buffer; the ragged ends of a part go out element by element.
-#pragma unroll
-        for (int ph = 0; ph < kPhases; ++ph) {
-            const uint64_t part_off = excl + phase_start[ph];
-            const uint32_t part_len = phase_start[ph + 1] - phase_start[ph];
-            const uint32_t shift = (uint32_t)(part_off & 7u);
-            if (ph > 0)
-                __syncthreads();  // the previous part has left the stage
-#pragma unroll
-            for (int r = ph * kPhaseRounds; r < (ph + 1) * kPhaseRounds; ++r)
-#pragma unroll
-                for (int j = 0; j < 2; ++j) {
-                    uint32_t p = shift + rank[r][j] - phase_start[ph];
-#pragma unroll
-                    for (int t = 0; t < kLaneElems; ++t)
-                        if ((m[r][j] >> t) & 1u)
-                            sh.stage[p++] = elem16(c[r][j], t);
-                }
-            __syncthreads();
-            const uint32_t first = shift, last = shift + part_len;  // valid staged range [first, last)
-            const int64_t dst0 = (int64_t)(part_off - shift);        // payload element of stage[0], multiple of 8
-            const uint32_t pieces = (last + 7u) >> 3;
-            for (uint32_t q = tid; q < pieces; q += kBlock) {
-                const uint32_t lo = q * 8u;
-                const int64_t d = dst0 + lo;
-                if (lo >= first && lo + 8u <= last && d + 8 <= capacity) {
-                    *reinterpret_cast<uint4 *>(payload + d) = *reinterpret_cast<const uint4 *>(&sh.stage[lo]);
-                } else {
-                    for (uint32_t t = 0; t < 8u; ++t) {
-                        const uint32_t i = lo + t;
-                        if (i >= first && i < last && d + t < capacity)
-                            payload[d + t] = sh.stage[i];
-                    }
-                }
-            }
-        }
+        __syncthreads();  // the next tile is known
     }
     const int epilogue = scan_epilogue(hdr, status, status_cap, epoch, aborted);
     report_failures(epilogue, single, items, count, kBatched, num_tiles);
@@ -342,7 +426,7 @@ __device__ __forceinline__ void load_tile_mask(const uint8_t *__restrict__ mask,
         for (int j = 0; j < 2; ++j) {
             const int64_t ch = piece_chunk(tile, r, wave, j);
             const int64_t mb = ch * kWave + lane, e = ch * kChunkElems + lane * kLaneElems;
-            uint32_t bits = (mb < mask_bytes) ? mask[mb] : 0u;
+            uint32_t bits = (mb < mask_bytes) ? ((const global_u8 *)mask)[mb] : 0u;
             if (e + kLaneElems > n)
                 bits &= (e < n) ? ((1u << (uint32_t)(n - e)) - 1u) : 0u;
             m[r][j] = bits;
@@ -497,12 +581,12 @@ __global__ __launch_bounds__(kBlock) void decode_merge_kernel(bitsnap_sparse_ite
             const int64_t s = src0 + lo;
             uint4 pv = make_uint4(0, 0, 0, 0);
             if (s + 8 <= payload_elems) {
-                pv = *reinterpret_cast<const uint4 *>(payload + s);
+                pv = load_global16(payload + s);
             } else {
                 uint32_t w[4] = {0, 0, 0, 0};
                 for (int t = 0; t < 8; ++t)
                     if (s + t < payload_elems)
-                        w[t >> 1] |= (uint32_t)payload[s + t] << ((t & 1) * 16);
+                        w[t >> 1] |= (uint32_t)((const global_u16 *)payload)[s + t] << ((t & 1) * 16);
                 pv = make_uint4(w[0], w[1], w[2], w[3]);
             }
             *reinterpret_cast<uint4 *>(&sh.stage[lo]) = pv;
@@ -531,19 +615,20 @@ __global__ __launch_bounds__(kBlock) void decode_merge_kernel(bitsnap_sparse_ite
 // tiles' payload offsets (8 bytes each, in the same place) followed by their counts (4 bytes each).
 // A raw offset is below 2^40, so as a scan word its flag bits read "not written": a decode never
 // confuses a later encode.
-constexpr size_t kWorkspaceBytesPerTile = 16;
+constexpr size_t kWorkspaceBytesPerTile = 8 * kStatusStride;
+static_assert(kWorkspaceBytesPerTile >= 12, "decode keeps 8 + 4 bytes per tile");
 
 static uint32_t g_spin_limit = kDefaultSpinLimit;
 
 // Persistent grid of the scan kernel.  Tiles are handed out by ticket, so nothing depends on every
 // workgroup being resident: a workgroup that only starts after others have finished finds no tile
-// left and exits.  Four per CU measured best (the occupancy query is conservative on this chip).
+// left and exits.  Registers and LDS allow two workgroups per CU.
 static int sparse_grid(const void *kernel, int64_t num_tiles)
 {
     const DeviceInfo &di = device_info();
     int per_cu = occupancy_blocks_per_cu(kernel, kBlock);
-    if (per_cu < 4)
-        per_cu = 4;
+    if (per_cu < 2)
+        per_cu = 2;
     int64_t resident = (int64_t)di.cu_count * per_cu;
     int64_t g = num_tiles < resident ? num_tiles : resident;
     return (int)(g < 1 ? 1 : g);

@@ -33,7 +33,7 @@ def test_sparse_size_helpers():
     for n in [0, 1, 8, 9, 127, 128, 129, 4096, 10**6 + 3]:
         mb = B.sparse_mask_bytes(n)
         assert mb % 16 == 0 and mb >= (n + 7) // 8 and mb < (n + 7) // 8 + 16
-        assert B.sparse_workspace_bytes(n) >= 256 + 8 * ((n + T - 1) // T)
+        assert B.sparse_workspace_bytes(n) >= 256 + 16 * ((n + T - 1) // T)
     assert B.sparse_mask_bytes(0) == 0
 
 
