@@ -49,7 +49,17 @@ __device__ __forceinline__ void wave_lds_sync()
 __device__ __forceinline__ float comp(const float4 &v, int j) { return j == 0 ? v.x : j == 1 ? v.y : j == 2 ? v.z : v.w; }
 
 typedef float float4v __attribute__((ext_vector_type(4)));
+typedef float float2v __attribute__((ext_vector_type(2)));
 #define BITSNAP_LDS __attribute__((address_space(3)))
+// Device buffers are addressed as global memory explicitly.  Through a generic pointer every
+// access is a flat instruction, which also counts as an LDS operation in flight, so each wait
+// for an LDS read would wait for the HBM traffic issued before it as well.
+#define BITSNAP_GLOBAL __attribute__((address_space(1)))
+template <typename T>
+__device__ __forceinline__ BITSNAP_GLOBAL T *global_ptr(T *p)
+{
+    return (BITSNAP_GLOBAL T *)p;
+}
 
 // Byte address of an LDS object, and LDS accesses by byte address.  The label search and the
 // min/max table below carry addresses, not indices, so that one shift-add per step does both the
@@ -58,7 +68,6 @@ __device__ __forceinline__ uint32_t lds_addr(const void *p) { return (uint32_t)(
 __device__ __forceinline__ float lds_read_f32(uint32_t a) { return *(const BITSNAP_LDS float *)(uintptr_t)a; }
 __device__ __forceinline__ float2 lds_read_f32x2(uint32_t a)
 {
-    typedef float float2v __attribute__((ext_vector_type(2)));
     const float2v t = *(const BITSNAP_LDS float2v *)(uintptr_t)a;
     return make_float2(t.x, t.y);
 }
@@ -66,7 +75,7 @@ __device__ __forceinline__ float2 lds_read_f32x2(uint32_t a)
 // streaming 16-byte load: the data is used once, keep it out of the way of everything else
 __device__ __forceinline__ float4 load_stream(const float *p)
 {
-    const float4v t = __builtin_nontemporal_load(reinterpret_cast<const float4v *>(p));
+    const float4v t = __builtin_nontemporal_load((const BITSNAP_GLOBAL float4v *)p);
     return make_float4(t.x, t.y, t.z, t.w);
 }
 
@@ -85,10 +94,10 @@ __device__ __forceinline__ void quantize_group(const float *__restrict__ x, int6
         if (kFull) {
             v[k] = load_stream(x + lo + off);
         } else {
-            v[k].x = off + 0 < len ? x[lo + off + 0] : 0.0f;
-            v[k].y = off + 1 < len ? x[lo + off + 1] : 0.0f;
-            v[k].z = off + 2 < len ? x[lo + off + 2] : 0.0f;
-            v[k].w = off + 3 < len ? x[lo + off + 3] : 0.0f;
+            v[k].x = off + 0 < len ? global_ptr(x)[lo + off + 0] : 0.0f;
+            v[k].y = off + 1 < len ? global_ptr(x)[lo + off + 1] : 0.0f;
+            v[k].z = off + 2 < len ? global_ptr(x)[lo + off + 2] : 0.0f;
+            v[k].w = off + 3 < len ? global_ptr(x)[lo + off + 3] : 0.0f;
         }
     }
     // running min/max table: this lane's column
@@ -125,8 +134,8 @@ __device__ __forceinline__ void quantize_group(const float *__restrict__ x, int6
     float mu = (float)mean;
     float sigma = (float)sqrt(q / (double)len);
     if (fit_in) {
-        mu = fit_in[2 * g];
-        sigma = fit_in[2 * g + 1];
+        mu = global_ptr(fit_in)[2 * g];
+        sigma = global_ptr(fit_in)[2 * g + 1];
     }
     if (status && lane == 0 && !(isfinite(mu) && isfinite(sigma)))
         atomicOr(status, 1u);
@@ -139,11 +148,11 @@ __device__ __forceinline__ void quantize_group(const float *__restrict__ x, int6
         const int tz = __ffs(lane) - 1;
         ws.tree[(1 << (3 - tz)) + (lane >> (tz + 1))] = edge;
         if (fit_out && lane < m)
-            fit_out[g * (m + 1) + 1 + lane] = edge;
+            global_ptr(fit_out)[g * (m + 1) + 1 + lane] = edge;
     }
     if (fit_out && lane == 0) {
-        fit_out[g * (m + 1) + 0] = mu;
-        fit_out[g * (m + 1) + 1] = sigma;
+        global_ptr(fit_out)[g * (m + 1) + 0] = mu;
+        global_ptr(fit_out)[g * (m + 1) + 1] = sigma;
     }
     const float root = read_lane(edge, 8);  // the middle edge, e_8: first step of every search
     wave_lds_sync();
@@ -208,9 +217,9 @@ __device__ __forceinline__ void quantize_group(const float *__restrict__ x, int6
             packed[k >> 1] |= l4 << (16 * (k & 1));
             // labels: two per byte, even element in the low nibble
             const int off = k * 256 + lane * 4;
-            uint8_t *lp = labels + ((lo + off) >> 1);
+            BITSNAP_GLOBAL uint8_t *lp = global_ptr(labels) + ((lo + off) >> 1);
             if (kFull || off + 3 < len) {
-                *reinterpret_cast<uint16_t *>(lp) = (uint16_t)l4;
+                *(BITSNAP_GLOBAL uint16_t *)lp = (uint16_t)l4;
             } else {
                 if (off < len)
                     lp[0] = (uint8_t)l4;
@@ -248,7 +257,7 @@ __device__ __forceinline__ void quantize_group(const float *__restrict__ x, int6
             }
             ws.coder[lane] = make_float2(b, inv);
             if (lane < m)
-                *reinterpret_cast<float2 *>(params + (g * m + lane) * 2) = make_float2(S, b);
+                *(BITSNAP_GLOBAL float2v *)(global_ptr(params) + (g * m + lane) * 2) = float2v{S, b};
         }
     }
     wave_lds_sync();
@@ -277,9 +286,9 @@ __device__ __forceinline__ void quantize_group(const float *__restrict__ x, int6
                 c4 = __builtin_amdgcn_cvt_pk_u8_f32(y, j, c4);
             }
             const int off = k * 256 + lane * 4;
-            uint8_t *cp = codes + lo + off;
+            BITSNAP_GLOBAL uint8_t *cp = global_ptr(codes) + lo + off;
             if (kFull || off + 3 < len) {
-                *reinterpret_cast<uint32_t *>(cp) = c4;
+                *(BITSNAP_GLOBAL uint32_t *)cp = c4;
             } else {
                 for (int j = 0; j < 4; ++j)
                     if (off + j < len)
@@ -319,7 +328,10 @@ __device__ __forceinline__ void dequantize_group(const uint8_t *__restrict__ cod
     if (lane < kMaxClusters) {
         float2 sb = make_float2(0.0f, 0.0f);
         if (lane < m)
-            sb = *reinterpret_cast<const float2 *>(params + (g * m + lane) * 2);
+        {
+            const float2v t = *(const BITSNAP_GLOBAL float2v *)(global_ptr(params) + (g * m + lane) * 2);
+            sb = make_float2(t.x, t.y);
+        }
         coder[lane] = make_float2(__fdiv_rn(sb.x, 255.0f), sb.y);  // (S/255, b)
     }
     wave_lds_sync();
@@ -331,13 +343,13 @@ __device__ __forceinline__ void dequantize_group(const uint8_t *__restrict__ cod
         const bool full = off + 3 < len;
         uint32_t c4 = 0, l4 = 0;
         if (full) {
-            c4 = *reinterpret_cast<const uint32_t *>(codes + lo + off);
-            l4 = *reinterpret_cast<const uint16_t *>(labels + ((lo + off) >> 1));
+            c4 = *(const BITSNAP_GLOBAL uint32_t *)(global_ptr(codes) + lo + off);
+            l4 = *(const BITSNAP_GLOBAL uint16_t *)(global_ptr(labels) + ((lo + off) >> 1));
         } else {
             for (int j = 0; j < 4; ++j)
                 if (off + j < len) {
-                    c4 |= (uint32_t)codes[lo + off + j] << (8 * j);
-                    l4 |= (uint32_t)((labels[(lo + off + j) >> 1] >> (4 * (j & 1))) & 15u) << (4 * j);
+                    c4 |= (uint32_t)global_ptr(codes)[lo + off + j] << (8 * j);
+                    l4 |= (uint32_t)((global_ptr(labels)[(lo + off + j) >> 1] >> (4 * (j & 1))) & 15u) << (4 * j);
                 }
         }
         float r[4];
@@ -347,11 +359,11 @@ __device__ __forceinline__ void dequantize_group(const uint8_t *__restrict__ cod
             r[j] = __fadd_rn(__fmul_rn((float)((c4 >> (8 * j)) & 255u), sb.x), sb.y);
         }
         if (full) {
-            *reinterpret_cast<float4 *>(out + lo + off) = make_float4(r[0], r[1], r[2], r[3]);
+            *(BITSNAP_GLOBAL float4v *)(global_ptr(out) + lo + off) = float4v{r[0], r[1], r[2], r[3]};
         } else {
             for (int j = 0; j < 4; ++j)
                 if (off + j < len)
-                    out[lo + off + j] = r[j];
+                    global_ptr(out)[lo + off + j] = r[j];
         }
     }
     wave_lds_sync();  // the coder table may be rewritten by this wave's next group
