@@ -14,6 +14,8 @@
 #include <math.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 #include "../../include/bitsnap.h"
 #include "cluster_general.hpp"
 #include "host_util.hpp"
@@ -31,11 +33,21 @@ __constant__ double kZDev[17][16] = {
 constexpr int kQBlock = 256;
 constexpr int kQWaves = kQBlock / kWave;
 constexpr int kMaxClusters = 16;
+// Label search by bins.  bin(x) = min(63, sat_u8(rne(x*r + c))) with r = 16/sigma and
+// c = 32 - mu*r is a non-decreasing function of x whatever the rounding (r > 0), so
+//   bin(x) < bin(e)  =>  x < e      and      bin(x) > bin(e)  =>  x > e
+// for every edge e, and the label of x, #{k : e_k <= x}, is the number of edges in lower bins
+// plus one comparison with the edge in x's own bin - provided no bin holds two edges, which is
+// checked per group on the actual edges; a group that fails the check takes the tree search.
+// 16 bins per sigma put the 15 normal quantiles of m = 16 at least 2.5 bins apart.
+constexpr int kBins = 64;
+constexpr float kBinsPerSigma = 16.0f, kBinOffset = 32.0f;
 
 struct alignas(16) WaveShared {
     float tab[2 * kMaxClusters][kWave];  // rows 0..15: running min per cluster, rows 16..31: running max
     float tree[kMaxClusters];            // node i of the edge search tree (node 1 = root), [0] unused
     float2 coder[kMaxClusters];          // (b, 255/S) for quantize, (S/255, b) for dequantize
+    float2 bins[kBins];                  // label search by bins: (the edge inside the bin or +inf, edges below the bin)
 };
 
 // Orders this wave's LDS writes before its later LDS reads (lanes exchange data through LDS).
@@ -70,6 +82,12 @@ __device__ __forceinline__ float2 lds_read_f32x2(uint32_t a)
 {
     const float2v t = *(const BITSNAP_LDS float2v *)(uintptr_t)a;
     return make_float2(t.x, t.y);
+}
+
+__device__ __forceinline__ uint32_t bin_of(float x, float r, float c)
+{
+    const uint32_t i = __builtin_amdgcn_cvt_pk_u8_f32(__fmaf_rn(x, r, c), 0, 0u);
+    return i < (uint32_t)(kBins - 1) ? i : (uint32_t)(kBins - 1);
 }
 
 // streaming 16-byte load: the data is used once, keep it out of the way of everything else
@@ -155,79 +173,122 @@ __device__ __forceinline__ void quantize_group(const float *__restrict__ x, int6
         global_ptr(fit_out)[g * (m + 1) + 1] = sigma;
     }
     const float root = read_lane(edge, 8);  // the middle edge, e_8: first step of every search
+    const float bin_r = __fdiv_rn(kBinsPerSigma, sigma);
+    const float bin_c = __fsub_rn(kBinOffset, __fmul_rn(mu, bin_r));
+    ws.bins[lane] = make_float2(INFINITY, 0.0f);
+    wave_lds_sync();
+    if (lane >= 1 && lane < m)
+        ws.bins[bin_of(edge, bin_r, bin_c)].x = edge;
+    wave_lds_sync();
+    bool by_bins;
+    {
+        const uint64_t occupied = __ballot(ws.bins[lane].x < INFINITY);
+        by_bins = (int)__popcll(occupied) == m - 1 && bin_r > 0.0f;  // every edge alone in its bin
+        const uint32_t below = __builtin_amdgcn_mbcnt_hi((uint32_t)(occupied >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)occupied, 0u));
+        ws.bins[lane].y = __uint_as_float(below);
+    }
     wave_lds_sync();
 
     // ---- steps 3-4: labels, per-cluster min and max.
-    // Search state a = byte address of tree node `node`: a = T + 4*node, so the step
+    // Tree search: the state a = byte address of tree node `node`: a = T + 4*node, so the step
     // node' = 2*node + c is a' = 2a + (c ? 4 - T : -T).  The last step also subtracts T + 64,
     // which leaves 4*label.
     const uint32_t T = lds_addr(&ws.tree[0]);
     const uint32_t a_lo = T + 8u, a_hi = T + 12u;                  // nodes 2 and 3
     const uint32_t k0 = 0u - T, k1 = 4u - T;
     const uint32_t k0_last = 0u - 2u * T - 64u, k1_last = 4u - 2u * T - 64u;
+    const uint32_t bins0 = lds_addr(&ws.bins[0]);
     const uint32_t tab0 = lds_addr(&ws.tab[0][lane]);              // + 256*label: this lane's min of the cluster
-    // The searches run in batches of kBatch float4 (4*kBatch elements): all LDS reads of one tree
-    // level are issued together and waited for once.  Left to itself the compiler's scheduler
+    // The searches run in batches of kBatch float4 (4*kBatch elements): all LDS reads of one step
+    // are issued together and waited for once.  Left to itself the compiler's scheduler
     // finishes one element's read-compare-step chain before starting the next, which exposes
-    // the LDS latency once per element and level; the scheduling barriers keep the batches intact.
+    // the LDS latency once per element and step; the scheduling barriers keep the batches intact.
     constexpr int kBatch = K >= 2 ? 2 : 1;
     constexpr int kB = 4 * kBatch;
     uint32_t packed[(K + 1) / 2];
 #pragma unroll
     for (int i = 0; i < (K + 1) / 2; ++i)
         packed[i] = 0;
+    auto label_pass = [&](auto by_bins_c) {
+        constexpr bool kByBins = decltype(by_bins_c)::value;
 #pragma unroll
-    for (int kb = 0; kb < K; kb += kBatch) {
-        float xs[kB];
-        uint32_t a[kB];
-#pragma unroll
-        for (int i = 0; i < kB; ++i) {
-            xs[i] = comp(v[kb + i / 4], i % 4);
-            a[i] = xs[i] >= root ? a_hi : a_lo;
-        }
-#pragma unroll
-        for (int st = 0; st < 3; ++st) {
-            float e[kB];
-            __builtin_amdgcn_sched_barrier(0);
+        for (int kb = 0; kb < K; kb += kBatch) {
+            float xs[kB];
+            uint32_t label[kB];
 #pragma unroll
             for (int i = 0; i < kB; ++i)
-                e[i] = lds_read_f32(a[i]);
+                xs[i] = comp(v[kb + i / 4], i % 4);
+            if (kByBins) {
+                uint32_t a[kB];
+                float2 cb[kB];
+#pragma unroll
+                for (int i = 0; i < kB; ++i)
+                    a[i] = bins0 + (bin_of(xs[i], bin_r, bin_c) << 3);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int i = 0; i < kB; ++i)
+                    cb[i] = lds_read_f32x2(a[i]);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int i = 0; i < kB; ++i)
+                    label[i] = __float_as_uint(cb[i].y) + (xs[i] >= cb[i].x ? 1u : 0u);
+            } else {
+                uint32_t a[kB];
+#pragma unroll
+                for (int i = 0; i < kB; ++i)
+                    a[i] = xs[i] >= root ? a_hi : a_lo;
+#pragma unroll
+                for (int st = 0; st < 3; ++st) {
+                    float e[kB];
+                    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                    for (int i = 0; i < kB; ++i)
+                        e[i] = lds_read_f32(a[i]);
+                    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                    for (int i = 0; i < kB; ++i)
+                        a[i] = (a[i] << 1) + (xs[i] >= e[i] ? (st == 2 ? k1_last : k1) : (st == 2 ? k0_last : k0));
+                }
+#pragma unroll
+                for (int i = 0; i < kB; ++i)
+                    label[i] = a[i] >> 2;
+            }
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int i = 0; i < kB; ++i)
-                a[i] = (a[i] << 1) + (xs[i] >= e[i] ? (st == 2 ? k1_last : k1) : (st == 2 ? k0_last : k0));
-        }
-        __builtin_amdgcn_sched_barrier(0);
+            for (int b = 0; b < kBatch; ++b) {
+                const int k = kb + b;
+                uint32_t l4 = 0;
 #pragma unroll
-        for (int b = 0; b < kBatch; ++b) {
-            const int k = kb + b;
-            uint32_t l4 = 0;
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const uint32_t al = a[4 * b + j];  // == 4*label
-                if (kFull || k * 256 + lane * 4 + j < len) {
-                    // LDS float min/max without return value: no round trip, no conflict (private column)
-                    float *pmin = (float *)(BITSNAP_LDS float *)(uintptr_t)(tab0 + (al << 6));
-                    __hip_atomic_fetch_min(pmin, xs[4 * b + j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
-                    __hip_atomic_fetch_max(pmin + kMaxClusters * kWave, xs[4 * b + j], __ATOMIC_RELAXED,
-                                           __HIP_MEMORY_SCOPE_WAVEFRONT);
-                    l4 |= j == 0 ? (al >> 2) : (al << (4 * j - 2));
+                for (int j = 0; j < 4; ++j) {
+                    const uint32_t l = label[4 * b + j];
+                    if (kFull || k * 256 + lane * 4 + j < len) {
+                        // LDS float min/max without return value: no round trip, no conflict (private column)
+                        float *pmin = (float *)(BITSNAP_LDS float *)(uintptr_t)(tab0 + (l << 8));
+                        __hip_atomic_fetch_min(pmin, xs[4 * b + j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+                        __hip_atomic_fetch_max(pmin + kMaxClusters * kWave, xs[4 * b + j], __ATOMIC_RELAXED,
+                                               __HIP_MEMORY_SCOPE_WAVEFRONT);
+                        l4 |= l << (4 * j);
+                    }
+                }
+                packed[k >> 1] |= l4 << (16 * (k & 1));
+                // labels: two per byte, even element in the low nibble
+                const int off = k * 256 + lane * 4;
+                BITSNAP_GLOBAL uint8_t *lp = global_ptr(labels) + ((lo + off) >> 1);
+                if (kFull || off + 3 < len) {
+                    *(BITSNAP_GLOBAL uint16_t *)lp = (uint16_t)l4;
+                } else {
+                    if (off < len)
+                        lp[0] = (uint8_t)l4;
+                    if (off + 2 < len)
+                        lp[1] = (uint8_t)(l4 >> 8);
                 }
             }
-            packed[k >> 1] |= l4 << (16 * (k & 1));
-            // labels: two per byte, even element in the low nibble
-            const int off = k * 256 + lane * 4;
-            BITSNAP_GLOBAL uint8_t *lp = global_ptr(labels) + ((lo + off) >> 1);
-            if (kFull || off + 3 < len) {
-                *(BITSNAP_GLOBAL uint16_t *)lp = (uint16_t)l4;
-            } else {
-                if (off < len)
-                    lp[0] = (uint8_t)l4;
-                if (off + 2 < len)
-                    lp[1] = (uint8_t)(l4 >> 8);
-            }
         }
-    }
+    };
+    if (by_bins)
+        label_pass(std::true_type{});
+    else
+        label_pass(std::false_type{});
     wave_lds_sync();
 
     // ---- reduce the table over its 64 columns: lane handles row (lane & 31), half (lane >> 5)

@@ -151,6 +151,23 @@ def test_exact_ties_round_to_the_even_code(scale):
     _compare(big, 4096, 16)
 
 
+@pytest.mark.parametrize("m", [16, 7, 2])
+def test_mean_far_from_zero_both_label_searches(m):
+    """Groups whose mean is 1e2 ... 1e8 deviations away from zero.  The edges mu + sigma*z_k then lose
+    precision until neighbouring edges coincide; the kernel's quick label search (one comparison per
+    element) gives way to its tree search group by group.  Every label must equal the oracle's either way."""
+    announce("cluster mean far from zero", m)
+    rng = np.random.default_rng(77 + m)
+    parts = []
+    for ratio in (1e2, 1e3, 1e4, 1e5, 3e5, 1e6, 3e6, 1e7, 1e8):
+        for sign in (1.0, -1.0):
+            sigma = 10.0 ** rng.integers(-4, 2)
+            parts.append((sign * ratio * sigma + rng.standard_normal(4096) * sigma).astype(np.float32))
+    x = np.concatenate(parts)
+    diff, groups = _compare(x, 4096, m)
+    assert groups == len(parts)
+
+
 def test_non_finite_input_sets_status_and_stays_in_bounds():
     announce("cluster non-finite")
     x = np.random.default_rng(1).standard_normal(3 * 4096).astype(np.float32)
