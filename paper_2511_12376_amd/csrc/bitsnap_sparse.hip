@@ -58,23 +58,31 @@ typedef __attribute__((address_space(1))) u32x4 global_u32x4;
 typedef __attribute__((address_space(1))) uint16_t global_u16;
 typedef __attribute__((address_space(1))) uint8_t global_u8;
 
+// kStream: non-temporal access, for data that is touched once.  Measured on the batched 7B pass:
+// streaming loads of cur/base and streaming stores of the payload are worth about 2 % to the
+// encoder; the decoder is about 2 % faster with ordinary stores of its output.
+template <bool kStream>
 __device__ __forceinline__ uint4 load_global16(const void *p)
 {
-    const u32x4 v = *(const global_u32x4 *)p;
+    const u32x4 v = kStream ? __builtin_nontemporal_load((const global_u32x4 *)p) : *(const global_u32x4 *)p;
     return make_uint4(v.x, v.y, v.z, v.w);
 }
+template <bool kStream>
 __device__ __forceinline__ void store_global16(void *p, uint4 v)
 {
     u32x4 t;
     t.x = v.x, t.y = v.y, t.z = v.z, t.w = v.w;
-    *(global_u32x4 *)p = t;
+    if (kStream)
+        __builtin_nontemporal_store(t, (global_u32x4 *)p);
+    else
+        *(global_u32x4 *)p = t;
 }
 
 // 8 elements to p[e0 .. e0+8) (e0 a multiple of 8), clipped at n
 __device__ __forceinline__ void store8(uint16_t *p, int64_t e0, int64_t n, uint4 v)
 {
     if (e0 + kLaneElems <= n) {
-        store_global16(p + e0, v);
+        store_global16<false>(p + e0, v);
         return;
     }
     const uint32_t w[4] = {v.x, v.y, v.z, v.w};
@@ -187,7 +195,7 @@ __device__ __forceinline__ void load_tile16(const uint16_t *__restrict__ p, int6
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
             const uint32_t e = e0 + (uint32_t)((r * kRoundChunks + j) * kChunkElems);
-            v[r][j] = load_global16(tp + (e < rem ? e : 0u));
+            v[r][j] = load_global16<true>(tp + (e < rem ? e : 0u));
         }
 }
 
@@ -288,7 +296,7 @@ __device__ __forceinline__ void copy_out_stage(const EncodeShared &sh, uint16_t 
             v.y = __builtin_amdgcn_alignbyte(w[2], w[1], odd_bytes);
             v.z = __builtin_amdgcn_alignbyte(w[3], w[2], odd_bytes);
             v.w = __builtin_amdgcn_alignbyte(w[4], w[3], odd_bytes);
-            store_global16(dst + lo, v);
+            store_global16<true>(dst + lo, v);
         } else {
             for (uint32_t t = 0; t < 8u; ++t) {
                 const uint32_t i = lo + t;
@@ -581,7 +589,7 @@ __global__ __launch_bounds__(kBlock) void decode_merge_kernel(bitsnap_sparse_ite
             const int64_t s = src0 + lo;
             uint4 pv = make_uint4(0, 0, 0, 0);
             if (s + 8 <= payload_elems) {
-                pv = load_global16(payload + s);
+                pv = load_global16<false>(payload + s);
             } else {
                 uint32_t w[4] = {0, 0, 0, 0};
                 for (int t = 0; t < 8; ++t)
