@@ -31,20 +31,11 @@ constexpr int kRoundChunks = 2 * kWaves;                   // a round: every wav
 constexpr int kRoundElems = kRoundChunks * kChunkElems;    // 4096
 constexpr int kRounds = 4;                                 // rounds per tile, all loaded before the scan
 constexpr int kTileElems = kRounds * kRoundElems;          // one ticket, one status word, one look-back
-constexpr int kPhases = (kRounds % 2 == 0) ? 2 : 1;         // the payload passes through LDS in this many parts
-constexpr int kPhaseRounds = kRounds / kPhases;
-constexpr int kStageElems = kPhaseRounds * kRoundElems + 8; // one part + alignment shift
 
-// decode: the payload passes through LDS in kPhases parts
+// The tile's changed values pass through `stage`: at their rank inside the tile in the encoder
+// (before the tile's place in the payload is known), as the aligned payload segment in the decoder.
 struct TileShared {
-    alignas(16) uint16_t stage[kStageElems];
-    uint32_t wave_total[kRounds][kWaves];
-};
-
-// encode: the whole tile's changed values are staged at their rank inside the tile, before the
-// tile's place in the payload is known
-struct EncodeShared {
-    alignas(16) uint16_t stage[kTileElems + 8];  // + the dword pair a realigning read may touch
+    alignas(16) uint16_t stage[kTileElems + 16];  // + what a realigning read (encode) or a shifted segment (decode) adds
     uint32_t wave_total[kRounds][kWaves];
     uint64_t excl;
     int64_t next_tile;
@@ -118,12 +109,10 @@ __device__ __forceinline__ int64_t piece_chunk(int64_t tile, int r, int wave, in
     return tile * (kRounds * kRoundChunks) + r * kRoundChunks + wave * 2 + j;
 }
 
-// Per-lane popcounts m[r][j] -> this lane's exclusive rank of each piece inside the tile, and the
-// rank at which each staging phase starts (the last entry is the tile total).  Contains one
-// __syncthreads.
-template <class Shared>
-__device__ __forceinline__ void tile_ranks(Shared &sh, const uint32_t (&cnt)[kRounds][2], int lane, int wave,
-                                           uint32_t (&rank)[kRounds][2], uint32_t (&phase_start)[kPhases + 1])
+// Per-lane popcounts cnt[r][j] -> this lane's exclusive rank of each piece inside the tile;
+// returns the tile total.  Contains one __syncthreads.
+__device__ __forceinline__ uint32_t tile_ranks(TileShared &sh, const uint32_t (&cnt)[kRounds][2], int lane, int wave,
+                                               uint32_t (&rank)[kRounds][2])
 {
     uint32_t ex[kRounds], t0[kRounds];
 #pragma unroll
@@ -140,8 +129,6 @@ __device__ __forceinline__ void tile_ranks(Shared &sh, const uint32_t (&cnt)[kRo
     uint32_t run = 0;
 #pragma unroll
     for (int r = 0; r < kRounds; ++r) {
-        if (r % kPhaseRounds == 0)
-            phase_start[r / kPhaseRounds] = run;
         uint32_t before = 0, all = 0;
 #pragma unroll
         for (int w = 0; w < kWaves; ++w) {
@@ -153,14 +140,14 @@ __device__ __forceinline__ void tile_ranks(Shared &sh, const uint32_t (&cnt)[kRo
         rank[r][1] = run + before + t0[r] + (ex[r] >> 16);
         run += all;
     }
-    phase_start[kPhases] = run;  // the tile total
+    return run;
 }
 
 // Wave 0, after the tile's count has been published: the count of everything before the tile in
 // the same tensor; publishes the inclusive value; the result reaches the other waves through
 // sh.excl / sh.aborted.  `tile` and `first_tile` (the tensor's first tile) are in the launch-wide
 // numbering.
-__device__ __forceinline__ void tile_look_back(EncodeShared &sh, ScanHeader *hdr, uint64_t *status, int64_t tile,
+__device__ __forceinline__ void tile_look_back(TileShared &sh, ScanHeader *hdr, uint64_t *status, int64_t tile,
                                                int64_t first_tile, uint32_t epoch, uint32_t spin_limit,
                                                uint32_t tile_total, int lane)
 {
@@ -214,7 +201,7 @@ __device__ __forceinline__ uint64_t uniform64(uint64_t t)
 }
 
 // The value thread 0 left in sh.next_tile, as a scalar in every thread (call after a barrier).
-__device__ __forceinline__ int64_t claimed_tile(const EncodeShared &sh) { return (int64_t)uniform64((uint64_t)sh.next_tile); }
+__device__ __forceinline__ int64_t claimed_tile(const TileShared &sh) { return (int64_t)uniform64((uint64_t)sh.next_tile); }
 
 // The tensor a launch-wide tile number belongs to.  Tickets only grow, so a workgroup walks the
 // item list forwards.  With kBatched == false there is one tensor, passed by value.
@@ -269,7 +256,7 @@ __device__ __forceinline__ void report_failures(int epilogue, const bitsnap_spar
 // stage elements from 8q - shift, read as five dwords and shifted by one element when shift is
 // odd.  The ragged ends of the tile's segment, and whatever would cross the payload capacity, go
 // out element by element.
-__device__ __forceinline__ void copy_out_stage(const EncodeShared &sh, uint16_t *__restrict__ payload, int64_t capacity,
+__device__ __forceinline__ void copy_out_stage(const TileShared &sh, uint16_t *__restrict__ payload, int64_t capacity,
                                                uint64_t excl, uint32_t total, int tid)
 {
     const uint32_t shift = (uint32_t)(excl & 7u);
@@ -325,7 +312,7 @@ __global__ __launch_bounds__(kBlock, 4) void encode_sparse_kernel(bitsnap_sparse
                                                                int64_t count, ScanHeader *hdr, uint64_t *status,
                                                                int64_t status_cap, int64_t num_tiles, uint32_t spin_limit)
 {
-    __shared__ EncodeShared sh;
+    __shared__ TileShared sh;
     const int tid0 = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid0 >> 6);
     const uint32_t epoch = hdr->epoch;
     bool aborted = false;
@@ -381,9 +368,7 @@ __global__ __launch_bounds__(kBlock, 4) void encode_sparse_kernel(bitsnap_sparse
                 if (mb + lane < wave_mask_bytes)
                     ((global_u8 *)(wave_mask + mb))[(uint32_t)lane] = (uint8_t)m[r][j];
             }
-        uint32_t phase_start[kPhases + 1];
-        tile_ranks(sh, cnt, lane, wave, rank, phase_start);  // barrier
-        const uint32_t total = phase_start[kPhases];
+        const uint32_t total = tile_ranks(sh, cnt, lane, wave, rank);  // barrier
         if (tid == 0)
             publish(status, gtile, make_status(tile == 0 ? kFlagInclusive : kFlagAggregate, epoch, total));
 
@@ -543,14 +528,18 @@ __global__ __launch_bounds__(kBlock) void decode_scan_kernel(bitsnap_sparse_item
         *it.n_changed = carry_s;
 }
 
-// One workgroup per tile: out = bit ? next payload element : base.
+// One workgroup per tile: out = bit ? next payload element : base.  The tile's place in the payload
+// and its length are known from the two kernels before, so mask, base and the payload segment are
+// all requested at once; the segment goes through LDS as aligned 16-byte pieces (stage[i] holds
+// payload element src0 + i, src0 a multiple of 8), from where every lane picks its elements by rank.
 template <bool kBatched>
-__global__ __launch_bounds__(kBlock) void decode_merge_kernel(bitsnap_sparse_item single,
-                                                              const bitsnap_sparse_item *__restrict__ items,
-                                                              int64_t count, const uint64_t *__restrict__ tile_offset)
+__global__ __launch_bounds__(kBlock, 4) void decode_merge_kernel(bitsnap_sparse_item single,
+                                                                 const bitsnap_sparse_item *__restrict__ items,
+                                                                 int64_t count, const uint64_t *__restrict__ tile_offset,
+                                                                 const uint32_t *__restrict__ tile_count)
 {
     __shared__ TileShared sh;
-    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int64_t gtile = blockIdx.x;
     const bitsnap_sparse_item &it = kBatched ? items[find_sparse_item(items, count, gtile)] : single;
     const uint16_t *base = (const uint16_t *)it.base;  // may alias out
@@ -561,62 +550,65 @@ __global__ __launch_bounds__(kBlock) void decode_merge_kernel(bitsnap_sparse_ite
     const int64_t mask_bytes = (n + 7) >> 3;
 
     const uint64_t excl = tile_offset[gtile];
+    const uint32_t total = tile_count[gtile];
+    const uint32_t shift = (uint32_t)(excl & 7u);
+    const int64_t src0 = (int64_t)(excl - shift);
+    const uint32_t pieces = (shift + total + 7u) >> 3;  // at most kTileElems / 8 + 1
+    constexpr int kPiecesPerThread = kTileElems / 8 / kBlock;
+
     uint32_t m[kRounds][2], cnt[kRounds][2], rank[kRounds][2];
-    uint4 v[kRounds][2];
+    uint4 v[kRounds][2], pv[kPiecesPerThread];
     load_tile_mask(mask, mask_bytes, tile, wave, lane, n, m);
     load_tile16(base, tile, wave, lane, n, v);
+    const uint16_t *__restrict__ seg = payload + src0;  // wave-uniform, 16-byte aligned
+    const int64_t seg_elems = payload_elems - src0;      // elements of seg that may be read
+#pragma unroll
+    for (int i = 0; i < kPiecesPerThread; ++i) {
+        const uint32_t q = (uint32_t)(i * kBlock + tid);
+        pv[i] = make_uint4(0, 0, 0, 0);
+        if (q < pieces) {
+            if ((int64_t)(q * 8u + 8u) <= seg_elems) {
+                pv[i] = load_global16<false>(seg + q * 8u);
+            } else {
+                uint32_t w[4] = {0, 0, 0, 0};
+                for (uint32_t t = 0; t < 8u; ++t)
+                    if ((int64_t)(q * 8u + t) < seg_elems)
+                        w[t >> 1] |= (uint32_t)((const global_u16 *)seg)[q * 8u + t] << ((t & 1) * 16);
+                pv[i] = make_uint4(w[0], w[1], w[2], w[3]);
+            }
+        }
+    }
 #pragma unroll
     for (int r = 0; r < kRounds; ++r)
 #pragma unroll
         for (int j = 0; j < 2; ++j)
             cnt[r][j] = __popc(m[r][j]);
-    uint32_t phase_start[kPhases + 1];
-    tile_ranks(sh, cnt, lane, wave, rank, phase_start);  // barrier
-
-    // the tile's payload segment, in kPhases contiguous parts -> LDS as aligned 16-byte pieces
+    tile_ranks(sh, cnt, lane, wave, rank);  // barrier
 #pragma unroll
-    for (int ph = 0; ph < kPhases; ++ph) {
-        const uint64_t part_off = excl + phase_start[ph];
-        const uint32_t part_len = phase_start[ph + 1] - phase_start[ph];
-        const uint32_t shift = (uint32_t)(part_off & 7u);
-        const uint32_t last = shift + part_len;
-        const int64_t src0 = (int64_t)(part_off - shift);
-        const uint32_t pieces = (last + 7u) >> 3;
-        if (ph > 0)
-            __syncthreads();  // the previous part has been consumed
-        for (uint32_t q = tid; q < pieces; q += kBlock) {
-            const uint32_t lo = q * 8u;
-            const int64_t s = src0 + lo;
-            uint4 pv = make_uint4(0, 0, 0, 0);
-            if (s + 8 <= payload_elems) {
-                pv = load_global16<false>(payload + s);
-            } else {
-                uint32_t w[4] = {0, 0, 0, 0};
-                for (int t = 0; t < 8; ++t)
-                    if (s + t < payload_elems)
-                        w[t >> 1] |= (uint32_t)((const global_u16 *)payload)[s + t] << ((t & 1) * 16);
-                pv = make_uint4(w[0], w[1], w[2], w[3]);
-            }
-            *reinterpret_cast<uint4 *>(&sh.stage[lo]) = pv;
-        }
-        __syncthreads();
-#pragma unroll
-        for (int r = ph * kPhaseRounds; r < (ph + 1) * kPhaseRounds; ++r)
-#pragma unroll
-            for (int j = 0; j < 2; ++j) {
-                uint32_t p = shift + rank[r][j] - phase_start[ph];
-                uint32_t w[4] = {v[r][j].x, v[r][j].y, v[r][j].z, v[r][j].w};
-#pragma unroll
-                for (int t = 0; t < kLaneElems; ++t) {
-                    if ((m[r][j] >> t) & 1u) {
-                        const uint32_t s = sh.stage[p++];
-                        w[t >> 1] = (t & 1) ? ((w[t >> 1] & 0x0000FFFFu) | (s << 16)) : ((w[t >> 1] & 0xFFFF0000u) | s);
-                    }
-                }
-                store8(out, piece_chunk(tile, r, wave, j) * kChunkElems + lane * kLaneElems, n,
-                       make_uint4(w[0], w[1], w[2], w[3]));
-            }
+    for (int i = 0; i < kPiecesPerThread; ++i)
+        *reinterpret_cast<uint4 *>(&sh.stage[(uint32_t)(i * kBlock + tid) * 8u]) = pv[i];
+    if (tid == 0 && pieces > (uint32_t)(kPiecesPerThread * kBlock)) {  // a full tile that starts off the 16-byte grid
+        const uint32_t q = (uint32_t)(kPiecesPerThread * kBlock);
+        for (uint32_t t = 0; t < 8u; ++t)
+            sh.stage[q * 8u + t] = (int64_t)(q * 8u + t) < seg_elems ? ((const global_u16 *)seg)[q * 8u + t] : (uint16_t)0;
     }
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < kRounds; ++r)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            uint32_t p = shift + rank[r][j];
+            uint32_t w[4] = {v[r][j].x, v[r][j].y, v[r][j].z, v[r][j].w};
+#pragma unroll
+            for (int t = 0; t < kLaneElems; ++t) {
+                if ((m[r][j] >> t) & 1u) {
+                    const uint32_t s = sh.stage[p++];
+                    w[t >> 1] = (t & 1) ? ((w[t >> 1] & 0x0000FFFFu) | (s << 16)) : ((w[t >> 1] & 0xFFFF0000u) | s);
+                }
+            }
+            store8(out, piece_chunk(tile, r, wave, j) * kChunkElems + lane * kLaneElems, n,
+                   make_uint4(w[0], w[1], w[2], w[3]));
+        }
 }
 
 // Workspace after the header: encode keeps one 8-byte scan word per tile there; decode keeps the
@@ -719,7 +711,7 @@ static int launch_decode(const bitsnap_sparse_item &single, const bitsnap_sparse
                        items, tile_count, tile_offset);
     if (num_tiles > 0)
         hipLaunchKernelGGL(decode_merge_kernel<kBatched>, dim3((unsigned)num_tiles), dim3(kBlock), 0, s, single, items,
-                           count, tile_offset);
+                           count, tile_offset, tile_count);
     return launch_status();
 }
 
