@@ -208,6 +208,33 @@ def main():
             torch.cuda.synchronize()
         copy_gbps = 5 * 2 * cal_bytes / (e0.elapsed_time(e1) * 1e-3) / 1e9
 
+    # ------------------------------------------------------------------ beside the step: one fit per tensor
+    # (group = 0, Algorithm 2 as the paper states it) on the first-moment state, one call per tensor;
+    # three passes over the tensor instead of one, codes and labels into the same buffers
+    gws = torch.empty(max(B.cluster_workspace_bytes(n, 0, M) for n in sizes), dtype=u8, device=dev)
+    gparams = torch.empty(M * 2, dtype=f32, device=dev)
+    gcalls = [(d["m"].data_ptr(), n, 0, M, e["q"][1]["codes"].data_ptr(), e["q"][1]["labels"].data_ptr(),
+               gparams.data_ptr(), None, None, status.data_ptr(), gws.data_ptr(), gws.numel(), sp)
+              for d, e, n in zip(inputs, enc, sizes)]
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for it in range(2):
+        e0.record(stream)
+        for a in gcalls:
+            rc = L.bitsnap_quantize_cluster(*a)
+            assert rc == 0, rc
+        e1.record(stream)
+        torch.cuda.synchronize()
+    whole_ms = e0.elapsed_time(e1)
+    whole_alg = 3 * 4 * n_total + n_total + (n_total + 1) // 2 + len(sizes) * M * 8
+    extras = {"quantize_whole_tensor_fit": {
+        "what": "group = 0 (one fit per tensor), first-moment state, one call per tensor, 3 passes over x",
+        "ms": round(whole_ms, 3), "api_calls": len(gcalls), "state_GBps": round(4 * n_total / whole_ms / 1e6, 1),
+        "hbm_GBps": round(whole_alg / whole_ms / 1e6, 1), "hbm_frac": round(whole_alg / whole_ms / 1e6 / HBM_PEAK_GBS, 4)}}
+    # the step's own codes of that state, for whoever looks at the buffers afterwards
+    for a in (c for k, c in enumerate(calls["quantize_cluster"]) if k % 3 == 1):
+        L.bitsnap_quantize_cluster(*a)
+    torch.cuda.synchronize()
+
     # ------------------------------------------------------------------ accounting
     n_changed = sum(int(e["n_changed"].item()) for e in enc)
     assert int(status.item()) == 0
@@ -259,7 +286,7 @@ def main():
                       "state_bytes_per_step": total_state, "generation_s": round(gen_s, 1)},
            "hbm_frac_of_peak": {op: ops[op]["hbm_frac"] for op in order},
            "copy_kernel_GBps": None if copy_gbps is None else round(copy_gbps, 1), "copy_kernel_bytes_each_way": cal_bytes,
-           "ops": ops, "roofline": roofline}
+           "ops": ops, "extras": extras, "roofline": roofline}
 
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(inputs, sizes, args.cpu_sample_tensors, cfg)

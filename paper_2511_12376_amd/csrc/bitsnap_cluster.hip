@@ -103,56 +103,6 @@ __global__ __launch_bounds__(kQBlock) void quantize_cluster_kernel(
     quantize_group<K, kFull>(x, lo, len, m, g, codes, labels, params, fit_out, fit_in, status, shared[wave], lane);
 }
 
-// Dequantisation of one group by one wave: codes[lo..lo+len) -> out[lo..lo+len).
-template <int K>
-__device__ __forceinline__ void dequantize_group(const uint8_t *__restrict__ codes, const uint8_t *__restrict__ labels,
-                                                 const float *__restrict__ params, int64_t lo, int len, int m, int64_t g,
-                                                 float *__restrict__ out, float2 *coder, int lane)
-{
-    if (lane < kMaxClusters) {
-        float2 sb = make_float2(0.0f, 0.0f);
-        if (lane < m)
-        {
-            const float2v t = *(const BITSNAP_GLOBAL float2v *)(global_ptr(params) + (g * m + lane) * 2);
-            sb = make_float2(t.x, t.y);
-        }
-        coder[lane] = make_float2(__fdiv_rn(sb.x, 255.0f), sb.y);  // (S/255, b)
-    }
-    wave_lds_sync();
-#pragma unroll
-    for (int k = 0; k < K; ++k) {
-        const int off = k * 256 + lane * 4;
-        if (off >= len)
-            break;
-        const bool full = off + 3 < len;
-        uint32_t c4 = 0, l4 = 0;
-        if (full) {
-            c4 = __builtin_nontemporal_load((const BITSNAP_GLOBAL uint32_t *)(global_ptr(codes) + lo + off));
-            l4 = __builtin_nontemporal_load((const BITSNAP_GLOBAL uint16_t *)(global_ptr(labels) + ((lo + off) >> 1)));
-        } else {
-            for (int j = 0; j < 4; ++j)
-                if (off + j < len) {
-                    c4 |= (uint32_t)global_ptr(codes)[lo + off + j] << (8 * j);
-                    l4 |= (uint32_t)((global_ptr(labels)[(lo + off + j) >> 1] >> (4 * (j & 1))) & 15u) << (4 * j);
-                }
-        }
-        float r[4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const float2 sb = coder[(l4 >> (4 * j)) & 15u];
-            r[j] = __fadd_rn(__fmul_rn((float)((c4 >> (8 * j)) & 255u), sb.x), sb.y);
-        }
-        if (full) {
-            __builtin_nontemporal_store(float4v{r[0], r[1], r[2], r[3]}, (BITSNAP_GLOBAL float4v *)(global_ptr(out) + lo + off));
-        } else {
-            for (int j = 0; j < 4; ++j)
-                if (off + j < len)
-                    global_ptr(out)[lo + off + j] = r[j];
-        }
-    }
-    wave_lds_sync();  // the coder table may be rewritten by this wave's next group
-}
-
 template <int K>
 __global__ __launch_bounds__(kQBlock) void dequantize_cluster_kernel(
     const uint8_t *__restrict__ codes, const uint8_t *__restrict__ labels, const float *__restrict__ params,
@@ -166,7 +116,7 @@ __global__ __launch_bounds__(kQBlock) void dequantize_cluster_kernel(
     constexpr int G = 256 * K;
     const int64_t lo = g * G;
     const int64_t rest = n - lo;
-    dequantize_group<K>(codes, labels, params, lo, rest >= G ? G : (int)rest, m, g, out, coder[wave], lane);
+    dequantize_group<K>(codes, labels, params, lo, rest >= G ? G : (int)rest, true, m, g, out, coder[wave], lane);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -247,7 +197,7 @@ __global__ __launch_bounds__(kQBlock) void dequantize_cluster_batched_kernel(
     const int64_t lo = g * G;
     const int64_t rest = it.n - lo;
     if (rest > 0)
-        dequantize_group<K>(it.codes, it.labels, it.params, lo, rest >= G ? G : (int)rest, m, g, (float *)it.values,
+        dequantize_group<K>(it.codes, it.labels, it.params, lo, rest >= G ? G : (int)rest, true, m, g, (float *)it.values,
                             coder[wave], lane);
 }
 

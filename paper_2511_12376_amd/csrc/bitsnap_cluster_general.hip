@@ -1,52 +1,45 @@
 // quantize_cluster / dequantize_cluster for group lengths the one-wave-per-group kernels do not
 // take: any even G and G = 0 (one group spanning the tensor, the paper's own formulation of
-// Algorithm 2).  A group is cut into chunks of 4096 elements, one 256-thread workgroup per chunk,
-// and Algorithm 2's steps become passes over HBM with the per-group state in the workspace:
-//   pass 1  sum per chunk                 -> finalize: mean
-//   pass 2  sum of (x-mean)^2 per chunk   -> finalize: mu, sigma, edges; min/max tables reset
-//   pass 3  labels; per-cluster min/max (LDS per chunk, then integer atomics on ordered keys)
-//           -> finalize: (S, b), 255/S
-//   pass 4  codes
-// Chunk partials are written out and summed in chunk order, so the fit does not depend on the
-// order in which workgroups run.  This path favours being right over being fast (x is read four
-// times).
+// Algorithm 2).  A group is cut into chunks of 4096 elements, one wavefront per chunk with the
+// chunk in registers (the building blocks of cluster_wave.hpp), and Algorithm 2's steps become
+// three passes over x with the per-group state in the workspace:
+//   pass 1  per chunk: sum and, about the chunk's own mean, the sum of squared deviations
+//           -> per slice of 256 chunks -> per group: mean, deviation (pairwise update formula), edges
+//   pass 2  per chunk: labels (not stored), per-cluster min/max
+//           -> per slice -> per group: (S, b), 255/S
+//   pass 3  per chunk: labels again, codes; both stored
+// x is read three times and 1.5 bytes per element are written: 13.5 bytes per element.  Chunk
+// results are written out and combined in chunk order, so nothing depends on the order in which
+// the waves run.
 #include <hip/hip_runtime.h>
 #include <math.h>
 #include <stdint.h>
 
 #include "../../include/bitsnap.h"
 #include "cluster_general.hpp"
+#include "cluster_wave.hpp"
 #include "host_util.hpp"
 #include "wave.hpp"
 
 namespace bitsnap {
 
 constexpr int kGBlock = 256;
-constexpr int kGChunk = 4096;
-constexpr int kGMaxClusters = 16;
-
-// the same quantile table as the one-wave-per-group kernels (a copy per translation unit)
-__constant__ double kZGeneral[17][16] = {
-#include "z_table.inc"
-};
+constexpr int kGWaves = kGBlock / kWave;
+constexpr int kGK = 16;                  // float4 per lane
+constexpr int kGChunk = 256 * kGK;       // 4096 elements per wave
 
 struct GroupState {  // one per group, in the workspace
-    double sum;
-    double dev;
     float mu, sigma;
-    float edges[kGMaxClusters];      // [k] = e_k, [0] unused
-    int32_t kmin[kGMaxClusters];     // ordered keys of the cluster minima / maxima
-    int32_t kmax[kGMaxClusters];
-    float2 coder[kGMaxClusters];     // (b, 255/S)
+    float2 coder[kMaxClusters];  // (b, 255/S)
 };
 
-// float <-> int key whose signed order is the float order (-0 sorts below +0); an involution
-__device__ __forceinline__ int32_t ordered_key(float x)
-{
-    const int32_t b = __float_as_int(x);
-    return b ^ ((b >> 31) & 0x7FFFFFFF);
-}
-__device__ __forceinline__ float from_key(int32_t k) { return __int_as_float(k ^ ((k >> 31) & 0x7FFFFFFF)); }
+struct ChunkStats {  // one per chunk, in the workspace
+    double sum, dev;
+};
+
+struct ChunkRanges {  // one per chunk, in the workspace
+    float mn[kMaxClusters], mx[kMaxClusters];
+};
 
 struct ChunkRef {
     int64_t group, lo;  // group index, first element (global)
@@ -67,6 +60,9 @@ __device__ __forceinline__ ChunkRef chunk_ref(int64_t c, int64_t n, int64_t G, i
     return r;
 }
 
+// A whole chunk whose first element is 16-byte aligned takes the vector loads and stores.
+__device__ __forceinline__ bool chunk_is_full(const ChunkRef &r) { return r.len == kGChunk && (r.lo & 3) == 0; }
+
 __device__ __forceinline__ double block_sum(double v, double *scratch)
 {
     v = wave_sum(v);
@@ -78,216 +74,299 @@ __device__ __forceinline__ double block_sum(double v, double *scratch)
     return (scratch[0] + scratch[1]) + (scratch[2] + scratch[3]);
 }
 
-template <bool kDeviation>
-__global__ __launch_bounds__(kGBlock) void general_partial_kernel(const float *__restrict__ x, int64_t n, int64_t G,
-                                                                  int64_t chunks_per_group, int64_t chunks,
-                                                                  const GroupState *__restrict__ gs,
-                                                                  double *__restrict__ partial)
+// ---- pass 1
+__global__ __launch_bounds__(kGBlock) void wide_stats_kernel(const float *__restrict__ x, int64_t n, int64_t G,
+                                                             int64_t chunks_per_group, int64_t chunks,
+                                                             ChunkStats *__restrict__ stats)
 {
-    __shared__ double scratch[kGBlock / kWave];
-    for (int64_t c = blockIdx.x; c < chunks; c += gridDim.x) {
-        const ChunkRef r = chunk_ref(c, n, G, chunks_per_group);
-        const double mean = kDeviation ? gs[r.group].sum : 0.0;  // after pass 1, .sum holds the mean
-        double acc = 0.0;
-        for (int e = threadIdx.x; e < r.len; e += kGBlock) {
-            const double v = (double)x[r.lo + e];
-            if (kDeviation) {
-                const double d = v - mean;
-                acc = fma(d, d, acc);
-            } else {
-                acc += v;
-            }
+    const int lane = threadIdx.x & (kWave - 1), wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int64_t c = (int64_t)blockIdx.x * kGWaves + wave;
+    if (c >= chunks)
+        return;
+    const ChunkRef r = chunk_ref(c, n, G, chunks_per_group);
+    double sum = 0.0, dev = 0.0;
+    if (r.len > 0) {
+        float4 v[kGK];
+        if (chunk_is_full(r)) {
+            load_elements<kGK, true>(x, r.lo, r.len, lane, v);
+            wave_stats<kGK, true>(v, r.len, lane, sum, dev);
+        } else {
+            load_elements<kGK, false>(x, r.lo, r.len, lane, v);
+            wave_stats<kGK, false>(v, r.len, lane, sum, dev);
         }
-        acc = block_sum(acc, scratch);
-        if (threadIdx.x == 0)
-            partial[c] = acc;
+    }
+    if (lane == 0) {
+        stats[c].sum = sum;
+        stats[c].dev = dev;
     }
 }
 
-// One workgroup per group: add the chunk partials in chunk order.
-//   stage 0: sum -> mean (kept in .sum)
-//   stage 1: deviation -> mu, sigma, edges, reset of the min/max keys
-__global__ __launch_bounds__(kGBlock) void general_finalize_fit_kernel(int stage, int64_t n, int64_t G,
-                                                                       int64_t chunks_per_group, int64_t groups, int m,
-                                                                       const double *__restrict__ partial, GroupState *gs,
-                                                                       float *__restrict__ fit_out,
-                                                                       const float *__restrict__ fit_in,
-                                                                       uint32_t *__restrict__ status)
+// The statistics of the chunks are combined in two levels, slices of 256 chunks and then the
+// group, each time with the pairwise update formula
+//   sum = sum of the parts' sums,   dev = sum over parts of  dev_p + n_p * (mean_p - mean)^2
+// (every term non-negative, nothing cancels), in a fixed association: a tensor-wide group of a
+// 131 M-element tensor has 32000 chunks, too many for one workgroup to walk through.
+constexpr int kGSlice = kGBlock;  // chunks per slice: one per thread
+
+// Elements in chunks [c0, c1) of a group of g_len elements.
+__device__ __forceinline__ double chunk_span_elems(int64_t c0, int64_t c1, int64_t g_len)
+{
+    const int64_t lo = c0 * kGChunk, hi = c1 * kGChunk;
+    return (double)((hi < g_len ? hi : g_len) - lo);
+}
+
+// grid: groups * slices_per_group workgroups
+__global__ __launch_bounds__(kGBlock) void wide_slice_stats_kernel(int64_t n, int64_t G, int64_t chunks_per_group,
+                                                                   int64_t slices_per_group, int64_t groups,
+                                                                   const ChunkStats *__restrict__ stats,
+                                                                   ChunkStats *__restrict__ slice_stats)
+{
+    __shared__ double scratch[kGBlock / kWave];
+    const int64_t g = blockIdx.x / slices_per_group, sl = blockIdx.x % slices_per_group;
+    if (g >= groups)
+        return;
+    const int64_t g_lo = g * G;
+    const int64_t g_len = (g_lo + G <= n) ? G : (n - g_lo);
+    const int64_t nch = (g_len + kGChunk - 1) / kGChunk;
+    const int64_t c = sl * kGSlice + threadIdx.x, c_end = (sl + 1) * kGSlice < nch ? (sl + 1) * kGSlice : nch;
+    const bool have = c < nch;
+    const ChunkStats mine = have ? stats[g * chunks_per_group + c] : ChunkStats{0.0, 0.0};
+    const double sum = block_sum(mine.sum, scratch);
+    double term = 0.0;
+    if (have && sl * kGSlice < nch) {
+        const double mean = sum / chunk_span_elems(sl * kGSlice, c_end, g_len);
+        const double n_c = chunk_span_elems(c, c + 1, g_len);
+        const double d = mine.sum / n_c - mean;
+        term = mine.dev + n_c * d * d;
+    }
+    const double dev = block_sum(term, scratch);
+    if (threadIdx.x == 0) {
+        slice_stats[g * slices_per_group + sl].sum = sum;
+        slice_stats[g * slices_per_group + sl].dev = dev;
+    }
+}
+
+// One workgroup per group: slices -> mean, deviation -> mu, sigma (Algorithm 2 step 1), edges.
+// Thread t takes slices t, t+256, ... in order, then the block tree.
+__global__ __launch_bounds__(kGBlock) void wide_fit_kernel(int64_t n, int64_t G, int64_t slices_per_group, int64_t groups,
+                                                           int m, const ChunkStats *__restrict__ slice_stats,
+                                                           GroupState *gs, float *__restrict__ fit_out,
+                                                           const float *__restrict__ fit_in, uint32_t *__restrict__ status)
 {
     __shared__ double scratch[kGBlock / kWave];
     for (int64_t g = blockIdx.x; g < groups; g += gridDim.x) {
         const int64_t g_lo = g * G;
         const int64_t g_len = (g_lo + G <= n) ? G : (n - g_lo);
         const int64_t nch = (g_len + kGChunk - 1) / kGChunk;
-        // fixed association: thread t takes chunks t, t+256, ... in order, then the block tree
+        const int64_t nsl = (nch + kGSlice - 1) / kGSlice;
+        const ChunkStats *ss = slice_stats + g * slices_per_group;
         double acc = 0.0;
-        for (int64_t c = threadIdx.x; c < nch; c += kGBlock)
-            acc += partial[g * chunks_per_group + c];
-        acc = block_sum(acc, scratch);
-        if (stage == 0) {
-            if (threadIdx.x == 0)
-                gs[g].sum = acc / (double)g_len;
-        } else {
-            float mu = (float)gs[g].sum;
-            float sigma = (float)sqrt(acc / (double)g_len);
-            if (fit_in) {
-                mu = fit_in[2 * g];
-                sigma = fit_in[2 * g + 1];
-            }
-            const int t = threadIdx.x;
-            if (t == 0) {
-                gs[g].mu = mu;
-                gs[g].sigma = sigma;
-                if (status && !(isfinite(mu) && isfinite(sigma)))
-                    atomicOr(status, 1u);
-                if (fit_out) {
-                    fit_out[g * (m + 1) + 0] = mu;
-                    fit_out[g * (m + 1) + 1] = sigma;
-                }
-            }
-            if (t < kGMaxClusters) {
-                float e = INFINITY;
-                if (t >= 1 && t < m)
-                    e = (float)__dadd_rn((double)mu, __dmul_rn((double)sigma, kZGeneral[m][t]));
-                gs[g].edges[t] = e;
-                if (fit_out && t >= 1 && t < m)
-                    fit_out[g * (m + 1) + 1 + t] = e;
-                gs[g].kmin[t] = 0x7FFFFFFF;
-                gs[g].kmax[t] = (int32_t)0x80000000;
+        for (int64_t k = threadIdx.x; k < nsl; k += kGBlock)
+            acc += ss[k].sum;
+        const double mean = block_sum(acc, scratch) / (double)g_len;
+        acc = 0.0;
+        for (int64_t k = threadIdx.x; k < nsl; k += kGBlock) {
+            const int64_t c_end = (k + 1) * kGSlice < nch ? (k + 1) * kGSlice : nch;
+            const double n_k = chunk_span_elems(k * kGSlice, c_end, g_len);
+            const double d = ss[k].sum / n_k - mean;
+            acc += ss[k].dev + n_k * d * d;
+        }
+        const double dev = block_sum(acc, scratch);
+        float mu = (float)mean;
+        float sigma = (float)sqrt(dev / (double)g_len);
+        if (fit_in) {
+            mu = fit_in[2 * g];
+            sigma = fit_in[2 * g + 1];
+        }
+        const int t = threadIdx.x;
+        if (t == 0) {
+            gs[g].mu = mu;
+            gs[g].sigma = sigma;
+            if (status && !(isfinite(mu) && isfinite(sigma)))
+                atomicOr(status, 1u);
+            if (fit_out) {
+                fit_out[g * (m + 1) + 0] = mu;
+                fit_out[g * (m + 1) + 1] = sigma;
             }
         }
+        if (fit_out && t >= 1 && t < m)  // the same expression as build_search
+            fit_out[g * (m + 1) + 1 + t] = (float)__dadd_rn((double)mu, __dmul_rn((double)sigma, kZDev[m][t]));
         __syncthreads();
     }
 }
 
-// Algorithm 2 step 3 as a plain count (the edges that do not exist are +inf)
-__device__ __forceinline__ int label_by_count(const float *edges, float x)
+// ---- pass 2
+template <bool kFull>
+__device__ __forceinline__ void chunk_ranges(const float *__restrict__ x, const ChunkRef &r, int m, float mu, float sigma,
+                                             WaveShared &ws, int lane, float &mn, float &mx)
 {
-    int l = 0;
-#pragma unroll
-    for (int k = 1; k < kGMaxClusters; ++k)
-        l += (edges[k] <= x) ? 1 : 0;
-    return l;
+    float4 v[kGK];
+    load_elements<kGK, kFull>(x, r.lo, r.len, lane, v);
+    reset_ranges(ws, lane);
+    float edge;
+    const LabelSearch ls = build_search(mu, sigma, m, ws, lane, edge);
+    uint32_t packed[(kGK + 1) / 2];
+    label_pass<kGK, kFull, false, true>(v, r.lo, r.len, ls, ws, lane, nullptr, packed);
+    reduce_ranges(ws, lane, mn, mx);
+    wave_lds_sync();
 }
 
-__global__ __launch_bounds__(kGBlock) void general_label_kernel(const float *__restrict__ x, int64_t n, int64_t G,
-                                                                int64_t chunks_per_group, int64_t chunks,
-                                                                GroupState *gs, uint8_t *__restrict__ labels)
+__global__ __launch_bounds__(kGBlock) void wide_range_kernel(const float *__restrict__ x, int64_t n, int64_t G,
+                                                             int64_t chunks_per_group, int64_t chunks, int m,
+                                                             const GroupState *__restrict__ gs,
+                                                             ChunkRanges *__restrict__ ranges)
 {
-    __shared__ float edges[kGMaxClusters];
-    __shared__ int32_t kmin[kGMaxClusters], kmax[kGMaxClusters];
-    for (int64_t c = blockIdx.x; c < chunks; c += gridDim.x) {
-        const ChunkRef r = chunk_ref(c, n, G, chunks_per_group);
-        __syncthreads();
-        if (threadIdx.x < kGMaxClusters) {
-            edges[threadIdx.x] = gs[r.group].edges[threadIdx.x];
-            kmin[threadIdx.x] = 0x7FFFFFFF;
-            kmax[threadIdx.x] = (int32_t)0x80000000;
-        }
-        __syncthreads();
-        // two elements per thread and step: r.lo is even, so a pair shares one label byte
-        for (int p = threadIdx.x; 2 * p < r.len; p += kGBlock) {
-            uint32_t byte = 0;
-            for (int j = 0; j < 2; ++j) {
-                const int e = 2 * p + j;
-                if (e < r.len) {
-                    const float v = x[r.lo + e];
-                    const int l = label_by_count(edges, v);
-                    byte |= (uint32_t)l << (4 * j);
-                    const int32_t key = ordered_key(v);
-                    atomicMin(&kmin[l], key);
-                    atomicMax(&kmax[l], key);
-                }
-            }
-            labels[(r.lo >> 1) + p] = (uint8_t)byte;
-        }
-        __syncthreads();
-        if (threadIdx.x < kGMaxClusters && kmin[threadIdx.x] <= kmax[threadIdx.x]) {
-            atomicMin(&gs[r.group].kmin[threadIdx.x], kmin[threadIdx.x]);
-            atomicMax(&gs[r.group].kmax[threadIdx.x], kmax[threadIdx.x]);
-        }
+    __shared__ WaveShared shared[kGWaves];
+    const int lane = threadIdx.x & (kWave - 1), wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int64_t c = (int64_t)blockIdx.x * kGWaves + wave;
+    if (c >= chunks)
+        return;
+    const ChunkRef r = chunk_ref(c, n, G, chunks_per_group);
+    float mn = INFINITY, mx = -INFINITY;
+    if (r.len > 0) {
+        const float mu = gs[r.group].mu, sigma = gs[r.group].sigma;
+        if (chunk_is_full(r))
+            chunk_ranges<true>(x, r, m, mu, sigma, shared[wave], lane, mn, mx);
+        else
+            chunk_ranges<false>(x, r, m, mu, sigma, shared[wave], lane, mn, mx);
+    }
+    if (lane < kMaxClusters) {
+        ranges[c].mn[lane] = mn;
+        ranges[c].mx[lane] = mx;
     }
 }
 
-__global__ __launch_bounds__(kGBlock) void general_finalize_params_kernel(int64_t groups, int m, GroupState *gs,
-                                                                          float *__restrict__ params)
+// Min / max of every cluster over `count` rows of 32 floats (16 minima, 16 maxima), by one
+// workgroup: thread t looks at column t % 32 of rows t/32, t/32 + 8, ...; the result is left in
+// part[0..32).
+__device__ __forceinline__ void reduce_range_rows(const float *__restrict__ rows, int64_t count, float *part)
 {
-    const int64_t i = (int64_t)blockIdx.x * kGBlock + threadIdx.x;
-    const int64_t g = i / kGMaxClusters;
-    const int c = (int)(i % kGMaxClusters);
+    const int col = threadIdx.x & 31, row = threadIdx.x >> 5;
+    const bool is_min = col < kMaxClusters;
+    float acc = is_min ? INFINITY : -INFINITY;
+    for (int64_t c = row; c < count; c += kGBlock / 32) {
+        const float t = rows[c * 32 + col];
+        acc = is_min ? fminf(acc, t) : fmaxf(acc, t);
+    }
+    __syncthreads();
+    part[threadIdx.x] = acc;
+    __syncthreads();
+    if (threadIdx.x < 32) {
+        for (int k = 1; k < kGBlock / 32; ++k) {
+            const float t = part[k * 32 + col];
+            acc = is_min ? fminf(acc, t) : fmaxf(acc, t);
+        }
+    }
+    __syncthreads();
+    if (threadIdx.x < 32)
+        part[threadIdx.x] = acc;
+    __syncthreads();
+}
+
+// grid: groups * slices_per_group workgroups, each over the (up to) 256 chunks of its slice
+__global__ __launch_bounds__(kGBlock) void wide_slice_ranges_kernel(int64_t n, int64_t G, int64_t chunks_per_group,
+                                                                    int64_t slices_per_group, int64_t groups,
+                                                                    const ChunkRanges *__restrict__ ranges,
+                                                                    ChunkRanges *__restrict__ slice_ranges)
+{
+    __shared__ float part[kGBlock];
+    const int64_t g = blockIdx.x / slices_per_group, sl = blockIdx.x % slices_per_group;
     if (g >= groups)
         return;
-    float S = 0.0f, b = 0.0f, inv = 0.0f;
-    const int32_t lo = gs[g].kmin[c], hi = gs[g].kmax[c];
-    if (lo <= hi) {  // the cluster has members
-        b = from_key(lo);
-        S = __fsub_rn(from_key(hi), b);
-        if (S > 0.0f) {
-            inv = __fdiv_rn(255.0f, S);
-            if (!isfinite(inv))
-                inv = 0.0f;
-        }
-    }
-    gs[g].coder[c] = make_float2(b, inv);
-    if (c < m)
-        *reinterpret_cast<float2 *>(params + (g * m + c) * 2) = make_float2(S, b);
+    const int64_t g_lo = g * G;
+    const int64_t g_len = (g_lo + G <= n) ? G : (n - g_lo);
+    const int64_t nch = (g_len + kGChunk - 1) / kGChunk;
+    const int64_t c0 = sl * kGSlice;
+    const int64_t cnt = c0 >= nch ? 0 : (nch - c0 < kGSlice ? nch - c0 : kGSlice);
+    reduce_range_rows(reinterpret_cast<const float *>(ranges + g * chunks_per_group + c0), cnt, part);
+    if (threadIdx.x < 32)
+        reinterpret_cast<float *>(slice_ranges + g * slices_per_group + sl)[threadIdx.x] = part[threadIdx.x];
 }
 
-__global__ __launch_bounds__(kGBlock) void general_code_kernel(const float *__restrict__ x, int64_t n, int64_t G,
-                                                               int64_t chunks_per_group, int64_t chunks,
-                                                               const GroupState *__restrict__ gs,
-                                                               const uint8_t *__restrict__ labels,
-                                                               uint8_t *__restrict__ codes)
+// One workgroup per group: slices -> min / max of every cluster -> (S, b), 255/S (Algorithm 2 step 4).
+__global__ __launch_bounds__(kGBlock) void wide_params_kernel(int64_t n, int64_t G, int64_t slices_per_group,
+                                                              int64_t groups, int m,
+                                                              const ChunkRanges *__restrict__ slice_ranges, GroupState *gs,
+                                                              float *__restrict__ params)
 {
-    __shared__ float2 coder[kGMaxClusters];
-    for (int64_t c = blockIdx.x; c < chunks; c += gridDim.x) {
-        const ChunkRef r = chunk_ref(c, n, G, chunks_per_group);
-        __syncthreads();
-        if (threadIdx.x < kGMaxClusters)
-            coder[threadIdx.x] = gs[r.group].coder[threadIdx.x];
-        __syncthreads();
-        for (int e = threadIdx.x; e < r.len; e += kGBlock) {
-            const int64_t idx = r.lo + e;
-            const int l = (labels[idx >> 1] >> (4 * (int)(idx & 1))) & 15;
-            const float2 bi = coder[l];
-            const float y = __fmul_rn(__fsub_rn(x[idx], bi.x), bi.y);
-            codes[idx] = (uint8_t)__builtin_amdgcn_cvt_pk_u8_f32(y, 0, 0u);  // rint, saturate, NaN -> 0
-        }
-    }
-}
-
-__global__ __launch_bounds__(kGBlock) void general_dequantize_kernel(const uint8_t *__restrict__ codes,
-                                                                     const uint8_t *__restrict__ labels,
-                                                                     const float *__restrict__ params, int64_t n,
-                                                                     int64_t G, int64_t chunks_per_group, int64_t chunks,
-                                                                     int m, float *__restrict__ out)
-{
-    __shared__ float2 coder[kGMaxClusters];  // (S/255, b)
-    for (int64_t c = blockIdx.x; c < chunks; c += gridDim.x) {
-        const ChunkRef r = chunk_ref(c, n, G, chunks_per_group);
-        __syncthreads();
-        if (threadIdx.x < kGMaxClusters) {
-            float2 sb = make_float2(0.0f, 0.0f);
+    __shared__ float part[kGBlock];
+    for (int64_t g = blockIdx.x; g < groups; g += gridDim.x) {
+        const int64_t g_lo = g * G;
+        const int64_t g_len = (g_lo + G <= n) ? G : (n - g_lo);
+        const int64_t nch = (g_len + kGChunk - 1) / kGChunk;
+        const int64_t nsl = (nch + kGSlice - 1) / kGSlice;
+        reduce_range_rows(reinterpret_cast<const float *>(slice_ranges + g * slices_per_group), nsl, part);
+        if (threadIdx.x < kMaxClusters) {
+            float S, b, inv;
+            cluster_coder(part[threadIdx.x], part[kMaxClusters + threadIdx.x], S, b, inv);
+            gs[g].coder[threadIdx.x] = make_float2(b, inv);
             if ((int)threadIdx.x < m)
-                sb = *reinterpret_cast<const float2 *>(params + (r.group * m + threadIdx.x) * 2);
-            coder[threadIdx.x] = make_float2(__fdiv_rn(sb.x, 255.0f), sb.y);
-        }
-        __syncthreads();
-        for (int e = threadIdx.x; e < r.len; e += kGBlock) {
-            const int64_t idx = r.lo + e;
-            const int l = (labels[idx >> 1] >> (4 * (int)(idx & 1))) & 15;
-            const float2 sb = coder[l];
-            out[idx] = __fadd_rn(__fmul_rn((float)codes[idx], sb.x), sb.y);
+                *reinterpret_cast<float2 *>(params + (g * m + threadIdx.x) * 2) = make_float2(S, b);
         }
     }
 }
 
-static void general_shape(int64_t n, int64_t group, int64_t &G, int64_t &groups, int64_t &cpg, int64_t &chunks)
+// ---- pass 3
+template <bool kFull>
+__device__ __forceinline__ void chunk_codes(const float *__restrict__ x, const ChunkRef &r, int m, const GroupState &st,
+                                            WaveShared &ws, int lane, uint8_t *__restrict__ labels,
+                                            uint8_t *__restrict__ codes)
+{
+    float4 v[kGK];
+    load_elements<kGK, kFull>(x, r.lo, r.len, lane, v);
+    if (lane < kMaxClusters)
+        ws.coder[lane] = st.coder[lane];
+    float edge;
+    const LabelSearch ls = build_search(st.mu, st.sigma, m, ws, lane, edge);
+    uint32_t packed[(kGK + 1) / 2];
+    label_pass<kGK, kFull, true, false>(v, r.lo, r.len, ls, ws, lane, labels, packed);
+    code_pass<kGK, kFull>(v, r.lo, r.len, packed, ws, lane, codes);
+}
+
+__global__ __launch_bounds__(kGBlock) void wide_code_kernel(const float *__restrict__ x, int64_t n, int64_t G,
+                                                            int64_t chunks_per_group, int64_t chunks, int m,
+                                                            const GroupState *__restrict__ gs, uint8_t *__restrict__ labels,
+                                                            uint8_t *__restrict__ codes)
+{
+    __shared__ WaveShared shared[kGWaves];
+    const int lane = threadIdx.x & (kWave - 1), wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int64_t c = (int64_t)blockIdx.x * kGWaves + wave;
+    if (c >= chunks)
+        return;
+    const ChunkRef r = chunk_ref(c, n, G, chunks_per_group);
+    if (r.len == 0)
+        return;
+    if (chunk_is_full(r))
+        chunk_codes<true>(x, r, m, gs[r.group], shared[wave], lane, labels, codes);
+    else
+        chunk_codes<false>(x, r, m, gs[r.group], shared[wave], lane, labels, codes);
+}
+
+__global__ __launch_bounds__(kGBlock) void wide_dequantize_kernel(const uint8_t *__restrict__ codes,
+                                                                  const uint8_t *__restrict__ labels,
+                                                                  const float *__restrict__ params, int64_t n, int64_t G,
+                                                                  int64_t chunks_per_group, int64_t chunks, int m,
+                                                                  float *__restrict__ out)
+{
+    __shared__ float2 coder[kGWaves][kMaxClusters];
+    const int lane = threadIdx.x & (kWave - 1), wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int64_t c = (int64_t)blockIdx.x * kGWaves + wave;
+    if (c >= chunks)
+        return;
+    const ChunkRef r = chunk_ref(c, n, G, chunks_per_group);
+    if (r.len == 0)
+        return;
+    dequantize_group<kGK>(codes, labels, params, r.lo, r.len, (r.lo & 3) == 0, m, r.group, out, coder[wave], lane);
+}
+
+static void general_shape(int64_t n, int64_t group, int64_t &G, int64_t &groups, int64_t &cpg, int64_t &chunks,
+                          int64_t &spg)
 {
     G = (group <= 0 || group > n) ? n : group;
     groups = (n + G - 1) / G;
     cpg = (G + kGChunk - 1) / kGChunk;
     chunks = groups * cpg;
+    spg = (cpg + kGSlice - 1) / kGSlice;
 }
 
 bool cluster_general_supported(int64_t n, int64_t group)
@@ -301,9 +380,10 @@ size_t cluster_general_workspace_bytes(int64_t n, int64_t group)
 {
     if (n <= 0)
         return 0;
-    int64_t G, groups, cpg, chunks;
-    general_shape(n, group, G, groups, cpg, chunks);
-    const size_t bytes = (size_t)groups * sizeof(GroupState) + (size_t)chunks * sizeof(double);
+    int64_t G, groups, cpg, chunks, spg;
+    general_shape(n, group, G, groups, cpg, chunks, spg);
+    const size_t bytes = (size_t)groups * sizeof(GroupState) +
+                         (size_t)(chunks + groups * spg) * (sizeof(ChunkStats) + sizeof(ChunkRanges));
     return (bytes + 255) / 256 * 256;
 }
 
@@ -317,32 +397,39 @@ int cluster_general_quantize(const float *x, int64_t n, int64_t group, int m, ui
                              float *params, float *fit_out, const float *fit_in, uint32_t *status, void *workspace,
                              hipStream_t s)
 {
-    int64_t G, groups, cpg, chunks;
-    general_shape(n, group, G, groups, cpg, chunks);
+    int64_t G, groups, cpg, chunks, spg;
+    general_shape(n, group, G, groups, cpg, chunks, spg);
+    const int64_t blocks = (chunks + kGWaves - 1) / kGWaves, slices = groups * spg;
+    if (blocks > 0x7FFFFFFF || slices > 0x7FFFFFFF)
+        return BITSNAP_E_SIZE;
+    static_assert(sizeof(GroupState) % 8 == 0 && sizeof(ChunkStats) % 8 == 0, "workspace parts stay 8-byte aligned");
     GroupState *gs = reinterpret_cast<GroupState *>(workspace);
-    double *partial = reinterpret_cast<double *>(gs + groups);
-    const dim3 block(kGBlock), cgrid(general_grid(chunks)), ggrid(general_grid(groups));
-    hipLaunchKernelGGL(general_partial_kernel<false>, cgrid, block, 0, s, x, n, G, cpg, chunks, gs, partial);
-    hipLaunchKernelGGL(general_finalize_fit_kernel, ggrid, block, 0, s, 0, n, G, cpg, groups, m, partial, gs, fit_out,
-                       fit_in, status);
-    hipLaunchKernelGGL(general_partial_kernel<true>, cgrid, block, 0, s, x, n, G, cpg, chunks, gs, partial);
-    hipLaunchKernelGGL(general_finalize_fit_kernel, ggrid, block, 0, s, 1, n, G, cpg, groups, m, partial, gs, fit_out,
-                       fit_in, status);
-    hipLaunchKernelGGL(general_label_kernel, cgrid, block, 0, s, x, n, G, cpg, chunks, gs, labels);
-    const int64_t pthreads = groups * kGMaxClusters;
-    hipLaunchKernelGGL(general_finalize_params_kernel, dim3((unsigned)((pthreads + kGBlock - 1) / kGBlock)), block, 0, s,
-                       groups, m, gs, params);
-    hipLaunchKernelGGL(general_code_kernel, cgrid, block, 0, s, x, n, G, cpg, chunks, gs, labels, codes);
+    ChunkStats *stats = reinterpret_cast<ChunkStats *>(gs + groups);
+    ChunkStats *slice_stats = stats + chunks;
+    ChunkRanges *ranges = reinterpret_cast<ChunkRanges *>(slice_stats + slices);
+    ChunkRanges *slice_ranges = ranges + chunks;
+    const dim3 block(kGBlock), cgrid((unsigned)blocks), sgrid((unsigned)slices), ggrid(general_grid(groups));
+    hipLaunchKernelGGL(wide_stats_kernel, cgrid, block, 0, s, x, n, G, cpg, chunks, stats);
+    hipLaunchKernelGGL(wide_slice_stats_kernel, sgrid, block, 0, s, n, G, cpg, spg, groups, stats, slice_stats);
+    hipLaunchKernelGGL(wide_fit_kernel, ggrid, block, 0, s, n, G, spg, groups, m, slice_stats, gs, fit_out, fit_in,
+                       status);
+    hipLaunchKernelGGL(wide_range_kernel, cgrid, block, 0, s, x, n, G, cpg, chunks, m, gs, ranges);
+    hipLaunchKernelGGL(wide_slice_ranges_kernel, sgrid, block, 0, s, n, G, cpg, spg, groups, ranges, slice_ranges);
+    hipLaunchKernelGGL(wide_params_kernel, ggrid, block, 0, s, n, G, spg, groups, m, slice_ranges, gs, params);
+    hipLaunchKernelGGL(wide_code_kernel, cgrid, block, 0, s, x, n, G, cpg, chunks, m, gs, labels, codes);
     return launch_status();
 }
 
 int cluster_general_dequantize(const uint8_t *codes, const uint8_t *labels, const float *params, int64_t n,
                                int64_t group, int m, float *out, hipStream_t s)
 {
-    int64_t G, groups, cpg, chunks;
-    general_shape(n, group, G, groups, cpg, chunks);
-    hipLaunchKernelGGL(general_dequantize_kernel, dim3(general_grid(chunks)), dim3(kGBlock), 0, s, codes, labels, params,
-                       n, G, cpg, chunks, m, out);
+    int64_t G, groups, cpg, chunks, spg;
+    general_shape(n, group, G, groups, cpg, chunks, spg);
+    const int64_t blocks = (chunks + kGWaves - 1) / kGWaves;
+    if (blocks > 0x7FFFFFFF)
+        return BITSNAP_E_SIZE;
+    hipLaunchKernelGGL(wide_dequantize_kernel, dim3((unsigned)blocks), dim3(kGBlock), 0, s, codes, labels, params, n, G,
+                       cpg, chunks, m, out);
     return launch_status();
 }
 

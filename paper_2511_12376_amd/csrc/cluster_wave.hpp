@@ -8,6 +8,7 @@
 //   label_pass      steps 3-4: labels (packed, optionally stored), per-cluster min/max in LDS
 //   reduce_ranges   step 4: min and max of every cluster over the wave's elements
 //   code_pass       steps 5-6: codes, stored
+//   dequantize_group  the inverse
 //
 // The one-wave-per-group kernels run all of them on one group; the wide-group kernels (a group
 // spans many waves) run them in three passes with the group's state in a workspace.
@@ -383,6 +384,60 @@ __device__ __forceinline__ void code_pass(const float4 (&v)[K], int64_t lo, int 
         }
     }
     wave_lds_sync();  // this wave may go on to other elements and rewrite the tables
+}
+
+// Dequantisation (x^ = q * (S/255) + b, product and sum rounded separately) of len <= 256*K
+// consecutive elements of group g by one wave: codes[lo..lo+len) -> out[lo..lo+len).  `aligned`:
+// lo is a multiple of 4, so four elements are one 4-byte, 2-byte and 16-byte access.
+template <int K>
+__device__ __forceinline__ void dequantize_group(const uint8_t *__restrict__ codes, const uint8_t *__restrict__ labels,
+                                                 const float *__restrict__ params, int64_t lo, int len, bool aligned,
+                                                 int m, int64_t g, float *__restrict__ out, float2 *coder, int lane)
+{
+    // codes and labels are requested first, the 16 (S, b) pairs next: one memory latency, not two
+    uint32_t c4[K], l4[K];
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        const int off = k * 256 + lane * 4;
+        c4[k] = 0, l4[k] = 0;
+        if (aligned && off + 3 < len) {
+            c4[k] = __builtin_nontemporal_load((const BITSNAP_GLOBAL uint32_t *)(global_ptr(codes) + lo + off));
+            l4[k] = __builtin_nontemporal_load((const BITSNAP_GLOBAL uint16_t *)(global_ptr(labels) + ((lo + off) >> 1)));
+        } else {
+            for (int j = 0; j < 4; ++j)
+                if (off + j < len) {
+                    c4[k] |= (uint32_t)global_ptr(codes)[lo + off + j] << (8 * j);
+                    l4[k] |= (uint32_t)((global_ptr(labels)[(lo + off + j) >> 1] >> (4 * ((lo + off + j) & 1))) & 15u) << (4 * j);
+                }
+        }
+    }
+    if (lane < kMaxClusters) {
+        float2 sb = make_float2(0.0f, 0.0f);
+        if (lane < m) {
+            const float2v t = *(const BITSNAP_GLOBAL float2v *)(global_ptr(params) + (g * m + lane) * 2);
+            sb = make_float2(t.x, t.y);
+        }
+        coder[lane] = make_float2(__fdiv_rn(sb.x, 255.0f), sb.y);  // (S/255, b)
+    }
+    wave_lds_sync();
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        const int off = k * 256 + lane * 4;
+        float r[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const float2 sb = coder[(l4[k] >> (4 * j)) & 15u];
+            r[j] = __fadd_rn(__fmul_rn((float)((c4[k] >> (8 * j)) & 255u), sb.x), sb.y);
+        }
+        if (aligned && off + 3 < len) {
+            __builtin_nontemporal_store(float4v{r[0], r[1], r[2], r[3]}, (BITSNAP_GLOBAL float4v *)(global_ptr(out) + lo + off));
+        } else {
+            for (int j = 0; j < 4; ++j)
+                if (off + j < len)
+                    global_ptr(out)[lo + off + j] = r[j];
+        }
+    }
+    wave_lds_sync();  // the coder table may be rewritten by this wave's next group
 }
 
 }  // namespace bitsnap

@@ -89,6 +89,17 @@ def test_other_group_lengths_and_whole_tensor(n, G, m):
     _compare(x, G, m)
 
 
+@pytest.mark.parametrize("n,G", [(3_000_007, 0), (3_000_007, 1_400_002), (2_500_000, 1_250_000), (1_100_000, 0)])
+def test_wide_groups_span_several_slices(n, G):
+    """Groups of more than 256 chunks of 4096 elements (their chunk results are combined in two levels),
+    with a ragged last chunk, and with group starts that are not 16-byte aligned (G % 4 == 2)."""
+    announce("cluster wide groups", n, G)
+    rng = np.random.default_rng(n % 1000 + G % 1000)
+    x = (rng.standard_normal(n) * 2e-3 + rng.standard_normal() * 1e-3).astype(np.float32)
+    x[::977] *= 6.0                                               # some elements far out in the tails
+    _compare(x, G, 16)
+
+
 def test_whole_tensor_fit_on_config0():
     cfg = synth.config(0)
     for t in (2, 4, 27):
