@@ -230,6 +230,26 @@ def main():
         "what": "group = 0 (one fit per tensor), first-moment state, one call per tensor, 3 passes over x",
         "ms": round(whole_ms, 3), "api_calls": len(gcalls), "state_GBps": round(4 * n_total / whole_ms / 1e6, 1),
         "hbm_GBps": round(whole_alg / whole_ms / 1e6, 1), "hbm_frac": round(whole_alg / whole_ms / 1e6 / HBM_PEAK_GBS, 4)}}
+    # steady state on the single largest tensor: each op alone, five calls in a row
+    big = max(range(len(sizes)), key=lambda i: sizes[i])
+    nb = sizes[big]
+    largest_ms = {}
+    for op in order:
+        call = calls[op][big if op.endswith("sparse") else 3 * big]
+        fn = getattr(L, "bitsnap_" + op)
+        for it in range(2):
+            e0.record(stream)
+            for _ in range(5):
+                fn(*call)
+            e1.record(stream)
+            torch.cuda.synchronize()
+        largest_ms[op] = e0.elapsed_time(e1) / 5
+    nc_big = int(enc[big]["n_changed"].item())
+    big_alg = {"encode_sparse": 4 * nb + (nb + 7) // 8 + 2 * nc_big, "decode_sparse": 4 * nb + (nb + 7) // 8 + 2 * nc_big,
+               "quantize_cluster": 5 * nb + (nb + 1) // 2 + B.cluster_groups(nb, GROUP) * M * 8,
+               "dequantize_cluster": 5 * nb + (nb + 1) // 2 + B.cluster_groups(nb, GROUP) * M * 8}
+    extras["largest_tensor"] = {"elements": nb, "ops": {op: {"ms": round(largest_ms[op], 4),
+                                "hbm_frac": round(big_alg[op] / largest_ms[op] / 1e6 / HBM_PEAK_GBS, 4)} for op in order}}
     # the step's own codes of that state, for whoever looks at the buffers afterwards
     for a in (c for k, c in enumerate(calls["quantize_cluster"]) if k % 3 == 1):
         L.bitsnap_quantize_cluster(*a)

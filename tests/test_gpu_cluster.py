@@ -277,3 +277,51 @@ def test_batched_equals_single_tensor_calls():
             assert np.array_equal(to_np(codes[k]), o["codes"]) and np.array_equal(to_np(labels[k]), o["labels"])
             assert np.array_equal(to_np(params[k]), o["params"])
             assert np.array_equal(to_np(outs[k]), oracle.dequantize_cluster(o["codes"], o["labels"], o["params"], sizes[k], G, m))
+
+
+def test_full_size_batched_pass_sampled():
+    """The launch configuration the benchmark reports: ONE batched launch per state over a list of 7B-shaped
+    tensors, Adam-recipe first and second moments.  The oracle recomputes sampled groups of every tensor; the
+    error bound of the method is checked on whole tensors on the device."""
+    announce("cluster full size batched")
+    cfg = synth.config(2)
+    picks = [0, 1, 2, 5, 9, 4]
+    for key in ("m", "v"):
+        xs = [synth.make_tensor_torch(cfg, t, DEV, adam_steps=12, want=(key,))[key] for t in picks]
+        sizes = [x.numel() for x in xs]
+        codes = [torch.empty(n, dtype=torch.uint8, device=DEV) for n in sizes]
+        labels = [torch.empty((n + 1) // 2, dtype=torch.uint8, device=DEV) for n in sizes]
+        params = [torch.empty(B.cluster_groups(n, 4096), 16, 2, dtype=torch.float32, device=DEV) for n in sizes]
+        fits = [torch.empty(B.cluster_groups(n, 4096), 17, dtype=torch.float32, device=DEV) for n in sizes]
+        status = torch.zeros(1, dtype=torch.int32, device=DEV)
+        items, total = B.cluster_items(xs, codes, labels, params, 4096, fit_out=fits)
+        B.quantize_cluster_batched(items, total, 4096, 16, status)
+        outs = [torch.empty(n, dtype=torch.float32, device=DEV) for n in sizes]
+        ditems, _ = B.cluster_items(outs, codes, labels, params, 4096)
+        B.dequantize_cluster_batched(ditems, total, 4096, 16)
+        torch.cuda.synchronize()
+        assert int(status.item()) == 0
+        rng = np.random.default_rng(11)
+        differ = checked = 0
+        for k, n in enumerate(sizes):
+            groups = n // 4096
+            for g in sorted(set([0, groups - 1] + list(rng.integers(0, groups, 8)))):
+                lo, hi = g * 4096, (g + 1) * 4096
+                xg, fit_g = to_np(xs[k][lo:hi]), to_np(fits[k][g])
+                o = oracle.quantize_cluster(xg, 4096, 16)
+                assert abs(float(fit_g[1]) - float(o["fit"][0, 1])) <= 1e-6 * float(o["fit"][0, 1])
+                assert abs(float(fit_g[0]) - float(o["fit"][0, 0])) <= 1e-6 * max(abs(float(o["fit"][0, 0])), float(o["fit"][0, 1]))
+                checked += 1
+                if not np.array_equal(fit_g[:2], o["fit"][0, :2]):
+                    differ += 1
+                    o = oracle.quantize_cluster(xg, 4096, 16, fit_in=fit_g[:2].copy())
+                assert np.array_equal(fit_g, o["fit"][0])
+                assert np.array_equal(to_np(params[k][g]), o["params"][0])
+                assert np.array_equal(to_np(codes[k][lo:hi]), o["codes"])
+                assert np.array_equal(to_np(labels[k][lo // 2:hi // 2]), o["labels"])
+                assert np.array_equal(to_np(outs[k][lo:hi]), oracle.dequantize_cluster(o["codes"], o["labels"], o["params"], 4096, 4096, 16))
+            lab = torch.stack([labels[k] & 15, labels[k] >> 4], dim=1).reshape(-1).long()
+            S = params[k][:, :, 0].reshape(-1)[torch.arange(n, device=DEV) // 4096 * 16 + lab]
+            err = (outs[k].double() - xs[k].double()).abs()
+            assert bool((err <= S.double() / 510 + 5e-7 * (xs[k].abs().double() + S.double())).all())
+        assert differ <= max(1, checked // 20)

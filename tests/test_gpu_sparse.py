@@ -235,3 +235,44 @@ def test_batched_equals_oracle_per_tensor():
     enc = B.encode_sparse(cur[3], base[3], workspace=ws)
     torch.cuda.synchronize()
     assert int(enc.n_changed.item()) == int(counts[3].item())
+
+
+def test_full_size_batched_pass_sampled():
+    """The launch configuration the benchmark reports: ONE batched launch over a list of 7B-shaped tensors
+    (the 131 M-element embedding, 16.8 M and 45 M matrices, 4096-element norms between them), Adam-recipe
+    change pattern.  Whole tensors are checked through properties on the device; the oracle recomputes
+    sampled tiles of every tensor."""
+    announce("sparse full size batched")
+    cfg = synth.config(2)
+    picks = [0, 1, 2, 3, 5, 8, 9, 4]                               # embedding, attention and MLP matrices, norms
+    data = [synth.make_tensor_torch(cfg, t, DEV, adam_steps=12, want=("base", "cur")) for t in picks]
+    sizes = [d["cur"].numel() for d in data]
+    cur, base = [d["cur"] for d in data], [d["base"] for d in data]
+    mask = [torch.empty(B.sparse_mask_bytes(n), dtype=torch.uint8, device=DEV) for n in sizes]
+    payload = [torch.empty(n, dtype=torch.int16, device=DEV) for n in sizes]
+    counts = [torch.zeros(1, dtype=torch.int64, device=DEV) for _ in sizes]
+    offs = [torch.zeros((n + T - 1) // T, dtype=torch.int32, device=DEV) for n in sizes]
+    items, total = B.sparse_items(sizes, src=cur, base=base, mask=mask, payload=payload, n_changed=counts, tile_offsets=offs)
+    ws = torch.zeros(B.sparse_batch_workspace_bytes(total), dtype=torch.uint8, device=DEV)
+    B.encode_sparse_batched(items, total, ws)
+    out = [torch.empty(n, dtype=torch.bfloat16, device=DEV) for n in sizes]
+    dcounts = [torch.zeros(1, dtype=torch.int64, device=DEV) for _ in sizes]
+    ditems, _ = B.sparse_items(sizes, base=base, mask=mask, payload=payload, out=out, n_changed=dcounts)
+    B.decode_sparse_batched(ditems, total, ws)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(5)
+    for k, n in enumerate(sizes):
+        c16, b16 = cur[k].view(torch.int16), base[k].view(torch.int16)
+        changed = c16 != b16
+        nc = int(changed.sum().item())
+        assert nc == int(counts[k].item()) == int(dcounts[k].item())
+        assert 0 < nc < n
+        assert torch.equal(out[k].view(torch.int16), c16)          # lossless at full size
+        assert torch.equal(payload[k][:nc], c16[changed])          # the changed values, in index order
+        ntiles = (n + T - 1) // T
+        o = to_np(offs[k]).view(np.uint32).astype(np.int64)
+        for t in sorted(set([0, ntiles - 1] + list(rng.integers(0, ntiles, 6)))):
+            lo, hi = t * T, min(n, (t + 1) * T)
+            o_mask, o_pay, o_nc = oracle.encode_sparse(c16[lo:hi].cpu().numpy().view(np.uint16), b16[lo:hi].cpu().numpy().view(np.uint16))
+            assert np.array_equal(to_np(mask[k][lo // 8:lo // 8 + o_mask.size]), o_mask)
+            assert np.array_equal(to_np(payload[k][o[t]:o[t] + o_nc]).view(np.uint16), o_pay)
