@@ -208,6 +208,25 @@ def main():
             torch.cuda.synchronize()
         copy_gbps = 5 * 2 * cal_bytes / (e0.elapsed_time(e1) * 1e-3) / 1e9
 
+    # what the memory system leaves to win for the cluster codecs: the same bytes in the same pattern, no arithmetic
+    mix_n = min(n_max, 1 << 28) // 4096 * 4096
+    mix_ceiling = None
+    if mix_n > 0:
+        mix_b = torch.empty(mix_n, dtype=u8, device=dev)
+        mix_h = torch.empty(mix_n // 2, dtype=u8, device=dev)
+        mix_w = deq_ring[2][:mix_n]
+        mix_ceiling = {}
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        for name, to_small in (("quantize_cluster", True), ("dequantize_cluster", False)):
+            for it in range(2):
+                e0.record(stream)
+                for _ in range(5):
+                    B.debug_stream_mix(mix_w, mix_b, mix_h, to_small)
+                e1.record(stream)
+                torch.cuda.synchronize()
+            mix_ceiling[name] = round(5 * 5.5 * mix_n / (e0.elapsed_time(e1) * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
+        del mix_b, mix_h
+
     # ------------------------------------------------------------------ beside the step: one fit per tensor
     # (group = 0, Algorithm 2 as the paper states it) on the first-moment state, one call per tensor;
     # three passes over the tensor instead of one, codes and labels into the same buffers
@@ -250,6 +269,24 @@ def main():
                "dequantize_cluster": 5 * nb + (nb + 1) // 2 + B.cluster_groups(nb, GROUP) * M * 8}
     extras["largest_tensor"] = {"elements": nb, "ops": {op: {"ms": round(largest_ms[op], 4),
                                 "hbm_frac": round(big_alg[op] / largest_ms[op] / 1e6 / HBM_PEAK_GBS, 4)} for op in order}}
+    # quantisation error on these synthetic Adam states, next to plain min-max 8-bit (one cluster): the
+    # comparison the paper's evaluation makes on trained states (its table of MRE and MSE against naive
+    # 8-bit quantisation); torch only computes the two error measures
+    def quality(x, group, m):
+        q = B.quantize_cluster(x, group, m)
+        xh = B.dequantize_cluster(q.codes, q.labels, q.params, x.numel(), group, m)
+        err = (xh.double() - x.double())
+        nz = x != 0
+        return {"MSE": float((err * err).mean().item()),
+                "MRE": float((err[nz].abs() / x[nz].double().abs()).mean().item())}
+    sample = min(range(len(sizes)), key=lambda i: abs(sizes[i] - 11008 * 4096))
+    extras["quantisation_error_synthetic"] = {
+        "tensor": cfg.tensors[tensors[sample]][0], "elements": sizes[sample],
+        "rows": {f"{state} {label}": quality(inputs[sample][key], group, m)
+                 for state, key in (("adam1", "m"), ("adam2", "v"))
+                 for label, group, m in (("16 clusters per 4096-element group", GROUP, M),
+                                         ("16 clusters per tensor", 0, M),
+                                         ("naive 8-bit (1 cluster per tensor)", 0, 1))}}
     # the step's own codes of that state, for whoever looks at the buffers afterwards
     for a in (c for k, c in enumerate(calls["quantize_cluster"]) if k % 3 == 1):
         L.bitsnap_quantize_cluster(*a)
@@ -306,6 +343,7 @@ def main():
                       "state_bytes_per_step": total_state, "generation_s": round(gen_s, 1)},
            "hbm_frac_of_peak": {op: ops[op]["hbm_frac"] for op in order},
            "copy_kernel_GBps": None if copy_gbps is None else round(copy_gbps, 1), "copy_kernel_bytes_each_way": cal_bytes,
+           "streaming_ceiling_frac_of_peak": mix_ceiling,
            "ops": ops, "extras": extras, "roofline": roofline}
 
     if not args.no_cpu_baseline:

@@ -51,6 +51,15 @@ const char *bitsnap_error_string(int code);
  * for HBM byte counters and for what a kernel without dependencies sustains on the same device. */
 int bitsnap_debug_stream_copy(void *dst, const void *src, int64_t bytes, bitsnap_stream_t stream);
 
+/* Diagnostic: streaming traffic with the byte mix and access pattern of the cluster codecs and
+ * next to no arithmetic, i.e. what the memory system leaves to win for those kernels.
+ *   wide [n] fp32, bytes [n], halves [n/2]: device buffers, aligned; n a multiple of 4096
+ *   to_small != 0: reads wide, writes bytes and halves (quantize_cluster's 4 : 1.5 traffic)
+ *   to_small == 0: reads bytes and halves, writes wide (dequantize_cluster's 1.5 : 4 traffic)
+ * The values written are meaningless. */
+int bitsnap_debug_stream_mix(void *wide, void *bytes, void *halves, int64_t n, int to_small,
+                             bitsnap_stream_t stream);
+
 /* ------------------------------------------------------------------------------------------
  * Sparse path.  Paper: "Bitmask Based Sparsification for Model States" (improved bitmask,
  * space n/8 + 2 n_c, Eq. improved-bitmask) and Algorithm 1.

@@ -16,7 +16,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libbitsnap.so")
 
 SYMBOLS = (
-    "bitsnap_version", "bitsnap_error_string", "bitsnap_debug_stream_copy",
+    "bitsnap_version", "bitsnap_error_string", "bitsnap_debug_stream_copy", "bitsnap_debug_stream_mix",
     "bitsnap_sparse_tile_elems", "bitsnap_sparse_mask_bytes", "bitsnap_sparse_workspace_bytes",
     "bitsnap_encode_sparse", "bitsnap_decode_sparse", "bitsnap_debug_set_spin_limit",
     "bitsnap_cluster_groups", "bitsnap_cluster_param_bytes", "bitsnap_cluster_label_bytes",
@@ -49,6 +49,7 @@ def lib():
     L.bitsnap_version.argtypes, L.bitsnap_version.restype = [], i
     L.bitsnap_error_string.argtypes, L.bitsnap_error_string.restype = [i], C.c_char_p
     L.bitsnap_debug_stream_copy.argtypes, L.bitsnap_debug_stream_copy.restype = [p, p, i64, p], i
+    L.bitsnap_debug_stream_mix.argtypes, L.bitsnap_debug_stream_mix.restype = [p, p, p, i64, i, p], i
     L.bitsnap_sparse_tile_elems.argtypes, L.bitsnap_sparse_tile_elems.restype = [], sz
     L.bitsnap_sparse_mask_bytes.argtypes, L.bitsnap_sparse_mask_bytes.restype = [i64], sz
     L.bitsnap_sparse_workspace_bytes.argtypes, L.bitsnap_sparse_workspace_bytes.restype = [i64], sz
@@ -147,6 +148,14 @@ def debug_stream_copy(dst, src, stream=None) -> None:
     nbytes = src.numel() * src.element_size()
     assert dst.numel() * dst.element_size() == nbytes
     _check(lib().bitsnap_debug_stream_copy(_ptr(dst), _ptr(src), nbytes, _stream(stream)), "bitsnap_debug_stream_copy")
+
+
+def debug_stream_mix(wide, small_bytes, small_halves, to_small: bool, stream=None) -> None:
+    """Streaming traffic with the cluster codecs' byte mix (wide: fp32 [n]; bytes [n]; halves [n/2])."""
+    n = wide.numel()
+    assert small_bytes.numel() == n and small_halves.numel() * 2 == n
+    _check(lib().bitsnap_debug_stream_mix(_ptr(wide), _ptr(small_bytes), _ptr(small_halves), n, int(bool(to_small)),
+                                          _stream(stream)), "bitsnap_debug_stream_mix")
 
 
 def new_sparse_workspace(n: int, device):

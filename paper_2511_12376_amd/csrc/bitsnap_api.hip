@@ -12,7 +12,73 @@ __global__ __launch_bounds__(256) void stream_copy_kernel(const uint4 *__restric
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride)
         dst[i] = src[i];
 }
+
+// Streaming kernels with the byte mix and the access pattern of the cluster codecs and next to
+// no arithmetic: one wave per 4096 elements, 16 bytes of fp32 per lane and access, non-temporal.
+//   to_small: reads 4 bytes per element, writes 1 + 1/2      (quantize_cluster's traffic)
+//   else:     reads 1 + 1/2 bytes per element, writes 4      (dequantize_cluster's traffic)
+typedef float mix_float4 __attribute__((ext_vector_type(4)));
+#define BITSNAP_MIX_GLOBAL __attribute__((address_space(1)))
+template <bool kToSmall>
+__global__ __launch_bounds__(256) void stream_mix_kernel(float *wide, uint8_t *bytes, uint8_t *halves, int64_t groups)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t g = (int64_t)blockIdx.x * 4 + wave;
+    if (g >= groups)
+        return;
+    const int64_t lo = g * 4096;
+    if (kToSmall) {
+        mix_float4 v[16];
+#pragma unroll
+        for (int k = 0; k < 16; ++k)
+            v[k] = __builtin_nontemporal_load((const BITSNAP_MIX_GLOBAL mix_float4 *)(wide + lo + k * 256 + lane * 4));
+#pragma unroll
+        for (int k = 0; k < 16; ++k) {
+            const uint32_t c4 = __float_as_uint(v[k].x) ^ __float_as_uint(v[k].y) ^ __float_as_uint(v[k].z) ^ __float_as_uint(v[k].w);
+            __builtin_nontemporal_store(c4, (BITSNAP_MIX_GLOBAL uint32_t *)(bytes + lo + k * 256 + lane * 4));
+            __builtin_nontemporal_store((uint16_t)(c4 >> 7), (BITSNAP_MIX_GLOBAL uint16_t *)(halves + ((lo + k * 256 + lane * 4) >> 1)));
+        }
+    } else {
+        uint32_t c4[16], l4[16];
+#pragma unroll
+        for (int k = 0; k < 16; ++k) {
+            c4[k] = __builtin_nontemporal_load((const BITSNAP_MIX_GLOBAL uint32_t *)(bytes + lo + k * 256 + lane * 4));
+            l4[k] = __builtin_nontemporal_load((const BITSNAP_MIX_GLOBAL uint16_t *)(halves + ((lo + k * 256 + lane * 4) >> 1)));
+        }
+#pragma unroll
+        for (int k = 0; k < 16; ++k) {
+            mix_float4 r;
+            r.x = (float)(c4[k] & 255u) + (float)(l4[k] & 15u);
+            r.y = (float)((c4[k] >> 8) & 255u);
+            r.z = (float)((c4[k] >> 16) & 255u);
+            r.w = (float)(c4[k] >> 24);
+            __builtin_nontemporal_store(r, (BITSNAP_MIX_GLOBAL mix_float4 *)(wide + lo + k * 256 + lane * 4));
+        }
+    }
+}
 }  // namespace bitsnap
+
+extern "C" int bitsnap_debug_stream_mix(void *wide, void *bytes, void *halves, int64_t n, int to_small,
+                                        bitsnap_stream_t stream)
+{
+    if (n < 0 || (n % 4096) != 0 || n / 4096 / 4 + 1 > 0x7FFFFFFF)
+        return BITSNAP_E_SIZE;
+    if (n == 0)
+        return BITSNAP_OK;
+    if (!wide || !bytes || !halves)
+        return BITSNAP_E_NULL;
+    if (!bitsnap::aligned16(wide) || !bitsnap::aligned16(bytes) || !bitsnap::aligned16(halves))
+        return BITSNAP_E_ALIGN;
+    const int64_t groups = n / 4096;
+    const dim3 grid((unsigned)((groups + 3) / 4)), block(256);
+    if (to_small)
+        hipLaunchKernelGGL(bitsnap::stream_mix_kernel<true>, grid, block, 0, (hipStream_t)stream, (float *)wide,
+                           (uint8_t *)bytes, (uint8_t *)halves, groups);
+    else
+        hipLaunchKernelGGL(bitsnap::stream_mix_kernel<false>, grid, block, 0, (hipStream_t)stream, (float *)wide,
+                           (uint8_t *)bytes, (uint8_t *)halves, groups);
+    return bitsnap::launch_status();
+}
 
 extern "C" int bitsnap_debug_stream_copy(void *dst, const void *src, int64_t bytes, bitsnap_stream_t stream)
 {
