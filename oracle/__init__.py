@@ -43,6 +43,10 @@ def _load():
     L.oracle_tile_offsets.argtypes = [p, i64, i64, p]
     L.oracle_tile_offsets.restype = None
     L.oracle_decode_sparse.argtypes = [p, p, p, i64, p]
+    L.oracle_encode_sparse_ex.argtypes = [p, p, i64, C.c_int, p, p, p]
+    L.oracle_encode_sparse_ex.restype = i64
+    L.oracle_decode_sparse_ex.argtypes = [p, p, p, i64, C.c_int, p]
+    L.oracle_decode_sparse_ex.restype = None
     L.oracle_decode_sparse.restype = None
     L.oracle_norm_quantile.argtypes = [C.c_int, C.c_int]
     L.oracle_norm_quantile.restype = C.c_double
@@ -88,6 +92,31 @@ def encode_sparse(cur, base) -> Tuple[np.ndarray, np.ndarray, int]:
     payload = np.empty(max(n, 1), np.uint16)
     nc = _load().oracle_encode_sparse(_ptr(cur), _ptr(base), n, _ptr(mask), _ptr(payload))
     return mask, payload[:nc].copy(), int(nc)
+
+
+def encode_sparse_ex(cur, base, delta: bool = False, new_base=None) -> Tuple[np.ndarray, np.ndarray, int]:
+    """Extended form: delta payload (cur XOR base) and / or a copy of cur into new_base (a uint16 array, which
+    may be `base` itself).  -> (mask, payload[n_c], n_c)."""
+    cur = _u16(cur)
+    n = cur.size
+    assert base.dtype == np.uint16 and base.flags.c_contiguous and base.size == n
+    if new_base is not None:
+        assert new_base.dtype == np.uint16 and new_base.flags.c_contiguous and new_base.size == n
+    mask = np.empty((n + 7) // 8, np.uint8)
+    payload = np.empty(max(n, 1), np.uint16)
+    nc = _load().oracle_encode_sparse_ex(_ptr(cur), _ptr(base), n, int(bool(delta)), _ptr(mask), _ptr(payload),
+                                         None if new_base is None else _ptr(new_base))
+    return mask, payload[:nc].copy(), int(nc)
+
+
+def decode_sparse_ex(base, mask, payload, delta: bool = False) -> np.ndarray:
+    base, payload = _u16(base), _u16(payload)
+    mask = np.ascontiguousarray(mask, dtype=np.uint8)
+    n = base.size
+    out = np.empty(max(n, 1), np.uint16)
+    pay = payload if payload.size else np.zeros(1, np.uint16)
+    _load().oracle_decode_sparse_ex(_ptr(base), _ptr(mask), _ptr(pay), n, int(bool(delta)), _ptr(out))
+    return out[:n].copy()
 
 
 def encode_sparse_naive(cur, base) -> Tuple[np.ndarray, np.ndarray, int]:

@@ -99,6 +99,52 @@ void oracle_decode_sparse(const uint16_t *base, const uint8_t *mask, const uint1
     }
 }
 
+/* The same codec with the two options of the extended entry points.
+ *   delta != 0   the payload holds the non-zero elements of the delta states themselves, with
+ *                the delta of two 16-bit patterns taken as their bitwise difference cur XOR base
+ *                (the section's "save the bitmask list and the non-zero elements" read literally;
+ *                an arithmetic fp16/bf16 difference would not reconstruct bit for bit);
+ *                delta == 0 stores the new values, as oracle_encode_sparse does.
+ *   new_base     if not NULL, receives a copy of cur: the tensor becomes the base of the next
+ *                delta checkpoints.  It may be the very array `base` (each element is compared
+ *                before it is overwritten).
+ * Mask, count and order of the payload are those of oracle_encode_sparse. */
+int64_t oracle_encode_sparse_ex(const uint16_t *cur, const uint16_t *base, int64_t n, int delta,
+                                uint8_t *mask, uint16_t *payload, uint16_t *new_base)
+{
+    int64_t nc = 0;
+    int64_t nbytes = (n + 7) / 8;
+    for (int64_t j = 0; j < nbytes; ++j)
+        mask[j] = 0;
+    for (int64_t i = 0; i < n; ++i) {
+        const uint16_t c = cur[i], b = base[i];
+        if (c != b) {
+            mask[i >> 3] = (uint8_t)(mask[i >> 3] | (1u << (i & 7)));
+            payload[nc] = delta ? (uint16_t)(c ^ b) : c;
+            nc += 1;
+        }
+        if (new_base)
+            new_base[i] = c;
+    }
+    return nc;
+}
+
+/* Inverse: out[i] = changed ? (delta ? base[i] XOR next payload element : next payload element)
+ * : base[i]. */
+void oracle_decode_sparse_ex(const uint16_t *base, const uint8_t *mask, const uint16_t *payload,
+                             int64_t n, int delta, uint16_t *out)
+{
+    int64_t r = 0;
+    for (int64_t i = 0; i < n; ++i) {
+        if ((mask[i >> 3] >> (i & 7)) & 1u) {
+            out[i] = delta ? (uint16_t)(base[i] ^ payload[r]) : payload[r];
+            r += 1;
+        } else {
+            out[i] = base[i];
+        }
+    }
+}
+
 /* ------------------------------------------------------------------------------------------
  * Cluster path
  * ---------------------------------------------------------------------------------------- */

@@ -20,6 +20,9 @@ MUTANTS = [
     ("mask_msb_first", "(1u << (i & 7))", "(0x80u >> (i & 7))", 0),
     ("payload_takes_base", "payload[nc] = cur[i];", "payload[nc] = base[i];", 0),
     ("payload_stores_difference", "payload[nc] = cur[i];", "payload[nc] = (uint16_t)(cur[i] - base[i]);", 0),
+    ("delta_payload_is_sum", "payload[nc] = delta ? (uint16_t)(c ^ b) : c;", "payload[nc] = delta ? (uint16_t)(c + b) : c;", 0),
+    ("delta_decode_drops_base", "out[i] = delta ? (uint16_t)(base[i] ^ payload[r]) : payload[r];", "out[i] = payload[r];", 0),
+    ("new_base_only_where_changed", "        if (new_base)\n            new_base[i] = c;\n    }", "        if (new_base && c != b)\n            new_base[i] = c;\n    }", 0),
     ("offsets_inclusive", "off[t] = run;", "off[t] = run + 1;", 0),
     ("sample_std", "sqrt(q / (double)len)", "sqrt(q / (double)(len - 1))", 0),
     ("mean_not_subtracted", "double d = (double)x[i] - mean;", "double d = (double)x[i];", 0),
@@ -46,6 +49,8 @@ def _pins(golden):
     yield lambda: ts.test_mask_payload_offsets_against_library_routines(4097)
     yield lambda: ts.test_naive_mask_and_coo_crossovers(golden)
     yield ts.test_decode_uses_payload_in_order
+    yield lambda: ts.test_delta_payload_is_the_nonzero_part_of_the_bitwise_difference(4097, 0.06)
+    yield lambda: ts.test_new_base_is_a_copy_of_cur_also_in_place(True)
     yield lambda: tc.test_quantiles_are_correctly_rounded(16)
     yield tc.test_equal_probability_edges
     yield tc.test_fit_exact_on_integers
@@ -75,7 +80,7 @@ def test_planted_mistake_is_caught(tmp_path, name, find, repl, occ):
                    check=True)
     good = oracle._load()
     mut = ctypes.CDLL(str(lib))
-    for sym in ("oracle_encode_sparse", "oracle_encode_sparse_naive", "oracle_tile_offsets", "oracle_decode_sparse",
+    for sym in ("oracle_encode_sparse", "oracle_encode_sparse_ex", "oracle_decode_sparse_ex", "oracle_encode_sparse_naive", "oracle_tile_offsets", "oracle_decode_sparse",
                 "oracle_norm_quantile", "oracle_cluster_fit", "oracle_cluster_edges", "oracle_quantize_cluster",
                 "oracle_dequantize_cluster", "oracle_code_bruteforce"):
         getattr(mut, sym).argtypes = getattr(good, sym).argtypes

@@ -151,3 +151,50 @@ def test_decode_uses_payload_in_order():
     payload = np.array([100, 200, 300, 400], np.uint16)
     out = oracle.decode_sparse(base, mask, payload)
     assert out.tolist() == [10, 100, 12, 13, 200, 15, 16, 300, 18, 400]
+
+
+# Extended form -------------------------------------------------------------------------------
+@pytest.mark.parametrize("n", [0, 1, 9, 4097, 20001])
+@pytest.mark.parametrize("p", [0.0, 0.06, 1.0])
+def test_delta_payload_is_the_nonzero_part_of_the_bitwise_difference(n, p):
+    """Delta reading of the section ("save the bitmask list and the non-zero elements" of the delta states):
+    the flattened delta is cur XOR base, the payload its non-zero elements in order (numpy's boolean selection);
+    mask and count are those of the value form; decoding is lossless."""
+    cur, base, nsel = _pair(n, p, 5000 + n)
+    mask, payload, nc = oracle.encode_sparse_ex(cur, base, delta=True)
+    mask0, payload0, nc0 = oracle.encode_sparse(cur, base)
+    assert nc == nc0 == nsel and np.array_equal(mask, mask0)
+    delta = cur ^ base
+    assert np.array_equal(payload, delta[delta != 0])
+    assert not (payload == 0).any()                               # a stored delta is never zero
+    assert np.array_equal(payload ^ base[delta != 0], payload0)   # the two payloads differ by the base
+    assert np.array_equal(oracle.decode_sparse_ex(base, mask, payload, delta=True), cur)
+    if nc:                                                        # the forms are not interchangeable
+        assert not np.array_equal(oracle.decode_sparse_ex(base, mask, payload, delta=False), cur)
+
+
+def test_value_form_of_extended_calls_equals_the_plain_ones():
+    cur, base, _ = _pair(8193, 0.3, 77)
+    a = oracle.encode_sparse_ex(cur, base, delta=False)
+    b = oracle.encode_sparse(cur, base)
+    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1]) and a[2] == b[2]
+    assert np.array_equal(oracle.decode_sparse_ex(base, a[0], a[1], delta=False), oracle.decode_sparse(base, b[0], b[1]))
+
+
+@pytest.mark.parametrize("delta", [False, True])
+def test_new_base_is_a_copy_of_cur_also_in_place(delta):
+    """The tensor becomes the base of the following delta checkpoints: new_base == cur afterwards, the encoding
+    is the one against the OLD base, and new_base may be the base array itself."""
+    cur, base, _ = _pair(4097, 0.2, 91)
+    ref = oracle.encode_sparse_ex(cur, base, delta=delta)
+    fresh = np.zeros_like(cur)
+    a = oracle.encode_sparse_ex(cur, base, delta=delta, new_base=fresh)
+    assert np.array_equal(fresh, cur)
+    in_place = base.copy()
+    b = oracle.encode_sparse_ex(cur, in_place, delta=delta, new_base=in_place)
+    assert np.array_equal(in_place, cur)
+    for got in (a, b):
+        assert np.array_equal(got[0], ref[0]) and np.array_equal(got[1], ref[1]) and got[2] == ref[2]
+    assert np.array_equal(oracle.decode_sparse_ex(base, ref[0], ref[1], delta=delta), cur)
+    # against the refreshed base the next checkpoint of an unchanged tensor is empty
+    assert oracle.encode_sparse_ex(cur, in_place, delta=delta)[2] == 0
