@@ -269,6 +269,30 @@ def main():
                "dequantize_cluster": 5 * nb + (nb + 1) // 2 + B.cluster_groups(nb, GROUP) * M * 8}
     extras["largest_tensor"] = {"elements": nb, "ops": {op: {"ms": round(largest_ms[op], 4),
                                 "hbm_frac": round(big_alg[op] / largest_ms[op] / 1e6 / HBM_PEAK_GBS, 4)} for op in order}}
+    # the sparse encoder's options: delta payload (cur XOR base) and a copy of cur into the next base (here: the
+    # decode arena), one batched launch; afterwards the plain encoder restores the value payload
+    ex_items, _ = B.sparse_items(sizes, src=[d["cur"] for d in inputs], base=[d["base"] for d in inputs],
+                                 mask=[e["mask"] for e in enc], payload=[e["payload"] for e in enc],
+                                 n_changed=[e["n_changed"] for e in enc], out=dec_out)
+    for it in range(2):
+        e0.record(stream)
+        rc = L.bitsnap_encode_sparse_batched_ex(ex_items.data_ptr(), len(sizes), total_tiles, B.SPARSE_DELTA,
+                                                bws.data_ptr(), bws.numel(), sp)
+        assert rc == 0, rc
+        e1.record(stream)
+        torch.cuda.synchronize()
+    ex_ms = e0.elapsed_time(e1)
+    assert all(torch.equal(o.view(i16), d["cur"].view(i16)) for o, d in list(zip(dec_out, inputs))[:4])
+    ex_nc = sum(int(e["n_changed"].item()) for e in enc)
+    ex_alg = 6 * n_total + sum((n + 7) // 8 for n in sizes) + 2 * ex_nc
+    extras["encode_sparse_delta_payload_and_new_base"] = {
+        "what": "batched, payload = cur XOR base, cur also copied into a second buffer (the next base)",
+        "ms": round(ex_ms, 3), "hbm_GBps": round(ex_alg / ex_ms / 1e6, 1),
+        "hbm_frac": round(ex_alg / ex_ms / 1e6 / HBM_PEAK_GBS, 4)}
+    fn, a = bcalls["encode_sparse"][0]
+    fn(*a)
+    torch.cuda.synchronize()
+
     # quantisation error on these synthetic Adam states, next to plain min-max 8-bit (one cluster): the
     # comparison the paper's evaluation makes on trained states (its table of MRE and MSE against naive
     # 8-bit quantisation); torch only computes the two error measures

@@ -122,6 +122,32 @@ int bitsnap_decode_sparse(const void *base, const uint8_t *mask, const void *pay
                           uint64_t *n_changed,
                           void *workspace, size_t workspace_bytes, bitsnap_stream_t stream);
 
+/* Options of the extended sparse entry points (flags). */
+#define BITSNAP_SPARSE_DELTA 1u /* the payload holds cur XOR base, not cur (see below) */
+
+/* bitsnap_encode_sparse with two options.
+ *   flags & BITSNAP_SPARSE_DELTA   the payload holds the non-zero elements of the delta states
+ *                    themselves - "save the bitmask list and the non-zero elements", as the paper's
+ *                    section on bitmask sparsification has it - with the delta of two 16-bit patterns
+ *                    taken bitwise, cur XOR base, which keeps the scheme lossless.  Mask, n_changed,
+ *                    tile_offsets and the order of the payload do not depend on the flag.
+ *   new_base         nullable; [n] 16-bit out, aligned: receives a copy of cur, for the checkpoint that
+ *                    becomes the base of the following delta checkpoints (the paper's interval
+ *                    between base checkpoints).  May be the buffer `base` itself; must not overlap
+ *                    cur, mask or payload.
+ * flags == 0 and new_base == NULL is bitsnap_encode_sparse. */
+int bitsnap_encode_sparse_ex(const void *cur, const void *base, int64_t n, int elem_bytes, uint32_t flags,
+                             uint8_t *mask, void *payload, int64_t payload_capacity_elems,
+                             uint32_t *tile_offsets, uint64_t *n_changed, void *new_base,
+                             void *workspace, size_t workspace_bytes, bitsnap_stream_t stream);
+
+/* bitsnap_decode_sparse for a payload written with the same flags:
+ * out[i] = bit i of mask ? (DELTA ? base[i] XOR next payload element : next payload element) : base[i]. */
+int bitsnap_decode_sparse_ex(const void *base, const uint8_t *mask, const void *payload,
+                             int64_t payload_elems, int64_t n, int elem_bytes, uint32_t flags, void *out,
+                             uint64_t *n_changed,
+                             void *workspace, size_t workspace_bytes, bitsnap_stream_t stream);
+
 /* Host-side knob for tests of the give-up path: the number of polls a workgroup spends waiting
  * for a predecessor's scan state before it reports failure through n_changed.  0 restores the
  * default (large enough never to trigger in normal operation). */
@@ -205,7 +231,7 @@ typedef struct bitsnap_sparse_item {
     const void *base;        /* [n] in                                                                  */
     uint8_t *mask;           /* encode: [bitsnap_sparse_mask_bytes(n)] out;   decode: [ceil(n/8)] in    */
     void *payload;           /* encode: [capacity] out;             decode: [capacity] in               */
-    void *out;               /* decode: [n] out (may equal base);   encode: unused                      */
+    void *out;               /* decode: [n] out (may equal base);   encode: unused (_ex: new_base)      */
     uint64_t *n_changed;     /* [1] out; required for encode, nullable for decode                       */
     uint32_t *tile_offsets;  /* encode: nullable, [ceil(n/tile_elems)] out;   decode: unused            */
     int64_t n;               /* elements, > 0                                                           */
@@ -225,6 +251,15 @@ int bitsnap_encode_sparse_batched(const bitsnap_sparse_item *items, int64_t coun
                                   void *workspace, size_t workspace_bytes, bitsnap_stream_t stream);
 int bitsnap_decode_sparse_batched(const bitsnap_sparse_item *items, int64_t count, int64_t total_tiles,
                                   void *workspace, size_t workspace_bytes, bitsnap_stream_t stream);
+
+/* The batched calls with the options of bitsnap_encode_sparse_ex / bitsnap_decode_sparse_ex.  In the
+ * encoder an item's `out`, where not NULL, is that tensor's new_base. */
+int bitsnap_encode_sparse_batched_ex(const bitsnap_sparse_item *items, int64_t count, int64_t total_tiles,
+                                     uint32_t flags, void *workspace, size_t workspace_bytes,
+                                     bitsnap_stream_t stream);
+int bitsnap_decode_sparse_batched_ex(const bitsnap_sparse_item *items, int64_t count, int64_t total_tiles,
+                                     uint32_t flags, void *workspace, size_t workspace_bytes,
+                                     bitsnap_stream_t stream);
 
 /* group must be one of 256, 512, 1024, 2048, 4096; total_groups = sum of ceil(n/group). */
 int bitsnap_quantize_cluster_batched(const bitsnap_cluster_item *items, int64_t count, int64_t total_groups,

@@ -18,7 +18,8 @@ LIB_PATH = os.path.join(_HERE, "libbitsnap.so")
 SYMBOLS = (
     "bitsnap_version", "bitsnap_error_string", "bitsnap_debug_stream_copy", "bitsnap_debug_stream_mix",
     "bitsnap_sparse_tile_elems", "bitsnap_sparse_mask_bytes", "bitsnap_sparse_workspace_bytes",
-    "bitsnap_encode_sparse", "bitsnap_decode_sparse", "bitsnap_debug_set_spin_limit",
+    "bitsnap_encode_sparse", "bitsnap_decode_sparse", "bitsnap_encode_sparse_ex", "bitsnap_decode_sparse_ex",
+    "bitsnap_encode_sparse_batched_ex", "bitsnap_decode_sparse_batched_ex", "bitsnap_debug_set_spin_limit",
     "bitsnap_cluster_groups", "bitsnap_cluster_param_bytes", "bitsnap_cluster_label_bytes",
     "bitsnap_cluster_fit_floats", "bitsnap_cluster_workspace_bytes", "bitsnap_cluster_z",
     "bitsnap_quantize_cluster", "bitsnap_dequantize_cluster",
@@ -57,6 +58,14 @@ def lib():
     L.bitsnap_encode_sparse.restype = i
     L.bitsnap_decode_sparse.argtypes = [p, p, p, i64, i64, i, p, p, p, sz, p]
     L.bitsnap_decode_sparse.restype = i
+    L.bitsnap_encode_sparse_ex.argtypes = [p, p, i64, i, C.c_uint32, p, p, i64, p, p, p, p, sz, p]
+    L.bitsnap_encode_sparse_ex.restype = i
+    L.bitsnap_decode_sparse_ex.argtypes = [p, p, p, i64, i64, i, C.c_uint32, p, p, p, sz, p]
+    L.bitsnap_decode_sparse_ex.restype = i
+    L.bitsnap_encode_sparse_batched_ex.argtypes = [p, i64, i64, C.c_uint32, p, sz, p]
+    L.bitsnap_encode_sparse_batched_ex.restype = i
+    L.bitsnap_decode_sparse_batched_ex.argtypes = [p, i64, i64, C.c_uint32, p, sz, p]
+    L.bitsnap_decode_sparse_batched_ex.restype = i
     L.bitsnap_debug_set_spin_limit.argtypes, L.bitsnap_debug_set_spin_limit.restype = [C.c_uint32], None
     L.bitsnap_cluster_groups.argtypes, L.bitsnap_cluster_groups.restype = [i64, i64], sz
     L.bitsnap_cluster_param_bytes.argtypes, L.bitsnap_cluster_param_bytes.restype = [i64, i64, i], sz
@@ -167,19 +176,35 @@ def new_sparse_workspace(n: int, device):
 # ----------------------------------------------------------------------------------------------
 # the four codecs.  Raw forms take every buffer; the caller allocates.
 # ----------------------------------------------------------------------------------------------
+SPARSE_DELTA = 1  # BITSNAP_SPARSE_DELTA
+
+
 def encode_sparse_raw(cur, base, n: int, mask, payload, payload_capacity: int, tile_offsets, n_changed,
-                      workspace, stream=None) -> None:
-    rc = lib().bitsnap_encode_sparse(_ptr(cur), _ptr(base), n, 2, _ptr(mask), _ptr(payload), payload_capacity,
-                                     _ptr(tile_offsets), _ptr(n_changed), _ptr(workspace),
-                                     workspace.numel() * workspace.element_size(), _stream(stream))
-    _check(rc, "bitsnap_encode_sparse")
+                      workspace, stream=None, *, flags: int = 0, new_base=None) -> None:
+    """flags == 0 and new_base is None: bitsnap_encode_sparse; otherwise bitsnap_encode_sparse_ex."""
+    wsb = workspace.numel() * workspace.element_size()
+    if flags == 0 and new_base is None:
+        rc = lib().bitsnap_encode_sparse(_ptr(cur), _ptr(base), n, 2, _ptr(mask), _ptr(payload), payload_capacity,
+                                         _ptr(tile_offsets), _ptr(n_changed), _ptr(workspace), wsb, _stream(stream))
+        _check(rc, "bitsnap_encode_sparse")
+    else:
+        rc = lib().bitsnap_encode_sparse_ex(_ptr(cur), _ptr(base), n, 2, flags, _ptr(mask), _ptr(payload),
+                                            payload_capacity, _ptr(tile_offsets), _ptr(n_changed), _ptr(new_base),
+                                            _ptr(workspace), wsb, _stream(stream))
+        _check(rc, "bitsnap_encode_sparse_ex")
 
 
-def decode_sparse_raw(base, mask, payload, payload_elems: int, n: int, out, n_changed, workspace, stream=None) -> None:
-    rc = lib().bitsnap_decode_sparse(_ptr(base), _ptr(mask), _ptr(payload), payload_elems, n, 2, _ptr(out),
-                                     _ptr(n_changed), _ptr(workspace),
-                                     workspace.numel() * workspace.element_size(), _stream(stream))
-    _check(rc, "bitsnap_decode_sparse")
+def decode_sparse_raw(base, mask, payload, payload_elems: int, n: int, out, n_changed, workspace, stream=None, *,
+                      flags: int = 0) -> None:
+    wsb = workspace.numel() * workspace.element_size()
+    if flags == 0:
+        rc = lib().bitsnap_decode_sparse(_ptr(base), _ptr(mask), _ptr(payload), payload_elems, n, 2, _ptr(out),
+                                         _ptr(n_changed), _ptr(workspace), wsb, _stream(stream))
+        _check(rc, "bitsnap_decode_sparse")
+    else:
+        rc = lib().bitsnap_decode_sparse_ex(_ptr(base), _ptr(mask), _ptr(payload), payload_elems, n, 2, flags, _ptr(out),
+                                            _ptr(n_changed), _ptr(workspace), wsb, _stream(stream))
+        _check(rc, "bitsnap_decode_sparse_ex")
 
 
 def quantize_cluster_raw(x, n: int, group: int, m: int, codes, labels, params, fit_out=None, fit_in=None,
@@ -207,9 +232,10 @@ def _flat16(t):
 
 
 def encode_sparse(cur, base, *, capacity: Optional[int] = None, want_offsets: bool = False, workspace=None,
-                  stream=None):
+                  stream=None, delta: bool = False, new_base=None):
     """-> namespace(mask uint8[mask_bytes], payload int16[capacity], n_changed uint64-as-int64[1] (device),
-    tile_offsets int32[tiles] or None, workspace).  Nothing is synchronised."""
+    tile_offsets int32[tiles] or None, workspace).  Nothing is synchronised.
+    delta: the payload holds cur XOR base; new_base: 16-bit tensor that receives a copy of cur (may be base)."""
     import torch
     cur, base = _flat16(cur), _flat16(base)
     n = cur.numel()
@@ -223,12 +249,14 @@ def encode_sparse(cur, base, *, capacity: Optional[int] = None, want_offsets: bo
     offs = torch.empty(max(tiles, 1), dtype=torch.int32, device=dev) if want_offsets else None
     if workspace is None:
         workspace = new_sparse_workspace(n, dev)
-    encode_sparse_raw(cur, base, n, mask, payload, capacity, offs, n_changed, workspace, stream)
+    encode_sparse_raw(cur, base, n, mask, payload, capacity, offs, n_changed, workspace, stream,
+                      flags=SPARSE_DELTA if delta else 0, new_base=None if new_base is None else _flat16(new_base))
     return SimpleNamespace(mask=mask, payload=payload, n_changed=n_changed, tile_offsets=offs, workspace=workspace,
                            n=n, capacity=capacity)
 
 
-def decode_sparse(base, mask, payload, payload_elems: int, *, out=None, workspace=None, stream=None):
+def decode_sparse(base, mask, payload, payload_elems: int, *, out=None, workspace=None, stream=None,
+                  delta: bool = False):
     """-> (out, n_changed[1] device).  ``out`` defaults to a new tensor like ``base``."""
     import torch
     base_f = _flat16(base)
@@ -239,7 +267,8 @@ def decode_sparse(base, mask, payload, payload_elems: int, *, out=None, workspac
     n_changed = torch.empty(1, dtype=torch.int64, device=base.device)
     if workspace is None:
         workspace = new_sparse_workspace(n, base.device)
-    decode_sparse_raw(base_f, mask, payload, payload_elems, n, out_f, n_changed, workspace, stream)
+    decode_sparse_raw(base_f, mask, payload, payload_elems, n, out_f, n_changed, workspace, stream,
+                      flags=SPARSE_DELTA if delta else 0)
     return out, n_changed
 
 
@@ -322,13 +351,26 @@ def sparse_items(n_list, *, src=None, base=None, mask=None, payload=None, out=No
     return torch.tensor(rows, dtype=torch.int64).to(dev), first
 
 
-def encode_sparse_batched(items, total_tiles: int, workspace, stream=None) -> None:
-    rc = lib().bitsnap_encode_sparse_batched(_ptr(items), items.shape[0], total_tiles, _ptr(workspace),
-                                             workspace.numel() * workspace.element_size(), _stream(stream))
-    _check(rc, "bitsnap_encode_sparse_batched")
+def encode_sparse_batched(items, total_tiles: int, workspace, stream=None, *, flags: Optional[int] = None) -> None:
+    """flags None: bitsnap_encode_sparse_batched; an int: the _ex form (an item's `out` is then its new_base)."""
+    wsb = workspace.numel() * workspace.element_size()
+    if flags is None:
+        rc = lib().bitsnap_encode_sparse_batched(_ptr(items), items.shape[0], total_tiles, _ptr(workspace), wsb,
+                                                 _stream(stream))
+        _check(rc, "bitsnap_encode_sparse_batched")
+    else:
+        rc = lib().bitsnap_encode_sparse_batched_ex(_ptr(items), items.shape[0], total_tiles, flags, _ptr(workspace), wsb,
+                                                    _stream(stream))
+        _check(rc, "bitsnap_encode_sparse_batched_ex")
 
 
-def decode_sparse_batched(items, total_tiles: int, workspace, stream=None) -> None:
-    rc = lib().bitsnap_decode_sparse_batched(_ptr(items), items.shape[0], total_tiles, _ptr(workspace),
-                                             workspace.numel() * workspace.element_size(), _stream(stream))
-    _check(rc, "bitsnap_decode_sparse_batched")
+def decode_sparse_batched(items, total_tiles: int, workspace, stream=None, *, flags: Optional[int] = None) -> None:
+    wsb = workspace.numel() * workspace.element_size()
+    if flags is None:
+        rc = lib().bitsnap_decode_sparse_batched(_ptr(items), items.shape[0], total_tiles, _ptr(workspace), wsb,
+                                                 _stream(stream))
+        _check(rc, "bitsnap_decode_sparse_batched")
+    else:
+        rc = lib().bitsnap_decode_sparse_batched_ex(_ptr(items), items.shape[0], total_tiles, flags, _ptr(workspace), wsb,
+                                                    _stream(stream))
+        _check(rc, "bitsnap_decode_sparse_batched_ex")

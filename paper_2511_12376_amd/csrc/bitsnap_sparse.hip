@@ -82,10 +82,11 @@ __device__ __forceinline__ void store8(uint16_t *p, int64_t e0, int64_t n, uint4
             ((global_u16 *)p)[e0 + t] = (uint16_t)(w[t >> 1] >> ((t & 1) * 16));
 }
 
-// bit t = 1 iff 16-bit element t of a differs from element t of b (Algorithm 1 steps 1-2)
-__device__ __forceinline__ uint32_t diff_bits(uint4 a, uint4 b)
+// bit t = 1 iff 16-bit element t of x is non-zero; with x = cur XOR base: the element changed
+// (Algorithm 1 steps 1-2)
+__device__ __forceinline__ uint32_t nonzero16_bits(uint4 v)
 {
-    const uint32_t x[4] = {a.x ^ b.x, a.y ^ b.y, a.z ^ b.z, a.w ^ b.w};
+    const uint32_t x[4] = {v.x, v.y, v.z, v.w};
     uint32_t m = 0;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
@@ -306,11 +307,15 @@ __device__ __forceinline__ void copy_out_stage(const TileShared &sh, uint16_t *_
 // to hide its round trip, a slow look-back delays the count of the workgroup's next tile, which
 // slows the look-backs of the tiles after that one, and so on: measured at half the throughput.)
 // launch_bounds: 4 waves per SIMD, i.e. two 512-thread workgroups per CU (128 registers per lane).
-template <bool kBatched>
+// kDelta: the payload holds cur XOR base (the non-zero elements of the delta states) instead of
+// cur.  refresh: item.out, where set, receives a copy of cur (it may be the base buffer itself: a
+// tile's base is in registers before the tile's copy of cur is stored, and no other tile touches it).
+template <bool kBatched, bool kDelta>
 __global__ __launch_bounds__(kBlock, 4) void encode_sparse_kernel(bitsnap_sparse_item single,
                                                                const bitsnap_sparse_item *__restrict__ items,
                                                                int64_t count, ScanHeader *hdr, uint64_t *status,
-                                                               int64_t status_cap, int64_t num_tiles, uint32_t spin_limit)
+                                                               int64_t status_cap, int64_t num_tiles, uint32_t spin_limit,
+                                                               int refresh)
 {
     __shared__ TileShared sh;
     const int tid0 = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid0 >> 6);
@@ -355,13 +360,20 @@ __global__ __launch_bounds__(kBlock, 4) void encode_sparse_kernel(bitsnap_sparse
         const int32_t wave_mask_bytes =
             (full_tile ? (int32_t)(kTileElems / 8) : (int32_t)(mask_bytes - tile * (kTileElems / 8))) - wave * (2 * kWave);
         const uint32_t tile_elems = full_tile ? (uint32_t)kTileElems : (uint32_t)(n - tile * kTileElems);
+        uint16_t *new_base = refresh ? (uint16_t *)it.out : nullptr;
 
         uint32_t m[kRounds][2], cnt[kRounds][2], rank[kRounds][2];
 #pragma unroll
         for (int r = 0; r < kRounds; ++r)
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
-                m[r][j] = diff_bits(c[r][j], b[r][j]) & piece_valid_bits(r, j, wave, lane, tile_elems);
+                if (new_base)
+                    store8(new_base, piece_chunk(tile, r, wave, j) * kChunkElems + lane * kLaneElems, n, c[r][j]);
+                const uint4 x = make_uint4(c[r][j].x ^ b[r][j].x, c[r][j].y ^ b[r][j].y, c[r][j].z ^ b[r][j].z,
+                                           c[r][j].w ^ b[r][j].w);
+                m[r][j] = nonzero16_bits(x) & piece_valid_bits(r, j, wave, lane, tile_elems);
+                if (kDelta)
+                    c[r][j] = x;
                 cnt[r][j] = __popc(m[r][j]);
                 // Algorithm 1 steps 3-4: one mask byte per lane; bytes past ceil(n/8) come out as 0
                 const int32_t mb = (r * kRoundChunks + j) * kWave;  // + lane, in this wave's part of the tile's mask
@@ -532,7 +544,8 @@ __global__ __launch_bounds__(kBlock) void decode_scan_kernel(bitsnap_sparse_item
 // and its length are known from the two kernels before, so mask, base and the payload segment are
 // all requested at once; the segment goes through LDS as aligned 16-byte pieces (stage[i] holds
 // payload element src0 + i, src0 a multiple of 8), from where every lane picks its elements by rank.
-template <bool kBatched>
+// kDelta: the payload holds cur XOR base; the element is base XOR payload.
+template <bool kBatched, bool kDelta>
 __global__ __launch_bounds__(kBlock, 4) void decode_merge_kernel(bitsnap_sparse_item single,
                                                                  const bitsnap_sparse_item *__restrict__ items,
                                                                  int64_t count, const uint64_t *__restrict__ tile_offset,
@@ -603,7 +616,10 @@ __global__ __launch_bounds__(kBlock, 4) void decode_merge_kernel(bitsnap_sparse_
             for (int t = 0; t < kLaneElems; ++t) {
                 if ((m[r][j] >> t) & 1u) {
                     const uint32_t s = sh.stage[p++];
-                    w[t >> 1] = (t & 1) ? ((w[t >> 1] & 0x0000FFFFu) | (s << 16)) : ((w[t >> 1] & 0xFFFF0000u) | s);
+                    if (kDelta)
+                        w[t >> 1] ^= s << ((t & 1) * 16);
+                    else
+                        w[t >> 1] = (t & 1) ? ((w[t >> 1] & 0x0000FFFFu) | (s << 16)) : ((w[t >> 1] & 0xFFFF0000u) | s);
                 }
             }
             store8(out, piece_chunk(tile, r, wave, j) * kChunkElems + lane * kLaneElems, n,
@@ -671,14 +687,14 @@ static int64_t tiles_of(int64_t n) { return n <= 0 ? 0 : (n + kTileElems - 1) / 
 
 template <typename Kernel>
 static int launch_scan(Kernel kernel, const bitsnap_sparse_item &single, const bitsnap_sparse_item *items, int64_t count,
-                       int64_t num_tiles, void *workspace, size_t workspace_bytes, bitsnap_stream_t stream)
+                       int64_t num_tiles, void *workspace, size_t workspace_bytes, bitsnap_stream_t stream, int refresh)
 {
     ScanHeader *hdr = reinterpret_cast<ScanHeader *>(workspace);
     uint64_t *status = reinterpret_cast<uint64_t *>(reinterpret_cast<char *>(workspace) + kScanHeaderBytes);
     const int64_t status_cap = (int64_t)((workspace_bytes - kScanHeaderBytes) / sizeof(uint64_t));
     const int grid = sparse_grid(reinterpret_cast<const void *>(kernel), num_tiles);
     hipLaunchKernelGGL(kernel, dim3(grid), dim3(kBlock), 0, (hipStream_t)stream, single, items, count, hdr, status,
-                       status_cap, num_tiles, g_spin_limit);
+                       status_cap, num_tiles, g_spin_limit, refresh);
     return launch_status();
 }
 
@@ -695,7 +711,7 @@ static int check_scan_workspace(void *workspace, size_t workspace_bytes, int64_t
 
 template <bool kBatched>
 static int launch_decode(const bitsnap_sparse_item &single, const bitsnap_sparse_item *items, int64_t count,
-                         int64_t num_tiles, void *workspace, bitsnap_stream_t stream)
+                         int64_t num_tiles, void *workspace, bitsnap_stream_t stream, bool delta)
 {
     uint64_t *tile_offset = reinterpret_cast<uint64_t *>(reinterpret_cast<char *>(workspace) + kScanHeaderBytes);
     uint32_t *tile_count = reinterpret_cast<uint32_t *>(tile_offset + num_tiles);
@@ -709,22 +725,26 @@ static int launch_decode(const bitsnap_sparse_item &single, const bitsnap_sparse
     // the scan also reports n_changed, for an empty tensor too
     hipLaunchKernelGGL(decode_scan_kernel<kBatched>, dim3((unsigned)(kBatched ? count : 1)), dim3(kBlock), 0, s, single,
                        items, tile_count, tile_offset);
-    if (num_tiles > 0)
-        hipLaunchKernelGGL(decode_merge_kernel<kBatched>, dim3((unsigned)num_tiles), dim3(kBlock), 0, s, single, items,
-                           count, tile_offset, tile_count);
+    if (num_tiles > 0 && delta)
+        hipLaunchKernelGGL((decode_merge_kernel<kBatched, true>), dim3((unsigned)num_tiles), dim3(kBlock), 0, s, single,
+                           items, count, tile_offset, tile_count);
+    else if (num_tiles > 0)
+        hipLaunchKernelGGL((decode_merge_kernel<kBatched, false>), dim3((unsigned)num_tiles), dim3(kBlock), 0, s, single,
+                           items, count, tile_offset, tile_count);
     return launch_status();
 }
 
-extern "C" int bitsnap_encode_sparse(const void *cur, const void *base, int64_t n, int elem_bytes, uint8_t *mask,
-                                     void *payload, int64_t payload_capacity_elems, uint32_t *tile_offsets,
-                                     uint64_t *n_changed, void *workspace, size_t workspace_bytes,
-                                     bitsnap_stream_t stream)
+extern "C" int bitsnap_encode_sparse_ex(const void *cur, const void *base, int64_t n, int elem_bytes, uint32_t flags,
+                                        uint8_t *mask, void *payload, int64_t payload_capacity_elems,
+                                        uint32_t *tile_offsets, uint64_t *n_changed, void *new_base, void *workspace,
+                                        size_t workspace_bytes, bitsnap_stream_t stream)
 {
-    if (n < 0 || elem_bytes != 2 || payload_capacity_elems < 0 || n >= (int64_t)1 << kValueBits)
+    if (n < 0 || elem_bytes != 2 || payload_capacity_elems < 0 || n >= (int64_t)1 << kValueBits ||
+        (flags & ~(uint32_t)BITSNAP_SPARSE_DELTA))
         return BITSNAP_E_SIZE;
     if (!n_changed || (n > 0 && (!cur || !base || !mask)) || (payload_capacity_elems > 0 && !payload))
         return BITSNAP_E_NULL;
-    if (!aligned16(cur) || !aligned16(base) || !aligned16(mask) || !aligned16(payload) ||
+    if (!aligned16(cur) || !aligned16(base) || !aligned16(mask) || !aligned16(payload) || !aligned16(new_base) ||
         ((uintptr_t)n_changed & 7u) || ((uintptr_t)tile_offsets & 3u))
         return BITSNAP_E_ALIGN;
     if (int rc = check_workspace(workspace, workspace_bytes, n))
@@ -736,18 +756,34 @@ extern "C" int bitsnap_encode_sparse(const void *cur, const void *base, int64_t 
     it.base = base;
     it.mask = mask;
     it.payload = payload;
+    it.out = new_base;
     it.n_changed = n_changed;
     it.tile_offsets = tile_offsets;
     it.n = n;
     it.capacity = payload_capacity_elems;
-    return launch_scan(&encode_sparse_kernel<false>, it, nullptr, 1, tiles_of(n), workspace, workspace_bytes, stream);
+    if (flags & BITSNAP_SPARSE_DELTA)
+        return launch_scan(&encode_sparse_kernel<false, true>, it, nullptr, 1, tiles_of(n), workspace, workspace_bytes,
+                           stream, new_base != nullptr);
+    return launch_scan(&encode_sparse_kernel<false, false>, it, nullptr, 1, tiles_of(n), workspace, workspace_bytes,
+                       stream, new_base != nullptr);
 }
 
-extern "C" int bitsnap_decode_sparse(const void *base, const uint8_t *mask, const void *payload, int64_t payload_elems,
-                                     int64_t n, int elem_bytes, void *out, uint64_t *n_changed, void *workspace,
-                                     size_t workspace_bytes, bitsnap_stream_t stream)
+extern "C" int bitsnap_encode_sparse(const void *cur, const void *base, int64_t n, int elem_bytes, uint8_t *mask,
+                                     void *payload, int64_t payload_capacity_elems, uint32_t *tile_offsets,
+                                     uint64_t *n_changed, void *workspace, size_t workspace_bytes,
+                                     bitsnap_stream_t stream)
 {
-    if (n < 0 || elem_bytes != 2 || payload_elems < 0 || n >= (int64_t)1 << kValueBits)
+    return bitsnap_encode_sparse_ex(cur, base, n, elem_bytes, 0u, mask, payload, payload_capacity_elems, tile_offsets,
+                                    n_changed, nullptr, workspace, workspace_bytes, stream);
+}
+
+extern "C" int bitsnap_decode_sparse_ex(const void *base, const uint8_t *mask, const void *payload,
+                                        int64_t payload_elems, int64_t n, int elem_bytes, uint32_t flags, void *out,
+                                        uint64_t *n_changed, void *workspace, size_t workspace_bytes,
+                                        bitsnap_stream_t stream)
+{
+    if (n < 0 || elem_bytes != 2 || payload_elems < 0 || n >= (int64_t)1 << kValueBits ||
+        (flags & ~(uint32_t)BITSNAP_SPARSE_DELTA))
         return BITSNAP_E_SIZE;
     if ((n > 0 && (!base || !mask || !out)) || (payload_elems > 0 && !payload))
         return BITSNAP_E_NULL;
@@ -763,7 +799,15 @@ extern "C" int bitsnap_decode_sparse(const void *base, const uint8_t *mask, cons
     it.n_changed = n_changed;
     it.n = n;
     it.capacity = payload_elems;
-    return launch_decode<false>(it, nullptr, 1, tiles_of(n), workspace, stream);
+    return launch_decode<false>(it, nullptr, 1, tiles_of(n), workspace, stream, (flags & BITSNAP_SPARSE_DELTA) != 0);
+}
+
+extern "C" int bitsnap_decode_sparse(const void *base, const uint8_t *mask, const void *payload, int64_t payload_elems,
+                                     int64_t n, int elem_bytes, void *out, uint64_t *n_changed, void *workspace,
+                                     size_t workspace_bytes, bitsnap_stream_t stream)
+{
+    return bitsnap_decode_sparse_ex(base, mask, payload, payload_elems, n, elem_bytes, 0u, out, n_changed, workspace,
+                                    workspace_bytes, stream);
 }
 
 extern "C" size_t bitsnap_sparse_batch_workspace_bytes(int64_t total_tiles)
@@ -784,23 +828,51 @@ static int check_batch(const bitsnap_sparse_item *items, int64_t count, int64_t 
     return check_scan_workspace(workspace, workspace_bytes, total_tiles);
 }
 
-extern "C" int bitsnap_encode_sparse_batched(const bitsnap_sparse_item *items, int64_t count, int64_t total_tiles,
-                                             void *workspace, size_t workspace_bytes, bitsnap_stream_t stream)
+static int encode_batched(const bitsnap_sparse_item *items, int64_t count, int64_t total_tiles, uint32_t flags,
+                          int refresh, void *workspace, size_t workspace_bytes, bitsnap_stream_t stream)
 {
+    if (flags & ~(uint32_t)BITSNAP_SPARSE_DELTA)
+        return BITSNAP_E_SIZE;
     if (int rc = check_batch(items, count, total_tiles, workspace, workspace_bytes))
         return rc;
     if (count == 0 || total_tiles == 0)
         return BITSNAP_OK;
-    return launch_scan(&encode_sparse_kernel<true>, bitsnap_sparse_item{}, items, count, total_tiles, workspace,
-                       workspace_bytes, stream);
+    if (flags & BITSNAP_SPARSE_DELTA)
+        return launch_scan(&encode_sparse_kernel<true, true>, bitsnap_sparse_item{}, items, count, total_tiles, workspace,
+                           workspace_bytes, stream, refresh);
+    return launch_scan(&encode_sparse_kernel<true, false>, bitsnap_sparse_item{}, items, count, total_tiles, workspace,
+                       workspace_bytes, stream, refresh);
+}
+
+extern "C" int bitsnap_encode_sparse_batched(const bitsnap_sparse_item *items, int64_t count, int64_t total_tiles,
+                                             void *workspace, size_t workspace_bytes, bitsnap_stream_t stream)
+{
+    return encode_batched(items, count, total_tiles, 0u, 0, workspace, workspace_bytes, stream);
+}
+
+extern "C" int bitsnap_encode_sparse_batched_ex(const bitsnap_sparse_item *items, int64_t count, int64_t total_tiles,
+                                                uint32_t flags, void *workspace, size_t workspace_bytes,
+                                                bitsnap_stream_t stream)
+{
+    return encode_batched(items, count, total_tiles, flags, 1, workspace, workspace_bytes, stream);
+}
+
+extern "C" int bitsnap_decode_sparse_batched_ex(const bitsnap_sparse_item *items, int64_t count, int64_t total_tiles,
+                                                uint32_t flags, void *workspace, size_t workspace_bytes,
+                                                bitsnap_stream_t stream)
+{
+    if (flags & ~(uint32_t)BITSNAP_SPARSE_DELTA)
+        return BITSNAP_E_SIZE;
+    if (int rc = check_batch(items, count, total_tiles, workspace, workspace_bytes))
+        return rc;
+    if (count == 0 || total_tiles == 0)
+        return BITSNAP_OK;
+    return launch_decode<true>(bitsnap_sparse_item{}, items, count, total_tiles, workspace, stream,
+                               (flags & BITSNAP_SPARSE_DELTA) != 0);
 }
 
 extern "C" int bitsnap_decode_sparse_batched(const bitsnap_sparse_item *items, int64_t count, int64_t total_tiles,
                                              void *workspace, size_t workspace_bytes, bitsnap_stream_t stream)
 {
-    if (int rc = check_batch(items, count, total_tiles, workspace, workspace_bytes))
-        return rc;
-    if (count == 0 || total_tiles == 0)
-        return BITSNAP_OK;
-    return launch_decode<true>(bitsnap_sparse_item{}, items, count, total_tiles, workspace, stream);
+    return bitsnap_decode_sparse_batched_ex(items, count, total_tiles, 0u, workspace, workspace_bytes, stream);
 }

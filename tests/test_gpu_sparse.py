@@ -276,3 +276,75 @@ def test_full_size_batched_pass_sampled():
             o_mask, o_pay, o_nc = oracle.encode_sparse(c16[lo:hi].cpu().numpy().view(np.uint16), b16[lo:hi].cpu().numpy().view(np.uint16))
             assert np.array_equal(to_np(mask[k][lo // 8:lo // 8 + o_mask.size]), o_mask)
             assert np.array_equal(to_np(payload[k][o[t]:o[t] + o_nc]).view(np.uint16), o_pay)
+
+
+@pytest.mark.parametrize("n", [0, 1, 9, 4097, T - 1, T, 2 * T + 5, 3 * T + 777, 1_000_003])
+@pytest.mark.parametrize("p", [0.0, 0.06, 0.7, 1.0])
+def test_delta_payload_and_new_base_match_oracle(n, p):
+    """The extended entry points: payload = non-zero elements of cur XOR base, and a copy of cur into the
+    next base, into a fresh buffer and in place over the base buffer."""
+    announce("sparse delta payload / new base", n, p)
+    cur, base = _pair(n, p, 9000 + n)
+    for delta in (True, False):
+        o_mask, o_pay, o_nc = oracle.encode_sparse_ex(cur, base, delta=delta)
+        cur_d, base_d = u16_to_dev(cur), u16_to_dev(base)
+        fresh = torch.full((max(n, 1),), 0x5A5A, dtype=torch.int16, device=DEV)[:n]
+        enc = B.encode_sparse(cur_d, base_d, delta=delta, new_base=fresh, want_offsets=True)
+        torch.cuda.synchronize()
+        assert int(enc.n_changed.item()) == o_nc
+        assert np.array_equal(to_np(enc.mask)[: o_mask.size], o_mask)
+        assert np.array_equal(to_np(enc.payload).view(np.uint16)[:o_nc], o_pay)
+        assert np.array_equal(to_np(fresh).view(np.uint16), cur)
+        assert np.array_equal(dev_to_u16(base_d), base)            # the base itself was left alone
+        out, nch = B.decode_sparse(base_d, enc.mask, enc.payload, o_nc, delta=delta, workspace=enc.workspace)
+        torch.cuda.synchronize()
+        assert int(nch.item()) == o_nc and np.array_equal(dev_to_u16(out), cur)
+        assert np.array_equal(dev_to_u16(out), oracle.decode_sparse_ex(base, o_mask, o_pay, delta=delta))
+        # in place: the base buffer becomes cur, the encoding is still the one against the old base
+        enc2 = B.encode_sparse(cur_d, base_d, delta=delta, new_base=base_d, workspace=enc.workspace)
+        torch.cuda.synchronize()
+        assert int(enc2.n_changed.item()) == o_nc
+        assert np.array_equal(to_np(enc2.mask)[: o_mask.size], o_mask)
+        assert np.array_equal(to_np(enc2.payload).view(np.uint16)[:o_nc], o_pay)
+        assert np.array_equal(dev_to_u16(base_d), cur)
+
+
+def test_batched_delta_payload_and_new_base():
+    announce("sparse batched delta / new base")
+    sizes = [1, T, T + 1, 5 * T + 77, 9, 200_003, 40 * T - 1]
+    ps = [1.0, 0.06, 0.5, 0.7, 0.0, 0.06, 0.3]
+    pairs = [_pair(n, p, 7000 + i) for i, (n, p) in enumerate(zip(sizes, ps))]
+    cur = [u16_to_dev(c) for c, _ in pairs]
+    base = [u16_to_dev(b) for _, b in pairs]
+    mask = [torch.zeros(B.sparse_mask_bytes(n), dtype=torch.uint8, device=DEV) for n in sizes]
+    payload = [torch.zeros(n + 8, dtype=torch.int16, device=DEV) for n in sizes]
+    counts = [torch.zeros(1, dtype=torch.int64, device=DEV) for _ in sizes]
+    # every second tensor refreshes its base in place, one gets a fresh copy, the others none
+    new_base = [base[k] if k % 2 == 0 else None for k in range(len(sizes))]
+    new_base[3] = torch.zeros(sizes[3], dtype=torch.bfloat16, device=DEV)
+    items, total = B.sparse_items(sizes, src=cur, base=base, mask=mask, payload=payload, n_changed=counts, out=new_base)
+    ws = torch.zeros(B.sparse_batch_workspace_bytes(total), dtype=torch.uint8, device=DEV)
+    B.encode_sparse_batched(items, total, ws, flags=B.SPARSE_DELTA)
+    torch.cuda.synchronize()
+    old_base = [u16_to_dev(b) for _, b in pairs]
+    out = [torch.zeros(n, dtype=torch.bfloat16, device=DEV) for n in sizes]
+    ditems, _ = B.sparse_items(sizes, base=old_base, mask=mask, payload=payload, out=out)
+    B.decode_sparse_batched(ditems, total, ws, flags=B.SPARSE_DELTA)
+    torch.cuda.synchronize()
+    for k, (c, b) in enumerate(pairs):
+        o_mask, o_pay, o_nc = oracle.encode_sparse_ex(c, b, delta=True)
+        assert int(counts[k].item()) == o_nc
+        assert np.array_equal(to_np(mask[k])[: o_mask.size], o_mask)
+        assert np.array_equal(to_np(payload[k]).view(np.uint16)[:o_nc], o_pay)
+        assert np.array_equal(dev_to_u16(out[k]), c)
+        if new_base[k] is not None:
+            assert np.array_equal(dev_to_u16(new_base[k]), c)
+        else:
+            assert np.array_equal(dev_to_u16(base[k]), b)
+    # the plain batched call ignores `out` in the encoder
+    base2 = [u16_to_dev(b) for _, b in pairs]
+    guard = [torch.full((n,), 0x1234, dtype=torch.int16, device=DEV) for n in sizes]
+    items2, _ = B.sparse_items(sizes, src=cur, base=base2, mask=mask, payload=payload, n_changed=counts, out=guard)
+    B.encode_sparse_batched(items2, total, ws)
+    torch.cuda.synchronize()
+    assert all(bool((g == 0x1234).all()) for g in guard)
