@@ -45,6 +45,7 @@ def parse():
     ap.add_argument("--mode", choices=["batched", "per-tensor"], default="batched",
                     help="which entry points the reported step uses; the other mode is timed too and reported beside it")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true", help="only the step: skip the figures reported under extras")
     ap.add_argument("--cpu-sample-tensors", type=int, default=4)
     return ap.parse_args()
 
@@ -208,113 +209,116 @@ def main():
             torch.cuda.synchronize()
         copy_gbps = 5 * 2 * cal_bytes / (e0.elapsed_time(e1) * 1e-3) / 1e9
 
-    # what the memory system leaves to win for the cluster codecs: the same bytes in the same pattern, no arithmetic
-    mix_n = min(n_max, 1 << 28) // 4096 * 4096
-    mix_ceiling = None
-    if mix_n > 0:
-        mix_b = torch.empty(mix_n, dtype=u8, device=dev)
-        mix_h = torch.empty(mix_n // 2, dtype=u8, device=dev)
-        mix_w = deq_ring[2][:mix_n]
-        mix_ceiling = {}
+    mix_ceiling, extras = None, {}
+    if not args.no_extras:
+        # what the memory system leaves to win for the cluster codecs: the same bytes in the same pattern, no arithmetic
+        mix_n = min(n_max, 1 << 28) // 4096 * 4096
+        mix_ceiling = None
+        if mix_n > 0:
+            mix_b = torch.empty(mix_n, dtype=u8, device=dev)
+            mix_h = torch.empty(mix_n // 2, dtype=u8, device=dev)
+            mix_w = deq_ring[2][:mix_n]
+            mix_ceiling = {}
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            for name, to_small in (("quantize_cluster", True), ("dequantize_cluster", False)):
+                for it in range(2):
+                    e0.record(stream)
+                    for _ in range(5):
+                        B.debug_stream_mix(mix_w, mix_b, mix_h, to_small)
+                    e1.record(stream)
+                    torch.cuda.synchronize()
+                mix_ceiling[name] = round(5 * 5.5 * mix_n / (e0.elapsed_time(e1) * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
+            del mix_b, mix_h
+
+        # ------------------------------------------------------------------ beside the step: one fit per tensor
+        # (group = 0, Algorithm 2 as the paper states it) on the first-moment state, one call per tensor;
+        # three passes over the tensor instead of one, codes and labels into the same buffers
+        gws = torch.empty(max(B.cluster_workspace_bytes(n, 0, M) for n in sizes), dtype=u8, device=dev)
+        gparams = torch.empty(M * 2, dtype=f32, device=dev)
+        gcalls = [(d["m"].data_ptr(), n, 0, M, e["q"][1]["codes"].data_ptr(), e["q"][1]["labels"].data_ptr(),
+                   gparams.data_ptr(), None, None, status.data_ptr(), gws.data_ptr(), gws.numel(), sp)
+                  for d, e, n in zip(inputs, enc, sizes)]
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        for name, to_small in (("quantize_cluster", True), ("dequantize_cluster", False)):
+        for it in range(2):
+            e0.record(stream)
+            for a in gcalls:
+                rc = L.bitsnap_quantize_cluster(*a)
+                assert rc == 0, rc
+            e1.record(stream)
+            torch.cuda.synchronize()
+        whole_ms = e0.elapsed_time(e1)
+        whole_alg = 3 * 4 * n_total + n_total + (n_total + 1) // 2 + len(sizes) * M * 8
+        extras = {"quantize_whole_tensor_fit": {
+            "what": "group = 0 (one fit per tensor), first-moment state, one call per tensor, 3 passes over x",
+            "ms": round(whole_ms, 3), "api_calls": len(gcalls), "state_GBps": round(4 * n_total / whole_ms / 1e6, 1),
+            "hbm_GBps": round(whole_alg / whole_ms / 1e6, 1), "hbm_frac": round(whole_alg / whole_ms / 1e6 / HBM_PEAK_GBS, 4)}}
+        # steady state on the single largest tensor: each op alone, five calls in a row
+        big = max(range(len(sizes)), key=lambda i: sizes[i])
+        nb = sizes[big]
+        largest_ms = {}
+        for op in order:
+            call = calls[op][big if op.endswith("sparse") else 3 * big]
+            fn = getattr(L, "bitsnap_" + op)
             for it in range(2):
                 e0.record(stream)
                 for _ in range(5):
-                    B.debug_stream_mix(mix_w, mix_b, mix_h, to_small)
+                    fn(*call)
                 e1.record(stream)
                 torch.cuda.synchronize()
-            mix_ceiling[name] = round(5 * 5.5 * mix_n / (e0.elapsed_time(e1) * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
-        del mix_b, mix_h
-
-    # ------------------------------------------------------------------ beside the step: one fit per tensor
-    # (group = 0, Algorithm 2 as the paper states it) on the first-moment state, one call per tensor;
-    # three passes over the tensor instead of one, codes and labels into the same buffers
-    gws = torch.empty(max(B.cluster_workspace_bytes(n, 0, M) for n in sizes), dtype=u8, device=dev)
-    gparams = torch.empty(M * 2, dtype=f32, device=dev)
-    gcalls = [(d["m"].data_ptr(), n, 0, M, e["q"][1]["codes"].data_ptr(), e["q"][1]["labels"].data_ptr(),
-               gparams.data_ptr(), None, None, status.data_ptr(), gws.data_ptr(), gws.numel(), sp)
-              for d, e, n in zip(inputs, enc, sizes)]
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    for it in range(2):
-        e0.record(stream)
-        for a in gcalls:
-            rc = L.bitsnap_quantize_cluster(*a)
-            assert rc == 0, rc
-        e1.record(stream)
-        torch.cuda.synchronize()
-    whole_ms = e0.elapsed_time(e1)
-    whole_alg = 3 * 4 * n_total + n_total + (n_total + 1) // 2 + len(sizes) * M * 8
-    extras = {"quantize_whole_tensor_fit": {
-        "what": "group = 0 (one fit per tensor), first-moment state, one call per tensor, 3 passes over x",
-        "ms": round(whole_ms, 3), "api_calls": len(gcalls), "state_GBps": round(4 * n_total / whole_ms / 1e6, 1),
-        "hbm_GBps": round(whole_alg / whole_ms / 1e6, 1), "hbm_frac": round(whole_alg / whole_ms / 1e6 / HBM_PEAK_GBS, 4)}}
-    # steady state on the single largest tensor: each op alone, five calls in a row
-    big = max(range(len(sizes)), key=lambda i: sizes[i])
-    nb = sizes[big]
-    largest_ms = {}
-    for op in order:
-        call = calls[op][big if op.endswith("sparse") else 3 * big]
-        fn = getattr(L, "bitsnap_" + op)
+            largest_ms[op] = e0.elapsed_time(e1) / 5
+        nc_big = int(enc[big]["n_changed"].item())
+        big_alg = {"encode_sparse": 4 * nb + (nb + 7) // 8 + 2 * nc_big, "decode_sparse": 4 * nb + (nb + 7) // 8 + 2 * nc_big,
+                   "quantize_cluster": 5 * nb + (nb + 1) // 2 + B.cluster_groups(nb, GROUP) * M * 8,
+                   "dequantize_cluster": 5 * nb + (nb + 1) // 2 + B.cluster_groups(nb, GROUP) * M * 8}
+        extras["largest_tensor"] = {"elements": nb, "ops": {op: {"ms": round(largest_ms[op], 4),
+                                    "hbm_frac": round(big_alg[op] / largest_ms[op] / 1e6 / HBM_PEAK_GBS, 4)} for op in order}}
+        # the sparse encoder's options: delta payload (cur XOR base) and a copy of cur into the next base (here: the
+        # decode arena), one batched launch; afterwards the plain encoder restores the value payload
+        ex_items, _ = B.sparse_items(sizes, src=[d["cur"] for d in inputs], base=[d["base"] for d in inputs],
+                                     mask=[e["mask"] for e in enc], payload=[e["payload"] for e in enc],
+                                     n_changed=[e["n_changed"] for e in enc], out=dec_out)
         for it in range(2):
             e0.record(stream)
-            for _ in range(5):
-                fn(*call)
+            rc = L.bitsnap_encode_sparse_batched_ex(ex_items.data_ptr(), len(sizes), total_tiles, B.SPARSE_DELTA,
+                                                    bws.data_ptr(), bws.numel(), sp)
+            assert rc == 0, rc
             e1.record(stream)
             torch.cuda.synchronize()
-        largest_ms[op] = e0.elapsed_time(e1) / 5
-    nc_big = int(enc[big]["n_changed"].item())
-    big_alg = {"encode_sparse": 4 * nb + (nb + 7) // 8 + 2 * nc_big, "decode_sparse": 4 * nb + (nb + 7) // 8 + 2 * nc_big,
-               "quantize_cluster": 5 * nb + (nb + 1) // 2 + B.cluster_groups(nb, GROUP) * M * 8,
-               "dequantize_cluster": 5 * nb + (nb + 1) // 2 + B.cluster_groups(nb, GROUP) * M * 8}
-    extras["largest_tensor"] = {"elements": nb, "ops": {op: {"ms": round(largest_ms[op], 4),
-                                "hbm_frac": round(big_alg[op] / largest_ms[op] / 1e6 / HBM_PEAK_GBS, 4)} for op in order}}
-    # the sparse encoder's options: delta payload (cur XOR base) and a copy of cur into the next base (here: the
-    # decode arena), one batched launch; afterwards the plain encoder restores the value payload
-    ex_items, _ = B.sparse_items(sizes, src=[d["cur"] for d in inputs], base=[d["base"] for d in inputs],
-                                 mask=[e["mask"] for e in enc], payload=[e["payload"] for e in enc],
-                                 n_changed=[e["n_changed"] for e in enc], out=dec_out)
-    for it in range(2):
-        e0.record(stream)
-        rc = L.bitsnap_encode_sparse_batched_ex(ex_items.data_ptr(), len(sizes), total_tiles, B.SPARSE_DELTA,
-                                                bws.data_ptr(), bws.numel(), sp)
-        assert rc == 0, rc
-        e1.record(stream)
+        ex_ms = e0.elapsed_time(e1)
+        assert all(torch.equal(o.view(i16), d["cur"].view(i16)) for o, d in list(zip(dec_out, inputs))[:4])
+        ex_nc = sum(int(e["n_changed"].item()) for e in enc)
+        ex_alg = 6 * n_total + sum((n + 7) // 8 for n in sizes) + 2 * ex_nc
+        extras["encode_sparse_delta_payload_and_new_base"] = {
+            "what": "batched, payload = cur XOR base, cur also copied into a second buffer (the next base)",
+            "ms": round(ex_ms, 3), "hbm_GBps": round(ex_alg / ex_ms / 1e6, 1),
+            "hbm_frac": round(ex_alg / ex_ms / 1e6 / HBM_PEAK_GBS, 4)}
+        fn, a = bcalls["encode_sparse"][0]
+        fn(*a)
         torch.cuda.synchronize()
-    ex_ms = e0.elapsed_time(e1)
-    assert all(torch.equal(o.view(i16), d["cur"].view(i16)) for o, d in list(zip(dec_out, inputs))[:4])
-    ex_nc = sum(int(e["n_changed"].item()) for e in enc)
-    ex_alg = 6 * n_total + sum((n + 7) // 8 for n in sizes) + 2 * ex_nc
-    extras["encode_sparse_delta_payload_and_new_base"] = {
-        "what": "batched, payload = cur XOR base, cur also copied into a second buffer (the next base)",
-        "ms": round(ex_ms, 3), "hbm_GBps": round(ex_alg / ex_ms / 1e6, 1),
-        "hbm_frac": round(ex_alg / ex_ms / 1e6 / HBM_PEAK_GBS, 4)}
-    fn, a = bcalls["encode_sparse"][0]
-    fn(*a)
-    torch.cuda.synchronize()
 
-    # quantisation error on these synthetic Adam states, next to plain min-max 8-bit (one cluster): the
-    # comparison the paper's evaluation makes on trained states (its table of MRE and MSE against naive
-    # 8-bit quantisation); torch only computes the two error measures
-    def quality(x, group, m):
-        q = B.quantize_cluster(x, group, m)
-        xh = B.dequantize_cluster(q.codes, q.labels, q.params, x.numel(), group, m)
-        err = (xh.double() - x.double())
-        nz = x != 0
-        return {"MSE": float((err * err).mean().item()),
-                "MRE": float((err[nz].abs() / x[nz].double().abs()).mean().item())}
-    sample = min(range(len(sizes)), key=lambda i: abs(sizes[i] - 11008 * 4096))
-    extras["quantisation_error_synthetic"] = {
-        "tensor": cfg.tensors[tensors[sample]][0], "elements": sizes[sample],
-        "rows": {f"{state} {label}": quality(inputs[sample][key], group, m)
-                 for state, key in (("adam1", "m"), ("adam2", "v"))
-                 for label, group, m in (("16 clusters per 4096-element group", GROUP, M),
-                                         ("16 clusters per tensor", 0, M),
-                                         ("naive 8-bit (1 cluster per tensor)", 0, 1))}}
-    # the step's own codes of that state, for whoever looks at the buffers afterwards
-    for a in (c for k, c in enumerate(calls["quantize_cluster"]) if k % 3 == 1):
-        L.bitsnap_quantize_cluster(*a)
-    torch.cuda.synchronize()
+        # quantisation error on these synthetic Adam states, next to plain min-max 8-bit (one cluster): the
+        # comparison the paper's evaluation makes on trained states (its table of MRE and MSE against naive
+        # 8-bit quantisation); torch only computes the two error measures
+        def quality(x, group, m):
+            q = B.quantize_cluster(x, group, m)
+            xh = B.dequantize_cluster(q.codes, q.labels, q.params, x.numel(), group, m)
+            err = (xh.double() - x.double())
+            nz = x != 0
+            return {"MSE": float((err * err).mean().item()),
+                    "MRE": float((err[nz].abs() / x[nz].double().abs()).mean().item())}
+        sample = min(range(len(sizes)), key=lambda i: abs(sizes[i] - 11008 * 4096))
+        extras["quantisation_error_synthetic"] = {
+            "tensor": cfg.tensors[tensors[sample]][0], "elements": sizes[sample],
+            "rows": {f"{state} {label}": quality(inputs[sample][key], group, m)
+                     for state, key in (("adam1", "m"), ("adam2", "v"))
+                     for label, group, m in (("16 clusters per 4096-element group", GROUP, M),
+                                             ("16 clusters per tensor", 0, M),
+                                             ("naive 8-bit (1 cluster per tensor)", 0, 1))}}
+        # the step's own codes of that state, for whoever looks at the buffers afterwards
+        for a in (c for k, c in enumerate(calls["quantize_cluster"]) if k % 3 == 1):
+            L.bitsnap_quantize_cluster(*a)
+        torch.cuda.synchronize()
+
 
     # ------------------------------------------------------------------ accounting
     n_changed = sum(int(e["n_changed"].item()) for e in enc)
