@@ -47,6 +47,10 @@ def _load():
     L.oracle_encode_sparse_ex.restype = i64
     L.oracle_decode_sparse_ex.argtypes = [p, p, p, i64, C.c_int, p]
     L.oracle_decode_sparse_ex.restype = None
+    L.oracle_encode_sparse32_ex.argtypes = [p, p, i64, C.c_int, p, p, p]
+    L.oracle_encode_sparse32_ex.restype = i64
+    L.oracle_decode_sparse32_ex.argtypes = [p, p, p, i64, C.c_int, p]
+    L.oracle_decode_sparse32_ex.restype = None
     L.oracle_decode_sparse.restype = None
     L.oracle_norm_quantile.argtypes = [C.c_int, C.c_int]
     L.oracle_norm_quantile.restype = C.c_double
@@ -116,6 +120,36 @@ def decode_sparse_ex(base, mask, payload, delta: bool = False) -> np.ndarray:
     out = np.empty(max(n, 1), np.uint16)
     pay = payload if payload.size else np.zeros(1, np.uint16)
     _load().oracle_decode_sparse_ex(_ptr(base), _ptr(mask), _ptr(pay), n, int(bool(delta)), _ptr(out))
+    return out[:n].copy()
+
+
+def _u32(a) -> np.ndarray:
+    a = np.ascontiguousarray(a)
+    assert a.dtype == np.uint32 and a.ndim == 1
+    return a
+
+
+def encode_sparse32(cur, base, delta: bool = False, new_base=None) -> Tuple[np.ndarray, np.ndarray, int]:
+    """32-bit elements (bit patterns as uint32).  -> (mask[ceil(n/8)], payload[n_c] uint32, n_c)."""
+    cur = _u32(cur)
+    n = cur.size
+    assert base.dtype == np.uint32 and base.flags.c_contiguous and base.size == n
+    if new_base is not None:
+        assert new_base.dtype == np.uint32 and new_base.flags.c_contiguous and new_base.size == n
+    mask = np.empty((n + 7) // 8, np.uint8)
+    payload = np.empty(max(n, 1), np.uint32)
+    nc = _load().oracle_encode_sparse32_ex(_ptr(cur), _ptr(base), n, int(bool(delta)), _ptr(mask), _ptr(payload),
+                                           None if new_base is None else _ptr(new_base))
+    return mask, payload[:nc].copy(), int(nc)
+
+
+def decode_sparse32(base, mask, payload, delta: bool = False) -> np.ndarray:
+    base, payload = _u32(base), _u32(payload)
+    mask = np.ascontiguousarray(mask, dtype=np.uint8)
+    n = base.size
+    out = np.empty(max(n, 1), np.uint32)
+    pay = payload if payload.size else np.zeros(1, np.uint32)
+    _load().oracle_decode_sparse32_ex(_ptr(base), _ptr(mask), _ptr(pay), n, int(bool(delta)), _ptr(out))
     return out[:n].copy()
 
 

@@ -145,6 +145,43 @@ void oracle_decode_sparse_ex(const uint16_t *base, const uint8_t *mask, const ui
     }
 }
 
+/* The same codec for tensors of 32-bit elements (fp32 model states): the element is "changed" iff
+ * its 32-bit pattern differs; the mask has one bit per element as before; the payload holds 32-bit
+ * values (the new ones, or cur XOR base with delta != 0).  Stored size: n/8 + 4 n_c bytes. */
+int64_t oracle_encode_sparse32_ex(const uint32_t *cur, const uint32_t *base, int64_t n, int delta,
+                                  uint8_t *mask, uint32_t *payload, uint32_t *new_base)
+{
+    int64_t nc = 0;
+    int64_t nbytes = (n + 7) / 8;
+    for (int64_t j = 0; j < nbytes; ++j)
+        mask[j] = 0;
+    for (int64_t i = 0; i < n; ++i) {
+        const uint32_t c = cur[i], b = base[i];
+        if (c != b) {
+            mask[i >> 3] = (uint8_t)(mask[i >> 3] | (1u << (i & 7)));
+            payload[nc] = delta ? (c ^ b) : c;
+            nc += 1;
+        }
+        if (new_base)
+            new_base[i] = c;
+    }
+    return nc;
+}
+
+void oracle_decode_sparse32_ex(const uint32_t *base, const uint8_t *mask, const uint32_t *payload,
+                               int64_t n, int delta, uint32_t *out)
+{
+    int64_t r = 0;
+    for (int64_t i = 0; i < n; ++i) {
+        if ((mask[i >> 3] >> (i & 7)) & 1u) {
+            out[i] = delta ? (base[i] ^ payload[r]) : payload[r];
+            r += 1;
+        } else {
+            out[i] = base[i];
+        }
+    }
+}
+
 /* ------------------------------------------------------------------------------------------
  * Cluster path
  * ---------------------------------------------------------------------------------------- */

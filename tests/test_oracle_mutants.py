@@ -23,6 +23,8 @@ MUTANTS = [
     ("delta_payload_is_sum", "payload[nc] = delta ? (uint16_t)(c ^ b) : c;", "payload[nc] = delta ? (uint16_t)(c + b) : c;", 0),
     ("delta_decode_drops_base", "out[i] = delta ? (uint16_t)(base[i] ^ payload[r]) : payload[r];", "out[i] = payload[r];", 0),
     ("new_base_only_where_changed", "        if (new_base)\n            new_base[i] = c;\n    }", "        if (new_base && c != b)\n            new_base[i] = c;\n    }", 0),
+    ("wide_elements_compare_low_half", "        const uint32_t c = cur[i], b = base[i];\n        if (c != b) {", "        const uint32_t c = cur[i], b = base[i];\n        if ((uint16_t)c != (uint16_t)b) {", 0),
+    ("wide_delta_decode_drops_base", "out[i] = delta ? (base[i] ^ payload[r]) : payload[r];", "out[i] = payload[r];", 0),
     ("offsets_inclusive", "off[t] = run;", "off[t] = run + 1;", 0),
     ("sample_std", "sqrt(q / (double)len)", "sqrt(q / (double)(len - 1))", 0),
     ("mean_not_subtracted", "double d = (double)x[i] - mean;", "double d = (double)x[i];", 0),
@@ -51,6 +53,7 @@ def _pins(golden):
     yield ts.test_decode_uses_payload_in_order
     yield lambda: ts.test_delta_payload_is_the_nonzero_part_of_the_bitwise_difference(4097, 0.06)
     yield lambda: ts.test_new_base_is_a_copy_of_cur_also_in_place(True)
+    yield lambda: ts.test_32_bit_elements_against_library_routines(4097, 0.06, True)
     yield lambda: tc.test_quantiles_are_correctly_rounded(16)
     yield tc.test_equal_probability_edges
     yield tc.test_fit_exact_on_integers
@@ -80,7 +83,7 @@ def test_planted_mistake_is_caught(tmp_path, name, find, repl, occ):
                    check=True)
     good = oracle._load()
     mut = ctypes.CDLL(str(lib))
-    for sym in ("oracle_encode_sparse", "oracle_encode_sparse_ex", "oracle_decode_sparse_ex", "oracle_encode_sparse_naive", "oracle_tile_offsets", "oracle_decode_sparse",
+    for sym in ("oracle_encode_sparse", "oracle_encode_sparse_ex", "oracle_decode_sparse_ex", "oracle_encode_sparse32_ex", "oracle_decode_sparse32_ex", "oracle_encode_sparse_naive", "oracle_tile_offsets", "oracle_decode_sparse",
                 "oracle_norm_quantile", "oracle_cluster_fit", "oracle_cluster_edges", "oracle_quantize_cluster",
                 "oracle_dequantize_cluster", "oracle_code_bruteforce"):
         getattr(mut, sym).argtypes = getattr(good, sym).argtypes

@@ -198,3 +198,46 @@ def test_new_base_is_a_copy_of_cur_also_in_place(delta):
     assert np.array_equal(oracle.decode_sparse_ex(base, ref[0], ref[1], delta=delta), cur)
     # against the refreshed base the next checkpoint of an unchanged tensor is empty
     assert oracle.encode_sparse_ex(cur, in_place, delta=delta)[2] == 0
+
+
+# 32-bit elements -----------------------------------------------------------------------------
+def _pair32(n, p, seed):
+    rng = np.random.default_rng(seed)
+    base = rng.integers(0, 1 << 32, n, dtype=np.uint32)
+    cur = base.copy()
+    sel = rng.random(n) < p
+    kind = rng.integers(0, 3, n)                                   # change only the low half, only the high half, or both
+    x = np.where(kind == 0, rng.integers(1, 1 << 16, n), np.where(kind == 1, rng.integers(1, 1 << 16, n) << 16,
+                 rng.integers(1, 1 << 32, n))).astype(np.uint32)
+    cur[sel] ^= x[sel]
+    return cur, base, int(sel.sum())
+
+
+@pytest.mark.parametrize("n", [0, 1, 7, 9, 4097, 20001])
+@pytest.mark.parametrize("p", [0.0, 0.06, 1.0])
+@pytest.mark.parametrize("delta", [False, True])
+def test_32_bit_elements_against_library_routines(n, p, delta):
+    """fp32 states: same mask (numpy.packbits, little), payload = boolean selection of the new values or of
+    cur XOR base, 4 bytes per changed element; lossless; a change confined to either 16-bit half counts."""
+    cur, base, nsel = _pair32(n, p, 6000 + n)
+    mask, payload, nc = oracle.encode_sparse32(cur, base, delta=delta)
+    changed = cur != base
+    assert nc == nsel == int(changed.sum())
+    assert np.array_equal(mask, np.packbits(changed, bitorder="little"))
+    assert payload.dtype == np.uint32
+    assert np.array_equal(payload, (cur ^ base)[changed] if delta else cur[changed])
+    assert np.array_equal(oracle.decode_sparse32(base, mask, payload, delta=delta), cur)
+    assert mask.nbytes + payload.nbytes == (n + 7) // 8 + 4 * nc   # the section's space formula with 4-byte values
+    fresh = np.zeros_like(cur)
+    again = oracle.encode_sparse32(cur, base, delta=delta, new_base=fresh)
+    assert np.array_equal(fresh, cur) and np.array_equal(again[1], payload) and again[2] == nc
+
+
+def test_32_bit_elements_are_not_two_16_bit_ones():
+    """One element whose two halves both change is ONE changed element with one 4-byte value."""
+    base = np.array([0x11112222, 0x33334444, 0x55556666], np.uint32)
+    cur = np.array([0x11112222, 0xAAAA4444, 0xBBBBCCCC], np.uint32)
+    mask, payload, nc = oracle.encode_sparse32(cur, base)
+    assert nc == 2 and mask.tolist() == [0b110] and payload.tolist() == [0xAAAA4444, 0xBBBBCCCC]
+    m16, p16, nc16 = oracle.encode_sparse(cur.view(np.uint16), base.view(np.uint16))
+    assert nc16 == 3                                               # the 16-bit view sees three changed halves
