@@ -279,7 +279,7 @@ def main():
                                      n_changed=[e["n_changed"] for e in enc], out=dec_out)
         for it in range(2):
             e0.record(stream)
-            rc = L.bitsnap_encode_sparse_batched_ex(ex_items.data_ptr(), len(sizes), total_tiles, B.SPARSE_DELTA,
+            rc = L.bitsnap_encode_sparse_batched_ex(ex_items.data_ptr(), len(sizes), total_tiles, 2, B.SPARSE_DELTA,
                                                     bws.data_ptr(), bws.numel(), sp)
             assert rc == 0, rc
             e1.record(stream)
@@ -295,6 +295,34 @@ def main():
         fn, a = bcalls["encode_sparse"][0]
         fn(*a)
         torch.cuda.synchronize()
+
+        # the sparse codec on 4-byte elements: the largest tensor's fp32 master weights against a copy in which
+        # 30 % of the elements have their lowest mantissa bit flipped (one call each, the steady state of a big tensor)
+        m32 = inputs[big]["master"].view(torch.int32)
+        g32 = torch.Generator(device=dev)
+        g32.manual_seed(synth.seed_for(cfg.index, 9999))
+        b32 = m32 ^ (torch.rand(nb, device=dev, generator=g32) < 0.3).to(torch.int32)
+        e32 = B.encode_sparse(m32, b32)
+        o32, _ = B.decode_sparse(b32, e32.mask, e32.payload, nb, workspace=e32.workspace)
+        torch.cuda.synchronize()
+        nc32 = int(e32.n_changed.item())
+        assert torch.equal(o32, m32) and nc32 == int((m32 != b32).sum().item())
+        alg32 = 8 * nb + (nb + 7) // 8 + 4 * nc32
+        row32 = {"elements": nb, "changed_fraction": round(nc32 / nb, 4)}
+        for name, fn32 in (("encode", lambda: B.encode_sparse_raw(m32, b32, nb, e32.mask, e32.payload, nb, None, e32.n_changed,
+                                                                  e32.workspace, elem_bytes=4)),
+                           ("decode", lambda: B.decode_sparse_raw(b32, e32.mask, e32.payload, nb, nb, o32, None,
+                                                                  e32.workspace, elem_bytes=4))):
+            for it in range(2):
+                e0.record(stream)
+                for _ in range(5):
+                    fn32()
+                e1.record(stream)
+                torch.cuda.synchronize()
+            ms32 = e0.elapsed_time(e1) / 5
+            row32[name] = {"ms": round(ms32, 4), "hbm_frac": round(alg32 / ms32 / 1e6 / HBM_PEAK_GBS, 4)}
+        extras["sparse_32_bit_elements"] = row32
+        del m32, b32, e32, o32
 
         # quantisation error on these synthetic Adam states, next to plain min-max 8-bit (one cluster): the
         # comparison the paper's evaluation makes on trained states (its table of MRE and MSE against naive

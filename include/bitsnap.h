@@ -64,16 +64,19 @@ int bitsnap_debug_stream_mix(void *wide, void *bytes, void *halves, int64_t n, i
  * Sparse path.  Paper: "Bitmask Based Sparsification for Model States" (improved bitmask,
  * space n/8 + 2 n_c, Eq. improved-bitmask) and Algorithm 1.
  *
- * Format of one encoded tensor of n 16-bit elements (fp16 and bf16 are the same to the codec):
- *   mask     bit i (byte i/8, bit position i%8, least significant first) is 1 iff the 16-bit
+ * Format of one encoded tensor of n elements of 2 bytes (fp16 and bf16 are the same to the codec)
+ * or 4 bytes:
+ *   mask     bit i (byte i/8, bit position i%8, least significant first) is 1 iff the bit
  *            pattern of cur[i] differs from base[i]; padding bits are 0.  ceil(n/8) bytes count
  *            as stored data.
  *   payload  the changed elements of cur (the new values, not differences), in index order:
  *            n_c elements of 2 bytes.
  * ---------------------------------------------------------------------------------------- */
 
-/* Number of elements covered by one entry of `tile_offsets` (32768). */
+/* Number of elements covered by one entry of `tile_offsets`: 32768 two-byte elements ... */
 size_t bitsnap_sparse_tile_elems(void);
+/* ... or 16384 four-byte ones (a tile is 64 KB of input either way); 0 for any other width. */
+size_t bitsnap_sparse_tile_elems_for(int elem_bytes);
 
 /* Bytes the caller must provide for `mask`: ceil(n/8) rounded up to a multiple of 16.  The
  * bytes after ceil(n/8) are written as 0. */
@@ -86,12 +89,16 @@ size_t bitsnap_sparse_mask_bytes(int64_t n);
  * hipMemset, torch.zeros); afterwards the kernels leave it ready for the next call, encode or
  * decode, of any size that fits, so one workspace serves a whole checkpoint. */
 size_t bitsnap_sparse_workspace_bytes(int64_t n);
+/* The same for elements of elem_bytes (2 or 4) bytes; bitsnap_sparse_workspace_bytes is the 2-byte case. */
+size_t bitsnap_sparse_workspace_bytes_for(int64_t n, int elem_bytes);
 
 /* Algorithm 1, steps 1-5, for one tensor.
- *   cur, base        [n] 16-bit elements, aligned
- *   elem_bytes       must be 2
+ *   cur, base        [n] elements of elem_bytes bytes, aligned
+ *   elem_bytes       2 (fp16 / bf16 model states, the paper's case) or 4 (fp32 states: the same
+ *                    scheme with 4-byte values, n/8 + 4 n_c bytes stored); the element is changed
+ *                    iff its whole bit pattern differs
  *   mask             [bitsnap_sparse_mask_bytes(n)] out, aligned
- *   payload          [payload_capacity_elems] 16-bit out, aligned.  If more than
+ *   payload          [payload_capacity_elems] elements out, aligned.  If more than
  *                    payload_capacity_elems elements changed, only the first
  *                    payload_capacity_elems are written; mask and n_changed are still complete,
  *                    so the caller can see the overflow (n_changed > capacity) and keep the
@@ -109,11 +116,11 @@ int bitsnap_encode_sparse(const void *cur, const void *base, int64_t n, int elem
                           void *workspace, size_t workspace_bytes, bitsnap_stream_t stream);
 
 /* Inverse of encode_sparse: out[i] = bit i of mask ? next payload element : base[i].
- *   base             [n] 16-bit, aligned
+ *   base             [n] elements of elem_bytes (2 or 4) bytes, aligned
  *   mask             [ceil(n/8)] bytes, aligned; bits at or beyond n are ignored
- *   payload          [payload_elems] 16-bit, aligned.  Never read at or beyond payload_elems;
+ *   payload          [payload_elems] elements, aligned.  Never read at or beyond payload_elems;
  *                    if the mask has more set bits than that, the surplus elements decode to 0.
- *   out              [n] 16-bit, aligned; may be the same buffer as base (in-place patch)
+ *   out              [n] elements, aligned; may be the same buffer as base (in-place patch)
  *   n_changed        nullable, [1] out: the number of set mask bits below n
  * Three launches: set bits per tile, payload offset per tile, then the merge, which has no
  * dependency between workgroups (nothing in decode waits, so it cannot give up). */
@@ -128,10 +135,10 @@ int bitsnap_decode_sparse(const void *base, const uint8_t *mask, const void *pay
 /* bitsnap_encode_sparse with two options.
  *   flags & BITSNAP_SPARSE_DELTA   the payload holds the non-zero elements of the delta states
  *                    themselves - "save the bitmask list and the non-zero elements", as the paper's
- *                    section on bitmask sparsification has it - with the delta of two 16-bit patterns
+ *                    section on bitmask sparsification has it - with the delta of two bit patterns
  *                    taken bitwise, cur XOR base, which keeps the scheme lossless.  Mask, n_changed,
  *                    tile_offsets and the order of the payload do not depend on the flag.
- *   new_base         nullable; [n] 16-bit out, aligned: receives a copy of cur, for the checkpoint that
+ *   new_base         nullable; [n] elements out, aligned: receives a copy of cur, for the checkpoint that
  *                    becomes the base of the following delta checkpoints (the paper's interval
  *                    between base checkpoints).  May be the buffer `base` itself; must not overlap
  *                    cur, mask or payload.
@@ -252,13 +259,14 @@ int bitsnap_encode_sparse_batched(const bitsnap_sparse_item *items, int64_t coun
 int bitsnap_decode_sparse_batched(const bitsnap_sparse_item *items, int64_t count, int64_t total_tiles,
                                   void *workspace, size_t workspace_bytes, bitsnap_stream_t stream);
 
-/* The batched calls with the options of bitsnap_encode_sparse_ex / bitsnap_decode_sparse_ex.  In the
- * encoder an item's `out`, where not NULL, is that tensor's new_base. */
+/* The batched calls with the options of bitsnap_encode_sparse_ex / bitsnap_decode_sparse_ex and the
+ * element width (2 or 4; first_tile and total_tiles count tiles of bitsnap_sparse_tile_elems_for(elem_bytes)
+ * elements).  In the encoder an item's `out`, where not NULL, is that tensor's new_base. */
 int bitsnap_encode_sparse_batched_ex(const bitsnap_sparse_item *items, int64_t count, int64_t total_tiles,
-                                     uint32_t flags, void *workspace, size_t workspace_bytes,
+                                     int elem_bytes, uint32_t flags, void *workspace, size_t workspace_bytes,
                                      bitsnap_stream_t stream);
 int bitsnap_decode_sparse_batched_ex(const bitsnap_sparse_item *items, int64_t count, int64_t total_tiles,
-                                     uint32_t flags, void *workspace, size_t workspace_bytes,
+                                     int elem_bytes, uint32_t flags, void *workspace, size_t workspace_bytes,
                                      bitsnap_stream_t stream);
 
 /* group must be one of 256, 512, 1024, 2048, 4096; total_groups = sum of ceil(n/group). */

@@ -17,7 +17,8 @@ LIB_PATH = os.path.join(_HERE, "libbitsnap.so")
 
 SYMBOLS = (
     "bitsnap_version", "bitsnap_error_string", "bitsnap_debug_stream_copy", "bitsnap_debug_stream_mix",
-    "bitsnap_sparse_tile_elems", "bitsnap_sparse_mask_bytes", "bitsnap_sparse_workspace_bytes",
+    "bitsnap_sparse_tile_elems", "bitsnap_sparse_tile_elems_for", "bitsnap_sparse_mask_bytes",
+    "bitsnap_sparse_workspace_bytes", "bitsnap_sparse_workspace_bytes_for",
     "bitsnap_encode_sparse", "bitsnap_decode_sparse", "bitsnap_encode_sparse_ex", "bitsnap_decode_sparse_ex",
     "bitsnap_encode_sparse_batched_ex", "bitsnap_decode_sparse_batched_ex", "bitsnap_debug_set_spin_limit",
     "bitsnap_cluster_groups", "bitsnap_cluster_param_bytes", "bitsnap_cluster_label_bytes",
@@ -62,10 +63,12 @@ def lib():
     L.bitsnap_encode_sparse_ex.restype = i
     L.bitsnap_decode_sparse_ex.argtypes = [p, p, p, i64, i64, i, C.c_uint32, p, p, p, sz, p]
     L.bitsnap_decode_sparse_ex.restype = i
-    L.bitsnap_encode_sparse_batched_ex.argtypes = [p, i64, i64, C.c_uint32, p, sz, p]
+    L.bitsnap_encode_sparse_batched_ex.argtypes = [p, i64, i64, i, C.c_uint32, p, sz, p]
     L.bitsnap_encode_sparse_batched_ex.restype = i
-    L.bitsnap_decode_sparse_batched_ex.argtypes = [p, i64, i64, C.c_uint32, p, sz, p]
+    L.bitsnap_decode_sparse_batched_ex.argtypes = [p, i64, i64, i, C.c_uint32, p, sz, p]
     L.bitsnap_decode_sparse_batched_ex.restype = i
+    L.bitsnap_sparse_tile_elems_for.argtypes, L.bitsnap_sparse_tile_elems_for.restype = [i], sz
+    L.bitsnap_sparse_workspace_bytes_for.argtypes, L.bitsnap_sparse_workspace_bytes_for.restype = [i64, i], sz
     L.bitsnap_debug_set_spin_limit.argtypes, L.bitsnap_debug_set_spin_limit.restype = [C.c_uint32], None
     L.bitsnap_cluster_groups.argtypes, L.bitsnap_cluster_groups.restype = [i64, i64], sz
     L.bitsnap_cluster_param_bytes.argtypes, L.bitsnap_cluster_param_bytes.restype = [i64, i64, i], sz
@@ -112,16 +115,18 @@ def version() -> int:
     return lib().bitsnap_version()
 
 
-def sparse_tile_elems() -> int:
-    return lib().bitsnap_sparse_tile_elems()
+def sparse_tile_elems(elem_bytes: int = 2) -> int:
+    return lib().bitsnap_sparse_tile_elems() if elem_bytes == 2 else lib().bitsnap_sparse_tile_elems_for(elem_bytes)
 
 
 def sparse_mask_bytes(n: int) -> int:
     return lib().bitsnap_sparse_mask_bytes(n)
 
 
-def sparse_workspace_bytes(n: int) -> int:
-    return lib().bitsnap_sparse_workspace_bytes(n)
+def sparse_workspace_bytes(n: int, elem_bytes: int = 2) -> int:
+    if elem_bytes == 2:
+        return lib().bitsnap_sparse_workspace_bytes(n)
+    return lib().bitsnap_sparse_workspace_bytes_for(n, elem_bytes)
 
 
 def cluster_groups(n: int, group: int) -> int:
@@ -167,10 +172,10 @@ def debug_stream_mix(wide, small_bytes, small_halves, to_small: bool, stream=Non
                                           _stream(stream)), "bitsnap_debug_stream_mix")
 
 
-def new_sparse_workspace(n: int, device):
+def new_sparse_workspace(n: int, device, elem_bytes: int = 2):
     """A zeroed workspace good for tensors of up to n elements (reusable across calls)."""
     import torch
-    return torch.zeros(sparse_workspace_bytes(n), dtype=torch.uint8, device=device)
+    return torch.zeros(sparse_workspace_bytes(n, elem_bytes), dtype=torch.uint8, device=device)
 
 
 # ----------------------------------------------------------------------------------------------
@@ -180,29 +185,29 @@ SPARSE_DELTA = 1  # BITSNAP_SPARSE_DELTA
 
 
 def encode_sparse_raw(cur, base, n: int, mask, payload, payload_capacity: int, tile_offsets, n_changed,
-                      workspace, stream=None, *, flags: int = 0, new_base=None) -> None:
+                      workspace, stream=None, *, flags: int = 0, new_base=None, elem_bytes: int = 2) -> None:
     """flags == 0 and new_base is None: bitsnap_encode_sparse; otherwise bitsnap_encode_sparse_ex."""
     wsb = workspace.numel() * workspace.element_size()
     if flags == 0 and new_base is None:
-        rc = lib().bitsnap_encode_sparse(_ptr(cur), _ptr(base), n, 2, _ptr(mask), _ptr(payload), payload_capacity,
+        rc = lib().bitsnap_encode_sparse(_ptr(cur), _ptr(base), n, elem_bytes, _ptr(mask), _ptr(payload), payload_capacity,
                                          _ptr(tile_offsets), _ptr(n_changed), _ptr(workspace), wsb, _stream(stream))
         _check(rc, "bitsnap_encode_sparse")
     else:
-        rc = lib().bitsnap_encode_sparse_ex(_ptr(cur), _ptr(base), n, 2, flags, _ptr(mask), _ptr(payload),
+        rc = lib().bitsnap_encode_sparse_ex(_ptr(cur), _ptr(base), n, elem_bytes, flags, _ptr(mask), _ptr(payload),
                                             payload_capacity, _ptr(tile_offsets), _ptr(n_changed), _ptr(new_base),
                                             _ptr(workspace), wsb, _stream(stream))
         _check(rc, "bitsnap_encode_sparse_ex")
 
 
 def decode_sparse_raw(base, mask, payload, payload_elems: int, n: int, out, n_changed, workspace, stream=None, *,
-                      flags: int = 0) -> None:
+                      flags: int = 0, elem_bytes: int = 2) -> None:
     wsb = workspace.numel() * workspace.element_size()
     if flags == 0:
-        rc = lib().bitsnap_decode_sparse(_ptr(base), _ptr(mask), _ptr(payload), payload_elems, n, 2, _ptr(out),
+        rc = lib().bitsnap_decode_sparse(_ptr(base), _ptr(mask), _ptr(payload), payload_elems, n, elem_bytes, _ptr(out),
                                          _ptr(n_changed), _ptr(workspace), wsb, _stream(stream))
         _check(rc, "bitsnap_decode_sparse")
     else:
-        rc = lib().bitsnap_decode_sparse_ex(_ptr(base), _ptr(mask), _ptr(payload), payload_elems, n, 2, flags, _ptr(out),
+        rc = lib().bitsnap_decode_sparse_ex(_ptr(base), _ptr(mask), _ptr(payload), payload_elems, n, elem_bytes, flags, _ptr(out),
                                             _ptr(n_changed), _ptr(workspace), wsb, _stream(stream))
         _check(rc, "bitsnap_decode_sparse_ex")
 
@@ -226,8 +231,8 @@ def dequantize_cluster_raw(codes, labels, params, n: int, group: int, m: int, ou
 # convenience forms: allocate the outputs with torch, then call the raw form
 # ----------------------------------------------------------------------------------------------
 def _flat16(t):
-    import torch
-    assert t.is_cuda and t.is_contiguous() and t.element_size() == 2, "need a contiguous 16-bit device tensor"
+    """Flat view of a contiguous device tensor of 2-byte or 4-byte elements (the name is historical)."""
+    assert t.is_cuda and t.is_contiguous() and t.element_size() in (2, 4), "need a contiguous 16- or 32-bit device tensor"
     return t.reshape(-1)
 
 
@@ -239,18 +244,20 @@ def encode_sparse(cur, base, *, capacity: Optional[int] = None, want_offsets: bo
     import torch
     cur, base = _flat16(cur), _flat16(base)
     n = cur.numel()
-    assert base.numel() == n
+    eb = cur.element_size()
+    assert base.numel() == n and base.element_size() == eb
     dev = cur.device
     capacity = n if capacity is None else capacity
     mask = torch.empty(sparse_mask_bytes(n), dtype=torch.uint8, device=dev)
-    payload = torch.empty(max(capacity, 1), dtype=torch.int16, device=dev)
+    payload = torch.empty(max(capacity, 1), dtype=torch.int16 if eb == 2 else torch.int32, device=dev)
     n_changed = torch.empty(1, dtype=torch.int64, device=dev)
-    tiles = (n + sparse_tile_elems() - 1) // sparse_tile_elems()
+    tiles = (n + sparse_tile_elems(eb) - 1) // sparse_tile_elems(eb)
     offs = torch.empty(max(tiles, 1), dtype=torch.int32, device=dev) if want_offsets else None
     if workspace is None:
-        workspace = new_sparse_workspace(n, dev)
+        workspace = new_sparse_workspace(n, dev, eb)
     encode_sparse_raw(cur, base, n, mask, payload, capacity, offs, n_changed, workspace, stream,
-                      flags=SPARSE_DELTA if delta else 0, new_base=None if new_base is None else _flat16(new_base))
+                      flags=SPARSE_DELTA if delta else 0, new_base=None if new_base is None else _flat16(new_base),
+                      elem_bytes=eb)
     return SimpleNamespace(mask=mask, payload=payload, n_changed=n_changed, tile_offsets=offs, workspace=workspace,
                            n=n, capacity=capacity)
 
@@ -265,10 +272,11 @@ def decode_sparse(base, mask, payload, payload_elems: int, *, out=None, workspac
         out = torch.empty_like(base)
     out_f = _flat16(out)
     n_changed = torch.empty(1, dtype=torch.int64, device=base.device)
+    eb = base_f.element_size()
     if workspace is None:
-        workspace = new_sparse_workspace(n, base.device)
+        workspace = new_sparse_workspace(n, base.device, eb)
     decode_sparse_raw(base_f, mask, payload, payload_elems, n, out_f, n_changed, workspace, stream,
-                      flags=SPARSE_DELTA if delta else 0)
+                      flags=SPARSE_DELTA if delta else 0, elem_bytes=eb)
     return out, n_changed
 
 
@@ -335,11 +343,11 @@ def sparse_batch_workspace_bytes(total_tiles: int) -> int:
 
 
 def sparse_items(n_list, *, src=None, base=None, mask=None, payload=None, out=None, n_changed=None,
-                 tile_offsets=None, capacity=None):
+                 tile_offsets=None, capacity=None, elem_bytes: int = 2):
     """Device array of bitsnap_sparse_item (10 x int64 per tensor) from parallel lists of torch tensors
     (None where a field is unused).  -> (items int64[count, 10], total_tiles)."""
     import torch
-    T = sparse_tile_elems()
+    T = sparse_tile_elems(elem_bytes)
     rows, first = [], 0
     ptr = lambda lst, k: 0 if lst is None or lst[k] is None else lst[k].data_ptr()
     for k, n in enumerate(n_list):
@@ -351,26 +359,28 @@ def sparse_items(n_list, *, src=None, base=None, mask=None, payload=None, out=No
     return torch.tensor(rows, dtype=torch.int64).to(dev), first
 
 
-def encode_sparse_batched(items, total_tiles: int, workspace, stream=None, *, flags: Optional[int] = None) -> None:
+def encode_sparse_batched(items, total_tiles: int, workspace, stream=None, *, flags: Optional[int] = None,
+                          elem_bytes: int = 2) -> None:
     """flags None: bitsnap_encode_sparse_batched; an int: the _ex form (an item's `out` is then its new_base)."""
     wsb = workspace.numel() * workspace.element_size()
-    if flags is None:
+    if flags is None and elem_bytes == 2:
         rc = lib().bitsnap_encode_sparse_batched(_ptr(items), items.shape[0], total_tiles, _ptr(workspace), wsb,
                                                  _stream(stream))
         _check(rc, "bitsnap_encode_sparse_batched")
     else:
-        rc = lib().bitsnap_encode_sparse_batched_ex(_ptr(items), items.shape[0], total_tiles, flags, _ptr(workspace), wsb,
-                                                    _stream(stream))
+        rc = lib().bitsnap_encode_sparse_batched_ex(_ptr(items), items.shape[0], total_tiles, elem_bytes, flags or 0,
+                                                    _ptr(workspace), wsb, _stream(stream))
         _check(rc, "bitsnap_encode_sparse_batched_ex")
 
 
-def decode_sparse_batched(items, total_tiles: int, workspace, stream=None, *, flags: Optional[int] = None) -> None:
+def decode_sparse_batched(items, total_tiles: int, workspace, stream=None, *, flags: Optional[int] = None,
+                          elem_bytes: int = 2) -> None:
     wsb = workspace.numel() * workspace.element_size()
-    if flags is None:
+    if flags is None and elem_bytes == 2:
         rc = lib().bitsnap_decode_sparse_batched(_ptr(items), items.shape[0], total_tiles, _ptr(workspace), wsb,
                                                  _stream(stream))
         _check(rc, "bitsnap_decode_sparse_batched")
     else:
-        rc = lib().bitsnap_decode_sparse_batched_ex(_ptr(items), items.shape[0], total_tiles, flags, _ptr(workspace), wsb,
-                                                    _stream(stream))
+        rc = lib().bitsnap_decode_sparse_batched_ex(_ptr(items), items.shape[0], total_tiles, elem_bytes, flags or 0,
+                                                    _ptr(workspace), wsb, _stream(stream))
         _check(rc, "bitsnap_decode_sparse_batched_ex")

@@ -3,10 +3,11 @@
 // its inverse.  Encode is one kernel and one pass over HBM; decode is three kernels, of which
 // only the last touches more than the mask.
 //
-// A tile is 32768 consecutive elements (4 rounds of 8192) and is processed by one 512-thread
-// workgroup; all of a tile's loads are issued before anything waits on them.  A lane owns 8
-// consecutive elements per 16-byte load (one mask byte); in each round a wavefront owns two
-// consecutive 512-element chunks.  Per-lane popcounts are scanned with DPP inside the wave,
+// Elements are 2 bytes (fp16 / bf16 model states) or 4 bytes (fp32 states); E is the element width.
+// A tile is 64 KB of each input - 32768 2-byte or 16384 4-byte elements, in rounds of 8192 - and
+// is processed by one 512-thread workgroup; all of a tile's loads are issued before anything
+// waits on them.  A lane owns pieces of 8 consecutive elements (one mask byte; one or two 16-byte
+// loads); in each round a wavefront owns two consecutive 512-element chunks.  Per-lane popcounts are scanned with DPP inside the wave,
 // through LDS across the eight waves and the rounds, and (encode) with the decoupled look-back
 // of scan_state.hpp across tiles.  The tile is large because every tile costs the machine one
 // same-address atomic (the ticket) and a handful of polls of its predecessors' scan words, and
@@ -15,6 +16,8 @@
 // payload buffer, whatever the tile's offset.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+
+#include <type_traits>
 
 #include "../../include/bitsnap.h"
 #include "host_util.hpp"
@@ -28,15 +31,31 @@ constexpr int kWaves = kBlock / kWave;
 constexpr int kLaneElems = 8;                              // one 16-byte load of 16-bit elements
 constexpr int kChunkElems = kWave * kLaneElems;            // 512: what one wave covers with one load
 constexpr int kRoundChunks = 2 * kWaves;                   // a round: every wave takes two consecutive chunks
-constexpr int kRoundElems = kRoundChunks * kChunkElems;    // 4096
-constexpr int kRounds = 4;                                 // rounds per tile, all loaded before the scan
-constexpr int kTileElems = kRounds * kRoundElems;          // one ticket, one status word, one look-back
+constexpr int kRoundElems = kRoundChunks * kChunkElems;    // 8192
+
+template <int E>
+struct Geom {
+    static_assert(E == 2 || E == 4, "16-bit or 32-bit elements");
+    typedef typename std::conditional<E == 2, uint16_t, uint32_t>::type elem_t;
+    typedef __attribute__((address_space(1))) elem_t global_elem_t;
+    static constexpr int kVecs = E / 2;                       // 16-byte loads per 8-element piece
+    static constexpr int kRounds = 8 / E;                     // rounds per tile, all loaded before the scan
+    static constexpr int kTileElems = kRounds * kRoundElems;  // one ticket, one status word, one look-back
+    static constexpr int kVecElems = 16 / E;                  // elements per 16 bytes
+};
+
+// The lane's 8 consecutive elements
+template <int E>
+struct Piece {
+    uint4 v[Geom<E>::kVecs];
+};
 
 // The tile's changed values pass through `stage`: at their rank inside the tile in the encoder
 // (before the tile's place in the payload is known), as the aligned payload segment in the decoder.
+template <int E>
 struct TileShared {
-    alignas(16) uint16_t stage[kTileElems + 16];  // + what a realigning read (encode) or a shifted segment (decode) adds
-    uint32_t wave_total[kRounds][kWaves];
+    alignas(16) typename Geom<E>::elem_t stage[Geom<E>::kTileElems + 16];  // + what realigning (encode) or a shifted segment (decode) adds
+    uint32_t wave_total[Geom<E>::kRounds][kWaves];
     uint64_t excl;
     int64_t next_tile;
     int aborted;
@@ -69,52 +88,69 @@ __device__ __forceinline__ void store_global16(void *p, uint4 v)
         *(global_u32x4 *)p = t;
 }
 
-// 8 elements to p[e0 .. e0+8) (e0 a multiple of 8), clipped at n
-__device__ __forceinline__ void store8(uint16_t *p, int64_t e0, int64_t n, uint4 v)
+__device__ __forceinline__ uint32_t word_of(const uint4 &v, int k) { return k == 0 ? v.x : k == 1 ? v.y : k == 2 ? v.z : v.w; }
+
+// element t (0..7) of a piece
+template <int E>
+__device__ __forceinline__ typename Geom<E>::elem_t piece_elem(const Piece<E> &pc, int t)
 {
-    if (e0 + kLaneElems <= n) {
-        store_global16<false>(p + e0, v);
-        return;
-    }
-    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
-    for (int t = 0; t < kLaneElems; ++t)
-        if (e0 + t < n)
-            ((global_u16 *)p)[e0 + t] = (uint16_t)(w[t >> 1] >> ((t & 1) * 16));
+    if (E == 2)
+        return (typename Geom<E>::elem_t)(word_of(pc.v[0], t >> 1) >> ((t & 1) * 16));
+    return (typename Geom<E>::elem_t)word_of(pc.v[(E == 4) ? (t >> 2) : 0], t & 3);
 }
 
-// bit t = 1 iff 16-bit element t of x is non-zero; with x = cur XOR base: the element changed
-// (Algorithm 1 steps 1-2)
-__device__ __forceinline__ uint32_t nonzero16_bits(uint4 v)
+// 8 elements to p[e0 .. e0+8) (e0 a multiple of 8), clipped at n
+template <int E>
+__device__ __forceinline__ void store8(typename Geom<E>::elem_t *p, int64_t e0, int64_t n, const Piece<E> &pc)
 {
-    const uint32_t x[4] = {v.x, v.y, v.z, v.w};
-    uint32_t m = 0;
+    if (e0 + kLaneElems <= n) {
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        m |= ((x[j] & 0xFFFFu) != 0u ? 1u : 0u) << (2 * j);
-        m |= ((x[j] >> 16) != 0u ? 1u : 0u) << (2 * j + 1);
+        for (int k = 0; k < Geom<E>::kVecs; ++k)
+            store_global16<false>(p + e0 + k * Geom<E>::kVecElems, pc.v[k]);
+        return;
+    }
+    for (int t = 0; t < kLaneElems; ++t)
+        if (e0 + t < n)
+            ((typename Geom<E>::global_elem_t *)p)[e0 + t] = piece_elem<E>(pc, t);
+}
+
+// bit t = 1 iff element t of x is non-zero; with x = cur XOR base: the element changed
+// (Algorithm 1 steps 1-2)
+template <int E>
+__device__ __forceinline__ uint32_t nonzero_bits(const Piece<E> &x)
+{
+    uint32_t m = 0;
+    if (E == 2) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const uint32_t w = word_of(x.v[0], j);
+            m |= ((w & 0xFFFFu) != 0u ? 1u : 0u) << (2 * j);
+            m |= ((w >> 16) != 0u ? 1u : 0u) << (2 * j + 1);
+        }
+    } else {
+#pragma unroll
+        for (int t = 0; t < 8; ++t)
+            m |= (word_of(x.v[(E == 4) ? (t >> 2) : 0], t & 3) != 0u ? 1u : 0u) << t;
     }
     return m;
 }
 
-__device__ __forceinline__ uint16_t elem16(const uint4 &v, int t)
-{
-    const uint32_t w = (t >> 1) == 0 ? v.x : (t >> 1) == 1 ? v.y : (t >> 1) == 2 ? v.z : v.w;
-    return (uint16_t)(w >> ((t & 1) * 16));
-}
-
 // Where the calling lane's 8-element pieces sit inside a tile: round r, piece j (0 or 1)
-//   chunk  = tile*8R + r*8 + wave*2 + j        element = chunk*512 + lane*8
+//   chunk  = tile*16R + r*16 + wave*2 + j        element = chunk*512 + lane*8
 // so element order is round-major, then wave, then piece, then lane.
+template <int E>
 __device__ __forceinline__ int64_t piece_chunk(int64_t tile, int r, int wave, int j)
 {
-    return tile * (kRounds * kRoundChunks) + r * kRoundChunks + wave * 2 + j;
+    return tile * (Geom<E>::kRounds * kRoundChunks) + r * kRoundChunks + wave * 2 + j;
 }
 
 // Per-lane popcounts cnt[r][j] -> this lane's exclusive rank of each piece inside the tile;
 // returns the tile total.  Contains one __syncthreads.
-__device__ __forceinline__ uint32_t tile_ranks(TileShared &sh, const uint32_t (&cnt)[kRounds][2], int lane, int wave,
-                                               uint32_t (&rank)[kRounds][2])
+template <int E>
+__device__ __forceinline__ uint32_t tile_ranks(TileShared<E> &sh, const uint32_t (&cnt)[Geom<E>::kRounds][2], int lane,
+                                               int wave, uint32_t (&rank)[Geom<E>::kRounds][2])
 {
+    constexpr int kRounds = Geom<E>::kRounds;
     uint32_t ex[kRounds], t0[kRounds];
 #pragma unroll
     for (int r = 0; r < kRounds; ++r) {
@@ -148,7 +184,8 @@ __device__ __forceinline__ uint32_t tile_ranks(TileShared &sh, const uint32_t (&
 // the same tensor; publishes the inclusive value; the result reaches the other waves through
 // sh.excl / sh.aborted.  `tile` and `first_tile` (the tensor's first tile) are in the launch-wide
 // numbering.
-__device__ __forceinline__ void tile_look_back(TileShared &sh, ScanHeader *hdr, uint64_t *status, int64_t tile,
+template <int E>
+__device__ __forceinline__ void tile_look_back(TileShared<E> &sh, ScanHeader *hdr, uint64_t *status, int64_t tile,
                                                int64_t first_tile, uint32_t epoch, uint32_t spin_limit,
                                                uint32_t tile_total, int lane)
 {
@@ -169,21 +206,27 @@ __device__ __forceinline__ void tile_look_back(TileShared &sh, ScanHeader *hdr, 
 // All of a tile's loads for the calling lane (issued back to back, nothing waits here): a
 // wave-uniform tile base plus a 32-bit offset each.  A piece that starts at or beyond the end of
 // the tensor reads the tile's first piece instead, and a piece that straddles the end is read
-// whole: the buffer is 16-byte aligned, so an aligned 16-byte piece never leaves the page its
-// first element is in.  The caller ignores what lies at or beyond n (piece_valid_bits).
-__device__ __forceinline__ void load_tile16(const uint16_t *__restrict__ p, int64_t tile, int wave, int lane, int64_t n,
-                                            uint4 (&v)[kRounds][2])
+// whole: the buffer is 16-byte aligned and a piece is 16 or 32 bytes at a multiple of its size, so
+// it never leaves the page its first element is in.  The caller ignores what lies at or beyond n
+// (piece_valid_bits).
+template <int E>
+__device__ __forceinline__ void load_tile(const typename Geom<E>::elem_t *__restrict__ p, int64_t tile, int wave, int lane,
+                                          int64_t n, Piece<E> (&v)[Geom<E>::kRounds][2])
 {
+    constexpr int kTileElems = Geom<E>::kTileElems;
     const int64_t t0 = tile * kTileElems;
-    const uint16_t *__restrict__ tp = p + t0;  // wave-uniform
+    const typename Geom<E>::elem_t *__restrict__ tp = p + t0;  // wave-uniform
     const uint32_t rem = n - t0 >= kTileElems ? (uint32_t)kTileElems : (uint32_t)(n - t0);
     const uint32_t e0 = (uint32_t)(wave * (2 * kChunkElems) + lane * kLaneElems);
 #pragma unroll
-    for (int r = 0; r < kRounds; ++r)
+    for (int r = 0; r < Geom<E>::kRounds; ++r)
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
             const uint32_t e = e0 + (uint32_t)((r * kRoundChunks + j) * kChunkElems);
-            v[r][j] = load_global16<true>(tp + (e < rem ? e : 0u));
+            const uint32_t es = e < rem ? e : 0u;
+#pragma unroll
+            for (int k = 0; k < Geom<E>::kVecs; ++k)
+                v[r][j].v[k] = load_global16<true>(tp + es + k * Geom<E>::kVecElems);
         }
 }
 
@@ -202,7 +245,11 @@ __device__ __forceinline__ uint64_t uniform64(uint64_t t)
 }
 
 // The value thread 0 left in sh.next_tile, as a scalar in every thread (call after a barrier).
-__device__ __forceinline__ int64_t claimed_tile(const TileShared &sh) { return (int64_t)uniform64((uint64_t)sh.next_tile); }
+template <int E>
+__device__ __forceinline__ int64_t claimed_tile(const TileShared<E> &sh)
+{
+    return (int64_t)uniform64((uint64_t)sh.next_tile);
+}
 
 // The tensor a launch-wide tile number belongs to.  Tickets only grow, so a workgroup walks the
 // item list forwards.  With kBatched == false there is one tensor, passed by value.
@@ -252,44 +299,52 @@ __device__ __forceinline__ void report_failures(int epilogue, const bitsnap_spar
     }
 }
 
-// Algorithm 1 step 5, second half: payload[excl + i] = stage[i], i < total.  Payload element
-// excl - shift is 16-byte aligned; piece q covers payload elements [dst0 + 8q, dst0 + 8q + 8), i.e.
-// stage elements from 8q - shift, read as five dwords and shifted by one element when shift is
-// odd.  The ragged ends of the tile's segment, and whatever would cross the payload capacity, go
-// out element by element.
-__device__ __forceinline__ void copy_out_stage(const TileShared &sh, uint16_t *__restrict__ payload, int64_t capacity,
-                                               uint64_t excl, uint32_t total, int tid)
+// Algorithm 1 step 5, second half: payload[excl + i] = stage[i], i < total.  With P = 16 / E
+// elements per 16 bytes, payload element excl - shift (shift = excl mod P) is 16-byte aligned;
+// piece q covers payload elements [dst0 + P*q, dst0 + P*q + P), i.e. stage elements from P*q - shift,
+// read as dwords and, for 2-byte elements and an odd shift, moved by one element.  The ragged
+// ends of the tile's segment, and whatever would cross the payload capacity, go out element by
+// element.
+template <int E>
+__device__ __forceinline__ void copy_out_stage(const TileShared<E> &sh, typename Geom<E>::elem_t *__restrict__ payload,
+                                               int64_t capacity, uint64_t excl, uint32_t total, int tid)
 {
-    const uint32_t shift = (uint32_t)(excl & 7u);
+    constexpr uint32_t P = Geom<E>::kVecElems;
+    const uint32_t shift = (uint32_t)(excl & (P - 1u));
     const uint32_t first = shift, last = shift + total;
     const int64_t dst0 = (int64_t)(excl - shift);
-    const uint32_t pieces = (last + 7u) >> 3;
-    const uint32_t odd_bytes = (shift & 1u) * 2u;
+    const uint32_t pieces = (last + P - 1u) / P;
+    const uint32_t odd_bytes = (E == 2) ? (shift & 1u) * 2u : 0u;
     const uint32_t *stage32 = reinterpret_cast<const uint32_t *>(sh.stage);
     uint64_t base_bits = (uint64_t)payload;
-    asm volatile("" : "+s"(base_bits));                              // stays in scalar registers
-    uint16_t *__restrict__ dst = (uint16_t *)base_bits + dst0;       // wave-uniform, 16-byte aligned
-    const int64_t room = capacity - dst0;                            // elements of dst that may be written
-    const uint32_t fits = room >= (int64_t)(kTileElems + 8) ? (uint32_t)(kTileElems + 8) : room > 0 ? (uint32_t)room : 0u;
+    asm volatile("" : "+s"(base_bits));                                             // stays in scalar registers
+    typename Geom<E>::elem_t *__restrict__ dst = (typename Geom<E>::elem_t *)base_bits + dst0;  // wave-uniform, 16-byte aligned
+    const int64_t room = capacity - dst0;                                            // elements of dst that may be written
+    constexpr int64_t kMost = Geom<E>::kTileElems + (int64_t)P;
+    const uint32_t fits = room >= kMost ? (uint32_t)kMost : room > 0 ? (uint32_t)room : 0u;
     for (uint32_t q = tid; q < pieces; q += kBlock) {
-        const uint32_t lo = q * 8u;
-        if (lo >= first && lo + 8u <= last && lo + 8u <= fits) {
-            const uint32_t w0 = (lo - shift) >> 1;
+        const uint32_t lo = q * P;
+        if (lo >= first && lo + P <= last && lo + P <= fits) {
+            const uint32_t w0 = ((lo - shift) * (uint32_t)E) >> 2;
             uint32_t w[5];
 #pragma unroll
-            for (int k = 0; k < 5; ++k)
+            for (int k = 0; k < (E == 2 ? 5 : 4); ++k)
                 w[k] = stage32[w0 + k];
             uint4 v;
-            v.x = __builtin_amdgcn_alignbyte(w[1], w[0], odd_bytes);
-            v.y = __builtin_amdgcn_alignbyte(w[2], w[1], odd_bytes);
-            v.z = __builtin_amdgcn_alignbyte(w[3], w[2], odd_bytes);
-            v.w = __builtin_amdgcn_alignbyte(w[4], w[3], odd_bytes);
+            if (E == 2) {
+                v.x = __builtin_amdgcn_alignbyte(w[1], w[0], odd_bytes);
+                v.y = __builtin_amdgcn_alignbyte(w[2], w[1], odd_bytes);
+                v.z = __builtin_amdgcn_alignbyte(w[3], w[2], odd_bytes);
+                v.w = __builtin_amdgcn_alignbyte(w[4], w[3], odd_bytes);
+            } else {
+                v = make_uint4(w[0], w[1], w[2], w[3]);
+            }
             store_global16<true>(dst + lo, v);
         } else {
-            for (uint32_t t = 0; t < 8u; ++t) {
+            for (uint32_t t = 0; t < P; ++t) {
                 const uint32_t i = lo + t;
                 if (i >= first && i < last && i < fits)
-                    ((global_u16 *)dst)[i] = sh.stage[i - shift];
+                    ((typename Geom<E>::global_elem_t *)dst)[i] = sh.stage[i - shift];
             }
         }
     }
@@ -310,14 +365,16 @@ __device__ __forceinline__ void copy_out_stage(const TileShared &sh, uint16_t *_
 // kDelta: the payload holds cur XOR base (the non-zero elements of the delta states) instead of
 // cur.  refresh: item.out, where set, receives a copy of cur (it may be the base buffer itself: a
 // tile's base is in registers before the tile's copy of cur is stored, and no other tile touches it).
-template <bool kBatched, bool kDelta>
+template <bool kBatched, bool kDelta, int E>
 __global__ __launch_bounds__(kBlock, 4) void encode_sparse_kernel(bitsnap_sparse_item single,
                                                                const bitsnap_sparse_item *__restrict__ items,
                                                                int64_t count, ScanHeader *hdr, uint64_t *status,
                                                                int64_t status_cap, int64_t num_tiles, uint32_t spin_limit,
                                                                int refresh)
 {
-    __shared__ TileShared sh;
+    typedef typename Geom<E>::elem_t elem_t;
+    constexpr int kRounds = Geom<E>::kRounds, kTileElems = Geom<E>::kTileElems;
+    __shared__ TileShared<E> sh;
     const int tid0 = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid0 >> 6);
     const uint32_t epoch = hdr->epoch;
     bool aborted = false;
@@ -328,7 +385,7 @@ __global__ __launch_bounds__(kBlock, 4) void encode_sparse_kernel(bitsnap_sparse
     __syncthreads();
     // the previous tile of this workgroup: staged in LDS, still to be copied out
     bool staged = false;
-    uint16_t *__restrict__ staged_payload = nullptr;
+    elem_t *__restrict__ staged_payload = nullptr;
     int64_t staged_capacity = 0;
     uint64_t staged_excl = 0;
     uint32_t staged_total = 0;
@@ -340,14 +397,14 @@ __global__ __launch_bounds__(kBlock, 4) void encode_sparse_kernel(bitsnap_sparse
         const int lane = tid & (kWave - 1);
         const int64_t gtile = claimed_tile(sh);
         const bool valid = gtile < num_tiles;
-        uint4 c[kRounds][2], b[kRounds][2];
+        Piece<E> c[kRounds][2], b[kRounds][2];
         if (valid) {  // this tile's loads fly while the previous tile's values leave
             cursor.seek(gtile);
-            load_tile16((const uint16_t *)cursor.it.src, gtile - cursor.it.first_tile, wave, lane, cursor.it.n, c);
-            load_tile16((const uint16_t *)cursor.it.base, gtile - cursor.it.first_tile, wave, lane, cursor.it.n, b);
+            load_tile<E>((const elem_t *)cursor.it.src, gtile - cursor.it.first_tile, wave, lane, cursor.it.n, c);
+            load_tile<E>((const elem_t *)cursor.it.base, gtile - cursor.it.first_tile, wave, lane, cursor.it.n, b);
         }
         if (staged)
-            copy_out_stage(sh, staged_payload, staged_capacity, staged_excl, staged_total, tid);
+            copy_out_stage<E>(sh, staged_payload, staged_capacity, staged_excl, staged_total, tid);
         if (!valid)
             break;
         __syncthreads();  // the stage has been read
@@ -360,7 +417,7 @@ __global__ __launch_bounds__(kBlock, 4) void encode_sparse_kernel(bitsnap_sparse
         const int32_t wave_mask_bytes =
             (full_tile ? (int32_t)(kTileElems / 8) : (int32_t)(mask_bytes - tile * (kTileElems / 8))) - wave * (2 * kWave);
         const uint32_t tile_elems = full_tile ? (uint32_t)kTileElems : (uint32_t)(n - tile * kTileElems);
-        uint16_t *new_base = refresh ? (uint16_t *)it.out : nullptr;
+        elem_t *new_base = refresh ? (elem_t *)it.out : nullptr;
 
         uint32_t m[kRounds][2], cnt[kRounds][2], rank[kRounds][2];
 #pragma unroll
@@ -368,10 +425,13 @@ __global__ __launch_bounds__(kBlock, 4) void encode_sparse_kernel(bitsnap_sparse
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
                 if (new_base)
-                    store8(new_base, piece_chunk(tile, r, wave, j) * kChunkElems + lane * kLaneElems, n, c[r][j]);
-                const uint4 x = make_uint4(c[r][j].x ^ b[r][j].x, c[r][j].y ^ b[r][j].y, c[r][j].z ^ b[r][j].z,
-                                           c[r][j].w ^ b[r][j].w);
-                m[r][j] = nonzero16_bits(x) & piece_valid_bits(r, j, wave, lane, tile_elems);
+                    store8<E>(new_base, piece_chunk<E>(tile, r, wave, j) * kChunkElems + lane * kLaneElems, n, c[r][j]);
+                Piece<E> x;
+#pragma unroll
+                for (int k = 0; k < Geom<E>::kVecs; ++k)
+                    x.v[k] = make_uint4(c[r][j].v[k].x ^ b[r][j].v[k].x, c[r][j].v[k].y ^ b[r][j].v[k].y,
+                                        c[r][j].v[k].z ^ b[r][j].v[k].z, c[r][j].v[k].w ^ b[r][j].v[k].w);
+                m[r][j] = nonzero_bits<E>(x) & piece_valid_bits(r, j, wave, lane, tile_elems);
                 if (kDelta)
                     c[r][j] = x;
                 cnt[r][j] = __popc(m[r][j]);
@@ -380,7 +440,7 @@ __global__ __launch_bounds__(kBlock, 4) void encode_sparse_kernel(bitsnap_sparse
                 if (mb + lane < wave_mask_bytes)
                     ((global_u8 *)(wave_mask + mb))[(uint32_t)lane] = (uint8_t)m[r][j];
             }
-        const uint32_t total = tile_ranks(sh, cnt, lane, wave, rank);  // barrier
+        const uint32_t total = tile_ranks<E>(sh, cnt, lane, wave, rank);  // barrier
         if (tid == 0)
             publish(status, gtile, make_status(tile == 0 ? kFlagInclusive : kFlagAggregate, epoch, total));
 
@@ -393,7 +453,7 @@ __global__ __launch_bounds__(kBlock, 4) void encode_sparse_kernel(bitsnap_sparse
 #pragma unroll
                 for (int t = 0; t < kLaneElems; ++t)
                     if ((m[r][j] >> t) & 1u)
-                        sh.stage[p++] = elem16(c[r][j], t);
+                        sh.stage[p++] = piece_elem<E>(c[r][j], t);
             }
         __syncthreads();  // the stage is complete
         if (wave == 0)
@@ -404,7 +464,7 @@ __global__ __launch_bounds__(kBlock, 4) void encode_sparse_kernel(bitsnap_sparse
             break;
         }
         staged = true;
-        staged_payload = (uint16_t *)it.payload;
+        staged_payload = (elem_t *)it.payload;
         staged_capacity = it.capacity;
         staged_excl = uniform64(sh.excl);
         staged_total = __builtin_amdgcn_readfirstlane(total);
@@ -422,14 +482,15 @@ __global__ __launch_bounds__(kBlock, 4) void encode_sparse_kernel(bitsnap_sparse
 }
 
 // The lane's mask bytes of one tile; bits at or beyond n are cleared.
+template <int E>
 __device__ __forceinline__ void load_tile_mask(const uint8_t *__restrict__ mask, int64_t mask_bytes, int64_t tile,
-                                               int wave, int lane, int64_t n, uint32_t (&m)[kRounds][2])
+                                               int wave, int lane, int64_t n, uint32_t (&m)[Geom<E>::kRounds][2])
 {
 #pragma unroll
-    for (int r = 0; r < kRounds; ++r)
+    for (int r = 0; r < Geom<E>::kRounds; ++r)
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
-            const int64_t ch = piece_chunk(tile, r, wave, j);
+            const int64_t ch = piece_chunk<E>(tile, r, wave, j);
             const int64_t mb = ch * kWave + lane, e = ch * kChunkElems + lane * kLaneElems;
             uint32_t bits = (mb < mask_bytes) ? ((const global_u8 *)mask)[mb] : 0u;
             if (e + kLaneElems > n)
@@ -459,8 +520,8 @@ __device__ __forceinline__ int64_t find_sparse_item(const bitsnap_sparse_item *_
     return lo;
 }
 
-// One wave per tile: popcount of the tile's 2 KB of mask (bits at or beyond n do not count).
-template <bool kBatched>
+// One wave per tile: popcount of the tile's 4 or 2 KB of mask (bits at or beyond n do not count).
+template <bool kBatched, int E>
 __global__ __launch_bounds__(kBlock) void decode_count_kernel(bitsnap_sparse_item single,
                                                               const bitsnap_sparse_item *__restrict__ items,
                                                               int64_t count, int64_t num_tiles,
@@ -473,7 +534,7 @@ __global__ __launch_bounds__(kBlock) void decode_count_kernel(bitsnap_sparse_ite
     const bitsnap_sparse_item &it = kBatched ? items[find_sparse_item(items, count, gt)] : single;
     const int64_t tile = gt - it.first_tile, n = it.n;
     const int64_t mask_bytes = (n + 7) >> 3;
-    constexpr int kTileMaskBytes = kTileElems / 8, kPerLane = kTileMaskBytes / kWave;  // 2048 and 32 at 4 rounds
+    constexpr int kTileMaskBytes = Geom<E>::kTileElems / 8, kPerLane = kTileMaskBytes / kWave;
     static_assert(kPerLane % 8 == 0, "a lane reads whole 8-byte pieces of the mask");
     uint32_t c = 0;
 #pragma unroll
@@ -505,7 +566,7 @@ __global__ __launch_bounds__(kBlock) void decode_count_kernel(bitsnap_sparse_ite
 
 // One workgroup per tensor: exclusive scan of its tiles' counts -> payload offset of every tile,
 // and the tensor's total.
-template <bool kBatched>
+template <bool kBatched, int E>
 __global__ __launch_bounds__(kBlock) void decode_scan_kernel(bitsnap_sparse_item single,
                                                              const bitsnap_sparse_item *__restrict__ items,
                                                              const uint32_t *__restrict__ tile_count,
@@ -514,7 +575,7 @@ __global__ __launch_bounds__(kBlock) void decode_scan_kernel(bitsnap_sparse_item
     __shared__ uint64_t wave_sum_s[kWaves];
     __shared__ uint64_t carry_s;
     const bitsnap_sparse_item &it = kBatched ? items[blockIdx.x] : single;
-    const int64_t ntiles = (it.n + kTileElems - 1) / kTileElems, first = it.first_tile;
+    const int64_t ntiles = (it.n + Geom<E>::kTileElems - 1) / Geom<E>::kTileElems, first = it.first_tile;
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
     if (tid == 0)
         carry_s = 0;
@@ -543,50 +604,55 @@ __global__ __launch_bounds__(kBlock) void decode_scan_kernel(bitsnap_sparse_item
 // One workgroup per tile: out = bit ? next payload element : base.  The tile's place in the payload
 // and its length are known from the two kernels before, so mask, base and the payload segment are
 // all requested at once; the segment goes through LDS as aligned 16-byte pieces (stage[i] holds
-// payload element src0 + i, src0 a multiple of 8), from where every lane picks its elements by rank.
-// kDelta: the payload holds cur XOR base; the element is base XOR payload.
-template <bool kBatched, bool kDelta>
+// payload element src0 + i, src0 a multiple of 16 / E), from where every lane picks its elements
+// by rank.  kDelta: the payload holds cur XOR base; the element is base XOR payload.
+template <bool kBatched, bool kDelta, int E>
 __global__ __launch_bounds__(kBlock, 4) void decode_merge_kernel(bitsnap_sparse_item single,
                                                                  const bitsnap_sparse_item *__restrict__ items,
                                                                  int64_t count, const uint64_t *__restrict__ tile_offset,
                                                                  const uint32_t *__restrict__ tile_count)
 {
-    __shared__ TileShared sh;
+    typedef typename Geom<E>::elem_t elem_t;
+    typedef typename Geom<E>::global_elem_t global_elem_t;
+    constexpr int kRounds = Geom<E>::kRounds, kTileElems = Geom<E>::kTileElems;
+    constexpr uint32_t P = Geom<E>::kVecElems;
+    __shared__ TileShared<E> sh;
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int64_t gtile = blockIdx.x;
     const bitsnap_sparse_item &it = kBatched ? items[find_sparse_item(items, count, gtile)] : single;
-    const uint16_t *base = (const uint16_t *)it.base;  // may alias out
+    const elem_t *base = (const elem_t *)it.base;  // may alias out
     const uint8_t *__restrict__ mask = it.mask;
-    const uint16_t *__restrict__ payload = (const uint16_t *)it.payload;
-    uint16_t *out = (uint16_t *)it.out;
+    const elem_t *__restrict__ payload = (const elem_t *)it.payload;
+    elem_t *out = (elem_t *)it.out;
     const int64_t n = it.n, payload_elems = it.capacity, tile = gtile - it.first_tile;
     const int64_t mask_bytes = (n + 7) >> 3;
 
     const uint64_t excl = tile_offset[gtile];
     const uint32_t total = tile_count[gtile];
-    const uint32_t shift = (uint32_t)(excl & 7u);
+    const uint32_t shift = (uint32_t)(excl & (P - 1u));
     const int64_t src0 = (int64_t)(excl - shift);
-    const uint32_t pieces = (shift + total + 7u) >> 3;  // at most kTileElems / 8 + 1
-    constexpr int kPiecesPerThread = kTileElems / 8 / kBlock;
+    const uint32_t pieces = (shift + total + P - 1u) / P;  // at most kTileElems / P + 1
+    constexpr int kPiecesPerThread = kTileElems / (int)P / kBlock;
 
     uint32_t m[kRounds][2], cnt[kRounds][2], rank[kRounds][2];
-    uint4 v[kRounds][2], pv[kPiecesPerThread];
-    load_tile_mask(mask, mask_bytes, tile, wave, lane, n, m);
-    load_tile16(base, tile, wave, lane, n, v);
-    const uint16_t *__restrict__ seg = payload + src0;  // wave-uniform, 16-byte aligned
-    const int64_t seg_elems = payload_elems - src0;      // elements of seg that may be read
+    Piece<E> v[kRounds][2];
+    uint4 pv[kPiecesPerThread];
+    load_tile_mask<E>(mask, mask_bytes, tile, wave, lane, n, m);
+    load_tile<E>(base, tile, wave, lane, n, v);
+    const elem_t *__restrict__ seg = payload + src0;  // wave-uniform, 16-byte aligned
+    const int64_t seg_elems = payload_elems - src0;    // elements of seg that may be read
 #pragma unroll
     for (int i = 0; i < kPiecesPerThread; ++i) {
         const uint32_t q = (uint32_t)(i * kBlock + tid);
         pv[i] = make_uint4(0, 0, 0, 0);
         if (q < pieces) {
-            if ((int64_t)(q * 8u + 8u) <= seg_elems) {
-                pv[i] = load_global16<false>(seg + q * 8u);
+            if ((int64_t)(q * P + P) <= seg_elems) {
+                pv[i] = load_global16<false>(seg + q * P);
             } else {
                 uint32_t w[4] = {0, 0, 0, 0};
-                for (uint32_t t = 0; t < 8u; ++t)
-                    if ((int64_t)(q * 8u + t) < seg_elems)
-                        w[t >> 1] |= (uint32_t)((const global_u16 *)seg)[q * 8u + t] << ((t & 1) * 16);
+                for (uint32_t t = 0; t < P; ++t)
+                    if ((int64_t)(q * P + t) < seg_elems)
+                        w[(t * E) >> 2] |= (uint32_t)((const global_elem_t *)seg)[q * P + t] << (((t * E) & 3u) * 8u);
                 pv[i] = make_uint4(w[0], w[1], w[2], w[3]);
             }
         }
@@ -596,14 +662,14 @@ __global__ __launch_bounds__(kBlock, 4) void decode_merge_kernel(bitsnap_sparse_
 #pragma unroll
         for (int j = 0; j < 2; ++j)
             cnt[r][j] = __popc(m[r][j]);
-    tile_ranks(sh, cnt, lane, wave, rank);  // barrier
+    tile_ranks<E>(sh, cnt, lane, wave, rank);  // barrier
 #pragma unroll
     for (int i = 0; i < kPiecesPerThread; ++i)
-        *reinterpret_cast<uint4 *>(&sh.stage[(uint32_t)(i * kBlock + tid) * 8u]) = pv[i];
+        *reinterpret_cast<uint4 *>(&sh.stage[(uint32_t)(i * kBlock + tid) * P]) = pv[i];
     if (tid == 0 && pieces > (uint32_t)(kPiecesPerThread * kBlock)) {  // a full tile that starts off the 16-byte grid
         const uint32_t q = (uint32_t)(kPiecesPerThread * kBlock);
-        for (uint32_t t = 0; t < 8u; ++t)
-            sh.stage[q * 8u + t] = (int64_t)(q * 8u + t) < seg_elems ? ((const global_u16 *)seg)[q * 8u + t] : (uint16_t)0;
+        for (uint32_t t = 0; t < P; ++t)
+            sh.stage[q * P + t] = (int64_t)(q * P + t) < seg_elems ? ((const global_elem_t *)seg)[q * P + t] : (elem_t)0;
     }
     __syncthreads();
 #pragma unroll
@@ -611,19 +677,28 @@ __global__ __launch_bounds__(kBlock, 4) void decode_merge_kernel(bitsnap_sparse_
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
             uint32_t p = shift + rank[r][j];
-            uint32_t w[4] = {v[r][j].x, v[r][j].y, v[r][j].z, v[r][j].w};
+            uint32_t w[2 * E];  // the piece's dwords
+#pragma unroll
+            for (int k = 0; k < 2 * E; ++k)
+                w[k] = word_of(v[r][j].v[k >> 2], k & 3);
 #pragma unroll
             for (int t = 0; t < kLaneElems; ++t) {
                 if ((m[r][j] >> t) & 1u) {
                     const uint32_t s = sh.stage[p++];
-                    if (kDelta)
+                    if (E == 4) {
+                        w[t] = kDelta ? (w[t] ^ s) : s;
+                    } else if (kDelta) {
                         w[t >> 1] ^= s << ((t & 1) * 16);
-                    else
+                    } else {
                         w[t >> 1] = (t & 1) ? ((w[t >> 1] & 0x0000FFFFu) | (s << 16)) : ((w[t >> 1] & 0xFFFF0000u) | s);
+                    }
                 }
             }
-            store8(out, piece_chunk(tile, r, wave, j) * kChunkElems + lane * kLaneElems, n,
-                   make_uint4(w[0], w[1], w[2], w[3]));
+            Piece<E> res;
+#pragma unroll
+            for (int k = 0; k < Geom<E>::kVecs; ++k)
+                res.v[k] = make_uint4(w[4 * k + 0], w[4 * k + 1], w[4 * k + 2], w[4 * k + 3]);
+            store8<E>(out, piece_chunk<E>(tile, r, wave, j) * kChunkElems + lane * kLaneElems, n, res);
         }
 }
 
@@ -650,13 +725,24 @@ static int sparse_grid(const void *kernel, int64_t num_tiles)
     return (int)(g < 1 ? 1 : g);
 }
 
-static int check_workspace(void *workspace, size_t workspace_bytes, int64_t n)
+static int64_t tile_elems_of(int elem_bytes) { return elem_bytes == 4 ? Geom<4>::kTileElems : Geom<2>::kTileElems; }
+static int64_t tiles_of(int64_t n, int elem_bytes)
+{
+    return n <= 0 ? 0 : (n + tile_elems_of(elem_bytes) - 1) / tile_elems_of(elem_bytes);
+}
+static size_t workspace_bytes_for_tiles(int64_t tiles)
+{
+    const size_t bytes = kScanHeaderBytes + (size_t)(tiles < 0 ? 0 : tiles) * kWorkspaceBytesPerTile;
+    return (bytes + 255) / 256 * 256;
+}
+
+static int check_workspace(void *workspace, size_t workspace_bytes, int64_t n, int elem_bytes)
 {
     if (!workspace)
         return BITSNAP_E_NULL;
     if (!aligned16(workspace))
         return BITSNAP_E_ALIGN;
-    if (workspace_bytes < bitsnap_sparse_workspace_bytes(n))
+    if (workspace_bytes < workspace_bytes_for_tiles(tiles_of(n, elem_bytes)))
         return BITSNAP_E_WORKSPACE;
     return BITSNAP_OK;
 }
@@ -665,7 +751,12 @@ static int check_workspace(void *workspace, size_t workspace_bytes, int64_t n)
 
 using namespace bitsnap;
 
-extern "C" size_t bitsnap_sparse_tile_elems(void) { return (size_t)kTileElems; }
+extern "C" size_t bitsnap_sparse_tile_elems(void) { return (size_t)Geom<2>::kTileElems; }
+
+extern "C" size_t bitsnap_sparse_tile_elems_for(int elem_bytes)
+{
+    return (elem_bytes == 2 || elem_bytes == 4) ? (size_t)tile_elems_of(elem_bytes) : 0;
+}
 
 extern "C" size_t bitsnap_sparse_mask_bytes(int64_t n)
 {
@@ -674,16 +765,14 @@ extern "C" size_t bitsnap_sparse_mask_bytes(int64_t n)
     return (size_t)((((n + 7) / 8) + 15) / 16 * 16);
 }
 
-extern "C" size_t bitsnap_sparse_workspace_bytes(int64_t n)
+extern "C" size_t bitsnap_sparse_workspace_bytes(int64_t n) { return workspace_bytes_for_tiles(tiles_of(n, 2)); }
+
+extern "C" size_t bitsnap_sparse_workspace_bytes_for(int64_t n, int elem_bytes)
 {
-    const int64_t tiles = n <= 0 ? 0 : (n + kTileElems - 1) / kTileElems;
-    const size_t bytes = kScanHeaderBytes + (size_t)tiles * kWorkspaceBytesPerTile;
-    return (bytes + 255) / 256 * 256;
+    return (elem_bytes == 2 || elem_bytes == 4) ? workspace_bytes_for_tiles(tiles_of(n, elem_bytes)) : 0;
 }
 
 extern "C" void bitsnap_debug_set_spin_limit(uint32_t polls) { g_spin_limit = polls ? polls : kDefaultSpinLimit; }
-
-static int64_t tiles_of(int64_t n) { return n <= 0 ? 0 : (n + kTileElems - 1) / kTileElems; }
 
 template <typename Kernel>
 static int launch_scan(Kernel kernel, const bitsnap_sparse_item &single, const bitsnap_sparse_item *items, int64_t count,
@@ -709,9 +798,9 @@ static int check_scan_workspace(void *workspace, size_t workspace_bytes, int64_t
     return BITSNAP_OK;
 }
 
-template <bool kBatched>
-static int launch_decode(const bitsnap_sparse_item &single, const bitsnap_sparse_item *items, int64_t count,
-                         int64_t num_tiles, void *workspace, bitsnap_stream_t stream, bool delta)
+template <bool kBatched, int E>
+static int launch_decode_e(const bitsnap_sparse_item &single, const bitsnap_sparse_item *items, int64_t count,
+                           int64_t num_tiles, void *workspace, bitsnap_stream_t stream, bool delta)
 {
     uint64_t *tile_offset = reinterpret_cast<uint64_t *>(reinterpret_cast<char *>(workspace) + kScanHeaderBytes);
     uint32_t *tile_count = reinterpret_cast<uint32_t *>(tile_offset + num_tiles);
@@ -719,19 +808,47 @@ static int launch_decode(const bitsnap_sparse_item &single, const bitsnap_sparse
     if (num_tiles > 0) {
         if ((num_tiles + kWaves - 1) / kWaves > 0x7FFFFFFF || num_tiles > 0x7FFFFFFF)
             return BITSNAP_E_SIZE;
-        hipLaunchKernelGGL(decode_count_kernel<kBatched>, dim3((unsigned)((num_tiles + kWaves - 1) / kWaves)), dim3(kBlock),
-                           0, s, single, items, count, num_tiles, tile_count);
+        hipLaunchKernelGGL((decode_count_kernel<kBatched, E>), dim3((unsigned)((num_tiles + kWaves - 1) / kWaves)),
+                           dim3(kBlock), 0, s, single, items, count, num_tiles, tile_count);
     }
     // the scan also reports n_changed, for an empty tensor too
-    hipLaunchKernelGGL(decode_scan_kernel<kBatched>, dim3((unsigned)(kBatched ? count : 1)), dim3(kBlock), 0, s, single,
-                       items, tile_count, tile_offset);
+    hipLaunchKernelGGL((decode_scan_kernel<kBatched, E>), dim3((unsigned)(kBatched ? count : 1)), dim3(kBlock), 0, s,
+                       single, items, tile_count, tile_offset);
     if (num_tiles > 0 && delta)
-        hipLaunchKernelGGL((decode_merge_kernel<kBatched, true>), dim3((unsigned)num_tiles), dim3(kBlock), 0, s, single,
+        hipLaunchKernelGGL((decode_merge_kernel<kBatched, true, E>), dim3((unsigned)num_tiles), dim3(kBlock), 0, s, single,
                            items, count, tile_offset, tile_count);
     else if (num_tiles > 0)
-        hipLaunchKernelGGL((decode_merge_kernel<kBatched, false>), dim3((unsigned)num_tiles), dim3(kBlock), 0, s, single,
+        hipLaunchKernelGGL((decode_merge_kernel<kBatched, false, E>), dim3((unsigned)num_tiles), dim3(kBlock), 0, s, single,
                            items, count, tile_offset, tile_count);
     return launch_status();
+}
+
+template <bool kBatched>
+static int launch_decode(const bitsnap_sparse_item &single, const bitsnap_sparse_item *items, int64_t count,
+                         int64_t num_tiles, void *workspace, bitsnap_stream_t stream, bool delta, int elem_bytes)
+{
+    if (elem_bytes == 4)
+        return launch_decode_e<kBatched, 4>(single, items, count, num_tiles, workspace, stream, delta);
+    return launch_decode_e<kBatched, 2>(single, items, count, num_tiles, workspace, stream, delta);
+}
+
+template <bool kBatched>
+static int launch_encode(const bitsnap_sparse_item &single, const bitsnap_sparse_item *items, int64_t count,
+                         int64_t num_tiles, void *workspace, size_t workspace_bytes, bitsnap_stream_t stream, bool delta,
+                         int refresh, int elem_bytes)
+{
+    if (elem_bytes == 4) {
+        if (delta)
+            return launch_scan(&encode_sparse_kernel<kBatched, true, 4>, single, items, count, num_tiles, workspace,
+                               workspace_bytes, stream, refresh);
+        return launch_scan(&encode_sparse_kernel<kBatched, false, 4>, single, items, count, num_tiles, workspace,
+                           workspace_bytes, stream, refresh);
+    }
+    if (delta)
+        return launch_scan(&encode_sparse_kernel<kBatched, true, 2>, single, items, count, num_tiles, workspace,
+                           workspace_bytes, stream, refresh);
+    return launch_scan(&encode_sparse_kernel<kBatched, false, 2>, single, items, count, num_tiles, workspace,
+                       workspace_bytes, stream, refresh);
 }
 
 extern "C" int bitsnap_encode_sparse_ex(const void *cur, const void *base, int64_t n, int elem_bytes, uint32_t flags,
@@ -739,7 +856,7 @@ extern "C" int bitsnap_encode_sparse_ex(const void *cur, const void *base, int64
                                         uint32_t *tile_offsets, uint64_t *n_changed, void *new_base, void *workspace,
                                         size_t workspace_bytes, bitsnap_stream_t stream)
 {
-    if (n < 0 || elem_bytes != 2 || payload_capacity_elems < 0 || n >= (int64_t)1 << kValueBits ||
+    if (n < 0 || (elem_bytes != 2 && elem_bytes != 4) || payload_capacity_elems < 0 || n >= (int64_t)1 << kValueBits ||
         (flags & ~(uint32_t)BITSNAP_SPARSE_DELTA))
         return BITSNAP_E_SIZE;
     if (!n_changed || (n > 0 && (!cur || !base || !mask)) || (payload_capacity_elems > 0 && !payload))
@@ -747,7 +864,7 @@ extern "C" int bitsnap_encode_sparse_ex(const void *cur, const void *base, int64
     if (!aligned16(cur) || !aligned16(base) || !aligned16(mask) || !aligned16(payload) || !aligned16(new_base) ||
         ((uintptr_t)n_changed & 7u) || ((uintptr_t)tile_offsets & 3u))
         return BITSNAP_E_ALIGN;
-    if (int rc = check_workspace(workspace, workspace_bytes, n))
+    if (int rc = check_workspace(workspace, workspace_bytes, n, elem_bytes))
         return rc;
     if (tile_offsets && n >= (int64_t)1 << 32)
         return BITSNAP_E_OFFSETS;
@@ -761,11 +878,8 @@ extern "C" int bitsnap_encode_sparse_ex(const void *cur, const void *base, int64
     it.tile_offsets = tile_offsets;
     it.n = n;
     it.capacity = payload_capacity_elems;
-    if (flags & BITSNAP_SPARSE_DELTA)
-        return launch_scan(&encode_sparse_kernel<false, true>, it, nullptr, 1, tiles_of(n), workspace, workspace_bytes,
-                           stream, new_base != nullptr);
-    return launch_scan(&encode_sparse_kernel<false, false>, it, nullptr, 1, tiles_of(n), workspace, workspace_bytes,
-                       stream, new_base != nullptr);
+    return launch_encode<false>(it, nullptr, 1, tiles_of(n, elem_bytes), workspace, workspace_bytes, stream,
+                                (flags & BITSNAP_SPARSE_DELTA) != 0, new_base != nullptr, elem_bytes);
 }
 
 extern "C" int bitsnap_encode_sparse(const void *cur, const void *base, int64_t n, int elem_bytes, uint8_t *mask,
@@ -782,14 +896,14 @@ extern "C" int bitsnap_decode_sparse_ex(const void *base, const uint8_t *mask, c
                                         uint64_t *n_changed, void *workspace, size_t workspace_bytes,
                                         bitsnap_stream_t stream)
 {
-    if (n < 0 || elem_bytes != 2 || payload_elems < 0 || n >= (int64_t)1 << kValueBits ||
+    if (n < 0 || (elem_bytes != 2 && elem_bytes != 4) || payload_elems < 0 || n >= (int64_t)1 << kValueBits ||
         (flags & ~(uint32_t)BITSNAP_SPARSE_DELTA))
         return BITSNAP_E_SIZE;
     if ((n > 0 && (!base || !mask || !out)) || (payload_elems > 0 && !payload))
         return BITSNAP_E_NULL;
     if (!aligned16(base) || !aligned16(mask) || !aligned16(payload) || !aligned16(out) || ((uintptr_t)n_changed & 7u))
         return BITSNAP_E_ALIGN;
-    if (int rc = check_workspace(workspace, workspace_bytes, n))
+    if (int rc = check_workspace(workspace, workspace_bytes, n, elem_bytes))
         return rc;
     bitsnap_sparse_item it = {};
     it.base = base;
@@ -799,7 +913,8 @@ extern "C" int bitsnap_decode_sparse_ex(const void *base, const uint8_t *mask, c
     it.n_changed = n_changed;
     it.n = n;
     it.capacity = payload_elems;
-    return launch_decode<false>(it, nullptr, 1, tiles_of(n), workspace, stream, (flags & BITSNAP_SPARSE_DELTA) != 0);
+    return launch_decode<false>(it, nullptr, 1, tiles_of(n, elem_bytes), workspace, stream,
+                                (flags & BITSNAP_SPARSE_DELTA) != 0, elem_bytes);
 }
 
 extern "C" int bitsnap_decode_sparse(const void *base, const uint8_t *mask, const void *payload, int64_t payload_elems,
@@ -810,11 +925,7 @@ extern "C" int bitsnap_decode_sparse(const void *base, const uint8_t *mask, cons
                                     workspace_bytes, stream);
 }
 
-extern "C" size_t bitsnap_sparse_batch_workspace_bytes(int64_t total_tiles)
-{
-    const size_t bytes = kScanHeaderBytes + (size_t)(total_tiles < 0 ? 0 : total_tiles) * kWorkspaceBytesPerTile;
-    return (bytes + 255) / 256 * 256;
-}
+extern "C" size_t bitsnap_sparse_batch_workspace_bytes(int64_t total_tiles) { return workspace_bytes_for_tiles(total_tiles); }
 
 static int check_batch(const bitsnap_sparse_item *items, int64_t count, int64_t total_tiles, void *workspace,
                        size_t workspace_bytes)
@@ -828,51 +939,48 @@ static int check_batch(const bitsnap_sparse_item *items, int64_t count, int64_t 
     return check_scan_workspace(workspace, workspace_bytes, total_tiles);
 }
 
-static int encode_batched(const bitsnap_sparse_item *items, int64_t count, int64_t total_tiles, uint32_t flags,
-                          int refresh, void *workspace, size_t workspace_bytes, bitsnap_stream_t stream)
+static int encode_batched(const bitsnap_sparse_item *items, int64_t count, int64_t total_tiles, int elem_bytes,
+                          uint32_t flags, int refresh, void *workspace, size_t workspace_bytes, bitsnap_stream_t stream)
 {
-    if (flags & ~(uint32_t)BITSNAP_SPARSE_DELTA)
+    if ((flags & ~(uint32_t)BITSNAP_SPARSE_DELTA) || (elem_bytes != 2 && elem_bytes != 4))
         return BITSNAP_E_SIZE;
     if (int rc = check_batch(items, count, total_tiles, workspace, workspace_bytes))
         return rc;
     if (count == 0 || total_tiles == 0)
         return BITSNAP_OK;
-    if (flags & BITSNAP_SPARSE_DELTA)
-        return launch_scan(&encode_sparse_kernel<true, true>, bitsnap_sparse_item{}, items, count, total_tiles, workspace,
-                           workspace_bytes, stream, refresh);
-    return launch_scan(&encode_sparse_kernel<true, false>, bitsnap_sparse_item{}, items, count, total_tiles, workspace,
-                       workspace_bytes, stream, refresh);
+    return launch_encode<true>(bitsnap_sparse_item{}, items, count, total_tiles, workspace, workspace_bytes, stream,
+                               (flags & BITSNAP_SPARSE_DELTA) != 0, refresh, elem_bytes);
 }
 
 extern "C" int bitsnap_encode_sparse_batched(const bitsnap_sparse_item *items, int64_t count, int64_t total_tiles,
                                              void *workspace, size_t workspace_bytes, bitsnap_stream_t stream)
 {
-    return encode_batched(items, count, total_tiles, 0u, 0, workspace, workspace_bytes, stream);
+    return encode_batched(items, count, total_tiles, 2, 0u, 0, workspace, workspace_bytes, stream);
 }
 
 extern "C" int bitsnap_encode_sparse_batched_ex(const bitsnap_sparse_item *items, int64_t count, int64_t total_tiles,
-                                                uint32_t flags, void *workspace, size_t workspace_bytes,
+                                                int elem_bytes, uint32_t flags, void *workspace, size_t workspace_bytes,
                                                 bitsnap_stream_t stream)
 {
-    return encode_batched(items, count, total_tiles, flags, 1, workspace, workspace_bytes, stream);
+    return encode_batched(items, count, total_tiles, elem_bytes, flags, 1, workspace, workspace_bytes, stream);
 }
 
 extern "C" int bitsnap_decode_sparse_batched_ex(const bitsnap_sparse_item *items, int64_t count, int64_t total_tiles,
-                                                uint32_t flags, void *workspace, size_t workspace_bytes,
+                                                int elem_bytes, uint32_t flags, void *workspace, size_t workspace_bytes,
                                                 bitsnap_stream_t stream)
 {
-    if (flags & ~(uint32_t)BITSNAP_SPARSE_DELTA)
+    if ((flags & ~(uint32_t)BITSNAP_SPARSE_DELTA) || (elem_bytes != 2 && elem_bytes != 4))
         return BITSNAP_E_SIZE;
     if (int rc = check_batch(items, count, total_tiles, workspace, workspace_bytes))
         return rc;
     if (count == 0 || total_tiles == 0)
         return BITSNAP_OK;
     return launch_decode<true>(bitsnap_sparse_item{}, items, count, total_tiles, workspace, stream,
-                               (flags & BITSNAP_SPARSE_DELTA) != 0);
+                               (flags & BITSNAP_SPARSE_DELTA) != 0, elem_bytes);
 }
 
 extern "C" int bitsnap_decode_sparse_batched(const bitsnap_sparse_item *items, int64_t count, int64_t total_tiles,
                                              void *workspace, size_t workspace_bytes, bitsnap_stream_t stream)
 {
-    return bitsnap_decode_sparse_batched_ex(items, count, total_tiles, 0u, workspace, workspace_bytes, stream);
+    return bitsnap_decode_sparse_batched_ex(items, count, total_tiles, 2, 0u, workspace, workspace_bytes, stream);
 }

@@ -63,7 +63,8 @@ def test_bad_arguments_are_rejected_on_the_host():
     enc = lambda cur, base, n, eb, mask, pay, cap, offs, nch, ws, wsb: L.bitsnap_encode_sparse(
         cur, base, n, eb, mask, pay, cap, offs, nch, ws, wsb, None)
     assert enc(a, a, -1, 2, a, a, 0, None, a, a, ws_bytes) == -2          # n < 0
-    assert enc(a, a, 4096, 4, a, a, 4096, None, a, a, ws_bytes) == -2     # element width
+    assert enc(a, a, 4096, 3, a, a, 4096, None, a, a, ws_bytes) == -2     # element width: 2 or 4 only
+    assert enc(a, a, 4096, 8, a, a, 4096, None, a, a, ws_bytes) == -2
     assert enc(None, a, 4096, 2, a, a, 4096, None, a, a, ws_bytes) == -1  # NULL input
     assert enc(a, a, 4096, 2, a, a, 4096, None, None, a, ws_bytes) == -1  # NULL n_changed
     assert enc(a + 2, a, 4096, 2, a, a, 4096, None, a, a, ws_bytes) == -3  # misaligned

@@ -348,3 +348,96 @@ def test_batched_delta_payload_and_new_base():
     B.encode_sparse_batched(items2, total, ws)
     torch.cuda.synchronize()
     assert all(bool((g == 0x1234).all()) for g in guard)
+
+
+# 32-bit elements -----------------------------------------------------------------------------
+T4 = B.sparse_tile_elems(4)
+
+
+def _pair32(n, p, seed):
+    rng = np.random.default_rng(seed)
+    base = rng.integers(0, 1 << 32, n, dtype=np.uint32)
+    cur = base.copy()
+    sel = rng.random(n) < p
+    kind = rng.integers(0, 3, n)                                   # low half only, high half only, both
+    x = np.where(kind == 0, rng.integers(1, 1 << 16, n), np.where(kind == 1, rng.integers(1, 1 << 16, n) << 16,
+                 rng.integers(1, 1 << 32, n))).astype(np.uint32)
+    cur[sel] ^= x[sel]
+    return cur, base
+
+
+def _u32_to_dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a).view(np.int32)).to(DEV)
+
+
+def _dev_to_u32(t):
+    return t.contiguous().view(torch.int32).cpu().numpy().view(np.uint32)
+
+
+@pytest.mark.parametrize("n", [0, 1, 7, 9, 4097, T4 - 1, T4, T4 + 1, 2 * T4 + 5, 3 * T4 + 777, 1_000_003])
+@pytest.mark.parametrize("p", [0.0, 0.06, 0.7, 1.0])
+def test_32_bit_elements_match_oracle(n, p):
+    """fp32 states through the same entry points (elem_bytes = 4): mask, offsets, payload, count, round trip,
+    value and delta payloads, the copy into the next base."""
+    announce("sparse 32-bit elements", n, p)
+    cur, base = _pair32(n, p, 12000 + n)
+    cur_d, base_d = _u32_to_dev(cur), _u32_to_dev(base)
+    for delta in (False, True):
+        o_mask, o_pay, o_nc = oracle.encode_sparse32(cur, base, delta=delta)
+        fresh = torch.full((max(n, 1),), 0x5A5A5A5A, dtype=torch.int32, device=DEV)[:n]
+        enc = B.encode_sparse(cur_d, base_d, delta=delta, new_base=fresh, want_offsets=True)
+        torch.cuda.synchronize()
+        assert int(enc.n_changed.item()) == o_nc
+        mask = to_np(enc.mask)
+        assert np.array_equal(mask[: o_mask.size], o_mask) and not mask[o_mask.size:].any()
+        assert np.array_equal(_dev_to_u32(enc.payload)[:o_nc], o_pay)
+        ntiles = (n + T4 - 1) // T4
+        offs = oracle.tile_offsets(o_mask, n, T4)
+        assert np.array_equal(to_np(enc.tile_offsets).view(np.uint32)[:ntiles], offs[:ntiles].astype(np.uint32))
+        assert np.array_equal(_dev_to_u32(fresh), cur)
+        out, nch = B.decode_sparse(base_d, enc.mask, enc.payload, o_nc, delta=delta, workspace=enc.workspace)
+        torch.cuda.synchronize()
+        assert int(nch.item()) == o_nc and np.array_equal(_dev_to_u32(out), cur)
+    # in place: decode over the base buffer, and a payload buffer that is too small
+    patched = base_d.clone()
+    enc = B.encode_sparse(cur_d, base_d)
+    B.decode_sparse(patched, enc.mask, enc.payload, int(enc.n_changed.item()), out=patched, workspace=enc.workspace)
+    torch.cuda.synchronize()
+    assert np.array_equal(_dev_to_u32(patched), cur)
+    o_mask, o_pay, o_nc = oracle.encode_sparse32(cur, base)
+    if o_nc > 3:
+        cap = o_nc // 2
+        small = B.encode_sparse(cur_d, base_d, capacity=cap)
+        torch.cuda.synchronize()
+        assert int(small.n_changed.item()) == o_nc
+        assert np.array_equal(_dev_to_u32(small.payload)[:cap], o_pay[:cap])
+
+
+def test_32_bit_elements_batched():
+    announce("sparse 32-bit batched")
+    sizes = [1, T4, T4 + 1, 5 * T4 + 77, 9, 200_003, 40 * T4 - 1]
+    ps = [1.0, 0.06, 0.5, 0.7, 0.0, 0.06, 0.3]
+    pairs = [_pair32(n, p, 13000 + i) for i, (n, p) in enumerate(zip(sizes, ps))]
+    cur = [_u32_to_dev(c) for c, _ in pairs]
+    base = [_u32_to_dev(b) for _, b in pairs]
+    mask = [torch.zeros(B.sparse_mask_bytes(n), dtype=torch.uint8, device=DEV) for n in sizes]
+    payload = [torch.zeros(n + 8, dtype=torch.int32, device=DEV) for n in sizes]
+    counts = [torch.zeros(1, dtype=torch.int64, device=DEV) for _ in sizes]
+    offs = [torch.zeros((n + T4 - 1) // T4, dtype=torch.int32, device=DEV) for n in sizes]
+    items, total = B.sparse_items(sizes, src=cur, base=base, mask=mask, payload=payload, n_changed=counts,
+                                  tile_offsets=offs, elem_bytes=4)
+    ws = torch.zeros(B.sparse_batch_workspace_bytes(total), dtype=torch.uint8, device=DEV)
+    for flags in (0, B.SPARSE_DELTA):
+        B.encode_sparse_batched(items, total, ws, flags=flags, elem_bytes=4)
+        out = [torch.zeros(n, dtype=torch.int32, device=DEV) for n in sizes]
+        ditems, _ = B.sparse_items(sizes, base=base, mask=mask, payload=payload, out=out, elem_bytes=4)
+        B.decode_sparse_batched(ditems, total, ws, flags=flags, elem_bytes=4)
+        torch.cuda.synchronize()
+        for k, (c, b) in enumerate(pairs):
+            o_mask, o_pay, o_nc = oracle.encode_sparse32(c, b, delta=bool(flags))
+            assert int(counts[k].item()) == o_nc
+            assert np.array_equal(to_np(mask[k])[: o_mask.size], o_mask)
+            assert np.array_equal(_dev_to_u32(payload[k])[:o_nc], o_pay)
+            o_off = oracle.tile_offsets(o_mask, sizes[k], T4)
+            assert np.array_equal(to_np(offs[k]).view(np.uint32), o_off[:-1].astype(np.uint32))
+            assert np.array_equal(_dev_to_u32(out[k]), c)
