@@ -204,11 +204,10 @@ __device__ __forceinline__ void tile_look_back(TileShared<E> &sh, ScanHeader *hd
 }
 
 // All of a tile's loads for the calling lane (issued back to back, nothing waits here): a
-// wave-uniform tile base plus a 32-bit offset each.  A piece that starts at or beyond the end of
-// the tensor reads the tile's first piece instead, and a piece that straddles the end is read
-// whole: the buffer is 16-byte aligned and a piece is 16 or 32 bytes at a multiple of its size, so
-// it never leaves the page its first element is in.  The caller ignores what lies at or beyond n
-// (piece_valid_bits).
+// wave-uniform tile base plus a 32-bit offset each.  A 16-byte load whose first element lies at or
+// beyond the end of the tensor reads the tile's first 16 bytes instead, and one that straddles the
+// end is made whole: the buffer is 16-byte aligned, so an aligned 16-byte load never leaves the
+// page its first element is in.  The caller ignores what lies at or beyond n (piece_valid_bits).
 template <int E>
 __device__ __forceinline__ void load_tile(const typename Geom<E>::elem_t *__restrict__ p, int64_t tile, int wave, int lane,
                                           int64_t n, Piece<E> (&v)[Geom<E>::kRounds][2])
@@ -223,10 +222,11 @@ __device__ __forceinline__ void load_tile(const typename Geom<E>::elem_t *__rest
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
             const uint32_t e = e0 + (uint32_t)((r * kRoundChunks + j) * kChunkElems);
-            const uint32_t es = e < rem ? e : 0u;
 #pragma unroll
-            for (int k = 0; k < Geom<E>::kVecs; ++k)
-                v[r][j].v[k] = load_global16<true>(tp + es + k * Geom<E>::kVecElems);
+            for (int k = 0; k < Geom<E>::kVecs; ++k) {
+                const uint32_t ek = e + (uint32_t)(k * Geom<E>::kVecElems);
+                v[r][j].v[k] = load_global16<true>(tp + (ek < rem ? ek : 0u));
+            }
         }
 }
 
