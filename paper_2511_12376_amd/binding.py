@@ -230,8 +230,8 @@ def dequantize_cluster_raw(codes, labels, params, n: int, group: int, m: int, ou
 # ----------------------------------------------------------------------------------------------
 # convenience forms: allocate the outputs with torch, then call the raw form
 # ----------------------------------------------------------------------------------------------
-def _flat16(t):
-    """Flat view of a contiguous device tensor of 2-byte or 4-byte elements (the name is historical)."""
+def _flat_elems(t):
+    """Flat view of a contiguous device tensor of 2-byte or 4-byte elements."""
     assert t.is_cuda and t.is_contiguous() and t.element_size() in (2, 4), "need a contiguous 16- or 32-bit device tensor"
     return t.reshape(-1)
 
@@ -242,7 +242,7 @@ def encode_sparse(cur, base, *, capacity: Optional[int] = None, want_offsets: bo
     tile_offsets int32[tiles] or None, workspace).  Nothing is synchronised.
     delta: the payload holds cur XOR base; new_base: 16-bit tensor that receives a copy of cur (may be base)."""
     import torch
-    cur, base = _flat16(cur), _flat16(base)
+    cur, base = _flat_elems(cur), _flat_elems(base)
     n = cur.numel()
     eb = cur.element_size()
     assert base.numel() == n and base.element_size() == eb
@@ -256,7 +256,7 @@ def encode_sparse(cur, base, *, capacity: Optional[int] = None, want_offsets: bo
     if workspace is None:
         workspace = new_sparse_workspace(n, dev, eb)
     encode_sparse_raw(cur, base, n, mask, payload, capacity, offs, n_changed, workspace, stream,
-                      flags=SPARSE_DELTA if delta else 0, new_base=None if new_base is None else _flat16(new_base),
+                      flags=SPARSE_DELTA if delta else 0, new_base=None if new_base is None else _flat_elems(new_base),
                       elem_bytes=eb)
     return SimpleNamespace(mask=mask, payload=payload, n_changed=n_changed, tile_offsets=offs, workspace=workspace,
                            n=n, capacity=capacity)
@@ -266,11 +266,11 @@ def decode_sparse(base, mask, payload, payload_elems: int, *, out=None, workspac
                   delta: bool = False):
     """-> (out, n_changed[1] device).  ``out`` defaults to a new tensor like ``base``."""
     import torch
-    base_f = _flat16(base)
+    base_f = _flat_elems(base)
     n = base_f.numel()
     if out is None:
         out = torch.empty_like(base)
-    out_f = _flat16(out)
+    out_f = _flat_elems(out)
     n_changed = torch.empty(1, dtype=torch.int64, device=base.device)
     eb = base_f.element_size()
     if workspace is None:
