@@ -43,7 +43,7 @@ struct alignas(16) WaveShared {
     float tab[2 * kMaxClusters][kWave];  // rows 0..15: running min per cluster, rows 16..31: running max
     float tree[kMaxClusters];            // node i of the edge search tree (node 1 = root), [0] unused
     float2 coder[kMaxClusters];          // (b, 255/S) for quantize, (S/255, b) for dequantize
-    float2 bins[kBins];                  // label search by bins: (the edge inside the bin or +inf, edges below the bin)
+    float2 bins[kBins];                  // label search by bins: (the edge inside the bin or NaN, edges below the bin)
 };
 
 // Orders this wave's LDS writes before its later LDS reads (lanes exchange data through LDS).
@@ -163,11 +163,11 @@ struct LabelSearch {
 };
 
 // ---- step 2: edges e_k = fl32(mu + sigma * z_k), product and sum rounded separately in fp64;
-// lane k holds e_k (returned through `edge`; +inf where there is no edge: never <= x).  Fills
-// ws.tree and ws.bins.
+// lane k holds e_k (returned through `edge`; NaN where there is no edge: never <= x, whatever x).
+// Fills ws.tree and ws.bins.
 __device__ __forceinline__ LabelSearch build_search(float mu, float sigma, int m, WaveShared &ws, int lane, float &edge)
 {
-    edge = INFINITY;
+    edge = __uint_as_float(0x7FC00000u);
     if (lane >= 1 && lane < m)
         edge = (float)__dadd_rn((double)mu, __dmul_rn((double)sigma, kZDev[m][lane]));
     if (lane >= 1 && lane < kMaxClusters) {
@@ -178,12 +178,13 @@ __device__ __forceinline__ LabelSearch build_search(float mu, float sigma, int m
     ls.root = read_lane(edge, 8);
     ls.bin_r = __fdiv_rn(kBinsPerSigma, sigma);
     ls.bin_c = __fsub_rn(kBinOffset, __fmul_rn(mu, ls.bin_r));
-    ws.bins[lane] = make_float2(INFINITY, 0.0f);
+    ws.bins[lane] = make_float2(__uint_as_float(0x7FC00000u), 0.0f);  // NaN: no edge here, and x >= NaN never holds
     wave_lds_sync();
     if (lane >= 1 && lane < m)
         ws.bins[bin_of(edge, ls.bin_r, ls.bin_c)].x = edge;
     wave_lds_sync();
-    const uint64_t occupied = __ballot(ws.bins[lane].x < INFINITY);
+    const float mine = ws.bins[lane].x;
+    const uint64_t occupied = __ballot(mine == mine);
     ls.by_bins = (int)__popcll(occupied) == m - 1 && ls.bin_r > 0.0f;
     const uint32_t below = __builtin_amdgcn_mbcnt_hi((uint32_t)(occupied >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)occupied, 0u));
     ws.bins[lane].y = __uint_as_float(below);

@@ -193,6 +193,28 @@ def test_non_finite_input_sets_status_and_stays_in_bounds():
     assert out.shape[0] == x.size
 
 
+@pytest.mark.parametrize("m", [16, 5, 1])
+@pytest.mark.parametrize("G", [4096, 0])
+def test_infinite_elements_keep_every_label_below_m(m, G):
+    """Values outside every bin of the label search (+inf, -inf, huge) in otherwise ordinary groups: the group
+    is reported through the status word, and whatever the output is, every label stays a valid cluster
+    index and the clean groups are exact."""
+    announce("cluster infinite elements", m, G)
+    rng = np.random.default_rng(5 + m)
+    x = (rng.standard_normal(4 * 4096) * 1e-3).astype(np.float32)
+    x[4096 + 7] = np.inf
+    x[2 * 4096 + 100] = -np.inf
+    x[2 * 4096 + 101] = np.inf
+    x[3 * 4096 + 9] = 3.0e38                                      # finite, but sigma overflows
+    g, q = _gpu_quantize(x, G, m)
+    assert g["status"] & 1
+    lab = oracle.unpack_labels(g["labels"], x.size)
+    assert lab.max() < m
+    if G == 4096:
+        o = oracle.quantize_cluster(x[:4096].copy(), 4096, m)
+        assert np.array_equal(g["codes"][:4096], o["codes"]) and np.array_equal(lab[:4096], oracle.unpack_labels(o["labels"], 4096))
+
+
 def test_dequantize_oracle_bytes():
     """GPU dequantise fed with the ORACLE's compressed bytes reproduces the oracle's output."""
     announce("cluster dequantize oracle bytes")
