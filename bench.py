@@ -210,6 +210,8 @@ def main():
         copy_gbps = 5 * 2 * cal_bytes / (e0.elapsed_time(e1) * 1e-3) / 1e9
 
     mix_ceiling, extras = None, {}
+    state_bytes_of = {"encode_sparse": 2 * n_total, "decode_sparse": 2 * n_total,
+                      "quantize_cluster": 12 * n_total, "dequantize_cluster": 12 * n_total}
     if not args.no_extras:
         # what the memory system leaves to win for the cluster codecs: the same bytes in the same pattern, no arithmetic
         mix_n = min(n_max, 1 << 28) // 4096 * 4096
@@ -323,6 +325,31 @@ def main():
             row32[name] = {"ms": round(ms32, 4), "hbm_frac": round(alg32 / ms32 / 1e6 / HBM_PEAK_GBS, 4)}
         extras["sparse_32_bit_elements"] = row32
         del m32, b32, e32, o32
+
+        # the one-call-per-tensor step again, captured once in a HIP graph and replayed: what is left of it when
+        # the host no longer issues 2328 calls per step
+        side = torch.cuda.Stream()
+        side.wait_stream(stream)
+        ssp = side.cuda_stream
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            for op in order:
+                fn = fns[op]
+                for a in calls[op]:
+                    rc = fn(*(a[:-1] + (ssp,)))
+                    assert rc == 0, rc
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        t_g = time.time()
+        for _ in range(3):
+            graph.replay()
+        torch.cuda.synchronize()
+        graph_ms = (time.time() - t_g) / 3 * 1e3
+        extras["per_tensor_step_replayed_from_graph"] = {"ms_per_step": round(graph_ms, 3),
+                                                         "value_GBps": round(sum(state_bytes_of.values()) / graph_ms / 1e6, 1),
+                                                         "kernel_nodes": sum(len(calls[op]) for op in order)}
+        del graph
 
         # quantisation error on these synthetic Adam states, next to plain min-max 8-bit (one cluster): the
         # comparison the paper's evaluation makes on trained states (its table of MRE and MSE against naive
