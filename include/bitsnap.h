@@ -3,7 +3,8 @@
  * (arXiv 2511.12376) as hand-written HIP kernels for gfx950 (MI355X).
  *
  *   encode_sparse / decode_sparse          bitmask-based delta sparsification of 16-bit model
- *                                          states against a base checkpoint (lossless)
+ *                                          states (or 32-bit ones) against a base checkpoint
+ *                                          (lossless)
  *   quantize_cluster / dequantize_cluster  cluster-based 8-bit quantisation of fp32 optimizer
  *                                          states (lossy, error bounded per cluster)
  *
