@@ -62,6 +62,12 @@ def _load():
     L.oracle_quantize_cluster.restype = None
     L.oracle_dequantize_cluster.argtypes = [p, p, p, i64, i64, C.c_int, p]
     L.oracle_dequantize_cluster.restype = None
+    L.oracle_quantize_cluster_ex.argtypes = [p, i64, i64, C.c_int, p, p, C.c_int, p, p, p, p]
+    L.oracle_quantize_cluster_ex.restype = None
+    L.oracle_dequantize_cluster_ex.argtypes = [p, p, p, i64, i64, C.c_int, p, C.c_int, p]
+    L.oracle_dequantize_cluster_ex.restype = None
+    L.oracle_code_qmap_bruteforce.argtypes = [C.c_float, C.c_float, C.c_float, p, p]
+    L.oracle_code_qmap_bruteforce.restype = C.c_int
     L.oracle_code_bruteforce.argtypes = [C.c_float, C.c_float, C.c_float, p]
     L.oracle_code_bruteforce.restype = C.c_int
     _lib = L
@@ -233,6 +239,50 @@ def dequantize_cluster(codes, labels, params, n: int, G: int = 4096, m: int = 16
     out = np.zeros(n, np.float32)
     _load().oracle_dequantize_cluster(_ptr(codes), _ptr(labels), _ptr(params), n, G, m, _ptr(out))
     return out
+
+
+def _qmap(qmap) -> Optional[np.ndarray]:
+    if qmap is None:
+        return None
+    q = np.ascontiguousarray(qmap, dtype=np.float32)
+    assert q.shape == (256,)
+    return q
+
+
+def quantize_cluster_ex(x, G: int = 4096, m: int = 16, fit_in=None, qmap=None, cluster_major: bool = False):
+    """Format variants: a 256-entry map Q (None = linear) and / or cluster-major codes.  Same dict as quantize_cluster."""
+    x = _f32(x)
+    n = x.size
+    g = n_groups(n, G)
+    codes = np.zeros(n, np.uint8)
+    labels = np.zeros((n + 1) // 2, np.uint8)
+    params = np.zeros((g, m, 2), np.float32)
+    fit = np.zeros((g, 2 + m - 1), np.float32)
+    fi = None
+    if fit_in is not None:
+        fi = np.ascontiguousarray(fit_in, dtype=np.float32).reshape(g, 2)
+    _load().oracle_quantize_cluster_ex(_ptr(x), n, G, m, _ptr(fi), _ptr(_qmap(qmap)), int(bool(cluster_major)),
+                                       _ptr(codes), _ptr(labels), _ptr(params), _ptr(fit))
+    return dict(codes=codes, labels=labels, params=params, fit=fit)
+
+
+def dequantize_cluster_ex(codes, labels, params, n: int, G: int = 4096, m: int = 16, qmap=None,
+                          cluster_major: bool = False) -> np.ndarray:
+    codes = np.ascontiguousarray(codes, dtype=np.uint8)
+    labels = np.ascontiguousarray(labels, dtype=np.uint8)
+    params = np.ascontiguousarray(params, dtype=np.float32)
+    out = np.zeros(n, np.float32)
+    _load().oracle_dequantize_cluster_ex(_ptr(codes), _ptr(labels), _ptr(params), n, G, m, _ptr(_qmap(qmap)),
+                                         int(bool(cluster_major)), _ptr(out))
+    return out
+
+
+def code_qmap_bruteforce(x, b, S, qmap) -> Tuple[int, float]:
+    gap = C.c_double()
+    q = _qmap(qmap)
+    j = _load().oracle_code_qmap_bruteforce(C.c_float(float(x)), C.c_float(float(b)), C.c_float(float(S)), _ptr(q),
+                                            C.byref(gap))
+    return int(j), float(gap.value)
 
 
 def code_bruteforce(x, b, S) -> Tuple[int, float]:

@@ -21,6 +21,7 @@
 #include <math.h>
 #include <stddef.h>
 #include <stdint.h>
+#include <stdlib.h>
 #include <string.h>
 
 /* ------------------------------------------------------------------------------------------
@@ -371,6 +372,157 @@ void oracle_dequantize_cluster(const uint8_t *codes, const uint8_t *labels, cons
         float t = (float)codes[i] * step;
         out[i] = t + b;
     }
+}
+
+/* ------------------------------------------------------------------------------------------
+ * Format variants of the cluster path: a general (non-linear) map Q^map, and the cluster-major
+ * arrangement of the codes that Eq. decluster describes.
+ * ---------------------------------------------------------------------------------------- */
+
+/* Eq. qmap-distance with a table of 256 reals: t = (x-b)/S, code = the j that minimises
+ * |Q_j - t|, the lowest such j when several do.  The decision is taken in fp32, the precision
+ * of the data: t = fl32(fl32(x-b) * fl32(1/S)), distance = fl32(|Q_j - t|).  S == 0, or S so
+ * small that 1/S is not finite, codes everything as 0 (as with the linear map). */
+static uint8_t code_of_qmap(float x, float b, float S, const float *qmap)
+{
+    if (!(S > 0.0f))
+        return 0;
+    float inv = 1.0f / S;
+    if (!isfinite(inv))
+        return 0;
+    float d = x - b;
+    float t = d * inv;
+    int best = 0;
+    float bd = INFINITY;
+    for (int j = 0; j < 256; ++j) {
+        float dist = fabsf(qmap[j] - t);
+        if (dist < bd) {
+            bd = dist;
+            best = j;
+        }
+    }
+    return (uint8_t)best;
+}
+
+/* Algorithm 2 with the two format options.
+ *   qmap          (nullable) [256]: Q^map; NULL = the linear map, exactly oracle_quantize_cluster
+ *   cluster_major 0: codes in element order
+ *                 1: inside every group the codes of cluster 0 come first, then those of cluster
+ *                    1, ...; inside a cluster in the order of the elements (the T_{C_i k} of
+ *                    Eq. decluster: k counts the members of cluster i in element order)
+ * labels, params and fit_out are those of oracle_quantize_cluster in either case. */
+void oracle_quantize_cluster_ex(const float *x, int64_t n, int64_t G, int m, const float *fit_in,
+                                const float *qmap, int cluster_major, uint8_t *codes,
+                                uint8_t *labels, float *params, float *fit_out)
+{
+    if (n <= 0)
+        return;
+    if (G <= 0 || G > n)
+        G = n;
+    /* steps 1-4 and the linear codes */
+    oracle_quantize_cluster(x, n, G, m, fit_in, codes, labels, params, fit_out);
+    int64_t groups = (n + G - 1) / G;
+    if (qmap) {
+        for (int64_t i = 0; i < n; ++i) {
+            int64_t g = i / G;
+            int l = (labels[i >> 1] >> ((i & 1) * 4)) & 15;
+            const float *pg = params + g * (int64_t)m * 2;
+            codes[i] = code_of_qmap(x[i], pg[2 * l + 1], pg[2 * l + 0], qmap);
+        }
+    }
+    if (cluster_major) {
+        uint8_t *tmp = (uint8_t *)malloc((size_t)G);
+        for (int64_t g = 0; g < groups; ++g) {
+            int64_t lo = g * G;
+            int64_t len = (lo + G <= n) ? G : (n - lo);
+            int64_t k = 0;
+            for (int c = 0; c < m; ++c)
+                for (int64_t i = 0; i < len; ++i) {
+                    int64_t idx = lo + i;
+                    int l = (labels[idx >> 1] >> ((idx & 1) * 4)) & 15;
+                    if (l == c)
+                        tmp[k++] = codes[idx];
+                }
+            memcpy(codes + lo, tmp, (size_t)len);
+        }
+        free(tmp);
+    }
+}
+
+/* The inverse: T^D = Q^map(T^Q) * S + b, evaluated as fl32(fl32(Q_q * S) + b) with a table
+ * (with qmap == NULL: the linear map as in oracle_dequantize_cluster), and Eq. decluster:
+ * V_j = T_{C_i k} with i = L_j and k = the number of earlier elements of the group that carry
+ * label i. */
+void oracle_dequantize_cluster_ex(const uint8_t *codes, const uint8_t *labels, const float *params,
+                                  int64_t n, int64_t G, int m, const float *qmap, int cluster_major,
+                                  float *out)
+{
+    if (n <= 0)
+        return;
+    if (G <= 0 || G > n)
+        G = n;
+    int64_t groups = (n + G - 1) / G;
+    for (int64_t g = 0; g < groups; ++g) {
+        int64_t lo = g * G;
+        int64_t len = (lo + G <= n) ? G : (n - lo);
+        const float *pg = params + g * (int64_t)m * 2;
+        int64_t start[16], seen[16];
+        for (int c = 0; c < 16; ++c)
+            start[c] = seen[c] = 0;
+        if (cluster_major) {
+            int64_t count[16] = {0};
+            for (int64_t i = 0; i < len; ++i) {
+                int64_t idx = lo + i;
+                count[(labels[idx >> 1] >> ((idx & 1) * 4)) & 15] += 1;
+            }
+            for (int c = 1; c < 16; ++c)
+                start[c] = start[c - 1] + count[c - 1];
+        }
+        for (int64_t i = 0; i < len; ++i) {
+            int64_t idx = lo + i;
+            int l = (labels[idx >> 1] >> ((idx & 1) * 4)) & 15;
+            uint8_t q = cluster_major ? codes[lo + start[l] + seen[l]] : codes[idx];
+            seen[l] += 1;
+            float S = pg[2 * l + 0];
+            float b = pg[2 * l + 1];
+            float t;
+            if (qmap) {
+                t = qmap[q] * S;
+            } else {
+                float step = S / 255.0f;
+                t = (float)q * step;
+            }
+            out[idx] = t + b;
+        }
+    }
+}
+
+/* Eq. qmap-distance with a table, for one element, in long double (64-bit significand: far
+ * finer than the fp32 decision above): the minimiser of |Q_j - (x-b)/S|, lowest j on ties, and
+ * the gap to the runner-up, so that a test can set near-ties aside. */
+int oracle_code_qmap_bruteforce(float x, float b, float S, const float *qmap, double *gap)
+{
+    if (!(S > 0.0f)) {
+        if (gap)
+            *gap = 1.0;
+        return 0;
+    }
+    long double t = ((long double)x - (long double)b) / (long double)S;
+    int best = 0;
+    long double bd = 1e300L, second = 1e300L;
+    for (int j = 0; j < 256; ++j) {
+        long double d = fabsl((long double)qmap[j] - t);
+        if (d < bd) {
+            second = bd;
+            bd = d;
+            best = j;
+        } else if (d < second) {
+            second = d;
+        }
+    }
+    if (gap)
+        *gap = (double)(second - bd);
+    return best;
 }
 
 /* Brute-force form of Eq. qmap-distance for one element: the j in [0,255] minimising

@@ -239,3 +239,40 @@ def make_tensor_torch(cfg: Config, t: int, device, n_limit: Optional[int] = None
 def iter_tensors(cfg: Config) -> Iterator[Tuple[int, str, int]]:
     for t, (name, shape) in enumerate(cfg.tensors):
         yield t, name, math.prod(shape)
+
+
+def qmap_table(kind: str = "linear") -> np.ndarray:
+    """A 256-entry map Q (fp32, non-decreasing, Q[0] = 0, Q[255] = 1) to pass to the quantiser's table variant:
+    an input like any tensor, none of the codec's arithmetic.
+
+    * ``linear``   j/255: the levels the plain entry points use.
+    * ``square``   (j/255)^2: levels dense near the cluster minimum.
+    * ``normal``   levels at equal steps of probability of a normal distribution cut off at +-2.5 sigma, rescaled
+      to [0, 1]: dense in the middle of the range.
+    * ``steps``    a coarse staircase with repeated entries (64 distinct levels, each four times).
+    """
+    j = np.arange(256, dtype=np.float64)
+    if kind == "linear":
+        q = j / 255.0
+    elif kind == "square":
+        q = (j / 255.0) ** 2
+    elif kind == "normal":
+        cdf = lambda z: 0.5 * (1.0 + math.erf(z / math.sqrt(2.0)))
+        lo, hi = cdf(-2.5), cdf(2.5)
+        q = np.empty(256)
+        for i in range(256):
+            p = lo + (hi - lo) * i / 255.0
+            a, b = -2.5, 2.5
+            for _ in range(80):
+                mid = 0.5 * (a + b)
+                if cdf(mid) < p:
+                    a = mid
+                else:
+                    b = mid
+            q[i] = (0.5 * (a + b) + 2.5) / 5.0
+        q[0], q[255] = 0.0, 1.0
+    elif kind == "steps":
+        q = np.floor(j / 4.0) / 63.0
+    else:
+        raise ValueError(kind)
+    return q.astype(np.float32)

@@ -12,6 +12,7 @@ import oracle
 import conftest
 import test_oracle_cluster as tc
 import test_oracle_sparse as ts
+import test_oracle_variants as tv
 
 SRC = os.path.join(os.path.dirname(oracle.__file__), "bitsnap_oracle.c")
 
@@ -41,6 +42,21 @@ MUTANTS = [
     ("label_nibbles_swapped", "(l << ((idx & 1) * 4))", "(l << ((1 - (idx & 1)) * 4))", 0),
     ("dequant_drops_offset", "out[i] = t + b;", "out[i] = t;", 0),
     ("dequant_wrong_group", "int64_t g = i / G;", "int64_t g = 0;", 0),
+    # format variants: a general map Q, cluster-major codes
+    ("table_tie_takes_highest", "if (dist < bd) {", "if (dist <= bd) {", 0),
+    ("table_code_without_offset", "float d = x - b;", "float d = x;", 1),
+    ("table_scaled_to_255", "float inv = 1.0f / S;", "float inv = 255.0f / S;", 0),
+    ("table_distance_signed", "float dist = fabsf(qmap[j] - t);", "float dist = qmap[j] - t;", 0),
+    ("table_dequant_drops_scale", "t = qmap[q] * S;", "t = qmap[q];", 0),
+    ("table_dequant_linear_levels", "t = qmap[q] * S;", "t = (float)q / 255.0f * S;", 0),
+    ("major_clusters_descending", "for (int c = 0; c < m; ++c)\n                for (int64_t i = 0; i < len; ++i) {",
+     "for (int c = m - 1; c >= 0; --c)\n                for (int64_t i = 0; i < len; ++i) {", 0),
+    ("major_members_reversed", "for (int c = 0; c < m; ++c)\n                for (int64_t i = 0; i < len; ++i) {",
+     "for (int c = 0; c < m; ++c)\n                for (int64_t i = len - 1; i >= 0; --i) {", 0),
+    ("major_over_the_whole_tensor", "uint8_t q = cluster_major ? codes[lo + start[l] + seen[l]] : codes[idx];",
+     "uint8_t q = cluster_major ? codes[start[l] + seen[l]] : codes[idx];", 0),
+    ("decluster_start_off_by_one_cluster", "start[c] = start[c - 1] + count[c - 1];", "start[c] = start[c - 1] + count[c];", 0),
+    ("decluster_rank_not_advanced", "            seen[l] += 1;\n", "", 0),
 ]
 
 
@@ -67,6 +83,14 @@ def _pins(golden):
     yield tc.test_dequantize_formula
     yield lambda: tc.test_stored_size_formula(golden)
     yield tc.test_degenerate_groups
+    yield lambda: tv.test_cluster_major_is_a_stable_sort_by_label_inside_each_group(1000, 4321)
+    yield tv.test_cluster_major_on_a_hand_made_group
+    yield lambda: tv.test_decluster_returns_every_value_to_its_position(512, 5000, 7)
+    yield lambda: tv.test_table_codes_are_the_nearest_entries("normal")
+    yield lambda: tv.test_table_codes_against_exhaustive_search("square")
+    yield tv.test_exact_ties_and_repeated_entries_take_the_lowest_index
+    yield lambda: tv.test_table_dequantisation_error_is_within_half_a_gap("square")
+    yield tv.test_table_dequantise_on_hand_made_inputs
 
 
 @pytest.mark.parametrize("name,find,repl,occ", MUTANTS, ids=[m[0] for m in MUTANTS])
@@ -85,7 +109,8 @@ def test_planted_mistake_is_caught(tmp_path, name, find, repl, occ):
     mut = ctypes.CDLL(str(lib))
     for sym in ("oracle_encode_sparse", "oracle_encode_sparse_ex", "oracle_decode_sparse_ex", "oracle_encode_sparse32_ex", "oracle_decode_sparse32_ex", "oracle_encode_sparse_naive", "oracle_tile_offsets", "oracle_decode_sparse",
                 "oracle_norm_quantile", "oracle_cluster_fit", "oracle_cluster_edges", "oracle_quantize_cluster",
-                "oracle_dequantize_cluster", "oracle_code_bruteforce"):
+                "oracle_dequantize_cluster", "oracle_code_bruteforce", "oracle_quantize_cluster_ex",
+                "oracle_dequantize_cluster_ex", "oracle_code_qmap_bruteforce"):
         getattr(mut, sym).argtypes = getattr(good, sym).argtypes
         getattr(mut, sym).restype = getattr(good, sym).restype
     oracle._lib = mut
