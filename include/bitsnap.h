@@ -213,6 +213,34 @@ int bitsnap_dequantize_cluster(const uint8_t *codes, const uint8_t *labels, cons
                                bitsnap_stream_t stream);
 
 /* ------------------------------------------------------------------------------------------
+ * Format variants of the cluster pair (group must be one of 256, 512, 1024, 2048, 4096).
+ *
+ * qmap   nullable, DEVICE [256] fp32, 4-byte aligned: the map Q^map of Eq. qmap-distance as a
+ *        table.  It must be non-decreasing (its contents cannot be checked on the host; with any
+ *        other table the codes are unspecified, still 0..255).  code = the index of the entry
+ *        nearest to t = (x-b)/S, the lowest such index where several are equally near, decided
+ *        in fp32: t = fl32(fl32(x-b) * fl32(1/S)), distance fl32(|Q_j - t|); a cluster whose
+ *        range cannot be coded (S = 0, or 1/S not finite) gets code 0.  Dequantisation is
+ *        "T^D = Q^map(T^Q)*S + b": out = fl32(fl32(Q[code] * S) + b).  NULL = the linear map of
+ *        the plain entry points (levels j/255, S/255 folded into one factor).
+ * flags  BITSNAP_CLUSTER_MAJOR: the codes of a group are stored cluster by cluster - all of
+ *        cluster 0, then cluster 1, ... - and inside a cluster in element order: the T_{C_i k}
+ *        of Eq. decluster, which dequantisation undoes through the labels (V_j = T_{C_i k} with
+ *        i = L_j, k = the number of earlier elements of the group with label i).  Labels stay in
+ *        element order; params, fit and status are those of bitsnap_quantize_cluster.
+ * With qmap == NULL and flags == 0 these are the plain entry points.
+ * ---------------------------------------------------------------------------------------- */
+#define BITSNAP_CLUSTER_MAJOR 1u
+
+int bitsnap_quantize_cluster_ex(const float *x, int64_t n, int64_t group, int m, uint32_t flags,
+                                const float *qmap, uint8_t *codes, uint8_t *labels, float *params,
+                                float *fit_out, const float *fit_in, uint32_t *status,
+                                bitsnap_stream_t stream);
+int bitsnap_dequantize_cluster_ex(const uint8_t *codes, const uint8_t *labels, const float *params,
+                                  int64_t n, int64_t group, int m, uint32_t flags, const float *qmap,
+                                  float *out, bitsnap_stream_t stream);
+
+/* ------------------------------------------------------------------------------------------
  * Batched forms: one launch for a whole list of tensors.  The paper compresses an entire
  * state_dict per checkpoint ("process the state_dict", section "Details of Modifications"); a
  * launch per tensor leaves the device ramping up and draining a few thousand groups at a time.

@@ -24,6 +24,7 @@ SYMBOLS = (
     "bitsnap_cluster_groups", "bitsnap_cluster_param_bytes", "bitsnap_cluster_label_bytes",
     "bitsnap_cluster_fit_floats", "bitsnap_cluster_workspace_bytes", "bitsnap_cluster_z",
     "bitsnap_quantize_cluster", "bitsnap_dequantize_cluster",
+    "bitsnap_quantize_cluster_ex", "bitsnap_dequantize_cluster_ex",
     "bitsnap_quantize_cluster_batched", "bitsnap_dequantize_cluster_batched",
     "bitsnap_sparse_batch_workspace_bytes", "bitsnap_encode_sparse_batched", "bitsnap_decode_sparse_batched",
 )
@@ -76,6 +77,10 @@ def lib():
     L.bitsnap_cluster_fit_floats.argtypes, L.bitsnap_cluster_fit_floats.restype = [i64, i64, i], sz
     L.bitsnap_cluster_workspace_bytes.argtypes, L.bitsnap_cluster_workspace_bytes.restype = [i64, i64, i], sz
     L.bitsnap_cluster_z.argtypes, L.bitsnap_cluster_z.restype = [i, i], C.c_double
+    L.bitsnap_quantize_cluster_ex.argtypes = [p, i64, i64, i, C.c_uint32, p, p, p, p, p, p, p, p]
+    L.bitsnap_quantize_cluster_ex.restype = i
+    L.bitsnap_dequantize_cluster_ex.argtypes = [p, p, p, i64, i64, i, C.c_uint32, p, p, p]
+    L.bitsnap_dequantize_cluster_ex.restype = i
     L.bitsnap_quantize_cluster.argtypes = [p, i64, i64, i, p, p, p, p, p, p, p, sz, p]
     L.bitsnap_quantize_cluster.restype = i
     L.bitsnap_dequantize_cluster.argtypes = [p, p, p, i64, i64, i, p, p]
@@ -182,6 +187,7 @@ def new_sparse_workspace(n: int, device, elem_bytes: int = 2):
 # the four codecs.  Raw forms take every buffer; the caller allocates.
 # ----------------------------------------------------------------------------------------------
 SPARSE_DELTA = 1  # BITSNAP_SPARSE_DELTA
+CLUSTER_MAJOR = 1  # BITSNAP_CLUSTER_MAJOR
 
 
 def encode_sparse_raw(cur, base, n: int, mask, payload, payload_capacity: int, tile_offsets, n_changed,
@@ -225,6 +231,20 @@ def dequantize_cluster_raw(codes, labels, params, n: int, group: int, m: int, ou
     rc = lib().bitsnap_dequantize_cluster(_ptr(codes), _ptr(labels), _ptr(params), n, group, m, _ptr(out),
                                           _stream(stream))
     _check(rc, "bitsnap_dequantize_cluster")
+
+
+def quantize_cluster_ex_raw(x, n: int, group: int, m: int, flags: int, qmap, codes, labels, params, fit_out=None,
+                            fit_in=None, status=None, stream=None) -> None:
+    rc = lib().bitsnap_quantize_cluster_ex(_ptr(x), n, group, m, flags, _ptr(qmap), _ptr(codes), _ptr(labels),
+                                           _ptr(params), _ptr(fit_out), _ptr(fit_in), _ptr(status), _stream(stream))
+    _check(rc, "bitsnap_quantize_cluster_ex")
+
+
+def dequantize_cluster_ex_raw(codes, labels, params, n: int, group: int, m: int, flags: int, qmap, out,
+                              stream=None) -> None:
+    rc = lib().bitsnap_dequantize_cluster_ex(_ptr(codes), _ptr(labels), _ptr(params), n, group, m, flags, _ptr(qmap),
+                                             _ptr(out), _stream(stream))
+    _check(rc, "bitsnap_dequantize_cluster_ex")
 
 
 # ----------------------------------------------------------------------------------------------
@@ -298,6 +318,35 @@ def quantize_cluster(x, group: int = 4096, m: int = 16, *, fit_in=None, want_fit
     ws = torch.zeros(wsb, dtype=torch.uint8, device=dev) if wsb else None
     quantize_cluster_raw(xf, n, group, m, codes, labels, params, fit, fit_in, status, ws, stream)
     return SimpleNamespace(codes=codes, labels=labels, params=params, fit=fit, status=status, n=n, group=group, m=m)
+
+
+def quantize_cluster_ex(x, group: int = 4096, m: int = 16, *, qmap=None, cluster_major: bool = False, fit_in=None,
+                        want_fit: bool = True, stream=None):
+    """quantize_cluster with the format options: qmap = device fp32[256] table (None: linear map), cluster_major =
+    codes stored cluster by cluster inside each group.  Same namespace as quantize_cluster."""
+    import torch
+    assert x.is_cuda and x.is_contiguous() and x.dtype == torch.float32
+    xf = x.reshape(-1)
+    n = xf.numel()
+    dev = x.device
+    g = cluster_groups(n, group)
+    codes = torch.empty(max(n, 1), dtype=torch.uint8, device=dev)[:n]
+    labels = torch.empty(max(cluster_label_bytes(n), 1), dtype=torch.uint8, device=dev)[:cluster_label_bytes(n)]
+    params = torch.empty((max(g, 1), m, 2), dtype=torch.float32, device=dev)[:g]
+    fit = torch.empty((max(g, 1), m + 1), dtype=torch.float32, device=dev)[:g] if want_fit else None
+    status = torch.zeros(1, dtype=torch.int32, device=dev)
+    quantize_cluster_ex_raw(xf, n, group, m, CLUSTER_MAJOR if cluster_major else 0, qmap, codes, labels, params, fit,
+                            fit_in, status, stream)
+    return SimpleNamespace(codes=codes, labels=labels, params=params, fit=fit, status=status, n=n, group=group, m=m)
+
+
+def dequantize_cluster_ex(codes, labels, params, n: int, group: int = 4096, m: int = 16, *, qmap=None,
+                          cluster_major: bool = False, out=None, stream=None):
+    import torch
+    if out is None:
+        out = torch.empty(max(n, 1), dtype=torch.float32, device=codes.device)[:n]
+    dequantize_cluster_ex_raw(codes, labels, params, n, group, m, CLUSTER_MAJOR if cluster_major else 0, qmap, out, stream)
+    return out
 
 
 def dequantize_cluster(codes, labels, params, n: int, group: int = 4096, m: int = 16, *, out=None, stream=None):

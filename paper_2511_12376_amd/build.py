@@ -8,7 +8,8 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libbitsnap.so")
-SOURCES = ["bitsnap_api.hip", "bitsnap_sparse.hip", "bitsnap_cluster.hip", "bitsnap_cluster_general.hip"]
+SOURCES = ["bitsnap_api.hip", "bitsnap_sparse.hip", "bitsnap_cluster.hip", "bitsnap_cluster_general.hip",
+           "bitsnap_cluster_variants.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 FLAGS = [

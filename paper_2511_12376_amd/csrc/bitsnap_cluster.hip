@@ -201,21 +201,6 @@ __global__ __launch_bounds__(kQBlock) void dequantize_cluster_batched_kernel(
                             coder[wave], lane);
 }
 
-// K (float4 per lane) of the one-wave-per-group kernels, or 0 when the group length needs the
-// multi-pass path
-static int group_k(int64_t n, int64_t group)
-{
-    (void)n;
-    switch (group) {
-    case 256: return 1;
-    case 512: return 2;
-    case 1024: return 4;
-    case 2048: return 8;
-    case 4096: return 16;
-    default: return 0;
-    }
-}
-
 }  // namespace bitsnap
 
 using namespace bitsnap;
@@ -244,7 +229,7 @@ extern "C" size_t bitsnap_cluster_fit_floats(int64_t n, int64_t group, int m)
 extern "C" size_t bitsnap_cluster_workspace_bytes(int64_t n, int64_t group, int m)
 {
     (void)m;
-    if (n <= 0 || group_k(n, group) != 0)
+    if (n <= 0 || one_wave_group_k(group) != 0)
         return 0;
     return cluster_general_workspace_bytes(n, group);
 }
@@ -265,7 +250,7 @@ extern "C" int bitsnap_quantize_cluster(const float *x, int64_t n, int64_t group
         return BITSNAP_E_SIZE;
     if (n == 0)
         return BITSNAP_OK;
-    const int K = group_k(n, group);
+    const int K = one_wave_group_k(group);
     if (K == 0 && !cluster_general_supported(n, group))
         return BITSNAP_E_SIZE;
     if (!x || !codes || !labels || !params)
@@ -318,7 +303,7 @@ extern "C" int bitsnap_dequantize_cluster(const uint8_t *codes, const uint8_t *l
         return BITSNAP_E_SIZE;
     if (n == 0)
         return BITSNAP_OK;
-    const int K = group_k(n, group);
+    const int K = one_wave_group_k(group);
     if (K == 0 && !cluster_general_supported(n, group))
         return BITSNAP_E_SIZE;
     if (!codes || !labels || !params || !out)
@@ -353,7 +338,7 @@ extern "C" int bitsnap_quantize_cluster_batched(const bitsnap_cluster_item *item
 {
     if (count < 0 || total_groups < 0 || m < 1 || m > kMaxClusters)
         return BITSNAP_E_SIZE;
-    const int K = group_k(0, group);
+    const int K = one_wave_group_k(group);
     if (K == 0)
         return BITSNAP_E_SIZE;  // the batched form exists for the one-wave-per-group lengths only
     if (count == 0 || total_groups == 0)
@@ -389,7 +374,7 @@ extern "C" int bitsnap_dequantize_cluster_batched(const bitsnap_cluster_item *it
 {
     if (count < 0 || total_groups < 0 || m < 1 || m > kMaxClusters)
         return BITSNAP_E_SIZE;
-    const int K = group_k(0, group);
+    const int K = one_wave_group_k(group);
     if (K == 0)
         return BITSNAP_E_SIZE;
     if (count == 0 || total_groups == 0)

@@ -1,0 +1,553 @@
+// Format variants of the cluster quantiser (paper: "Cluster Based Quantization for Optimizer
+// States"):
+//   * a general map Q^map in Eq. qmap-distance: code = the entry of a 256-entry table nearest to
+//     (x-b)/S, and T^D = Q(T^Q)*S + b on the way back;
+//   * the cluster-major arrangement of Eq. decluster: inside a group the codes of cluster 0 come
+//     first, then cluster 1, ..., each cluster's codes in element order.
+//
+// One wavefront per group, as in the plain kernels, and steps 1-4 of Algorithm 2 are the same
+// code.  The table lives in LDS once per workgroup and is searched by bisection.  The
+// cluster-major arrangement is a stable 16-way partition of the group's codes done inside the
+// wave through LDS: the codes and the labels are laid down in element order; then lane l takes
+// the 4K consecutive elements l*4K .. l*4K+4K-1, counts its labels into a private column of a
+// [16][64] counter table, an exclusive prefix sum over that table read row by row (cluster, then
+// lane) turns every counter into the position of the lane's first member of the cluster, and a
+// second walk over the same elements hands out consecutive positions.
+#include <hip/hip_runtime.h>
+#include <math.h>
+#include <stdint.h>
+
+#include "../../include/bitsnap.h"
+#include "cluster_general.hpp"
+#include "cluster_wave.hpp"
+#include "host_util.hpp"
+#include "wave.hpp"
+
+namespace bitsnap {
+
+constexpr int kVBlock = 256;
+constexpr int kVWaves = kVBlock / kWave;
+constexpr int kLevels = 256;
+
+// LDS of one wave for the partition.
+struct MajorView {
+    uint32_t *counters;  // [16][64]: cluster c, lane l at c*64 + l
+    uint32_t *bytes;     // [256*K] bytes: the group's codes (element order on one side, cluster-major on the other)
+    uint32_t *labels;    // [256*K] nibbles: the group's labels in element order
+};
+
+struct alignas(16) QuantizeShared {
+    WaveShared ws;
+    uint32_t labels[kMaxClusters * 256 / 8];
+};
+
+struct alignas(16) DequantizeShared {
+    uint32_t counters[kMaxClusters][kWave];
+    uint32_t bytes[kMaxClusters * 256 / 4];
+    uint32_t labels[kMaxClusters * 256 / 8];
+    float2 coder[kMaxClusters];
+};
+
+__device__ __forceinline__ uint32_t lds_fetch_add(uint32_t *p, uint32_t v)
+{
+    return __hip_atomic_fetch_add(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+}
+
+// The lane's own labels: halfword i holds those of elements lane*4K + 4i .. + 3.
+template <int K>
+__device__ __forceinline__ void own_labels(const MajorView &mv, int lane, uint32_t (&lh)[K])
+{
+    const uint16_t *l16 = (const uint16_t *)mv.labels;
+#pragma unroll
+    for (int i = 0; i < K; ++i)
+        lh[i] = l16[lane * K + i];
+}
+
+// Counts the lane's labels and turns the counter table into first positions: afterwards
+// counters[c][lane] = members of clusters < c in the group + members of c in lower lanes.
+template <int K, bool kFull>
+__device__ __forceinline__ void major_positions(const MajorView &mv, const uint32_t (&lh)[K], int len, int lane)
+{
+#pragma unroll
+    for (int c = 0; c < kMaxClusters; ++c)
+        mv.counters[c * kWave + lane] = 0;
+#pragma unroll
+    for (int i = 0; i < K; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            if (kFull || lane * 4 * K + 4 * i + j < len)
+                lds_fetch_add(&mv.counters[((lh[i] >> (4 * j)) & 15u) * kWave + lane], 1u);
+    wave_lds_sync();
+    // exclusive prefix over the 1024 counters in row order: 16 consecutive ones per lane
+    uint32_t c[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i)
+        c[i] = mv.counters[lane * 16 + i];
+    uint32_t total = 0;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const uint32_t t = c[i];
+        c[i] = total;
+        total += t;
+    }
+    const uint32_t before = wave_inclusive_add(total) - total;
+    wave_lds_sync();  // every lane has read its 16 counters (other lanes' columns) before any is rewritten
+#pragma unroll
+    for (int i = 0; i < 16; ++i)
+        mv.counters[lane * 16 + i] = c[i] + before;
+    wave_lds_sync();
+}
+
+// Element order -> cluster-major.  In: mv.bytes and mv.labels hold the group in element order.
+// Out: mv.bytes holds the cluster-major arrangement.
+template <int K, bool kFull>
+__device__ __forceinline__ void to_cluster_major(const MajorView &mv, int len, int lane)
+{
+    uint32_t lh[K], cw[K];
+    own_labels<K>(mv, lane, lh);
+#pragma unroll
+    for (int i = 0; i < K; ++i)
+        cw[i] = mv.bytes[lane * K + i];
+    major_positions<K, kFull>(mv, lh, len, lane);  // its barriers also order the reads above before the writes below
+    uint8_t *b8 = (uint8_t *)mv.bytes;
+#pragma unroll
+    for (int i = 0; i < K; ++i) {
+        uint32_t pos[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            pos[j] = 0;
+            if (kFull || lane * 4 * K + 4 * i + j < len)
+                pos[j] = lds_fetch_add(&mv.counters[((lh[i] >> (4 * j)) & 15u) * kWave + lane], 1u);
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            if (kFull || lane * 4 * K + 4 * i + j < len)
+                b8[pos[j]] = (uint8_t)(cw[i] >> (8 * j));
+    }
+    wave_lds_sync();
+}
+
+// Cluster-major -> element order.  In: mv.bytes cluster-major, mv.labels element order.
+// Out: mv.bytes in element order.
+template <int K, bool kFull>
+__device__ __forceinline__ void from_cluster_major(const MajorView &mv, int len, int lane)
+{
+    uint32_t lh[K], cw[K];
+    own_labels<K>(mv, lane, lh);
+    major_positions<K, kFull>(mv, lh, len, lane);
+    const uint8_t *b8 = (const uint8_t *)mv.bytes;
+#pragma unroll
+    for (int i = 0; i < K; ++i) {
+        uint32_t pos[4];
+        cw[i] = 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            pos[j] = 0;
+            if (kFull || lane * 4 * K + 4 * i + j < len)
+                pos[j] = lds_fetch_add(&mv.counters[((lh[i] >> (4 * j)) & 15u) * kWave + lane], 1u);
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            if (kFull || lane * 4 * K + 4 * i + j < len)
+                cw[i] |= (uint32_t)b8[pos[j]] << (8 * j);
+    }
+    wave_lds_sync();  // every lane has fetched its codes before the element-order copy overwrites them
+#pragma unroll
+    for (int i = 0; i < K; ++i)
+        mv.bytes[lane * K + i] = cw[i];
+    wave_lds_sync();
+}
+
+// Eq. qmap-distance with a table, decided in fp32: the index of the entry nearest to t, the
+// lowest index where several are equally near (in rounded distance).  The table is
+// non-decreasing, so the nearest entry is one of the two that bracket t: p = the last entry
+// <= t (8 bisection steps over entries 1..255) and its successor.  Entries below p can only tie
+// with it, never beat it; the walk down at the end finds the first of such a run.
+constexpr int kTableBatch = 8;
+__device__ __forceinline__ void table_codes(const float *table, const float (&t)[kTableBatch], uint32_t (&code)[kTableBatch])
+{
+    uint32_t p[kTableBatch];
+#pragma unroll
+    for (int i = 0; i < kTableBatch; ++i)
+        p[i] = 0;
+#pragma unroll
+    for (int s = kLevels / 2; s >= 1; s >>= 1) {
+        float q[kTableBatch];
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < kTableBatch; ++i)
+            q[i] = table[p[i] + s];
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < kTableBatch; ++i)
+            p[i] += q[i] <= t[i] ? (uint32_t)s : 0u;
+    }
+    float ql[kTableBatch], qh[kTableBatch], qb[kTableBatch];
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int i = 0; i < kTableBatch; ++i) {
+        ql[i] = table[p[i]];
+        qh[i] = table[p[i] < kLevels - 1 ? p[i] + 1 : kLevels - 1];
+        qb[i] = table[p[i] > 0 ? p[i] - 1 : 0];
+    }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int i = 0; i < kTableBatch; ++i) {
+        const float dl = fabsf(__fsub_rn(ql[i], t[i])), dh = fabsf(__fsub_rn(qh[i], t[i]));
+        uint32_t w = p[i];
+        if (dh < dl) {
+            w = p[i] < kLevels - 1 ? p[i] + 1 : kLevels - 1;
+        } else if (w > 0 && fabsf(__fsub_rn(qb[i], t[i])) <= dl) {
+            --w;  // a run of equally near entries (repeated entries, or a distance that rounds the same)
+            while (w > 0 && fabsf(__fsub_rn(table[w - 1], t[i])) <= dl)
+                --w;
+        }
+        code[i] = w;
+    }
+}
+
+// Codes of the wave's elements into registers: c4[k] = the four codes of float4 k.
+// ws.coder holds (b, 255/S) for the linear map and (b, 1/S) for a table.
+template <int K, bool kTable>
+__device__ __forceinline__ void codes_to_registers(const float4 (&v)[K], const uint32_t (&packed)[(K + 1) / 2], WaveShared &ws,
+                                                   const float *table, uint32_t (&c4)[K])
+{
+    constexpr int kF = kTableBatch / 4 < K ? kTableBatch / 4 : K;  // float4 per batch
+#pragma unroll
+    for (int kb = 0; kb < K; kb += kF) {
+        float t[kTableBatch];
+        uint32_t code[kTableBatch];
+#pragma unroll
+        for (int i = 0; i < kTableBatch; ++i) {
+            t[i] = 0.0f;
+            if (i < 4 * kF) {
+                const int k = kb + i / 4;
+                const uint32_t l4 = (packed[k >> 1] >> (16 * (k & 1))) & 0xFFFFu;
+                const float2 bi = ws.coder[(l4 >> (4 * (i % 4))) & 15u];
+                t[i] = __fmul_rn(__fsub_rn(comp(v[k], i % 4), bi.x), bi.y);
+                if (kTable && bi.y == 0.0f)
+                    t[i] = __uint_as_float(0x7FC00000u);  // a range that cannot be coded: NaN finds entry 0
+            }
+        }
+        if (kTable) {
+            table_codes(table, t, code);
+#pragma unroll
+            for (int f = 0; f < kF; ++f)
+                c4[kb + f] = code[4 * f] | (code[4 * f + 1] << 8) | (code[4 * f + 2] << 16) | (code[4 * f + 3] << 24);
+        } else {
+#pragma unroll
+            for (int f = 0; f < kF; ++f) {
+                uint32_t c = 0;
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    c = __builtin_amdgcn_cvt_pk_u8_f32(t[4 * f + j], j, c);
+                c4[kb + f] = c;
+            }
+        }
+    }
+}
+
+template <int K, bool kFull>
+__device__ __forceinline__ void store_codes(const uint32_t (&c4)[K], int64_t lo, int len, int lane, uint8_t *__restrict__ codes)
+{
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        const int off = k * 256 + lane * 4;
+        BITSNAP_GLOBAL uint8_t *cp = global_ptr(codes) + lo + off;
+        if (kFull || off + 3 < len) {
+            __builtin_nontemporal_store(c4[k], (BITSNAP_GLOBAL uint32_t *)cp);
+        } else {
+            for (int j = 0; j < 4; ++j)
+                if (off + j < len)
+                    cp[j] = (uint8_t)(c4[k] >> (8 * j));
+        }
+    }
+}
+
+template <int K, bool kFull, bool kTable, bool kMajor>
+__global__ __launch_bounds__(kVBlock) void quantize_cluster_ex_kernel(
+    const float *__restrict__ x, int64_t n, int64_t first_group, int64_t groups, int m, const float *__restrict__ qmap,
+    uint8_t *__restrict__ codes, uint8_t *__restrict__ labels, float *__restrict__ params, float *__restrict__ fit_out,
+    const float *__restrict__ fit_in, uint32_t *__restrict__ status)
+{
+    __shared__ QuantizeShared shared[kVWaves];
+    __shared__ float table[kLevels];
+    if (kTable) {
+        table[threadIdx.x] = global_ptr(qmap)[threadIdx.x];  // kVBlock == kLevels
+        __syncthreads();
+    }
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
+    const int64_t g = first_group + (int64_t)blockIdx.x * kVWaves + wave;
+    if (g >= first_group + groups)
+        return;  // after the only workgroup barrier
+    constexpr int G = 256 * K;
+    const int64_t lo = g * G;
+    const int64_t rest = n - lo;
+    const int len = kFull ? G : (int)(rest < G ? rest : G);
+    WaveShared &ws = shared[wave].ws;
+
+    // ---- steps 1-4 of Algorithm 2, as in the plain kernel
+    float4 v[K];
+    load_elements<K, kFull>(x, lo, len, lane, v);
+    reset_ranges(ws, lane);
+    double sum, dev;
+    wave_stats<K, kFull>(v, len, lane, sum, dev);
+    float mu = (float)(sum / (double)len);
+    float sigma = (float)sqrt(dev / (double)len);
+    if (fit_in) {
+        mu = global_ptr(fit_in)[2 * g];
+        sigma = global_ptr(fit_in)[2 * g + 1];
+    }
+    if (status && lane == 0 && !(isfinite(mu) && isfinite(sigma)))
+        atomicOr(status, 1u);
+    float edge;
+    const LabelSearch ls = build_search(mu, sigma, m, ws, lane, edge);
+    if (fit_out) {
+        if (lane >= 1 && lane < m)
+            global_ptr(fit_out)[g * (m + 1) + 1 + lane] = edge;
+        if (lane == 0) {
+            global_ptr(fit_out)[g * (m + 1) + 0] = mu;
+            global_ptr(fit_out)[g * (m + 1) + 1] = sigma;
+        }
+    }
+    uint32_t packed[(K + 1) / 2];
+    label_pass<K, kFull, true, true>(v, lo, len, ls, ws, lane, labels, packed);
+    float mn, mx;
+    reduce_ranges(ws, lane, mn, mx);
+    if (lane < kMaxClusters) {
+        float S, b, inv;
+        cluster_coder(mn, mx, S, b, inv);
+        if (kTable) {
+            inv = S > 0.0f ? __fdiv_rn(1.0f, S) : 0.0f;
+            if (!isfinite(inv))
+                inv = 0.0f;
+        }
+        ws.coder[lane] = make_float2(b, inv);
+        if (lane < m)
+            *(BITSNAP_GLOBAL float2v *)(global_ptr(params) + (g * m + lane) * 2) = float2v{S, b};
+    }
+    wave_lds_sync();
+
+    // ---- steps 5-6
+    uint32_t c4[K];
+    codes_to_registers<K, kTable>(v, packed, ws, table, c4);
+    if (kMajor) {
+        // the min/max table is done with: its first half becomes the counters, its second half the codes
+        MajorView mv;
+        mv.counters = (uint32_t *)&ws.tab[0][0];
+        mv.bytes = (uint32_t *)&ws.tab[kMaxClusters][0];
+        mv.labels = shared[wave].labels;
+        uint16_t *l16 = (uint16_t *)mv.labels;
+#pragma unroll
+        for (int k = 0; k < K; ++k) {
+            mv.bytes[k * kWave + lane] = c4[k];
+            l16[k * kWave + lane] = (uint16_t)(packed[k >> 1] >> (16 * (k & 1)));
+        }
+        wave_lds_sync();
+        to_cluster_major<K, kFull>(mv, len, lane);
+#pragma unroll
+        for (int k = 0; k < K; ++k)
+            c4[k] = mv.bytes[k * kWave + lane];
+    }
+    store_codes<K, kFull>(c4, lo, len, lane, codes);
+}
+
+template <int K, bool kTable, bool kMajor>
+__global__ __launch_bounds__(kVBlock) void dequantize_cluster_ex_kernel(
+    const uint8_t *__restrict__ codes, const uint8_t *__restrict__ labels, const float *__restrict__ params, int64_t n,
+    int64_t groups, int m, const float *__restrict__ qmap, float *__restrict__ out)
+{
+    __shared__ DequantizeShared shared[kVWaves];
+    __shared__ float table[kLevels];
+    if (kTable) {
+        table[threadIdx.x] = global_ptr(qmap)[threadIdx.x];
+        __syncthreads();
+    }
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
+    const int64_t g = (int64_t)blockIdx.x * kVWaves + wave;
+    if (g >= groups)
+        return;
+    constexpr int G = 256 * K;
+    const int64_t lo = g * G;
+    const int64_t rest = n - lo;
+    const int len = rest >= G ? G : (int)rest;
+    DequantizeShared &sh = shared[wave];
+
+    uint32_t c4[K], l4[K];
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        const int off = k * 256 + lane * 4;
+        c4[k] = 0, l4[k] = 0;
+        if (off + 3 < len) {
+            c4[k] = __builtin_nontemporal_load((const BITSNAP_GLOBAL uint32_t *)(global_ptr(codes) + lo + off));
+            l4[k] = __builtin_nontemporal_load((const BITSNAP_GLOBAL uint16_t *)(global_ptr(labels) + ((lo + off) >> 1)));
+        } else {
+            for (int j = 0; j < 4; ++j)
+                if (off + j < len) {
+                    c4[k] |= (uint32_t)global_ptr(codes)[lo + off + j] << (8 * j);
+                    l4[k] |= (uint32_t)((global_ptr(labels)[(lo + off + j) >> 1] >> (4 * ((lo + off + j) & 1))) & 15u) << (4 * j);
+                }
+        }
+    }
+    if (lane < kMaxClusters) {
+        float2 sb = make_float2(0.0f, 0.0f);
+        if (lane < m) {
+            const float2v t = *(const BITSNAP_GLOBAL float2v *)(global_ptr(params) + (g * m + lane) * 2);
+            sb = make_float2(t.x, t.y);
+        }
+        sh.coder[lane] = kTable ? sb : make_float2(__fdiv_rn(sb.x, 255.0f), sb.y);  // (S or S/255, b)
+    }
+    if (kMajor) {
+        MajorView mv;
+        mv.counters = &sh.counters[0][0];
+        mv.bytes = sh.bytes;
+        mv.labels = sh.labels;
+        uint16_t *l16 = (uint16_t *)mv.labels;
+#pragma unroll
+        for (int k = 0; k < K; ++k) {
+            mv.bytes[k * kWave + lane] = c4[k];
+            l16[k * kWave + lane] = (uint16_t)l4[k];
+        }
+        wave_lds_sync();
+        if (len == G)
+            from_cluster_major<K, true>(mv, len, lane);
+        else
+            from_cluster_major<K, false>(mv, len, lane);
+#pragma unroll
+        for (int k = 0; k < K; ++k)
+            c4[k] = mv.bytes[k * kWave + lane];
+    } else {
+        wave_lds_sync();
+    }
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        const int off = k * 256 + lane * 4;
+        float r[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const float2 sb = sh.coder[(l4[k] >> (4 * j)) & 15u];
+            const uint32_t q = (c4[k] >> (8 * j)) & 255u;
+            const float level = kTable ? table[q] : (float)q;
+            r[j] = __fadd_rn(__fmul_rn(level, sb.x), sb.y);
+        }
+        if (off + 3 < len) {
+            __builtin_nontemporal_store(float4v{r[0], r[1], r[2], r[3]}, (BITSNAP_GLOBAL float4v *)(global_ptr(out) + lo + off));
+        } else {
+            for (int j = 0; j < 4; ++j)
+                if (off + j < len)
+                    global_ptr(out)[lo + off + j] = r[j];
+        }
+    }
+}
+
+template <int K, bool kTable, bool kMajor>
+static void launch_quantize_ex(const float *x, int64_t n, int m, const float *qmap, uint8_t *codes, uint8_t *labels,
+                               float *params, float *fit_out, const float *fit_in, uint32_t *status, hipStream_t s)
+{
+    const int64_t G = 256 * (int64_t)K;
+    const int64_t full = n / G;
+    const bool tail = (n % G) != 0;
+    const int64_t blocks = (full + kVWaves - 1) / kVWaves;
+    if (full > 0)
+        hipLaunchKernelGGL((quantize_cluster_ex_kernel<K, true, kTable, kMajor>), dim3((unsigned)blocks), dim3(kVBlock), 0, s,
+                           x, n, (int64_t)0, full, m, qmap, codes, labels, params, fit_out, fit_in, status);
+    if (tail)
+        hipLaunchKernelGGL((quantize_cluster_ex_kernel<K, false, kTable, kMajor>), dim3(1), dim3(kVBlock), 0, s, x, n, full,
+                           (int64_t)1, m, qmap, codes, labels, params, fit_out, fit_in, status);
+}
+
+template <int K, bool kTable, bool kMajor>
+static void launch_dequantize_ex(const uint8_t *codes, const uint8_t *labels, const float *params, int64_t n, int m,
+                                 const float *qmap, float *out, hipStream_t s)
+{
+    const int64_t G = 256 * (int64_t)K;
+    const int64_t groups = (n + G - 1) / G;
+    const int64_t blocks = (groups + kVWaves - 1) / kVWaves;
+    hipLaunchKernelGGL((dequantize_cluster_ex_kernel<K, kTable, kMajor>), dim3((unsigned)blocks), dim3(kVBlock), 0, s, codes,
+                       labels, params, n, groups, m, qmap, out);
+}
+
+}  // namespace bitsnap
+
+using namespace bitsnap;
+
+#define BITSNAP_BY_K(K, CALL)          \
+    switch (K) {                       \
+    case 1: CALL(1); break;            \
+    case 2: CALL(2); break;            \
+    case 4: CALL(4); break;            \
+    case 8: CALL(8); break;            \
+    default: CALL(16); break;          \
+    }
+
+extern "C" int bitsnap_quantize_cluster_ex(const float *x, int64_t n, int64_t group, int m, uint32_t flags,
+                                           const float *qmap, uint8_t *codes, uint8_t *labels, float *params,
+                                           float *fit_out, const float *fit_in, uint32_t *status,
+                                           bitsnap_stream_t stream)
+{
+    if (n < 0 || m < 1 || m > kMaxClusters || (flags & ~(uint32_t)BITSNAP_CLUSTER_MAJOR))
+        return BITSNAP_E_SIZE;
+    const int K = one_wave_group_k(group);
+    if (K == 0 || (n + 256 * (int64_t)K - 1) / (256 * (int64_t)K) / kVWaves > 0x7FFFFFFF)
+        return BITSNAP_E_SIZE;
+    if (n == 0)
+        return BITSNAP_OK;
+    const bool major = (flags & BITSNAP_CLUSTER_MAJOR) != 0;
+    if (!qmap && !major)
+        return bitsnap_quantize_cluster(x, n, group, m, codes, labels, params, fit_out, fit_in, status, nullptr, 0, stream);
+    if (!x || !codes || !labels || !params)
+        return BITSNAP_E_NULL;
+    if (!aligned16(x) || !aligned16(codes) || !aligned16(labels) || !aligned16(params) || ((uintptr_t)fit_out & 3u) ||
+        ((uintptr_t)fit_in & 3u) || ((uintptr_t)status & 3u) || ((uintptr_t)qmap & 3u))
+        return BITSNAP_E_ALIGN;
+    hipStream_t s = (hipStream_t)stream;
+#define BITSNAP_Q_TM(KK) launch_quantize_ex<KK, true, true>(x, n, m, qmap, codes, labels, params, fit_out, fit_in, status, s)
+#define BITSNAP_Q_T(KK) launch_quantize_ex<KK, true, false>(x, n, m, qmap, codes, labels, params, fit_out, fit_in, status, s)
+#define BITSNAP_Q_M(KK) launch_quantize_ex<KK, false, true>(x, n, m, qmap, codes, labels, params, fit_out, fit_in, status, s)
+    if (qmap && major) {
+        BITSNAP_BY_K(K, BITSNAP_Q_TM)
+    } else if (qmap) {
+        BITSNAP_BY_K(K, BITSNAP_Q_T)
+    } else {
+        BITSNAP_BY_K(K, BITSNAP_Q_M)
+    }
+#undef BITSNAP_Q_TM
+#undef BITSNAP_Q_T
+#undef BITSNAP_Q_M
+    return launch_status();
+}
+
+extern "C" int bitsnap_dequantize_cluster_ex(const uint8_t *codes, const uint8_t *labels, const float *params,
+                                             int64_t n, int64_t group, int m, uint32_t flags, const float *qmap,
+                                             float *out, bitsnap_stream_t stream)
+{
+    if (n < 0 || m < 1 || m > kMaxClusters || (flags & ~(uint32_t)BITSNAP_CLUSTER_MAJOR))
+        return BITSNAP_E_SIZE;
+    const int K = one_wave_group_k(group);
+    if (K == 0 || (n + 256 * (int64_t)K - 1) / (256 * (int64_t)K) / kVWaves > 0x7FFFFFFF)
+        return BITSNAP_E_SIZE;
+    if (n == 0)
+        return BITSNAP_OK;
+    const bool major = (flags & BITSNAP_CLUSTER_MAJOR) != 0;
+    if (!qmap && !major)
+        return bitsnap_dequantize_cluster(codes, labels, params, n, group, m, out, stream);
+    if (!codes || !labels || !params || !out)
+        return BITSNAP_E_NULL;
+    if (!aligned16(codes) || !aligned16(labels) || !aligned16(params) || !aligned16(out) || ((uintptr_t)qmap & 3u))
+        return BITSNAP_E_ALIGN;
+    hipStream_t s = (hipStream_t)stream;
+#define BITSNAP_D_TM(KK) launch_dequantize_ex<KK, true, true>(codes, labels, params, n, m, qmap, out, s)
+#define BITSNAP_D_T(KK) launch_dequantize_ex<KK, true, false>(codes, labels, params, n, m, qmap, out, s)
+#define BITSNAP_D_M(KK) launch_dequantize_ex<KK, false, true>(codes, labels, params, n, m, qmap, out, s)
+    if (qmap && major) {
+        BITSNAP_BY_K(K, BITSNAP_D_TM)
+    } else if (qmap) {
+        BITSNAP_BY_K(K, BITSNAP_D_T)
+    } else {
+        BITSNAP_BY_K(K, BITSNAP_D_M)
+    }
+#undef BITSNAP_D_TM
+#undef BITSNAP_D_T
+#undef BITSNAP_D_M
+    return launch_status();
+}

@@ -14,4 +14,18 @@ int cluster_general_quantize(const float *x, int64_t n, int64_t group, int m, ui
 int cluster_general_dequantize(const uint8_t *codes, const uint8_t *labels, const float *params, int64_t n,
                                int64_t group, int m, float *out, hipStream_t s);
 
+// K (float4 per lane) of the one-wave-per-group kernels for a group length, or 0 when the length
+// needs the multi-pass path.
+inline int one_wave_group_k(int64_t group)
+{
+    switch (group) {
+    case 256: return 1;
+    case 512: return 2;
+    case 1024: return 4;
+    case 2048: return 8;
+    case 4096: return 16;
+    default: return 0;
+    }
+}
+
 }  // namespace bitsnap

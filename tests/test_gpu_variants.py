@@ -1,0 +1,151 @@
+"""GPU parity: the format variants of the cluster pair (a 256-entry map Q in Eq. qmap-distance, cluster-major codes of
+Eq. decluster) through the C ABI against the CPU oracle.
+
+Protocol as for the plain pair: the GPU's (mu, sigma) are compared with the oracle's at 1e-6 elsewhere; here the oracle
+is run with the GPU's fit, and labels, (S, b), codes (in either arrangement) and the dequantised values must then be
+bit-exact.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from gpu_util import DEV, announce, f32_to_dev, to_np
+from paper_2511_12376_amd import binding as B
+from paper_2511_12376_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+def _states(seed, n, scale=1e-3):
+    rng = np.random.default_rng(seed)
+    return (rng.standard_normal(n) * scale).astype(np.float32)
+
+
+def _check(x, G, m, kind, major):
+    n = x.size
+    Q = None if kind is None else synth.qmap_table(kind)
+    Qd = None if Q is None else f32_to_dev(Q)
+    q = B.quantize_cluster_ex(f32_to_dev(x), G, m, qmap=Qd, cluster_major=major)
+    torch.cuda.synchronize()
+    assert int(q.status.item()) == 0
+    fit = to_np(q.fit)
+    o = oracle.quantize_cluster_ex(x, G, m, fit_in=fit[:, :2].copy(), qmap=Q, cluster_major=major)
+    assert np.array_equal(to_np(q.labels), o["labels"])
+    assert np.array_equal(to_np(q.params), o["params"])
+    assert np.array_equal(to_np(q.codes), o["codes"])
+    xh = B.dequantize_cluster_ex(q.codes, q.labels, q.params, n, G, m, qmap=Qd, cluster_major=major)
+    torch.cuda.synchronize()
+    want = oracle.dequantize_cluster_ex(o["codes"], o["labels"], o["params"], n, G, m, qmap=Q, cluster_major=major)
+    assert np.array_equal(to_np(xh), want)
+    return o, want
+
+
+@pytest.mark.parametrize("kind,major", [(None, True), ("normal", False), ("square", True), ("steps", True), ("linear", False)])
+@pytest.mark.parametrize("G", [256, 512, 1024, 2048, 4096])
+def test_variants_match_the_oracle(G, kind, major):
+    announce("variants", G, kind, major)
+    n = 9 * G + G // 2 + 3            # several workgroups of full groups and a ragged last group
+    _check(_states(G, n), G, 16, kind, major)
+
+
+@pytest.mark.parametrize("m", [1, 2, 7, 15])
+def test_variants_with_fewer_clusters(m):
+    announce("variants m", m)
+    _check(_states(m, 5 * 4096 + 77), 4096, m, "normal", True)
+    _check(_states(m + 50, 3 * 1024 + 1), 1024, m, None, True)
+
+
+@pytest.mark.parametrize("n", [1, 2, 3, 5, 63, 255, 257, 4095, 4097])
+def test_variants_on_short_and_ragged_tensors(n):
+    announce("variants short", n)
+    _check(_states(n, n), 4096, 16, "square", True)
+    _check(_states(n + 1, n), 256, 16, None, True)
+
+
+def test_cluster_major_round_trip_equals_the_element_order_round_trip():
+    announce("variants round trip")
+    x = _states(11, 20 * 4096)
+    xd = f32_to_dev(x)
+    a = B.quantize_cluster(xd, 4096, 16)
+    b = B.quantize_cluster_ex(xd, 4096, 16, cluster_major=True)
+    ya = B.dequantize_cluster(a.codes, a.labels, a.params, x.size, 4096, 16)
+    yb = B.dequantize_cluster_ex(b.codes, b.labels, b.params, x.size, 4096, 16, cluster_major=True)
+    torch.cuda.synchronize()
+    assert torch.equal(a.labels, b.labels) and torch.equal(a.params, b.params) and torch.equal(ya, yb)
+    assert not torch.equal(a.codes, b.codes)
+    # without options the extended calls are the plain calls
+    c = B.quantize_cluster_ex(xd, 4096, 16)
+    yc = B.dequantize_cluster_ex(c.codes, c.labels, c.params, x.size, 4096, 16)
+    torch.cuda.synchronize()
+    assert torch.equal(a.codes, c.codes) and torch.equal(ya, yc)
+
+
+def test_exact_ties_and_repeated_entries_take_the_lowest_index():
+    announce("variants ties")
+    Q = np.ones(256, np.float32)
+    Q[0], Q[1], Q[2], Q[3], Q[4] = 0.0, 0.25, 0.25, 0.75, 0.75
+    base = np.array([0.0, 1.0, 0.5, 0.25, 0.125, 0.75, 0.875, 0.3], np.float32)
+    x = np.tile(base, 32)                                             # one group of 256, one cluster: b = 0, S = 1
+    q = B.quantize_cluster_ex(f32_to_dev(x), 256, 1, qmap=f32_to_dev(Q))
+    torch.cuda.synchronize()
+    assert list(to_np(q.codes)[:8]) == [0, 5, 1, 1, 0, 3, 3, 1]
+    o = oracle.quantize_cluster_ex(x, 256, 1, qmap=Q)
+    assert np.array_equal(to_np(q.codes), o["codes"])
+    # a table of one repeated level: every code is the first entry
+    flat = np.full(256, 0.5, np.float32)
+    q = B.quantize_cluster_ex(f32_to_dev(x), 256, 1, qmap=f32_to_dev(flat))
+    torch.cuda.synchronize()
+    assert np.all(to_np(q.codes) == 0)
+
+
+def test_degenerate_groups():
+    announce("variants degenerate")
+    x = _states(12, 4 * 4096)
+    x[:4096] = 0.25                              # constant group: sigma = 0, every range is empty or a point
+    x[4096:8192] = np.repeat(_states(13, 16), 256)   # sixteen distinct values
+    x[8192:8192 + 100] = 1e30                    # outliers far from the rest
+    for kind, major in ((None, True), ("normal", True), ("steps", False)):
+        o, want = _check(x, 4096, 16, kind, major)
+        assert np.all(want[:4096] == np.float32(0.25))
+
+
+def test_argument_checks():
+    x = f32_to_dev(_states(14, 4096))
+    with pytest.raises(B.BitsnapError):
+        B.quantize_cluster_ex(x, 1000, 16, cluster_major=True)          # not a one-wave group length
+    with pytest.raises(B.BitsnapError):
+        B.quantize_cluster_ex(x, 0, 16, cluster_major=True)             # whole-tensor groups: plain entry point only
+    q = B.quantize_cluster_ex(x, 4096, 16, cluster_major=True)
+    out = torch.empty(4096, dtype=torch.float32, device=DEV)
+    with pytest.raises(B.BitsnapError):
+        B.dequantize_cluster_ex_raw(q.codes, q.labels, q.params, 4096, 4096, 16, 2, None, out)   # unknown flag
+    with pytest.raises(B.BitsnapError):
+        B.dequantize_cluster_ex_raw(q.codes, q.labels, q.params, 4096, 4096, 17, 1, None, out)   # m > 16
+    torch.cuda.synchronize()
+
+
+def test_full_size_tensor_on_sampled_groups():
+    """The largest tensor of the 7B-shaped checkpoint (131 M elements): every group is independent, so sampled groups
+    are checked one by one against the oracle run on that group alone."""
+    announce("variants full size")
+    cfg = synth.config(2)
+    d = synth.make_tensor_torch(cfg, 0, DEV)
+    x = d["m"].reshape(-1)
+    n = x.numel()
+    Q = synth.qmap_table("normal")
+    Qd = f32_to_dev(Q)
+    q = B.quantize_cluster_ex(x, 4096, 16, qmap=Qd, cluster_major=True)
+    xh = B.dequantize_cluster_ex(q.codes, q.labels, q.params, n, 4096, 16, qmap=Qd, cluster_major=True)
+    torch.cuda.synchronize()
+    groups = n // 4096
+    rng = np.random.default_rng(15)
+    for g in [0, 1, groups - 1] + list(rng.integers(0, groups, 40)):
+        lo, hi = int(g) * 4096, int(g) * 4096 + 4096
+        xs = to_np(x[lo:hi])
+        o = oracle.quantize_cluster_ex(xs, 4096, 16, fit_in=to_np(q.fit[g, :2]).reshape(1, 2).copy(), qmap=Q, cluster_major=True)
+        assert np.array_equal(to_np(q.codes[lo:hi]), o["codes"]), g
+        assert np.array_equal(to_np(q.labels[lo // 2:hi // 2]), o["labels"]), g
+        assert np.array_equal(to_np(q.params[g]), o["params"][0]), g
+        want = oracle.dequantize_cluster_ex(o["codes"], o["labels"], o["params"], 4096, 4096, 16, qmap=Q, cluster_major=True)
+        assert np.array_equal(to_np(xh[lo:hi]), want), g
