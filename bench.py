@@ -326,6 +326,34 @@ def main():
         extras["sparse_32_bit_elements"] = row32
         del m32, b32, e32, o32
 
+        # the cluster pair's format variants on the largest tensor's first Adam moment: a non-linear 256-entry map
+        # (bisection in LDS per element) and cluster-major codes (a stable 16-way partition inside the wave)
+        xq = inputs[big]["m"].reshape(-1)
+        qtab = torch.from_numpy(synth.qmap_table("normal")).to(dev)
+        valg = 5 * nb + (nb + 1) // 2 + B.cluster_groups(nb, GROUP) * M * 8
+        rows_v = {}
+        for label, tab, major in (("cluster-major codes", None, True), ("table map", qtab, False),
+                                  ("table map, cluster-major codes", qtab, True)):
+            qv = B.quantize_cluster_ex(xq, GROUP, M, qmap=tab, cluster_major=major)
+            ov = torch.empty(nb, dtype=torch.float32, device=dev)
+            fl = B.CLUSTER_MAJOR if major else 0
+            row = {}
+            for name, fnv in (("quantize", lambda: B.quantize_cluster_ex_raw(xq, nb, GROUP, M, fl, tab, qv.codes, qv.labels,
+                                                                             qv.params, None, None, qv.status)),
+                              ("dequantize", lambda: B.dequantize_cluster_ex_raw(qv.codes, qv.labels, qv.params, nb, GROUP, M,
+                                                                                 fl, tab, ov))):
+                for it in range(2):
+                    e0.record(stream)
+                    for _ in range(5):
+                        fnv()
+                    e1.record(stream)
+                    torch.cuda.synchronize()
+                msv = e0.elapsed_time(e1) / 5
+                row[name] = {"ms": round(msv, 4), "hbm_frac": round(valg / msv / 1e6 / HBM_PEAK_GBS, 4)}
+            rows_v[label] = row
+            del qv, ov
+        extras["cluster_format_variants"] = {"elements": nb, "rows": rows_v}
+
         # the one-call-per-tensor step again, captured once in a HIP graph and replayed: what is left of it when
         # the host no longer issues 2328 calls per step
         side = torch.cuda.Stream()

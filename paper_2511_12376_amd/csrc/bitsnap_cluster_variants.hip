@@ -6,7 +6,9 @@
 //     first, then cluster 1, ..., each cluster's codes in element order.
 //
 // One wavefront per group, as in the plain kernels, and steps 1-4 of Algorithm 2 are the same
-// code.  The table lives in LDS once per workgroup and is searched by bisection.  The
+// code.  The table lives in LDS once per workgroup, turned into a step function over 1024 bins
+// of (x-b)/S where its levels are far enough apart for that, and searched by bisection otherwise.
+// The
 // cluster-major arrangement is a stable 16-way partition of the group's codes done inside the
 // wave through LDS: the codes and the labels are laid down in element order; then lane l takes
 // the 4K consecutive elements l*4K .. l*4K+4K-1, counts its labels into a private column of a
@@ -158,13 +160,147 @@ __device__ __forceinline__ void from_cluster_major(const MajorView &mv, int len,
     wave_lds_sync();
 }
 
-// Eq. qmap-distance with a table, decided in fp32: the index of the entry nearest to t, the
-// lowest index where several are equally near (in rounded distance).  The table is
-// non-decreasing, so the nearest entry is one of the two that bracket t: p = the last entry
-// <= t (8 bisection steps over entries 1..255) and its successor.  Entries below p can only tie
-// with it, never beat it; the walk down at the end finds the first of such a run.
+// ---------------------------------------------------------------------------------------------
+// Eq. qmap-distance with a table, decided in fp32: code(t) = the index of the entry nearest to
+// t in rounded distance fl32(|Q_j - t|), the lowest index where several are equally near.
+//
+// General search.  The table is non-decreasing, so the nearest entry is one of the two that
+// bracket t: p = the last entry <= t among entries 1..255 (0 if there is none; 8 bisection
+// steps) and its successor.  Entries below p can only tie with it, never beat it; the walk down
+// at the end finds the first of such a run.
+//
+// Search by bins.  Let L_0 < L_1 < ... be the distinct levels of the table and f_k the first
+// index of level k.  For a well-separated table code(t) = f_k with k = #{i >= 1 : theta_i <= t},
+// where theta_i is the smallest fp32 t that is nearer (in rounded distance) to L_i than to
+// L_{i-1}: a step function, evaluated like the label search - bin(t) = min(1023, floor(1024 t))
+// is non-decreasing, every bin stores the threshold inside it (or NaN) and the codes below and
+// at that threshold, so an element costs one 8-byte LDS read and a compare.  It needs
+//   * at most one threshold per bin, and every threshold found within a few ulps of the midpoint;
+//   * no two levels so close that, seen from a t whose nearest level is the upper of them, their
+//     rounded distances coincide (the reference then answers with the lower one's index): with
+//     t <= 1 + 2^-22, which holds for every element because x - b <= S, it is enough that
+//     L_k - L_{k-1} >= 2^-20 (min(L_{k+1}, 1 + 2^-22) - L_{k-1}) for all k.
+// Both are checked on the table itself, once per workgroup; a table that fails takes the
+// general search.
+// ---------------------------------------------------------------------------------------------
+constexpr int kTableBins = 1024;
+constexpr float kTMax = 1.0f + 0x1p-22f;
+
+struct alignas(16) TableShared {
+    float q[kLevels];
+    float2 bins[kTableBins];     // (threshold in the bin or NaN, code below it | code at and above it << 16)
+    uint16_t bin_of_entry[kLevels];  // bin of the threshold that starts entry j's level (first entries only)
+    uint32_t general;            // != 0: this table takes the general search
+};
+
+__device__ __forceinline__ uint32_t table_bin(float t)
+{
+    // floor(1024 t) held to 0..1023; NaN goes to bin 0
+    return (uint32_t)fminf(fmaxf(__fmul_rn(t, (float)kTableBins), 0.0f), (float)(kTableBins - 1));
+}
+
+__device__ __forceinline__ float next_up(float x)
+{
+    if (x == 0.0f)
+        return __uint_as_float(1u);
+    const uint32_t u = __float_as_uint(x);
+    return __uint_as_float(x > 0.0f ? u + 1u : u - 1u);
+}
+
+__device__ __forceinline__ float next_down(float x)
+{
+    if (x == 0.0f)
+        return __uint_as_float(0x80000001u);
+    const uint32_t u = __float_as_uint(x);
+    return __uint_as_float(x > 0.0f ? u - 1u : u + 1u);
+}
+
+// Fills the workgroup's copy of the table and its bins; thread j of the kVBlock == kLevels
+// threads takes entry j.  Contains workgroup barriers: call with every thread.
+__device__ __forceinline__ void load_table(TableShared &ts, const float *__restrict__ qmap)
+{
+    const int j = threadIdx.x;
+    const float nan = __uint_as_float(0x7FC00000u);
+    ts.q[j] = global_ptr(qmap)[j];
+    for (int i = 0; i < kTableBins / kLevels; ++i)
+        ts.bins[j * (kTableBins / kLevels) + i] = make_float2(nan, 0.0f);
+    if (j == 0)
+        ts.general = 0;
+    __syncthreads();
+    const float B = ts.q[j];
+    const bool first = j == 0 || ts.q[j - 1] != B;  // entry j starts a level
+    int below = 0, above = j + 1;                   // first entry of the level below, first entry of the level above
+    float theta = nan;
+    bool bad = !(B == B) || (j > 0 && ts.q[j - 1] > B);  // NaN entry or a decreasing step
+    if (first) {
+        while (above < kLevels && ts.q[above] == B)
+            ++above;
+        if (j > 0) {
+            const float A = ts.q[j - 1];
+            below = j - 1;
+            while (below > 0 && ts.q[below - 1] == A)
+                --below;
+            // theta: the smallest t with fl|B - t| < fl|A - t|; the predicate is monotone in t
+            float c = __fadd_rn(__fmul_rn(0.5f, A), __fmul_rn(0.5f, B));
+            bool found = false;
+            for (int it = 0; it < 32 && !found; ++it) {
+                if (fabsf(__fsub_rn(B, c)) < fabsf(__fsub_rn(A, c))) {
+                    const float d = next_down(c);
+                    if (fabsf(__fsub_rn(B, d)) < fabsf(__fsub_rn(A, d)))
+                        c = d;
+                    else
+                        found = true;
+                } else {
+                    c = next_up(c);
+                }
+            }
+            theta = c;
+            const float next_level = above < kLevels ? ts.q[above] : kTMax;
+            const float span = __fsub_rn(fminf(next_level, kTMax), A);
+            bad = bad || !found || !(__fsub_rn(B, A) >= __fmul_rn(span, 0x1p-20f));
+            const uint32_t bin = table_bin(theta);
+            ts.bin_of_entry[j] = (uint16_t)bin;
+            ts.bins[bin].y = __uint_as_float((uint32_t)j);  // claim the bin
+        }
+    }
+    __syncthreads();
+    if (first && j > 0 && __float_as_uint(ts.bins[ts.bin_of_entry[j]].y) != (uint32_t)j)
+        bad = true;  // another threshold claimed the same bin
+    if (bad)
+        atomicOr(&ts.general, 1u);
+    __syncthreads();
+    if (first && ts.general == 0) {
+        // entry j's level answers from just after its own threshold up to the next level's threshold
+        const int from = j == 0 ? 0 : (int)ts.bin_of_entry[j] + 1;
+        const int to = above < kLevels ? (int)ts.bin_of_entry[above] : kTableBins;  // the next threshold's bin, or the end
+        for (int b = from; b < to; ++b)
+            ts.bins[b] = make_float2(nan, __uint_as_float((uint32_t)j | ((uint32_t)j << 16)));
+        if (j > 0)
+            ts.bins[ts.bin_of_entry[j]] = make_float2(theta, __uint_as_float((uint32_t)below | ((uint32_t)j << 16)));
+    }
+    __syncthreads();
+}
+
 constexpr int kTableBatch = 8;
-__device__ __forceinline__ void table_codes(const float *table, const float (&t)[kTableBatch], uint32_t (&code)[kTableBatch])
+
+__device__ __forceinline__ void table_codes_by_bins(const TableShared &ts, const float (&t)[kTableBatch],
+                                                    uint32_t (&code)[kTableBatch])
+{
+    float2 e[kTableBatch];
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int i = 0; i < kTableBatch; ++i)
+        e[i] = ts.bins[table_bin(t[i])];
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int i = 0; i < kTableBatch; ++i) {
+        const uint32_t c = __float_as_uint(e[i].y);
+        code[i] = t[i] >= e[i].x ? c >> 16 : c & 0xFFFFu;
+    }
+}
+
+__device__ __forceinline__ void table_codes_general(const TableShared &ts, const float (&t)[kTableBatch],
+                                                    uint32_t (&code)[kTableBatch])
 {
     uint32_t p[kTableBatch];
 #pragma unroll
@@ -176,7 +312,7 @@ __device__ __forceinline__ void table_codes(const float *table, const float (&t)
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int i = 0; i < kTableBatch; ++i)
-            q[i] = table[p[i] + s];
+            q[i] = ts.q[p[i] + s];
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int i = 0; i < kTableBatch; ++i)
@@ -186,9 +322,9 @@ __device__ __forceinline__ void table_codes(const float *table, const float (&t)
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int i = 0; i < kTableBatch; ++i) {
-        ql[i] = table[p[i]];
-        qh[i] = table[p[i] < kLevels - 1 ? p[i] + 1 : kLevels - 1];
-        qb[i] = table[p[i] > 0 ? p[i] - 1 : 0];
+        ql[i] = ts.q[p[i]];
+        qh[i] = ts.q[p[i] < kLevels - 1 ? p[i] + 1 : kLevels - 1];
+        qb[i] = ts.q[p[i] > 0 ? p[i] - 1 : 0];
     }
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -199,7 +335,7 @@ __device__ __forceinline__ void table_codes(const float *table, const float (&t)
             w = p[i] < kLevels - 1 ? p[i] + 1 : kLevels - 1;
         } else if (w > 0 && fabsf(__fsub_rn(qb[i], t[i])) <= dl) {
             --w;  // a run of equally near entries (repeated entries, or a distance that rounds the same)
-            while (w > 0 && fabsf(__fsub_rn(table[w - 1], t[i])) <= dl)
+            while (w > 0 && fabsf(__fsub_rn(ts.q[w - 1], t[i])) <= dl)
                 --w;
         }
         code[i] = w;
@@ -210,7 +346,7 @@ __device__ __forceinline__ void table_codes(const float *table, const float (&t)
 // ws.coder holds (b, 255/S) for the linear map and (b, 1/S) for a table.
 template <int K, bool kTable>
 __device__ __forceinline__ void codes_to_registers(const float4 (&v)[K], const uint32_t (&packed)[(K + 1) / 2], WaveShared &ws,
-                                                   const float *table, uint32_t (&c4)[K])
+                                                   const TableShared &table, uint32_t (&c4)[K])
 {
     constexpr int kF = kTableBatch / 4 < K ? kTableBatch / 4 : K;  // float4 per batch
 #pragma unroll
@@ -230,7 +366,10 @@ __device__ __forceinline__ void codes_to_registers(const float4 (&v)[K], const u
             }
         }
         if (kTable) {
-            table_codes(table, t, code);
+            if (table.general)
+                table_codes_general(table, t, code);
+            else
+                table_codes_by_bins(table, t, code);
 #pragma unroll
             for (int f = 0; f < kF; ++f)
                 c4[kb + f] = code[4 * f] | (code[4 * f + 1] << 8) | (code[4 * f + 2] << 16) | (code[4 * f + 3] << 24);
@@ -264,27 +403,15 @@ __device__ __forceinline__ void store_codes(const uint32_t (&c4)[K], int64_t lo,
     }
 }
 
+// Algorithm 2 with the format options for one group of len <= 256*K elements, by one wave.
 template <int K, bool kFull, bool kTable, bool kMajor>
-__global__ __launch_bounds__(kVBlock) void quantize_cluster_ex_kernel(
-    const float *__restrict__ x, int64_t n, int64_t first_group, int64_t groups, int m, const float *__restrict__ qmap,
-    uint8_t *__restrict__ codes, uint8_t *__restrict__ labels, float *__restrict__ params, float *__restrict__ fit_out,
-    const float *__restrict__ fit_in, uint32_t *__restrict__ status)
+__device__ __forceinline__ void quantize_group_ex(const float *__restrict__ x, int64_t lo, int len, int m, int64_t g,
+                                                  uint8_t *__restrict__ codes, uint8_t *__restrict__ labels,
+                                                  float *__restrict__ params, float *__restrict__ fit_out,
+                                                  const float *__restrict__ fit_in, uint32_t *__restrict__ status,
+                                                  QuantizeShared &shared, const TableShared &table, int lane)
 {
-    __shared__ QuantizeShared shared[kVWaves];
-    __shared__ float table[kLevels];
-    if (kTable) {
-        table[threadIdx.x] = global_ptr(qmap)[threadIdx.x];  // kVBlock == kLevels
-        __syncthreads();
-    }
-    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
-    const int64_t g = first_group + (int64_t)blockIdx.x * kVWaves + wave;
-    if (g >= first_group + groups)
-        return;  // after the only workgroup barrier
-    constexpr int G = 256 * K;
-    const int64_t lo = g * G;
-    const int64_t rest = n - lo;
-    const int len = kFull ? G : (int)(rest < G ? rest : G);
-    WaveShared &ws = shared[wave].ws;
+    WaveShared &ws = shared.ws;
 
     // ---- steps 1-4 of Algorithm 2, as in the plain kernel
     float4 v[K];
@@ -336,7 +463,7 @@ __global__ __launch_bounds__(kVBlock) void quantize_cluster_ex_kernel(
         MajorView mv;
         mv.counters = (uint32_t *)&ws.tab[0][0];
         mv.bytes = (uint32_t *)&ws.tab[kMaxClusters][0];
-        mv.labels = shared[wave].labels;
+        mv.labels = shared.labels;
         uint16_t *l16 = (uint16_t *)mv.labels;
 #pragma unroll
         for (int k = 0; k < K; ++k) {
@@ -350,6 +477,33 @@ __global__ __launch_bounds__(kVBlock) void quantize_cluster_ex_kernel(
             c4[k] = mv.bytes[k * kWave + lane];
     }
     store_codes<K, kFull>(c4, lo, len, lane, codes);
+    wave_lds_sync();  // this wave may go on to another group and rewrite the tables
+}
+
+// Every wave walks over groups first_group + w, + w + W, ... (w = its index among the W waves of
+// the grid): the grid is sized to the device when a table has to be prepared per workgroup, and
+// to one group per wave otherwise.
+template <int K, bool kFull, bool kTable, bool kMajor>
+__global__ __launch_bounds__(kVBlock, 3) void quantize_cluster_ex_kernel(
+    const float *__restrict__ x, int64_t n, int64_t first_group, int64_t groups, int m, const float *__restrict__ qmap,
+    uint8_t *__restrict__ codes, uint8_t *__restrict__ labels, float *__restrict__ params, float *__restrict__ fit_out,
+    const float *__restrict__ fit_in, uint32_t *__restrict__ status)
+{
+    __shared__ QuantizeShared shared[kVWaves];
+    __shared__ TableShared table;
+    if (kTable)
+        load_table(table, qmap);
+    // no workgroup barrier from here on: waves leave when they run out of groups
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
+    constexpr int G = 256 * K;
+    for (int64_t g = first_group + (int64_t)blockIdx.x * kVWaves + wave; g < first_group + groups;
+         g += (int64_t)gridDim.x * kVWaves) {
+        const int64_t lo = g * G;
+        const int64_t rest = n - lo;
+        const int len = kFull ? G : (int)(rest < G ? rest : G);
+        quantize_group_ex<K, kFull, kTable, kMajor>(x, lo, len, m, g, codes, labels, params, fit_out, fit_in, status,
+                                                    shared[wave], table, lane);
+    }
 }
 
 template <int K, bool kTable, bool kMajor>
@@ -360,7 +514,7 @@ __global__ __launch_bounds__(kVBlock) void dequantize_cluster_ex_kernel(
     __shared__ DequantizeShared shared[kVWaves];
     __shared__ float table[kLevels];
     if (kTable) {
-        table[threadIdx.x] = global_ptr(qmap)[threadIdx.x];
+        table[threadIdx.x] = global_ptr(qmap)[threadIdx.x];  // kVBlock == kLevels
         __syncthreads();
     }
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
@@ -447,7 +601,13 @@ static void launch_quantize_ex(const float *x, int64_t n, int m, const float *qm
     const int64_t G = 256 * (int64_t)K;
     const int64_t full = n / G;
     const bool tail = (n % G) != 0;
-    const int64_t blocks = (full + kVWaves - 1) / kVWaves;
+    int64_t blocks = (full + kVWaves - 1) / kVWaves;
+    if (kTable) {
+        const void *kernel = (const void *)quantize_cluster_ex_kernel<K, true, kTable, kMajor>;
+        const int64_t resident = (int64_t)device_info().cu_count * occupancy_blocks_per_cu(kernel, kVBlock);
+        if (blocks > resident)
+            blocks = resident;
+    }
     if (full > 0)
         hipLaunchKernelGGL((quantize_cluster_ex_kernel<K, true, kTable, kMajor>), dim3((unsigned)blocks), dim3(kVBlock), 0, s,
                            x, n, (int64_t)0, full, m, qmap, codes, labels, params, fit_out, fit_in, status);

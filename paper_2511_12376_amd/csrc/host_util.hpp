@@ -39,7 +39,7 @@ inline int occupancy_blocks_per_cu(const void *kernel, int block)
         const void *k;
         int v;
     };
-    static Entry cache[16];
+    static Entry cache[64];
     static int used = 0;
     static std::mutex mu;
     std::lock_guard<std::mutex> lock(mu);
@@ -49,7 +49,7 @@ inline int occupancy_blocks_per_cu(const void *kernel, int block)
     int per_cu = 0;
     if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, block, 0) != hipSuccess || per_cu < 1)
         per_cu = 1;
-    if (used < 16)
+    if (used < 64)
         cache[used++] = Entry{kernel, per_cu};
     return per_cu;
 }

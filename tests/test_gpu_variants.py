@@ -149,3 +149,54 @@ def test_full_size_tensor_on_sampled_groups():
         assert np.array_equal(to_np(q.params[g]), o["params"][0]), g
         want = oracle.dequantize_cluster_ex(o["codes"], o["labels"], o["params"], 4096, 4096, 16, qmap=Q, cluster_major=True)
         assert np.array_equal(to_np(xh[lo:hi]), want), g
+
+
+def _around_the_midpoints(Q, pad_seed):
+    """One group of 4096 values in [0, 1] that holds 0, 1 and, for every pair of neighbouring levels of Q, the fp32
+    numbers within 4 steps of their midpoint: with one cluster b = 0 and S = 1, so (x-b)/S = x exactly."""
+    lv = np.unique(Q[(Q >= 0) & (Q <= 1)])
+    mids = ((lv[:-1].astype(np.float64) + lv[1:].astype(np.float64)) / 2).astype(np.float32)
+    vals = [np.array([0.0, 1.0], np.float32), mids]
+    up, dn = mids.copy(), mids.copy()
+    for _ in range(4):
+        up = np.nextafter(up, np.float32(2))
+        dn = np.nextafter(dn, np.float32(-1))
+        vals += [up.copy(), dn.copy()]
+    x = np.concatenate(vals)
+    x = x[(x >= 0) & (x <= 1)]
+    assert x.size <= 4096
+    pad = np.random.default_rng(pad_seed).random(4096 - x.size).astype(np.float32)
+    return np.concatenate([x, pad])
+
+
+def _tables():
+    lin = synth.qmap_table("linear")
+    close = lin.copy()
+    close[100] = np.nextafter(close[99], np.float32(2))          # two levels one step apart
+    close[200] = np.nextafter(np.nextafter(close[199], np.float32(2)), np.float32(2))
+    wide = np.linspace(-0.2, 1.3, 256).astype(np.float32)         # levels outside [0, 1]
+    coarse = np.repeat(np.linspace(0, 1, 4), 64).astype(np.float32)
+    dense = (np.arange(256) / 255.0).astype(np.float64) ** 6      # many levels inside one bin of width 1/1024 near 0
+    return {"linear": lin, "normal": synth.qmap_table("normal"), "square": synth.qmap_table("square"),
+            "steps": synth.qmap_table("steps"), "close": close, "wide": wide, "coarse": coarse,
+            "dense": dense.astype(np.float32)}
+
+
+@pytest.mark.parametrize("name", ["linear", "normal", "square", "steps", "close", "wide", "coarse", "dense"])
+def test_table_codes_exactly_at_the_decision_points(name):
+    announce("variants decision points", name)
+    Q = _tables()[name]
+    x = _around_the_midpoints(Q, 21)
+    q = B.quantize_cluster_ex(f32_to_dev(x), 4096, 1, qmap=f32_to_dev(Q))
+    torch.cuda.synchronize()
+    assert to_np(q.params)[0, 0, 0] == 1.0 and to_np(q.params)[0, 0, 1] == 0.0
+    o = oracle.quantize_cluster_ex(x, 4096, 1, qmap=Q)
+    assert np.array_equal(to_np(q.codes), o["codes"])
+    # and on ordinary states, 16 clusters
+    _check(_states(22, 6 * 4096 + 5), 4096, 16, None, False) if name == "linear" else None
+    y = _states(23, 6 * 4096 + 5)
+    Qd = f32_to_dev(Q)
+    g = B.quantize_cluster_ex(f32_to_dev(y), 4096, 16, qmap=Qd, cluster_major=True)
+    torch.cuda.synchronize()
+    oy = oracle.quantize_cluster_ex(y, 4096, 16, fit_in=to_np(g.fit)[:, :2].copy(), qmap=Q, cluster_major=True)
+    assert np.array_equal(to_np(g.codes), oy["codes"])
