@@ -352,7 +352,26 @@ def main():
                 row[name] = {"ms": round(msv, 4), "hbm_frac": round(valg / msv / 1e6 / HBM_PEAK_GBS, 4)}
             rows_v[label] = row
             del qv, ov
-        extras["cluster_format_variants"] = {"elements": nb, "rows": rows_v}
+        # and over the whole first-moment state in one batched launch (table map + cluster-major codes); the plain
+        # batched call afterwards restores that state's element-order codes
+        alg_state = 5 * n_total + sum((n + 1) // 2 for n in sizes) + total_groups * M * 8
+        row_b = {}
+        for name, fnb in (("quantize", lambda: B.quantize_cluster_batched_ex(q_items[1], total_groups, GROUP, M, qmap=qtab,
+                                                                             cluster_major=True, status=status)),
+                          ("dequantize", lambda: B.dequantize_cluster_batched_ex(dq_items[1], total_groups, GROUP, M,
+                                                                                 qmap=qtab, cluster_major=True))):
+            for it in range(2):
+                e0.record(stream)
+                fnb()
+                e1.record(stream)
+                torch.cuda.synchronize()
+            msb = e0.elapsed_time(e1)
+            row_b[name] = {"ms": round(msb, 3), "hbm_frac": round(alg_state / msb / 1e6 / HBM_PEAK_GBS, 4)}
+        fn, a = bcalls["quantize_cluster"][1]
+        fn(*a)
+        torch.cuda.synchronize()
+        extras["cluster_format_variants"] = {"elements": nb, "rows": rows_v,
+                                             "batched_first_moment_state_table_map_cluster_major": row_b}
 
         # the one-call-per-tensor step again, captured once in a HIP graph and replayed: what is left of it when
         # the host no longer issues 2328 calls per step

@@ -304,6 +304,15 @@ int bitsnap_quantize_cluster_batched(const bitsnap_cluster_item *items, int64_t 
 int bitsnap_dequantize_cluster_batched(const bitsnap_cluster_item *items, int64_t count, int64_t total_groups,
                                        int64_t group, int m, bitsnap_stream_t stream);
 
+/* The batched cluster calls with the options of bitsnap_quantize_cluster_ex /
+ * bitsnap_dequantize_cluster_ex (flags and qmap apply to every item). */
+int bitsnap_quantize_cluster_batched_ex(const bitsnap_cluster_item *items, int64_t count, int64_t total_groups,
+                                        int64_t group, int m, uint32_t flags, const float *qmap, uint32_t *status,
+                                        bitsnap_stream_t stream);
+int bitsnap_dequantize_cluster_batched_ex(const bitsnap_cluster_item *items, int64_t count, int64_t total_groups,
+                                          int64_t group, int m, uint32_t flags, const float *qmap,
+                                          bitsnap_stream_t stream);
+
 #ifdef __cplusplus
 }
 #endif

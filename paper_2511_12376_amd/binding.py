@@ -25,6 +25,7 @@ SYMBOLS = (
     "bitsnap_cluster_fit_floats", "bitsnap_cluster_workspace_bytes", "bitsnap_cluster_z",
     "bitsnap_quantize_cluster", "bitsnap_dequantize_cluster",
     "bitsnap_quantize_cluster_ex", "bitsnap_dequantize_cluster_ex",
+    "bitsnap_quantize_cluster_batched_ex", "bitsnap_dequantize_cluster_batched_ex",
     "bitsnap_quantize_cluster_batched", "bitsnap_dequantize_cluster_batched",
     "bitsnap_sparse_batch_workspace_bytes", "bitsnap_encode_sparse_batched", "bitsnap_decode_sparse_batched",
 )
@@ -77,6 +78,10 @@ def lib():
     L.bitsnap_cluster_fit_floats.argtypes, L.bitsnap_cluster_fit_floats.restype = [i64, i64, i], sz
     L.bitsnap_cluster_workspace_bytes.argtypes, L.bitsnap_cluster_workspace_bytes.restype = [i64, i64, i], sz
     L.bitsnap_cluster_z.argtypes, L.bitsnap_cluster_z.restype = [i, i], C.c_double
+    L.bitsnap_quantize_cluster_batched_ex.argtypes = [p, i64, i64, i64, i, C.c_uint32, p, p, p]
+    L.bitsnap_quantize_cluster_batched_ex.restype = i
+    L.bitsnap_dequantize_cluster_batched_ex.argtypes = [p, i64, i64, i64, i, C.c_uint32, p, p]
+    L.bitsnap_dequantize_cluster_batched_ex.restype = i
     L.bitsnap_quantize_cluster_ex.argtypes = [p, i64, i64, i, C.c_uint32, p, p, p, p, p, p, p, p]
     L.bitsnap_quantize_cluster_ex.restype = i
     L.bitsnap_dequantize_cluster_ex.argtypes = [p, p, p, i64, i64, i, C.c_uint32, p, p, p]
@@ -385,6 +390,21 @@ def quantize_cluster_batched(items, total_groups: int, group: int, m: int, statu
 def dequantize_cluster_batched(items, total_groups: int, group: int, m: int, stream=None) -> None:
     rc = lib().bitsnap_dequantize_cluster_batched(_ptr(items), items.shape[0], total_groups, group, m, _stream(stream))
     _check(rc, "bitsnap_dequantize_cluster_batched")
+
+
+def quantize_cluster_batched_ex(items, total_groups: int, group: int, m: int, *, qmap=None, cluster_major: bool = False,
+                                status=None, stream=None) -> None:
+    rc = lib().bitsnap_quantize_cluster_batched_ex(_ptr(items), items.shape[0], total_groups, group, m,
+                                                   CLUSTER_MAJOR if cluster_major else 0, _ptr(qmap), _ptr(status),
+                                                   _stream(stream))
+    _check(rc, "bitsnap_quantize_cluster_batched_ex")
+
+
+def dequantize_cluster_batched_ex(items, total_groups: int, group: int, m: int, *, qmap=None, cluster_major: bool = False,
+                                  stream=None) -> None:
+    rc = lib().bitsnap_dequantize_cluster_batched_ex(_ptr(items), items.shape[0], total_groups, group, m,
+                                                     CLUSTER_MAJOR if cluster_major else 0, _ptr(qmap), _stream(stream))
+    _check(rc, "bitsnap_dequantize_cluster_batched_ex")
 
 
 def sparse_batch_workspace_bytes(total_tiles: int) -> int:

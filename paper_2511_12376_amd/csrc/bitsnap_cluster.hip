@@ -16,6 +16,7 @@
 
 #include "../../include/bitsnap.h"
 #include "cluster_general.hpp"
+#include "cluster_items.hpp"
 #include "cluster_wave.hpp"
 #include "host_util.hpp"
 #include "wave.hpp"
@@ -126,21 +127,6 @@ __global__ __launch_bounds__(kQBlock) void dequantize_cluster_kernel(
 // phases overlap; a single tensor of a few thousand groups is one round (one group per wave slot)
 // whose phases cannot overlap.
 // ---------------------------------------------------------------------------------------------
-
-// The item that holds list-wide group gg: the last one whose first_group <= gg (binary search;
-// every operand is wave-uniform, so this runs on the scalar unit).
-__device__ __forceinline__ int64_t find_item(const bitsnap_cluster_item *__restrict__ items, int64_t count, int64_t gg)
-{
-    int64_t lo = 0, hi = count - 1;
-    while (lo < hi) {
-        const int64_t mid = (lo + hi + 1) >> 1;
-        if (items[mid].first_group <= gg)
-            lo = mid;
-        else
-            hi = mid - 1;
-    }
-    return lo;
-}
 
 __device__ __forceinline__ int64_t uniform_i64(int64_t v)
 {

@@ -21,6 +21,7 @@
 
 #include "../../include/bitsnap.h"
 #include "cluster_general.hpp"
+#include "cluster_items.hpp"
 #include "cluster_wave.hpp"
 #include "host_util.hpp"
 #include "wave.hpp"
@@ -506,27 +507,13 @@ __global__ __launch_bounds__(kVBlock, 3) void quantize_cluster_ex_kernel(
     }
 }
 
+// The inverse for one group of len <= 256*K elements, by one wave.
 template <int K, bool kTable, bool kMajor>
-__global__ __launch_bounds__(kVBlock) void dequantize_cluster_ex_kernel(
-    const uint8_t *__restrict__ codes, const uint8_t *__restrict__ labels, const float *__restrict__ params, int64_t n,
-    int64_t groups, int m, const float *__restrict__ qmap, float *__restrict__ out)
+__device__ __forceinline__ void dequantize_group_ex(const uint8_t *__restrict__ codes, const uint8_t *__restrict__ labels,
+                                                    const float *__restrict__ params, int64_t lo, int len, int m, int64_t g,
+                                                    float *__restrict__ out, DequantizeShared &sh, const float *table, int lane)
 {
-    __shared__ DequantizeShared shared[kVWaves];
-    __shared__ float table[kLevels];
-    if (kTable) {
-        table[threadIdx.x] = global_ptr(qmap)[threadIdx.x];  // kVBlock == kLevels
-        __syncthreads();
-    }
-    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
-    const int64_t g = (int64_t)blockIdx.x * kVWaves + wave;
-    if (g >= groups)
-        return;
     constexpr int G = 256 * K;
-    const int64_t lo = g * G;
-    const int64_t rest = n - lo;
-    const int len = rest >= G ? G : (int)rest;
-    DequantizeShared &sh = shared[wave];
-
     uint32_t c4[K], l4[K];
 #pragma unroll
     for (int k = 0; k < K; ++k) {
@@ -592,6 +579,96 @@ __global__ __launch_bounds__(kVBlock) void dequantize_cluster_ex_kernel(
                     global_ptr(out)[lo + off + j] = r[j];
         }
     }
+    wave_lds_sync();  // this wave may go on to another group and rewrite the tables
+}
+
+// The table of the dequantisers: one copy per workgroup (kVBlock == kLevels threads).
+__device__ __forceinline__ void load_levels(float *table, const float *__restrict__ qmap)
+{
+    table[threadIdx.x] = global_ptr(qmap)[threadIdx.x];
+    __syncthreads();
+}
+
+template <int K, bool kTable, bool kMajor>
+__global__ __launch_bounds__(kVBlock) void dequantize_cluster_ex_kernel(
+    const uint8_t *__restrict__ codes, const uint8_t *__restrict__ labels, const float *__restrict__ params, int64_t n,
+    int64_t groups, int m, const float *__restrict__ qmap, float *__restrict__ out)
+{
+    __shared__ DequantizeShared shared[kVWaves];
+    __shared__ float table[kLevels];
+    if (kTable)
+        load_levels(table, qmap);
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
+    const int64_t g = (int64_t)blockIdx.x * kVWaves + wave;
+    if (g >= groups)
+        return;
+    constexpr int G = 256 * K;
+    const int64_t lo = g * G;
+    const int64_t rest = n - lo;
+    dequantize_group_ex<K, kTable, kMajor>(codes, labels, params, lo, rest >= G ? G : (int)rest, m, g, out, shared[wave], table,
+                                           lane);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Batched forms: groups are numbered across the list of tensors as in the plain batched kernels.
+// ---------------------------------------------------------------------------------------------
+template <int K, bool kFull, bool kTable, bool kMajor>
+__global__ __launch_bounds__(kVBlock, 3) void quantize_cluster_ex_batched_kernel(
+    const bitsnap_cluster_item *__restrict__ items, int64_t count, int64_t total_groups, int m,
+    const float *__restrict__ qmap, uint32_t *__restrict__ status)
+{
+    __shared__ QuantizeShared shared[kVWaves];
+    __shared__ TableShared table;
+    if (kTable)
+        load_table(table, qmap);
+    const int lane = threadIdx.x & (kWave - 1), wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    constexpr int G = 256 * K;
+    const int64_t stride = (int64_t)gridDim.x * kVWaves;
+    if (kFull) {
+        for (int64_t gg = (int64_t)blockIdx.x * kVWaves + wave; gg < total_groups; gg += stride) {
+            const bitsnap_cluster_item &it = items[find_item(items, count, gg)];
+            const int64_t g = gg - it.first_group;
+            const int64_t lo = g * G;
+            if (it.n - lo >= G)  // a short last group is left to the tail launch
+                quantize_group_ex<K, true, kTable, kMajor>((const float *)it.values, lo, G, m, g, it.codes, it.labels,
+                                                           it.params, it.fit_out, it.fit_in, status, shared[wave], table,
+                                                           lane);
+        }
+    } else {
+        // one wave per tensor: its short last group, if it has one
+        for (int64_t t = (int64_t)blockIdx.x * kVWaves + wave; t < count; t += stride) {
+            const bitsnap_cluster_item &it = items[t];
+            const int64_t g = it.n / G;
+            const int rest = (int)(it.n - g * G);
+            if (rest > 0)
+                quantize_group_ex<K, false, kTable, kMajor>((const float *)it.values, g * G, rest, m, g, it.codes, it.labels,
+                                                            it.params, it.fit_out, it.fit_in, status, shared[wave], table,
+                                                            lane);
+        }
+    }
+}
+
+template <int K, bool kTable, bool kMajor>
+__global__ __launch_bounds__(kVBlock) void dequantize_cluster_ex_batched_kernel(
+    const bitsnap_cluster_item *__restrict__ items, int64_t count, int64_t total_groups, int m,
+    const float *__restrict__ qmap)
+{
+    __shared__ DequantizeShared shared[kVWaves];
+    __shared__ float table[kLevels];
+    if (kTable)
+        load_levels(table, qmap);
+    const int lane = threadIdx.x & (kWave - 1), wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    constexpr int G = 256 * K;
+    const int64_t gg = (int64_t)blockIdx.x * kVWaves + wave;
+    if (gg >= total_groups)
+        return;
+    const bitsnap_cluster_item &it = items[find_item(items, count, gg)];
+    const int64_t g = gg - it.first_group;
+    const int64_t lo = g * G;
+    const int64_t rest = it.n - lo;
+    if (rest > 0)
+        dequantize_group_ex<K, kTable, kMajor>(it.codes, it.labels, it.params, lo, rest >= G ? G : (int)rest, m, g,
+                                               (float *)it.values, shared[wave], table, lane);
 }
 
 template <int K, bool kTable, bool kMajor>
@@ -709,5 +786,105 @@ extern "C" int bitsnap_dequantize_cluster_ex(const uint8_t *codes, const uint8_t
 #undef BITSNAP_D_TM
 #undef BITSNAP_D_T
 #undef BITSNAP_D_M
+    return launch_status();
+}
+
+static int64_t ex_batched_blocks(int64_t total_groups) { return (total_groups + kVWaves - 1) / kVWaves; }
+
+template <int K, bool kTable, bool kMajor>
+static void launch_quantize_ex_batched(const bitsnap_cluster_item *items, int64_t count, int64_t total_groups, int m,
+                                       const float *qmap, uint32_t *status, hipStream_t s)
+{
+    int64_t blocks = ex_batched_blocks(total_groups), tblocks = (count + kVWaves - 1) / kVWaves;
+    if (kTable) {
+        const void *kernel = (const void *)quantize_cluster_ex_batched_kernel<K, true, kTable, kMajor>;
+        const int64_t resident = (int64_t)device_info().cu_count * occupancy_blocks_per_cu(kernel, kVBlock);
+        blocks = blocks < resident ? blocks : resident;
+        tblocks = tblocks < resident ? tblocks : resident;
+    }
+    hipLaunchKernelGGL((quantize_cluster_ex_batched_kernel<K, true, kTable, kMajor>), dim3((unsigned)blocks), dim3(kVBlock), 0,
+                       s, items, count, total_groups, m, qmap, status);
+    hipLaunchKernelGGL((quantize_cluster_ex_batched_kernel<K, false, kTable, kMajor>), dim3((unsigned)tblocks), dim3(kVBlock),
+                       0, s, items, count, total_groups, m, qmap, status);
+}
+
+template <int K, bool kTable, bool kMajor>
+static void launch_dequantize_ex_batched(const bitsnap_cluster_item *items, int64_t count, int64_t total_groups, int m,
+                                         const float *qmap, hipStream_t s)
+{
+    hipLaunchKernelGGL((dequantize_cluster_ex_batched_kernel<K, kTable, kMajor>), dim3((unsigned)ex_batched_blocks(total_groups)),
+                       dim3(kVBlock), 0, s, items, count, total_groups, m, qmap);
+}
+
+static int check_ex_batched(const bitsnap_cluster_item *items, int64_t count, int64_t total_groups, int64_t group, int m,
+                            uint32_t flags, const float *qmap, const uint32_t *status, int &K)
+{
+    if (count < 0 || total_groups < 0 || m < 1 || m > kMaxClusters || (flags & ~(uint32_t)BITSNAP_CLUSTER_MAJOR))
+        return BITSNAP_E_SIZE;
+    K = one_wave_group_k(group);
+    if (K == 0 || ex_batched_blocks(total_groups) > 0x7FFFFFFF)
+        return BITSNAP_E_SIZE;
+    if (count == 0 || total_groups == 0)
+        return BITSNAP_OK;
+    if (!items)
+        return BITSNAP_E_NULL;
+    if (((uintptr_t)items & 7u) || ((uintptr_t)status & 3u) || ((uintptr_t)qmap & 3u))
+        return BITSNAP_E_ALIGN;
+    return 1;  // go on
+}
+
+extern "C" int bitsnap_quantize_cluster_batched_ex(const bitsnap_cluster_item *items, int64_t count, int64_t total_groups,
+                                                   int64_t group, int m, uint32_t flags, const float *qmap,
+                                                   uint32_t *status, bitsnap_stream_t stream)
+{
+    int K = 0;
+    const int rc = check_ex_batched(items, count, total_groups, group, m, flags, qmap, status, K);
+    if (rc <= 0)
+        return rc;
+    const bool major = (flags & BITSNAP_CLUSTER_MAJOR) != 0;
+    if (!qmap && !major)
+        return bitsnap_quantize_cluster_batched(items, count, total_groups, group, m, status, stream);
+    hipStream_t s = (hipStream_t)stream;
+#define BITSNAP_QB_TM(KK) launch_quantize_ex_batched<KK, true, true>(items, count, total_groups, m, qmap, status, s)
+#define BITSNAP_QB_T(KK) launch_quantize_ex_batched<KK, true, false>(items, count, total_groups, m, qmap, status, s)
+#define BITSNAP_QB_M(KK) launch_quantize_ex_batched<KK, false, true>(items, count, total_groups, m, qmap, status, s)
+    if (qmap && major) {
+        BITSNAP_BY_K(K, BITSNAP_QB_TM)
+    } else if (qmap) {
+        BITSNAP_BY_K(K, BITSNAP_QB_T)
+    } else {
+        BITSNAP_BY_K(K, BITSNAP_QB_M)
+    }
+#undef BITSNAP_QB_TM
+#undef BITSNAP_QB_T
+#undef BITSNAP_QB_M
+    return launch_status();
+}
+
+extern "C" int bitsnap_dequantize_cluster_batched_ex(const bitsnap_cluster_item *items, int64_t count, int64_t total_groups,
+                                                     int64_t group, int m, uint32_t flags, const float *qmap,
+                                                     bitsnap_stream_t stream)
+{
+    int K = 0;
+    const int rc = check_ex_batched(items, count, total_groups, group, m, flags, qmap, nullptr, K);
+    if (rc <= 0)
+        return rc;
+    const bool major = (flags & BITSNAP_CLUSTER_MAJOR) != 0;
+    if (!qmap && !major)
+        return bitsnap_dequantize_cluster_batched(items, count, total_groups, group, m, stream);
+    hipStream_t s = (hipStream_t)stream;
+#define BITSNAP_DB_TM(KK) launch_dequantize_ex_batched<KK, true, true>(items, count, total_groups, m, qmap, s)
+#define BITSNAP_DB_T(KK) launch_dequantize_ex_batched<KK, true, false>(items, count, total_groups, m, qmap, s)
+#define BITSNAP_DB_M(KK) launch_dequantize_ex_batched<KK, false, true>(items, count, total_groups, m, qmap, s)
+    if (qmap && major) {
+        BITSNAP_BY_K(K, BITSNAP_DB_TM)
+    } else if (qmap) {
+        BITSNAP_BY_K(K, BITSNAP_DB_T)
+    } else {
+        BITSNAP_BY_K(K, BITSNAP_DB_M)
+    }
+#undef BITSNAP_DB_TM
+#undef BITSNAP_DB_T
+#undef BITSNAP_DB_M
     return launch_status();
 }

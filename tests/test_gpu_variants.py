@@ -200,3 +200,52 @@ def test_table_codes_exactly_at_the_decision_points(name):
     torch.cuda.synchronize()
     oy = oracle.quantize_cluster_ex(y, 4096, 16, fit_in=to_np(g.fit)[:, :2].copy(), qmap=Q, cluster_major=True)
     assert np.array_equal(to_np(g.codes), oy["codes"])
+
+
+@pytest.mark.parametrize("kind,major", [(None, True), ("normal", False), ("square", True)])
+@pytest.mark.parametrize("G", [256, 4096])
+def test_batched_variants_equal_the_single_tensor_calls(G, kind, major):
+    announce("variants batched", G, kind, major)
+    sizes = [5 * G + 17, 3, G, 40 * G, G - 1, 12 * G + G // 2, 1]
+    xs = [f32_to_dev(_states(100 + i, k)) for i, k in enumerate(sizes)]
+    Q = None if kind is None else synth.qmap_table(kind)
+    Qd = None if Q is None else f32_to_dev(Q)
+    codes = [torch.zeros(k, dtype=torch.uint8, device=DEV) for k in sizes]
+    labels = [torch.zeros((k + 1) // 2, dtype=torch.uint8, device=DEV) for k in sizes]
+    params = [torch.zeros(B.cluster_groups(k, G), 16, 2, dtype=torch.float32, device=DEV) for k in sizes]
+    fits = [torch.zeros(B.cluster_groups(k, G), 17, dtype=torch.float32, device=DEV) for k in sizes]
+    status = torch.zeros(1, dtype=torch.int32, device=DEV)
+    items, groups = B.cluster_items(xs, codes, labels, params, G, fit_out=fits)
+    B.quantize_cluster_batched_ex(items, groups, G, 16, qmap=Qd, cluster_major=major, status=status)
+    outs = [torch.zeros(k, dtype=torch.float32, device=DEV) for k in sizes]
+    ditems, _ = B.cluster_items(outs, codes, labels, params, G)
+    B.dequantize_cluster_batched_ex(ditems, groups, G, 16, qmap=Qd, cluster_major=major)
+    torch.cuda.synchronize()
+    assert int(status.item()) == 0
+    for i, k in enumerate(sizes):
+        one = B.quantize_cluster_ex(xs[i], G, 16, qmap=Qd, cluster_major=major)
+        back = B.dequantize_cluster_ex(one.codes, one.labels, one.params, k, G, 16, qmap=Qd, cluster_major=major)
+        torch.cuda.synchronize()
+        assert torch.equal(codes[i], one.codes) and torch.equal(labels[i], one.labels), (i, k)
+        assert torch.equal(params[i], one.params) and torch.equal(fits[i], one.fit) and torch.equal(outs[i], back), (i, k)
+    # and one of them against the oracle
+    i = 5
+    o = oracle.quantize_cluster_ex(to_np(xs[i]), G, 16, fit_in=to_np(fits[i])[:, :2].copy(), qmap=Q, cluster_major=major)
+    assert np.array_equal(to_np(codes[i]), o["codes"]) and np.array_equal(to_np(labels[i]), o["labels"])
+    assert np.array_equal(to_np(outs[i]), oracle.dequantize_cluster_ex(o["codes"], o["labels"], o["params"], sizes[i], G, 16,
+                                                                        qmap=Q, cluster_major=major))
+
+
+def test_batched_variants_argument_checks():
+    x = f32_to_dev(_states(14, 4096))
+    c = torch.zeros(4096, dtype=torch.uint8, device=DEV)
+    l = torch.zeros(2048, dtype=torch.uint8, device=DEV)
+    p = torch.zeros(1, 16, 2, dtype=torch.float32, device=DEV)
+    items, groups = B.cluster_items([x], [c], [l], [p], 4096)
+    with pytest.raises(B.BitsnapError):
+        B.quantize_cluster_batched_ex(items, groups, 1000, 16, cluster_major=True)
+    with pytest.raises(B.BitsnapError):
+        B.quantize_cluster_batched_ex(items, groups, 4096, 0, cluster_major=True)
+    rc = B.lib().bitsnap_dequantize_cluster_batched_ex(items.data_ptr(), 1, groups, 4096, 16, 4, None, None)
+    assert rc != 0                                                   # unknown flag
+    torch.cuda.synchronize()
