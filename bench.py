@@ -352,6 +352,26 @@ def main():
                 row[name] = {"ms": round(msv, 4), "hbm_frac": round(valg / msv / 1e6 / HBM_PEAK_GBS, 4)}
             rows_v[label] = row
             del qv, ov
+        # the paper's own formulation on the same tensor: one fit and one cluster-major arrangement for the whole tensor
+        wsz = B.cluster_workspace_bytes_ex(nb, 0, M, B.CLUSTER_MAJOR)
+        wsv = torch.zeros(wsz, dtype=u8, device=dev)
+        qv = B.quantize_cluster_ex(xq, 0, M, qmap=qtab, cluster_major=True)
+        ov = torch.empty(nb, dtype=torch.float32, device=dev)
+        row = {}
+        for name, fnv in (("quantize", lambda: B.quantize_cluster_ex_raw(xq, nb, 0, M, B.CLUSTER_MAJOR, qtab, qv.codes, qv.labels,
+                                                                         qv.params, None, None, qv.status, wsv)),
+                          ("dequantize", lambda: B.dequantize_cluster_ex_raw(qv.codes, qv.labels, qv.params, nb, 0, M,
+                                                                             B.CLUSTER_MAJOR, qtab, ov, wsv))):
+            for it in range(2):
+                e0.record(stream)
+                for _ in range(3):
+                    fnv()
+                e1.record(stream)
+                torch.cuda.synchronize()
+            row[name] = {"ms": round(e0.elapsed_time(e1) / 3, 4)}
+        rows_v["table map, cluster-major codes, one group per tensor"] = row
+        del qv, ov, wsv
+
         # and over the whole first-moment state in one batched launch (table map + cluster-major codes); the plain
         # batched call afterwards restores that state's element-order codes
         alg_state = 5 * n_total + sum((n + 1) // 2 for n in sizes) + total_groups * M * 8

@@ -213,7 +213,7 @@ int bitsnap_dequantize_cluster(const uint8_t *codes, const uint8_t *labels, cons
                                bitsnap_stream_t stream);
 
 /* ------------------------------------------------------------------------------------------
- * Format variants of the cluster pair (group must be one of 256, 512, 1024, 2048, 4096).
+ * Format variants of the cluster pair.
  *
  * qmap   nullable, DEVICE [256] fp32, 4-byte aligned: the map Q^map of Eq. qmap-distance as a
  *        table.  It must be non-decreasing (its contents cannot be checked on the host; with any
@@ -228,17 +228,25 @@ int bitsnap_dequantize_cluster(const uint8_t *codes, const uint8_t *labels, cons
  *        of Eq. decluster, which dequantisation undoes through the labels (V_j = T_{C_i k} with
  *        i = L_j, k = the number of earlier elements of the group with label i).  Labels stay in
  *        element order; params, fit and status are those of bitsnap_quantize_cluster.
+ * group  as in the plain calls: 0 = the whole tensor is one group (the paper's formulation:
+ *        one fit, and with BITSNAP_CLUSTER_MAJOR one cluster-major arrangement, per tensor).
+ * workspace  [bitsnap_cluster_workspace_bytes_ex(n, group, m, flags)] bytes, 16-byte aligned;
+ *        may be NULL when that is 0 (the group lengths 256 .. 4096).  Dequantisation uses it only
+ *        with BITSNAP_CLUSTER_MAJOR, where it needs n < 2^32 (as does quantisation).
  * With qmap == NULL and flags == 0 these are the plain entry points.
  * ---------------------------------------------------------------------------------------- */
 #define BITSNAP_CLUSTER_MAJOR 1u
 
+size_t bitsnap_cluster_workspace_bytes_ex(int64_t n, int64_t group, int m, uint32_t flags);
+
 int bitsnap_quantize_cluster_ex(const float *x, int64_t n, int64_t group, int m, uint32_t flags,
                                 const float *qmap, uint8_t *codes, uint8_t *labels, float *params,
-                                float *fit_out, const float *fit_in, uint32_t *status,
-                                bitsnap_stream_t stream);
+                                float *fit_out, const float *fit_in, uint32_t *status, void *workspace,
+                                size_t workspace_bytes, bitsnap_stream_t stream);
 int bitsnap_dequantize_cluster_ex(const uint8_t *codes, const uint8_t *labels, const float *params,
                                   int64_t n, int64_t group, int m, uint32_t flags, const float *qmap,
-                                  float *out, bitsnap_stream_t stream);
+                                  float *out, void *workspace, size_t workspace_bytes,
+                                  bitsnap_stream_t stream);
 
 /* ------------------------------------------------------------------------------------------
  * Batched forms: one launch for a whole list of tensors.  The paper compresses an entire
@@ -305,7 +313,7 @@ int bitsnap_dequantize_cluster_batched(const bitsnap_cluster_item *items, int64_
                                        int64_t group, int m, bitsnap_stream_t stream);
 
 /* The batched cluster calls with the options of bitsnap_quantize_cluster_ex /
- * bitsnap_dequantize_cluster_ex (flags and qmap apply to every item). */
+ * bitsnap_dequantize_cluster_ex (flags and qmap apply to every item; group one of 256 .. 4096). */
 int bitsnap_quantize_cluster_batched_ex(const bitsnap_cluster_item *items, int64_t count, int64_t total_groups,
                                         int64_t group, int m, uint32_t flags, const float *qmap, uint32_t *status,
                                         bitsnap_stream_t stream);

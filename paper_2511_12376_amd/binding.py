@@ -24,7 +24,7 @@ SYMBOLS = (
     "bitsnap_cluster_groups", "bitsnap_cluster_param_bytes", "bitsnap_cluster_label_bytes",
     "bitsnap_cluster_fit_floats", "bitsnap_cluster_workspace_bytes", "bitsnap_cluster_z",
     "bitsnap_quantize_cluster", "bitsnap_dequantize_cluster",
-    "bitsnap_quantize_cluster_ex", "bitsnap_dequantize_cluster_ex",
+    "bitsnap_quantize_cluster_ex", "bitsnap_dequantize_cluster_ex", "bitsnap_cluster_workspace_bytes_ex",
     "bitsnap_quantize_cluster_batched_ex", "bitsnap_dequantize_cluster_batched_ex",
     "bitsnap_quantize_cluster_batched", "bitsnap_dequantize_cluster_batched",
     "bitsnap_sparse_batch_workspace_bytes", "bitsnap_encode_sparse_batched", "bitsnap_decode_sparse_batched",
@@ -82,10 +82,12 @@ def lib():
     L.bitsnap_quantize_cluster_batched_ex.restype = i
     L.bitsnap_dequantize_cluster_batched_ex.argtypes = [p, i64, i64, i64, i, C.c_uint32, p, p]
     L.bitsnap_dequantize_cluster_batched_ex.restype = i
-    L.bitsnap_quantize_cluster_ex.argtypes = [p, i64, i64, i, C.c_uint32, p, p, p, p, p, p, p, p]
+    L.bitsnap_quantize_cluster_ex.argtypes = [p, i64, i64, i, C.c_uint32, p, p, p, p, p, p, p, p, sz, p]
     L.bitsnap_quantize_cluster_ex.restype = i
-    L.bitsnap_dequantize_cluster_ex.argtypes = [p, p, p, i64, i64, i, C.c_uint32, p, p, p]
+    L.bitsnap_dequantize_cluster_ex.argtypes = [p, p, p, i64, i64, i, C.c_uint32, p, p, p, sz, p]
     L.bitsnap_dequantize_cluster_ex.restype = i
+    L.bitsnap_cluster_workspace_bytes_ex.argtypes = [i64, i64, i, C.c_uint32]
+    L.bitsnap_cluster_workspace_bytes_ex.restype = sz
     L.bitsnap_quantize_cluster.argtypes = [p, i64, i64, i, p, p, p, p, p, p, p, sz, p]
     L.bitsnap_quantize_cluster.restype = i
     L.bitsnap_dequantize_cluster.argtypes = [p, p, p, i64, i64, i, p, p]
@@ -238,17 +240,24 @@ def dequantize_cluster_raw(codes, labels, params, n: int, group: int, m: int, ou
     _check(rc, "bitsnap_dequantize_cluster")
 
 
+def cluster_workspace_bytes_ex(n: int, group: int, m: int, flags: int) -> int:
+    return lib().bitsnap_cluster_workspace_bytes_ex(n, group, m, flags)
+
+
 def quantize_cluster_ex_raw(x, n: int, group: int, m: int, flags: int, qmap, codes, labels, params, fit_out=None,
-                            fit_in=None, status=None, stream=None) -> None:
+                            fit_in=None, status=None, workspace=None, stream=None) -> None:
+    wb = 0 if workspace is None else workspace.numel() * workspace.element_size()
     rc = lib().bitsnap_quantize_cluster_ex(_ptr(x), n, group, m, flags, _ptr(qmap), _ptr(codes), _ptr(labels),
-                                           _ptr(params), _ptr(fit_out), _ptr(fit_in), _ptr(status), _stream(stream))
+                                           _ptr(params), _ptr(fit_out), _ptr(fit_in), _ptr(status), _ptr(workspace), wb,
+                                           _stream(stream))
     _check(rc, "bitsnap_quantize_cluster_ex")
 
 
 def dequantize_cluster_ex_raw(codes, labels, params, n: int, group: int, m: int, flags: int, qmap, out,
-                              stream=None) -> None:
+                              workspace=None, stream=None) -> None:
+    wb = 0 if workspace is None else workspace.numel() * workspace.element_size()
     rc = lib().bitsnap_dequantize_cluster_ex(_ptr(codes), _ptr(labels), _ptr(params), n, group, m, flags, _ptr(qmap),
-                                             _ptr(out), _stream(stream))
+                                             _ptr(out), _ptr(workspace), wb, _stream(stream))
     _check(rc, "bitsnap_dequantize_cluster_ex")
 
 
@@ -340,17 +349,24 @@ def quantize_cluster_ex(x, group: int = 4096, m: int = 16, *, qmap=None, cluster
     params = torch.empty((max(g, 1), m, 2), dtype=torch.float32, device=dev)[:g]
     fit = torch.empty((max(g, 1), m + 1), dtype=torch.float32, device=dev)[:g] if want_fit else None
     status = torch.zeros(1, dtype=torch.int32, device=dev)
-    quantize_cluster_ex_raw(xf, n, group, m, CLUSTER_MAJOR if cluster_major else 0, qmap, codes, labels, params, fit,
-                            fit_in, status, stream)
-    return SimpleNamespace(codes=codes, labels=labels, params=params, fit=fit, status=status, n=n, group=group, m=m)
+    flags = CLUSTER_MAJOR if cluster_major else 0
+    wsb = cluster_workspace_bytes_ex(n, group, m, flags)
+    ws = torch.zeros(wsb, dtype=torch.uint8, device=dev) if wsb else None
+    quantize_cluster_ex_raw(xf, n, group, m, flags, qmap, codes, labels, params, fit, fit_in, status, ws, stream)
+    return SimpleNamespace(codes=codes, labels=labels, params=params, fit=fit, status=status, n=n, group=group, m=m,
+                           workspace=ws)
 
 
 def dequantize_cluster_ex(codes, labels, params, n: int, group: int = 4096, m: int = 16, *, qmap=None,
-                          cluster_major: bool = False, out=None, stream=None):
+                          cluster_major: bool = False, out=None, workspace=None, stream=None):
     import torch
     if out is None:
         out = torch.empty(max(n, 1), dtype=torch.float32, device=codes.device)[:n]
-    dequantize_cluster_ex_raw(codes, labels, params, n, group, m, CLUSTER_MAJOR if cluster_major else 0, qmap, out, stream)
+    flags = CLUSTER_MAJOR if cluster_major else 0
+    if workspace is None:
+        wsb = cluster_workspace_bytes_ex(n, group, m, flags)
+        workspace = torch.zeros(wsb, dtype=torch.uint8, device=codes.device) if wsb else None
+    dequantize_cluster_ex_raw(codes, labels, params, n, group, m, flags, qmap, out, workspace, stream)
     return out
 
 

@@ -11,12 +11,22 @@
 // x is read three times and 1.5 bytes per element are written: 13.5 bytes per element.  Chunk
 // results are written out and combined in chunk order, so nothing depends on the order in which
 // the waves run.
+//
+// Format variants (a table for Q^map, cluster-major codes; see cluster_variants.hpp).  The table
+// only changes how pass 3 turns (x-b)/S into a code.  Cluster-major codes of a wide group are a
+// stable 16-way partition across all its chunks: pass 2 also leaves the number of members of
+// every cluster per chunk, the two reduction levels turn these into exclusive prefix sums
+// (chunk within slice, slice within group, cluster within group), and pass 3 partitions its
+// chunk inside the wave and copies each cluster's run of codes to
+//   group start + cluster base + slice base + chunk offset.
+// Dequantisation rebuilds the same sums from the stored labels and collects the runs again.
 #include <hip/hip_runtime.h>
 #include <math.h>
 #include <stdint.h>
 
 #include "../../include/bitsnap.h"
 #include "cluster_general.hpp"
+#include "cluster_variants.hpp"
 #include "cluster_wave.hpp"
 #include "host_util.hpp"
 #include "wave.hpp"
@@ -39,6 +49,10 @@ struct ChunkStats {  // one per chunk, in the workspace
 
 struct ChunkRanges {  // one per chunk, in the workspace
     float mn[kMaxClusters], mx[kMaxClusters];
+};
+
+struct ChunkCounts {  // one per chunk, per slice and per group, in the workspace (cluster-major codes only)
+    uint32_t cnt[kMaxClusters];
 };
 
 struct ChunkRef {
@@ -195,10 +209,38 @@ __global__ __launch_bounds__(kGBlock) void wide_fit_kernel(int64_t n, int64_t G,
     }
 }
 
+// Members of every cluster among the wave's elements: lane c < 16 (every lane with lane % 16 == c)
+// returns the count of cluster c.  label(k, j) = the label of element k*256 + lane*4 + j;
+// `counters` is a [16][64] LDS table, one private column per lane.
+template <int K, bool kFull, typename Label>
+__device__ __forceinline__ uint32_t wave_label_counts(Label label, int len, int lane, uint32_t *counters)
+{
+#pragma unroll
+    for (int c = 0; c < kMaxClusters; ++c)
+        counters[c * kWave + lane] = 0;
+#pragma unroll
+    for (int k = 0; k < K; ++k)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            if (kFull || k * 256 + lane * 4 + j < len)
+                lds_fetch_add(&counters[label(k, j) * kWave + lane], 1u);
+    wave_lds_sync();
+    const int row = lane & 15, quarter = lane >> 4;
+    uint32_t v = 0;
+#pragma unroll
+    for (int j = 0; j < 16; ++j)
+        v += counters[row * kWave + quarter * 16 + ((j + lane) & 15)];
+    v += (uint32_t)__shfl_xor((int)v, 16, kWave);
+    v += (uint32_t)__shfl_xor((int)v, 32, kWave);
+    wave_lds_sync();
+    return v;
+}
+
 // ---- pass 2
-template <bool kFull>
+template <bool kFull, bool kCounts>
 __device__ __forceinline__ void chunk_ranges(const float *__restrict__ x, const ChunkRef &r, int m, float mu, float sigma,
-                                             WaveShared &ws, int lane, float &mn, float &mx)
+                                             WaveShared &ws, uint32_t *counters, int lane, float &mn, float &mx,
+                                             uint32_t &count)
 {
     float4 v[kGK];
     load_elements<kGK, kFull>(x, r.lo, r.len, lane, v);
@@ -209,30 +251,40 @@ __device__ __forceinline__ void chunk_ranges(const float *__restrict__ x, const 
     label_pass<kGK, kFull, false, true>(v, r.lo, r.len, ls, ws, lane, nullptr, packed);
     reduce_ranges(ws, lane, mn, mx);
     wave_lds_sync();
+    if (kCounts)
+        count = wave_label_counts<kGK, kFull>(
+            [&](int k, int j) { return (packed[k >> 1] >> (16 * (k & 1) + 4 * j)) & 15u; }, r.len, lane, counters);
 }
 
+template <bool kCounts>
 __global__ __launch_bounds__(kGBlock) void wide_range_kernel(const float *__restrict__ x, int64_t n, int64_t G,
                                                              int64_t chunks_per_group, int64_t chunks, int m,
                                                              const GroupState *__restrict__ gs,
-                                                             ChunkRanges *__restrict__ ranges)
+                                                             ChunkRanges *__restrict__ ranges,
+                                                             ChunkCounts *__restrict__ counts)
 {
     __shared__ WaveShared shared[kGWaves];
+    __shared__ uint32_t counters[kCounts ? kGWaves : 1][kMaxClusters * kWave];
     const int lane = threadIdx.x & (kWave - 1), wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int64_t c = (int64_t)blockIdx.x * kGWaves + wave;
     if (c >= chunks)
         return;
     const ChunkRef r = chunk_ref(c, n, G, chunks_per_group);
     float mn = INFINITY, mx = -INFINITY;
+    uint32_t count = 0;
     if (r.len > 0) {
         const float mu = gs[r.group].mu, sigma = gs[r.group].sigma;
+        uint32_t *col = counters[kCounts ? wave : 0];
         if (chunk_is_full(r))
-            chunk_ranges<true>(x, r, m, mu, sigma, shared[wave], lane, mn, mx);
+            chunk_ranges<true, kCounts>(x, r, m, mu, sigma, shared[wave], col, lane, mn, mx, count);
         else
-            chunk_ranges<false>(x, r, m, mu, sigma, shared[wave], lane, mn, mx);
+            chunk_ranges<false, kCounts>(x, r, m, mu, sigma, shared[wave], col, lane, mn, mx, count);
     }
     if (lane < kMaxClusters) {
         ranges[c].mn[lane] = mn;
         ranges[c].mx[lane] = mx;
+        if (kCounts)
+            counts[c].cnt[lane] = count;
     }
 }
 
@@ -263,11 +315,78 @@ __device__ __forceinline__ void reduce_range_rows(const float *__restrict__ rows
     __syncthreads();
 }
 
+// The per-chunk member counts of one slice (thread t holds chunk t of `cnt` chunks) become, in
+// place, the members in earlier chunks of the slice; *total receives the slice's own counts.
+// Called by a whole workgroup.
+__device__ __forceinline__ void slice_counts_scan(ChunkCounts *__restrict__ chunk, int64_t cnt, ChunkCounts *__restrict__ total)
+{
+    __shared__ uint32_t wave_total[kGWaves][kMaxClusters];
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
+    const bool have = (int64_t)threadIdx.x < cnt;
+    uint32_t v[kMaxClusters], inc[kMaxClusters];
+#pragma unroll
+    for (int c = 0; c < kMaxClusters; ++c) {
+        v[c] = have ? chunk[threadIdx.x].cnt[c] : 0u;
+        inc[c] = wave_inclusive_add(v[c]);
+        if (lane == kWave - 1)
+            wave_total[wave][c] = inc[c];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int c = 0; c < kMaxClusters; ++c) {
+        uint32_t before = 0;
+        for (int w = 0; w < wave; ++w)
+            before += wave_total[w][c];
+        if (have)
+            chunk[threadIdx.x].cnt[c] = before + inc[c] - v[c];
+        if (threadIdx.x == kGBlock - 1)
+            total->cnt[c] = before + inc[c];
+    }
+}
+
+// The per-slice member counts of one group (`nsl` slices) become, in place, the members in
+// earlier slices; *base receives, per cluster, the members of all lower clusters of the group.
+// Called by a whole workgroup; thread t works on cluster t % 16 and on every 16th slice.
+__device__ __forceinline__ void group_counts_scan(ChunkCounts *__restrict__ slice, int64_t nsl, ChunkCounts *__restrict__ base)
+{
+    __shared__ uint32_t tile[16][kMaxClusters];
+    __shared__ uint32_t running[kMaxClusters];
+    const int c = threadIdx.x & 15, s = threadIdx.x >> 4;
+    if (threadIdx.x < kMaxClusters)
+        running[threadIdx.x] = 0;
+    __syncthreads();
+    for (int64_t sl0 = 0; sl0 < nsl; sl0 += 16) {
+        const int64_t sl = sl0 + s;
+        const uint32_t v = sl < nsl ? slice[sl].cnt[c] : 0u;
+        tile[s][c] = v;
+        __syncthreads();
+        uint32_t before = running[c];
+        for (int k = 0; k < s; ++k)
+            before += tile[k][c];
+        if (sl < nsl)
+            slice[sl].cnt[c] = before;
+        __syncthreads();
+        if (s == 15)
+            running[c] = before + v;
+        __syncthreads();
+    }
+    if (threadIdx.x < kMaxClusters) {
+        uint32_t lower = 0;
+        for (int k = 0; k < (int)threadIdx.x; ++k)
+            lower += running[k];
+        base->cnt[threadIdx.x] = lower;
+    }
+    __syncthreads();
+}
+
 // grid: groups * slices_per_group workgroups, each over the (up to) 256 chunks of its slice
-__global__ __launch_bounds__(kGBlock) void wide_slice_ranges_kernel(int64_t n, int64_t G, int64_t chunks_per_group,
-                                                                    int64_t slices_per_group, int64_t groups,
-                                                                    const ChunkRanges *__restrict__ ranges,
-                                                                    ChunkRanges *__restrict__ slice_ranges)
+template <bool kRanges, bool kCounts>
+__global__ __launch_bounds__(kGBlock) void wide_slice_kernel(int64_t n, int64_t G, int64_t chunks_per_group,
+                                                             int64_t slices_per_group, int64_t groups,
+                                                             const ChunkRanges *__restrict__ ranges,
+                                                             ChunkRanges *__restrict__ slice_ranges,
+                                                             ChunkCounts *__restrict__ counts,
+                                                             ChunkCounts *__restrict__ slice_counts)
 {
     __shared__ float part[kGBlock];
     const int64_t g = blockIdx.x / slices_per_group, sl = blockIdx.x % slices_per_group;
@@ -278,16 +397,24 @@ __global__ __launch_bounds__(kGBlock) void wide_slice_ranges_kernel(int64_t n, i
     const int64_t nch = (g_len + kGChunk - 1) / kGChunk;
     const int64_t c0 = sl * kGSlice;
     const int64_t cnt = c0 >= nch ? 0 : (nch - c0 < kGSlice ? nch - c0 : kGSlice);
-    reduce_range_rows(reinterpret_cast<const float *>(ranges + g * chunks_per_group + c0), cnt, part);
-    if (threadIdx.x < 32)
-        reinterpret_cast<float *>(slice_ranges + g * slices_per_group + sl)[threadIdx.x] = part[threadIdx.x];
+    if (kRanges) {
+        reduce_range_rows(reinterpret_cast<const float *>(ranges + g * chunks_per_group + c0), cnt, part);
+        if (threadIdx.x < 32)
+            reinterpret_cast<float *>(slice_ranges + g * slices_per_group + sl)[threadIdx.x] = part[threadIdx.x];
+    }
+    if (kCounts)
+        slice_counts_scan(counts + g * chunks_per_group + c0, cnt, slice_counts + g * slices_per_group + sl);
 }
 
-// One workgroup per group: slices -> min / max of every cluster -> (S, b), 255/S (Algorithm 2 step 4).
-__global__ __launch_bounds__(kGBlock) void wide_params_kernel(int64_t n, int64_t G, int64_t slices_per_group,
-                                                              int64_t groups, int m,
-                                                              const ChunkRanges *__restrict__ slice_ranges, GroupState *gs,
-                                                              float *__restrict__ params)
+// One workgroup per group: slices -> min / max of every cluster -> (S, b), 255/S (Algorithm 2 step 4);
+// with kCounts also the slices' and clusters' places in the cluster-major arrangement.
+template <bool kRanges, bool kCounts>
+__global__ __launch_bounds__(kGBlock) void wide_group_kernel(int64_t n, int64_t G, int64_t slices_per_group,
+                                                             int64_t groups, int m,
+                                                             const ChunkRanges *__restrict__ slice_ranges, GroupState *gs,
+                                                             float *__restrict__ params,
+                                                             ChunkCounts *__restrict__ slice_counts,
+                                                             ChunkCounts *__restrict__ cluster_base)
 {
     __shared__ float part[kGBlock];
     for (int64_t g = blockIdx.x; g < groups; g += gridDim.x) {
@@ -295,14 +422,18 @@ __global__ __launch_bounds__(kGBlock) void wide_params_kernel(int64_t n, int64_t
         const int64_t g_len = (g_lo + G <= n) ? G : (n - g_lo);
         const int64_t nch = (g_len + kGChunk - 1) / kGChunk;
         const int64_t nsl = (nch + kGSlice - 1) / kGSlice;
-        reduce_range_rows(reinterpret_cast<const float *>(slice_ranges + g * slices_per_group), nsl, part);
-        if (threadIdx.x < kMaxClusters) {
-            float S, b, inv;
-            cluster_coder(part[threadIdx.x], part[kMaxClusters + threadIdx.x], S, b, inv);
-            gs[g].coder[threadIdx.x] = make_float2(b, inv);
-            if ((int)threadIdx.x < m)
-                *reinterpret_cast<float2 *>(params + (g * m + threadIdx.x) * 2) = make_float2(S, b);
+        if (kRanges) {
+            reduce_range_rows(reinterpret_cast<const float *>(slice_ranges + g * slices_per_group), nsl, part);
+            if (threadIdx.x < kMaxClusters) {
+                float S, b, inv;
+                cluster_coder(part[threadIdx.x], part[kMaxClusters + threadIdx.x], S, b, inv);
+                gs[g].coder[threadIdx.x] = make_float2(b, inv);
+                if ((int)threadIdx.x < m)
+                    *reinterpret_cast<float2 *>(params + (g * m + threadIdx.x) * 2) = make_float2(S, b);
+            }
         }
+        if (kCounts)
+            group_counts_scan(slice_counts + g * slices_per_group, nsl, cluster_base + g);
     }
 }
 
@@ -359,6 +490,275 @@ __global__ __launch_bounds__(kGBlock) void wide_dequantize_kernel(const uint8_t 
     dequantize_group<kGK>(codes, labels, params, r.lo, r.len, (r.lo & 3) == 0, m, r.group, out, coder[wave], lane);
 }
 
+// ---- format variants: pass 3 and the dequantiser with a table and / or cluster-major codes
+
+// Where the chunk's run of cluster `lane` (< 16) starts, relative to the group's first code.
+__device__ __forceinline__ uint32_t segment_dest(const ChunkCounts *__restrict__ counts,
+                                                 const ChunkCounts *__restrict__ slice_counts,
+                                                 const ChunkCounts *__restrict__ cluster_base, int64_t c, int64_t group,
+                                                 int64_t chunks_per_group, int64_t slices_per_group, int lane)
+{
+    if (lane >= kMaxClusters)
+        return 0;
+    const int64_t sl = (c % chunks_per_group) / kGSlice;
+    return cluster_base[group].cnt[lane] + slice_counts[group * slices_per_group + sl].cnt[lane] + counts[c].cnt[lane];
+}
+
+template <bool kFull, bool kTable, bool kMajor>
+__device__ __forceinline__ void chunk_codes_ex(const float *__restrict__ x, const ChunkRef &r, int m, const GroupState &st,
+                                               const float *__restrict__ params, int64_t g_lo, int64_t g_len, uint32_t dest,
+                                               QuantizeShared &sh, const TableShared &table, int lane,
+                                               uint8_t *__restrict__ labels, uint8_t *__restrict__ codes)
+{
+    WaveShared &ws = sh.ws;
+    float4 v[kGK];
+    load_elements<kGK, kFull>(x, r.lo, r.len, lane, v);
+    if (lane < kMaxClusters) {
+        float2 coder = st.coder[lane];  // (b, 255/S)
+        if (kTable) {
+            // (b, 1/S) from the stored S, with the same rule for a range that cannot be coded
+            const float S = lane < m ? global_ptr(params)[(r.group * m + lane) * 2] : 0.0f;
+            float inv = S > 0.0f ? __fdiv_rn(1.0f, S) : 0.0f;
+            if (!isfinite(inv))
+                inv = 0.0f;
+            coder.y = inv;
+        }
+        ws.coder[lane] = coder;
+    }
+    float edge;
+    const LabelSearch ls = build_search(st.mu, st.sigma, m, ws, lane, edge);
+    uint32_t packed[(kGK + 1) / 2];
+    label_pass<kGK, kFull, true, false>(v, r.lo, r.len, ls, ws, lane, labels, packed);
+    uint32_t c4[kGK];
+    codes_to_registers<kGK, kTable>(v, packed, ws, table, c4);
+    if (!kMajor) {
+        store_codes<kGK, kFull>(c4, r.lo, r.len, lane, codes);
+        wave_lds_sync();
+        return;
+    }
+    MajorView mv;
+    mv.counters = (uint32_t *)&ws.tab[0][0];
+    mv.bytes = (uint32_t *)&ws.tab[kMaxClusters][0];
+    mv.labels = sh.labels;
+    uint16_t *l16 = (uint16_t *)mv.labels;
+#pragma unroll
+    for (int k = 0; k < kGK; ++k) {
+        mv.bytes[k * kWave + lane] = c4[k];
+        l16[k * kWave + lane] = (uint16_t)(packed[k >> 1] >> (16 * (k & 1)));
+    }
+    wave_lds_sync();
+    uint32_t start;
+    to_cluster_major<kGK, kFull>(mv, r.len, lane, start);
+    // every cluster's run of the chunk goes to its place in the group's arrangement
+    const uint8_t *b8 = (const uint8_t *)mv.bytes;
+#pragma unroll
+    for (int cl = 0; cl < kMaxClusters; ++cl) {
+        const uint32_t s0 = read_lane(start, cl), s1 = read_lane(start, cl + 1);  // lane 16 holds len
+        const uint32_t d = read_lane(dest, cl);
+        for (uint32_t i = (uint32_t)lane; i < s1 - s0; i += kWave)
+            if ((int64_t)d + i < g_len)  // holds whenever the counts are consistent; keeps any store inside the group
+                global_ptr(codes)[g_lo + d + i] = b8[s0 + i];
+    }
+    wave_lds_sync();
+}
+
+template <bool kTable, bool kMajor>
+__global__ __launch_bounds__(kGBlock, 3) void wide_code_ex_kernel(
+    const float *__restrict__ x, int64_t n, int64_t G, int64_t chunks_per_group, int64_t slices_per_group, int64_t chunks,
+    int m, const GroupState *__restrict__ gs, const float *__restrict__ params, const float *__restrict__ qmap,
+    const ChunkCounts *__restrict__ counts, const ChunkCounts *__restrict__ slice_counts,
+    const ChunkCounts *__restrict__ cluster_base, uint8_t *__restrict__ labels, uint8_t *__restrict__ codes)
+{
+    __shared__ QuantizeShared shared[kGWaves];
+    __shared__ TableShared table;
+    if (kTable)
+        load_table(table, qmap);
+    // no workgroup barrier from here on
+    const int lane = threadIdx.x & (kWave - 1), wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    for (int64_t c = (int64_t)blockIdx.x * kGWaves + wave; c < chunks; c += (int64_t)gridDim.x * kGWaves) {
+        const ChunkRef r = chunk_ref(c, n, G, chunks_per_group);
+        if (r.len == 0)
+            continue;
+        const int64_t g_lo = r.group * G;
+        const int64_t g_len = (g_lo + G <= n) ? G : (n - g_lo);
+        const uint32_t dest =
+            kMajor ? segment_dest(counts, slice_counts, cluster_base, c, r.group, chunks_per_group, slices_per_group, lane) : 0u;
+        if (chunk_is_full(r))
+            chunk_codes_ex<true, kTable, kMajor>(x, r, m, gs[r.group], params, g_lo, g_len, dest, shared[wave], table, lane,
+                                                 labels, codes);
+        else
+            chunk_codes_ex<false, kTable, kMajor>(x, r, m, gs[r.group], params, g_lo, g_len, dest, shared[wave], table, lane,
+                                                  labels, codes);
+    }
+}
+
+// Labels of a chunk as stored (two per byte), four per float4 position: l4[k] = elements
+// k*256 + lane*4 .. + 3.  `aligned`: the chunk starts at a multiple of 4 elements.
+__device__ __forceinline__ void load_chunk_labels(const uint8_t *__restrict__ labels, int64_t lo, int len, bool aligned,
+                                                  int lane, uint32_t (&l4)[kGK])
+{
+#pragma unroll
+    for (int k = 0; k < kGK; ++k) {
+        const int off = k * 256 + lane * 4;
+        l4[k] = 0;
+        if (aligned && off + 3 < len) {
+            l4[k] = __builtin_nontemporal_load((const BITSNAP_GLOBAL uint16_t *)(global_ptr(labels) + ((lo + off) >> 1)));
+        } else {
+            for (int j = 0; j < 4; ++j)
+                if (off + j < len)
+                    l4[k] |= (uint32_t)((global_ptr(labels)[(lo + off + j) >> 1] >> (4 * ((lo + off + j) & 1))) & 15u) << (4 * j);
+        }
+    }
+}
+
+// Dequantisation of cluster-major codes, first pass: members of every cluster per chunk, from the labels.
+__global__ __launch_bounds__(kGBlock) void wide_label_counts_kernel(const uint8_t *__restrict__ labels, int64_t n, int64_t G,
+                                                                    int64_t chunks_per_group, int64_t chunks,
+                                                                    ChunkCounts *__restrict__ counts)
+{
+    __shared__ uint32_t counters[kGWaves][kMaxClusters * kWave];
+    const int lane = threadIdx.x & (kWave - 1), wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int64_t c = (int64_t)blockIdx.x * kGWaves + wave;
+    if (c >= chunks)
+        return;
+    const ChunkRef r = chunk_ref(c, n, G, chunks_per_group);
+    uint32_t count = 0;
+    if (r.len > 0) {
+        uint32_t l4[kGK];
+        load_chunk_labels(labels, r.lo, r.len, (r.lo & 3) == 0, lane, l4);
+        count = wave_label_counts<kGK, false>([&](int k, int j) { return (l4[k] >> (4 * j)) & 15u; }, r.len, lane,
+                                              counters[wave]);
+    }
+    if (lane < kMaxClusters)
+        counts[c].cnt[lane] = count;
+}
+
+template <bool kTable, bool kMajor>
+__global__ __launch_bounds__(kGBlock, 2) void wide_dequantize_ex_kernel(
+    const uint8_t *__restrict__ codes, const uint8_t *__restrict__ labels, const float *__restrict__ params, int64_t n,
+    int64_t G, int64_t chunks_per_group, int64_t slices_per_group, int64_t chunks, int m, const float *__restrict__ qmap,
+    const ChunkCounts *__restrict__ counts, const ChunkCounts *__restrict__ slice_counts,
+    const ChunkCounts *__restrict__ cluster_base, float *__restrict__ out)
+{
+    __shared__ DequantizeShared shared[kGWaves];
+    __shared__ float table[kLevels];
+    if (kTable)
+        load_levels(table, qmap);
+    const int lane = threadIdx.x & (kWave - 1), wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int64_t c = (int64_t)blockIdx.x * kGWaves + wave;
+    if (c >= chunks)
+        return;
+    const ChunkRef r = chunk_ref(c, n, G, chunks_per_group);
+    if (r.len == 0)
+        return;
+    DequantizeShared &sh = shared[wave];
+    const bool aligned = (r.lo & 3) == 0;
+    const int64_t g_lo = r.group * G;
+    const int64_t g_len = (g_lo + G <= n) ? G : (n - g_lo);
+    uint32_t c4[kGK], l4[kGK];
+    load_chunk_labels(labels, r.lo, r.len, aligned, lane, l4);
+    if (!kMajor) {
+#pragma unroll
+        for (int k = 0; k < kGK; ++k) {
+            const int off = k * 256 + lane * 4;
+            c4[k] = 0;
+            if (aligned && off + 3 < r.len) {
+                c4[k] = __builtin_nontemporal_load((const BITSNAP_GLOBAL uint32_t *)(global_ptr(codes) + r.lo + off));
+            } else {
+                for (int j = 0; j < 4; ++j)
+                    if (off + j < r.len)
+                        c4[k] |= (uint32_t)global_ptr(codes)[r.lo + off + j] << (8 * j);
+            }
+        }
+    }
+    if (lane < kMaxClusters) {
+        float2 sb = make_float2(0.0f, 0.0f);
+        if (lane < m) {
+            const float2v t = *(const BITSNAP_GLOBAL float2v *)(global_ptr(params) + (r.group * m + lane) * 2);
+            sb = make_float2(t.x, t.y);
+        }
+        sh.coder[lane] = kTable ? sb : make_float2(__fdiv_rn(sb.x, 255.0f), sb.y);  // (S or S/255, b)
+    }
+    if (kMajor) {
+        MajorView mv;
+        mv.counters = &sh.counters[0][0];
+        mv.bytes = sh.bytes;
+        mv.labels = sh.labels;
+        uint16_t *l16 = (uint16_t *)mv.labels;
+#pragma unroll
+        for (int k = 0; k < kGK; ++k)
+            l16[k * kWave + lane] = (uint16_t)l4[k];
+        wave_lds_sync();
+        const uint32_t dest = segment_dest(counts, slice_counts, cluster_base, c, r.group, chunks_per_group, slices_per_group, lane);
+        uint8_t *b8 = (uint8_t *)mv.bytes;
+        const int len = r.len;
+        // The chunk's 16 runs of codes, collected once their places inside the chunk are known.  Lane l takes the
+        // chunk's cluster-major positions l, l + 64, ...: the run a position belongs to only moves forward, and
+        // all of a lane's loads are issued before the first of them is used.
+        uint32_t *seg_start = sh.seg_start, *seg_delta = sh.seg_delta;
+        auto collect = [&](uint32_t start) {
+            if (lane <= kMaxClusters)
+                seg_start[lane] = start;  // lane 16 holds len
+            if (lane < kMaxClusters)
+                seg_delta[lane] = dest - start;  // position in the chunk -> place in the group
+            wave_lds_sync();
+            uint32_t cl = 0, next = seg_start[1], delta = seg_delta[0];
+            uint32_t src[4 * kGK], b[4 * kGK];
+#pragma unroll
+            for (int it = 0; it < 4 * kGK; ++it) {
+                const uint32_t p = (uint32_t)lane + (uint32_t)it * kWave;
+                src[it] = 0xFFFFFFFFu;
+                if (p < (uint32_t)len) {
+                    while (p >= next) {
+                        ++cl;
+                        next = seg_start[cl + 1];
+                        delta = seg_delta[cl];
+                    }
+                    src[it] = delta + p;
+                }
+            }
+#pragma unroll
+            for (int it = 0; it < 4 * kGK; ++it)  // holds whenever the counts are consistent; keeps any load inside the group
+                b[it] = (int64_t)src[it] < g_len ? (uint32_t)global_ptr(codes)[g_lo + src[it]] : 0u;
+#pragma unroll
+            for (int it = 0; it < 4 * kGK; ++it) {
+                const uint32_t p = (uint32_t)lane + (uint32_t)it * kWave;
+                if (p < (uint32_t)len)
+                    b8[p] = (uint8_t)b[it];
+            }
+            wave_lds_sync();
+        };
+        if (len == kGChunk)
+            from_cluster_major<kGK, true>(mv, len, lane, collect);
+        else
+            from_cluster_major<kGK, false>(mv, len, lane, collect);
+#pragma unroll
+        for (int k = 0; k < kGK; ++k)
+            c4[k] = mv.bytes[k * kWave + lane];
+    } else {
+        wave_lds_sync();
+    }
+#pragma unroll
+    for (int k = 0; k < kGK; ++k) {
+        const int off = k * 256 + lane * 4;
+        float v[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const float2 sb = sh.coder[(l4[k] >> (4 * j)) & 15u];
+            const uint32_t q = (c4[k] >> (8 * j)) & 255u;
+            const float level = kTable ? table[q] : (float)q;
+            v[j] = __fadd_rn(__fmul_rn(level, sb.x), sb.y);
+        }
+        if (aligned && off + 3 < r.len) {
+            __builtin_nontemporal_store(float4v{v[0], v[1], v[2], v[3]}, (BITSNAP_GLOBAL float4v *)(global_ptr(out) + r.lo + off));
+        } else {
+            for (int j = 0; j < 4; ++j)
+                if (off + j < r.len)
+                    global_ptr(out)[r.lo + off + j] = v[j];
+        }
+    }
+}
+
 static void general_shape(int64_t n, int64_t group, int64_t &G, int64_t &groups, int64_t &cpg, int64_t &chunks,
                           int64_t &spg)
 {
@@ -413,9 +813,12 @@ int cluster_general_quantize(const float *x, int64_t n, int64_t group, int m, ui
     hipLaunchKernelGGL(wide_slice_stats_kernel, sgrid, block, 0, s, n, G, cpg, spg, groups, stats, slice_stats);
     hipLaunchKernelGGL(wide_fit_kernel, ggrid, block, 0, s, n, G, spg, groups, m, slice_stats, gs, fit_out, fit_in,
                        status);
-    hipLaunchKernelGGL(wide_range_kernel, cgrid, block, 0, s, x, n, G, cpg, chunks, m, gs, ranges);
-    hipLaunchKernelGGL(wide_slice_ranges_kernel, sgrid, block, 0, s, n, G, cpg, spg, groups, ranges, slice_ranges);
-    hipLaunchKernelGGL(wide_params_kernel, ggrid, block, 0, s, n, G, spg, groups, m, slice_ranges, gs, params);
+    hipLaunchKernelGGL(wide_range_kernel<false>, cgrid, block, 0, s, x, n, G, cpg, chunks, m, gs, ranges,
+                       (ChunkCounts *)nullptr);
+    hipLaunchKernelGGL((wide_slice_kernel<true, false>), sgrid, block, 0, s, n, G, cpg, spg, groups, ranges, slice_ranges,
+                       (ChunkCounts *)nullptr, (ChunkCounts *)nullptr);
+    hipLaunchKernelGGL((wide_group_kernel<true, false>), ggrid, block, 0, s, n, G, spg, groups, m, slice_ranges, gs, params,
+                       (ChunkCounts *)nullptr, (ChunkCounts *)nullptr);
     hipLaunchKernelGGL(wide_code_kernel, cgrid, block, 0, s, x, n, G, cpg, chunks, m, gs, labels, codes);
     return launch_status();
 }
@@ -430,6 +833,116 @@ int cluster_general_dequantize(const uint8_t *codes, const uint8_t *labels, cons
         return BITSNAP_E_SIZE;
     hipLaunchKernelGGL(wide_dequantize_kernel, dim3((unsigned)blocks), dim3(kGBlock), 0, s, codes, labels, params, n, G,
                        cpg, chunks, m, out);
+    return launch_status();
+}
+
+// ---- host side of the format variants
+
+static size_t counts_bytes(int64_t chunks, int64_t slices, int64_t groups)
+{
+    return (size_t)(chunks + slices + groups) * sizeof(ChunkCounts);
+}
+
+size_t cluster_general_workspace_bytes_ex(int64_t n, int64_t group, bool major)
+{
+    if (n <= 0)
+        return 0;
+    if (!major)
+        return cluster_general_workspace_bytes(n, group);
+    int64_t G, groups, cpg, chunks, spg;
+    general_shape(n, group, G, groups, cpg, chunks, spg);
+    return cluster_general_workspace_bytes(n, group) + (counts_bytes(chunks, groups * spg, groups) + 255) / 256 * 256;
+}
+
+// Grid of the persistent pass-3 kernel when a table has to be prepared per workgroup.
+template <bool kTable, bool kMajor>
+static unsigned code_ex_grid(int64_t blocks)
+{
+    if (!kTable)
+        return (unsigned)blocks;
+    const void *kernel = (const void *)wide_code_ex_kernel<kTable, kMajor>;
+    const int64_t resident = (int64_t)device_info().cu_count * occupancy_blocks_per_cu(kernel, kGBlock);
+    return (unsigned)(blocks < resident ? blocks : resident);
+}
+
+int cluster_general_quantize_ex(const float *x, int64_t n, int64_t group, int m, bool major, const float *qmap,
+                                uint8_t *codes, uint8_t *labels, float *params, float *fit_out, const float *fit_in,
+                                uint32_t *status, void *workspace, hipStream_t s)
+{
+    int64_t G, groups, cpg, chunks, spg;
+    general_shape(n, group, G, groups, cpg, chunks, spg);
+    const int64_t blocks = (chunks + kGWaves - 1) / kGWaves, slices = groups * spg;
+    if (blocks > 0x7FFFFFFF || slices > 0x7FFFFFFF || (major && n > 0xFFFFFFFFll))
+        return BITSNAP_E_SIZE;  // places inside a group are 32-bit
+    GroupState *gs = reinterpret_cast<GroupState *>(workspace);
+    ChunkStats *stats = reinterpret_cast<ChunkStats *>(gs + groups);
+    ChunkStats *slice_stats = stats + chunks;
+    ChunkRanges *ranges = reinterpret_cast<ChunkRanges *>(slice_stats + slices);
+    ChunkRanges *slice_ranges = ranges + chunks;
+    ChunkCounts *counts = reinterpret_cast<ChunkCounts *>((char *)workspace + cluster_general_workspace_bytes(n, group));
+    ChunkCounts *slice_counts = counts + chunks, *cluster_base = slice_counts + slices;
+    const dim3 block(kGBlock), cgrid((unsigned)blocks), sgrid((unsigned)slices), ggrid(general_grid(groups));
+    hipLaunchKernelGGL(wide_stats_kernel, cgrid, block, 0, s, x, n, G, cpg, chunks, stats);
+    hipLaunchKernelGGL(wide_slice_stats_kernel, sgrid, block, 0, s, n, G, cpg, spg, groups, stats, slice_stats);
+    hipLaunchKernelGGL(wide_fit_kernel, ggrid, block, 0, s, n, G, spg, groups, m, slice_stats, gs, fit_out, fit_in,
+                       status);
+    if (major) {
+        hipLaunchKernelGGL(wide_range_kernel<true>, cgrid, block, 0, s, x, n, G, cpg, chunks, m, gs, ranges, counts);
+        hipLaunchKernelGGL((wide_slice_kernel<true, true>), sgrid, block, 0, s, n, G, cpg, spg, groups, ranges, slice_ranges,
+                           counts, slice_counts);
+        hipLaunchKernelGGL((wide_group_kernel<true, true>), ggrid, block, 0, s, n, G, spg, groups, m, slice_ranges, gs,
+                           params, slice_counts, cluster_base);
+    } else {
+        hipLaunchKernelGGL(wide_range_kernel<false>, cgrid, block, 0, s, x, n, G, cpg, chunks, m, gs, ranges,
+                           (ChunkCounts *)nullptr);
+        hipLaunchKernelGGL((wide_slice_kernel<true, false>), sgrid, block, 0, s, n, G, cpg, spg, groups, ranges,
+                           slice_ranges, (ChunkCounts *)nullptr, (ChunkCounts *)nullptr);
+        hipLaunchKernelGGL((wide_group_kernel<true, false>), ggrid, block, 0, s, n, G, spg, groups, m, slice_ranges, gs,
+                           params, (ChunkCounts *)nullptr, (ChunkCounts *)nullptr);
+    }
+#define BITSNAP_CODE_EX(T, M)                                                                                           \
+    hipLaunchKernelGGL((wide_code_ex_kernel<T, M>), dim3(code_ex_grid<T, M>(blocks)), block, 0, s, x, n, G, cpg, spg, chunks, \
+                       m, gs, params, qmap, counts, slice_counts, cluster_base, labels, codes)
+    if (qmap && major)
+        BITSNAP_CODE_EX(true, true);
+    else if (qmap)
+        BITSNAP_CODE_EX(true, false);
+    else
+        BITSNAP_CODE_EX(false, true);
+#undef BITSNAP_CODE_EX
+    return launch_status();
+}
+
+int cluster_general_dequantize_ex(const uint8_t *codes, const uint8_t *labels, const float *params, int64_t n,
+                                  int64_t group, int m, bool major, const float *qmap, float *out, void *workspace,
+                                  hipStream_t s)
+{
+    int64_t G, groups, cpg, chunks, spg;
+    general_shape(n, group, G, groups, cpg, chunks, spg);
+    const int64_t blocks = (chunks + kGWaves - 1) / kGWaves, slices = groups * spg;
+    if (blocks > 0x7FFFFFFF || slices > 0x7FFFFFFF || (major && n > 0xFFFFFFFFll))
+        return BITSNAP_E_SIZE;
+    ChunkCounts *counts = major ? reinterpret_cast<ChunkCounts *>((char *)workspace + cluster_general_workspace_bytes(n, group))
+                                : nullptr;
+    ChunkCounts *slice_counts = counts + (major ? chunks : 0), *cluster_base = slice_counts + (major ? slices : 0);
+    const dim3 block(kGBlock), cgrid((unsigned)blocks), sgrid((unsigned)slices), ggrid(general_grid(groups));
+    if (major) {
+        hipLaunchKernelGGL(wide_label_counts_kernel, cgrid, block, 0, s, labels, n, G, cpg, chunks, counts);
+        hipLaunchKernelGGL((wide_slice_kernel<false, true>), sgrid, block, 0, s, n, G, cpg, spg, groups,
+                           (const ChunkRanges *)nullptr, (ChunkRanges *)nullptr, counts, slice_counts);
+        hipLaunchKernelGGL((wide_group_kernel<false, true>), ggrid, block, 0, s, n, G, spg, groups, m,
+                           (const ChunkRanges *)nullptr, (GroupState *)nullptr, (float *)nullptr, slice_counts, cluster_base);
+    }
+#define BITSNAP_DEQ_EX(T, M)                                                                                            \
+    hipLaunchKernelGGL((wide_dequantize_ex_kernel<T, M>), cgrid, block, 0, s, codes, labels, params, n, G, cpg, spg, chunks, \
+                       m, qmap, counts, slice_counts, cluster_base, out)
+    if (qmap && major)
+        BITSNAP_DEQ_EX(true, true);
+    else if (qmap)
+        BITSNAP_DEQ_EX(true, false);
+    else
+        BITSNAP_DEQ_EX(false, true);
+#undef BITSNAP_DEQ_EX
     return launch_status();
 }
 

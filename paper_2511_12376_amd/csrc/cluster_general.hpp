@@ -14,6 +14,16 @@ int cluster_general_quantize(const float *x, int64_t n, int64_t group, int m, ui
 int cluster_general_dequantize(const uint8_t *codes, const uint8_t *labels, const float *params, int64_t n,
                                int64_t group, int m, float *out, hipStream_t s);
 
+// The same with the format options (a table for the quantisation map, cluster-major codes); with
+// `major` the workspace also holds the per-chunk cluster counts, and dequantisation needs it too.
+size_t cluster_general_workspace_bytes_ex(int64_t n, int64_t group, bool major);
+int cluster_general_quantize_ex(const float *x, int64_t n, int64_t group, int m, bool major, const float *qmap,
+                                uint8_t *codes, uint8_t *labels, float *params, float *fit_out, const float *fit_in,
+                                uint32_t *status, void *workspace, hipStream_t s);
+int cluster_general_dequantize_ex(const uint8_t *codes, const uint8_t *labels, const float *params, int64_t n,
+                                  int64_t group, int m, bool major, const float *qmap, float *out, void *workspace,
+                                  hipStream_t s);
+
 // K (float4 per lane) of the one-wave-per-group kernels for a group length, or 0 when the length
 // needs the multi-pass path.
 inline int one_wave_group_k(int64_t group)

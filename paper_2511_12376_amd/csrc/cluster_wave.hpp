@@ -281,7 +281,7 @@ __device__ __forceinline__ void label_pass_impl(const float4 (&v)[K], int64_t lo
             if (kStore) {
                 const int off = k * 256 + lane * 4;
                 BITSNAP_GLOBAL uint8_t *lp = global_ptr(labels) + ((lo + off) >> 1);
-                if (kFull || off + 3 < len) {
+                if (kFull || (off + 3 < len && (lo & 3) == 0)) {  // four whole elements at an aligned place
                     __builtin_nontemporal_store((uint16_t)l4, (BITSNAP_GLOBAL uint16_t *)lp);
                 } else {
                     if (off < len)
@@ -375,7 +375,7 @@ __device__ __forceinline__ void code_pass(const float4 (&v)[K], int64_t lo, int 
             }
             const int off = k * 256 + lane * 4;
             BITSNAP_GLOBAL uint8_t *cp = global_ptr(codes) + lo + off;
-            if (kFull || off + 3 < len) {
+            if (kFull || (off + 3 < len && (lo & 3) == 0)) {
                 __builtin_nontemporal_store(c4, (BITSNAP_GLOBAL uint32_t *)cp);
             } else {
                 for (int j = 0; j < 4; ++j)

@@ -79,7 +79,7 @@ def test_quantize_dequantize_match_oracle(n, G, m):
 
 
 @pytest.mark.parametrize("n", [1, 7, 1000, 4097, 50_001, 300_000])
-@pytest.mark.parametrize("G,m", [(0, 16), (1000, 16), (6000, 7), (2, 16), (10_000, 16), (0, 1)])
+@pytest.mark.parametrize("G,m", [(0, 16), (1000, 16), (1002, 16), (6000, 7), (6002, 16), (2, 16), (10_000, 16), (0, 1)])
 def test_other_group_lengths_and_whole_tensor(n, G, m):
     """Group lengths outside the one-wave-per-group kernels, and G = 0: one fit for the whole
     tensor, which is how the paper states Algorithm 2."""

@@ -113,9 +113,11 @@ def test_degenerate_groups():
 def test_argument_checks():
     x = f32_to_dev(_states(14, 4096))
     with pytest.raises(B.BitsnapError):
-        B.quantize_cluster_ex(x, 1000, 16, cluster_major=True)          # not a one-wave group length
+        B.quantize_cluster_ex(x, 1001, 16, cluster_major=True)          # an odd group length would split a label byte
     with pytest.raises(B.BitsnapError):
-        B.quantize_cluster_ex(x, 0, 16, cluster_major=True)             # whole-tensor groups: plain entry point only
+        B.quantize_cluster_ex_raw(x, 4096, 0, 16, B.CLUSTER_MAJOR, None, torch.empty(4096, dtype=torch.uint8, device=DEV),
+                                  torch.empty(2048, dtype=torch.uint8, device=DEV),
+                                  torch.empty(1, 16, 2, dtype=torch.float32, device=DEV))   # wide group without a workspace
     q = B.quantize_cluster_ex(x, 4096, 16, cluster_major=True)
     out = torch.empty(4096, dtype=torch.float32, device=DEV)
     with pytest.raises(B.BitsnapError):
@@ -249,3 +251,70 @@ def test_batched_variants_argument_checks():
     rc = B.lib().bitsnap_dequantize_cluster_batched_ex(items.data_ptr(), 1, groups, 4096, 16, 4, None, None)
     assert rc != 0                                                   # unknown flag
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("kind,major", [(None, True), ("normal", False), ("square", True), ("close", True)])
+@pytest.mark.parametrize("G,n", [(0, 1_300_003), (0, 4097), (0, 77), (1000, 10_500), (1002, 20_040 + 7), (6000, 100_000),
+                                 (10_000, 1_000_003), (2, 1001), (1_048_576 + 8192, 2_200_000)])
+def test_wide_groups_match_the_oracle(G, n, kind, major):
+    """Whole-tensor groups and the other lengths of the multi-pass path: one fit per group, and with cluster-major
+    codes one arrangement per group, across chunks and slices of chunks."""
+    announce("variants wide", G, n, kind, major)
+    x = _states(G + n, n)
+    if kind == "close":
+        Q = _tables()["close"]
+        Qd = f32_to_dev(Q)
+        q = B.quantize_cluster_ex(f32_to_dev(x), G, 16, qmap=Qd, cluster_major=major)
+        torch.cuda.synchronize()
+        o = oracle.quantize_cluster_ex(x, G, 16, fit_in=to_np(q.fit)[:, :2].copy(), qmap=Q, cluster_major=major)
+        assert np.array_equal(to_np(q.labels), o["labels"]) and np.array_equal(to_np(q.params), o["params"])
+        assert np.array_equal(to_np(q.codes), o["codes"])
+        xh = B.dequantize_cluster_ex(q.codes, q.labels, q.params, n, G, 16, qmap=Qd, cluster_major=major)
+        torch.cuda.synchronize()
+        assert np.array_equal(to_np(xh), oracle.dequantize_cluster_ex(o["codes"], o["labels"], o["params"], n, G, 16, qmap=Q,
+                                                                      cluster_major=major))
+    else:
+        _check(x, G, 16, kind, major)
+
+
+@pytest.mark.parametrize("m", [1, 3, 15])
+def test_wide_groups_with_fewer_clusters(m):
+    announce("variants wide m", m)
+    _check(_states(60 + m, 300_000), 0, m, "normal", True)
+    _check(_states(70 + m, 50_001), 10_000, m, None, True)
+
+
+def test_wide_cluster_major_round_trip_equals_the_element_order_round_trip():
+    announce("variants wide round trip")
+    x = _states(31, 2_000_000)
+    xd = f32_to_dev(x)
+    a = B.quantize_cluster(xd, 0, 16)
+    b = B.quantize_cluster_ex(xd, 0, 16, cluster_major=True)
+    ya = B.dequantize_cluster(a.codes, a.labels, a.params, x.size, 0, 16)
+    yb = B.dequantize_cluster_ex(b.codes, b.labels, b.params, x.size, 0, 16, cluster_major=True)
+    torch.cuda.synchronize()
+    assert torch.equal(a.labels, b.labels) and torch.equal(a.params, b.params) and torch.equal(ya, yb)
+    lab = oracle.unpack_labels(to_np(a.labels), x.size)
+    assert np.array_equal(to_np(b.codes), to_np(a.codes)[np.argsort(lab, kind="stable")])
+
+
+def test_whole_tensor_group_of_a_16m_element_tensor():
+    """One fit and one cluster-major arrangement for a whole 16.8 M-element tensor (4096 chunks in 16 slices), with a
+    non-linear table: the paper's formulation end to end."""
+    announce("variants wide 16M")
+    cfg = synth.config(2)
+    d = synth.make_tensor_torch(cfg, 2, DEV, want=("m",))
+    x = d["m"].reshape(-1)
+    n = x.numel()
+    assert n == 4096 * 4096
+    Q = synth.qmap_table("normal")
+    Qd = f32_to_dev(Q)
+    q = B.quantize_cluster_ex(x, 0, 16, qmap=Qd, cluster_major=True)
+    xh = B.dequantize_cluster_ex(q.codes, q.labels, q.params, n, 0, 16, qmap=Qd, cluster_major=True)
+    torch.cuda.synchronize()
+    assert int(q.status.item()) == 0
+    o = oracle.quantize_cluster_ex(to_np(x), 0, 16, fit_in=to_np(q.fit)[:, :2].copy(), qmap=Q, cluster_major=True)
+    assert np.array_equal(to_np(q.params), o["params"]) and np.array_equal(to_np(q.labels), o["labels"])
+    assert np.array_equal(to_np(q.codes), o["codes"])
+    assert np.array_equal(to_np(xh), oracle.dequantize_cluster_ex(o["codes"], o["labels"], o["params"], n, 0, 16, qmap=Q,
+                                                                  cluster_major=True))
