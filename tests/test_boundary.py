@@ -92,6 +92,39 @@ def test_bad_arguments_are_rejected_on_the_host():
     assert d(a, a, a, 4096, 4096, 0, a) == -2 and d(None, None, None, 0, 4096, 16, None) == 0
 
 
+def test_cluster_format_variants_are_checked_on_the_host():
+    L = B.lib()
+    buf = ctypes.create_string_buffer(1 << 16)
+    a = (ctypes.addressof(buf) + 255) // 256 * 256
+    MAJOR = B.CLUSTER_MAJOR
+    # workspace: none for the one-wave group lengths; the multi-pass path's own, plus the cluster counts with MAJOR
+    assert B.cluster_workspace_bytes_ex(1 << 20, 4096, 16, MAJOR) == 0
+    plain = B.cluster_workspace_bytes(1 << 20, 0, 16)
+    assert B.cluster_workspace_bytes_ex(1 << 20, 0, 16, 0) == plain
+    chunks = (1 << 20) // 4096
+    assert B.cluster_workspace_bytes_ex(1 << 20, 0, 16, MAJOR) >= plain + 64 * (chunks + 1 + 1)
+    q = lambda x, n, g, m, fl, tab, codes, labels, params, ws, wsb: L.bitsnap_quantize_cluster_ex(
+        x, n, g, m, fl, tab, codes, labels, params, None, None, None, ws, wsb, None)
+    assert q(a, 4096, 4096, 16, 2, None, a, a, a, None, 0) == -2            # unknown flag
+    assert q(a, 4096, 4096, 17, MAJOR, None, a, a, a, None, 0) == -2        # m > 16
+    assert q(a, 8192, 1001, 16, MAJOR, None, a, a, a, None, 0) == -2        # odd group length
+    assert q(a, 8192, 0, 16, MAJOR, None, a, a, a, None, 0) == -1           # wide group: workspace required
+    assert q(a, 8192, 0, 16, MAJOR, None, a, a, a, a, 64) == -4             # ... and large enough
+    assert q(a, 4096, 4096, 16, MAJOR, a + 2, a, a, a, None, 0) == -3       # misaligned table
+    assert q(None, 4096, 4096, 16, MAJOR, None, a, a, a, None, 0) == -1
+    assert q(None, 0, 4096, 16, MAJOR, None, None, None, None, None, 0) == 0
+    assert q(a, 1 << 33, 0, 16, MAJOR, None, a, a, a, a, B.cluster_workspace_bytes_ex(1 << 33, 0, 16, MAJOR)) == -2  # places are 32-bit
+    d = lambda codes, labels, params, n, g, m, fl, tab, out, ws, wsb: L.bitsnap_dequantize_cluster_ex(
+        codes, labels, params, n, g, m, fl, tab, out, ws, wsb, None)
+    assert d(a, a, a, 4096, 4096, 16, 4, None, a, None, 0) == -2
+    assert d(a, a, a, 8192, 0, 16, MAJOR, None, a, None, 0) == -1           # the partition needs the workspace here too
+    assert d(a, a, a, 4096, 4096, 16, MAJOR, None, None, None, 0) == -1
+    assert d(a, a, a, 4096, 4096, 16, MAJOR, None, a + 4, None, 0) == -3
+    qb = lambda items, count, groups, g, m, fl: L.bitsnap_quantize_cluster_batched_ex(items, count, groups, g, m, fl, None, None, None)
+    assert qb(a, 1, 1, 1000, 16, MAJOR) == -2 and qb(a, 1, 1, 4096, 16, 8) == -2 and qb(None, 1, 1, 4096, 16, MAJOR) == -1
+    assert qb(a, 0, 0, 4096, 16, MAJOR) == 0
+
+
 def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(B, "_lib", None)
     monkeypatch.setattr(B, "LIB_PATH", os.path.join(ROOT, "no_such_dir", "libbitsnap.so"))
