@@ -1,20 +1,11 @@
 // Format variants of the cluster quantiser (paper: "Cluster Based Quantization for Optimizer
-// States"):
+// States") for the group lengths that one wavefront handles:
 //   * a general map Q^map in Eq. qmap-distance: code = the entry of a 256-entry table nearest to
 //     (x-b)/S, and T^D = Q(T^Q)*S + b on the way back;
 //   * the cluster-major arrangement of Eq. decluster: inside a group the codes of cluster 0 come
 //     first, then cluster 1, ..., each cluster's codes in element order.
-//
-// One wavefront per group, as in the plain kernels, and steps 1-4 of Algorithm 2 are the same
-// code.  The table lives in LDS once per workgroup, turned into a step function over 1024 bins
-// of (x-b)/S where its levels are far enough apart for that, and searched by bisection otherwise.
-// The
-// cluster-major arrangement is a stable 16-way partition of the group's codes done inside the
-// wave through LDS: the codes and the labels are laid down in element order; then lane l takes
-// the 4K consecutive elements l*4K .. l*4K+4K-1, counts its labels into a private column of a
-// [16][64] counter table, an exclusive prefix sum over that table read row by row (cluster, then
-// lane) turns every counter into the position of the lane's first member of the cluster, and a
-// second walk over the same elements hands out consecutive positions.
+// Steps 1-4 of Algorithm 2 are the plain kernels' code; the table search and the partition are
+// in cluster_variants.hpp.  Wide groups go to the multi-pass kernels.
 #include <hip/hip_runtime.h>
 #include <math.h>
 #include <stdint.h>

@@ -3,6 +3,15 @@
 // qmap-distance, and the stable 16-way partition that turns element-order codes into the
 // cluster-major arrangement of Eq. decluster and back.  Used by the one-wave-per-group kernels
 // and by the multi-pass kernels for wide groups.
+//
+// The table lives in LDS once per workgroup, turned into a step function over 1024 bins of
+// (x-b)/S where its levels are far enough apart for that, and searched by bisection otherwise.
+// The partition runs inside the wave through LDS: the codes and the labels are laid down in
+// element order; then lane l takes the 4K consecutive elements l*4K .. l*4K+4K-1, counts its
+// labels into a private column of a [16][64] counter table, an exclusive prefix sum over that
+// table read row by row (cluster, then lane) turns every counter into the position of the lane's
+// first member of the cluster, and a second walk over the same elements hands out consecutive
+// positions.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <math.h>
