@@ -313,13 +313,24 @@ int bitsnap_dequantize_cluster_batched(const bitsnap_cluster_item *items, int64_
                                        int64_t group, int m, bitsnap_stream_t stream);
 
 /* The batched cluster calls with the options of bitsnap_quantize_cluster_ex /
- * bitsnap_dequantize_cluster_ex (flags and qmap apply to every item; group one of 256 .. 4096). */
+ * bitsnap_dequantize_cluster_ex (flags and qmap apply to every item), and with group = 0: one
+ * group per tensor for the whole list (the paper's formulation, a checkpoint pass at a time).
+ *   group   one of 256 .. 4096, or 0.
+ *           With 0, groups are not the unit of the list-wide numbering (every tensor has one);
+ *           chunks of bitsnap_cluster_chunk_elems() elements are: an item's first_group is the sum
+ *           of ceil(n / chunk_elems) over all earlier items and total_groups that sum over all
+ *           items; params holds [m][2] and fit_out [m+1] floats per tensor.
+ *   workspace  [bitsnap_cluster_batch_workspace_bytes(total_groups, count, group, flags)], 16-byte
+ *           aligned; 0 bytes (may be NULL) unless group = 0.  Dequantisation uses it only with
+ *           BITSNAP_CLUSTER_MAJOR, which needs every n < 2^32 when group = 0. */
+size_t bitsnap_cluster_chunk_elems(void);
+size_t bitsnap_cluster_batch_workspace_bytes(int64_t total_groups, int64_t count, int64_t group, uint32_t flags);
 int bitsnap_quantize_cluster_batched_ex(const bitsnap_cluster_item *items, int64_t count, int64_t total_groups,
                                         int64_t group, int m, uint32_t flags, const float *qmap, uint32_t *status,
-                                        bitsnap_stream_t stream);
+                                        void *workspace, size_t workspace_bytes, bitsnap_stream_t stream);
 int bitsnap_dequantize_cluster_batched_ex(const bitsnap_cluster_item *items, int64_t count, int64_t total_groups,
-                                          int64_t group, int m, uint32_t flags, const float *qmap,
-                                          bitsnap_stream_t stream);
+                                          int64_t group, int m, uint32_t flags, const float *qmap, void *workspace,
+                                          size_t workspace_bytes, bitsnap_stream_t stream);
 
 #ifdef __cplusplus
 }

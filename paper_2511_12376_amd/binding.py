@@ -26,6 +26,7 @@ SYMBOLS = (
     "bitsnap_quantize_cluster", "bitsnap_dequantize_cluster",
     "bitsnap_quantize_cluster_ex", "bitsnap_dequantize_cluster_ex", "bitsnap_cluster_workspace_bytes_ex",
     "bitsnap_quantize_cluster_batched_ex", "bitsnap_dequantize_cluster_batched_ex",
+    "bitsnap_cluster_chunk_elems", "bitsnap_cluster_batch_workspace_bytes",
     "bitsnap_quantize_cluster_batched", "bitsnap_dequantize_cluster_batched",
     "bitsnap_sparse_batch_workspace_bytes", "bitsnap_encode_sparse_batched", "bitsnap_decode_sparse_batched",
 )
@@ -78,10 +79,13 @@ def lib():
     L.bitsnap_cluster_fit_floats.argtypes, L.bitsnap_cluster_fit_floats.restype = [i64, i64, i], sz
     L.bitsnap_cluster_workspace_bytes.argtypes, L.bitsnap_cluster_workspace_bytes.restype = [i64, i64, i], sz
     L.bitsnap_cluster_z.argtypes, L.bitsnap_cluster_z.restype = [i, i], C.c_double
-    L.bitsnap_quantize_cluster_batched_ex.argtypes = [p, i64, i64, i64, i, C.c_uint32, p, p, p]
+    L.bitsnap_quantize_cluster_batched_ex.argtypes = [p, i64, i64, i64, i, C.c_uint32, p, p, p, sz, p]
     L.bitsnap_quantize_cluster_batched_ex.restype = i
-    L.bitsnap_dequantize_cluster_batched_ex.argtypes = [p, i64, i64, i64, i, C.c_uint32, p, p]
+    L.bitsnap_dequantize_cluster_batched_ex.argtypes = [p, i64, i64, i64, i, C.c_uint32, p, p, sz, p]
     L.bitsnap_dequantize_cluster_batched_ex.restype = i
+    L.bitsnap_cluster_chunk_elems.argtypes, L.bitsnap_cluster_chunk_elems.restype = [], sz
+    L.bitsnap_cluster_batch_workspace_bytes.argtypes = [i64, i64, i64, C.c_uint32]
+    L.bitsnap_cluster_batch_workspace_bytes.restype = sz
     L.bitsnap_quantize_cluster_ex.argtypes = [p, i64, i64, i, C.c_uint32, p, p, p, p, p, p, p, p, sz, p]
     L.bitsnap_quantize_cluster_ex.restype = i
     L.bitsnap_dequantize_cluster_ex.argtypes = [p, p, p, i64, i64, i, C.c_uint32, p, p, p, sz, p]
@@ -383,7 +387,8 @@ def dequantize_cluster(codes, labels, params, n: int, group: int = 4096, m: int 
 # ----------------------------------------------------------------------------------------------
 def cluster_items(values, codes, labels, params, group: int, fit_out=None, fit_in=None):
     """Device array of bitsnap_cluster_item (8 x int64 per tensor) for lists of torch tensors.
-    ``values`` holds x (quantize) or out (dequantize).  -> (items int64[count, 8], total_groups)."""
+    ``values`` holds x (quantize) or out (dequantize).  -> (items int64[count, 8], total_groups); with group = 0
+    (one group per tensor, for the *_batched_ex calls) the numbering counts chunks instead of groups."""
     import torch
     rows, first = [], 0
     for k, v in enumerate(values):
@@ -392,7 +397,7 @@ def cluster_items(values, codes, labels, params, group: int, fit_out=None, fit_i
         rows.append([v.data_ptr(), codes[k].data_ptr(), labels[k].data_ptr(), params[k].data_ptr(),
                      0 if fit_out is None else fit_out[k].data_ptr(), 0 if fit_in is None else fit_in[k].data_ptr(),
                      n, first])
-        first += cluster_groups(n, group)
+        first += cluster_groups(n, group) if group > 0 else (n + cluster_chunk_elems() - 1) // cluster_chunk_elems()
     items = torch.tensor(rows, dtype=torch.int64).to(values[0].device)
     return items, first
 
@@ -408,18 +413,30 @@ def dequantize_cluster_batched(items, total_groups: int, group: int, m: int, str
     _check(rc, "bitsnap_dequantize_cluster_batched")
 
 
+def cluster_chunk_elems() -> int:
+    return lib().bitsnap_cluster_chunk_elems()
+
+
+def cluster_batch_workspace_bytes(total_groups: int, count: int, group: int, flags: int = 0) -> int:
+    return lib().bitsnap_cluster_batch_workspace_bytes(total_groups, count, group, flags)
+
+
 def quantize_cluster_batched_ex(items, total_groups: int, group: int, m: int, *, qmap=None, cluster_major: bool = False,
-                                status=None, stream=None) -> None:
+                                status=None, workspace=None, stream=None) -> None:
+    """group = 0: one group per tensor; build the items with cluster_items(..., group=0), which then counts chunks."""
+    wb = 0 if workspace is None else workspace.numel() * workspace.element_size()
     rc = lib().bitsnap_quantize_cluster_batched_ex(_ptr(items), items.shape[0], total_groups, group, m,
                                                    CLUSTER_MAJOR if cluster_major else 0, _ptr(qmap), _ptr(status),
-                                                   _stream(stream))
+                                                   _ptr(workspace), wb, _stream(stream))
     _check(rc, "bitsnap_quantize_cluster_batched_ex")
 
 
 def dequantize_cluster_batched_ex(items, total_groups: int, group: int, m: int, *, qmap=None, cluster_major: bool = False,
-                                  stream=None) -> None:
+                                  workspace=None, stream=None) -> None:
+    wb = 0 if workspace is None else workspace.numel() * workspace.element_size()
     rc = lib().bitsnap_dequantize_cluster_batched_ex(_ptr(items), items.shape[0], total_groups, group, m,
-                                                     CLUSTER_MAJOR if cluster_major else 0, _ptr(qmap), _stream(stream))
+                                                     CLUSTER_MAJOR if cluster_major else 0, _ptr(qmap), _ptr(workspace), wb,
+                                                     _stream(stream))
     _check(rc, "bitsnap_dequantize_cluster_batched_ex")
 
 

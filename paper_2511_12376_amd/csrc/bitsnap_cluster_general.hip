@@ -26,6 +26,7 @@
 
 #include "../../include/bitsnap.h"
 #include "cluster_general.hpp"
+#include "cluster_items.hpp"
 #include "cluster_variants.hpp"
 #include "cluster_wave.hpp"
 #include "host_util.hpp"
@@ -77,6 +78,142 @@ __device__ __forceinline__ ChunkRef chunk_ref(int64_t c, int64_t n, int64_t G, i
 // A whole chunk whose first element is 16-byte aligned takes the vector loads and stores.
 __device__ __forceinline__ bool chunk_is_full(const ChunkRef &r) { return r.len == kGChunk && (r.lo & 3) == 0; }
 
+constexpr int kGSlice = kGBlock;  // chunks per slice of the two-level reductions: one per thread
+
+// One tensor as the kernels see it, and where its chunks, slices and groups sit in the workspace arrays.
+struct WideTensor {
+    void *values;  // x (quantise) or out (dequantise)
+    uint8_t *codes, *labels;
+    float *params, *fit_out;
+    const float *fit_in;
+    int64_t n, G, cpg, spg, groups;     // elements, group length, chunks per group, slices per group, groups
+    int64_t chunk0, slice0, group0;     // index of its first chunk / slice / group in the workspace arrays
+};
+
+__host__ __device__ inline WideTensor wide_tensor(void *values, uint8_t *codes, uint8_t *labels, float *params,
+                                                  float *fit_out, const float *fit_in, int64_t n, int64_t group)
+{
+    WideTensor t;
+    t.values = values, t.codes = codes, t.labels = labels, t.params = params, t.fit_out = fit_out, t.fit_in = fit_in;
+    t.n = n;
+    t.G = (group <= 0 || group > n) ? n : group;
+    t.groups = (n + t.G - 1) / t.G;
+    t.cpg = (t.G + kGChunk - 1) / kGChunk;
+    t.spg = (t.cpg + kGSlice - 1) / kGSlice;
+    t.chunk0 = t.slice0 = t.group0 = 0;
+    return t;
+}
+
+// Where a kernel's work items come from: one tensor (any group length), or a list of tensors with
+// one group each (the batched form of group = 0).  Work is numbered across the whole source:
+// chunk gc, slice gs, group gg; the of_* calls name the tensor and the index inside it.
+struct OneTensor {
+    WideTensor t;
+    __device__ int64_t chunks() const { return t.groups * t.cpg; }
+    __device__ int64_t slices() const { return t.groups * t.spg; }
+    __device__ int64_t groups() const { return t.groups; }
+    __device__ WideTensor of_chunk(int64_t gc, int64_t &c) const
+    {
+        c = gc;
+        return t;
+    }
+    __device__ WideTensor of_slice(int64_t gs, int64_t &g, int64_t &sl) const
+    {
+        g = gs / t.spg, sl = gs % t.spg;
+        return t;
+    }
+    __device__ WideTensor of_group(int64_t gg, int64_t &g) const
+    {
+        g = gg;
+        return t;
+    }
+};
+
+struct TensorList {
+    const bitsnap_cluster_item *items;  // first_group counts chunks here
+    int64_t count, total_chunks;
+    const int64_t *slice0;              // [count + 1], written by wide_list_slices_kernel; the last entry is the total
+    __device__ int64_t chunks() const { return total_chunks; }
+    __device__ int64_t slices() const { return slice0[count]; }
+    __device__ int64_t groups() const { return count; }
+    __device__ WideTensor tensor(int64_t i) const
+    {
+        const bitsnap_cluster_item &it = items[i];
+        WideTensor t = wide_tensor(it.values, it.codes, it.labels, it.params, it.fit_out, it.fit_in, it.n, 0);
+        t.chunk0 = it.first_group, t.slice0 = slice0 ? slice0[i] : 0, t.group0 = i;  // no slice list where no reduction runs
+        return t;
+    }
+    __device__ WideTensor of_chunk(int64_t gc, int64_t &c) const
+    {
+        const WideTensor t = tensor(find_item(items, count, gc));
+        c = gc - t.chunk0;
+        return t;
+    }
+    __device__ WideTensor of_slice(int64_t gs, int64_t &g, int64_t &sl) const
+    {
+        int64_t lo = 0, hi = count - 1;  // the last tensor whose first slice is <= gs
+        while (lo < hi) {
+            const int64_t mid = (lo + hi + 1) >> 1;
+            if (slice0[mid] <= gs)
+                lo = mid;
+            else
+                hi = mid - 1;
+        }
+        const WideTensor t = tensor(lo);
+        g = 0, sl = gs - t.slice0;
+        return t;
+    }
+    __device__ WideTensor of_group(int64_t gg, int64_t &g) const
+    {
+        g = 0;
+        return tensor(gg);
+    }
+};
+
+// The workspace, cut up.
+struct WideSpace {
+    GroupState *gs;
+    ChunkStats *stats, *slice_stats;
+    ChunkRanges *ranges, *slice_ranges;
+    ChunkCounts *counts, *slice_counts, *cluster_base;  // cluster-major codes only
+};
+
+// slice0[i] = slices of all tensors before i (one group each), slice0[count] = all of them.  One workgroup.
+__global__ __launch_bounds__(kGBlock) void wide_list_slices_kernel(const bitsnap_cluster_item *__restrict__ items,
+                                                                   int64_t count, int64_t *__restrict__ slice0)
+{
+    __shared__ uint32_t wave_total[kGWaves];
+    __shared__ int64_t running;
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
+    if (threadIdx.x == 0)
+        running = 0;
+    __syncthreads();
+    for (int64_t base = 0; base < count; base += kGBlock) {
+        const int64_t i = base + threadIdx.x;
+        uint32_t v = 0;
+        if (i < count) {
+            const int64_t chunks = (items[i].n + kGChunk - 1) / kGChunk;
+            v = (uint32_t)((chunks + kGSlice - 1) / kGSlice);
+        }
+        const uint32_t inc = wave_inclusive_add(v);
+        if (lane == kWave - 1)
+            wave_total[wave] = inc;
+        __syncthreads();
+        uint32_t before = 0;
+        for (int w = 0; w < wave; ++w)
+            before += wave_total[w];
+        const int64_t start = running;
+        if (i < count)
+            slice0[i] = start + before + inc - v;
+        __syncthreads();
+        if (threadIdx.x == kGBlock - 1)
+            running = start + before + inc;
+        __syncthreads();
+    }
+    if (threadIdx.x == 0)
+        slice0[count] = running;
+}
+
 __device__ __forceinline__ double block_sum(double v, double *scratch)
 {
     v = wave_sum(v);
@@ -89,15 +226,17 @@ __device__ __forceinline__ double block_sum(double v, double *scratch)
 }
 
 // ---- pass 1
-__global__ __launch_bounds__(kGBlock) void wide_stats_kernel(const float *__restrict__ x, int64_t n, int64_t G,
-                                                             int64_t chunks_per_group, int64_t chunks,
-                                                             ChunkStats *__restrict__ stats)
+template <typename Src>
+__global__ __launch_bounds__(kGBlock) void wide_stats_kernel(Src src, WideSpace sp)
 {
     const int lane = threadIdx.x & (kWave - 1), wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int64_t c = (int64_t)blockIdx.x * kGWaves + wave;
-    if (c >= chunks)
+    const int64_t gc = (int64_t)blockIdx.x * kGWaves + wave;
+    if (gc >= src.chunks())
         return;
-    const ChunkRef r = chunk_ref(c, n, G, chunks_per_group);
+    int64_t c;
+    const WideTensor t = src.of_chunk(gc, c);
+    const float *x = (const float *)t.values;
+    const ChunkRef r = chunk_ref(c, t.n, t.G, t.cpg);
     double sum = 0.0, dev = 0.0;
     if (r.len > 0) {
         float4 v[kGK];
@@ -110,8 +249,8 @@ __global__ __launch_bounds__(kGBlock) void wide_stats_kernel(const float *__rest
         }
     }
     if (lane == 0) {
-        stats[c].sum = sum;
-        stats[c].dev = dev;
+        sp.stats[t.chunk0 + c].sum = sum;
+        sp.stats[t.chunk0 + c].dev = dev;
     }
 }
 
@@ -120,8 +259,6 @@ __global__ __launch_bounds__(kGBlock) void wide_stats_kernel(const float *__rest
 //   sum = sum of the parts' sums,   dev = sum over parts of  dev_p + n_p * (mean_p - mean)^2
 // (every term non-negative, nothing cancels), in a fixed association: a tensor-wide group of a
 // 131 M-element tensor has 32000 chunks, too many for one workgroup to walk through.
-constexpr int kGSlice = kGBlock;  // chunks per slice: one per thread
-
 // Elements in chunks [c0, c1) of a group of g_len elements.
 __device__ __forceinline__ double chunk_span_elems(int64_t c0, int64_t c1, int64_t g_len)
 {
@@ -129,22 +266,27 @@ __device__ __forceinline__ double chunk_span_elems(int64_t c0, int64_t c1, int64
     return (double)((hi < g_len ? hi : g_len) - lo);
 }
 
-// grid: groups * slices_per_group workgroups
-__global__ __launch_bounds__(kGBlock) void wide_slice_stats_kernel(int64_t n, int64_t G, int64_t chunks_per_group,
-                                                                   int64_t slices_per_group, int64_t groups,
-                                                                   const ChunkStats *__restrict__ stats,
-                                                                   ChunkStats *__restrict__ slice_stats)
+// The elements of group g of a tensor.
+__device__ __forceinline__ int64_t group_len(const WideTensor &t, int64_t g)
+{
+    const int64_t g_lo = g * t.G;
+    return (g_lo + t.G <= t.n) ? t.G : (t.n - g_lo);
+}
+
+// grid: one workgroup per slice (a list of tensors may be launched with more: they leave at once)
+template <typename Src>
+__global__ __launch_bounds__(kGBlock) void wide_slice_stats_kernel(Src src, WideSpace sp)
 {
     __shared__ double scratch[kGBlock / kWave];
-    const int64_t g = blockIdx.x / slices_per_group, sl = blockIdx.x % slices_per_group;
-    if (g >= groups)
+    if ((int64_t)blockIdx.x >= src.slices())
         return;
-    const int64_t g_lo = g * G;
-    const int64_t g_len = (g_lo + G <= n) ? G : (n - g_lo);
+    int64_t g, sl;
+    const WideTensor t = src.of_slice(blockIdx.x, g, sl);
+    const int64_t g_len = group_len(t, g);
     const int64_t nch = (g_len + kGChunk - 1) / kGChunk;
     const int64_t c = sl * kGSlice + threadIdx.x, c_end = (sl + 1) * kGSlice < nch ? (sl + 1) * kGSlice : nch;
     const bool have = c < nch;
-    const ChunkStats mine = have ? stats[g * chunks_per_group + c] : ChunkStats{0.0, 0.0};
+    const ChunkStats mine = have ? sp.stats[t.chunk0 + g * t.cpg + c] : ChunkStats{0.0, 0.0};
     const double sum = block_sum(mine.sum, scratch);
     double term = 0.0;
     if (have && sl * kGSlice < nch) {
@@ -155,25 +297,27 @@ __global__ __launch_bounds__(kGBlock) void wide_slice_stats_kernel(int64_t n, in
     }
     const double dev = block_sum(term, scratch);
     if (threadIdx.x == 0) {
-        slice_stats[g * slices_per_group + sl].sum = sum;
-        slice_stats[g * slices_per_group + sl].dev = dev;
+        sp.slice_stats[t.slice0 + g * t.spg + sl].sum = sum;
+        sp.slice_stats[t.slice0 + g * t.spg + sl].dev = dev;
     }
 }
 
 // One workgroup per group: slices -> mean, deviation -> mu, sigma (Algorithm 2 step 1), edges.
 // Thread t takes slices t, t+256, ... in order, then the block tree.
-__global__ __launch_bounds__(kGBlock) void wide_fit_kernel(int64_t n, int64_t G, int64_t slices_per_group, int64_t groups,
-                                                           int m, const ChunkStats *__restrict__ slice_stats,
-                                                           GroupState *gs, float *__restrict__ fit_out,
-                                                           const float *__restrict__ fit_in, uint32_t *__restrict__ status)
+template <typename Src>
+__global__ __launch_bounds__(kGBlock) void wide_fit_kernel(Src src, WideSpace sp, int m, uint32_t *__restrict__ status)
 {
     __shared__ double scratch[kGBlock / kWave];
-    for (int64_t g = blockIdx.x; g < groups; g += gridDim.x) {
-        const int64_t g_lo = g * G;
-        const int64_t g_len = (g_lo + G <= n) ? G : (n - g_lo);
+    for (int64_t gg = blockIdx.x; gg < src.groups(); gg += gridDim.x) {
+        int64_t g;
+        const WideTensor t = src.of_group(gg, g);
+        float *fit_out = t.fit_out;
+        const float *fit_in = t.fit_in;
+        GroupState *gs = sp.gs + t.group0;
+        const int64_t g_len = group_len(t, g);
         const int64_t nch = (g_len + kGChunk - 1) / kGChunk;
         const int64_t nsl = (nch + kGSlice - 1) / kGSlice;
-        const ChunkStats *ss = slice_stats + g * slices_per_group;
+        const ChunkStats *ss = sp.slice_stats + t.slice0 + g * t.spg;
         double acc = 0.0;
         for (int64_t k = threadIdx.x; k < nsl; k += kGBlock)
             acc += ss[k].sum;
@@ -192,8 +336,8 @@ __global__ __launch_bounds__(kGBlock) void wide_fit_kernel(int64_t n, int64_t G,
             mu = fit_in[2 * g];
             sigma = fit_in[2 * g + 1];
         }
-        const int t = threadIdx.x;
-        if (t == 0) {
+        const int tid = threadIdx.x;
+        if (tid == 0) {
             gs[g].mu = mu;
             gs[g].sigma = sigma;
             if (status && !(isfinite(mu) && isfinite(sigma)))
@@ -203,8 +347,8 @@ __global__ __launch_bounds__(kGBlock) void wide_fit_kernel(int64_t n, int64_t G,
                 fit_out[g * (m + 1) + 1] = sigma;
             }
         }
-        if (fit_out && t >= 1 && t < m)  // the same expression as build_search
-            fit_out[g * (m + 1) + 1 + t] = (float)__dadd_rn((double)mu, __dmul_rn((double)sigma, kZDev[m][t]));
+        if (fit_out && tid >= 1 && tid < m)  // the same expression as build_search
+            fit_out[g * (m + 1) + 1 + tid] = (float)__dadd_rn((double)mu, __dmul_rn((double)sigma, kZDev[m][tid]));
         __syncthreads();
     }
 }
@@ -256,24 +400,23 @@ __device__ __forceinline__ void chunk_ranges(const float *__restrict__ x, const 
             [&](int k, int j) { return (packed[k >> 1] >> (16 * (k & 1) + 4 * j)) & 15u; }, r.len, lane, counters);
 }
 
-template <bool kCounts>
-__global__ __launch_bounds__(kGBlock) void wide_range_kernel(const float *__restrict__ x, int64_t n, int64_t G,
-                                                             int64_t chunks_per_group, int64_t chunks, int m,
-                                                             const GroupState *__restrict__ gs,
-                                                             ChunkRanges *__restrict__ ranges,
-                                                             ChunkCounts *__restrict__ counts)
+template <typename Src, bool kCounts>
+__global__ __launch_bounds__(kGBlock) void wide_range_kernel(Src src, WideSpace sp, int m)
 {
     __shared__ WaveShared shared[kGWaves];
     __shared__ uint32_t counters[kCounts ? kGWaves : 1][kMaxClusters * kWave];
     const int lane = threadIdx.x & (kWave - 1), wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int64_t c = (int64_t)blockIdx.x * kGWaves + wave;
-    if (c >= chunks)
+    const int64_t gc = (int64_t)blockIdx.x * kGWaves + wave;
+    if (gc >= src.chunks())
         return;
-    const ChunkRef r = chunk_ref(c, n, G, chunks_per_group);
+    int64_t c;
+    const WideTensor t = src.of_chunk(gc, c);
+    const float *x = (const float *)t.values;
+    const ChunkRef r = chunk_ref(c, t.n, t.G, t.cpg);
     float mn = INFINITY, mx = -INFINITY;
     uint32_t count = 0;
     if (r.len > 0) {
-        const float mu = gs[r.group].mu, sigma = gs[r.group].sigma;
+        const float mu = sp.gs[t.group0 + r.group].mu, sigma = sp.gs[t.group0 + r.group].sigma;
         uint32_t *col = counters[kCounts ? wave : 0];
         if (chunk_is_full(r))
             chunk_ranges<true, kCounts>(x, r, m, mu, sigma, shared[wave], col, lane, mn, mx, count);
@@ -281,10 +424,10 @@ __global__ __launch_bounds__(kGBlock) void wide_range_kernel(const float *__rest
             chunk_ranges<false, kCounts>(x, r, m, mu, sigma, shared[wave], col, lane, mn, mx, count);
     }
     if (lane < kMaxClusters) {
-        ranges[c].mn[lane] = mn;
-        ranges[c].mx[lane] = mx;
+        sp.ranges[t.chunk0 + c].mn[lane] = mn;
+        sp.ranges[t.chunk0 + c].mx[lane] = mx;
         if (kCounts)
-            counts[c].cnt[lane] = count;
+            sp.counts[t.chunk0 + c].cnt[lane] = count;
     }
 }
 
@@ -379,61 +522,52 @@ __device__ __forceinline__ void group_counts_scan(ChunkCounts *__restrict__ slic
     __syncthreads();
 }
 
-// grid: groups * slices_per_group workgroups, each over the (up to) 256 chunks of its slice
-template <bool kRanges, bool kCounts>
-__global__ __launch_bounds__(kGBlock) void wide_slice_kernel(int64_t n, int64_t G, int64_t chunks_per_group,
-                                                             int64_t slices_per_group, int64_t groups,
-                                                             const ChunkRanges *__restrict__ ranges,
-                                                             ChunkRanges *__restrict__ slice_ranges,
-                                                             ChunkCounts *__restrict__ counts,
-                                                             ChunkCounts *__restrict__ slice_counts)
+// grid: one workgroup per slice, each over the (up to) 256 chunks of its slice
+template <typename Src, bool kRanges, bool kCounts>
+__global__ __launch_bounds__(kGBlock) void wide_slice_kernel(Src src, WideSpace sp)
 {
     __shared__ float part[kGBlock];
-    const int64_t g = blockIdx.x / slices_per_group, sl = blockIdx.x % slices_per_group;
-    if (g >= groups)
+    if ((int64_t)blockIdx.x >= src.slices())
         return;
-    const int64_t g_lo = g * G;
-    const int64_t g_len = (g_lo + G <= n) ? G : (n - g_lo);
-    const int64_t nch = (g_len + kGChunk - 1) / kGChunk;
+    int64_t g, sl;
+    const WideTensor t = src.of_slice(blockIdx.x, g, sl);
+    const int64_t nch = (group_len(t, g) + kGChunk - 1) / kGChunk;
     const int64_t c0 = sl * kGSlice;
     const int64_t cnt = c0 >= nch ? 0 : (nch - c0 < kGSlice ? nch - c0 : kGSlice);
+    const int64_t chunk = t.chunk0 + g * t.cpg + c0, slice = t.slice0 + g * t.spg + sl;
     if (kRanges) {
-        reduce_range_rows(reinterpret_cast<const float *>(ranges + g * chunks_per_group + c0), cnt, part);
+        reduce_range_rows(reinterpret_cast<const float *>(sp.ranges + chunk), cnt, part);
         if (threadIdx.x < 32)
-            reinterpret_cast<float *>(slice_ranges + g * slices_per_group + sl)[threadIdx.x] = part[threadIdx.x];
+            reinterpret_cast<float *>(sp.slice_ranges + slice)[threadIdx.x] = part[threadIdx.x];
     }
     if (kCounts)
-        slice_counts_scan(counts + g * chunks_per_group + c0, cnt, slice_counts + g * slices_per_group + sl);
+        slice_counts_scan(sp.counts + chunk, cnt, sp.slice_counts + slice);
 }
 
 // One workgroup per group: slices -> min / max of every cluster -> (S, b), 255/S (Algorithm 2 step 4);
 // with kCounts also the slices' and clusters' places in the cluster-major arrangement.
-template <bool kRanges, bool kCounts>
-__global__ __launch_bounds__(kGBlock) void wide_group_kernel(int64_t n, int64_t G, int64_t slices_per_group,
-                                                             int64_t groups, int m,
-                                                             const ChunkRanges *__restrict__ slice_ranges, GroupState *gs,
-                                                             float *__restrict__ params,
-                                                             ChunkCounts *__restrict__ slice_counts,
-                                                             ChunkCounts *__restrict__ cluster_base)
+template <typename Src, bool kRanges, bool kCounts>
+__global__ __launch_bounds__(kGBlock) void wide_group_kernel(Src src, WideSpace sp, int m)
 {
     __shared__ float part[kGBlock];
-    for (int64_t g = blockIdx.x; g < groups; g += gridDim.x) {
-        const int64_t g_lo = g * G;
-        const int64_t g_len = (g_lo + G <= n) ? G : (n - g_lo);
-        const int64_t nch = (g_len + kGChunk - 1) / kGChunk;
+    for (int64_t gg = blockIdx.x; gg < src.groups(); gg += gridDim.x) {
+        int64_t g;
+        const WideTensor t = src.of_group(gg, g);
+        const int64_t nch = (group_len(t, g) + kGChunk - 1) / kGChunk;
         const int64_t nsl = (nch + kGSlice - 1) / kGSlice;
+        const int64_t slice = t.slice0 + g * t.spg;
         if (kRanges) {
-            reduce_range_rows(reinterpret_cast<const float *>(slice_ranges + g * slices_per_group), nsl, part);
+            reduce_range_rows(reinterpret_cast<const float *>(sp.slice_ranges + slice), nsl, part);
             if (threadIdx.x < kMaxClusters) {
                 float S, b, inv;
                 cluster_coder(part[threadIdx.x], part[kMaxClusters + threadIdx.x], S, b, inv);
-                gs[g].coder[threadIdx.x] = make_float2(b, inv);
+                sp.gs[t.group0 + g].coder[threadIdx.x] = make_float2(b, inv);
                 if ((int)threadIdx.x < m)
-                    *reinterpret_cast<float2 *>(params + (g * m + threadIdx.x) * 2) = make_float2(S, b);
+                    *reinterpret_cast<float2 *>(t.params + (g * m + threadIdx.x) * 2) = make_float2(S, b);
             }
         }
         if (kCounts)
-            group_counts_scan(slice_counts + g * slices_per_group, nsl, cluster_base + g);
+            group_counts_scan(sp.slice_counts + slice, nsl, sp.cluster_base + t.group0 + g);
     }
 }
 
@@ -454,54 +588,53 @@ __device__ __forceinline__ void chunk_codes(const float *__restrict__ x, const C
     code_pass<kGK, kFull>(v, r.lo, r.len, packed, ws, lane, codes);
 }
 
-__global__ __launch_bounds__(kGBlock) void wide_code_kernel(const float *__restrict__ x, int64_t n, int64_t G,
-                                                            int64_t chunks_per_group, int64_t chunks, int m,
-                                                            const GroupState *__restrict__ gs, uint8_t *__restrict__ labels,
-                                                            uint8_t *__restrict__ codes)
+template <typename Src>
+__global__ __launch_bounds__(kGBlock) void wide_code_kernel(Src src, WideSpace sp, int m)
 {
     __shared__ WaveShared shared[kGWaves];
     const int lane = threadIdx.x & (kWave - 1), wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int64_t c = (int64_t)blockIdx.x * kGWaves + wave;
-    if (c >= chunks)
+    const int64_t gc = (int64_t)blockIdx.x * kGWaves + wave;
+    if (gc >= src.chunks())
         return;
-    const ChunkRef r = chunk_ref(c, n, G, chunks_per_group);
+    int64_t c;
+    const WideTensor t = src.of_chunk(gc, c);
+    const ChunkRef r = chunk_ref(c, t.n, t.G, t.cpg);
     if (r.len == 0)
         return;
+    const GroupState &st = sp.gs[t.group0 + r.group];
     if (chunk_is_full(r))
-        chunk_codes<true>(x, r, m, gs[r.group], shared[wave], lane, labels, codes);
+        chunk_codes<true>((const float *)t.values, r, m, st, shared[wave], lane, t.labels, t.codes);
     else
-        chunk_codes<false>(x, r, m, gs[r.group], shared[wave], lane, labels, codes);
+        chunk_codes<false>((const float *)t.values, r, m, st, shared[wave], lane, t.labels, t.codes);
 }
 
-__global__ __launch_bounds__(kGBlock) void wide_dequantize_kernel(const uint8_t *__restrict__ codes,
-                                                                  const uint8_t *__restrict__ labels,
-                                                                  const float *__restrict__ params, int64_t n, int64_t G,
-                                                                  int64_t chunks_per_group, int64_t chunks, int m,
-                                                                  float *__restrict__ out)
+template <typename Src>
+__global__ __launch_bounds__(kGBlock) void wide_dequantize_kernel(Src src, int m)
 {
     __shared__ float2 coder[kGWaves][kMaxClusters];
     const int lane = threadIdx.x & (kWave - 1), wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int64_t c = (int64_t)blockIdx.x * kGWaves + wave;
-    if (c >= chunks)
+    const int64_t gc = (int64_t)blockIdx.x * kGWaves + wave;
+    if (gc >= src.chunks())
         return;
-    const ChunkRef r = chunk_ref(c, n, G, chunks_per_group);
+    int64_t c;
+    const WideTensor t = src.of_chunk(gc, c);
+    const ChunkRef r = chunk_ref(c, t.n, t.G, t.cpg);
     if (r.len == 0)
         return;
-    dequantize_group<kGK>(codes, labels, params, r.lo, r.len, (r.lo & 3) == 0, m, r.group, out, coder[wave], lane);
+    dequantize_group<kGK>(t.codes, t.labels, t.params, r.lo, r.len, (r.lo & 3) == 0, m, r.group, (float *)t.values,
+                          coder[wave], lane);
 }
 
 // ---- format variants: pass 3 and the dequantiser with a table and / or cluster-major codes
 
 // Where the chunk's run of cluster `lane` (< 16) starts, relative to the group's first code.
-__device__ __forceinline__ uint32_t segment_dest(const ChunkCounts *__restrict__ counts,
-                                                 const ChunkCounts *__restrict__ slice_counts,
-                                                 const ChunkCounts *__restrict__ cluster_base, int64_t c, int64_t group,
-                                                 int64_t chunks_per_group, int64_t slices_per_group, int lane)
+__device__ __forceinline__ uint32_t segment_dest(const WideSpace &sp, const WideTensor &t, int64_t c, int64_t group, int lane)
 {
     if (lane >= kMaxClusters)
         return 0;
-    const int64_t sl = (c % chunks_per_group) / kGSlice;
-    return cluster_base[group].cnt[lane] + slice_counts[group * slices_per_group + sl].cnt[lane] + counts[c].cnt[lane];
+    const int64_t sl = (c % t.cpg) / kGSlice;
+    return sp.cluster_base[t.group0 + group].cnt[lane] + sp.slice_counts[t.slice0 + group * t.spg + sl].cnt[lane] +
+           sp.counts[t.chunk0 + c].cnt[lane];
 }
 
 template <bool kFull, bool kTable, bool kMajor>
@@ -562,12 +695,8 @@ __device__ __forceinline__ void chunk_codes_ex(const float *__restrict__ x, cons
     wave_lds_sync();
 }
 
-template <bool kTable, bool kMajor>
-__global__ __launch_bounds__(kGBlock, 3) void wide_code_ex_kernel(
-    const float *__restrict__ x, int64_t n, int64_t G, int64_t chunks_per_group, int64_t slices_per_group, int64_t chunks,
-    int m, const GroupState *__restrict__ gs, const float *__restrict__ params, const float *__restrict__ qmap,
-    const ChunkCounts *__restrict__ counts, const ChunkCounts *__restrict__ slice_counts,
-    const ChunkCounts *__restrict__ cluster_base, uint8_t *__restrict__ labels, uint8_t *__restrict__ codes)
+template <typename Src, bool kTable, bool kMajor>
+__global__ __launch_bounds__(kGBlock, 3) void wide_code_ex_kernel(Src src, WideSpace sp, int m, const float *__restrict__ qmap)
 {
     __shared__ QuantizeShared shared[kGWaves];
     __shared__ TableShared table;
@@ -575,20 +704,23 @@ __global__ __launch_bounds__(kGBlock, 3) void wide_code_ex_kernel(
         load_table(table, qmap);
     // no workgroup barrier from here on
     const int lane = threadIdx.x & (kWave - 1), wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    for (int64_t c = (int64_t)blockIdx.x * kGWaves + wave; c < chunks; c += (int64_t)gridDim.x * kGWaves) {
-        const ChunkRef r = chunk_ref(c, n, G, chunks_per_group);
+    const int64_t chunks = src.chunks();
+    for (int64_t gc = (int64_t)blockIdx.x * kGWaves + wave; gc < chunks; gc += (int64_t)gridDim.x * kGWaves) {
+        int64_t c;
+        const WideTensor t = src.of_chunk(gc, c);
+        const ChunkRef r = chunk_ref(c, t.n, t.G, t.cpg);
         if (r.len == 0)
             continue;
-        const int64_t g_lo = r.group * G;
-        const int64_t g_len = (g_lo + G <= n) ? G : (n - g_lo);
-        const uint32_t dest =
-            kMajor ? segment_dest(counts, slice_counts, cluster_base, c, r.group, chunks_per_group, slices_per_group, lane) : 0u;
+        const int64_t g_lo = r.group * t.G;
+        const int64_t g_len = group_len(t, r.group);
+        const uint32_t dest = kMajor ? segment_dest(sp, t, c, r.group, lane) : 0u;
+        const GroupState &st = sp.gs[t.group0 + r.group];
         if (chunk_is_full(r))
-            chunk_codes_ex<true, kTable, kMajor>(x, r, m, gs[r.group], params, g_lo, g_len, dest, shared[wave], table, lane,
-                                                 labels, codes);
+            chunk_codes_ex<true, kTable, kMajor>((const float *)t.values, r, m, st, t.params, g_lo, g_len, dest, shared[wave],
+                                                 table, lane, t.labels, t.codes);
         else
-            chunk_codes_ex<false, kTable, kMajor>(x, r, m, gs[r.group], params, g_lo, g_len, dest, shared[wave], table, lane,
-                                                  labels, codes);
+            chunk_codes_ex<false, kTable, kMajor>((const float *)t.values, r, m, st, t.params, g_lo, g_len, dest, shared[wave],
+                                                  table, lane, t.labels, t.codes);
     }
 }
 
@@ -612,49 +744,52 @@ __device__ __forceinline__ void load_chunk_labels(const uint8_t *__restrict__ la
 }
 
 // Dequantisation of cluster-major codes, first pass: members of every cluster per chunk, from the labels.
-__global__ __launch_bounds__(kGBlock) void wide_label_counts_kernel(const uint8_t *__restrict__ labels, int64_t n, int64_t G,
-                                                                    int64_t chunks_per_group, int64_t chunks,
-                                                                    ChunkCounts *__restrict__ counts)
+template <typename Src>
+__global__ __launch_bounds__(kGBlock) void wide_label_counts_kernel(Src src, WideSpace sp)
 {
     __shared__ uint32_t counters[kGWaves][kMaxClusters * kWave];
     const int lane = threadIdx.x & (kWave - 1), wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int64_t c = (int64_t)blockIdx.x * kGWaves + wave;
-    if (c >= chunks)
+    const int64_t gc = (int64_t)blockIdx.x * kGWaves + wave;
+    if (gc >= src.chunks())
         return;
-    const ChunkRef r = chunk_ref(c, n, G, chunks_per_group);
+    int64_t c;
+    const WideTensor t = src.of_chunk(gc, c);
+    const ChunkRef r = chunk_ref(c, t.n, t.G, t.cpg);
     uint32_t count = 0;
     if (r.len > 0) {
         uint32_t l4[kGK];
-        load_chunk_labels(labels, r.lo, r.len, (r.lo & 3) == 0, lane, l4);
+        load_chunk_labels(t.labels, r.lo, r.len, (r.lo & 3) == 0, lane, l4);
         count = wave_label_counts<kGK, false>([&](int k, int j) { return (l4[k] >> (4 * j)) & 15u; }, r.len, lane,
                                               counters[wave]);
     }
     if (lane < kMaxClusters)
-        counts[c].cnt[lane] = count;
+        sp.counts[t.chunk0 + c].cnt[lane] = count;
 }
 
-template <bool kTable, bool kMajor>
-__global__ __launch_bounds__(kGBlock, 2) void wide_dequantize_ex_kernel(
-    const uint8_t *__restrict__ codes, const uint8_t *__restrict__ labels, const float *__restrict__ params, int64_t n,
-    int64_t G, int64_t chunks_per_group, int64_t slices_per_group, int64_t chunks, int m, const float *__restrict__ qmap,
-    const ChunkCounts *__restrict__ counts, const ChunkCounts *__restrict__ slice_counts,
-    const ChunkCounts *__restrict__ cluster_base, float *__restrict__ out)
+template <typename Src, bool kTable, bool kMajor>
+__global__ __launch_bounds__(kGBlock, 2) void wide_dequantize_ex_kernel(Src src, WideSpace sp, int m,
+                                                                        const float *__restrict__ qmap)
 {
     __shared__ DequantizeShared shared[kGWaves];
     __shared__ float table[kLevels];
     if (kTable)
         load_levels(table, qmap);
     const int lane = threadIdx.x & (kWave - 1), wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int64_t c = (int64_t)blockIdx.x * kGWaves + wave;
-    if (c >= chunks)
+    const int64_t gc = (int64_t)blockIdx.x * kGWaves + wave;
+    if (gc >= src.chunks())
         return;
-    const ChunkRef r = chunk_ref(c, n, G, chunks_per_group);
+    int64_t c;
+    const WideTensor t = src.of_chunk(gc, c);
+    const uint8_t *codes = t.codes, *labels = t.labels;
+    const float *params = t.params;
+    float *out = (float *)t.values;
+    const ChunkRef r = chunk_ref(c, t.n, t.G, t.cpg);
     if (r.len == 0)
         return;
     DequantizeShared &sh = shared[wave];
     const bool aligned = (r.lo & 3) == 0;
-    const int64_t g_lo = r.group * G;
-    const int64_t g_len = (g_lo + G <= n) ? G : (n - g_lo);
+    const int64_t g_lo = r.group * t.G;
+    const int64_t g_len = group_len(t, r.group);
     uint32_t c4[kGK], l4[kGK];
     load_chunk_labels(labels, r.lo, r.len, aligned, lane, l4);
     if (!kMajor) {
@@ -689,7 +824,7 @@ __global__ __launch_bounds__(kGBlock, 2) void wide_dequantize_ex_kernel(
         for (int k = 0; k < kGK; ++k)
             l16[k * kWave + lane] = (uint16_t)l4[k];
         wave_lds_sync();
-        const uint32_t dest = segment_dest(counts, slice_counts, cluster_base, c, r.group, chunks_per_group, slices_per_group, lane);
+        const uint32_t dest = segment_dest(sp, t, c, r.group, lane);
         uint8_t *b8 = (uint8_t *)mv.bytes;
         const int len = r.len;
         // The chunk's 16 runs of codes, collected once their places inside the chunk are known.  Lane l takes the
@@ -759,15 +894,9 @@ __global__ __launch_bounds__(kGBlock, 2) void wide_dequantize_ex_kernel(
     }
 }
 
-static void general_shape(int64_t n, int64_t group, int64_t &G, int64_t &groups, int64_t &cpg, int64_t &chunks,
-                          int64_t &spg)
-{
-    G = (group <= 0 || group > n) ? n : group;
-    groups = (n + G - 1) / G;
-    cpg = (G + kGChunk - 1) / kGChunk;
-    chunks = groups * cpg;
-    spg = (cpg + kGSlice - 1) / kGSlice;
-}
+// ---------------------------------------------------------------------------------------------
+// host side
+// ---------------------------------------------------------------------------------------------
 
 bool cluster_general_supported(int64_t n, int64_t group)
 {
@@ -776,15 +905,49 @@ bool cluster_general_supported(int64_t n, int64_t group)
     return group <= 0 || group >= n || (group % 2) == 0;  // a group boundary must not split a label byte
 }
 
-size_t cluster_general_workspace_bytes(int64_t n, int64_t group)
+// Workspace for `chunks` chunks in `slices` slices and `groups` groups; `major`: with the cluster
+// counts.  `extra` bytes (a multiple of 8) come first.
+static size_t space_bytes(int64_t chunks, int64_t slices, int64_t groups, bool major, size_t extra)
+{
+    size_t bytes = extra + (size_t)groups * sizeof(GroupState) +
+                   (size_t)(chunks + slices) * (sizeof(ChunkStats) + sizeof(ChunkRanges));
+    if (major)
+        bytes += (size_t)(chunks + slices + groups) * sizeof(ChunkCounts);
+    return (bytes + 255) / 256 * 256;
+}
+
+static WideSpace cut_space(void *workspace, int64_t chunks, int64_t slices, int64_t groups, size_t extra)
+{
+    static_assert(sizeof(GroupState) % 8 == 0 && sizeof(ChunkStats) % 8 == 0 && sizeof(ChunkRanges) % 8 == 0,
+                  "workspace parts stay 8-byte aligned");
+    WideSpace sp;
+    sp.gs = reinterpret_cast<GroupState *>((char *)workspace + extra);
+    sp.stats = reinterpret_cast<ChunkStats *>(sp.gs + groups);
+    sp.slice_stats = sp.stats + chunks;
+    sp.ranges = reinterpret_cast<ChunkRanges *>(sp.slice_stats + slices);
+    sp.slice_ranges = sp.ranges + chunks;
+    sp.counts = reinterpret_cast<ChunkCounts *>(sp.slice_ranges + slices);  // present only with cluster-major codes
+    sp.slice_counts = sp.counts + chunks;
+    sp.cluster_base = sp.slice_counts + slices;
+    return sp;
+}
+
+size_t cluster_general_workspace_bytes_ex(int64_t n, int64_t group, bool major)
 {
     if (n <= 0)
         return 0;
-    int64_t G, groups, cpg, chunks, spg;
-    general_shape(n, group, G, groups, cpg, chunks, spg);
-    const size_t bytes = (size_t)groups * sizeof(GroupState) +
-                         (size_t)(chunks + groups * spg) * (sizeof(ChunkStats) + sizeof(ChunkRanges));
-    return (bytes + 255) / 256 * 256;
+    const WideTensor t = wide_tensor(nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, n, group);
+    return space_bytes(t.groups * t.cpg, t.groups * t.spg, t.groups, major, 0);
+}
+
+size_t cluster_general_workspace_bytes(int64_t n, int64_t group) { return cluster_general_workspace_bytes_ex(n, group, false); }
+
+size_t cluster_list_workspace_bytes(int64_t total_chunks, int64_t count, bool major)
+{
+    if (total_chunks <= 0 || count <= 0)
+        return 0;
+    // every tensor has at most chunks/256 + 1 slices; the list of first slices comes first
+    return space_bytes(total_chunks, total_chunks / kGSlice + count, count, major, (size_t)(count + 1) * sizeof(int64_t));
 }
 
 static int general_grid(int64_t work)
@@ -793,157 +956,153 @@ static int general_grid(int64_t work)
     return (int)(work < 1 ? 1 : (work < cap ? work : cap));
 }
 
-int cluster_general_quantize(const float *x, int64_t n, int64_t group, int m, uint8_t *codes, uint8_t *labels,
-                             float *params, float *fit_out, const float *fit_in, uint32_t *status, void *workspace,
-                             hipStream_t s)
-{
-    int64_t G, groups, cpg, chunks, spg;
-    general_shape(n, group, G, groups, cpg, chunks, spg);
-    const int64_t blocks = (chunks + kGWaves - 1) / kGWaves, slices = groups * spg;
-    if (blocks > 0x7FFFFFFF || slices > 0x7FFFFFFF)
-        return BITSNAP_E_SIZE;
-    static_assert(sizeof(GroupState) % 8 == 0 && sizeof(ChunkStats) % 8 == 0, "workspace parts stay 8-byte aligned");
-    GroupState *gs = reinterpret_cast<GroupState *>(workspace);
-    ChunkStats *stats = reinterpret_cast<ChunkStats *>(gs + groups);
-    ChunkStats *slice_stats = stats + chunks;
-    ChunkRanges *ranges = reinterpret_cast<ChunkRanges *>(slice_stats + slices);
-    ChunkRanges *slice_ranges = ranges + chunks;
-    const dim3 block(kGBlock), cgrid((unsigned)blocks), sgrid((unsigned)slices), ggrid(general_grid(groups));
-    hipLaunchKernelGGL(wide_stats_kernel, cgrid, block, 0, s, x, n, G, cpg, chunks, stats);
-    hipLaunchKernelGGL(wide_slice_stats_kernel, sgrid, block, 0, s, n, G, cpg, spg, groups, stats, slice_stats);
-    hipLaunchKernelGGL(wide_fit_kernel, ggrid, block, 0, s, n, G, spg, groups, m, slice_stats, gs, fit_out, fit_in,
-                       status);
-    hipLaunchKernelGGL(wide_range_kernel<false>, cgrid, block, 0, s, x, n, G, cpg, chunks, m, gs, ranges,
-                       (ChunkCounts *)nullptr);
-    hipLaunchKernelGGL((wide_slice_kernel<true, false>), sgrid, block, 0, s, n, G, cpg, spg, groups, ranges, slice_ranges,
-                       (ChunkCounts *)nullptr, (ChunkCounts *)nullptr);
-    hipLaunchKernelGGL((wide_group_kernel<true, false>), ggrid, block, 0, s, n, G, spg, groups, m, slice_ranges, gs, params,
-                       (ChunkCounts *)nullptr, (ChunkCounts *)nullptr);
-    hipLaunchKernelGGL(wide_code_kernel, cgrid, block, 0, s, x, n, G, cpg, chunks, m, gs, labels, codes);
-    return launch_status();
-}
-
-int cluster_general_dequantize(const uint8_t *codes, const uint8_t *labels, const float *params, int64_t n,
-                               int64_t group, int m, float *out, hipStream_t s)
-{
-    int64_t G, groups, cpg, chunks, spg;
-    general_shape(n, group, G, groups, cpg, chunks, spg);
-    const int64_t blocks = (chunks + kGWaves - 1) / kGWaves;
-    if (blocks > 0x7FFFFFFF)
-        return BITSNAP_E_SIZE;
-    hipLaunchKernelGGL(wide_dequantize_kernel, dim3((unsigned)blocks), dim3(kGBlock), 0, s, codes, labels, params, n, G,
-                       cpg, chunks, m, out);
-    return launch_status();
-}
-
-// ---- host side of the format variants
-
-static size_t counts_bytes(int64_t chunks, int64_t slices, int64_t groups)
-{
-    return (size_t)(chunks + slices + groups) * sizeof(ChunkCounts);
-}
-
-size_t cluster_general_workspace_bytes_ex(int64_t n, int64_t group, bool major)
-{
-    if (n <= 0)
-        return 0;
-    if (!major)
-        return cluster_general_workspace_bytes(n, group);
-    int64_t G, groups, cpg, chunks, spg;
-    general_shape(n, group, G, groups, cpg, chunks, spg);
-    return cluster_general_workspace_bytes(n, group) + (counts_bytes(chunks, groups * spg, groups) + 255) / 256 * 256;
-}
-
 // Grid of the persistent pass-3 kernel when a table has to be prepared per workgroup.
-template <bool kTable, bool kMajor>
+template <typename Src, bool kTable, bool kMajor>
 static unsigned code_ex_grid(int64_t blocks)
 {
     if (!kTable)
         return (unsigned)blocks;
-    const void *kernel = (const void *)wide_code_ex_kernel<kTable, kMajor>;
+    const void *kernel = (const void *)wide_code_ex_kernel<Src, kTable, kMajor>;
     const int64_t resident = (int64_t)device_info().cu_count * occupancy_blocks_per_cu(kernel, kGBlock);
     return (unsigned)(blocks < resident ? blocks : resident);
+}
+
+// The three passes over `chunks` chunks, at most `slices` slices and `groups` groups of `src`.
+template <typename Src>
+static int quantize_passes(const Src &src, const WideSpace &sp, int64_t chunks, int64_t slices, int64_t groups, int m,
+                           bool major, const float *qmap, uint32_t *status, hipStream_t s)
+{
+    const int64_t blocks = (chunks + kGWaves - 1) / kGWaves;
+    if (blocks > 0x7FFFFFFF || slices > 0x7FFFFFFF)
+        return BITSNAP_E_SIZE;
+    const dim3 block(kGBlock), cgrid((unsigned)blocks), sgrid((unsigned)slices), ggrid(general_grid(groups));
+    hipLaunchKernelGGL(wide_stats_kernel<Src>, cgrid, block, 0, s, src, sp);
+    hipLaunchKernelGGL(wide_slice_stats_kernel<Src>, sgrid, block, 0, s, src, sp);
+    hipLaunchKernelGGL(wide_fit_kernel<Src>, ggrid, block, 0, s, src, sp, m, status);
+    if (major) {
+        hipLaunchKernelGGL((wide_range_kernel<Src, true>), cgrid, block, 0, s, src, sp, m);
+        hipLaunchKernelGGL((wide_slice_kernel<Src, true, true>), sgrid, block, 0, s, src, sp);
+        hipLaunchKernelGGL((wide_group_kernel<Src, true, true>), ggrid, block, 0, s, src, sp, m);
+    } else {
+        hipLaunchKernelGGL((wide_range_kernel<Src, false>), cgrid, block, 0, s, src, sp, m);
+        hipLaunchKernelGGL((wide_slice_kernel<Src, true, false>), sgrid, block, 0, s, src, sp);
+        hipLaunchKernelGGL((wide_group_kernel<Src, true, false>), ggrid, block, 0, s, src, sp, m);
+    }
+#define BITSNAP_CODE_EX(T, M)                                                                                     \
+    hipLaunchKernelGGL((wide_code_ex_kernel<Src, T, M>), dim3(code_ex_grid<Src, T, M>(blocks)), block, 0, s, src, sp, m, qmap)
+    if (qmap && major)
+        BITSNAP_CODE_EX(true, true);
+    else if (qmap)
+        BITSNAP_CODE_EX(true, false);
+    else if (major)
+        BITSNAP_CODE_EX(false, true);
+    else
+        hipLaunchKernelGGL(wide_code_kernel<Src>, cgrid, block, 0, s, src, sp, m);
+#undef BITSNAP_CODE_EX
+    return launch_status();
+}
+
+template <typename Src>
+static int dequantize_passes(const Src &src, const WideSpace &sp, int64_t chunks, int64_t slices, int64_t groups, int m,
+                             bool major, const float *qmap, hipStream_t s)
+{
+    const int64_t blocks = (chunks + kGWaves - 1) / kGWaves;
+    if (blocks > 0x7FFFFFFF || slices > 0x7FFFFFFF)
+        return BITSNAP_E_SIZE;
+    const dim3 block(kGBlock), cgrid((unsigned)blocks), sgrid((unsigned)slices), ggrid(general_grid(groups));
+    if (major) {
+        hipLaunchKernelGGL(wide_label_counts_kernel<Src>, cgrid, block, 0, s, src, sp);
+        hipLaunchKernelGGL((wide_slice_kernel<Src, false, true>), sgrid, block, 0, s, src, sp);
+        hipLaunchKernelGGL((wide_group_kernel<Src, false, true>), ggrid, block, 0, s, src, sp, m);
+    }
+#define BITSNAP_DEQ_EX(T, M) hipLaunchKernelGGL((wide_dequantize_ex_kernel<Src, T, M>), cgrid, block, 0, s, src, sp, m, qmap)
+    if (qmap && major)
+        BITSNAP_DEQ_EX(true, true);
+    else if (qmap)
+        BITSNAP_DEQ_EX(true, false);
+    else if (major)
+        BITSNAP_DEQ_EX(false, true);
+    else
+        hipLaunchKernelGGL(wide_dequantize_kernel<Src>, cgrid, block, 0, s, src, m);
+#undef BITSNAP_DEQ_EX
+    return launch_status();
 }
 
 int cluster_general_quantize_ex(const float *x, int64_t n, int64_t group, int m, bool major, const float *qmap,
                                 uint8_t *codes, uint8_t *labels, float *params, float *fit_out, const float *fit_in,
                                 uint32_t *status, void *workspace, hipStream_t s)
 {
-    int64_t G, groups, cpg, chunks, spg;
-    general_shape(n, group, G, groups, cpg, chunks, spg);
-    const int64_t blocks = (chunks + kGWaves - 1) / kGWaves, slices = groups * spg;
-    if (blocks > 0x7FFFFFFF || slices > 0x7FFFFFFF || (major && n > 0xFFFFFFFFll))
+    if (major && n > 0xFFFFFFFFll)
         return BITSNAP_E_SIZE;  // places inside a group are 32-bit
-    GroupState *gs = reinterpret_cast<GroupState *>(workspace);
-    ChunkStats *stats = reinterpret_cast<ChunkStats *>(gs + groups);
-    ChunkStats *slice_stats = stats + chunks;
-    ChunkRanges *ranges = reinterpret_cast<ChunkRanges *>(slice_stats + slices);
-    ChunkRanges *slice_ranges = ranges + chunks;
-    ChunkCounts *counts = reinterpret_cast<ChunkCounts *>((char *)workspace + cluster_general_workspace_bytes(n, group));
-    ChunkCounts *slice_counts = counts + chunks, *cluster_base = slice_counts + slices;
-    const dim3 block(kGBlock), cgrid((unsigned)blocks), sgrid((unsigned)slices), ggrid(general_grid(groups));
-    hipLaunchKernelGGL(wide_stats_kernel, cgrid, block, 0, s, x, n, G, cpg, chunks, stats);
-    hipLaunchKernelGGL(wide_slice_stats_kernel, sgrid, block, 0, s, n, G, cpg, spg, groups, stats, slice_stats);
-    hipLaunchKernelGGL(wide_fit_kernel, ggrid, block, 0, s, n, G, spg, groups, m, slice_stats, gs, fit_out, fit_in,
-                       status);
-    if (major) {
-        hipLaunchKernelGGL(wide_range_kernel<true>, cgrid, block, 0, s, x, n, G, cpg, chunks, m, gs, ranges, counts);
-        hipLaunchKernelGGL((wide_slice_kernel<true, true>), sgrid, block, 0, s, n, G, cpg, spg, groups, ranges, slice_ranges,
-                           counts, slice_counts);
-        hipLaunchKernelGGL((wide_group_kernel<true, true>), ggrid, block, 0, s, n, G, spg, groups, m, slice_ranges, gs,
-                           params, slice_counts, cluster_base);
-    } else {
-        hipLaunchKernelGGL(wide_range_kernel<false>, cgrid, block, 0, s, x, n, G, cpg, chunks, m, gs, ranges,
-                           (ChunkCounts *)nullptr);
-        hipLaunchKernelGGL((wide_slice_kernel<true, false>), sgrid, block, 0, s, n, G, cpg, spg, groups, ranges,
-                           slice_ranges, (ChunkCounts *)nullptr, (ChunkCounts *)nullptr);
-        hipLaunchKernelGGL((wide_group_kernel<true, false>), ggrid, block, 0, s, n, G, spg, groups, m, slice_ranges, gs,
-                           params, (ChunkCounts *)nullptr, (ChunkCounts *)nullptr);
-    }
-#define BITSNAP_CODE_EX(T, M)                                                                                           \
-    hipLaunchKernelGGL((wide_code_ex_kernel<T, M>), dim3(code_ex_grid<T, M>(blocks)), block, 0, s, x, n, G, cpg, spg, chunks, \
-                       m, gs, params, qmap, counts, slice_counts, cluster_base, labels, codes)
-    if (qmap && major)
-        BITSNAP_CODE_EX(true, true);
-    else if (qmap)
-        BITSNAP_CODE_EX(true, false);
-    else
-        BITSNAP_CODE_EX(false, true);
-#undef BITSNAP_CODE_EX
-    return launch_status();
+    OneTensor src;
+    src.t = wide_tensor(const_cast<float *>(x), codes, labels, params, fit_out, fit_in, n, group);
+    const int64_t chunks = src.t.groups * src.t.cpg, slices = src.t.groups * src.t.spg;
+    return quantize_passes(src, cut_space(workspace, chunks, slices, src.t.groups, 0), chunks, slices, src.t.groups, m, major,
+                           qmap, status, s);
+}
+
+int cluster_general_quantize(const float *x, int64_t n, int64_t group, int m, uint8_t *codes, uint8_t *labels,
+                             float *params, float *fit_out, const float *fit_in, uint32_t *status, void *workspace,
+                             hipStream_t s)
+{
+    return cluster_general_quantize_ex(x, n, group, m, false, nullptr, codes, labels, params, fit_out, fit_in, status,
+                                       workspace, s);
 }
 
 int cluster_general_dequantize_ex(const uint8_t *codes, const uint8_t *labels, const float *params, int64_t n,
                                   int64_t group, int m, bool major, const float *qmap, float *out, void *workspace,
                                   hipStream_t s)
 {
-    int64_t G, groups, cpg, chunks, spg;
-    general_shape(n, group, G, groups, cpg, chunks, spg);
-    const int64_t blocks = (chunks + kGWaves - 1) / kGWaves, slices = groups * spg;
-    if (blocks > 0x7FFFFFFF || slices > 0x7FFFFFFF || (major && n > 0xFFFFFFFFll))
+    if (major && n > 0xFFFFFFFFll)
         return BITSNAP_E_SIZE;
-    ChunkCounts *counts = major ? reinterpret_cast<ChunkCounts *>((char *)workspace + cluster_general_workspace_bytes(n, group))
-                                : nullptr;
-    ChunkCounts *slice_counts = counts + (major ? chunks : 0), *cluster_base = slice_counts + (major ? slices : 0);
-    const dim3 block(kGBlock), cgrid((unsigned)blocks), sgrid((unsigned)slices), ggrid(general_grid(groups));
+    OneTensor src;
+    src.t = wide_tensor(out, const_cast<uint8_t *>(codes), const_cast<uint8_t *>(labels), const_cast<float *>(params), nullptr,
+                        nullptr, n, group);
+    const int64_t chunks = src.t.groups * src.t.cpg, slices = src.t.groups * src.t.spg;
+    WideSpace sp = {};
+    if (major)
+        sp = cut_space(workspace, chunks, slices, src.t.groups, 0);
+    return dequantize_passes(src, sp, chunks, slices, src.t.groups, m, major, qmap, s);
+}
+
+int cluster_general_dequantize(const uint8_t *codes, const uint8_t *labels, const float *params, int64_t n,
+                               int64_t group, int m, float *out, hipStream_t s)
+{
+    return cluster_general_dequantize_ex(codes, labels, params, n, group, m, false, nullptr, out, nullptr, s);
+}
+
+// A list of tensors, one group each.  The workspace starts with the list of first slices.
+static TensorList list_source(const bitsnap_cluster_item *items, int64_t count, int64_t total_chunks, void *workspace,
+                              hipStream_t s)
+{
+    TensorList src;
+    src.items = items, src.count = count, src.total_chunks = total_chunks;
+    src.slice0 = reinterpret_cast<const int64_t *>(workspace);
+    hipLaunchKernelGGL(wide_list_slices_kernel, dim3(1), dim3(kGBlock), 0, s, items, count, reinterpret_cast<int64_t *>(workspace));
+    return src;
+}
+
+int cluster_list_quantize(const bitsnap_cluster_item *items, int64_t count, int64_t total_chunks, int m, bool major,
+                          const float *qmap, uint32_t *status, void *workspace, hipStream_t s)
+{
+    const int64_t slices = total_chunks / kGSlice + count;
+    const TensorList src = list_source(items, count, total_chunks, workspace, s);
+    return quantize_passes(src, cut_space(workspace, total_chunks, slices, count, (size_t)(count + 1) * sizeof(int64_t)),
+                           total_chunks, slices, count, m, major, qmap, status, s);
+}
+
+int cluster_list_dequantize(const bitsnap_cluster_item *items, int64_t count, int64_t total_chunks, int m, bool major,
+                            const float *qmap, void *workspace, hipStream_t s)
+{
+    const int64_t slices = total_chunks / kGSlice + count;
+    TensorList src;
+    src.items = items, src.count = count, src.total_chunks = total_chunks, src.slice0 = nullptr;
+    WideSpace sp = {};
     if (major) {
-        hipLaunchKernelGGL(wide_label_counts_kernel, cgrid, block, 0, s, labels, n, G, cpg, chunks, counts);
-        hipLaunchKernelGGL((wide_slice_kernel<false, true>), sgrid, block, 0, s, n, G, cpg, spg, groups,
-                           (const ChunkRanges *)nullptr, (ChunkRanges *)nullptr, counts, slice_counts);
-        hipLaunchKernelGGL((wide_group_kernel<false, true>), ggrid, block, 0, s, n, G, spg, groups, m,
-                           (const ChunkRanges *)nullptr, (GroupState *)nullptr, (float *)nullptr, slice_counts, cluster_base);
+        src = list_source(items, count, total_chunks, workspace, s);
+        sp = cut_space(workspace, total_chunks, slices, count, (size_t)(count + 1) * sizeof(int64_t));
     }
-#define BITSNAP_DEQ_EX(T, M)                                                                                            \
-    hipLaunchKernelGGL((wide_dequantize_ex_kernel<T, M>), cgrid, block, 0, s, codes, labels, params, n, G, cpg, spg, chunks, \
-                       m, qmap, counts, slice_counts, cluster_base, out)
-    if (qmap && major)
-        BITSNAP_DEQ_EX(true, true);
-    else if (qmap)
-        BITSNAP_DEQ_EX(true, false);
-    else
-        BITSNAP_DEQ_EX(false, true);
-#undef BITSNAP_DEQ_EX
-    return launch_status();
+    return dequantize_passes(src, sp, total_chunks, slices, count, m, major, qmap, s);
 }
 
 }  // namespace bitsnap

@@ -459,13 +459,25 @@ static void launch_dequantize_ex_batched(const bitsnap_cluster_item *items, int6
                        dim3(kVBlock), 0, s, items, count, total_groups, m, qmap);
 }
 
+extern "C" size_t bitsnap_cluster_chunk_elems(void) { return 4096; }
+
+extern "C" size_t bitsnap_cluster_batch_workspace_bytes(int64_t total_groups, int64_t count, int64_t group, uint32_t flags)
+{
+    if (group != 0)
+        return 0;
+    return cluster_list_workspace_bytes(total_groups, count, (flags & BITSNAP_CLUSTER_MAJOR) != 0);
+}
+
+// Checks shared by the two calls; 1 = go on, else the value to return.  group == 0 (one group per
+// tensor) takes the multi-pass kernels over the whole list and needs the workspace.
 static int check_ex_batched(const bitsnap_cluster_item *items, int64_t count, int64_t total_groups, int64_t group, int m,
-                            uint32_t flags, const float *qmap, const uint32_t *status, int &K)
+                            uint32_t flags, const float *qmap, const uint32_t *status, const void *workspace,
+                            size_t workspace_bytes, bool need_workspace, int &K)
 {
     if (count < 0 || total_groups < 0 || m < 1 || m > kMaxClusters || (flags & ~(uint32_t)BITSNAP_CLUSTER_MAJOR))
         return BITSNAP_E_SIZE;
     K = one_wave_group_k(group);
-    if (K == 0 || ex_batched_blocks(total_groups) > 0x7FFFFFFF)
+    if ((K == 0 && group != 0) || ex_batched_blocks(total_groups) > 0x7FFFFFFF)
         return BITSNAP_E_SIZE;
     if (count == 0 || total_groups == 0)
         return BITSNAP_OK;
@@ -473,21 +485,33 @@ static int check_ex_batched(const bitsnap_cluster_item *items, int64_t count, in
         return BITSNAP_E_NULL;
     if (((uintptr_t)items & 7u) || ((uintptr_t)status & 3u) || ((uintptr_t)qmap & 3u))
         return BITSNAP_E_ALIGN;
-    return 1;  // go on
+    if (K == 0 && need_workspace) {
+        if (!workspace)
+            return BITSNAP_E_NULL;
+        if (!aligned16(workspace))
+            return BITSNAP_E_ALIGN;
+        if (workspace_bytes < bitsnap_cluster_batch_workspace_bytes(total_groups, count, group, flags))
+            return BITSNAP_E_WORKSPACE;
+    }
+    return 1;
 }
 
 extern "C" int bitsnap_quantize_cluster_batched_ex(const bitsnap_cluster_item *items, int64_t count, int64_t total_groups,
                                                    int64_t group, int m, uint32_t flags, const float *qmap,
-                                                   uint32_t *status, bitsnap_stream_t stream)
+                                                   uint32_t *status, void *workspace, size_t workspace_bytes,
+                                                   bitsnap_stream_t stream)
 {
     int K = 0;
-    const int rc = check_ex_batched(items, count, total_groups, group, m, flags, qmap, status, K);
+    const int rc = check_ex_batched(items, count, total_groups, group, m, flags, qmap, status, workspace, workspace_bytes,
+                                    true, K);
     if (rc <= 0)
         return rc;
     const bool major = (flags & BITSNAP_CLUSTER_MAJOR) != 0;
+    hipStream_t s = (hipStream_t)stream;
+    if (K == 0)
+        return cluster_list_quantize(items, count, total_groups, m, major, qmap, status, workspace, s);
     if (!qmap && !major)
         return bitsnap_quantize_cluster_batched(items, count, total_groups, group, m, status, stream);
-    hipStream_t s = (hipStream_t)stream;
 #define BITSNAP_QB_TM(KK) launch_quantize_ex_batched<KK, true, true>(items, count, total_groups, m, qmap, status, s)
 #define BITSNAP_QB_T(KK) launch_quantize_ex_batched<KK, true, false>(items, count, total_groups, m, qmap, status, s)
 #define BITSNAP_QB_M(KK) launch_quantize_ex_batched<KK, false, true>(items, count, total_groups, m, qmap, status, s)
@@ -506,16 +530,19 @@ extern "C" int bitsnap_quantize_cluster_batched_ex(const bitsnap_cluster_item *i
 
 extern "C" int bitsnap_dequantize_cluster_batched_ex(const bitsnap_cluster_item *items, int64_t count, int64_t total_groups,
                                                      int64_t group, int m, uint32_t flags, const float *qmap,
-                                                     bitsnap_stream_t stream)
+                                                     void *workspace, size_t workspace_bytes, bitsnap_stream_t stream)
 {
     int K = 0;
-    const int rc = check_ex_batched(items, count, total_groups, group, m, flags, qmap, nullptr, K);
+    const bool major = (flags & BITSNAP_CLUSTER_MAJOR) != 0;
+    const int rc = check_ex_batched(items, count, total_groups, group, m, flags, qmap, nullptr, workspace, workspace_bytes,
+                                    major, K);
     if (rc <= 0)
         return rc;
-    const bool major = (flags & BITSNAP_CLUSTER_MAJOR) != 0;
+    hipStream_t s = (hipStream_t)stream;
+    if (K == 0)
+        return cluster_list_dequantize(items, count, total_groups, m, major, qmap, workspace, s);
     if (!qmap && !major)
         return bitsnap_dequantize_cluster_batched(items, count, total_groups, group, m, stream);
-    hipStream_t s = (hipStream_t)stream;
 #define BITSNAP_DB_TM(KK) launch_dequantize_ex_batched<KK, true, true>(items, count, total_groups, m, qmap, s)
 #define BITSNAP_DB_T(KK) launch_dequantize_ex_batched<KK, true, false>(items, count, total_groups, m, qmap, s)
 #define BITSNAP_DB_M(KK) launch_dequantize_ex_batched<KK, false, true>(items, count, total_groups, m, qmap, s)

@@ -4,6 +4,8 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include "../../include/bitsnap.h"
+
 namespace bitsnap {
 
 bool cluster_general_supported(int64_t n, int64_t group);
@@ -23,6 +25,14 @@ int cluster_general_quantize_ex(const float *x, int64_t n, int64_t group, int m,
 int cluster_general_dequantize_ex(const uint8_t *codes, const uint8_t *labels, const float *params, int64_t n,
                                   int64_t group, int m, bool major, const float *qmap, float *out, void *workspace,
                                   hipStream_t s);
+
+// A list of tensors with one group each (the batched form of group = 0): items[i].first_group
+// counts the 4096-element chunks of all earlier items, total_chunks all of them.
+size_t cluster_list_workspace_bytes(int64_t total_chunks, int64_t count, bool major);
+int cluster_list_quantize(const bitsnap_cluster_item *items, int64_t count, int64_t total_chunks, int m, bool major,
+                          const float *qmap, uint32_t *status, void *workspace, hipStream_t s);
+int cluster_list_dequantize(const bitsnap_cluster_item *items, int64_t count, int64_t total_chunks, int m, bool major,
+                            const float *qmap, void *workspace, hipStream_t s);
 
 // K (float4 per lane) of the one-wave-per-group kernels for a group length, or 0 when the length
 // needs the multi-pass path.

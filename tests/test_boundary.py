@@ -102,7 +102,7 @@ def test_cluster_format_variants_are_checked_on_the_host():
     plain = B.cluster_workspace_bytes(1 << 20, 0, 16)
     assert B.cluster_workspace_bytes_ex(1 << 20, 0, 16, 0) == plain
     chunks = (1 << 20) // 4096
-    assert B.cluster_workspace_bytes_ex(1 << 20, 0, 16, MAJOR) >= plain + 64 * (chunks + 1 + 1)
+    assert B.cluster_workspace_bytes_ex(1 << 20, 0, 16, MAJOR) > plain - 256 + 64 * (chunks + 1 + 1)   # sizes round up to 256
     q = lambda x, n, g, m, fl, tab, codes, labels, params, ws, wsb: L.bitsnap_quantize_cluster_ex(
         x, n, g, m, fl, tab, codes, labels, params, None, None, None, ws, wsb, None)
     assert q(a, 4096, 4096, 16, 2, None, a, a, a, None, 0) == -2            # unknown flag
@@ -120,9 +120,19 @@ def test_cluster_format_variants_are_checked_on_the_host():
     assert d(a, a, a, 8192, 0, 16, MAJOR, None, a, None, 0) == -1           # the partition needs the workspace here too
     assert d(a, a, a, 4096, 4096, 16, MAJOR, None, None, None, 0) == -1
     assert d(a, a, a, 4096, 4096, 16, MAJOR, None, a + 4, None, 0) == -3
-    qb = lambda items, count, groups, g, m, fl: L.bitsnap_quantize_cluster_batched_ex(items, count, groups, g, m, fl, None, None, None)
+    qb = lambda items, count, groups, g, m, fl, ws=None, wsb=0: L.bitsnap_quantize_cluster_batched_ex(
+        items, count, groups, g, m, fl, None, None, ws, wsb, None)
     assert qb(a, 1, 1, 1000, 16, MAJOR) == -2 and qb(a, 1, 1, 4096, 16, 8) == -2 and qb(None, 1, 1, 4096, 16, MAJOR) == -1
     assert qb(a, 0, 0, 4096, 16, MAJOR) == 0
+    # one group per tensor for a whole list: chunks are numbered, and a workspace is needed
+    assert B.cluster_chunk_elems() == 4096
+    assert B.cluster_batch_workspace_bytes(1000, 3, 4096, MAJOR) == 0
+    need = B.cluster_batch_workspace_bytes(1000, 3, 0, 0)
+    assert need >= 8 * 4 + 3 * 136 + (1000 + 3) * 144 and B.cluster_batch_workspace_bytes(1000, 3, 0, MAJOR) > need
+    assert qb(a, 3, 1000, 0, 16, 0) == -1 and qb(a, 3, 1000, 0, 16, 0, a, 64) == -4
+    db = lambda items, count, groups, g, m, fl, ws=None, wsb=0: L.bitsnap_dequantize_cluster_batched_ex(
+        items, count, groups, g, m, fl, None, ws, wsb, None)
+    assert db(a, 3, 1000, 0, 16, MAJOR) == -1 and db(a, 3, 1000, 2000, 16, 0) == -2
 
 
 def test_missing_library_fails_loudly(monkeypatch):

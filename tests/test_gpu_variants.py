@@ -248,7 +248,7 @@ def test_batched_variants_argument_checks():
         B.quantize_cluster_batched_ex(items, groups, 1000, 16, cluster_major=True)
     with pytest.raises(B.BitsnapError):
         B.quantize_cluster_batched_ex(items, groups, 4096, 0, cluster_major=True)
-    rc = B.lib().bitsnap_dequantize_cluster_batched_ex(items.data_ptr(), 1, groups, 4096, 16, 4, None, None)
+    rc = B.lib().bitsnap_dequantize_cluster_batched_ex(items.data_ptr(), 1, groups, 4096, 16, 4, None, None, 0, None)
     assert rc != 0                                                   # unknown flag
     torch.cuda.synchronize()
 
@@ -318,3 +318,46 @@ def test_whole_tensor_group_of_a_16m_element_tensor():
     assert np.array_equal(to_np(q.codes), o["codes"])
     assert np.array_equal(to_np(xh), oracle.dequantize_cluster_ex(o["codes"], o["labels"], o["params"], n, 0, 16, qmap=Q,
                                                                   cluster_major=True))
+
+
+@pytest.mark.parametrize("kind,major", [(None, False), (None, True), ("normal", False), ("square", True)])
+def test_one_group_per_tensor_for_a_whole_list(kind, major):
+    """The batched form of group = 0 gives, tensor by tensor, exactly what the single-tensor call gives (same chunk
+    and slice arithmetic), for tensors of one chunk, a few chunks, and more than one slice of chunks."""
+    announce("variants list group 0", kind, major)
+    sizes = [5 * 4096 + 17, 3, 4096, 1_300_003, 4095, 300 * 4096, 1, 70_000]
+    xs = [f32_to_dev(_states(200 + i, k)) for i, k in enumerate(sizes)]
+    Q = None if kind is None else synth.qmap_table(kind)
+    Qd = None if Q is None else f32_to_dev(Q)
+    flags = B.CLUSTER_MAJOR if major else 0
+    codes = [torch.zeros(k, dtype=torch.uint8, device=DEV) for k in sizes]
+    labels = [torch.zeros((k + 1) // 2, dtype=torch.uint8, device=DEV) for k in sizes]
+    params = [torch.zeros(1, 16, 2, dtype=torch.float32, device=DEV) for k in sizes]
+    fits = [torch.zeros(1, 17, dtype=torch.float32, device=DEV) for k in sizes]
+    status = torch.zeros(1, dtype=torch.int32, device=DEV)
+    items, chunks = B.cluster_items(xs, codes, labels, params, 0, fit_out=fits)
+    assert chunks == sum((k + 4095) // 4096 for k in sizes)
+    ws = torch.zeros(B.cluster_batch_workspace_bytes(chunks, len(sizes), 0, flags), dtype=torch.uint8, device=DEV)
+    B.quantize_cluster_batched_ex(items, chunks, 0, 16, qmap=Qd, cluster_major=major, status=status, workspace=ws)
+    outs = [torch.zeros(k, dtype=torch.float32, device=DEV) for k in sizes]
+    ditems, _ = B.cluster_items(outs, codes, labels, params, 0)
+    B.dequantize_cluster_batched_ex(ditems, chunks, 0, 16, qmap=Qd, cluster_major=major, workspace=ws)
+    torch.cuda.synchronize()
+    assert int(status.item()) == 0
+    for i, k in enumerate(sizes):
+        one = B.quantize_cluster_ex(xs[i], 0, 16, qmap=Qd, cluster_major=major)
+        back = B.dequantize_cluster_ex(one.codes, one.labels, one.params, k, 0, 16, qmap=Qd, cluster_major=major)
+        torch.cuda.synchronize()
+        assert torch.equal(fits[i], one.fit) and torch.equal(params[i], one.params), (i, k)
+        assert torch.equal(labels[i], one.labels) and torch.equal(codes[i], one.codes) and torch.equal(outs[i], back), (i, k)
+    # and the largest against the oracle
+    i = 3
+    o = oracle.quantize_cluster_ex(to_np(xs[i]), 0, 16, fit_in=to_np(fits[i])[:, :2].copy(), qmap=Q, cluster_major=major)
+    assert np.array_equal(to_np(codes[i]), o["codes"]) and np.array_equal(to_np(labels[i]), o["labels"])
+    assert np.array_equal(to_np(params[i]), o["params"])
+    assert np.array_equal(to_np(outs[i]), oracle.dequantize_cluster_ex(o["codes"], o["labels"], o["params"], sizes[i], 0, 16,
+                                                                        qmap=Q, cluster_major=major))
+    # a second call with the same workspace (nothing in it needs clearing)
+    B.quantize_cluster_batched_ex(items, chunks, 0, 16, qmap=Qd, cluster_major=major, status=status, workspace=ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(to_np(codes[i]), o["codes"])
