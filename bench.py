@@ -254,6 +254,22 @@ def main():
             "what": "group = 0 (one fit per tensor), first-moment state, one call per tensor, 3 passes over x",
             "ms": round(whole_ms, 3), "api_calls": len(gcalls), "state_GBps": round(4 * n_total / whole_ms / 1e6, 1),
             "hbm_GBps": round(whole_alg / whole_ms / 1e6, 1), "hbm_frac": round(whole_alg / whole_ms / 1e6 / HBM_PEAK_GBS, 4)}}
+        del gws
+        # the same through one batched call for the whole state (the passes then stream over the list of tensors)
+        lparams = [torch.empty(1, M, 2, dtype=f32, device=dev) for _ in sizes]
+        litems, lchunks = B.cluster_items([d["m"] for d in inputs], [e["q"][1]["codes"] for e in enc],
+                                          [e["q"][1]["labels"] for e in enc], lparams, 0)
+        lws = torch.zeros(B.cluster_batch_workspace_bytes(lchunks, len(sizes), 0, 0), dtype=u8, device=dev)
+        for it in range(2):
+            e0.record(stream)
+            B.quantize_cluster_batched_ex(litems, lchunks, 0, M, status=status, workspace=lws)
+            e1.record(stream)
+            torch.cuda.synchronize()
+        list_ms = e0.elapsed_time(e1)
+        extras["quantize_whole_tensor_fit"]["batched"] = {
+            "ms": round(list_ms, 3), "api_calls": 1, "hbm_GBps": round(whole_alg / list_ms / 1e6, 1),
+            "hbm_frac": round(whole_alg / list_ms / 1e6 / HBM_PEAK_GBS, 4)}
+        del lws, lparams, litems
         # steady state on the single largest tensor: each op alone, five calls in a row
         big = max(range(len(sizes)), key=lambda i: sizes[i])
         nb = sizes[big]
