@@ -479,6 +479,8 @@ static int check_ex_batched(const bitsnap_cluster_item *items, int64_t count, in
     K = one_wave_group_k(group);
     if ((K == 0 && group != 0) || ex_batched_blocks(total_groups) > 0x7FFFFFFF)
         return BITSNAP_E_SIZE;
+    if (K == 0 && (count > 0x3FFFFFFF || total_groups / 256 + count > 0x7FFFFFFF))  // grid of the slice kernels
+        return BITSNAP_E_SIZE;
     if (count == 0 || total_groups == 0)
         return BITSNAP_OK;
     if (!items)
