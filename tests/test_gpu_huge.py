@@ -97,3 +97,67 @@ def test_cluster_pair_beyond_two_to_the_31_elements():
     # every element is within half a code step of its cluster's range (a property that holds at any size)
     err = (xh - x).abs_()
     assert float(err.max().item()) <= 1e-3 * 12 / 255
+
+
+def _pieces(n, step=1 << 28):
+    return [(lo, min(n, lo + step)) for lo in range(0, n, step)]
+
+
+def test_whole_tensor_group_beyond_two_to_the_31_elements():
+    """group = 0 on 2^31 + 12 365 elements: 524 292 chunks in 2049 slices, one fit, one cluster-major arrangement."""
+    n = (1 << 31) + 3 * 4096 + 77
+    announce("huge whole-tensor group", n)
+    g = torch.Generator(device=DEV)
+    g.manual_seed(80)
+    x = torch.empty(n, dtype=torch.float32, device=DEV)
+    for lo, hi in _pieces(n):
+        x[lo:hi].normal_(2e-4, 1e-3, generator=g)
+    q = B.quantize_cluster(x, 0, 16)
+    torch.cuda.synchronize()
+    assert int(q.status.item()) == 0
+    # the fit against torch's fp64 reductions
+    mean = sum(float(x[lo:hi].double().sum().item()) for lo, hi in _pieces(n)) / n
+    var = sum(float(((x[lo:hi].double() - mean) ** 2).sum().item()) for lo, hi in _pieces(n)) / n
+    fit = to_np(q.fit)[0]
+    assert abs(fit[0] - mean) <= 1e-6 * max(abs(mean), var ** 0.5) and abs(fit[1] - var ** 0.5) <= 1e-6 * var ** 0.5
+    assert np.array_equal(fit[2:], oracle.cluster_edges(fit[0], fit[1], 16))
+    # labels = number of edges <= x (torch.bucketize), (S, b) = range of every cluster
+    edges = torch.from_numpy(fit[2:].copy()).to(DEV)
+    lab = torch.empty(n, dtype=torch.uint8, device=DEV)
+    for lo, hi in _pieces(n):
+        lab[lo:hi] = torch.bucketize(x[lo:hi], edges, right=True).to(torch.uint8)
+    packed = q.labels
+    assert torch.equal(packed[: n // 2], lab[0:n - 1:2] | (lab[1:n:2] << 4)) and int(packed[n // 2].item()) == int(lab[n - 1].item())
+    params = to_np(q.params)[0]
+    lows, highs = [], []
+    for c in range(16):
+        mn = min(float(x[lo:hi][lab[lo:hi] == c].min().item()) for lo, hi in _pieces(n))
+        mx = max(float(x[lo:hi][lab[lo:hi] == c].max().item()) for lo, hi in _pieces(n))
+        assert params[c, 1] == np.float32(mn) and params[c, 0] == np.float32(mx) - np.float32(mn), c
+        lows.append(mn), highs.append(mx)
+    # codes of sampled stretches through the oracle: a small tensor that holds the stretch and every cluster's two
+    # extremes has the same (S, b), so its codes for the stretch are the whole tensor's
+    ends = np.array(lows + highs, np.float32)
+    xh = B.dequantize_cluster(q.codes, q.labels, q.params, n, 0, 16)
+    torch.cuda.synchronize()
+    for lo in (0, 123_456 * 4096, (1 << 31) - 2048, n - 5000):
+        xs = np.concatenate([to_np(x[lo:lo + 5000]), ends])
+        o = oracle.quantize_cluster(xs, 0, 16, fit_in=fit[:2].reshape(1, 2).copy())
+        assert np.array_equal(o["params"][0], params)
+        assert np.array_equal(to_np(q.codes[lo:lo + 5000]), o["codes"][:5000]), lo
+        assert np.array_equal(to_np(xh[lo:lo + 5000]),
+                              oracle.dequantize_cluster(o["codes"], o["labels"], o["params"], xs.size, 0, 16)[:5000]), lo
+    # cluster-major codes: cluster c's run is the selection of its members' codes, in element order
+    qm = B.quantize_cluster_ex(x, 0, 16, cluster_major=True)
+    torch.cuda.synchronize()
+    assert torch.equal(qm.labels, q.labels) and torch.equal(qm.params, q.params)
+    pos = 0
+    for c in range(16):
+        for lo, hi in _pieces(n):
+            sel = q.codes[lo:hi][lab[lo:hi] == c]
+            assert torch.equal(qm.codes[pos:pos + sel.numel()], sel), (c, lo)
+            pos += sel.numel()
+    assert pos == n
+    back = B.dequantize_cluster_ex(qm.codes, qm.labels, qm.params, n, 0, 16, cluster_major=True, workspace=qm.workspace)
+    torch.cuda.synchronize()
+    assert torch.equal(back, xh)
