@@ -116,19 +116,26 @@ __device__ __forceinline__ void to_cluster_major(const MajorView &mv, int len, i
     major_positions<K, kFull>(mv, lh, len, lane);  // its barriers also order the reads above before the writes below
     start = cluster_start(mv, len, lane);
     uint8_t *b8 = (uint8_t *)mv.bytes;
+    // positions are handed out kWalk elements at a time: one LDS round trip per batch, not per element
+    constexpr int kWalk = 4 * (K >= 4 ? 4 : K);
 #pragma unroll
-    for (int i = 0; i < K; ++i) {
-        uint32_t pos[4];
+    for (int e0 = 0; e0 < 4 * K; e0 += kWalk) {
+        uint32_t pos[kWalk];
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            pos[j] = 0;
-            if (kFull || lane * 4 * K + 4 * i + j < len)
-                pos[j] = lds_fetch_add(&mv.counters[((lh[i] >> (4 * j)) & 15u) * kWave + lane], 1u);
+        for (int e = 0; e < kWalk; ++e) {
+            const int i = (e0 + e) >> 2, j = (e0 + e) & 3;
+            pos[e] = 0;
+            if (kFull || lane * 4 * K + e0 + e < len)
+                pos[e] = lds_fetch_add(&mv.counters[((lh[i] >> (4 * j)) & 15u) * kWave + lane], 1u);
         }
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
-            if (kFull || lane * 4 * K + 4 * i + j < len)
-                b8[pos[j]] = (uint8_t)(cw[i] >> (8 * j));
+        for (int e = 0; e < kWalk; ++e) {
+            const int i = (e0 + e) >> 2, j = (e0 + e) & 3;
+            if (kFull || lane * 4 * K + e0 + e < len)
+                b8[pos[e]] = (uint8_t)(cw[i] >> (8 * j));
+        }
     }
     wave_lds_sync();
 }
@@ -149,20 +156,32 @@ __device__ __forceinline__ void from_cluster_major(const MajorView &mv, int len,
     major_positions<K, kFull>(mv, lh, len, lane);
     fill(cluster_start(mv, len, lane));
     const uint8_t *b8 = (const uint8_t *)mv.bytes;
+    constexpr int kWalk = 4 * (K >= 4 ? 4 : K);
 #pragma unroll
-    for (int i = 0; i < K; ++i) {
-        uint32_t pos[4];
+    for (int i = 0; i < K; ++i)
         cw[i] = 0;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            pos[j] = 0;
-            if (kFull || lane * 4 * K + 4 * i + j < len)
-                pos[j] = lds_fetch_add(&mv.counters[((lh[i] >> (4 * j)) & 15u) * kWave + lane], 1u);
-        }
+    for (int e0 = 0; e0 < 4 * K; e0 += kWalk) {
+        uint32_t pos[kWalk], got[kWalk];
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
-            if (kFull || lane * 4 * K + 4 * i + j < len)
-                cw[i] |= (uint32_t)b8[pos[j]] << (8 * j);
+        for (int e = 0; e < kWalk; ++e) {
+            const int i = (e0 + e) >> 2, j = (e0 + e) & 3;
+            pos[e] = 0;
+            if (kFull || lane * 4 * K + e0 + e < len)
+                pos[e] = lds_fetch_add(&mv.counters[((lh[i] >> (4 * j)) & 15u) * kWave + lane], 1u);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int e = 0; e < kWalk; ++e)
+            got[e] = b8[pos[e]];  // position 0 for an element that does not exist: in bounds, ignored
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int e = 0; e < kWalk; ++e) {
+            const int i = (e0 + e) >> 2, j = (e0 + e) & 3;
+            if (kFull || lane * 4 * K + e0 + e < len)
+                cw[i] |= got[e] << (8 * j);
+        }
     }
     wave_lds_sync();  // every lane has fetched its codes before the element-order copy overwrites them
 #pragma unroll
