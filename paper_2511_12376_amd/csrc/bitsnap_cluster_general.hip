@@ -20,6 +20,10 @@
 // chunk inside the wave and copies each cluster's run of codes to
 //   group start + cluster base + slice base + chunk offset.
 // Dequantisation rebuilds the same sums from the stored labels and collects the runs again.
+//
+// Every kernel takes its chunks, slices and groups from a "source": one tensor with any group
+// length, or a list of tensors with one group each, numbered across the list, so that a pass
+// over a whole checkpoint state is one launch.
 #include <hip/hip_runtime.h>
 #include <math.h>
 #include <stdint.h>
