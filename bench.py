@@ -314,6 +314,29 @@ def main():
         fn(*a)
         torch.cuda.synchronize()
 
+        # decode given the encoder's tile offsets (4 bytes per 32768 elements kept with the mask): no counting
+        # pass over the mask, one launch for the whole list
+        T2 = B.sparse_tile_elems(2)
+        offs = [torch.empty((n + T2 - 1) // T2, dtype=torch.int32, device=dev) for n in sizes]
+        o_enc_items, _ = B.sparse_items(sizes, src=[d["cur"] for d in inputs], base=[d["base"] for d in inputs],
+                                        mask=[e["mask"] for e in enc], payload=[e["payload"] for e in enc],
+                                        n_changed=[e["n_changed"] for e in enc], tile_offsets=offs)
+        B.encode_sparse_batched(o_enc_items, total_tiles, bws)
+        o_dec_items, _ = B.sparse_items(sizes, base=[d["base"] for d in inputs], mask=[e["mask"] for e in enc],
+                                        payload=[e["payload"] for e in enc], out=dec_out, tile_offsets=offs)
+        for it in range(2):
+            e0.record(stream)
+            B.decode_sparse_batched(o_dec_items, total_tiles, bws, flags=B.SPARSE_OFFSETS)
+            e1.record(stream)
+            torch.cuda.synchronize()
+        od_ms = e0.elapsed_time(e1)
+        assert all(torch.equal(o.view(i16), d["cur"].view(i16)) for o, d in list(zip(dec_out, inputs))[:4])
+        od_alg = 4 * n_total + sum((n + 7) // 8 for n in sizes) + 2 * ex_nc
+        extras["decode_sparse_with_encoder_tile_offsets"] = {
+            "what": "batched decode that reads the encoder's tile_offsets instead of counting the mask first",
+            "ms": round(od_ms, 3), "hbm_frac": round(od_alg / od_ms / 1e6 / HBM_PEAK_GBS, 4)}
+        del offs, o_enc_items, o_dec_items
+
         # the sparse codec on 4-byte elements: the largest tensor's fp32 master weights against a copy in which
         # 30 % of the elements have their lowest mantissa bit flipped (one call each, the steady state of a big tensor)
         m32 = inputs[big]["master"].view(torch.int32)

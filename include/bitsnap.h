@@ -131,7 +131,8 @@ int bitsnap_decode_sparse(const void *base, const uint8_t *mask, const void *pay
                           void *workspace, size_t workspace_bytes, bitsnap_stream_t stream);
 
 /* Options of the extended sparse entry points (flags). */
-#define BITSNAP_SPARSE_DELTA 1u /* the payload holds cur XOR base, not cur (see below) */
+#define BITSNAP_SPARSE_DELTA 1u   /* the payload holds cur XOR base, not cur (see below) */
+#define BITSNAP_SPARSE_OFFSETS 2u /* batched decode: every item carries the encoder's tile_offsets */
 
 /* bitsnap_encode_sparse with two options.
  *   flags & BITSNAP_SPARSE_DELTA   the payload holds the non-zero elements of the delta states
@@ -150,10 +151,15 @@ int bitsnap_encode_sparse_ex(const void *cur, const void *base, int64_t n, int e
                              void *workspace, size_t workspace_bytes, bitsnap_stream_t stream);
 
 /* bitsnap_decode_sparse for a payload written with the same flags:
- * out[i] = bit i of mask ? (DELTA ? base[i] XOR next payload element : next payload element) : base[i]. */
+ * out[i] = bit i of mask ? (DELTA ? base[i] XOR next payload element : next payload element) : base[i].
+ *   tile_offsets  nullable; [ceil(n / tile_elems)] uint32 in: the array the encoder wrote for this
+ *                 tensor.  With it the decoder does not count the mask first (one launch instead of
+ *                 three); n must be below 2^32, and payload_elems must not be below the number of
+ *                 changed elements.  Offsets that do not belong to the mask give unspecified output
+ *                 values, inside out[0..n). */
 int bitsnap_decode_sparse_ex(const void *base, const uint8_t *mask, const void *payload,
-                             int64_t payload_elems, int64_t n, int elem_bytes, uint32_t flags, void *out,
-                             uint64_t *n_changed,
+                             int64_t payload_elems, int64_t n, int elem_bytes, uint32_t flags,
+                             const uint32_t *tile_offsets, void *out, uint64_t *n_changed,
                              void *workspace, size_t workspace_bytes, bitsnap_stream_t stream);
 
 /* Host-side knob for tests of the give-up path: the number of polls a workgroup spends waiting
@@ -277,7 +283,7 @@ typedef struct bitsnap_sparse_item {
     void *payload;           /* encode: [capacity] out;             decode: [capacity] in               */
     void *out;               /* decode: [n] out (may equal base);   encode: unused (_ex: new_base)      */
     uint64_t *n_changed;     /* [1] out; required for encode, nullable for decode                       */
-    uint32_t *tile_offsets;  /* encode: nullable, [ceil(n/tile_elems)] out;   decode: unused            */
+    uint32_t *tile_offsets;  /* encode: nullable, [ceil(n/tile_elems)] out;   decode (_ex, OFFSETS): in */
     int64_t n;               /* elements, > 0                                                           */
     int64_t capacity;        /* encode: payload capacity in elements;   decode: payload elements        */
     int64_t first_tile;      /* sum of ceil(n/tile_elems) over all earlier items                        */
@@ -298,7 +304,9 @@ int bitsnap_decode_sparse_batched(const bitsnap_sparse_item *items, int64_t coun
 
 /* The batched calls with the options of bitsnap_encode_sparse_ex / bitsnap_decode_sparse_ex and the
  * element width (2 or 4; first_tile and total_tiles count tiles of bitsnap_sparse_tile_elems_for(elem_bytes)
- * elements).  In the encoder an item's `out`, where not NULL, is that tensor's new_base. */
+ * elements).  In the encoder an item's `out`, where not NULL, is that tensor's new_base.  The decoder
+ * takes BITSNAP_SPARSE_OFFSETS: every item's tile_offsets is the array the encoder wrote (every
+ * n < 2^32; the caller sees to that), and the list is decoded in one launch. */
 int bitsnap_encode_sparse_batched_ex(const bitsnap_sparse_item *items, int64_t count, int64_t total_tiles,
                                      int elem_bytes, uint32_t flags, void *workspace, size_t workspace_bytes,
                                      bitsnap_stream_t stream);

@@ -64,7 +64,7 @@ def lib():
     L.bitsnap_decode_sparse.restype = i
     L.bitsnap_encode_sparse_ex.argtypes = [p, p, i64, i, C.c_uint32, p, p, i64, p, p, p, p, sz, p]
     L.bitsnap_encode_sparse_ex.restype = i
-    L.bitsnap_decode_sparse_ex.argtypes = [p, p, p, i64, i64, i, C.c_uint32, p, p, p, sz, p]
+    L.bitsnap_decode_sparse_ex.argtypes = [p, p, p, i64, i64, i, C.c_uint32, p, p, p, p, sz, p]
     L.bitsnap_decode_sparse_ex.restype = i
     L.bitsnap_encode_sparse_batched_ex.argtypes = [p, i64, i64, i, C.c_uint32, p, sz, p]
     L.bitsnap_encode_sparse_batched_ex.restype = i
@@ -198,6 +198,7 @@ def new_sparse_workspace(n: int, device, elem_bytes: int = 2):
 # the four codecs.  Raw forms take every buffer; the caller allocates.
 # ----------------------------------------------------------------------------------------------
 SPARSE_DELTA = 1  # BITSNAP_SPARSE_DELTA
+SPARSE_OFFSETS = 2  # BITSNAP_SPARSE_OFFSETS (batched decode)
 CLUSTER_MAJOR = 1  # BITSNAP_CLUSTER_MAJOR
 
 
@@ -217,15 +218,17 @@ def encode_sparse_raw(cur, base, n: int, mask, payload, payload_capacity: int, t
 
 
 def decode_sparse_raw(base, mask, payload, payload_elems: int, n: int, out, n_changed, workspace, stream=None, *,
-                      flags: int = 0, elem_bytes: int = 2) -> None:
+                      flags: int = 0, elem_bytes: int = 2, tile_offsets=None) -> None:
+    """tile_offsets: the encoder's array for this tensor; the decoder then skips its counting pass."""
     wsb = workspace.numel() * workspace.element_size()
-    if flags == 0:
+    if flags == 0 and tile_offsets is None:
         rc = lib().bitsnap_decode_sparse(_ptr(base), _ptr(mask), _ptr(payload), payload_elems, n, elem_bytes, _ptr(out),
                                          _ptr(n_changed), _ptr(workspace), wsb, _stream(stream))
         _check(rc, "bitsnap_decode_sparse")
     else:
-        rc = lib().bitsnap_decode_sparse_ex(_ptr(base), _ptr(mask), _ptr(payload), payload_elems, n, elem_bytes, flags, _ptr(out),
-                                            _ptr(n_changed), _ptr(workspace), wsb, _stream(stream))
+        rc = lib().bitsnap_decode_sparse_ex(_ptr(base), _ptr(mask), _ptr(payload), payload_elems, n, elem_bytes, flags,
+                                            _ptr(tile_offsets), _ptr(out), _ptr(n_changed), _ptr(workspace), wsb,
+                                            _stream(stream))
         _check(rc, "bitsnap_decode_sparse_ex")
 
 
@@ -301,8 +304,9 @@ def encode_sparse(cur, base, *, capacity: Optional[int] = None, want_offsets: bo
 
 
 def decode_sparse(base, mask, payload, payload_elems: int, *, out=None, workspace=None, stream=None,
-                  delta: bool = False):
-    """-> (out, n_changed[1] device).  ``out`` defaults to a new tensor like ``base``."""
+                  delta: bool = False, tile_offsets=None):
+    """-> (out, n_changed[1] device).  ``out`` defaults to a new tensor like ``base``.  tile_offsets: the encoder's
+    (encode_sparse(..., want_offsets=True)); the decoder then runs one kernel instead of three."""
     import torch
     base_f = _flat_elems(base)
     n = base_f.numel()
@@ -314,7 +318,7 @@ def decode_sparse(base, mask, payload, payload_elems: int, *, out=None, workspac
     if workspace is None:
         workspace = new_sparse_workspace(n, base.device, eb)
     decode_sparse_raw(base_f, mask, payload, payload_elems, n, out_f, n_changed, workspace, stream,
-                      flags=SPARSE_DELTA if delta else 0, elem_bytes=eb)
+                      flags=SPARSE_DELTA if delta else 0, elem_bytes=eb, tile_offsets=tile_offsets)
     return out, n_changed
 
 

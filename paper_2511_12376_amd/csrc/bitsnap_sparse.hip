@@ -606,7 +606,11 @@ __global__ __launch_bounds__(kBlock) void decode_scan_kernel(bitsnap_sparse_item
 // all requested at once; the segment goes through LDS as aligned 16-byte pieces (stage[i] holds
 // payload element src0 + i, src0 a multiple of 16 / E), from where every lane picks its elements
 // by rank.  kDelta: the payload holds cur XOR base; the element is base XOR payload.
-template <bool kBatched, bool kDelta, int E>
+// kOffsets: the tensor comes with the encoder's tile_offsets, so the tile's place in the payload
+// is read from there and no counting pass ran; the tile's length is the distance to the next
+// offset, and for the tensor's last tile whatever the payload still holds, at most a tile's worth
+// (reading more than the tile's own values is harmless: only ranks below its count are used).
+template <bool kBatched, bool kDelta, bool kOffsets, int E>
 __global__ __launch_bounds__(kBlock, 4) void decode_merge_kernel(bitsnap_sparse_item single,
                                                                  const bitsnap_sparse_item *__restrict__ items,
                                                                  int64_t count, const uint64_t *__restrict__ tile_offset,
@@ -627,8 +631,20 @@ __global__ __launch_bounds__(kBlock, 4) void decode_merge_kernel(bitsnap_sparse_
     const int64_t n = it.n, payload_elems = it.capacity, tile = gtile - it.first_tile;
     const int64_t mask_bytes = (n + 7) >> 3;
 
-    const uint64_t excl = tile_offset[gtile];
-    const uint32_t total = tile_count[gtile];
+    uint64_t excl;
+    uint32_t total;
+    const bool last_tile = (tile + 1) * (int64_t)kTileElems >= n;
+    if (kOffsets) {
+        // the same for every thread: kept in scalar registers
+        const uint32_t here = __builtin_amdgcn_readfirstlane(it.tile_offsets[tile]);
+        const uint32_t next = last_tile ? 0u : __builtin_amdgcn_readfirstlane(it.tile_offsets[tile + 1]);
+        excl = here;
+        const int64_t rest = last_tile ? payload_elems - (int64_t)here : (int64_t)next - (int64_t)here;
+        total = __builtin_amdgcn_readfirstlane(rest <= 0 ? 0u : rest < kTileElems ? (uint32_t)rest : (uint32_t)kTileElems);
+    } else {
+        excl = tile_offset[gtile];
+        total = tile_count[gtile];
+    }
     const uint32_t shift = (uint32_t)(excl & (P - 1u));
     const int64_t src0 = (int64_t)(excl - shift);
     const uint32_t pieces = (shift + total + P - 1u) / P;  // at most kTileElems / P + 1
@@ -662,7 +678,7 @@ __global__ __launch_bounds__(kBlock, 4) void decode_merge_kernel(bitsnap_sparse_
 #pragma unroll
         for (int j = 0; j < 2; ++j)
             cnt[r][j] = __popc(m[r][j]);
-    tile_ranks<E>(sh, cnt, lane, wave, rank);  // barrier
+    const uint32_t tile_total = tile_ranks<E>(sh, cnt, lane, wave, rank);  // barrier
 #pragma unroll
     for (int i = 0; i < kPiecesPerThread; ++i)
         *reinterpret_cast<uint4 *>(&sh.stage[(uint32_t)(i * kBlock + tid) * P]) = pv[i];
@@ -700,6 +716,8 @@ __global__ __launch_bounds__(kBlock, 4) void decode_merge_kernel(bitsnap_sparse_
                 res.v[k] = make_uint4(w[4 * k + 0], w[4 * k + 1], w[4 * k + 2], w[4 * k + 3]);
             store8<E>(out, piece_chunk<E>(tile, r, wave, j) * kChunkElems + lane * kLaneElems, n, res);
         }
+    if (kOffsets && last_tile && tid == 0 && it.n_changed)
+        *it.n_changed = excl + tile_total;  // no scan kernel ran to report it; last, when few registers are live
 }
 
 // Workspace after the header: encode keeps one 8-byte scan word per tile there; decode keeps the
@@ -800,11 +818,22 @@ static int check_scan_workspace(void *workspace, size_t workspace_bytes, int64_t
 
 template <bool kBatched, int E>
 static int launch_decode_e(const bitsnap_sparse_item &single, const bitsnap_sparse_item *items, int64_t count,
-                           int64_t num_tiles, void *workspace, bitsnap_stream_t stream, bool delta)
+                           int64_t num_tiles, void *workspace, bitsnap_stream_t stream, bool delta, bool offsets)
 {
     uint64_t *tile_offset = reinterpret_cast<uint64_t *>(reinterpret_cast<char *>(workspace) + kScanHeaderBytes);
     uint32_t *tile_count = reinterpret_cast<uint32_t *>(tile_offset + num_tiles);
     hipStream_t s = (hipStream_t)stream;
+    if (offsets && num_tiles > 0) {  // the encoder's tile offsets are given: one launch, nothing to count
+        if (num_tiles > 0x7FFFFFFF)
+            return BITSNAP_E_SIZE;
+        if (delta)
+            hipLaunchKernelGGL((decode_merge_kernel<kBatched, true, true, E>), dim3((unsigned)num_tiles), dim3(kBlock), 0, s,
+                               single, items, count, tile_offset, tile_count);
+        else
+            hipLaunchKernelGGL((decode_merge_kernel<kBatched, false, true, E>), dim3((unsigned)num_tiles), dim3(kBlock), 0, s,
+                               single, items, count, tile_offset, tile_count);
+        return launch_status();
+    }
     if (num_tiles > 0) {
         if ((num_tiles + kWaves - 1) / kWaves > 0x7FFFFFFF || num_tiles > 0x7FFFFFFF)
             return BITSNAP_E_SIZE;
@@ -815,21 +844,22 @@ static int launch_decode_e(const bitsnap_sparse_item &single, const bitsnap_spar
     hipLaunchKernelGGL((decode_scan_kernel<kBatched, E>), dim3((unsigned)(kBatched ? count : 1)), dim3(kBlock), 0, s,
                        single, items, tile_count, tile_offset);
     if (num_tiles > 0 && delta)
-        hipLaunchKernelGGL((decode_merge_kernel<kBatched, true, E>), dim3((unsigned)num_tiles), dim3(kBlock), 0, s, single,
-                           items, count, tile_offset, tile_count);
+        hipLaunchKernelGGL((decode_merge_kernel<kBatched, true, false, E>), dim3((unsigned)num_tiles), dim3(kBlock), 0, s,
+                           single, items, count, tile_offset, tile_count);
     else if (num_tiles > 0)
-        hipLaunchKernelGGL((decode_merge_kernel<kBatched, false, E>), dim3((unsigned)num_tiles), dim3(kBlock), 0, s, single,
-                           items, count, tile_offset, tile_count);
+        hipLaunchKernelGGL((decode_merge_kernel<kBatched, false, false, E>), dim3((unsigned)num_tiles), dim3(kBlock), 0, s,
+                           single, items, count, tile_offset, tile_count);
     return launch_status();
 }
 
 template <bool kBatched>
 static int launch_decode(const bitsnap_sparse_item &single, const bitsnap_sparse_item *items, int64_t count,
-                         int64_t num_tiles, void *workspace, bitsnap_stream_t stream, bool delta, int elem_bytes)
+                         int64_t num_tiles, void *workspace, bitsnap_stream_t stream, bool delta, bool offsets,
+                         int elem_bytes)
 {
     if (elem_bytes == 4)
-        return launch_decode_e<kBatched, 4>(single, items, count, num_tiles, workspace, stream, delta);
-    return launch_decode_e<kBatched, 2>(single, items, count, num_tiles, workspace, stream, delta);
+        return launch_decode_e<kBatched, 4>(single, items, count, num_tiles, workspace, stream, delta, offsets);
+    return launch_decode_e<kBatched, 2>(single, items, count, num_tiles, workspace, stream, delta, offsets);
 }
 
 template <bool kBatched>
@@ -892,36 +922,40 @@ extern "C" int bitsnap_encode_sparse(const void *cur, const void *base, int64_t 
 }
 
 extern "C" int bitsnap_decode_sparse_ex(const void *base, const uint8_t *mask, const void *payload,
-                                        int64_t payload_elems, int64_t n, int elem_bytes, uint32_t flags, void *out,
-                                        uint64_t *n_changed, void *workspace, size_t workspace_bytes,
-                                        bitsnap_stream_t stream)
+                                        int64_t payload_elems, int64_t n, int elem_bytes, uint32_t flags,
+                                        const uint32_t *tile_offsets, void *out, uint64_t *n_changed, void *workspace,
+                                        size_t workspace_bytes, bitsnap_stream_t stream)
 {
     if (n < 0 || (elem_bytes != 2 && elem_bytes != 4) || payload_elems < 0 || n >= (int64_t)1 << kValueBits ||
         (flags & ~(uint32_t)BITSNAP_SPARSE_DELTA))
         return BITSNAP_E_SIZE;
     if ((n > 0 && (!base || !mask || !out)) || (payload_elems > 0 && !payload))
         return BITSNAP_E_NULL;
-    if (!aligned16(base) || !aligned16(mask) || !aligned16(payload) || !aligned16(out) || ((uintptr_t)n_changed & 7u))
+    if (!aligned16(base) || !aligned16(mask) || !aligned16(payload) || !aligned16(out) || ((uintptr_t)n_changed & 7u) ||
+        ((uintptr_t)tile_offsets & 3u))
         return BITSNAP_E_ALIGN;
     if (int rc = check_workspace(workspace, workspace_bytes, n, elem_bytes))
         return rc;
+    if (tile_offsets && n >= (int64_t)1 << 32)
+        return BITSNAP_E_OFFSETS;
     bitsnap_sparse_item it = {};
     it.base = base;
     it.mask = const_cast<uint8_t *>(mask);
     it.payload = const_cast<void *>(payload);
     it.out = out;
     it.n_changed = n_changed;
+    it.tile_offsets = const_cast<uint32_t *>(tile_offsets);
     it.n = n;
     it.capacity = payload_elems;
     return launch_decode<false>(it, nullptr, 1, tiles_of(n, elem_bytes), workspace, stream,
-                                (flags & BITSNAP_SPARSE_DELTA) != 0, elem_bytes);
+                                (flags & BITSNAP_SPARSE_DELTA) != 0, tile_offsets != nullptr, elem_bytes);
 }
 
 extern "C" int bitsnap_decode_sparse(const void *base, const uint8_t *mask, const void *payload, int64_t payload_elems,
                                      int64_t n, int elem_bytes, void *out, uint64_t *n_changed, void *workspace,
                                      size_t workspace_bytes, bitsnap_stream_t stream)
 {
-    return bitsnap_decode_sparse_ex(base, mask, payload, payload_elems, n, elem_bytes, 0u, out, n_changed, workspace,
+    return bitsnap_decode_sparse_ex(base, mask, payload, payload_elems, n, elem_bytes, 0u, nullptr, out, n_changed, workspace,
                                     workspace_bytes, stream);
 }
 
@@ -969,14 +1003,14 @@ extern "C" int bitsnap_decode_sparse_batched_ex(const bitsnap_sparse_item *items
                                                 int elem_bytes, uint32_t flags, void *workspace, size_t workspace_bytes,
                                                 bitsnap_stream_t stream)
 {
-    if ((flags & ~(uint32_t)BITSNAP_SPARSE_DELTA) || (elem_bytes != 2 && elem_bytes != 4))
+    if ((flags & ~(uint32_t)(BITSNAP_SPARSE_DELTA | BITSNAP_SPARSE_OFFSETS)) || (elem_bytes != 2 && elem_bytes != 4))
         return BITSNAP_E_SIZE;
     if (int rc = check_batch(items, count, total_tiles, workspace, workspace_bytes))
         return rc;
     if (count == 0 || total_tiles == 0)
         return BITSNAP_OK;
     return launch_decode<true>(bitsnap_sparse_item{}, items, count, total_tiles, workspace, stream,
-                               (flags & BITSNAP_SPARSE_DELTA) != 0, elem_bytes);
+                               (flags & BITSNAP_SPARSE_DELTA) != 0, (flags & BITSNAP_SPARSE_OFFSETS) != 0, elem_bytes);
 }
 
 extern "C" int bitsnap_decode_sparse_batched(const bitsnap_sparse_item *items, int64_t count, int64_t total_tiles,

@@ -441,3 +441,59 @@ def test_32_bit_elements_batched():
             o_off = oracle.tile_offsets(o_mask, sizes[k], T4)
             assert np.array_equal(to_np(offs[k]).view(np.uint32), o_off[:-1].astype(np.uint32))
             assert np.array_equal(_dev_to_u32(out[k]), c)
+
+
+@pytest.mark.parametrize("n", [1, 9, 4097, T - 1, T, T + 1, 2 * T + 5, 7 * T + 777, 1_000_003])
+@pytest.mark.parametrize("p", [0.0, 0.06, 0.7, 1.0])
+def test_decode_with_the_encoders_tile_offsets(n, p):
+    """Given the encoder's tile offsets the decoder skips its counting pass; the result and the reported count are
+    the same.  Also with the delta payload, with 4-byte elements, and with a payload buffer larger than the count."""
+    announce("decode with offsets", n, p)
+    cur, base = _pair(n, p, 7000 + n % 997)
+    for delta in (False, True):
+        enc = B.encode_sparse(u16_to_dev(cur), u16_to_dev(base), want_offsets=True, delta=delta)
+        out, cnt = B.decode_sparse(u16_to_dev(base), enc.mask, enc.payload, n, workspace=enc.workspace, delta=delta,
+                                   tile_offsets=enc.tile_offsets)
+        torch.cuda.synchronize()
+        assert np.array_equal(dev_to_u16(out), cur)
+        assert int(cnt.item()) == int(enc.n_changed.item()) == int((cur != base).sum())
+    T4_ = B.sparse_tile_elems(4)
+    rng = np.random.default_rng(n)
+    b32 = rng.integers(0, 1 << 32, n, dtype=np.uint64).astype(np.uint32)
+    c32 = b32.copy()
+    sel = rng.random(n) < p
+    c32[sel] ^= rng.integers(1, 1 << 32, n, dtype=np.uint64).astype(np.uint32)[sel]
+    to32 = lambda a: torch.from_numpy(a.view(np.int32)).to(DEV)
+    enc = B.encode_sparse(to32(c32), to32(b32), want_offsets=True)
+    assert enc.tile_offsets.numel() == max((n + T4_ - 1) // T4_, 1)
+    out, cnt = B.decode_sparse(to32(b32), enc.mask, enc.payload, n, workspace=enc.workspace, tile_offsets=enc.tile_offsets)
+    torch.cuda.synchronize()
+    assert np.array_equal(to_np(out).view(np.uint32), c32) and int(cnt.item()) == int(sel.sum())
+
+
+def test_batched_decode_with_tile_offsets():
+    announce("batched decode with offsets")
+    sizes = [1, T, T + 1, 5 * T + 77, 9, 3 * T, 200_003, 8, 40 * T - 1, 65]
+    ps = [1.0, 0.06, 0.5, 0.7, 0.0, 1.0, 0.06, 0.5, 0.3, 0.2]
+    pairs = [_pair(n, p, 4100 + i) for i, (n, p) in enumerate(zip(sizes, ps))]
+    cur = [u16_to_dev(c) for c, _ in pairs]
+    base = [u16_to_dev(b) for _, b in pairs]
+    mask = [torch.zeros(B.sparse_mask_bytes(n), dtype=torch.uint8, device=DEV) for n in sizes]
+    payload = [torch.zeros(n + 8, dtype=torch.int16, device=DEV) for n in sizes]
+    counts = [torch.zeros(1, dtype=torch.int64, device=DEV) for _ in sizes]
+    offs = [torch.zeros((n + T - 1) // T, dtype=torch.int32, device=DEV) for n in sizes]
+    items, total = B.sparse_items(sizes, src=cur, base=base, mask=mask, payload=payload, n_changed=counts, tile_offsets=offs)
+    ws = torch.zeros(B.sparse_batch_workspace_bytes(total), dtype=torch.uint8, device=DEV)
+    B.encode_sparse_batched(items, total, ws)
+    out = [torch.zeros(n, dtype=torch.bfloat16, device=DEV) for n in sizes]
+    dcounts = [torch.full((1,), -1, dtype=torch.int64, device=DEV) for _ in sizes]
+    ditems, _ = B.sparse_items(sizes, base=base, mask=mask, payload=payload, out=out, n_changed=dcounts, tile_offsets=offs)
+    B.decode_sparse_batched(ditems, total, ws, flags=B.SPARSE_OFFSETS)
+    torch.cuda.synchronize()
+    for k, (c, b) in enumerate(pairs):
+        assert np.array_equal(dev_to_u16(out[k]), c), k
+        assert int(dcounts[k].item()) == int(counts[k].item()) == int((c != b).sum()), k
+    # the workspace was not touched by that decode: an encode right after it is fine
+    B.encode_sparse_batched(items, total, ws)
+    torch.cuda.synchronize()
+    assert int(counts[3].item()) == int((pairs[3][0] != pairs[3][1]).sum())
