@@ -644,10 +644,9 @@ __device__ __forceinline__ uint32_t segment_dest(const WideSpace &sp, const Wide
 template <bool kFull, bool kTable, bool kMajor>
 __device__ __forceinline__ void chunk_codes_ex(const float *__restrict__ x, const ChunkRef &r, int m, const GroupState &st,
                                                const float *__restrict__ params, int64_t g_lo, int64_t g_len, uint32_t dest,
-                                               QuantizeShared &sh, const TableShared &table, int lane,
+                                               WaveShared &ws, const TableShared &table, int lane,
                                                uint8_t *__restrict__ labels, uint8_t *__restrict__ codes)
 {
-    WaveShared &ws = sh.ws;
     float4 v[kGK];
     load_elements<kGK, kFull>(x, r.lo, r.len, lane, v);
     if (lane < kMaxClusters) {
@@ -673,10 +672,7 @@ __device__ __forceinline__ void chunk_codes_ex(const float *__restrict__ x, cons
         wave_lds_sync();
         return;
     }
-    MajorView mv;
-    mv.counters = (uint32_t *)&ws.tab[0][0];
-    mv.bytes = (uint32_t *)&ws.tab[kMaxClusters][0];
-    mv.labels = sh.labels;
+    const MajorView mv = major_view(ws);
     uint16_t *l16 = (uint16_t *)mv.labels;
 #pragma unroll
     for (int k = 0; k < kGK; ++k) {
@@ -702,7 +698,7 @@ __device__ __forceinline__ void chunk_codes_ex(const float *__restrict__ x, cons
 template <typename Src, bool kTable, bool kMajor>
 __global__ __launch_bounds__(kGBlock, 3) void wide_code_ex_kernel(Src src, WideSpace sp, int m, const float *__restrict__ qmap)
 {
-    __shared__ QuantizeShared shared[kGWaves];
+    __shared__ WaveShared shared[kGWaves];
     __shared__ TableShared table;
     if (kTable)
         load_table(table, qmap);
@@ -820,7 +816,7 @@ __global__ __launch_bounds__(kGBlock, 2) void wide_dequantize_ex_kernel(Src src,
     }
     if (kMajor) {
         MajorView mv;
-        mv.counters = &sh.counters[0][0];
+        mv.counters = sh.counters;
         mv.bytes = sh.bytes;
         mv.labels = sh.labels;
         uint16_t *l16 = (uint16_t *)mv.labels;

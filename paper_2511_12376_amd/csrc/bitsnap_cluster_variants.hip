@@ -26,9 +26,8 @@ __device__ __forceinline__ void quantize_group_ex(const float *__restrict__ x, i
                                                   uint8_t *__restrict__ codes, uint8_t *__restrict__ labels,
                                                   float *__restrict__ params, float *__restrict__ fit_out,
                                                   const float *__restrict__ fit_in, uint32_t *__restrict__ status,
-                                                  QuantizeShared &shared, const TableShared &table, int lane)
+                                                  WaveShared &ws, const TableShared &table, int lane)
 {
-    WaveShared &ws = shared.ws;
 
     // ---- steps 1-4 of Algorithm 2, as in the plain kernel
     float4 v[K];
@@ -76,11 +75,7 @@ __device__ __forceinline__ void quantize_group_ex(const float *__restrict__ x, i
     uint32_t c4[K];
     codes_to_registers<K, kTable>(v, packed, ws, table, c4);
     if (kMajor) {
-        // the min/max table is done with: its first half becomes the counters, its second half the codes
-        MajorView mv;
-        mv.counters = (uint32_t *)&ws.tab[0][0];
-        mv.bytes = (uint32_t *)&ws.tab[kMaxClusters][0];
-        mv.labels = shared.labels;
+        const MajorView mv = major_view(ws);  // the min/max table is done with
         uint16_t *l16 = (uint16_t *)mv.labels;
 #pragma unroll
         for (int k = 0; k < K; ++k) {
@@ -102,20 +97,29 @@ __device__ __forceinline__ void quantize_group_ex(const float *__restrict__ x, i
 // the grid): the grid is sized to the device when a table has to be prepared per workgroup, and
 // to one group per wave otherwise.
 template <int K, bool kFull, bool kTable, bool kMajor>
-__global__ __launch_bounds__(kVBlock, 3) void quantize_cluster_ex_kernel(
+__global__ __launch_bounds__(kVBlock, kTable ? 3 : 4) void quantize_cluster_ex_kernel(
     const float *__restrict__ x, int64_t n, int64_t first_group, int64_t groups, int m, const float *__restrict__ qmap,
     uint8_t *__restrict__ codes, uint8_t *__restrict__ labels, float *__restrict__ params, float *__restrict__ fit_out,
     const float *__restrict__ fit_in, uint32_t *__restrict__ status)
 {
-    __shared__ QuantizeShared shared[kVWaves];
+    __shared__ WaveShared shared[kVWaves];
     __shared__ TableShared table;
     if (kTable)
         load_table(table, qmap);
     // no workgroup barrier from here on: waves leave when they run out of groups
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
     constexpr int G = 256 * K;
-    for (int64_t g = first_group + (int64_t)blockIdx.x * kVWaves + wave; g < first_group + groups;
-         g += (int64_t)gridDim.x * kVWaves) {
+    int64_t g = first_group + (int64_t)blockIdx.x * kVWaves + wave;
+    if (!kTable) {  // one group per wave: written without the loop, which costs registers
+        if (g < first_group + groups) {
+            const int64_t lo = g * G;
+            const int64_t rest = n - lo;
+            quantize_group_ex<K, kFull, kTable, kMajor>(x, lo, kFull ? G : (int)(rest < G ? rest : G), m, g, codes, labels,
+                                                        params, fit_out, fit_in, status, shared[wave], table, lane);
+        }
+        return;
+    }
+    for (; g < first_group + groups; g += (int64_t)gridDim.x * kVWaves) {
         const int64_t lo = g * G;
         const int64_t rest = n - lo;
         const int len = kFull ? G : (int)(rest < G ? rest : G);
@@ -157,7 +161,7 @@ __device__ __forceinline__ void dequantize_group_ex(const uint8_t *__restrict__ 
     }
     if (kMajor) {
         MajorView mv;
-        mv.counters = &sh.counters[0][0];
+        mv.counters = sh.counters;
         mv.bytes = sh.bytes;
         mv.labels = sh.labels;
         uint16_t *l16 = (uint16_t *)mv.labels;
@@ -200,7 +204,7 @@ __device__ __forceinline__ void dequantize_group_ex(const uint8_t *__restrict__ 
 }
 
 template <int K, bool kTable, bool kMajor>
-__global__ __launch_bounds__(kVBlock) void dequantize_cluster_ex_kernel(
+__global__ __launch_bounds__(kVBlock, 4) void dequantize_cluster_ex_kernel(
     const uint8_t *__restrict__ codes, const uint8_t *__restrict__ labels, const float *__restrict__ params, int64_t n,
     int64_t groups, int m, const float *__restrict__ qmap, float *__restrict__ out)
 {
@@ -223,19 +227,19 @@ __global__ __launch_bounds__(kVBlock) void dequantize_cluster_ex_kernel(
 // Batched forms: groups are numbered across the list of tensors as in the plain batched kernels.
 // ---------------------------------------------------------------------------------------------
 template <int K, bool kFull, bool kTable, bool kMajor>
-__global__ __launch_bounds__(kVBlock, 3) void quantize_cluster_ex_batched_kernel(
+__global__ __launch_bounds__(kVBlock, kTable ? 3 : 4) void quantize_cluster_ex_batched_kernel(
     const bitsnap_cluster_item *__restrict__ items, int64_t count, int64_t total_groups, int m,
     const float *__restrict__ qmap, uint32_t *__restrict__ status)
 {
-    __shared__ QuantizeShared shared[kVWaves];
+    __shared__ WaveShared shared[kVWaves];
     __shared__ TableShared table;
     if (kTable)
         load_table(table, qmap);
     const int lane = threadIdx.x & (kWave - 1), wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     constexpr int G = 256 * K;
-    const int64_t stride = (int64_t)gridDim.x * kVWaves;
-    if (kFull) {
-        for (int64_t gg = (int64_t)blockIdx.x * kVWaves + wave; gg < total_groups; gg += stride) {
+    // list-wide group gg (kFull) or the short last group of tensor gg (!kFull)
+    auto one = [&](int64_t gg) {
+        if (kFull) {
             const bitsnap_cluster_item &it = items[find_item(items, count, gg)];
             const int64_t g = gg - it.first_group;
             const int64_t lo = g * G;
@@ -243,11 +247,8 @@ __global__ __launch_bounds__(kVBlock, 3) void quantize_cluster_ex_batched_kernel
                 quantize_group_ex<K, true, kTable, kMajor>((const float *)it.values, lo, G, m, g, it.codes, it.labels,
                                                            it.params, it.fit_out, it.fit_in, status, shared[wave], table,
                                                            lane);
-        }
-    } else {
-        // one wave per tensor: its short last group, if it has one
-        for (int64_t t = (int64_t)blockIdx.x * kVWaves + wave; t < count; t += stride) {
-            const bitsnap_cluster_item &it = items[t];
+        } else {
+            const bitsnap_cluster_item &it = items[gg];
             const int64_t g = it.n / G;
             const int rest = (int)(it.n - g * G);
             if (rest > 0)
@@ -255,11 +256,20 @@ __global__ __launch_bounds__(kVBlock, 3) void quantize_cluster_ex_batched_kernel
                                                             it.params, it.fit_out, it.fit_in, status, shared[wave], table,
                                                             lane);
         }
+    };
+    const int64_t end = kFull ? total_groups : count;
+    int64_t gg = (int64_t)blockIdx.x * kVWaves + wave;
+    if (!kTable) {  // one turn per wave: written without the loop, which costs registers
+        if (gg < end)
+            one(gg);
+        return;
     }
+    for (; gg < end; gg += (int64_t)gridDim.x * kVWaves)
+        one(gg);
 }
 
 template <int K, bool kTable, bool kMajor>
-__global__ __launch_bounds__(kVBlock) void dequantize_cluster_ex_batched_kernel(
+__global__ __launch_bounds__(kVBlock, 4) void dequantize_cluster_ex_batched_kernel(
     const bitsnap_cluster_item *__restrict__ items, int64_t count, int64_t total_groups, int m,
     const float *__restrict__ qmap)
 {

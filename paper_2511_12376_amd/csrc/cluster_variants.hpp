@@ -26,20 +26,27 @@ constexpr int kVBlock = 256;
 constexpr int kVWaves = kVBlock / kWave;
 constexpr int kLevels = 256;
 
-// LDS of one wave for the partition.
+// LDS of one wave for the partition: 8 KB, so that sixteen waves fit a CU next to their other tables.
 struct MajorView {
-    uint32_t *counters;  // [16][64]: cluster c, lane l at c*64 + l
+    uint32_t *counters;  // [16][32] words of two 16-bit counters: cluster c, lane l in word c*32 + l%32, upper half for l >= 32
     uint32_t *bytes;     // [256*K] bytes: the group's codes (element order on one side, cluster-major on the other)
     uint32_t *labels;    // [256*K] nibbles: the group's labels in element order
 };
+constexpr int kCounterWords = kMaxClusters * kWave / 2;
 
-struct alignas(16) QuantizeShared {
-    WaveShared ws;
-    uint32_t labels[kMaxClusters * 256 / 8];
-};
+// In the quantiser the partition runs when the min/max table is done with, and takes its place:
+// rows 0-7 the counters, rows 8-15 the labels, rows 16-31 the code bytes.
+__device__ __forceinline__ MajorView major_view(WaveShared &ws)
+{
+    MajorView mv;
+    mv.counters = (uint32_t *)&ws.tab[0][0];
+    mv.labels = (uint32_t *)&ws.tab[kMaxClusters / 2][0];
+    mv.bytes = (uint32_t *)&ws.tab[kMaxClusters][0];
+    return mv;
+}
 
 struct alignas(16) DequantizeShared {
-    uint32_t counters[kMaxClusters][kWave];
+    uint32_t counters[kCounterWords];
     uint32_t bytes[kMaxClusters * 256 / 4];
     uint32_t labels[kMaxClusters * 256 / 8];
     float2 coder[kMaxClusters];
@@ -61,26 +68,44 @@ __device__ __forceinline__ void own_labels(const MajorView &mv, int lane, uint32
         lh[i] = l16[lane * K + i];
 }
 
-// Counts the lane's labels and turns the counter table into first positions: afterwards
-// counters[c][lane] = members of clusters < c in the group + members of c in lower lanes.
+// The counter of (cluster, lane): a 16-bit half of a word that lanes l and l + 32 share.  Counts and
+// positions stay below 2^13, so an add to the lower half never carries into the upper one.
+__device__ __forceinline__ uint32_t counter_word(uint32_t cluster, int lane) { return cluster * (kWave / 2) + (uint32_t)(lane & 31); }
+__device__ __forceinline__ uint32_t counter_shift(int lane) { return (uint32_t)(lane >> 5) * 16u; }
+
+// Takes the next position of `cluster` in this lane's counter.
+__device__ __forceinline__ uint32_t take_position(const MajorView &mv, uint32_t cluster, int lane)
+{
+    const uint32_t shift = counter_shift(lane);
+    return (lds_fetch_add(&mv.counters[counter_word(cluster, lane)], 1u << shift) >> shift) & 0xFFFFu;
+}
+
+// Counts the lane's labels and turns the counter table into first positions: afterwards the
+// counter of (c, lane) = members of clusters < c in the group + members of c in lower lanes.
 template <int K, bool kFull>
 __device__ __forceinline__ void major_positions(const MajorView &mv, const uint32_t (&lh)[K], int len, int lane)
 {
+    if (lane < kWave / 2) {
 #pragma unroll
-    for (int c = 0; c < kMaxClusters; ++c)
-        mv.counters[c * kWave + lane] = 0;
+        for (int c = 0; c < kMaxClusters; ++c)
+            mv.counters[c * (kWave / 2) + lane] = 0;
+    }
+    wave_lds_sync();
+    const uint32_t one = 1u << counter_shift(lane);
 #pragma unroll
     for (int i = 0; i < K; ++i)
 #pragma unroll
         for (int j = 0; j < 4; ++j)
             if (kFull || lane * 4 * K + 4 * i + j < len)
-                lds_fetch_add(&mv.counters[((lh[i] >> (4 * j)) & 15u) * kWave + lane], 1u);
+                lds_fetch_add(&mv.counters[counter_word((lh[i] >> (4 * j)) & 15u, lane)], one);
     wave_lds_sync();
-    // exclusive prefix over the 1024 counters in row order: 16 consecutive ones per lane
+    // Exclusive prefix over the 1024 counters in (cluster, lane) order, 16 consecutive ones per lane:
+    // lane L takes cluster L/4, lanes 16*(L%4) .. +15, i.e. 16 consecutive words and one half of each.
+    const uint32_t w0 = (uint32_t)(lane >> 2) * (kWave / 2) + (uint32_t)(lane & 1) * 16u, upper = (uint32_t)(lane >> 1) & 1u;
     uint32_t c[16];
 #pragma unroll
     for (int i = 0; i < 16; ++i)
-        c[i] = mv.counters[lane * 16 + i];
+        c[i] = (mv.counters[w0 + i] >> (16u * upper)) & 0xFFFFu;
     uint32_t total = 0;
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
@@ -90,9 +115,10 @@ __device__ __forceinline__ void major_positions(const MajorView &mv, const uint3
     }
     const uint32_t before = wave_inclusive_add(total) - total;
     wave_lds_sync();  // every lane has read its 16 counters (other lanes' columns) before any is rewritten
+    uint16_t *c16 = (uint16_t *)mv.counters;
 #pragma unroll
     for (int i = 0; i < 16; ++i)
-        mv.counters[lane * 16 + i] = c[i] + before;
+        c16[2u * (w0 + i) + upper] = (uint16_t)(c[i] + before);
     wave_lds_sync();
 }
 
@@ -100,7 +126,7 @@ __device__ __forceinline__ void major_positions(const MajorView &mv, const uint3
 // cluster c's first member (lane 0's counter of that cluster), the other lanes get len.
 __device__ __forceinline__ uint32_t cluster_start(const MajorView &mv, int len, int lane)
 {
-    return lane < kMaxClusters ? mv.counters[lane * kWave] : (uint32_t)len;
+    return lane < kMaxClusters ? (mv.counters[lane * (kWave / 2)] & 0xFFFFu) : (uint32_t)len;
 }
 
 // Element order -> cluster-major.  In: mv.bytes and mv.labels hold the group in element order.
@@ -127,7 +153,7 @@ __device__ __forceinline__ void to_cluster_major(const MajorView &mv, int len, i
             const int i = (e0 + e) >> 2, j = (e0 + e) & 3;
             pos[e] = 0;
             if (kFull || lane * 4 * K + e0 + e < len)
-                pos[e] = lds_fetch_add(&mv.counters[((lh[i] >> (4 * j)) & 15u) * kWave + lane], 1u);
+                pos[e] = take_position(mv, (lh[i] >> (4 * j)) & 15u, lane);
         }
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -169,7 +195,7 @@ __device__ __forceinline__ void from_cluster_major(const MajorView &mv, int len,
             const int i = (e0 + e) >> 2, j = (e0 + e) & 3;
             pos[e] = 0;
             if (kFull || lane * 4 * K + e0 + e < len)
-                pos[e] = lds_fetch_add(&mv.counters[((lh[i] >> (4 * j)) & 15u) * kWave + lane], 1u);
+                pos[e] = take_position(mv, (lh[i] >> (4 * j)) & 15u, lane);
         }
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
