@@ -460,9 +460,9 @@ def main():
         # quantisation error on these synthetic Adam states, next to plain min-max 8-bit (one cluster): the
         # comparison the paper's evaluation makes on trained states (its table of MRE and MSE against naive
         # 8-bit quantisation); torch only computes the two error measures
-        def quality(x, group, m):
-            q = B.quantize_cluster(x, group, m)
-            xh = B.dequantize_cluster(q.codes, q.labels, q.params, x.numel(), group, m)
+        def quality(x, group, m, tab=None):
+            q = B.quantize_cluster_ex(x, group, m, qmap=tab)
+            xh = B.dequantize_cluster_ex(q.codes, q.labels, q.params, x.numel(), group, m, qmap=tab, workspace=q.workspace)
             err = (xh.double() - x.double())
             nz = x != 0
             return {"MSE": float((err * err).mean().item()),
@@ -470,11 +470,13 @@ def main():
         sample = min(range(len(sizes)), key=lambda i: abs(sizes[i] - 11008 * 4096))
         extras["quantisation_error_synthetic"] = {
             "tensor": cfg.tensors[tensors[sample]][0], "elements": sizes[sample],
-            "rows": {f"{state} {label}": quality(inputs[sample][key], group, m)
+            "rows": {f"{state} {label}": quality(inputs[sample][key], group, m, tab)
                      for state, key in (("adam1", "m"), ("adam2", "v"))
-                     for label, group, m in (("16 clusters per 4096-element group", GROUP, M),
-                                             ("16 clusters per tensor", 0, M),
-                                             ("naive 8-bit (1 cluster per tensor)", 0, 1))}}
+                     for label, group, m, tab in (("16 clusters per 4096-element group", GROUP, M, None),
+                                                  ("16 clusters per 4096-element group, levels dense in mid-range", GROUP, M, qtab),
+                                                  ("16 clusters per tensor", 0, M, None),
+                                                  ("naive 8-bit (1 cluster per tensor)", 0, 1, None),
+                                                  ("1 cluster per tensor, levels dense in mid-range", 0, 1, qtab))}}
         # the step's own codes of that state, for whoever looks at the buffers afterwards
         for a in (c for k, c in enumerate(calls["quantize_cluster"]) if k % 3 == 1):
             L.bitsnap_quantize_cluster(*a)
