@@ -38,7 +38,9 @@ enum {
     BITSNAP_E_ALIGN = -3,       /* a pointer that must be 16-byte aligned is not           */
     BITSNAP_E_WORKSPACE = -4,   /* workspace missing or smaller than *_workspace_bytes()   */
     BITSNAP_E_OFFSETS = -5,     /* tile_offsets requested but n >= 2^32                    */
-    BITSNAP_E_LAUNCH = -6       /* the HIP runtime refused the launch                      */
+    BITSNAP_E_LAUNCH = -6,      /* the HIP runtime refused the launch                      */
+    BITSNAP_E_STATIC_LIMIT = -7 /* bitsnap_encode_sparse_static: more tiles than
+                                   BITSNAP_STATIC_MAX_TILES                                */
 };
 
 /* Library version, major*10000 + minor*100 + patch. */
@@ -161,6 +163,21 @@ int bitsnap_decode_sparse_ex(const void *base, const uint8_t *mask, const void *
                              int64_t payload_elems, int64_t n, int elem_bytes, uint32_t flags,
                              const uint32_t *tile_offsets, void *out, uint64_t *n_changed,
                              void *workspace, size_t workspace_bytes, bitsnap_stream_t stream);
+
+/* bitsnap_encode_sparse for callers that cannot allocate device memory, not even a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments,
+ * outputs and errors as bitsnap_encode_sparse, without the workspace: the scan state lives in a
+ * device array inside the library (256 bytes + 128 per tile = 2 MiB + 256 bytes on every GPU the
+ * call has run on, held until the process ends).  The call allocates and frees nothing.
+ *   - a tensor of more than BITSNAP_STATIC_MAX_TILES tiles (536,870,912 two-byte or 268,435,456
+ *     four-byte elements) is rejected with BITSNAP_E_STATIC_LIMIT before anything is launched;
+ *   - all calls on one GPU share the one array: two of them that overlap in time (different
+ *     streams, different threads) race, exactly like two calls that share a workspace;
+ *   - the first call on a GPU also enqueues a small kernel that clears the array. */
+#define BITSNAP_STATIC_MAX_TILES 16384
+int bitsnap_encode_sparse_static(const void *cur, const void *base, int64_t n, int elem_bytes,
+                                 uint8_t *mask, void *payload, int64_t payload_capacity_elems,
+                                 uint32_t *tile_offsets, uint64_t *n_changed, bitsnap_stream_t stream);
 
 /* Host-side knob for tests of the give-up path: the number of polls a workgroup spends waiting
  * for a predecessor's scan state before it reports failure through n_changed.  0 restores the

@@ -29,6 +29,7 @@ SYMBOLS = (
     "bitsnap_cluster_chunk_elems", "bitsnap_cluster_batch_workspace_bytes",
     "bitsnap_quantize_cluster_batched", "bitsnap_dequantize_cluster_batched",
     "bitsnap_sparse_batch_workspace_bytes", "bitsnap_encode_sparse_batched", "bitsnap_decode_sparse_batched",
+    "bitsnap_encode_sparse_static",
 )
 
 
@@ -60,6 +61,8 @@ def lib():
     L.bitsnap_sparse_workspace_bytes.argtypes, L.bitsnap_sparse_workspace_bytes.restype = [i64], sz
     L.bitsnap_encode_sparse.argtypes = [p, p, i64, i, p, p, i64, p, p, p, sz, p]
     L.bitsnap_encode_sparse.restype = i
+    L.bitsnap_encode_sparse_static.argtypes = [p, p, i64, i, p, p, i64, p, p, p]
+    L.bitsnap_encode_sparse_static.restype = i
     L.bitsnap_decode_sparse.argtypes = [p, p, p, i64, i64, i, p, p, p, sz, p]
     L.bitsnap_decode_sparse.restype = i
     L.bitsnap_encode_sparse_ex.argtypes = [p, p, i64, i, C.c_uint32, p, p, i64, p, p, p, p, sz, p]
@@ -215,6 +218,17 @@ def encode_sparse_raw(cur, base, n: int, mask, payload, payload_capacity: int, t
                                             payload_capacity, _ptr(tile_offsets), _ptr(n_changed), _ptr(new_base),
                                             _ptr(workspace), wsb, _stream(stream))
         _check(rc, "bitsnap_encode_sparse_ex")
+
+
+STATIC_MAX_TILES = 16384  # BITSNAP_STATIC_MAX_TILES
+
+
+def encode_sparse_static_raw(cur, base, n: int, mask, payload, payload_capacity: int, tile_offsets, n_changed,
+                             stream=None, *, elem_bytes: int = 2) -> None:
+    """bitsnap_encode_sparse_static: the encoder with the library's own scan buffer (no workspace, no allocation)."""
+    rc = lib().bitsnap_encode_sparse_static(_ptr(cur), _ptr(base), n, elem_bytes, _ptr(mask), _ptr(payload),
+                                            payload_capacity, _ptr(tile_offsets), _ptr(n_changed), _stream(stream))
+    _check(rc, "bitsnap_encode_sparse_static")
 
 
 def decode_sparse_raw(base, mask, payload, payload_elems: int, n: int, out, n_changed, workspace, stream=None, *,

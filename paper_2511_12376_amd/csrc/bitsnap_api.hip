@@ -108,6 +108,7 @@ extern "C" const char *bitsnap_error_string(int code)
     case BITSNAP_E_WORKSPACE: return "workspace missing or too small";
     case BITSNAP_E_OFFSETS: return "tile_offsets requested for a tensor of 2^32 elements or more";
     case BITSNAP_E_LAUNCH: return "the HIP runtime refused the kernel launch";
+    case BITSNAP_E_STATIC_LIMIT: return "tensor has more tiles than the library's built-in scan buffer serves (BITSNAP_STATIC_MAX_TILES)";
     default: return "unknown bitsnap error code";
     }
 }

@@ -17,6 +17,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+#include <mutex>
 #include <type_traits>
 
 #include "../../include/bitsnap.h"
@@ -727,7 +729,7 @@ __global__ __launch_bounds__(kBlock, 4) void decode_merge_kernel(bitsnap_sparse_
 constexpr size_t kWorkspaceBytesPerTile = 8 * kStatusStride;
 static_assert(kWorkspaceBytesPerTile >= 12, "decode keeps 8 + 4 bytes per tile");
 
-static uint32_t g_spin_limit = kDefaultSpinLimit;
+static std::atomic<uint32_t> g_spin_limit{kDefaultSpinLimit};
 
 // Persistent grid of the scan kernel.  Tiles are handed out by ticket, so nothing depends on every
 // workgroup being resident: a workgroup that only starts after others have finished finds no tile
@@ -790,7 +792,10 @@ extern "C" size_t bitsnap_sparse_workspace_bytes_for(int64_t n, int elem_bytes)
     return (elem_bytes == 2 || elem_bytes == 4) ? workspace_bytes_for_tiles(tiles_of(n, elem_bytes)) : 0;
 }
 
-extern "C" void bitsnap_debug_set_spin_limit(uint32_t polls) { g_spin_limit = polls ? polls : kDefaultSpinLimit; }
+extern "C" void bitsnap_debug_set_spin_limit(uint32_t polls)
+{
+    g_spin_limit.store(polls ? polls : kDefaultSpinLimit, std::memory_order_relaxed);
+}
 
 template <typename Kernel>
 static int launch_scan(Kernel kernel, const bitsnap_sparse_item &single, const bitsnap_sparse_item *items, int64_t count,
@@ -801,7 +806,7 @@ static int launch_scan(Kernel kernel, const bitsnap_sparse_item &single, const b
     const int64_t status_cap = (int64_t)((workspace_bytes - kScanHeaderBytes) / sizeof(uint64_t));
     const int grid = sparse_grid(reinterpret_cast<const void *>(kernel), num_tiles);
     hipLaunchKernelGGL(kernel, dim3(grid), dim3(kBlock), 0, (hipStream_t)stream, single, items, count, hdr, status,
-                       status_cap, num_tiles, g_spin_limit, refresh);
+                       status_cap, num_tiles, g_spin_limit.load(std::memory_order_relaxed), refresh);
     return launch_status();
 }
 
@@ -957,6 +962,74 @@ extern "C" int bitsnap_decode_sparse(const void *base, const uint8_t *mask, cons
 {
     return bitsnap_decode_sparse_ex(base, mask, payload, payload_elems, n, elem_bytes, 0u, nullptr, out, n_changed, workspace,
                                     workspace_bytes, stream);
+}
+
+// ---------------------------------------------------------------------------------------------
+// The encoder for callers that cannot allocate: its scan state lives in a device array that is part
+// of the library's code object instead of a caller-supplied workspace.
+// ---------------------------------------------------------------------------------------------
+namespace bitsnap {
+constexpr size_t kStaticScratchBytes = kScanHeaderBytes + (size_t)BITSNAP_STATIC_MAX_TILES * kWorkspaceBytesPerTile;
+}
+// One copy per GPU, at an address of its own on each, held until the process ends.
+static __device__ __align__(256) unsigned char scratch[bitsnap::kStaticScratchBytes];
+
+namespace bitsnap {
+
+// Everything the scan state holds (header, epoch and status words) back to "never used".
+__global__ __launch_bounds__(256) void clear_scratch_kernel(uint4 *p, size_t n16)
+{
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride)
+        p[i] = make_uint4(0, 0, 0, 0);
+}
+
+// The device address of `scratch` on the current GPU (the array's name means nothing to host code
+// beyond being the handle this lookup takes).  Looked up once per device; *first tells the caller
+// that this is the first use on that device.
+static int static_scratch(void **ptr, bool *first)
+{
+    static void *addr[kMaxDevices];
+    static std::mutex mu;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices)
+        return BITSNAP_E_LAUNCH;
+    std::lock_guard<std::mutex> lock(mu);
+    *first = addr[dev] == nullptr;
+    if (!addr[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p)
+            return BITSNAP_E_LAUNCH;
+        addr[dev] = p;
+    }
+    *ptr = addr[dev];
+    return BITSNAP_OK;
+}
+
+}  // namespace bitsnap
+
+extern "C" int bitsnap_encode_sparse_static(const void *cur, const void *base, int64_t n, int elem_bytes, uint8_t *mask,
+                                            void *payload, int64_t payload_capacity_elems, uint32_t *tile_offsets,
+                                            uint64_t *n_changed, bitsnap_stream_t stream)
+{
+    if (n < 0 || (elem_bytes != 2 && elem_bytes != 4))
+        return BITSNAP_E_SIZE;
+    if (tiles_of(n, elem_bytes) > (int64_t)BITSNAP_STATIC_MAX_TILES)
+        return BITSNAP_E_STATIC_LIMIT;
+    void *ws = nullptr;
+    bool first = false;
+    if (int rc = static_scratch(&ws, &first))
+        return rc;
+    if (first) {
+        // A fill kernel, not a memset: this call may be recorded into a graph.  The array starts out
+        // as zeros anyway; clearing it is right at any time no call that uses it is in flight.
+        hipLaunchKernelGGL(clear_scratch_kernel, dim3(64), dim3(256), 0, (hipStream_t)stream, (uint4 *)ws,
+                           kStaticScratchBytes / 16);
+        if (int rc = launch_status())
+            return rc;
+    }
+    return bitsnap_encode_sparse_ex(cur, base, n, elem_bytes, 0u, mask, payload, payload_capacity_elems, tile_offsets,
+                                    n_changed, nullptr, ws, kStaticScratchBytes, stream);
 }
 
 extern "C" size_t bitsnap_sparse_batch_workspace_bytes(int64_t total_tiles) { return workspace_bytes_for_tiles(total_tiles); }
