@@ -1,19 +1,21 @@
 // encode_sparse / decode_sparse: bitmask-based delta sparsification of 16-bit model states
 // (paper: "Bitmask Based Sparsification for Model States", improved bitmask; Algorithm 1) and
 // its inverse.  Encode is one kernel and one pass over HBM; decode is three kernels, of which
-// only the last touches more than the mask.
+// only the last touches more than the mask (one kernel for tensors of a few tiles, or when the
+// encoder's tile offsets come with the mask).
 //
 // Elements are 2 bytes (fp16 / bf16 model states) or 4 bytes (fp32 states); E is the element width.
 // A tile is 64 KB of each input - 32768 2-byte or 16384 4-byte elements, in rounds of 8192 - and
 // is processed by one 512-thread workgroup; all of a tile's loads are issued before anything
 // waits on them.  A lane owns pieces of 8 consecutive elements (one mask byte; one or two 16-byte
-// loads); in each round a wavefront owns two consecutive 512-element chunks.  Per-lane popcounts are scanned with DPP inside the wave,
-// through LDS across the eight waves and the rounds, and (encode) with the decoupled look-back
-// of scan_state.hpp across tiles.  The tile is large because every tile costs the machine one
+// loads); in the encoder a wavefront owns, in each round, two consecutive 512-element chunks, in the
+// decoder's merge one contiguous eighth of the tile.  Per-lane popcounts are scanned with DPP inside
+// the wave, and in the encoder through LDS across the eight waves and the rounds and with the
+// decoupled look-back of scan_state.hpp across tiles.  The tile is large because every tile costs the machine one
 // same-address atomic (the ticket) and a handful of polls of its predecessors' scan words, and
 // both are served far more slowly than streaming traffic.  Changed values are staged in LDS so
 // that the payload leaves (encode) or enters (decode) HBM as 16-byte accesses aligned on the
-// payload buffer, whatever the tile's offset.
+// payload buffer, whatever the tile's (decode: the wave's) offset.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -102,13 +104,13 @@ __device__ __forceinline__ typename Geom<E>::elem_t piece_elem(const Piece<E> &p
 }
 
 // 8 elements to p[e0 .. e0+8) (e0 a multiple of 8), clipped at n
-template <int E>
+template <bool kStream, int E>
 __device__ __forceinline__ void store8(typename Geom<E>::elem_t *p, int64_t e0, int64_t n, const Piece<E> &pc)
 {
     if (e0 + kLaneElems <= n) {
 #pragma unroll
         for (int k = 0; k < Geom<E>::kVecs; ++k)
-            store_global16<false>(p + e0 + k * Geom<E>::kVecElems, pc.v[k]);
+            store_global16<kStream>(p + e0 + k * Geom<E>::kVecElems, pc.v[k]);
         return;
     }
     for (int t = 0; t < kLaneElems; ++t)
@@ -427,7 +429,7 @@ __global__ __launch_bounds__(kBlock, 4) void encode_sparse_kernel(bitsnap_sparse
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
                 if (new_base)
-                    store8<E>(new_base, piece_chunk<E>(tile, r, wave, j) * kChunkElems + lane * kLaneElems, n, c[r][j]);
+                    store8<false, E>(new_base, piece_chunk<E>(tile, r, wave, j) * kChunkElems + lane * kLaneElems, n, c[r][j]);
                 Piece<E> x;
 #pragma unroll
                 for (int k = 0; k < Geom<E>::kVecs; ++k)
@@ -483,29 +485,12 @@ __global__ __launch_bounds__(kBlock, 4) void encode_sparse_kernel(bitsnap_sparse
     report_failures(epilogue, single, items, count, kBatched, num_tiles);
 }
 
-// The lane's mask bytes of one tile; bits at or beyond n are cleared.
-template <int E>
-__device__ __forceinline__ void load_tile_mask(const uint8_t *__restrict__ mask, int64_t mask_bytes, int64_t tile,
-                                               int wave, int lane, int64_t n, uint32_t (&m)[Geom<E>::kRounds][2])
-{
-#pragma unroll
-    for (int r = 0; r < Geom<E>::kRounds; ++r)
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            const int64_t ch = piece_chunk<E>(tile, r, wave, j);
-            const int64_t mb = ch * kWave + lane, e = ch * kChunkElems + lane * kLaneElems;
-            uint32_t bits = (mb < mask_bytes) ? ((const global_u8 *)mask)[mb] : 0u;
-            if (e + kLaneElems > n)
-                bits &= (e < n) ? ((1u << (uint32_t)(n - e)) - 1u) : 0u;
-            m[r][j] = bits;
-        }
-}
-
 // ---------------------------------------------------------------------------------------------
 // decode_sparse.  The ranks of the inverse only depend on the mask, which is 1/33 of the data, so
-// the decoder does not scan while it streams: a first kernel counts the set bits of every tile,
-// a second turns the counts into per-tile payload offsets (one workgroup per tensor), and the
-// third, which moves all the bytes, has no dependency between workgroups at all.
+// the decoder does not scan while it streams: a first kernel counts the set bits of every tile and
+// of every wave's segment inside it, a second turns the tile counts into per-tile payload offsets
+// (one workgroup per tensor), and the third, which moves all the bytes, has no dependency between
+// workgroups, and none between the waves of a workgroup either.
 // ---------------------------------------------------------------------------------------------
 
 // The item that holds launch-wide tile gt (binary search on wave-uniform operands).
@@ -522,12 +507,14 @@ __device__ __forceinline__ int64_t find_sparse_item(const bitsnap_sparse_item *_
     return lo;
 }
 
-// One wave per tile: popcount of the tile's 4 or 2 KB of mask (bits at or beyond n do not count).
+// One wave per tile: popcount of the tile's 4 or 2 KB of mask (bits at or beyond n do not count), and the
+// places of the tile's eight segments inside the tile.
 template <bool kBatched, int E>
 __global__ __launch_bounds__(kBlock) void decode_count_kernel(bitsnap_sparse_item single,
                                                               const bitsnap_sparse_item *__restrict__ items,
                                                               int64_t count, int64_t num_tiles,
-                                                              uint32_t *__restrict__ tile_count)
+                                                              uint32_t *__restrict__ tile_count,
+                                                              uint32_t *__restrict__ seg_prefix)
 {
     const int lane = threadIdx.x & (kWave - 1), wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int64_t gt = (int64_t)blockIdx.x * kWaves + wave;
@@ -538,21 +525,26 @@ __global__ __launch_bounds__(kBlock) void decode_count_kernel(bitsnap_sparse_ite
     const int64_t mask_bytes = (n + 7) >> 3;
     constexpr int kTileMaskBytes = Geom<E>::kTileElems / 8, kPerLane = kTileMaskBytes / kWave;
     static_assert(kPerLane % 8 == 0, "a lane reads whole 8-byte pieces of the mask");
-    uint32_t c = 0;
+    // Pass q covers 512 consecutive mask bytes, i.e. one or two whole segments (a wave's part of the tile in
+    // the merge): the running sums at the segments' last lanes are the segments' places inside the tile.
+    constexpr int kSegsPerPass = (kWave * 8) / (Geom<E>::kTileElems / kWaves / 8);
+    // All of the lane's loads are issued before the first is used.  An 8-byte piece that straddles the end of the
+    // mask is read whole (the buffer is 16-byte aligned, so the load stays inside the 16-byte block of the mask's
+    // last byte); one that lies beyond it reads the tile's first bytes instead; what is not mask is cleared below.
+    uint2 loaded[kPerLane / 8];
 #pragma unroll
     for (int q = 0; q < kPerLane / 8; ++q) {
         const int64_t b0 = tile * kTileMaskBytes + (int64_t)(q * kWave + lane) * 8;  // byte offset, 8-aligned
-        uint32_t w[2] = {0, 0};
-        if (b0 + 8 <= mask_bytes) {
-            const uint2 v = *reinterpret_cast<const uint2 *>(it.mask + b0);
-            w[0] = v.x, w[1] = v.y;
-        } else {
-            for (int t = 0; t < 8; ++t)
-                if (b0 + t < mask_bytes)
-                    w[t >> 2] |= (uint32_t)it.mask[b0 + t] << ((t & 3) * 8);
-        }
+        loaded[q] = *reinterpret_cast<const uint2 *>(it.mask + (b0 < mask_bytes ? b0 : tile * kTileMaskBytes));
+    }
+    uint32_t run = 0;
+#pragma unroll
+    for (int q = 0; q < kPerLane / 8; ++q) {
+        const int64_t b0 = tile * kTileMaskBytes + (int64_t)(q * kWave + lane) * 8;
+        uint32_t w[2] = {loaded[q].x, loaded[q].y};
         // bits at or beyond n carry no element
         const int64_t e0 = b0 * 8;
+        uint32_t c = 0;
 #pragma unroll
         for (int k = 0; k < 2; ++k) {
             const int64_t ek = e0 + 32 * k;
@@ -560,10 +552,17 @@ __global__ __launch_bounds__(kBlock) void decode_count_kernel(bitsnap_sparse_ite
                 w[k] &= (ek < n) ? ((1u << (uint32_t)(n - ek)) - 1u) : 0u;
             c += __popc(w[k]);
         }
+        const uint32_t incl = wave_inclusive_add(c);
+#pragma unroll
+        for (int sgm = 0; sgm < kSegsPerPass; ++sgm) {
+            const uint32_t inside = sgm == 0 ? 0u : read_lane(incl, sgm == 0 ? 0 : sgm * (kWave / kSegsPerPass) - 1);
+            if (lane == 0)
+                seg_prefix[gt * kWaves + q * kSegsPerPass + sgm] = run + inside;
+        }
+        run += read_lane(incl, kWave - 1);
     }
-    c = wave_inclusive_add(c);
-    if (lane == kWave - 1)
-        tile_count[gt] = c;
+    if (lane == 0)
+        tile_count[gt] = run;
 }
 
 // One workgroup per tensor: exclusive scan of its tiles' counts -> payload offset of every tile,
@@ -603,131 +602,222 @@ __global__ __launch_bounds__(kBlock) void decode_scan_kernel(bitsnap_sparse_item
         *it.n_changed = carry_s;
 }
 
-// One workgroup per tile: out = bit ? next payload element : base.  The tile's place in the payload
-// and its length are known from the two kernels before, so mask, base and the payload segment are
-// all requested at once; the segment goes through LDS as aligned 16-byte pieces (stage[i] holds
-// payload element src0 + i, src0 a multiple of 16 / E), from where every lane picks its elements
-// by rank.  kDelta: the payload holds cur XOR base; the element is base XOR payload.
-// kOffsets: the tensor comes with the encoder's tile_offsets, so the tile's place in the payload
-// is read from there and no counting pass ran; the tile's length is the distance to the next
-// offset, and for the tensor's last tile whatever the payload still holds, at most a tile's worth
-// (reading more than the tile's own values is harmless: only ranks below its count are used).
-template <bool kBatched, bool kDelta, bool kOffsets, int E>
+// The merge: out = bit ? next payload element : base.  One workgroup per tile, and inside the tile one
+// wavefront per segment (an eighth of the tile: 8 KB of output), each entirely on its own - no barrier
+// anywhere.  A wave requests its base pieces, its own mask bytes and the mask bytes between the start of the
+// tile and its segment at once; the popcount of the latter is the segment's place behind the tile's offset
+// (the other waves of the tile read the same few KB, from L2).  Then it fetches its part of the payload as
+// aligned 16-byte pieces into its private region of LDS (region[i] holds payload element src0 + i, src0 a
+// multiple of 16 / E), from where every lane picks its elements by rank.  With the eight waves of a tile
+// meeting at two barriers per tile, and ordinary instead of non-temporal accesses to payload and output,
+// this kernel ran 3 to 6 points of HBM peak slower (a 524 M-element tensor: 62 / 62 / 66 % at 0 / 6 / 71 %
+// changed against 67 / 68 / 69 %).
+// kDelta: the payload holds cur XOR base; the element is base XOR payload.
+// kSource: where the tile's offset in the payload comes from - the counting and scanning kernels
+// (kFromWorkspace), the encoder's tile_offsets (kFromEncoder), or nowhere: the wave counts the tensor's whole
+// mask before its segment itself (kFromMask; tensors of a few tiles, decoded by this one launch).
+enum { kFromWorkspace = 0, kFromEncoder = 1, kFromMask = 2 };
+constexpr int kSoloTiles = 8;  // single tensors of up to this many tiles take kFromMask
+
+template <int E>
+struct DecGeom {
+    static constexpr int kSegElems = Geom<E>::kTileElems / kWaves;      // 4096 two-byte or 2048 four-byte elements
+    static constexpr int kPieces = kSegElems / kChunkElems;             // 512-element pieces per segment: 8 or 4
+    static constexpr int kSegMaskBytes = kSegElems / 8;
+    static constexpr int kVecsPerLane = kSegElems / Geom<E>::kVecElems / kWave;  // 16-byte payload pieces per lane: 8
+    static_assert(kPieces % 2 == 0, "counts are scanned two to a word");
+};
+
+template <bool kBatched, bool kDelta, int kSource, int E>
 __global__ __launch_bounds__(kBlock, 4) void decode_merge_kernel(bitsnap_sparse_item single,
                                                                  const bitsnap_sparse_item *__restrict__ items,
                                                                  int64_t count, const uint64_t *__restrict__ tile_offset,
-                                                                 const uint32_t *__restrict__ tile_count)
+                                                                 const uint32_t *__restrict__ tile_count,
+                                                                 const uint32_t *__restrict__ seg_prefix)
 {
     typedef typename Geom<E>::elem_t elem_t;
     typedef typename Geom<E>::global_elem_t global_elem_t;
-    constexpr int kRounds = Geom<E>::kRounds, kTileElems = Geom<E>::kTileElems;
+    constexpr int kTileElems = Geom<E>::kTileElems, kSegElems = DecGeom<E>::kSegElems, kPieces = DecGeom<E>::kPieces,
+                  kVecs = Geom<E>::kVecs, kVecElems = Geom<E>::kVecElems, kVecsPerLane = DecGeom<E>::kVecsPerLane;
     constexpr uint32_t P = Geom<E>::kVecElems;
-    __shared__ TileShared<E> sh;
+    __shared__ alignas(16) elem_t regions[kWaves][kSegElems + 4 * P];  // + a shifted segment's end + what the merge reads past it
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int64_t gtile = blockIdx.x;
     const bitsnap_sparse_item &it = kBatched ? items[find_sparse_item(items, count, gtile)] : single;
-    const elem_t *base = (const elem_t *)it.base;  // may alias out
+    const int64_t n = it.n, payload_elems = it.capacity, tile = gtile - it.first_tile;
+    const int64_t seg0 = tile * kTileElems + (int64_t)wave * kSegElems;  // first element of the wave's segment
+    if (seg0 >= n)
+        return;
+    // every field of the item that is needed is fetched here, not where it is used: a word of the item array
+    // read late would be waited for on its own
+    const elem_t *base = (const elem_t *)it.base + seg0;  // may alias out
     const uint8_t *__restrict__ mask = it.mask;
     const elem_t *__restrict__ payload = (const elem_t *)it.payload;
+    const uint32_t *__restrict__ encoder_offsets = it.tile_offsets;
+    uint64_t *count_out = it.n_changed;
     elem_t *out = (elem_t *)it.out;
-    const int64_t n = it.n, payload_elems = it.capacity, tile = gtile - it.first_tile;
+    elem_t *region = regions[wave];
     const int64_t mask_bytes = (n + 7) >> 3;
-
-    uint64_t excl;
-    uint32_t total;
-    const bool last_tile = (tile + 1) * (int64_t)kTileElems >= n;
-    if (kOffsets) {
-        // the same for every thread: kept in scalar registers
-        const uint32_t here = __builtin_amdgcn_readfirstlane(it.tile_offsets[tile]);
-        const uint32_t next = last_tile ? 0u : __builtin_amdgcn_readfirstlane(it.tile_offsets[tile + 1]);
-        excl = here;
-        const int64_t rest = last_tile ? payload_elems - (int64_t)here : (int64_t)next - (int64_t)here;
-        total = __builtin_amdgcn_readfirstlane(rest <= 0 ? 0u : rest < kTileElems ? (uint32_t)rest : (uint32_t)kTileElems);
-    } else {
-        excl = tile_offset[gtile];
-        total = tile_count[gtile];
+    const uint32_t rem = n - seg0 >= kSegElems ? (uint32_t)kSegElems : (uint32_t)(n - seg0);
+    const uint32_t e0 = (uint32_t)(lane * kLaneElems);
+    // What the counting and scanning kernels left: the place and the length of every segment.  Read before
+    // anything else is requested, so that waiting for these few words does not mean waiting for the base as well
+    // (loads return in the order they were issued).
+    uint64_t known_start = 0;
+    uint32_t known_count = 0;
+    if (kSource == kFromWorkspace) {
+        const uint32_t here = __builtin_amdgcn_readfirstlane(seg_prefix[gtile * kWaves + wave]);
+        const uint32_t next = __builtin_amdgcn_readfirstlane(wave + 1 < kWaves ? seg_prefix[gtile * kWaves + wave + 1] : tile_count[gtile]);
+        known_start = uniform64(tile_offset[gtile]) + here;
+        known_count = next - here;
     }
-    const uint32_t shift = (uint32_t)(excl & (P - 1u));
-    const int64_t src0 = (int64_t)(excl - shift);
-    const uint32_t pieces = (shift + total + P - 1u) / P;  // at most kTileElems / P + 1
-    constexpr int kPiecesPerThread = kTileElems / (int)P / kBlock;
 
-    uint32_t m[kRounds][2], cnt[kRounds][2], rank[kRounds][2];
-    Piece<E> v[kRounds][2];
-    uint4 pv[kPiecesPerThread];
-    load_tile_mask<E>(mask, mask_bytes, tile, wave, lane, n, m);
-    load_tile<E>(base, tile, wave, lane, n, v);
-    const elem_t *__restrict__ seg = payload + src0;  // wave-uniform, 16-byte aligned
-    const int64_t seg_elems = payload_elems - src0;    // elements of seg that may be read
+    // base: a 16-byte load whose first element lies at or beyond the end of the tensor reads the segment's first
+    // 16 bytes instead; one that straddles the end is made whole (the buffer is 16-byte aligned)
+    Piece<E> v[kPieces];
 #pragma unroll
-    for (int i = 0; i < kPiecesPerThread; ++i) {
-        const uint32_t q = (uint32_t)(i * kBlock + tid);
-        pv[i] = make_uint4(0, 0, 0, 0);
-        if (q < pieces) {
-            if ((int64_t)(q * P + P) <= seg_elems) {
-                pv[i] = load_global16<false>(seg + q * P);
-            } else {
-                uint32_t w[4] = {0, 0, 0, 0};
-                for (uint32_t t = 0; t < P; ++t)
-                    if ((int64_t)(q * P + t) < seg_elems)
-                        w[(t * E) >> 2] |= (uint32_t)((const global_elem_t *)seg)[q * P + t] << (((t * E) & 3u) * 8u);
-                pv[i] = make_uint4(w[0], w[1], w[2], w[3]);
-            }
+    for (int q = 0; q < kPieces; ++q)
+#pragma unroll
+        for (int k = 0; k < kVecs; ++k) {
+            const uint32_t ek = e0 + (uint32_t)(q * kChunkElems + k * kVecElems);
+            v[q].v[k] = load_global16<true>(base + (ek < rem ? ek : 0u));
         }
+    // the segment's own mask bytes, one per lane and piece; bits at or beyond n carry no element
+    uint32_t m[kPieces];
+#pragma unroll
+    for (int q = 0; q < kPieces; ++q) {
+        const int64_t mb = (seg0 >> 3) + q * kWave + lane;
+        uint32_t bits = (mb < mask_bytes) ? ((const global_u8 *)mask)[mb] : 0u;
+        const int32_t left = (int32_t)rem - (int32_t)(q * kChunkElems) - (int32_t)e0;
+        bits &= left >= kLaneElems ? 0xFFu : left > 0 ? (1u << left) - 1u : 0u;
+        m[q] = bits;
     }
+    // The segment's changed values, payload elements [start, start + seg_count), as aligned 16-byte pieces.
+    uint64_t start = 0;
+    uint32_t seg_count = 0, shift = 0, pieces = 0;
+    uint4 pv[kVecsPerLane];
+    const elem_t *__restrict__ seg = nullptr;
+    int64_t seg_elems = 0;
+    // Non-temporal accesses to payload and output pay where little changed (the output is mostly a copy of the
+    // base: 66 -> 69-70 % of HBM peak on checkpoints with 6 % changed) and cost where most did (66 -> 63 % at 71 %
+    // changed), so every wave picks by its own segment.
+    bool dense = false;
+    auto request_payload = [&]() {
+        dense = 2 * seg_count > (uint32_t)kSegElems;
+        shift = (uint32_t)(start & (P - 1u));
+        const int64_t src0 = (int64_t)(start - shift);
+        pieces = (shift + seg_count + P - 1u) / P;           // at most kSegElems / P + 1
+        seg = payload + src0;                                // wave-uniform, 16-byte aligned
+        seg_elems = payload_elems - src0;                    // elements of seg that may be read
 #pragma unroll
-    for (int r = 0; r < kRounds; ++r)
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-            cnt[r][j] = __popc(m[r][j]);
-    const uint32_t tile_total = tile_ranks<E>(sh, cnt, lane, wave, rank);  // barrier
-#pragma unroll
-    for (int i = 0; i < kPiecesPerThread; ++i)
-        *reinterpret_cast<uint4 *>(&sh.stage[(uint32_t)(i * kBlock + tid) * P]) = pv[i];
-    if (tid == 0 && pieces > (uint32_t)(kPiecesPerThread * kBlock)) {  // a full tile that starts off the 16-byte grid
-        const uint32_t q = (uint32_t)(kPiecesPerThread * kBlock);
-        for (uint32_t t = 0; t < P; ++t)
-            sh.stage[q * P + t] = (int64_t)(q * P + t) < seg_elems ? ((const global_elem_t *)seg)[q * P + t] : (elem_t)0;
-    }
-    __syncthreads();
-#pragma unroll
-    for (int r = 0; r < kRounds; ++r)
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            uint32_t p = shift + rank[r][j];
-            uint32_t w[2 * E];  // the piece's dwords
-#pragma unroll
-            for (int k = 0; k < 2 * E; ++k)
-                w[k] = word_of(v[r][j].v[k >> 2], k & 3);
-#pragma unroll
-            for (int t = 0; t < kLaneElems; ++t) {
-                if ((m[r][j] >> t) & 1u) {
-                    const uint32_t s = sh.stage[p++];
-                    if (E == 4) {
-                        w[t] = kDelta ? (w[t] ^ s) : s;
-                    } else if (kDelta) {
-                        w[t >> 1] ^= s << ((t & 1) * 16);
-                    } else {
-                        w[t >> 1] = (t & 1) ? ((w[t >> 1] & 0x0000FFFFu) | (s << 16)) : ((w[t >> 1] & 0xFFFF0000u) | s);
-                    }
+        for (int i = 0; i < kVecsPerLane; ++i) {
+            const uint32_t q = (uint32_t)(i * kWave + lane);
+            pv[i] = make_uint4(0, 0, 0, 0);  // never read at or beyond payload_elems: what is missing decodes to 0
+            if (q < pieces) {
+                if ((int64_t)(q * P + P) <= seg_elems) {
+                    pv[i] = dense ? load_global16<false>(seg + q * P) : load_global16<true>(seg + q * P);
+                } else {
+                    uint32_t w[4] = {0, 0, 0, 0};
+                    for (uint32_t t = 0; t < P; ++t)
+                        if ((int64_t)(q * P + t) < seg_elems)
+                            w[(t * E) >> 2] |= (uint32_t)((const global_elem_t *)seg)[q * P + t] << (((t * E) & 3u) * 8u);
+                    pv[i] = make_uint4(w[0], w[1], w[2], w[3]);
                 }
             }
-            Piece<E> res;
-#pragma unroll
-            for (int k = 0; k < Geom<E>::kVecs; ++k)
-                res.v[k] = make_uint4(w[4 * k + 0], w[4 * k + 1], w[4 * k + 2], w[4 * k + 3]);
-            store8<E>(out, piece_chunk<E>(tile, r, wave, j) * kChunkElems + lane * kLaneElems, n, res);
         }
-    if (kOffsets && last_tile && tid == 0 && it.n_changed)
-        *it.n_changed = excl + tile_total;  // no scan kernel ran to report it; last, when few registers are live
+    };
+    if (kSource == kFromWorkspace) {
+        start = known_start;
+        seg_count = known_count;
+        request_payload();
+    }
+    // ranks inside the segment
+    uint32_t rank[kPieces], counted = 0;
+#pragma unroll
+    for (int q = 0; q < kPieces; q += 2) {
+        const uint32_t c0 = __popc(m[q]), c1 = __popc(m[q + 1]);
+        const uint32_t pk = c0 | (c1 << 16);
+        const uint32_t incl = wave_inclusive_add(pk);
+        const uint32_t tot = read_lane(incl, kWave - 1);
+        const uint32_t ex = incl - pk;
+        rank[q] = counted + (ex & 0xFFFFu);
+        rank[q + 1] = counted + (tot & 0xFFFFu) + (ex >> 16);
+        counted += (tot & 0xFFFFu) + (tot >> 16);
+    }
+    if (kSource != kFromWorkspace) {
+        // set bits between the point the known offset refers to and the segment (whole bytes of whole segments)
+        const int64_t from = kSource == kFromMask ? 0 : tile * (int64_t)(kTileElems / 8);
+        const int32_t prior_bytes = (int32_t)((seg0 >> 3) - from);
+        uint32_t before = 0;
+#pragma unroll 8
+        for (int32_t o = lane * 8; o < prior_bytes; o += kWave * 8) {
+            const uint2 w = *reinterpret_cast<const uint2 *>(mask + from + o);
+            before += __popc(w.x) + __popc(w.y);
+        }
+        before = read_lane(wave_inclusive_add(before), kWave - 1);
+        const uint64_t tile_excl = kSource == kFromEncoder ? (uint64_t)__builtin_amdgcn_readfirstlane(encoder_offsets[tile]) : 0ull;
+        start = tile_excl + before;
+        seg_count = counted;
+        request_payload();
+    }
+#pragma unroll
+    for (int i = 0; i < kVecsPerLane; ++i)
+        *reinterpret_cast<uint4 *>(&region[(uint32_t)(i * kWave + lane) * P]) = pv[i];
+    if (lane == 0 && pieces > (uint32_t)(kVecsPerLane * kWave)) {  // a full segment that starts off the 16-byte grid
+        const uint32_t q = (uint32_t)(kVecsPerLane * kWave);
+        for (uint32_t t = 0; t < P; ++t)
+            region[q * P + t] = (int64_t)(q * P + t) < seg_elems ? ((const global_elem_t *)seg)[q * P + t] : (elem_t)0;
+    }
+    __builtin_amdgcn_wave_barrier();  // the region is read by other lanes of this wave than wrote it
+    // Element t of a piece takes region[p + (set bits below t)] if its bit is set.  Straight-line code: the value
+    // is read whether or not the bit is set (the region is long enough for that) and then kept or dropped
+    // through a mask of the bit; with a branch per element the merge was four times as many instructions.
+#pragma unroll
+    for (int q = 0; q < kPieces; ++q) {
+        const uint32_t p = shift + rank[q];
+        uint32_t w[2 * E];  // the piece's dwords
+#pragma unroll
+        for (int k = 0; k < 2 * E; ++k)
+            w[k] = word_of(v[q].v[k >> 2], k & 3);
+        uint32_t val[kLaneElems], keep[kLaneElems];
+#pragma unroll
+        for (int t = 0; t < kLaneElems; ++t) {
+            val[t] = region[p + __popc(m[q] & ((1u << t) - 1u))];
+            keep[t] = (uint32_t)(-(int32_t)((m[q] >> t) & 1u));  // all ones where the element changed
+        }
+        if (E == 4) {
+#pragma unroll
+            for (int t = 0; t < kLaneElems; ++t)
+                w[t] = kDelta ? (w[t] ^ (val[t] & keep[t])) : ((val[t] & keep[t]) | (w[t] & ~keep[t]));
+        } else {
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const uint32_t pair = (val[2 * k] & 0xFFFFu) | (val[2 * k + 1] << 16);
+                const uint32_t km = (keep[2 * k] & 0xFFFFu) | (keep[2 * k + 1] << 16);
+                w[k] = kDelta ? (w[k] ^ (pair & km)) : ((pair & km) | (w[k] & ~km));
+            }
+        }
+        Piece<E> res;
+#pragma unroll
+        for (int k = 0; k < kVecs; ++k)
+            res.v[k] = make_uint4(w[4 * k + 0], w[4 * k + 1], w[4 * k + 2], w[4 * k + 3]);
+        if (dense)
+            store8<false, E>(out, seg0 + q * kChunkElems + e0, n, res);
+        else
+            store8<true, E>(out, seg0 + q * kChunkElems + e0, n, res);
+    }
+    // no scan kernel ran to report the count: the wave that holds the tensor's last element knows it
+    if (kSource != kFromWorkspace && lane == 0 && count_out && seg0 + kSegElems >= n)
+        *count_out = start + seg_count;
 }
 
 // Workspace after the header: encode keeps one 8-byte scan word per tile there; decode keeps the
-// tiles' payload offsets (8 bytes each, in the same place) followed by their counts (4 bytes each).
+// tiles' payload offsets (8 bytes each, in the same place) followed by their counts (4 bytes each)
+// and the places of their segments (8 x 4 bytes each).
 // A raw offset is below 2^40, so as a scan word its flag bits read "not written": a decode never
 // confuses a later encode.
 constexpr size_t kWorkspaceBytesPerTile = 8 * kStatusStride;
-static_assert(kWorkspaceBytesPerTile >= 12, "decode keeps 8 + 4 bytes per tile");
+static_assert(kWorkspaceBytesPerTile >= 12 + 4 * kWaves, "decode keeps 8 + 4 + 4 * 8 bytes per tile");
 
 static std::atomic<uint32_t> g_spin_limit{kDefaultSpinLimit};
 
@@ -821,6 +911,15 @@ static int check_scan_workspace(void *workspace, size_t workspace_bytes, int64_t
     return BITSNAP_OK;
 }
 
+template <bool kBatched, bool kDelta, int kSource, int E>
+static void launch_merge(const bitsnap_sparse_item &single, const bitsnap_sparse_item *items, int64_t count,
+                         int64_t num_tiles, const uint64_t *tile_offset, hipStream_t s)
+{
+    const uint32_t *tile_count = reinterpret_cast<const uint32_t *>(tile_offset + num_tiles);
+    hipLaunchKernelGGL((decode_merge_kernel<kBatched, kDelta, kSource, E>), dim3((unsigned)num_tiles), dim3(kBlock), 0, s,
+                       single, items, count, tile_offset, tile_count, tile_count + num_tiles);
+}
+
 template <bool kBatched, int E>
 static int launch_decode_e(const bitsnap_sparse_item &single, const bitsnap_sparse_item *items, int64_t count,
                            int64_t num_tiles, void *workspace, bitsnap_stream_t stream, bool delta, bool offsets)
@@ -828,32 +927,32 @@ static int launch_decode_e(const bitsnap_sparse_item &single, const bitsnap_spar
     uint64_t *tile_offset = reinterpret_cast<uint64_t *>(reinterpret_cast<char *>(workspace) + kScanHeaderBytes);
     uint32_t *tile_count = reinterpret_cast<uint32_t *>(tile_offset + num_tiles);
     hipStream_t s = (hipStream_t)stream;
+    if (num_tiles > 0x7FFFFFFF || (num_tiles + kWaves - 1) / kWaves > 0x7FFFFFFF)
+        return BITSNAP_E_SIZE;
     if (offsets && num_tiles > 0) {  // the encoder's tile offsets are given: one launch, nothing to count
-        if (num_tiles > 0x7FFFFFFF)
-            return BITSNAP_E_SIZE;
         if (delta)
-            hipLaunchKernelGGL((decode_merge_kernel<kBatched, true, true, E>), dim3((unsigned)num_tiles), dim3(kBlock), 0, s,
-                               single, items, count, tile_offset, tile_count);
+            launch_merge<kBatched, true, kFromEncoder, E>(single, items, count, num_tiles, tile_offset, s);
         else
-            hipLaunchKernelGGL((decode_merge_kernel<kBatched, false, true, E>), dim3((unsigned)num_tiles), dim3(kBlock), 0, s,
-                               single, items, count, tile_offset, tile_count);
+            launch_merge<kBatched, false, kFromEncoder, E>(single, items, count, num_tiles, tile_offset, s);
         return launch_status();
     }
-    if (num_tiles > 0) {
-        if ((num_tiles + kWaves - 1) / kWaves > 0x7FFFFFFF || num_tiles > 0x7FFFFFFF)
-            return BITSNAP_E_SIZE;
-        hipLaunchKernelGGL((decode_count_kernel<kBatched, E>), dim3((unsigned)((num_tiles + kWaves - 1) / kWaves)),
-                           dim3(kBlock), 0, s, single, items, count, num_tiles, tile_count);
+    if (!kBatched && num_tiles > 0 && num_tiles <= kSoloTiles) {  // a small tensor: every wave counts for itself
+        if (delta)
+            launch_merge<kBatched, true, kFromMask, E>(single, items, count, num_tiles, tile_offset, s);
+        else
+            launch_merge<kBatched, false, kFromMask, E>(single, items, count, num_tiles, tile_offset, s);
+        return launch_status();
     }
+    if (num_tiles > 0)
+        hipLaunchKernelGGL((decode_count_kernel<kBatched, E>), dim3((unsigned)((num_tiles + kWaves - 1) / kWaves)),
+                           dim3(kBlock), 0, s, single, items, count, num_tiles, tile_count, tile_count + num_tiles);
     // the scan also reports n_changed, for an empty tensor too
     hipLaunchKernelGGL((decode_scan_kernel<kBatched, E>), dim3((unsigned)(kBatched ? count : 1)), dim3(kBlock), 0, s,
                        single, items, tile_count, tile_offset);
     if (num_tiles > 0 && delta)
-        hipLaunchKernelGGL((decode_merge_kernel<kBatched, true, false, E>), dim3((unsigned)num_tiles), dim3(kBlock), 0, s,
-                           single, items, count, tile_offset, tile_count);
+        launch_merge<kBatched, true, kFromWorkspace, E>(single, items, count, num_tiles, tile_offset, s);
     else if (num_tiles > 0)
-        hipLaunchKernelGGL((decode_merge_kernel<kBatched, false, false, E>), dim3((unsigned)num_tiles), dim3(kBlock), 0, s,
-                           single, items, count, tile_offset, tile_count);
+        launch_merge<kBatched, false, kFromWorkspace, E>(single, items, count, num_tiles, tile_offset, s);
     return launch_status();
 }
 
