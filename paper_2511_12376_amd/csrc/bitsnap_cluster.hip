@@ -84,24 +84,27 @@ __device__ __forceinline__ void quantize_group(const float *__restrict__ x, int6
     code_pass<K, kFull>(v, lo, len, packed, ws, lane, codes);
 }
 
-// Full groups: one wave per group, `groups` of them.  The short last group of a tensor (if any)
-// goes through the same code with bounds checks, as a launch of its own (kFull = false, one wave).
-template <int K, bool kFull>
+// One wave per group.  A tensor's short last group (if it has one) goes through the same code with bounds
+// checks, in the same launch: both forms fit the register budget of four waves per SIMD, and a launch of
+// its own for one wave costs as much as a launch for a few thousand.
+template <int K>
 __global__ __launch_bounds__(kQBlock) void quantize_cluster_kernel(
-    const float *__restrict__ x, int64_t n, int64_t first_group, int64_t groups, int m, uint8_t *__restrict__ codes,
+    const float *__restrict__ x, int64_t n, int64_t groups, int m, uint8_t *__restrict__ codes,
     uint8_t *__restrict__ labels, float *__restrict__ params, float *__restrict__ fit_out,
     const float *__restrict__ fit_in, uint32_t *__restrict__ status)
 {
     __shared__ WaveShared shared[kQWaves];
-    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
-    const int64_t g = first_group + (int64_t)blockIdx.x * kQWaves + wave;
-    if (g >= first_group + groups)
+    const int lane = threadIdx.x & (kWave - 1), wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int64_t g = (int64_t)blockIdx.x * kQWaves + wave;
+    if (g >= groups)
         return;  // whole wave leaves; the kernel has no workgroup barrier
     constexpr int G = 256 * K;
     const int64_t lo = g * G;
     const int64_t rest = n - lo;
-    const int len = kFull ? G : (int)(rest < G ? rest : G);
-    quantize_group<K, kFull>(x, lo, len, m, g, codes, labels, params, fit_out, fit_in, status, shared[wave], lane);
+    if (rest >= G)
+        quantize_group<K, true>(x, lo, G, m, g, codes, labels, params, fit_out, fit_in, status, shared[wave], lane);
+    else
+        quantize_group<K, false>(x, lo, (int)rest, m, g, codes, labels, params, fit_out, fit_in, status, shared[wave], lane);
 }
 
 template <int K>
@@ -135,7 +138,7 @@ __device__ __forceinline__ int64_t uniform_i64(int64_t v)
     return (int64_t)(((uint64_t)hi << 32) | lo);
 }
 
-template <int K, bool kFull>
+template <int K>
 __global__ __launch_bounds__(kQBlock) void quantize_cluster_batched_kernel(
     const bitsnap_cluster_item *__restrict__ items, int64_t count, int64_t total_groups, int m,
     uint32_t *__restrict__ status)
@@ -144,28 +147,19 @@ __global__ __launch_bounds__(kQBlock) void quantize_cluster_batched_kernel(
     // the wave index as a scalar: group and item bookkeeping then lives in SGPRs
     const int lane = threadIdx.x & (kWave - 1), wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     constexpr int G = 256 * K;
-    if (kFull) {
-        const int64_t gg = (int64_t)blockIdx.x * kQWaves + wave;
-        if (gg >= total_groups)
-            return;
-        const bitsnap_cluster_item &it = items[find_item(items, count, gg)];
-        const int64_t g = gg - it.first_group;
-        const int64_t lo = g * G;
-        if (it.n - lo >= G)  // a short last group is left to the tail launch
-            quantize_group<K, true>((const float *)it.values, lo, G, m, g, it.codes, it.labels, it.params, it.fit_out,
-                                    it.fit_in, status, shared[wave], lane);
-    } else {
-        // one wave per tensor: its short last group, if it has one
-        const int64_t t = (int64_t)blockIdx.x * kQWaves + wave;
-        if (t >= count)
-            return;
-        const bitsnap_cluster_item &it = items[t];
-        const int64_t g = it.n / G;
-        const int rest = (int)(it.n - g * G);
-        if (rest > 0)
-            quantize_group<K, false>((const float *)it.values, g * G, rest, m, g, it.codes, it.labels, it.params,
-                                     it.fit_out, it.fit_in, status, shared[wave], lane);
-    }
+    const int64_t gg = (int64_t)blockIdx.x * kQWaves + wave;
+    if (gg >= total_groups)
+        return;
+    const bitsnap_cluster_item &it = items[find_item(items, count, gg)];
+    const int64_t g = gg - it.first_group;
+    const int64_t lo = g * G;
+    const int64_t rest = it.n - lo;
+    if (rest >= G)
+        quantize_group<K, true>((const float *)it.values, lo, G, m, g, it.codes, it.labels, it.params, it.fit_out,
+                                it.fit_in, status, shared[wave], lane);
+    else if (rest > 0)  // the tensor's short last group
+        quantize_group<K, false>((const float *)it.values, lo, (int)rest, m, g, it.codes, it.labels, it.params,
+                                 it.fit_out, it.fit_in, status, shared[wave], lane);
 }
 
 template <int K>
@@ -255,22 +249,15 @@ extern "C" int bitsnap_quantize_cluster(const float *x, int64_t n, int64_t group
                                         (hipStream_t)stream);
     }
     const int64_t G = 256 * (int64_t)K;
-    const int64_t full = n / G;                  // groups that are complete
-    const bool tail = (n % G) != 0;              // plus one short group
-    const int64_t blocks = (full + kQWaves - 1) / kQWaves;
+    const int64_t groups = (n + G - 1) / G;      // the last one may be short
+    const int64_t blocks = (groups + kQWaves - 1) / kQWaves;
     if (blocks > 0x7FFFFFFF)
         return BITSNAP_E_SIZE;
     const dim3 block(kQBlock);
     hipStream_t s = (hipStream_t)stream;
-#define BITSNAP_LAUNCH_Q(KK)                                                                                       \
-    do {                                                                                                           \
-        if (full > 0)                                                                                              \
-            hipLaunchKernelGGL((quantize_cluster_kernel<KK, true>), dim3((unsigned)blocks), block, 0, s, x, n,     \
-                               (int64_t)0, full, m, codes, labels, params, fit_out, fit_in, status);               \
-        if (tail)                                                                                                  \
-            hipLaunchKernelGGL((quantize_cluster_kernel<KK, false>), dim3(1), block, 0, s, x, n, full, (int64_t)1, \
-                               m, codes, labels, params, fit_out, fit_in, status);                                 \
-    } while (0)
+#define BITSNAP_LAUNCH_Q(KK)                                                                              \
+    hipLaunchKernelGGL((quantize_cluster_kernel<KK>), dim3((unsigned)blocks), block, 0, s, x, n, groups, \
+                       m, codes, labels, params, fit_out, fit_in, status)
     switch (K) {
     case 1: BITSNAP_LAUNCH_Q(1); break;
     case 2: BITSNAP_LAUNCH_Q(2); break;
@@ -335,15 +322,10 @@ extern "C" int bitsnap_quantize_cluster_batched(const bitsnap_cluster_item *item
         return BITSNAP_E_ALIGN;
     if (batched_blocks(total_groups) > 0x7FFFFFFF)
         return BITSNAP_E_SIZE;
-    const dim3 block(kQBlock), grid((unsigned)batched_blocks(total_groups)), tgrid((unsigned)((count + kQWaves - 1) / kQWaves));
+    const dim3 block(kQBlock), grid((unsigned)batched_blocks(total_groups));
     hipStream_t s = (hipStream_t)stream;
-#define BITSNAP_LAUNCH_QB(KK)                                                                                     \
-    do {                                                                                                          \
-        hipLaunchKernelGGL((quantize_cluster_batched_kernel<KK, true>), grid, block, 0, s, items, count,          \
-                           total_groups, m, status);                                                              \
-        hipLaunchKernelGGL((quantize_cluster_batched_kernel<KK, false>), tgrid, block, 0, s, items, count,        \
-                           total_groups, m, status);                                                              \
-    } while (0)
+#define BITSNAP_LAUNCH_QB(KK) \
+    hipLaunchKernelGGL((quantize_cluster_batched_kernel<KK>), grid, block, 0, s, items, count, total_groups, m, status)
     switch (K) {
     case 1: BITSNAP_LAUNCH_QB(1); break;
     case 2: BITSNAP_LAUNCH_QB(2); break;

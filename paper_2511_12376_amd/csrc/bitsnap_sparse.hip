@@ -369,7 +369,9 @@ __device__ __forceinline__ void copy_out_stage(const TileShared<E> &sh, typename
 // kDelta: the payload holds cur XOR base (the non-zero elements of the delta states) instead of
 // cur.  refresh: item.out, where set, receives a copy of cur (it may be the base buffer itself: a
 // tile's base is in registers before the tile's copy of cur is stored, and no other tile touches it).
-template <bool kBatched, bool kDelta, int E>
+// kSolo: the launch is one workgroup for a tensor of one tile, which needs no ticket, no scan state and no
+// last-workgroup bookkeeping: the workspace is not touched at all.
+template <bool kBatched, bool kDelta, int E, bool kSolo = false>
 __global__ __launch_bounds__(kBlock, 4) void encode_sparse_kernel(bitsnap_sparse_item single,
                                                                const bitsnap_sparse_item *__restrict__ items,
                                                                int64_t count, ScanHeader *hdr, uint64_t *status,
@@ -380,12 +382,12 @@ __global__ __launch_bounds__(kBlock, 4) void encode_sparse_kernel(bitsnap_sparse
     constexpr int kRounds = Geom<E>::kRounds, kTileElems = Geom<E>::kTileElems;
     __shared__ TileShared<E> sh;
     const int tid0 = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid0 >> 6);
-    const uint32_t epoch = hdr->epoch;
+    const uint32_t epoch = kSolo ? 0u : hdr->epoch;
     bool aborted = false;
     ItemCursor<kBatched> cursor(single, items, count);
 
     if (tid0 == 0)
-        sh.next_tile = (int64_t)atomicAdd(&hdr->ticket, 1u);
+        sh.next_tile = kSolo ? 0 : (int64_t)atomicAdd(&hdr->ticket, 1u);
     __syncthreads();
     // the previous tile of this workgroup: staged in LDS, still to be copied out
     bool staged = false;
@@ -445,7 +447,7 @@ __global__ __launch_bounds__(kBlock, 4) void encode_sparse_kernel(bitsnap_sparse
                     ((global_u8 *)(wave_mask + mb))[(uint32_t)lane] = (uint8_t)m[r][j];
             }
         const uint32_t total = tile_ranks<E>(sh, cnt, lane, wave, rank);  // barrier
-        if (tid == 0)
+        if (!kSolo && tid == 0)
             publish(status, gtile, make_status(tile == 0 ? kFlagInclusive : kFlagAggregate, epoch, total));
 
         // Algorithm 1 step 5, first half: changed values in index order, at their rank inside the tile
@@ -477,10 +479,12 @@ __global__ __launch_bounds__(kBlock, 4) void encode_sparse_kernel(bitsnap_sparse
                 it.tile_offsets[tile] = (uint32_t)staged_excl;
             if ((tile + 1) * kTileElems >= n)  // the tensor's last tile knows the total
                 *it.n_changed = staged_excl + total;
-            sh.next_tile = (int64_t)atomicAdd(&hdr->ticket, 1u);
+            sh.next_tile = kSolo ? 1 : (int64_t)atomicAdd(&hdr->ticket, 1u);
         }
         __syncthreads();  // the next tile is known
     }
+    if (kSolo)
+        return;
     const int epilogue = scan_epilogue(hdr, status, status_cap, epoch, aborted);
     report_failures(epilogue, single, items, count, kBatched, num_tiles);
 }
@@ -971,6 +975,27 @@ static int launch_encode(const bitsnap_sparse_item &single, const bitsnap_sparse
                          int64_t num_tiles, void *workspace, size_t workspace_bytes, bitsnap_stream_t stream, bool delta,
                          int refresh, int elem_bytes)
 {
+    if (!kBatched && num_tiles == 1) {  // one workgroup, nothing to coordinate
+        ScanHeader *hdr = reinterpret_cast<ScanHeader *>(workspace);
+        const dim3 one(1), block(kBlock);
+        hipStream_t s = (hipStream_t)stream;
+#define BITSNAP_LAUNCH_SOLO(D, EB)                                                                                   \
+    hipLaunchKernelGGL((encode_sparse_kernel<false, D, EB, true>), one, block, 0, s, single, items, count, hdr, nullptr, \
+                       (int64_t)0, num_tiles, 0u, refresh)
+        if (elem_bytes == 4) {
+            if (delta)
+                BITSNAP_LAUNCH_SOLO(true, 4);
+            else
+                BITSNAP_LAUNCH_SOLO(false, 4);
+        } else {
+            if (delta)
+                BITSNAP_LAUNCH_SOLO(true, 2);
+            else
+                BITSNAP_LAUNCH_SOLO(false, 2);
+        }
+#undef BITSNAP_LAUNCH_SOLO
+        return launch_status();
+    }
     if (elem_bytes == 4) {
         if (delta)
             return launch_scan(&encode_sparse_kernel<kBatched, true, 4>, single, items, count, num_tiles, workspace,
