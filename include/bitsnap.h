@@ -16,7 +16,12 @@
  *   - Return value: BITSNAP_OK or a negative BITSNAP_E_* code.  Errors are found on the host
  *     before anything is launched; a rejected call has touched no buffer.
  *   - Tensors are flat and contiguous.  Pointers named below as "aligned" must be multiples
- *     of 16 bytes.
+ *     of 16 bytes.  Input buffers that are aligned (cur, base, mask, payload, codes, labels, x) are
+ *     read in whole 16-byte pieces: a buffer whose length is not a multiple of 16 bytes is read up
+ *     to the next 16-byte boundary past its last element (never beyond that, and what lies there
+ *     does not influence any output).  Any allocator that hands out 16-byte granules - hipMalloc,
+ *     torch - satisfies this; a sub-buffer carved out of a larger one must leave those bytes
+ *     readable.
  *   - Two calls that share a workspace must not overlap in time.
  */
 #ifndef BITSNAP_H
@@ -48,6 +53,9 @@ int bitsnap_version(void);
 
 /* Static, NUL-terminated text for a return code (host pointer, never freed). */
 const char *bitsnap_error_string(int code);
+
+/* The bitsnap_debug_* entry points are measurement and test aids, not part of the codec's surface:
+ * they may change or disappear between versions. */
 
 /* Diagnostic: a plain 16-byte-per-lane streaming copy of `bytes` (a multiple of 16) from src to
  * dst, both aligned.  It moves exactly `bytes` in and `bytes` out, which makes it the yardstick
@@ -139,9 +147,9 @@ int bitsnap_decode_sparse(const void *base, const uint8_t *mask, const void *pay
 
 /* bitsnap_encode_sparse with two options.
  *   flags & BITSNAP_SPARSE_DELTA   the payload holds the non-zero elements of the delta states
- *                    themselves - "save the bitmask list and the non-zero elements", as the paper's
- *                    section on bitmask sparsification has it - with the delta of two bit patterns
- *                    taken bitwise, cur XOR base, which keeps the scheme lossless.  Mask, n_changed,
+ *                    themselves (the literal reading of what the section "Bitmask Based
+ *                    Sparsification for Model States" stores beside the mask), with the delta of two
+ *                    bit patterns taken bitwise, cur XOR base, which keeps the scheme lossless.  Mask, n_changed,
  *                    tile_offsets and the order of the payload do not depend on the flag.
  *   new_base         nullable; [n] elements out, aligned: receives a copy of cur, for the checkpoint that
  *                    becomes the base of the following delta checkpoints (the paper's interval
@@ -182,7 +190,9 @@ int bitsnap_encode_sparse_static(const void *cur, const void *base, int64_t n, i
 
 /* Host-side knob for tests of the give-up path: the number of polls a workgroup spends waiting
  * for a predecessor's scan state before it reports failure through n_changed.  0 restores the
- * default (large enough never to trigger in normal operation). */
+ * default (large enough never to trigger in normal operation).  The value is PROCESS-GLOBAL (one
+ * atomic word, read by every later encode call on any thread, stream or device when it launches):
+ * a test aid, not to be called by code that encodes concurrently on other threads. */
 void bitsnap_debug_set_spin_limit(uint32_t polls);
 
 /* ------------------------------------------------------------------------------------------
@@ -244,8 +254,9 @@ int bitsnap_dequantize_cluster(const uint8_t *codes, const uint8_t *labels, cons
  *        other table the codes are unspecified, still 0..255).  code = the index of the entry
  *        nearest to t = (x-b)/S, the lowest such index where several are equally near, decided
  *        in fp32: t = fl32(fl32(x-b) * fl32(1/S)), distance fl32(|Q_j - t|); a cluster whose
- *        range cannot be coded (S = 0, or 1/S not finite) gets code 0.  Dequantisation is
- *        "T^D = Q^map(T^Q)*S + b": out = fl32(fl32(Q[code] * S) + b).  NULL = the linear map of
+ *        range cannot be coded (S = 0, or 1/S not finite) gets code 0.  Dequantisation maps the code
+ *        back through the table, scales by S and adds b (the section's dequantisation formula):
+ *        out = fl32(fl32(Q[code] * S) + b).  NULL = the linear map of
  *        the plain entry points (levels j/255, S/255 folded into one factor).
  * flags  BITSNAP_CLUSTER_MAJOR: the codes of a group are stored cluster by cluster - all of
  *        cluster 0, then cluster 1, ... - and inside a cluster in element order: the T_{C_i k}
@@ -274,7 +285,7 @@ int bitsnap_dequantize_cluster_ex(const uint8_t *codes, const uint8_t *labels, c
 
 /* ------------------------------------------------------------------------------------------
  * Batched forms: one launch for a whole list of tensors.  The paper compresses an entire
- * state_dict per checkpoint ("process the state_dict", section "Details of Modifications"); a
+ * state_dict per checkpoint (section "Details of Modifications"); a
  * launch per tensor leaves the device ramping up and draining a few thousand groups at a time.
  * Results are identical to calling the single-tensor entry point on every item.
  *

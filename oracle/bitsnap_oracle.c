@@ -103,7 +103,7 @@ void oracle_decode_sparse(const uint16_t *base, const uint8_t *mask, const uint1
 /* The same codec with the two options of the extended entry points.
  *   delta != 0   the payload holds the non-zero elements of the delta states themselves, with
  *                the delta of two 16-bit patterns taken as their bitwise difference cur XOR base
- *                (the section's "save the bitmask list and the non-zero elements" read literally;
+ *                (what the section stores beside the mask, read literally;
  *                an arithmetic fp16/bf16 difference would not reconstruct bit for bit);
  *                delta == 0 stores the new values, as oracle_encode_sparse does.
  *   new_base     if not NULL, receives a copy of cur: the tensor becomes the base of the next

@@ -48,6 +48,41 @@ def test_cluster_size_helpers_follow_size_analysis():
     assert B.cluster_fit_floats(n, 4096, m) == 256 * 17
 
 
+def _quantile_decimal(k, m):
+    """Phi^{-1}(k/m) to about 60 digits: Taylor series of erf plus Newton's iteration, all in Decimal."""
+    from decimal import Decimal, getcontext
+    getcontext().prec = 70
+    pi = Decimal("3.14159265358979323846264338327950288419716939937510582097494459230781640628620899862803")
+    p = Decimal(k) / Decimal(m)
+
+    def cdf(z):
+        x = z / Decimal(2).sqrt()
+        s, term, n = Decimal(0), x, 0
+        while True:
+            t = term / (2 * n + 1)
+            s += t
+            if abs(t) < Decimal(10) ** -65:
+                break
+            n += 1
+            term = -term * x * x / n
+        return (1 + 2 * s / pi.sqrt()) / 2
+
+    z = Decimal(0)
+    for _ in range(100):
+        dz = (cdf(z) - p) * (2 * pi).sqrt() / (-(z * z) / 2).exp()
+        z -= dz
+        if abs(dz) < Decimal(10) ** -60:
+            break
+    return z
+
+
+def test_quantile_table_is_the_correctly_rounded_normal_quantile():
+    # the library's literals against the mathematics itself, not against the oracle
+    for m in range(2, 17):
+        for k in range(1, m):
+            assert B.cluster_z(k, m) == float(_quantile_decimal(k, m))
+
+
 def test_quantile_table_matches_oracle_bit_for_bit():
     for m in range(2, 17):
         for k in range(1, m):

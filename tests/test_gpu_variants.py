@@ -1,8 +1,8 @@
 """GPU parity: the format variants of the cluster pair (a 256-entry map Q in Eq. qmap-distance, cluster-major codes of
 Eq. decluster) through the C ABI against the CPU oracle.
 
-Protocol as for the plain pair: the GPU's (mu, sigma) are compared with the oracle's at 1e-6 elsewhere; here the oracle
-is run with the GPU's fit, and labels, (S, b), codes (in either arrangement) and the dequantised values must then be
+Protocol as for the plain pair: the GPU's (mu, sigma) are compared with the oracle's own at 1e-6; then the oracle is
+run with the GPU's fit, and labels, (S, b), codes (in either arrangement) and the dequantised values must be
 bit-exact.
 """
 import numpy as np
@@ -30,6 +30,12 @@ def _check(x, G, m, kind, major):
     torch.cuda.synchronize()
     assert int(q.status.item()) == 0
     fit = to_np(q.fit)
+    # the GPU's own fit against the oracle's own fit, group by group (sigma relative to sigma, mu to max(|mu|, sigma))
+    own = oracle.quantize_cluster_ex(x, G, m, qmap=Q, cluster_major=major)["fit"]
+    mu_g, sg_g = fit[:, 0].astype(np.float64), fit[:, 1].astype(np.float64)
+    mu_o, sg_o = own[:, 0].astype(np.float64), own[:, 1].astype(np.float64)
+    assert np.all(np.abs(sg_g - sg_o) <= 1e-6 * sg_o)
+    assert np.all(np.abs(mu_g - mu_o) <= 1e-6 * np.maximum(np.abs(mu_o), sg_o))
     o = oracle.quantize_cluster_ex(x, G, m, fit_in=fit[:, :2].copy(), qmap=Q, cluster_major=major)
     assert np.array_equal(to_np(q.labels), o["labels"])
     assert np.array_equal(to_np(q.params), o["params"])

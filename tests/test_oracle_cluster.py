@@ -157,7 +157,8 @@ def test_error_bound_endpoints_and_monotone_codes():
         grp = np.arange(n) // 4096
         S = q["params"][grp, lab, 0].astype(np.float64)
         b = q["params"][grp, lab, 1].astype(np.float64)
-        ulp = np.spacing(np.abs(x)).astype(np.float64)
+        # fp32 rounding of q*step + b happens at the magnitude of the cluster's ends, not of x (b + q*step can cancel)
+        ulp = np.spacing(np.maximum(np.abs(b), np.abs(b + S)).astype(np.float32)).astype(np.float64)
         # half the spacing of the 256 levels inside the element's own cluster
         assert np.all(np.abs(x.astype(np.float64) - xh) <= S / 510 * (1 + 1e-5) + 2 * ulp)
         # code 0 is the cluster minimum (exactly), code 255 the maximum (to an ulp)

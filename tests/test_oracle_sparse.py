@@ -157,7 +157,7 @@ def test_decode_uses_payload_in_order():
 @pytest.mark.parametrize("n", [0, 1, 9, 4097, 20001])
 @pytest.mark.parametrize("p", [0.0, 0.06, 1.0])
 def test_delta_payload_is_the_nonzero_part_of_the_bitwise_difference(n, p):
-    """Delta reading of the section ("save the bitmask list and the non-zero elements" of the delta states):
+    """Delta reading of the section (beside the mask it stores the non-zero elements of the delta states):
     the flattened delta is cur XOR base, the payload its non-zero elements in order (numpy's boolean selection);
     mask and count are those of the value form; decoding is lossless."""
     cur, base, nsel = _pair(n, p, 5000 + n)
