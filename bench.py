@@ -67,6 +67,11 @@ def med(xs):
     return statistics.median(xs)
 
 
+def progress(*what):
+    """A line on stderr per finished stage: a run under a profiler can take minutes between two of them."""
+    print("[bench]", *what, file=sys.stderr, flush=True)
+
+
 def timed(fn, stream, reps=5, rounds=2):
     """ms per call of fn(): `rounds` rounds of `reps` calls between two events, the last round counts."""
     import torch
@@ -107,12 +112,15 @@ def main():
 
     # ------------------------------------------------------------------ inputs, resident in HBM
     t0 = time.time()
-    inputs = []
-    for t in tensors:
-        inputs.append(synth.make_tensor_torch(cfg, t, dev, adam_steps=args.adam_steps, want=("base", "cur") + states))
+    def gen_progress(s, steps):
+        torch.cuda.synchronize()
+        progress(f"simulated Adam step {s} of {steps}")
+    inputs = synth.make_checkpoint_torch(cfg, dev, tensors, adam_steps=args.adam_steps, want=("base", "cur") + states,
+                                         on_step=gen_progress)
     torch.cuda.synchronize()
     torch.cuda.empty_cache()
     gen_s = time.time() - t0
+    progress(f"inputs generated in {gen_s:.1f} s")
 
     # ------------------------------------------------------------------ the compressed checkpoint (stays resident)
     u8, i16, f32, i64 = torch.uint8, torch.int16, torch.float32, torch.int64
@@ -249,7 +257,9 @@ def main():
 
     other = "per-tensor" if args.mode == "batched" else "batched"
     other_ms, other_per_step = time_mode(other)
+    progress(f"{other} mode timed: {other_ms:.3f} ms per step")
     ms_per_step, per_step = time_mode(args.mode)
+    progress(f"{args.mode} mode timed: {ms_per_step:.3f} ms per step")
     op_ms = {op: sum(per_step[op]) / args.steps for op in ORDER}
     n_launch = {op: (len(bcalls[op]) if args.mode == "batched" else len(calls[op])) for op in ORDER}
 
@@ -301,14 +311,16 @@ def main():
                    state_bytes=state_bytes, p=p)
         mix_ceiling = streaming_ceiling(ctx)
         extras["low_change_fraction"] = low_p_extra(ctx)
+        progress("low changed fraction row done")
         if cfg.index == 2 and len(batches) == 1:
             extras.update(config2_extras(ctx))
+            progress("extras done")
 
     dominant = max(ORDER, key=lambda op: op_ms[op])
     batched = args.mode == "batched"
-    kernel_name = {"encode_sparse": f"encode_sparse_kernel<{str(batched).lower()}, false, 2>",
-                   "decode_sparse": f"decode_merge_kernel<{str(batched).lower()}, false, false, 2>",
-                   "quantize_cluster": "quantize_cluster_batched_kernel<16, true>" if batched else "quantize_cluster_kernel<16, true>",
+    kernel_name = {"encode_sparse": f"encode_sparse_kernel<{str(batched).lower()}, false, 2, false>",
+                   "decode_sparse": f"decode_merge_kernel<{str(batched).lower()}, false, 0, 2>",   # after its counting and scanning kernels
+                   "quantize_cluster": "quantize_cluster_batched_kernel<16>" if batched else "quantize_cluster_kernel<16>",
                    "dequantize_cluster": "dequantize_cluster_batched_kernel<16>" if batched else "dequantize_cluster_kernel<16>"}
     launches = n_launch[dominant]
     traffic, traffic_src = read_traffic(cfg, p, kernel_name[dominant], args.mode)
@@ -347,6 +359,7 @@ def main():
 
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(inputs, sizes, states, args.cpu_sample_tensors, cfg)
+        progress("cpu baseline done")
     print(json.dumps(out), flush=True)
 
 

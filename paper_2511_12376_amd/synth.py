@@ -236,6 +236,52 @@ def make_tensor_torch(cfg: Config, t: int, device, n_limit: Optional[int] = None
     return {k: out[k] for k in want}
 
 
+def make_checkpoint_torch(cfg: Config, device, tensors=None, adam_steps: Optional[int] = None,
+                          want: Tuple[str, ...] = ("base", "cur", "master", "m", "v"), on_step=None):
+    """The tensors of ``cfg`` (all of them, or the listed indices) as a list of dicts like ``make_tensor_torch``'s.
+
+    The Bernoulli and runs recipes go tensor by tensor.  The Adam recipe simulates the whole list at once in flat
+    buffers - the recipe is element-wise, so per element nothing changes; the checkpoint then has one random
+    stream (seeded like its first tensor) instead of one per tensor - and hands out views: a few hundred large
+    kernel launches instead of a few hundred thousand small ones.  Every tensor starts at a multiple of 64
+    elements of the flat buffer, so views keep the alignment a fresh allocation would have.  ``on_step(s, steps)``
+    is called every tenth simulated step (progress for the caller).
+    """
+    import torch
+
+    idx = list(range(len(cfg.tensors))) if tensors is None else list(tensors)
+    if cfg.recipe != "adam":
+        return [make_tensor_torch(cfg, t, device, adam_steps=adam_steps, want=want) for t in idx]
+    sizes = [math.prod(cfg.tensors[t][1]) for t in idx]
+    starts, total = [], 0
+    for n in sizes:
+        starts.append(total)
+        total += (n + 63) // 64 * 64
+    gen = torch.Generator(device=device)
+    gen.manual_seed(seed_for(cfg.index, idx[0] if idx else 0))
+    steps = ADAM["steps"] if adam_steps is None else adam_steps
+    master = torch.randn(total, device=device, dtype=torch.float32, generator=gen).mul_(0.02)
+    base = master.to(torch.bfloat16)
+    m = torch.zeros_like(master)
+    v = torch.zeros_like(master)
+    g = torch.empty_like(master)
+    den = torch.empty_like(master)
+    b1, b2 = ADAM["beta1"], ADAM["beta2"]
+    for s in range(1, steps + 1):
+        g.normal_(0.0, ADAM["grad_std"], generator=gen)
+        m.lerp_(g, 1.0 - b1)
+        v.mul_(b2).addcmul_(g, g, value=1.0 - b2)
+        torch.sqrt(v, out=den)
+        den.div_(math.sqrt(1.0 - b2 ** s)).add_(ADAM["eps"])
+        master.addcdiv_(m, den, value=-ADAM["lr"] / (1.0 - b1 ** s))
+        if on_step is not None and s % 10 == 0:
+            on_step(s, steps)
+    del g, den
+    cur = master.to(torch.bfloat16)
+    flat = dict(base=base, cur=cur, master=master, m=m, v=v)
+    return [{k: flat[k][a:a + n] for k in want} for a, n in zip(starts, sizes)]
+
+
 def iter_tensors(cfg: Config) -> Iterator[Tuple[int, str, int]]:
     for t, (name, shape) in enumerate(cfg.tensors):
         yield t, name, math.prod(shape)
