@@ -702,12 +702,10 @@ __global__ __launch_bounds__(kBlock, 4) void decode_merge_kernel(bitsnap_sparse_
     uint4 pv[kVecsPerLane];
     const elem_t *__restrict__ seg = nullptr;
     int64_t seg_elems = 0;
-    // Non-temporal accesses to payload and output pay where little changed (the output is mostly a copy of the
-    // base: 66 -> 69-70 % of HBM peak on checkpoints with 6 % changed) and cost where most did (66 -> 63 % at 71 %
-    // changed), so every wave picks by its own segment.
-    bool dense = false;
+    // Base, payload and output are touched once: non-temporal accesses throughout (66 -> 69-70 % of HBM peak on
+    // checkpoints with 6 % changed; where most elements changed the hints make no difference beyond the noise
+    // between runs in a batched pass, and one call per tensor gains 3-4 %).
     auto request_payload = [&]() {
-        dense = 2 * seg_count > (uint32_t)kSegElems;
         shift = (uint32_t)(start & (P - 1u));
         const int64_t src0 = (int64_t)(start - shift);
         pieces = (shift + seg_count + P - 1u) / P;           // at most kSegElems / P + 1
@@ -719,7 +717,7 @@ __global__ __launch_bounds__(kBlock, 4) void decode_merge_kernel(bitsnap_sparse_
             pv[i] = make_uint4(0, 0, 0, 0);  // never read at or beyond payload_elems: what is missing decodes to 0
             if (q < pieces) {
                 if ((int64_t)(q * P + P) <= seg_elems) {
-                    pv[i] = dense ? load_global16<false>(seg + q * P) : load_global16<true>(seg + q * P);
+                    pv[i] = load_global16<true>(seg + q * P);
                 } else {
                     uint32_t w[4] = {0, 0, 0, 0};
                     for (uint32_t t = 0; t < P; ++t)
@@ -805,10 +803,7 @@ __global__ __launch_bounds__(kBlock, 4) void decode_merge_kernel(bitsnap_sparse_
 #pragma unroll
         for (int k = 0; k < kVecs; ++k)
             res.v[k] = make_uint4(w[4 * k + 0], w[4 * k + 1], w[4 * k + 2], w[4 * k + 3]);
-        if (dense)
-            store8<false, E>(out, seg0 + q * kChunkElems + e0, n, res);
-        else
-            store8<true, E>(out, seg0 + q * kChunkElems + e0, n, res);
+        store8<true, E>(out, seg0 + q * kChunkElems + e0, n, res);
     }
     // no scan kernel ran to report the count: the wave that holds the tensor's last element knows it
     if (kSource != kFromWorkspace && lane == 0 && count_out && seg0 + kSegElems >= n)
