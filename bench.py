@@ -47,8 +47,8 @@ DEFAULT_BATCH_ELEMS = {3: 1 << 30, 4: 1 << 30}
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=5)
-    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=2)
     ap.add_argument("--p", type=float, default=None, help="change fraction for the Bernoulli / runs configs")
     ap.add_argument("--limit-tensors", type=int, default=0, help="only the first N tensors (debugging)")
@@ -680,7 +680,7 @@ def read_traffic(cfg, p, kernel, mode):
 
 def cpu_baseline(inputs, sizes, states, k, cfg):
     """The CPU oracle, as it stands, on a bounded sample of the same workload: the same four operations on 2-D
-    tensors after the embeddings.  Two legs: one thread on `k` tensors, then one tensor per thread on as many
+    tensors after the embeddings.  Two legs: one thread on `k` tensors, then three tensors per thread on as many
     threads as this box gives one GPU's job (the oracle is plain C behind ctypes, which releases the
     interpreter lock for the duration of a call; nothing in the oracle changes)."""
     import numpy as np
@@ -694,7 +694,7 @@ def cpu_baseline(inputs, sizes, states, k, cfg):
     pick = [i for i, n in enumerate(sizes) if 2_000_000 <= n <= 30_000_000]
     if not pick:
         pick = list(range(len(sizes)))
-    pick_one, pick_all = pick[:k], pick[:threads]
+    pick_one, pick_all = pick[:k], pick[:3 * threads]
 
     def to_host(i):
         d = inputs[i]
@@ -735,7 +735,7 @@ def cpu_baseline(inputs, sizes, states, k, cfg):
     used = min(threads, len(pick_all))
     return {"value": round(state_all / sec_all / 1e9, 4), "unit": "GB/s", "cores": used, "cores_total": cores_total,
             "kind": "oracle",
-            "sample": f"{len(pick_all)} tensors of configs[{cfg.index}] ({sum(sizes[i] for i in pick_all)} params, one per thread, "
+            "sample": f"{len(pick_all)} tensors of configs[{cfg.index}] ({sum(sizes[i] for i in pick_all)} params, one at a time per thread, "
                       f"{used} threads), all four operations, {round(sec_all, 1)} s",
             "one_core": {"value": round(state_one / sec_one / 1e9, 4), "unit": "GB/s", "cores": 1,
                          "state_GBps_per_op": per_op_one,

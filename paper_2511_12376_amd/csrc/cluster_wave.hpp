@@ -115,33 +115,50 @@ __device__ __forceinline__ void load_elements(const float *__restrict__ x, int64
 
 // ---- step 1: sum of the elements and, about their mean, the sum of squared deviations; fp64
 // per-lane partial sums, then a DPP tree across the wave (fixed association: reproducible).
+// The deviations come from one pass where that is safe: the square of an fp32 number is exact in fp64, so
+// Q = sum of x^2 carries only the rounding of its 4096 additions (below 1e-14 relative), and
+// Q - S^2/n loses log2(Q / result) of the 53 bits to cancellation.  Where the result keeps more than 1/64 of
+// Q (|mean| below 8 deviations) its relative error stays under 1e-12, far below what changes the fp32
+// rounding of the deviation in more than one group in a million; every other group (and every group whose
+// elements are all equal, where the result must be an exact zero) takes the second pass over x - mean.
 template <int K, bool kFull>
 __device__ __forceinline__ void wave_stats(float4 (&v)[K], int len, int lane, double &sum, double &dev)
 {
-    double s = 0.0;
+    double s0 = 0.0, s1 = 0.0, q0 = 0.0, q1 = 0.0;
 #pragma unroll
-    for (int k = 0; k < K; ++k)
-        s += ((double)v[k].x + (double)v[k].y) + ((double)v[k].z + (double)v[k].w);  // padding adds 0
-    s = wave_sum(s);
+    for (int k = 0; k < K; ++k) {  // padding adds 0 to both
+        const double x = (double)v[k].x, y = (double)v[k].y, z = (double)v[k].z, w = (double)v[k].w;
+        s0 += x + y;
+        s1 += z + w;
+        q0 = fma(x, x, q0);
+        q1 = fma(y, y, q1);
+        q0 = fma(z, z, q0);
+        q1 = fma(w, w, q1);
+    }
+    const double s = wave_sum(s0 + s1), q = wave_sum(q0 + q1);
     const double mean = s / (double)len;
-    // Keep the elements as fp32 in registers: without this the compiler holds on to the fp64 copies
-    // made for the sum above, which doubles the register footprint and halves the occupancy.
+    double d = fma(-s, mean, q);
+    if (!(d > q * 0x1p-6)) {  // wave-uniform
+        // Keep the elements as fp32 in registers: without this the compiler holds on to the fp64 copies
+        // made above, which doubles the register footprint and halves the occupancy.
 #pragma unroll
-    for (int k = 0; k < K; ++k)
-        asm volatile("" : "+v"(v[k].x), "+v"(v[k].y), "+v"(v[k].z), "+v"(v[k].w));
-    double q = 0.0;
+        for (int k = 0; k < K; ++k)
+            asm volatile("" : "+v"(v[k].x), "+v"(v[k].y), "+v"(v[k].z), "+v"(v[k].w));
+        double t = 0.0;
 #pragma unroll
-    for (int k = 0; k < K; ++k) {
+        for (int k = 0; k < K; ++k) {
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            if (kFull || k * 256 + lane * 4 + j < len) {
-                const double d = (double)comp(v[k], j) - mean;
-                q = fma(d, d, q);
+            for (int j = 0; j < 4; ++j) {
+                if (kFull || k * 256 + lane * 4 + j < len) {
+                    const double e = (double)comp(v[k], j) - mean;
+                    t = fma(e, e, t);
+                }
             }
         }
+        d = wave_sum(t);
     }
     sum = s;
-    dev = wave_sum(q);
+    dev = d;
 }
 
 // Running min/max table: this lane's column back to "no members" (call before label_pass with

@@ -179,6 +179,29 @@ def test_mean_far_from_zero_both_label_searches(m):
     assert groups == len(parts)
 
 
+def test_deviation_on_both_sides_of_the_one_pass_limit():
+    """The kernel takes the squared deviations from the sums of x and x*x where the mean is within a few
+    deviations of zero, and from a second pass over x - mean elsewhere.  Groups on both sides of that
+    limit (|mean| from 0 to 1e5 deviations, and means of the size fp32 can barely resolve), group lengths
+    with one wave per group and with many, ragged ends: (mu, sigma) must be the oracle's bits in at least
+    999 of 1000 groups, and within 1e-6 everywhere (checked by _compare)."""
+    rng = np.random.default_rng(99)
+    parts = []
+    for ratio in (0.0, 0.5, 2.0, 4.0, 6.0, 7.0, 7.5, 7.8, 7.9, 7.95, 8.0, 8.05, 8.1, 8.5, 9.0, 12.0, 30.0, 1e3, 1e5):
+        for sigma in (1.3e-8, 1e-3, 17.0):
+            for _ in range(4):
+                parts.append((ratio * sigma + rng.standard_normal(4096) * sigma).astype(np.float32))
+    x = np.concatenate(parts + [np.float32(3.0) + rng.standard_normal(1234).astype(np.float32) * np.float32(0.4)])
+    differing = total = 0
+    for G in (4096, 1024, 0, 20_000):
+        announce("cluster deviation both ways", G)
+        a, b = _compare(x, G, 16)
+        differing += a
+        total += b
+    print(f"groups whose fp32 (mu, sigma) differ between GPU and oracle: {differing} of {total}")
+    assert differing <= total // 1000
+
+
 def test_non_finite_input_sets_status_and_stays_in_bounds():
     announce("cluster non-finite")
     x = np.random.default_rng(1).standard_normal(3 * 4096).astype(np.float32)
