@@ -192,7 +192,8 @@ int bitsnap_encode_sparse_static(const void *cur, const void *base, int64_t n, i
  * for a predecessor's scan state before it reports failure through n_changed.  0 restores the
  * default (large enough never to trigger in normal operation).  The value is PROCESS-GLOBAL (one
  * atomic word, read by every later encode call on any thread, stream or device when it launches):
- * a test aid, not to be called by code that encodes concurrently on other threads. */
+ * a test aid, not to be called by code that encodes concurrently on other threads.  The call does
+ * nothing unless the environment variable BITSNAP_DEBUG_KNOBS is "1" when it is made. */
 void bitsnap_debug_set_spin_limit(uint32_t polls);
 
 /* ------------------------------------------------------------------------------------------

@@ -17,6 +17,7 @@
 // that the payload leaves (encode) or enters (decode) HBM as 16-byte accesses aligned on the
 // payload buffer, whatever the tile's (decode: the wave's) offset.
 #include <hip/hip_runtime.h>
+#include <stdlib.h>
 #include <stdint.h>
 
 #include <atomic>
@@ -883,6 +884,10 @@ extern "C" size_t bitsnap_sparse_workspace_bytes_for(int64_t n, int elem_bytes)
 
 extern "C" void bitsnap_debug_set_spin_limit(uint32_t polls)
 {
+    // opt-in: a stray call in a production process must not be able to make encodes give up
+    const char *knobs = getenv("BITSNAP_DEBUG_KNOBS");
+    if (!knobs || knobs[0] != '1' || knobs[1] != '\0')
+        return;
     g_spin_limit.store(polls ? polls : kDefaultSpinLimit, std::memory_order_relaxed);
 }
 

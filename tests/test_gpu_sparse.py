@@ -146,10 +146,27 @@ def test_workspace_reuse_and_epoch_wrap():
     assert 0 < h[2] < 16                                           # the tag wrapped and started again
 
 
-def test_give_up_path_reports_and_recovers():
+def test_spin_limit_knob_needs_its_opt_in(monkeypatch):
+    """Without BITSNAP_DEBUG_KNOBS=1 in the environment the test knob does nothing: an encode of 2000 tiles
+    after set_spin_limit(1) is as good as any other."""
+    announce("sparse spin-limit knob without opt-in")
+    monkeypatch.delenv("BITSNAP_DEBUG_KNOBS", raising=False)
+    n = 2000 * T
+    cur, base = _pair(n, 0.2, 78)
+    try:
+        B.debug_set_spin_limit(1)
+        enc = B.encode_sparse(u16_to_dev(cur), u16_to_dev(base))
+        torch.cuda.synchronize()
+    finally:
+        B.debug_set_spin_limit(0)
+    assert int(enc.n_changed.item()) == oracle.encode_sparse(cur, base)[2]
+
+
+def test_give_up_path_reports_and_recovers(monkeypatch):
     """With a spin limit of one poll, workgroups that have to wait give up.  The call must still
     finish, report the failure through n_changed, and leave the workspace usable."""
     announce("sparse give-up path")
+    monkeypatch.setenv("BITSNAP_DEBUG_KNOBS", "1")
     n = 2000 * T
     cur, base = _pair(n, 0.2, 77)
     ws = B.new_sparse_workspace(n, DEV)
