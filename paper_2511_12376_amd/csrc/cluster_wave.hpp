@@ -297,7 +297,8 @@ __device__ __forceinline__ void label_pass_impl(const float4 (&v)[K], int64_t lo
             packed[k >> 1] |= l4 << (16 * (k & 1));
             if (kStore) {
                 const int off = k * 256 + lane * 4;
-                BITSNAP_GLOBAL uint8_t *lp = global_ptr(labels) + ((lo + off) >> 1);
+                // lo and off are even; written as a sum, the constant part of off becomes the store's offset field
+                BITSNAP_GLOBAL uint8_t *lp = global_ptr(labels) + (lo >> 1) + (lane * 2) + k * 128;
                 if (kFull || (off + 3 < len && (lo & 3) == 0)) {  // four whole elements at an aligned place
                     __builtin_nontemporal_store((uint16_t)l4, (BITSNAP_GLOBAL uint16_t *)lp);
                 } else {
@@ -377,8 +378,10 @@ __device__ __forceinline__ void code_pass(const float4 (&v)[K], int64_t lo, int 
 #pragma unroll
         for (int i = 0; i < kB; ++i) {
             const int k = kb + i / 4;
-            const uint32_t l4 = (packed[k >> 1] >> (16 * (k & 1))) & 0xFFFFu;
-            bi[i] = lds_read_f32x2(coder0 + (((l4 >> (4 * (i % 4))) & 15u) << 3));
+            // bit-field extract + shift-add: two instructions per address
+            uint32_t label;
+            asm("v_bfe_u32 %0, %1, %2, 4" : "=v"(label) : "v"(packed[k >> 1]), "n"(16 * (k & 1) + 4 * (i % 4)));
+            bi[i] = lds_read_f32x2((label << 3) + coder0);
         }
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -420,7 +423,7 @@ __device__ __forceinline__ void dequantize_group(const uint8_t *__restrict__ cod
         c4[k] = 0, l4[k] = 0;
         if (aligned && off + 3 < len) {
             c4[k] = __builtin_nontemporal_load((const BITSNAP_GLOBAL uint32_t *)(global_ptr(codes) + lo + off));
-            l4[k] = __builtin_nontemporal_load((const BITSNAP_GLOBAL uint16_t *)(global_ptr(labels) + ((lo + off) >> 1)));
+            l4[k] = __builtin_nontemporal_load((const BITSNAP_GLOBAL uint16_t *)(global_ptr(labels) + (lo >> 1) + lane * 2 + k * 128));
         } else {
             for (int j = 0; j < 4; ++j)
                 if (off + j < len) {
