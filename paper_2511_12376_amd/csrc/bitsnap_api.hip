@@ -19,11 +19,12 @@ __global__ __launch_bounds__(256) void stream_copy_kernel(const uint4 *__restric
 //   else:     reads 1 + 1/2 bytes per element, writes 4      (dequantize_cluster's traffic)
 typedef float mix_float4 __attribute__((ext_vector_type(4)));
 #define BITSNAP_MIX_GLOBAL __attribute__((address_space(1)))
-template <bool kToSmall>
-__global__ __launch_bounds__(256) void stream_mix_kernel(float *wide, uint8_t *bytes, uint8_t *halves, int64_t groups)
+// kThreads: the workgroup size of the codec whose traffic is imitated (it changes what the memory system delivers)
+template <bool kToSmall, int kThreads>
+__global__ __launch_bounds__(kThreads) void stream_mix_kernel(float *wide, uint8_t *bytes, uint8_t *halves, int64_t groups)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int64_t g = (int64_t)blockIdx.x * 4 + wave;
+    const int64_t g = (int64_t)blockIdx.x * (kThreads / 64) + wave;
     if (g >= groups)
         return;
     const int64_t lo = g * 4096;
@@ -61,7 +62,7 @@ __global__ __launch_bounds__(256) void stream_mix_kernel(float *wide, uint8_t *b
 extern "C" int bitsnap_debug_stream_mix(void *wide, void *bytes, void *halves, int64_t n, int to_small,
                                         bitsnap_stream_t stream)
 {
-    if (n < 0 || (n % 4096) != 0 || n / 4096 / 4 + 1 > 0x7FFFFFFF)
+    if (n < 0 || (n % 4096) != 0 || n / 4096 > 0x7FFFFFFF)
         return BITSNAP_E_SIZE;
     if (n == 0)
         return BITSNAP_OK;
@@ -70,13 +71,14 @@ extern "C" int bitsnap_debug_stream_mix(void *wide, void *bytes, void *halves, i
     if (!bitsnap::aligned16(wide) || !bitsnap::aligned16(bytes) || !bitsnap::aligned16(halves))
         return BITSNAP_E_ALIGN;
     const int64_t groups = n / 4096;
-    const dim3 grid((unsigned)((groups + 3) / 4)), block(256);
+    constexpr int kSmallThreads = 64, kWideThreads = 1024;  // as the batched quantiser and dequantiser
     if (to_small)
-        hipLaunchKernelGGL(bitsnap::stream_mix_kernel<true>, grid, block, 0, (hipStream_t)stream, (float *)wide,
-                           (uint8_t *)bytes, (uint8_t *)halves, groups);
+        hipLaunchKernelGGL((bitsnap::stream_mix_kernel<true, kSmallThreads>), dim3((unsigned)groups), dim3(kSmallThreads), 0,
+                           (hipStream_t)stream, (float *)wide, (uint8_t *)bytes, (uint8_t *)halves, groups);
     else
-        hipLaunchKernelGGL(bitsnap::stream_mix_kernel<false>, grid, block, 0, (hipStream_t)stream, (float *)wide,
-                           (uint8_t *)bytes, (uint8_t *)halves, groups);
+        hipLaunchKernelGGL((bitsnap::stream_mix_kernel<false, kWideThreads>), dim3((unsigned)((groups + 15) / 16)),
+                           dim3(kWideThreads), 0, (hipStream_t)stream, (float *)wide, (uint8_t *)bytes, (uint8_t *)halves,
+                           groups);
     return bitsnap::launch_status();
 }
 

@@ -27,8 +27,20 @@ static const double kZHost[17][16] = {
 #include "z_table.inc"
 };
 
-constexpr int kQBlock = 256;
+// Waves do not cooperate in these kernels, so the workgroup is only the unit in which wave slots and LDS are handed
+// out and given back.  Measured on the batched pass of a 6.7 G-element state: the quantiser (reads 4 bytes per
+// element, writes 1.5) runs at 73-74 % of HBM peak in 256-thread workgroups, 75-76 % in 128-thread ones and 77 % as
+// single waves, whose slots are refilled one by one; the dequantiser (reads 1.5, writes 4) is the other way
+// round: 67-68 % in 64- or 128-thread workgroups, 70-72 % in 256-thread ones, 73-75 % in 512- or 1024-thread
+// ones - its stores profit from neighbouring groups being written at about the same time.  A single tensor of
+// a few thousand groups is one round of waves whatever the workgroup, and there the larger ones lose 4 %
+// (they start and end later), so only the batched dequantiser uses them.
+constexpr int kQBlock = 64;     // quantize_cluster kernels
 constexpr int kQWaves = kQBlock / kWave;
+constexpr int kDBlock = 256;    // dequantize_cluster kernel, one tensor
+constexpr int kDWaves = kDBlock / kWave;
+constexpr int kDListBlock = 1024;  // dequantize_cluster kernel, list of tensors
+constexpr int kDListWaves = kDListBlock / kWave;
 
 // Algorithm 2 for one group of len <= 256*K elements, by one wave.
 template <int K, bool kFull>
@@ -108,13 +120,13 @@ __global__ __launch_bounds__(kQBlock) void quantize_cluster_kernel(
 }
 
 template <int K>
-__global__ __launch_bounds__(kQBlock) void dequantize_cluster_kernel(
+__global__ __launch_bounds__(kDBlock) void dequantize_cluster_kernel(
     const uint8_t *__restrict__ codes, const uint8_t *__restrict__ labels, const float *__restrict__ params,
     int64_t n, int64_t groups, int m, float *__restrict__ out)
 {
-    __shared__ float2 coder[kQWaves][kMaxClusters];
+    __shared__ float2 coder[kDWaves][kMaxClusters];
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
-    const int64_t g = (int64_t)blockIdx.x * kQWaves + wave;
+    const int64_t g = (int64_t)blockIdx.x * kDWaves + wave;
     if (g >= groups)
         return;
     constexpr int G = 256 * K;
@@ -163,13 +175,13 @@ __global__ __launch_bounds__(kQBlock) void quantize_cluster_batched_kernel(
 }
 
 template <int K>
-__global__ __launch_bounds__(kQBlock) void dequantize_cluster_batched_kernel(
+__global__ __launch_bounds__(kDListBlock) void dequantize_cluster_batched_kernel(
     const bitsnap_cluster_item *__restrict__ items, int64_t count, int64_t total_groups, int m)
 {
-    __shared__ float2 coder[kQWaves][kMaxClusters];
+    __shared__ float2 coder[kDListWaves][kMaxClusters];
     const int lane = threadIdx.x & (kWave - 1), wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     constexpr int G = 256 * K;
-    const int64_t gg = (int64_t)blockIdx.x * kQWaves + wave;
+    const int64_t gg = (int64_t)blockIdx.x * kDListWaves + wave;
     if (gg >= total_groups)
         return;
     const bitsnap_cluster_item &it = items[find_item(items, count, gg)];
@@ -286,10 +298,10 @@ extern "C" int bitsnap_dequantize_cluster(const uint8_t *codes, const uint8_t *l
     if (K == 0)
         return cluster_general_dequantize(codes, labels, params, n, group, m, out, (hipStream_t)stream);
     const int64_t groups = (int64_t)bitsnap_cluster_groups(n, group);
-    const int64_t blocks = (groups + kQWaves - 1) / kQWaves;
+    const int64_t blocks = (groups + kDWaves - 1) / kDWaves;
     if (blocks > 0x7FFFFFFF)
         return BITSNAP_E_SIZE;
-    const dim3 grid((unsigned)blocks), block(kQBlock);
+    const dim3 grid((unsigned)blocks), block(kDBlock);
     hipStream_t s = (hipStream_t)stream;
 #define BITSNAP_LAUNCH_D(KK) \
     hipLaunchKernelGGL(dequantize_cluster_kernel<KK>, grid, block, 0, s, codes, labels, params, n, groups, m, out)
@@ -304,7 +316,7 @@ extern "C" int bitsnap_dequantize_cluster(const uint8_t *codes, const uint8_t *l
     return launch_status();
 }
 
-static int64_t batched_blocks(int64_t total_groups) { return (total_groups + kQWaves - 1) / kQWaves; }
+static int64_t batched_blocks(int64_t total_groups, int waves) { return (total_groups + waves - 1) / waves; }
 
 extern "C" int bitsnap_quantize_cluster_batched(const bitsnap_cluster_item *items, int64_t count, int64_t total_groups,
                                                 int64_t group, int m, uint32_t *status, bitsnap_stream_t stream)
@@ -320,9 +332,9 @@ extern "C" int bitsnap_quantize_cluster_batched(const bitsnap_cluster_item *item
         return BITSNAP_E_NULL;
     if (((uintptr_t)items & 7u) || ((uintptr_t)status & 3u))
         return BITSNAP_E_ALIGN;
-    if (batched_blocks(total_groups) > 0x7FFFFFFF)
+    if (batched_blocks(total_groups, kQWaves) > 0x7FFFFFFF)
         return BITSNAP_E_SIZE;
-    const dim3 block(kQBlock), grid((unsigned)batched_blocks(total_groups));
+    const dim3 block(kQBlock), grid((unsigned)batched_blocks(total_groups, kQWaves));
     hipStream_t s = (hipStream_t)stream;
 #define BITSNAP_LAUNCH_QB(KK) \
     hipLaunchKernelGGL((quantize_cluster_batched_kernel<KK>), grid, block, 0, s, items, count, total_groups, m, status)
@@ -351,9 +363,9 @@ extern "C" int bitsnap_dequantize_cluster_batched(const bitsnap_cluster_item *it
         return BITSNAP_E_NULL;
     if ((uintptr_t)items & 7u)
         return BITSNAP_E_ALIGN;
-    if (batched_blocks(total_groups) > 0x7FFFFFFF)
+    if (batched_blocks(total_groups, kDListWaves) > 0x7FFFFFFF)
         return BITSNAP_E_SIZE;
-    const dim3 block(kQBlock), grid((unsigned)batched_blocks(total_groups));
+    const dim3 block(kDListBlock), grid((unsigned)batched_blocks(total_groups, kDListWaves));
     hipStream_t s = (hipStream_t)stream;
 #define BITSNAP_LAUNCH_DB(KK) \
     hipLaunchKernelGGL(dequantize_cluster_batched_kernel<KK>, grid, block, 0, s, items, count, total_groups, m)

@@ -514,15 +514,16 @@ __device__ __forceinline__ int64_t find_sparse_item(const bitsnap_sparse_item *_
 
 // One wave per tile: popcount of the tile's 4 or 2 KB of mask (bits at or beyond n do not count), and the
 // places of the tile's eight segments inside the tile.
+constexpr int kCountWaves = 2;  // tiles per workgroup of the counting kernel (small workgroups: see kMergeWaves)
 template <bool kBatched, int E>
-__global__ __launch_bounds__(kBlock) void decode_count_kernel(bitsnap_sparse_item single,
+__global__ __launch_bounds__(kCountWaves * kWave) void decode_count_kernel(bitsnap_sparse_item single,
                                                               const bitsnap_sparse_item *__restrict__ items,
                                                               int64_t count, int64_t num_tiles,
                                                               uint32_t *__restrict__ tile_count,
                                                               uint32_t *__restrict__ seg_prefix)
 {
     const int lane = threadIdx.x & (kWave - 1), wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int64_t gt = (int64_t)blockIdx.x * kWaves + wave;
+    const int64_t gt = (int64_t)blockIdx.x * kCountWaves + wave;
     if (gt >= num_tiles)
         return;
     const bitsnap_sparse_item &it = kBatched ? items[find_sparse_item(items, count, gt)] : single;
@@ -623,6 +624,13 @@ __global__ __launch_bounds__(kBlock) void decode_scan_kernel(bitsnap_sparse_item
 // mask before its segment itself (kFromMask; tensors of a few tiles, decoded by this one launch).
 enum { kFromWorkspace = 0, kFromEncoder = 1, kFromMask = 2 };
 constexpr int kSoloTiles = 8;  // single tensors of up to this many tiles take kFromMask
+// Waves of a tile do not cooperate, so the workgroup is only the unit in which the hardware hands out wave
+// slots and LDS: a new workgroup starts when a whole one has left.  With the byte mix of this kernel and no
+// logic, 16 waves per CU stream at 67-70 % of HBM peak as 512-thread workgroups, 72-74 % as 256-thread ones,
+// 77-78 % as 128-thread ones and 74-75 % as single waves.
+constexpr int kMergeWaves = 2;                          // waves (segments) per workgroup
+constexpr int kMergeBlock = kMergeWaves * kWave;
+constexpr int kMergeBlocksPerTile = kWaves / kMergeWaves;
 
 template <int E>
 struct DecGeom {
@@ -634,7 +642,7 @@ struct DecGeom {
 };
 
 template <bool kBatched, bool kDelta, int kSource, int E>
-__global__ __launch_bounds__(kBlock, 4) void decode_merge_kernel(bitsnap_sparse_item single,
+__global__ __launch_bounds__(kMergeBlock) void decode_merge_kernel(bitsnap_sparse_item single,
                                                                  const bitsnap_sparse_item *__restrict__ items,
                                                                  int64_t count, const uint64_t *__restrict__ tile_offset,
                                                                  const uint32_t *__restrict__ tile_count,
@@ -645,9 +653,10 @@ __global__ __launch_bounds__(kBlock, 4) void decode_merge_kernel(bitsnap_sparse_
     constexpr int kTileElems = Geom<E>::kTileElems, kSegElems = DecGeom<E>::kSegElems, kPieces = DecGeom<E>::kPieces,
                   kVecs = Geom<E>::kVecs, kVecElems = Geom<E>::kVecElems, kVecsPerLane = DecGeom<E>::kVecsPerLane;
     constexpr uint32_t P = Geom<E>::kVecElems;
-    __shared__ alignas(16) elem_t regions[kWaves][kSegElems + 4 * P];  // + a shifted segment's end + what the merge reads past it
-    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int64_t gtile = blockIdx.x;
+    __shared__ alignas(16) elem_t regions[kMergeWaves][kSegElems + 4 * P];  // + a shifted segment's end + what the merge reads past it
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), local_wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int64_t gtile = blockIdx.x / kMergeBlocksPerTile;
+    const int wave = (int)(blockIdx.x % kMergeBlocksPerTile) * kMergeWaves + local_wave;  // the segment inside the tile
     const bitsnap_sparse_item &it = kBatched ? items[find_sparse_item(items, count, gtile)] : single;
     const int64_t n = it.n, payload_elems = it.capacity, tile = gtile - it.first_tile;
     const int64_t seg0 = tile * kTileElems + (int64_t)wave * kSegElems;  // first element of the wave's segment
@@ -661,7 +670,7 @@ __global__ __launch_bounds__(kBlock, 4) void decode_merge_kernel(bitsnap_sparse_
     const uint32_t *__restrict__ encoder_offsets = it.tile_offsets;
     uint64_t *count_out = it.n_changed;
     elem_t *out = (elem_t *)it.out;
-    elem_t *region = regions[wave];
+    elem_t *region = regions[local_wave];
     const int64_t mask_bytes = (n + 7) >> 3;
     const uint32_t rem = n - seg0 >= kSegElems ? (uint32_t)kSegElems : (uint32_t)(n - seg0);
     const uint32_t e0 = (uint32_t)(lane * kLaneElems);
@@ -920,8 +929,8 @@ static void launch_merge(const bitsnap_sparse_item &single, const bitsnap_sparse
                          int64_t num_tiles, const uint64_t *tile_offset, hipStream_t s)
 {
     const uint32_t *tile_count = reinterpret_cast<const uint32_t *>(tile_offset + num_tiles);
-    hipLaunchKernelGGL((decode_merge_kernel<kBatched, kDelta, kSource, E>), dim3((unsigned)num_tiles), dim3(kBlock), 0, s,
-                       single, items, count, tile_offset, tile_count, tile_count + num_tiles);
+    hipLaunchKernelGGL((decode_merge_kernel<kBatched, kDelta, kSource, E>), dim3((unsigned)(num_tiles * kMergeBlocksPerTile)),
+                       dim3(kMergeBlock), 0, s, single, items, count, tile_offset, tile_count, tile_count + num_tiles);
 }
 
 template <bool kBatched, int E>
@@ -931,7 +940,7 @@ static int launch_decode_e(const bitsnap_sparse_item &single, const bitsnap_spar
     uint64_t *tile_offset = reinterpret_cast<uint64_t *>(reinterpret_cast<char *>(workspace) + kScanHeaderBytes);
     uint32_t *tile_count = reinterpret_cast<uint32_t *>(tile_offset + num_tiles);
     hipStream_t s = (hipStream_t)stream;
-    if (num_tiles > 0x7FFFFFFF || (num_tiles + kWaves - 1) / kWaves > 0x7FFFFFFF)
+    if (num_tiles > 0x7FFFFFFF / kMergeBlocksPerTile)
         return BITSNAP_E_SIZE;
     if (offsets && num_tiles > 0) {  // the encoder's tile offsets are given: one launch, nothing to count
         if (delta)
@@ -948,8 +957,8 @@ static int launch_decode_e(const bitsnap_sparse_item &single, const bitsnap_spar
         return launch_status();
     }
     if (num_tiles > 0)
-        hipLaunchKernelGGL((decode_count_kernel<kBatched, E>), dim3((unsigned)((num_tiles + kWaves - 1) / kWaves)),
-                           dim3(kBlock), 0, s, single, items, count, num_tiles, tile_count, tile_count + num_tiles);
+        hipLaunchKernelGGL((decode_count_kernel<kBatched, E>), dim3((unsigned)((num_tiles + kCountWaves - 1) / kCountWaves)),
+                           dim3(kCountWaves * kWave), 0, s, single, items, count, num_tiles, tile_count, tile_count + num_tiles);
     // the scan also reports n_changed, for an empty tensor too
     hipLaunchKernelGGL((decode_scan_kernel<kBatched, E>), dim3((unsigned)(kBatched ? count : 1)), dim3(kBlock), 0, s,
                        single, items, tile_count, tile_offset);
