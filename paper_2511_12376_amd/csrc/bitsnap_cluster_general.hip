@@ -40,6 +40,10 @@ namespace bitsnap {
 
 constexpr int kGBlock = 256;
 constexpr int kGWaves = kGBlock / kWave;
+// The three passes that stream over x (statistics, ranges, codes) run one wave per workgroup, as the one-wave
+// quantiser does: their waves share nothing, and single-wave workgroups stream reads best on this chip.
+constexpr int kStreamBlock = 64;
+constexpr int kStreamWaves = kStreamBlock / kWave;
 constexpr int kGK = 16;                  // float4 per lane
 constexpr int kGChunk = 256 * kGK;       // 4096 elements per wave
 
@@ -231,10 +235,10 @@ __device__ __forceinline__ double block_sum(double v, double *scratch)
 
 // ---- pass 1
 template <typename Src>
-__global__ __launch_bounds__(kGBlock) void wide_stats_kernel(Src src, WideSpace sp)
+__global__ __launch_bounds__(kStreamBlock) void wide_stats_kernel(Src src, WideSpace sp)
 {
     const int lane = threadIdx.x & (kWave - 1), wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int64_t gc = (int64_t)blockIdx.x * kGWaves + wave;
+    const int64_t gc = (int64_t)blockIdx.x * kStreamWaves + wave;
     if (gc >= src.chunks())
         return;
     int64_t c;
@@ -405,12 +409,12 @@ __device__ __forceinline__ void chunk_ranges(const float *__restrict__ x, const 
 }
 
 template <typename Src, bool kCounts>
-__global__ __launch_bounds__(kGBlock) void wide_range_kernel(Src src, WideSpace sp, int m)
+__global__ __launch_bounds__(kStreamBlock) void wide_range_kernel(Src src, WideSpace sp, int m)
 {
-    __shared__ WaveShared shared[kGWaves];
-    __shared__ uint32_t counters[kCounts ? kGWaves : 1][kMaxClusters * kWave];
+    __shared__ WaveShared shared[kStreamWaves];
+    __shared__ uint32_t counters[kCounts ? kStreamWaves : 1][kMaxClusters * kWave];
     const int lane = threadIdx.x & (kWave - 1), wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int64_t gc = (int64_t)blockIdx.x * kGWaves + wave;
+    const int64_t gc = (int64_t)blockIdx.x * kStreamWaves + wave;
     if (gc >= src.chunks())
         return;
     int64_t c;
@@ -593,11 +597,11 @@ __device__ __forceinline__ void chunk_codes(const float *__restrict__ x, const C
 }
 
 template <typename Src>
-__global__ __launch_bounds__(kGBlock) void wide_code_kernel(Src src, WideSpace sp, int m)
+__global__ __launch_bounds__(kStreamBlock) void wide_code_kernel(Src src, WideSpace sp, int m)
 {
-    __shared__ WaveShared shared[kGWaves];
+    __shared__ WaveShared shared[kStreamWaves];
     const int lane = threadIdx.x & (kWave - 1), wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int64_t gc = (int64_t)blockIdx.x * kGWaves + wave;
+    const int64_t gc = (int64_t)blockIdx.x * kStreamWaves + wave;
     if (gc >= src.chunks())
         return;
     int64_t c;
@@ -972,19 +976,20 @@ template <typename Src>
 static int quantize_passes(const Src &src, const WideSpace &sp, int64_t chunks, int64_t slices, int64_t groups, int m,
                            bool major, const float *qmap, uint32_t *status, hipStream_t s)
 {
-    const int64_t blocks = (chunks + kGWaves - 1) / kGWaves;
-    if (blocks > 0x7FFFFFFF || slices > 0x7FFFFFFF)
+    const int64_t blocks = (chunks + kGWaves - 1) / kGWaves, stream_blocks = (chunks + kStreamWaves - 1) / kStreamWaves;
+    if (blocks > 0x7FFFFFFF || stream_blocks > 0x7FFFFFFF || slices > 0x7FFFFFFF)
         return BITSNAP_E_SIZE;
-    const dim3 block(kGBlock), cgrid((unsigned)blocks), sgrid((unsigned)slices), ggrid(general_grid(groups));
-    hipLaunchKernelGGL(wide_stats_kernel<Src>, cgrid, block, 0, s, src, sp);
+    const dim3 block(kGBlock), sgrid((unsigned)slices), ggrid(general_grid(groups));
+    const dim3 stream_block(kStreamBlock), stream_grid((unsigned)stream_blocks);
+    hipLaunchKernelGGL(wide_stats_kernel<Src>, stream_grid, stream_block, 0, s, src, sp);
     hipLaunchKernelGGL(wide_slice_stats_kernel<Src>, sgrid, block, 0, s, src, sp);
     hipLaunchKernelGGL(wide_fit_kernel<Src>, ggrid, block, 0, s, src, sp, m, status);
     if (major) {
-        hipLaunchKernelGGL((wide_range_kernel<Src, true>), cgrid, block, 0, s, src, sp, m);
+        hipLaunchKernelGGL((wide_range_kernel<Src, true>), stream_grid, stream_block, 0, s, src, sp, m);
         hipLaunchKernelGGL((wide_slice_kernel<Src, true, true>), sgrid, block, 0, s, src, sp);
         hipLaunchKernelGGL((wide_group_kernel<Src, true, true>), ggrid, block, 0, s, src, sp, m);
     } else {
-        hipLaunchKernelGGL((wide_range_kernel<Src, false>), cgrid, block, 0, s, src, sp, m);
+        hipLaunchKernelGGL((wide_range_kernel<Src, false>), stream_grid, stream_block, 0, s, src, sp, m);
         hipLaunchKernelGGL((wide_slice_kernel<Src, true, false>), sgrid, block, 0, s, src, sp);
         hipLaunchKernelGGL((wide_group_kernel<Src, true, false>), ggrid, block, 0, s, src, sp, m);
     }
@@ -997,7 +1002,7 @@ static int quantize_passes(const Src &src, const WideSpace &sp, int64_t chunks, 
     else if (major)
         BITSNAP_CODE_EX(false, true);
     else
-        hipLaunchKernelGGL(wide_code_kernel<Src>, cgrid, block, 0, s, src, sp, m);
+        hipLaunchKernelGGL(wide_code_kernel<Src>, stream_grid, stream_block, 0, s, src, sp, m);
 #undef BITSNAP_CODE_EX
     return launch_status();
 }

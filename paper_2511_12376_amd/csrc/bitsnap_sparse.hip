@@ -608,16 +608,15 @@ __global__ __launch_bounds__(kBlock) void decode_scan_kernel(bitsnap_sparse_item
         *it.n_changed = carry_s;
 }
 
-// The merge: out = bit ? next payload element : base.  One workgroup per tile, and inside the tile one
-// wavefront per segment (an eighth of the tile: 8 KB of output), each entirely on its own - no barrier
-// anywhere.  A wave requests its base pieces, its own mask bytes and the mask bytes between the start of the
+// The merge: out = bit ? next payload element : base.  One wavefront per segment (an eighth of a tile: 8 KB
+// of output), each entirely on its own - no barrier anywhere; kMergeWaves of them make a workgroup.  A wave
+// requests its base pieces, its own mask bytes and the mask bytes between the start of the
 // tile and its segment at once; the popcount of the latter is the segment's place behind the tile's offset
 // (the other waves of the tile read the same few KB, from L2).  Then it fetches its part of the payload as
 // aligned 16-byte pieces into its private region of LDS (region[i] holds payload element src0 + i, src0 a
 // multiple of 16 / E), from where every lane picks its elements by rank.  With the eight waves of a tile
-// meeting at two barriers per tile, and ordinary instead of non-temporal accesses to payload and output,
-// this kernel ran 3 to 6 points of HBM peak slower (a 524 M-element tensor: 62 / 62 / 66 % at 0 / 6 / 71 %
-// changed against 67 / 68 / 69 %).
+// in one workgroup, meeting at two barriers per tile, and ordinary instead of non-temporal accesses to payload
+// and output, this kernel ran 5 to 8 points of HBM peak slower.
 // kDelta: the payload holds cur XOR base; the element is base XOR payload.
 // kSource: where the tile's offset in the payload comes from - the counting and scanning kernels
 // (kFromWorkspace), the encoder's tile_offsets (kFromEncoder), or nowhere: the wave counts the tensor's whole
