@@ -324,6 +324,8 @@ def main():
                    "dequantize_cluster": "dequantize_cluster_batched_kernel<16>" if batched else "dequantize_cluster_kernel<16>"}
     launches = n_launch[dominant]
     traffic, traffic_src = read_traffic(cfg, p, kernel_name[dominant], args.mode)
+    if args.limit_tensors or args.batch_elems is not None:   # the committed counter readings are of the whole workload
+        traffic, traffic_src = None, None
     roofline = {"bound": "hbm", "kernel": kernel_name[dominant],
                 "achieved": round(alg_bytes[dominant] / (op_ms[dominant] * 1e-3) / 1e9, 1),
                 "peak": HBM_PEAK_GBS, "unit": "GB/s",
