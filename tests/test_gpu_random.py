@@ -35,7 +35,7 @@ def _changes(rng, n):
     return np.full(n, kind == 5)
 
 
-@pytest.mark.parametrize("seed", range(40))
+@pytest.mark.parametrize("seed", range(100))
 def test_sparse_pair_on_random_cases(seed):
     rng = np.random.default_rng(1000 + seed)
     wide = bool(rng.integers(0, 2))
@@ -68,7 +68,7 @@ def test_sparse_pair_on_random_cases(seed):
     assert np.array_equal(dec_o(base, o_mask, o_pay, delta=delta), cur)
 
 
-@pytest.mark.parametrize("seed", range(40))
+@pytest.mark.parametrize("seed", range(100))
 def test_cluster_pair_on_random_cases(seed):
     rng = np.random.default_rng(2000 + seed)
     G = int(rng.choice([256, 512, 1024, 2048, 4096, 0, 2 * int(rng.integers(1, 5000)), 4096 * int(rng.integers(2, 40)) + 2 * int(rng.integers(0, 2048))]))
