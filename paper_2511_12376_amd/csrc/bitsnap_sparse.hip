@@ -619,10 +619,13 @@ __global__ __launch_bounds__(kBlock) void decode_scan_kernel(bitsnap_sparse_item
 // and output, this kernel ran 5 to 8 points of HBM peak slower.
 // kDelta: the payload holds cur XOR base; the element is base XOR payload.
 // kSource: where the tile's offset in the payload comes from - the counting and scanning kernels
-// (kFromWorkspace), the encoder's tile_offsets (kFromEncoder), or nowhere: the wave counts the tensor's whole
-// mask before its segment itself (kFromMask; tensors of a few tiles, decoded by this one launch).
-enum { kFromWorkspace = 0, kFromEncoder = 1, kFromMask = 2 };
-constexpr int kSoloTiles = 8;  // single tensors of up to this many tiles take kFromMask
+// (kFromWorkspace), the counting kernel alone (kFromCounts: the wave adds up the counts of the tensor's earlier
+// tiles itself, a few KB from L2, which saves a single tensor of moderate size the scanning launch), the
+// encoder's tile_offsets (kFromEncoder), or nowhere: the wave counts the tensor's whole mask before its
+// segment itself (kFromMask; tensors of a few tiles, decoded by this one launch).
+enum { kFromWorkspace = 0, kFromEncoder = 1, kFromMask = 2, kFromCounts = 3 };
+constexpr int kSoloTiles = 8;        // single tensors of up to this many tiles take kFromMask
+constexpr int kCountsTiles = 2048;   // single tensors of up to this many tiles take kFromCounts (offsets stay below 2^32)
 // Waves of a tile do not cooperate, so the workgroup is only the unit in which the hardware hands out wave
 // slots and LDS: a new workgroup starts when a whole one has left.  With the byte mix of this kernel and no
 // logic, 16 waves per CU stream at 67-70 % of HBM peak as 512-thread workgroups, 72-74 % as 256-thread ones,
@@ -678,10 +681,19 @@ __global__ __launch_bounds__(kMergeBlock) void decode_merge_kernel(bitsnap_spars
     // (loads return in the order they were issued).
     uint64_t known_start = 0;
     uint32_t known_count = 0;
-    if (kSource == kFromWorkspace) {
+    if (kSource == kFromWorkspace || kSource == kFromCounts) {
+        uint64_t tile_excl;
+        if (kSource == kFromCounts) {  // the counts of the tensor's earlier tiles (at most kCountsTiles of them)
+            uint32_t partial = 0;
+            for (int64_t i = lane; i < tile; i += kWave)
+                partial += tile_count[it.first_tile + i];
+            tile_excl = read_lane(wave_inclusive_add(partial), kWave - 1);
+        } else {
+            tile_excl = uniform64(tile_offset[gtile]);
+        }
         const uint32_t here = __builtin_amdgcn_readfirstlane(seg_prefix[gtile * kWaves + wave]);
         const uint32_t next = __builtin_amdgcn_readfirstlane(wave + 1 < kWaves ? seg_prefix[gtile * kWaves + wave + 1] : tile_count[gtile]);
-        known_start = uniform64(tile_offset[gtile]) + here;
+        known_start = tile_excl + here;
         known_count = next - here;
     }
 
@@ -737,7 +749,7 @@ __global__ __launch_bounds__(kMergeBlock) void decode_merge_kernel(bitsnap_spars
             }
         }
     };
-    if (kSource == kFromWorkspace) {
+    if (kSource == kFromWorkspace || kSource == kFromCounts) {
         start = known_start;
         seg_count = known_count;
         request_payload();
@@ -755,7 +767,7 @@ __global__ __launch_bounds__(kMergeBlock) void decode_merge_kernel(bitsnap_spars
         rank[q + 1] = counted + (tot & 0xFFFFu) + (ex >> 16);
         counted += (tot & 0xFFFFu) + (tot >> 16);
     }
-    if (kSource != kFromWorkspace) {
+    if (kSource == kFromEncoder || kSource == kFromMask) {
         // set bits between the point the known offset refers to and the segment (whole bytes of whole segments)
         const int64_t from = kSource == kFromMask ? 0 : tile * (int64_t)(kTileElems / 8);
         const int32_t prior_bytes = (int32_t)((seg0 >> 3) - from);
@@ -946,6 +958,15 @@ static int launch_decode_e(const bitsnap_sparse_item &single, const bitsnap_spar
             launch_merge<kBatched, true, kFromEncoder, E>(single, items, count, num_tiles, tile_offset, s);
         else
             launch_merge<kBatched, false, kFromEncoder, E>(single, items, count, num_tiles, tile_offset, s);
+        return launch_status();
+    }
+    if (!kBatched && num_tiles > kSoloTiles && num_tiles <= kCountsTiles) {  // counting kernel, then the merge adds up the counts
+        hipLaunchKernelGGL((decode_count_kernel<kBatched, E>), dim3((unsigned)((num_tiles + kCountWaves - 1) / kCountWaves)),
+                           dim3(kCountWaves * kWave), 0, s, single, items, count, num_tiles, tile_count, tile_count + num_tiles);
+        if (delta)
+            launch_merge<kBatched, true, kFromCounts, E>(single, items, count, num_tiles, tile_offset, s);
+        else
+            launch_merge<kBatched, false, kFromCounts, E>(single, items, count, num_tiles, tile_offset, s);
         return launch_status();
     }
     if (!kBatched && num_tiles > 0 && num_tiles <= kSoloTiles) {  // a small tensor: every wave counts for itself

@@ -64,6 +64,47 @@ def test_encode_decode_match_oracle(n, p):
     assert np.array_equal(dev_to_u16(out2), o_out)
 
 
+@pytest.mark.parametrize("tiles", [8, 9, 10, 511, 1376, 2047, 2048, 2049])
+@pytest.mark.parametrize("elem_bytes", [2, 4])
+def test_decode_on_both_sides_of_its_launch_plans(tiles, elem_bytes):
+    """A single tensor is decoded by one launch up to 8 tiles, by two (counting kernel + merge that adds up the
+    tile counts itself) up to 2048, by three beyond; the last tile is ragged, the changed fraction differs from
+    tile to tile, and the decoder runs on the oracle's bytes, also in place."""
+    announce("sparse decode launch plans", tiles, elem_bytes)
+    te = B.sparse_tile_elems(elem_bytes)
+    n = (tiles - 1) * te + 4097
+    rng = np.random.default_rng(7000 + 10 * tiles + elem_bytes)
+    dt = np.uint16 if elem_bytes == 2 else np.uint32
+    base = rng.integers(0, 1 << 16, n, dtype=np.uint16).astype(dt)
+    if elem_bytes == 4:
+        base |= rng.integers(0, 1 << 16, n, dtype=np.uint32).astype(dt) << 16
+    cur = base.copy()
+    p_tile = rng.choice([0.0, 0.01, 0.3, 1.0], size=tiles)          # a different changed fraction in every tile
+    sel = rng.random(n) < np.repeat(p_tile, te)[:n]
+    cur[sel] ^= dt(1)
+    if elem_bytes == 2:
+        o_mask, o_pay, o_nc = oracle.encode_sparse(cur, base)
+        o_out = oracle.decode_sparse(base, o_mask, o_pay)
+    else:
+        o_mask, o_pay, o_nc = oracle.encode_sparse32(cur, base)
+        o_out = oracle.decode_sparse32(base, o_mask, o_pay)
+    assert o_nc == int(sel.sum()) and np.array_equal(o_out, cur)
+    tdt = torch.int16 if elem_bytes == 2 else torch.int32
+    as_dev = lambda a: torch.from_numpy(a.view(np.int16 if elem_bytes == 2 else np.int32)).to(DEV)
+    mask_d = torch.zeros(max(B.sparse_mask_bytes(n), 16), dtype=torch.uint8, device=DEV)
+    mask_d[: o_mask.size] = torch.from_numpy(o_mask).to(DEV)
+    pay_d = as_dev(np.concatenate([o_pay, np.zeros(8, dt)]))
+    base_d = as_dev(base)
+    out, cnt = B.decode_sparse(base_d, mask_d, pay_d, o_nc)
+    torch.cuda.synchronize()
+    assert int(cnt.item()) == o_nc
+    assert np.array_equal(to_np(out).view(dt), cur)
+    inplace = base_d.clone()
+    out2, cnt2 = B.decode_sparse(inplace, mask_d, pay_d, o_nc, out=inplace)
+    torch.cuda.synchronize()
+    assert int(cnt2.item()) == o_nc and np.array_equal(to_np(inplace).view(dt), cur)
+
+
 def test_decode_in_place_and_special_patterns():
     announce("sparse in-place / -0 / NaN")
     pats = np.array([0x0000, 0x8000, 0x7FC1, 0x7FC2, 0x7F80, 0x0001], np.uint16)
