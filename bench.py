@@ -319,7 +319,9 @@ def main():
     dominant = max(ORDER, key=lambda op: op_ms[op])
     batched = args.mode == "batched"
     kernel_name = {"encode_sparse": f"encode_sparse_kernel<{str(batched).lower()}, false, 2, false>",
-                   "decode_sparse": f"decode_merge_kernel<{str(batched).lower()}, false, 0, 2>",   # after its counting and scanning kernels
+                   # after its counting kernel; a single tensor of up to 2048 tiles (nearly all of them) takes the form
+                   # of the merge that adds up the tile counts itself (source 3), a list the scanned offsets (source 0)
+                   "decode_sparse": "decode_merge_kernel<true, false, 0, 2>" if batched else "decode_merge_kernel<false, false, 3, 2>",
                    "quantize_cluster": "quantize_cluster_batched_kernel<16>" if batched else "quantize_cluster_kernel<16>",
                    "dequantize_cluster": "dequantize_cluster_batched_kernel<16>" if batched else "dequantize_cluster_kernel<16>"}
     launches = n_launch[dominant]

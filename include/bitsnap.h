@@ -136,7 +136,7 @@ int bitsnap_encode_sparse(const void *cur, const void *base, int64_t n, int elem
  * Three launches: set bits per tile, payload offset per tile, then the merge, which has no
  * dependency between workgroups (nothing in decode waits, so it cannot give up); a tensor of at
  * most 8 tiles is decoded by one launch, in which every wavefront counts the mask before its part,
- * and one of at most 2048 tiles by two (the merge adds up the tile counts itself). */
+ * and one of at most 4096 tiles by two (the merge adds up the tile counts itself). */
 int bitsnap_decode_sparse(const void *base, const uint8_t *mask, const void *payload,
                           int64_t payload_elems, int64_t n, int elem_bytes, void *out,
                           uint64_t *n_changed,

@@ -625,7 +625,7 @@ __global__ __launch_bounds__(kBlock) void decode_scan_kernel(bitsnap_sparse_item
 // segment itself (kFromMask; tensors of a few tiles, decoded by this one launch).
 enum { kFromWorkspace = 0, kFromEncoder = 1, kFromMask = 2, kFromCounts = 3 };
 constexpr int kSoloTiles = 8;        // single tensors of up to this many tiles take kFromMask
-constexpr int kCountsTiles = 2048;   // single tensors of up to this many tiles take kFromCounts (offsets stay below 2^32)
+constexpr int kCountsTiles = 4096;   // single tensors of up to this many tiles take kFromCounts (offsets stay below 2^32)
 // Waves of a tile do not cooperate, so the workgroup is only the unit in which the hardware hands out wave
 // slots and LDS: a new workgroup starts when a whole one has left.  With the byte mix of this kernel and no
 // logic, 16 waves per CU stream at 67-70 % of HBM peak as 512-thread workgroups, 72-74 % as 256-thread ones,
@@ -683,10 +683,28 @@ __global__ __launch_bounds__(kMergeBlock) void decode_merge_kernel(bitsnap_spars
     uint32_t known_count = 0;
     if (kSource == kFromWorkspace || kSource == kFromCounts) {
         uint64_t tile_excl;
-        if (kSource == kFromCounts) {  // the counts of the tensor's earlier tiles (at most kCountsTiles of them)
+        if (kSource == kFromCounts) {
+            // the counts of the tensor's earlier tiles (at most kCountsTiles of them), two per lane and load, a
+            // batch of loads in flight at a time; the array is 8-byte aligned and holds an entry for this tile
+            // too, so the second word of a pair is always there
+            const uint32_t *__restrict__ counts = tile_count + it.first_tile;
+            constexpr int kBatch = 16;
             uint32_t partial = 0;
-            for (int64_t i = lane; i < tile; i += kWave)
-                partial += tile_count[it.first_tile + i];
+            for (int64_t lo = 0; lo < tile; lo += kBatch * kWave * 2) {
+                uint2 pair[kBatch];
+#pragma unroll
+                for (int k = 0; k < kBatch; ++k) {
+                    const int64_t i = lo + (int64_t)(k * kWave + lane) * 2;
+                    pair[k] = make_uint2(0u, 0u);
+                    if (i < tile)
+                        pair[k] = *reinterpret_cast<const uint2 *>(counts + i);
+                }
+#pragma unroll
+                for (int k = 0; k < kBatch; ++k) {
+                    const int64_t i = lo + (int64_t)(k * kWave + lane) * 2;
+                    partial += pair[k].x + (i + 1 < tile ? pair[k].y : 0u);
+                }
+            }
             tile_excl = read_lane(wave_inclusive_add(partial), kWave - 1);
         } else {
             tile_excl = uniform64(tile_offset[gtile]);

@@ -16,7 +16,7 @@ WORKLOADS = [(1, 0.01), (1, 0.06), (1, 0.2), (2, None), (3, None), (4, None)]
 KERNELS = {
     "batched": ["encode_sparse_kernel<true, false, 2, false>", "decode_merge_kernel<true, false, 0, 2>",
                 "quantize_cluster_batched_kernel<16>", "dequantize_cluster_batched_kernel<16>"],
-    "per-tensor": ["encode_sparse_kernel<false, false, 2, false>", "decode_merge_kernel<false, false, 0, 2>",
+    "per-tensor": ["encode_sparse_kernel<false, false, 2, false>", "decode_merge_kernel<false, false, 3, 2>",
                    "quantize_cluster_kernel<16>", "dequantize_cluster_kernel<16>"],
 }
 

@@ -64,11 +64,11 @@ def test_encode_decode_match_oracle(n, p):
     assert np.array_equal(dev_to_u16(out2), o_out)
 
 
-@pytest.mark.parametrize("tiles", [8, 9, 10, 511, 1376, 2047, 2048, 2049])
+@pytest.mark.parametrize("tiles", [8, 9, 10, 511, 1376, 2049, 4095, 4096, 4097])
 @pytest.mark.parametrize("elem_bytes", [2, 4])
 def test_decode_on_both_sides_of_its_launch_plans(tiles, elem_bytes):
     """A single tensor is decoded by one launch up to 8 tiles, by two (counting kernel + merge that adds up the
-    tile counts itself) up to 2048, by three beyond; the last tile is ragged, the changed fraction differs from
+    tile counts itself) up to 4096, by three beyond; the last tile is ragged, the changed fraction differs from
     tile to tile, and the decoder runs on the oracle's bytes, also in place."""
     announce("sparse decode launch plans", tiles, elem_bytes)
     te = B.sparse_tile_elems(elem_bytes)
