@@ -202,6 +202,40 @@ def test_deviation_on_both_sides_of_the_one_pass_limit():
     assert differing <= total // 1000
 
 
+@pytest.mark.parametrize("n", [1025, 1027, 1500, 2047, 2048, 2049, 3071, 3072, 3073, 3074, 4093, 4094, 4095, 4096])
+@pytest.mark.parametrize("G,m", [(4096, 16), (4096, 5), (4096, 1)])
+def test_single_group_tensors_shared_by_four_waves(n, G, m):
+    """A tensor that is one group of more than 1024 elements is quantised by four waves that split it: every
+    way the split can be ragged (a part that is empty, one element, odd, a byte of labels shared by two parts
+    does not occur: parts start at multiples of 1024), data with the mean at zero, far from zero, constant."""
+    announce("cluster single group, four waves", n, G, m)
+    rng = np.random.default_rng(50_000 + n + m)
+    for kind in range(4):
+        if kind == 0:
+            x = rng.standard_normal(n) * 3e-4
+        elif kind == 1:
+            x = 1.0 + rng.standard_normal(n) * 1e-5            # mean 1e5 deviations from zero
+        elif kind == 2:
+            x = np.full(n, -2.5)                               # constant: sigma = 0 exactly
+        else:
+            x = np.square(rng.standard_normal(n)) * 1e-8       # one-sided
+            x[rng.integers(0, n)] = 1.0                        # and an outlier
+        _compare(x.astype(np.float32), G, m)
+    if n <= 2048:                                              # a shorter group length that still holds the whole tensor
+        _compare((rng.standard_normal(n) * 0.02).astype(np.float32), 2048, 16)
+
+
+@pytest.mark.parametrize("n", [4097, 5000, 8191, 8192, 8193, 70_001, 1024 * 4096 - 5, 1024 * 4096, 1024 * 4096 + 1, 1025 * 4096])
+@pytest.mark.parametrize("G", [4096, 2048])
+def test_tensors_of_few_groups_and_just_beyond(n, G):
+    """Up to 1024 groups of 2048 or 4096 elements are quantised four waves to a group; beyond, one wave to a
+    group.  Sizes on both sides, with a last group of 1 element, of one part, of ragged parts."""
+    announce("cluster few groups", n, G)
+    rng = np.random.default_rng(60_000 + n % 9973 + G)
+    x = (rng.standard_normal(n) * 2.3e-4 + np.repeat(rng.standard_normal((n + G - 1) // G) * 1e-3, G)[:n]).astype(np.float32)
+    _compare(x, G, 16)
+
+
 def test_non_finite_input_sets_status_and_stays_in_bounds():
     announce("cluster non-finite")
     x = np.random.default_rng(1).standard_normal(3 * 4096).astype(np.float32)
