@@ -233,6 +233,22 @@ __global__ __launch_bounds__(kDBlock) void dequantize_cluster_kernel(
     dequantize_group<K>(codes, labels, params, lo, rest >= G ? G : (int)rest, true, m, g, out, coder[wave], lane);
 }
 
+// The dequantiser for tensors of few groups: four waves per group as in quantize_cluster_shared_kernel; here the
+// parts share nothing but the group's 16 (S, b) pairs, which every wave fetches for itself.
+__global__ __launch_bounds__(kSmallWaves *kWave) void dequantize_cluster_shared_kernel(
+    const uint8_t *__restrict__ codes, const uint8_t *__restrict__ labels, const float *__restrict__ params, int64_t n,
+    int G, int m, float *__restrict__ out)
+{
+    __shared__ float2 coder[kSmallWaves][kMaxClusters];
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
+    const int64_t g = blockIdx.x, g_lo = g * G;
+    const int g_len = n - g_lo >= G ? G : (int)(n - g_lo);
+    const int len = g_len - wave * kSmallPart >= kSmallPart ? kSmallPart : (g_len > wave * kSmallPart ? g_len - wave * kSmallPart : 0);
+    if (len <= 0)
+        return;  // whole wave leaves; no workgroup barrier in this kernel
+    dequantize_group<kSmallK>(codes, labels, params, g_lo + wave * kSmallPart, len, true, m, g, out, coder[wave], lane);
+}
+
 // ---------------------------------------------------------------------------------------------
 // Batched forms: one launch for a list of tensors.  Groups are numbered across the list
 // (item.first_group = groups of all earlier items) and the grid has one wave per group of the
@@ -407,6 +423,11 @@ extern "C" int bitsnap_dequantize_cluster(const uint8_t *codes, const uint8_t *l
         return BITSNAP_E_SIZE;
     const dim3 grid((unsigned)blocks), block(kDBlock);
     hipStream_t s = (hipStream_t)stream;
+    if (groups <= kSharedGroups && 256 * K > kSmallPart && n > kSmallPart) {  // few groups: four waves share each
+        hipLaunchKernelGGL(dequantize_cluster_shared_kernel, dim3((unsigned)groups), dim3(kSmallWaves * kWave), 0, s, codes, labels,
+                           params, n, 256 * K, m, out);
+        return launch_status();
+    }
 #define BITSNAP_LAUNCH_D(KK) \
     hipLaunchKernelGGL(dequantize_cluster_kernel<KK>, grid, block, 0, s, codes, labels, params, n, groups, m, out)
     switch (K) {
