@@ -17,7 +17,7 @@ KERNELS = {
     "batched": ["encode_sparse_kernel<true, false, 2, false>", "decode_merge_kernel<true, false, 0, 2>",
                 "quantize_cluster_batched_kernel<16>", "dequantize_cluster_batched_kernel<16>"],
     "per-tensor": ["encode_sparse_kernel<false, false, 2, false>", "decode_merge_kernel<false, false, 3, 2>",
-                   "quantize_cluster_kernel<16>", "dequantize_cluster_kernel<16>"],
+                   "quantize_cluster_kernel<16>", "dequantize_cluster_shared_kernel"],
 }
 
 
