@@ -9,7 +9,7 @@
 // is processed by one 512-thread workgroup; all of a tile's loads are issued before anything
 // waits on them.  A lane owns pieces of 8 consecutive elements (one mask byte; one or two 16-byte
 // loads); in the encoder a wavefront owns, in each round, two consecutive 512-element chunks, in the
-// decoder's merge one contiguous eighth of the tile.  Per-lane popcounts are scanned with DPP inside
+// decoder's merge one contiguous sixteenth of the tile.  Per-lane popcounts are scanned with DPP inside
 // the wave, and in the encoder through LDS across the eight waves and the rounds and with the
 // decoupled look-back of scan_state.hpp across tiles.  The tile is large because every tile costs the machine one
 // same-address atomic (the ticket) and a handful of polls of its predecessors' scan words, and
@@ -512,8 +512,12 @@ __device__ __forceinline__ int64_t find_sparse_item(const bitsnap_sparse_item *_
     return lo;
 }
 
+// Segments per tile in the decoder: a wave of the merge owns one (2048 two-byte or 1024 four-byte elements).  With 8
+// segments of twice the size, single tensors decode 2 to 10 % slower (the smaller the tensor, the more); lists the same.
+constexpr int kDecSegs = 16;
+
 // One wave per tile: popcount of the tile's 4 or 2 KB of mask (bits at or beyond n do not count), and the
-// places of the tile's eight segments inside the tile.
+// places of the tile's segments inside the tile.
 constexpr int kCountWaves = 2;  // tiles per workgroup of the counting kernel (small workgroups: see kMergeWaves)
 template <bool kBatched, int E>
 __global__ __launch_bounds__(kCountWaves * kWave) void decode_count_kernel(bitsnap_sparse_item single,
@@ -533,7 +537,7 @@ __global__ __launch_bounds__(kCountWaves * kWave) void decode_count_kernel(bitsn
     static_assert(kPerLane % 8 == 0, "a lane reads whole 8-byte pieces of the mask");
     // Pass q covers 512 consecutive mask bytes, i.e. one or two whole segments (a wave's part of the tile in
     // the merge): the running sums at the segments' last lanes are the segments' places inside the tile.
-    constexpr int kSegsPerPass = (kWave * 8) / (Geom<E>::kTileElems / kWaves / 8);
+    constexpr int kSegsPerPass = (kWave * 8) / (Geom<E>::kTileElems / kDecSegs / 8);
     // All of the lane's loads are issued before the first is used.  An 8-byte piece that straddles the end of the
     // mask is read whole (the buffer is 16-byte aligned, so the load stays inside the 16-byte block of the mask's
     // last byte); one that lies beyond it reads the tile's first bytes instead; what is not mask is cleared below.
@@ -563,7 +567,7 @@ __global__ __launch_bounds__(kCountWaves * kWave) void decode_count_kernel(bitsn
         for (int sgm = 0; sgm < kSegsPerPass; ++sgm) {
             const uint32_t inside = sgm == 0 ? 0u : read_lane(incl, sgm == 0 ? 0 : sgm * (kWave / kSegsPerPass) - 1);
             if (lane == 0)
-                seg_prefix[gt * kWaves + q * kSegsPerPass + sgm] = run + inside;
+                seg_prefix[gt * kDecSegs + q * kSegsPerPass + sgm] = run + inside;
         }
         run += read_lane(incl, kWave - 1);
     }
@@ -608,7 +612,7 @@ __global__ __launch_bounds__(kBlock) void decode_scan_kernel(bitsnap_sparse_item
         *it.n_changed = carry_s;
 }
 
-// The merge: out = bit ? next payload element : base.  One wavefront per segment (an eighth of a tile: 8 KB
+// The merge: out = bit ? next payload element : base.  One wavefront per segment (a sixteenth of a tile: 4 KB
 // of output), each entirely on its own - no barrier anywhere; kMergeWaves of them make a workgroup.  A wave
 // requests its base pieces, its own mask bytes and the mask bytes between the start of the
 // tile and its segment at once; the popcount of the latter is the segment's place behind the tile's offset
@@ -632,14 +636,14 @@ constexpr int kCountsTiles = 4096;   // single tensors of up to this many tiles 
 // 77-78 % as 128-thread ones and 74-75 % as single waves.
 constexpr int kMergeWaves = 2;                          // waves (segments) per workgroup
 constexpr int kMergeBlock = kMergeWaves * kWave;
-constexpr int kMergeBlocksPerTile = kWaves / kMergeWaves;
+constexpr int kMergeBlocksPerTile = kDecSegs / kMergeWaves;
 
 template <int E>
 struct DecGeom {
-    static constexpr int kSegElems = Geom<E>::kTileElems / kWaves;      // 4096 two-byte or 2048 four-byte elements
-    static constexpr int kPieces = kSegElems / kChunkElems;             // 512-element pieces per segment: 8 or 4
+    static constexpr int kSegElems = Geom<E>::kTileElems / kDecSegs;    // 2048 two-byte or 1024 four-byte elements
+    static constexpr int kPieces = kSegElems / kChunkElems;             // 512-element pieces per segment: 4 or 2
     static constexpr int kSegMaskBytes = kSegElems / 8;
-    static constexpr int kVecsPerLane = kSegElems / Geom<E>::kVecElems / kWave;  // 16-byte payload pieces per lane: 8
+    static constexpr int kVecsPerLane = kSegElems / Geom<E>::kVecElems / kWave;  // 16-byte payload pieces per lane: 4
     static_assert(kPieces % 2 == 0, "counts are scanned two to a word");
 };
 
@@ -709,8 +713,8 @@ __global__ __launch_bounds__(kMergeBlock) void decode_merge_kernel(bitsnap_spars
         } else {
             tile_excl = uniform64(tile_offset[gtile]);
         }
-        const uint32_t here = __builtin_amdgcn_readfirstlane(seg_prefix[gtile * kWaves + wave]);
-        const uint32_t next = __builtin_amdgcn_readfirstlane(wave + 1 < kWaves ? seg_prefix[gtile * kWaves + wave + 1] : tile_count[gtile]);
+        const uint32_t here = __builtin_amdgcn_readfirstlane(seg_prefix[gtile * kDecSegs + wave]);
+        const uint32_t next = __builtin_amdgcn_readfirstlane(wave + 1 < kDecSegs ? seg_prefix[gtile * kDecSegs + wave + 1] : tile_count[gtile]);
         known_start = tile_excl + here;
         known_count = next - here;
     }
@@ -855,7 +859,7 @@ __global__ __launch_bounds__(kMergeBlock) void decode_merge_kernel(bitsnap_spars
 // A raw offset is below 2^40, so as a scan word its flag bits read "not written": a decode never
 // confuses a later encode.
 constexpr size_t kWorkspaceBytesPerTile = 8 * kStatusStride;
-static_assert(kWorkspaceBytesPerTile >= 12 + 4 * kWaves, "decode keeps 8 + 4 + 4 * 8 bytes per tile");
+static_assert(kWorkspaceBytesPerTile >= 12 + 4 * kDecSegs, "decode keeps 8 + 4 + 4 * segments bytes per tile");
 
 static std::atomic<uint32_t> g_spin_limit{kDefaultSpinLimit};
 
