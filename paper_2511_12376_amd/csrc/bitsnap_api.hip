@@ -116,7 +116,7 @@ extern "C" int bitsnap_debug_stream_copy(void *dst, const void *src, int64_t byt
     return bitsnap::launch_status();
 }
 
-extern "C" int bitsnap_version(void) { return 100; /* 0.1.0 */ }
+extern "C" int bitsnap_version(void) { return 200; /* 0.2.0: bitsnap_encode_sparse_static, the opt-in of the test knob */ }
 
 extern "C" const char *bitsnap_error_string(int code)
 {
