@@ -10,10 +10,10 @@
 // waits on them.  A lane owns pieces of 8 consecutive elements (one mask byte; one or two 16-byte
 // loads); in the encoder a wavefront owns, in each round, two consecutive 512-element chunks, in the
 // decoder's merge one contiguous sixteenth of the tile.  Per-lane popcounts are scanned with DPP inside
-// the wave, and in the encoder through LDS across the eight waves and the rounds and with the
-// decoupled look-back of scan_state.hpp across tiles.  The tile is large because every tile costs the machine one
-// same-address atomic (the ticket) and a handful of polls of its predecessors' scan words, and
-// both are served far more slowly than streaming traffic.  Changed values are staged in LDS so
+// the wave, and in the encoder through LDS across the eight waves and the rounds and by the
+// scanning wave of scan_state.hpp across tiles.  The tile is large because every tile costs the machine one
+// same-address atomic (the ticket; the chip serves 88 million of them per second, one every 11.4 ns)
+// and two words of scan state.  Changed values are staged in LDS so
 // that the payload leaves (encode) or enters (decode) HBM as 16-byte accesses aligned on the
 // payload buffer, whatever the tile's (decode: the wave's) offset.
 #include <hip/hip_runtime.h>
@@ -185,29 +185,6 @@ __device__ __forceinline__ uint32_t tile_ranks(TileShared<E> &sh, const uint32_t
     return run;
 }
 
-// Wave 0, after the tile's count has been published: the count of everything before the tile in
-// the same tensor; publishes the inclusive value; the result reaches the other waves through
-// sh.excl / sh.aborted.  `tile` and `first_tile` (the tensor's first tile) are in the launch-wide
-// numbering.
-template <int E>
-__device__ __forceinline__ void tile_look_back(TileShared<E> &sh, ScanHeader *hdr, uint64_t *status, int64_t tile,
-                                               int64_t first_tile, uint32_t epoch, uint32_t spin_limit,
-                                               uint32_t tile_total, int lane)
-{
-    uint64_t excl = 0;
-    bool aborted = false;
-    if (tile != first_tile) {
-        excl = look_back(status, hdr, tile, first_tile, epoch, spin_limit, aborted);
-        if (lane == 0)
-            publish(status, tile, aborted ? make_status(kFlagAbort, epoch, 0)
-                                          : make_status(kFlagInclusive, epoch, excl + tile_total));
-    }
-    if (lane == 0) {
-        sh.excl = excl;
-        sh.aborted = aborted ? 1 : 0;
-    }
-}
-
 // All of a tile's loads for the calling lane (issued back to back, nothing waits here): a
 // wave-uniform tile base plus a 32-bit offset each.  A 16-byte load whose first element lies at or
 // beyond the end of the tensor reads the tile's first 16 bytes instead, and one that straddles the
@@ -355,22 +332,33 @@ __device__ __forceinline__ void copy_out_stage(const TileShared<E> &sh, typename
     }
 }
 
-// Order of work in one turn of the loop:
-//   the tile's loads are issued -> the previous tile's staged values go out as 16-byte stores
-//   aligned on the payload buffer, realigned on the way out of LDS -> mask bytes and counts ->
-//   ranks inside the tile -> the tile's count is published -> changed values are scattered into
-//   LDS at their rank inside the tile (this needs nothing from other tiles, so it runs while the
-//   preceding tiles are still publishing) -> look-back (wave 0) -> ticket for the next tile.
-// So HBM reads of a tile overlap the copy-out of the tile before it.  The ticket is requested
-// only after the look-back: between the ticket and the published count of a tile then lies one
-// load latency and nothing that waits on other workgroups.  (With the ticket requested earlier,
-// to hide its round trip, a slow look-back delays the count of the workgroup's next tile, which
-// slows the look-backs of the tiles after that one, and so on: measured at half the throughput.)
+// What a workgroup remembers of the tile whose values wait in its stage.
+template <int E>
+struct StagedTile {
+    typename Geom<E>::elem_t *payload;
+    int64_t capacity;
+    uint32_t *offsets;
+    uint64_t *count_out;
+    int64_t gtile, tile;  // launch-wide number, number inside the tensor
+    uint32_t total;       // number of staged values
+    bool first, last;     // the tensor's first / last tile
+};
+
+// The workgroup that draws ticket 0 lends its first wave to the scan (scan_state.hpp) and does nothing else; the
+// others take tiles.  Order of work in one turn of a tile workgroup's loop:
+//   the tile's loads are issued -> thread 0 fetches the previous tile's place in the payload (its count went
+//   to the scanning wave a whole scatter, ticket and load issue ago) -> the previous tile's staged values go
+//   out as 16-byte stores aligned on the payload buffer, realigned on the way out of LDS -> mask bytes and
+//   counts -> ranks inside the tile -> the tile's count goes to the scanning wave -> changed values are
+//   scattered into LDS at their rank inside the tile -> ticket for the next tile.
+// So a tile's HBM reads overlap the wait for, and the copy-out of, the tile before it, and between a ticket and
+// the count of its tile lies one load latency and nothing that waits on another workgroup: the scanning wave
+// answers tiles in ticket order, so a count that comes late holds up every tile behind it.
 // launch_bounds: 4 waves per SIMD, i.e. two 512-thread workgroups per CU (128 registers per lane).
 // kDelta: the payload holds cur XOR base (the non-zero elements of the delta states) instead of
 // cur.  refresh: item.out, where set, receives a copy of cur (it may be the base buffer itself: a
 // tile's base is in registers before the tile's copy of cur is stored, and no other tile touches it).
-// kSolo: the launch is one workgroup for a tensor of one tile, which needs no ticket, no scan state and no
+// kSolo: the launch is one workgroup for a tensor of one tile, which needs no ticket, no scan and no
 // last-workgroup bookkeeping: the workspace is not touched at all.
 template <bool kBatched, bool kDelta, int E, bool kSolo = false>
 __global__ __launch_bounds__(kBlock, 4) void encode_sparse_kernel(bitsnap_sparse_item single,
@@ -382,20 +370,23 @@ __global__ __launch_bounds__(kBlock, 4) void encode_sparse_kernel(bitsnap_sparse
     typedef typename Geom<E>::elem_t elem_t;
     constexpr int kRounds = Geom<E>::kRounds, kTileElems = Geom<E>::kTileElems;
     __shared__ TileShared<E> sh;
+    __shared__ StagedTile<E> st;
     const int tid0 = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid0 >> 6);
     const uint32_t epoch = kSolo ? 0u : hdr->epoch;
     bool aborted = false;
     ItemCursor<kBatched> cursor(single, items, count);
 
     if (tid0 == 0)
-        sh.next_tile = kSolo ? 0 : (int64_t)atomicAdd(&hdr->ticket, 1u);
+        sh.next_tile = kSolo ? 0 : (int64_t)atomicAdd(&hdr->ticket, 1u) - 1;
     __syncthreads();
-    // the previous tile of this workgroup: staged in LDS, still to be copied out
-    bool staged = false;
-    elem_t *__restrict__ staged_payload = nullptr;
-    int64_t staged_capacity = 0;
-    uint64_t staged_excl = 0;
-    uint32_t staged_total = 0;
+    if (!kSolo && claimed_tile(sh) < 0) {  // ticket 0: the scan
+        if (wave == 0)
+            aborted = serve_scan(hdr, status, num_tiles, epoch, spin_limit);
+        const int epilogue = scan_epilogue(hdr, status, status_cap, epoch, aborted);  // thread 0 is in wave 0
+        report_failures(epilogue, single, items, count, kBatched, num_tiles);
+        return;
+    }
+    bool staged = false;  // the previous tile of this workgroup is in the stage (and described in st), still to be copied out
     for (;;) {
         // The thread's index is made opaque once per turn: otherwise every per-piece offset derived
         // from it counts as loop-invariant and is kept in (or spilled from) a register of its own.
@@ -410,11 +401,33 @@ __global__ __launch_bounds__(kBlock, 4) void encode_sparse_kernel(bitsnap_sparse
             load_tile<E>((const elem_t *)cursor.it.src, gtile - cursor.it.first_tile, wave, lane, cursor.it.n, c);
             load_tile<E>((const elem_t *)cursor.it.base, gtile - cursor.it.first_tile, wave, lane, cursor.it.n, b);
         }
-        if (staged)
-            copy_out_stage<E>(sh, staged_payload, staged_capacity, staged_excl, staged_total, tid);
+        if (staged) {
+            if (tid == 0) {
+                uint32_t zero = 0;
+                asm volatile("" : "+v"(zero));  // made here, not kept in registers across the loop
+                uint64_t before = zero;         // a tensor's first tile starts its payload
+                bool ok = true;
+                if (!st.first)
+                    ok = await_prefix(hdr, status, num_tiles, st.gtile, epoch, spin_limit, before);
+                sh.excl = before;
+                sh.aborted = ok ? 0 : 1;
+                if (ok) {
+                    if (st.offsets)
+                        st.offsets[st.tile] = (uint32_t)before;
+                    if (st.last)  // the tensor's last tile knows the total
+                        *st.count_out = before + st.total;
+                }
+            }
+            __syncthreads();  // sh.excl / sh.aborted are set
+            if (sh.aborted) {
+                aborted = true;
+                break;
+            }
+            copy_out_stage<E>(sh, (elem_t *)uniform64((uint64_t)st.payload), (int64_t)uniform64((uint64_t)st.capacity),
+                              uniform64(sh.excl), __builtin_amdgcn_readfirstlane(st.total), tid);
+        }
         if (!valid)
             break;
-        __syncthreads();  // the stage has been read
 
         const bitsnap_sparse_item &it = cursor.it;
         const int64_t n = it.n, tile = gtile - it.first_tile;
@@ -447,9 +460,10 @@ __global__ __launch_bounds__(kBlock, 4) void encode_sparse_kernel(bitsnap_sparse
                 if (mb + lane < wave_mask_bytes)
                     ((global_u8 *)(wave_mask + mb))[(uint32_t)lane] = (uint8_t)m[r][j];
             }
-        const uint32_t total = tile_ranks<E>(sh, cnt, lane, wave, rank);  // barrier
+        // the barrier inside: every thread has also finished reading the stage and st for the tile that left above
+        const uint32_t total = tile_ranks<E>(sh, cnt, lane, wave, rank);
         if (!kSolo && tid == 0)
-            publish(status, gtile, make_status(tile == 0 ? kFlagInclusive : kFlagAggregate, epoch, total));
+            publish_count(status, gtile, tile == 0, epoch, total);
 
         // Algorithm 1 step 5, first half: changed values in index order, at their rank inside the tile
 #pragma unroll
@@ -462,27 +476,20 @@ __global__ __launch_bounds__(kBlock, 4) void encode_sparse_kernel(bitsnap_sparse
                     if ((m[r][j] >> t) & 1u)
                         sh.stage[p++] = piece_elem<E>(c[r][j], t);
             }
-        __syncthreads();  // the stage is complete
-        if (wave == 0)
-            tile_look_back(sh, hdr, status, gtile, it.first_tile, epoch, spin_limit, total, lane);
-        __syncthreads();  // sh.excl / sh.aborted are set
-        if (sh.aborted) {
-            aborted = true;
-            break;
-        }
         staged = true;
-        staged_payload = (elem_t *)it.payload;
-        staged_capacity = it.capacity;
-        staged_excl = uniform64(sh.excl);
-        staged_total = __builtin_amdgcn_readfirstlane(total);
         if (tid == 0) {
-            if (it.tile_offsets)
-                it.tile_offsets[tile] = (uint32_t)staged_excl;
-            if ((tile + 1) * kTileElems >= n)  // the tensor's last tile knows the total
-                *it.n_changed = staged_excl + total;
-            sh.next_tile = kSolo ? 1 : (int64_t)atomicAdd(&hdr->ticket, 1u);
+            st.payload = (elem_t *)it.payload;
+            st.capacity = it.capacity;
+            st.offsets = it.tile_offsets;
+            st.count_out = it.n_changed;
+            st.gtile = gtile;
+            st.tile = tile;
+            st.total = total;
+            st.first = tile == 0;
+            st.last = (tile + 1) * kTileElems >= n;
+            sh.next_tile = kSolo ? 1 : (int64_t)atomicAdd(&hdr->ticket, 1u) - 1;
         }
-        __syncthreads();  // the next tile is known
+        __syncthreads();  // the stage is complete, the next tile is known
     }
     if (kSolo)
         return;
@@ -853,12 +860,12 @@ __global__ __launch_bounds__(kMergeBlock) void decode_merge_kernel(bitsnap_spars
         *count_out = start + seg_count;
 }
 
-// Workspace after the header: encode keeps one 8-byte scan word per tile there; decode keeps the
-// tiles' payload offsets (8 bytes each, in the same place) followed by their counts (4 bytes each)
-// and the places of their segments (8 x 4 bytes each).
-// A raw offset is below 2^40, so as a scan word its flag bits read "not written": a decode never
-// confuses a later encode.
-constexpr size_t kWorkspaceBytesPerTile = 8 * kStatusStride;
+// Workspace after the header: encode keeps its count and prefix words there (scan_state.hpp: 8 bytes per tile,
+// then, from a 128-byte boundary, 64 bytes per tile); decode keeps the tiles' payload offsets (8 bytes each)
+// followed by their counts (4 bytes each) and the places of their segments (16 x 4 bytes each).
+// A raw offset is below 2^40 and a count or a place below 2^16, so as scan words their flag bits read "not
+// written": a decode never confuses a later encode.
+constexpr size_t kWorkspaceBytesPerTile = kScanBytesPerTile;
 static_assert(kWorkspaceBytesPerTile >= 12 + 4 * kDecSegs, "decode keeps 8 + 4 + 4 * segments bytes per tile");
 
 static std::atomic<uint32_t> g_spin_limit{kDefaultSpinLimit};
@@ -940,7 +947,7 @@ static int launch_scan(Kernel kernel, const bitsnap_sparse_item &single, const b
     ScanHeader *hdr = reinterpret_cast<ScanHeader *>(workspace);
     uint64_t *status = reinterpret_cast<uint64_t *>(reinterpret_cast<char *>(workspace) + kScanHeaderBytes);
     const int64_t status_cap = (int64_t)((workspace_bytes - kScanHeaderBytes) / sizeof(uint64_t));
-    const int grid = sparse_grid(reinterpret_cast<const void *>(kernel), num_tiles);
+    const int grid = sparse_grid(reinterpret_cast<const void *>(kernel), num_tiles + 1);  // + the workgroup of the scanning wave
     hipLaunchKernelGGL(kernel, dim3(grid), dim3(kBlock), 0, (hipStream_t)stream, single, items, count, hdr, status,
                        status_cap, num_tiles, g_spin_limit.load(std::memory_order_relaxed), refresh);
     return launch_status();
