@@ -292,7 +292,8 @@ def main():
             rows[op] = {"ms": round(mean, 3), "ms_median": round(med(ms_lists[op]), 3), "ms_min": round(min(ms_lists[op]), 3),
                         "api_calls": launches[op], "state_GBps": round(state_bytes[op] / mean / 1e6, 1),
                         "hbm_GBps": round(alg_bytes[op] / mean / 1e6, 1),
-                        "hbm_frac": round(alg_bytes[op] / mean / 1e6 / HBM_PEAK_GBS, 4)}
+                        "hbm_frac": round(alg_bytes[op] / mean / 1e6 / HBM_PEAK_GBS, 4),
+                        "algorithmic_bytes": int(round(alg_bytes[op]))}
         return rows
 
     ops = op_rows(per_step, n_launch)
