@@ -555,3 +555,55 @@ def test_batched_decode_with_tile_offsets():
     B.encode_sparse_batched(items, total, ws)
     torch.cuda.synchronize()
     assert int(counts[3].item()) == int((pairs[3][0] != pairs[3][1]).sum())
+
+
+@pytest.mark.parametrize("elem_bytes", [2, 4])
+def test_batched_scan_restarts_at_every_place_of_the_scanning_waves_window(elem_bytes):
+    """The scanning wave adds up the tiles' counts 64 at a time (four such windows per round) and restarts at the
+    first tile of every tensor.  Lists whose tensors are 1, 2, 62 ... 257 tiles long put those restarts at the
+    first and the last lane of a window, several into one window, and none into others; single-tensor calls of the
+    same lengths cover windows that end with the tensor.  Counts, offsets and payloads are the oracle's."""
+    announce(f"sparse scan windows, {elem_bytes}-byte elements")
+    Te = B.sparse_tile_elems(elem_bytes)
+    tiles = [1, 1, 1, 2, 59, 1, 63, 1, 64, 65, 1, 1, 127, 128, 1, 255, 256, 257, 1, 62, 2, 1]
+    sizes = [t * Te - (k * 997) % (Te - 1) for k, t in enumerate(tiles)]      # ragged last tiles, tile counts as listed
+    assert [(n + Te - 1) // Te for n in sizes] == tiles
+    mk = _pair if elem_bytes == 2 else _pair32
+    pairs = [mk(n, [0.3, 0.0, 1.0, 0.06][k % 4], 9100 + k) for k, n in enumerate(sizes)]
+    up = u16_to_dev if elem_bytes == 2 else _u32_to_dev
+    dt = torch.int16 if elem_bytes == 2 else torch.int32
+    view = np.uint16 if elem_bytes == 2 else np.uint32
+    cur = [up(c) for c, _ in pairs]
+    base = [up(b) for _, b in pairs]
+    mask = [torch.full((B.sparse_mask_bytes(n),), 0xEE, dtype=torch.uint8, device=DEV) for n in sizes]
+    payload = [torch.zeros(n + 8, dtype=dt, device=DEV) for n in sizes]
+    counts = [torch.zeros(1, dtype=torch.int64, device=DEV) for _ in sizes]
+    offs = [torch.zeros(t, dtype=torch.int32, device=DEV) for t in tiles]
+    items, total = B.sparse_items(sizes, src=cur, base=base, mask=mask, payload=payload, n_changed=counts, tile_offsets=offs,
+                                  elem_bytes=elem_bytes)
+    assert total == sum(tiles)
+    ws = torch.zeros(B.sparse_batch_workspace_bytes(total), dtype=torch.uint8, device=DEV)
+    B.encode_sparse_batched(items, total, ws, flags=None if elem_bytes == 2 else 0, elem_bytes=elem_bytes)
+    torch.cuda.synchronize()
+    enc_fn = oracle.encode_sparse if elem_bytes == 2 else oracle.encode_sparse32
+    expected = []
+    for k, (c, b) in enumerate(pairs):
+        o_mask, o_pay, o_nc = enc_fn(c, b)[:3]
+        expected.append((o_mask, o_pay, o_nc))
+        assert int(counts[k].item()) == o_nc, (k, tiles[k])
+        assert np.array_equal(to_np(mask[k])[: o_mask.size], o_mask)
+        assert np.array_equal(to_np(payload[k]).view(view)[:o_nc], o_pay), (k, tiles[k])
+        o_off = oracle.tile_offsets(o_mask, sizes[k], Te)
+        assert np.array_equal(to_np(offs[k]).view(np.uint32), o_off[:-1].astype(np.uint32)), (k, tiles[k])
+    # one call per tensor with the same workspace: every window ends with the tensor
+    for k in (3, 6, 8, 9, 13, 16, 17):
+        pay = torch.zeros(sizes[k] + 8, dtype=dt, device=DEV)
+        msk = torch.zeros(B.sparse_mask_bytes(sizes[k]), dtype=torch.uint8, device=DEV)
+        nc = torch.zeros(1, dtype=torch.int64, device=DEV)
+        off = torch.zeros(tiles[k], dtype=torch.int32, device=DEV)
+        B.encode_sparse_raw(cur[k], base[k], sizes[k], msk, pay, sizes[k] + 8, off, nc, ws, elem_bytes=elem_bytes)
+        torch.cuda.synchronize()
+        o_mask, o_pay, o_nc = expected[k]
+        assert int(nc.item()) == o_nc
+        assert np.array_equal(to_np(pay).view(view)[:o_nc], o_pay)
+        assert np.array_equal(to_np(off).view(np.uint32), oracle.tile_offsets(o_mask, sizes[k], Te)[:-1].astype(np.uint32))
