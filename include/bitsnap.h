@@ -94,9 +94,9 @@ size_t bitsnap_sparse_tile_elems_for(int elem_bytes);
 size_t bitsnap_sparse_mask_bytes(int64_t n);
 
 /* Bytes of workspace encode_sparse / decode_sparse need for a tensor of n elements (256 bytes
- * plus 128 per tile).  encode keeps its cross-workgroup scan state there, one cache line per
- * tile because all workgroups poll the same few lines; decode the payload offset and count of
- * every tile.  It must contain zeros the first time it is used (any means:
+ * plus 128 per tile).  encode keeps its cross-workgroup scan state there (a count word and an
+ * answer word per tile, the latter on a 64-byte slot of its own); decode the payload offset and
+ * count of every tile.  It must contain zeros the first time it is used (any means:
  * hipMemset, torch.zeros); afterwards the kernels leave it ready for the next call, encode or
  * decode, of any size that fits, so one workspace serves a whole checkpoint. */
 size_t bitsnap_sparse_workspace_bytes(int64_t n);
@@ -190,7 +190,8 @@ int bitsnap_encode_sparse_static(const void *cur, const void *base, int64_t n, i
                                  uint32_t *tile_offsets, uint64_t *n_changed, bitsnap_stream_t stream);
 
 /* Host-side knob for tests of the give-up path: the number of polls a workgroup spends waiting
- * for a predecessor's scan state before it reports failure through n_changed.  0 restores the
+ * for its tile's place in the payload (and the scanning wave for a tile's count) before it
+ * reports failure through n_changed.  0 restores the
  * default (large enough never to trigger in normal operation).  The value is PROCESS-GLOBAL (one
  * atomic word, read by every later encode call on any thread, stream or device when it launches):
  * a test aid, not to be called by code that encodes concurrently on other threads.  The call does
