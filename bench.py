@@ -324,7 +324,7 @@ def main():
                    # of the merge that adds up the tile counts itself (source 3), a list the scanned offsets (source 0)
                    "decode_sparse": "decode_merge_kernel<true, false, 0, 2>" if batched else "decode_merge_kernel<false, false, 3, 2>",
                    "quantize_cluster": "quantize_cluster_batched_kernel<16>" if batched else "quantize_cluster_kernel<16>",
-                   "dequantize_cluster": "dequantize_cluster_batched_kernel<16>" if batched else "dequantize_cluster_shared_kernel"}
+                   "dequantize_cluster": "dequantize_cluster_batched_parts_kernel<8>" if batched else "dequantize_cluster_parts_kernel<8>"}
     launches = n_launch[dominant]
     traffic, traffic_src = read_traffic(cfg, p, kernel_name[dominant], args.mode)
     if args.limit_tensors or args.batch_elems is not None:   # the committed counter readings are of the whole workload

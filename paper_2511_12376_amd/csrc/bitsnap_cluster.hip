@@ -253,23 +253,26 @@ __global__ __launch_bounds__(kDBlock) void dequantize_cluster_kernel(
     dequantize_group<K>(codes, labels, params, lo, rest >= G ? G : (int)rest, true, m, g, out, coder[wave], lane);
 }
 
-// The single-tensor dequantiser for groups of 2048 or 4096 elements: one wave per 1024 elements (four waves, a
-// workgroup, per group of 4096); the parts share nothing but the group's 16 (S, b) pairs, which every wave fetches
-// for itself.  Lighter waves in several rounds instead of one round of heavy ones: 8.6 -> 5.6 ms over the 1160
-// calls of a GPT-2-XL-shaped list, 21.4 -> 20.2 ms over the 873 calls of a Llama-2-7B-shaped one.  (In the batched
-// dequantiser, whose rounds overlap anyway, the same split costs 10 %.)
-__global__ __launch_bounds__(kSmallWaves *kWave) void dequantize_cluster_shared_kernel(
+// The dequantiser for groups of 2048 or 4096 elements: one wave per 512 elements, one workgroup (4 or 8 waves) per
+// group; the parts share nothing but the group's 16 (S, b) pairs, which every wave fetches for itself.  Many light,
+// short-lived waves keep reads and writes mixed evenly: with this kernel's traffic and no arithmetic, 256 elements
+// per wave stream at 78-81 % of HBM peak, 512 at 74-78 %, 1024 and 4096 at 63-71 %; with the arithmetic and the
+// fetch of the pairs 512 is best (a 537 M-element tensor: 79.7 % against 68 % for 256, 73-74 % for 1024 and 70-74 %
+// for 4096 elements per wave).
+constexpr int kDeqPartK = 2, kDeqPart = 256 * kDeqPartK;
+template <int W>  // W = waves per group: the group holds W * 512 elements
+__global__ __launch_bounds__(W *kWave) void dequantize_cluster_parts_kernel(
     const uint8_t *__restrict__ codes, const uint8_t *__restrict__ labels, const float *__restrict__ params, int64_t n,
-    int G, int m, float *__restrict__ out)
+    int m, float *__restrict__ out)
 {
-    __shared__ float2 coder[kSmallWaves][kMaxClusters];
-    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
-    const int64_t g = blockIdx.x, g_lo = g * G;
-    const int g_len = n - g_lo >= G ? G : (int)(n - g_lo);
-    const int len = g_len - wave * kSmallPart >= kSmallPart ? kSmallPart : (g_len > wave * kSmallPart ? g_len - wave * kSmallPart : 0);
-    if (len <= 0)
+    __shared__ float2 coder[W][kMaxClusters];
+    const int lane = threadIdx.x & (kWave - 1), wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int64_t g = blockIdx.x;
+    const int64_t lo = g * (W * kDeqPart) + wave * kDeqPart;
+    const int64_t rest = n - lo;
+    if (rest <= 0)
         return;  // whole wave leaves; no workgroup barrier in this kernel
-    dequantize_group<kSmallK>(codes, labels, params, g_lo + wave * kSmallPart, len, true, m, g, out, coder[wave], lane);
+    dequantize_group<kDeqPartK>(codes, labels, params, lo, rest >= kDeqPart ? kDeqPart : (int)rest, true, m, g, out, coder[wave], lane);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -328,6 +331,29 @@ __global__ __launch_bounds__(kDListBlock) void dequantize_cluster_batched_kernel
     if (rest > 0)
         dequantize_group<K>(it.codes, it.labels, it.params, lo, rest >= G ? G : (int)rest, true, m, g, (float *)it.values,
                             coder[wave], lane);
+}
+
+// The same for a list of tensors: one workgroup per group of the whole list, one wave per 512 elements; every wave
+// looks its item up itself (a binary search on the scalar unit: nine dependent loads for the 291 items of a
+// Llama-2-7B-shaped list, most of them hits in the scalar cache).  One lookup per workgroup handed on through LDS,
+// and an eight-way search with fewer round trips but more loads, were slower; so were workgroups that walk several
+// groups with one lookup.  Llama-2-7B-shaped states: 70.9 -> 76-77 % of HBM peak against one wave per group.
+template <int W>
+__global__ __launch_bounds__(W *kWave) void dequantize_cluster_batched_parts_kernel(
+    const bitsnap_cluster_item *__restrict__ items, int64_t count, int64_t total_groups, int m)
+{
+    __shared__ float2 coder[W][kMaxClusters];
+    const int lane = threadIdx.x & (kWave - 1), wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int64_t gg = blockIdx.x;
+    if (gg >= total_groups)
+        return;
+    const bitsnap_cluster_item &it = items[find_item(items, count, gg)];
+    const int64_t g = gg - it.first_group;
+    const int64_t lo = g * (W * kDeqPart) + wave * kDeqPart;
+    const int64_t rest = it.n - lo;
+    if (rest > 0)
+        dequantize_group<kDeqPartK>(it.codes, it.labels, it.params, lo, rest >= kDeqPart ? kDeqPart : (int)rest, true, m, g,
+                                    (float *)it.values, coder[wave], lane);
 }
 
 }  // namespace bitsnap
@@ -446,10 +472,13 @@ extern "C" int bitsnap_dequantize_cluster(const uint8_t *codes, const uint8_t *l
         return BITSNAP_E_SIZE;
     const dim3 grid((unsigned)blocks), block(kDBlock);
     hipStream_t s = (hipStream_t)stream;
-    if (256 * K > kSmallPart && groups <= 0x7FFFFFFF) {  // groups of 2048 or 4096 elements: one wave per 1024 of them
-        const int parts = 256 * K / kSmallPart;
-        hipLaunchKernelGGL(dequantize_cluster_shared_kernel, dim3((unsigned)groups), dim3(parts * kWave), 0, s, codes, labels,
-                           params, n, 256 * K, m, out);
+    if (256 * K >= 4 * kDeqPart && groups <= 0x7FFFFFFF) {  // groups of 2048 or 4096 elements: one wave per 512 of them
+        if (256 * K == 8 * kDeqPart)
+            hipLaunchKernelGGL(dequantize_cluster_parts_kernel<8>, dim3((unsigned)groups), dim3(8 * kWave), 0, s, codes, labels,
+                               params, n, m, out);
+        else
+            hipLaunchKernelGGL(dequantize_cluster_parts_kernel<4>, dim3((unsigned)groups), dim3(4 * kWave), 0, s, codes, labels,
+                               params, n, m, out);
         return launch_status();
     }
 #define BITSNAP_LAUNCH_D(KK) \
@@ -516,6 +545,15 @@ extern "C" int bitsnap_dequantize_cluster_batched(const bitsnap_cluster_item *it
         return BITSNAP_E_SIZE;
     const dim3 block(kDListBlock), grid((unsigned)batched_blocks(total_groups, kDListWaves));
     hipStream_t s = (hipStream_t)stream;
+    if (256 * K >= 4 * kDeqPart && total_groups <= 0x7FFFFFFF) {  // groups of 2048 or 4096 elements: a workgroup each
+        if (256 * K == 8 * kDeqPart)
+            hipLaunchKernelGGL(dequantize_cluster_batched_parts_kernel<8>, dim3((unsigned)total_groups), dim3(8 * kWave), 0, s,
+                               items, count, total_groups, m);
+        else
+            hipLaunchKernelGGL(dequantize_cluster_batched_parts_kernel<4>, dim3((unsigned)total_groups), dim3(4 * kWave), 0, s,
+                               items, count, total_groups, m);
+        return launch_status();
+    }
 #define BITSNAP_LAUNCH_DB(KK) \
     hipLaunchKernelGGL(dequantize_cluster_batched_kernel<KK>, grid, block, 0, s, items, count, total_groups, m)
     switch (K) {

@@ -15,9 +15,9 @@ from paper_2511_12376_amd import synth  # noqa: E402
 WORKLOADS = [(1, 0.01), (1, 0.06), (1, 0.2), (2, None), (3, None), (4, None)]
 KERNELS = {
     "batched": ["encode_sparse_kernel<true, false, 2, false>", "decode_merge_kernel<true, false, 0, 2>",
-                "quantize_cluster_batched_kernel<16>", "dequantize_cluster_batched_kernel<16>"],
+                "quantize_cluster_batched_kernel<16>", "dequantize_cluster_batched_parts_kernel<8>"],
     "per-tensor": ["encode_sparse_kernel<false, false, 2, false>", "decode_merge_kernel<false, false, 3, 2>",
-                   "quantize_cluster_kernel<16>", "dequantize_cluster_shared_kernel"],
+                   "quantize_cluster_kernel<16>", "dequantize_cluster_parts_kernel<8>"],
 }
 
 
