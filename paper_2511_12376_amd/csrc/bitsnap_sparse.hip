@@ -9,7 +9,7 @@
 // is processed by one 512-thread workgroup; all of a tile's loads are issued before anything
 // waits on them.  A lane owns pieces of 8 consecutive elements (one mask byte; one or two 16-byte
 // loads); in the encoder a wavefront owns, in each round, two consecutive 512-element chunks, in the
-// decoder's merge one contiguous sixteenth of the tile.  Per-lane popcounts are scanned with DPP inside
+// decoder's merge one contiguous segment of 1024 elements.  Per-lane popcounts are scanned with DPP inside
 // the wave, and in the encoder through LDS across the eight waves and the rounds and by the
 // scanning wave of scan_state.hpp across tiles.  The tile is large because every tile costs the machine one
 // same-address atomic (the ticket; the chip serves 88 million of them per second, one every 11.4 ns)
@@ -546,9 +546,18 @@ __device__ __forceinline__ int64_t find_sparse_item(const bitsnap_sparse_item *_
     return lo;
 }
 
-// Segments per tile in the decoder: a wave of the merge owns one (2048 two-byte or 1024 four-byte elements).  With 8
-// segments of twice the size, single tensors decode 2 to 10 % slower (the smaller the tensor, the more); lists the same.
-constexpr int kDecSegs = 16;
+// Segments per tile in the decoder: a wave of the merge owns one (1024 elements: 2 KB of two-byte, 4 KB of four-byte
+// output).  The lighter the waves, the more evenly reads and writes mix: a plain copy streams at 72-76 % of HBM peak
+// with 4 KB per wave, at 75-80 % with 2 KB; with 16 segments of two-byte elements instead of 32 a pass over a list
+// decodes at 73 instead of 77 % where 71 % of the elements changed (74 and 75 % where 6 % did), with 8 segments
+// single tensors lose another 2 to 10 %.
+template <int E>
+constexpr int kDecSegsOf = E == 2 ? 32 : 16;
+// The segments' places inside their tile are kept as 16-bit numbers, three to a 64-bit word whose upper 16 bits stay
+// zero: whatever a decode leaves in the workspace then reads as "not written" to the encoder's scan (scan_state.hpp).
+template <int E>
+constexpr int kSegWordsOf = (kDecSegsOf<E> + 2) / 3;
+__device__ __forceinline__ int seg_slot(int k) { return (k / 3) * 4 + k % 3; }
 
 // One wave per tile: popcount of the tile's 4 or 2 KB of mask (bits at or beyond n do not count), and the
 // places of the tile's segments inside the tile.
@@ -558,7 +567,7 @@ __global__ __launch_bounds__(kCountWaves * kWave) void decode_count_kernel(bitsn
                                                               const bitsnap_sparse_item *__restrict__ items,
                                                               int64_t count, int64_t num_tiles,
                                                               uint32_t *__restrict__ tile_count,
-                                                              uint32_t *__restrict__ seg_prefix)
+                                                              uint16_t *__restrict__ seg_place)
 {
     const int lane = threadIdx.x & (kWave - 1), wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int64_t gt = (int64_t)blockIdx.x * kCountWaves + wave;
@@ -571,6 +580,7 @@ __global__ __launch_bounds__(kCountWaves * kWave) void decode_count_kernel(bitsn
     static_assert(kPerLane % 8 == 0, "a lane reads whole 8-byte pieces of the mask");
     // Pass q covers 512 consecutive mask bytes, i.e. one or two whole segments (a wave's part of the tile in
     // the merge): the running sums at the segments' last lanes are the segments' places inside the tile.
+    constexpr int kDecSegs = kDecSegsOf<E>;
     constexpr int kSegsPerPass = (kWave * 8) / (Geom<E>::kTileElems / kDecSegs / 8);
     // All of the lane's loads are issued before the first is used.  An 8-byte piece that straddles the end of the
     // mask is read whole (the buffer is 16-byte aligned, so the load stays inside the 16-byte block of the mask's
@@ -600,13 +610,19 @@ __global__ __launch_bounds__(kCountWaves * kWave) void decode_count_kernel(bitsn
 #pragma unroll
         for (int sgm = 0; sgm < kSegsPerPass; ++sgm) {
             const uint32_t inside = sgm == 0 ? 0u : read_lane(incl, sgm == 0 ? 0 : sgm * (kWave / kSegsPerPass) - 1);
-            if (lane == 0)
-                seg_prefix[gt * kDecSegs + q * kSegsPerPass + sgm] = run + inside;
+            if (lane == 0)  // below the tile's 2^15 elements
+                seg_place[gt * (4 * kSegWordsOf<E>) + seg_slot(q * kSegsPerPass + sgm)] = (uint16_t)(run + inside);
         }
         run += read_lane(incl, kWave - 1);
     }
     if (lane == 0)
         tile_count[gt] = run;
+    if (lane < kSegWordsOf<E>) {  // the upper 16 bits of every word, and what the last word has beyond the last segment
+        seg_place[gt * (4 * kSegWordsOf<E>) + 4 * lane + 3] = 0;
+        if (lane == kSegWordsOf<E> - 1)
+            for (int k = kDecSegs; k < 3 * kSegWordsOf<E>; ++k)
+                seg_place[gt * (4 * kSegWordsOf<E>) + seg_slot(k)] = 0;
+    }
 }
 
 // One workgroup per tensor: exclusive scan of its tiles' counts -> payload offset of every tile,
@@ -646,8 +662,7 @@ __global__ __launch_bounds__(kBlock) void decode_scan_kernel(bitsnap_sparse_item
         *it.n_changed = carry_s;
 }
 
-// The merge: out = bit ? next payload element : base.  One wavefront per segment (a sixteenth of a tile: 4 KB
-// of output), each entirely on its own - no barrier anywhere; kMergeWaves of them make a workgroup.  A wave
+// The merge: out = bit ? next payload element : base.  One wavefront per segment (1024 elements), each entirely on its own - no barrier anywhere; kMergeWaves of them make a workgroup.  A wave
 // requests its base pieces, its own mask bytes and the mask bytes between the start of the
 // tile and its segment at once; the popcount of the latter is the segment's place behind the tile's offset
 // (the other waves of the tile read the same few KB, from L2).  Then it fetches its part of the payload as
@@ -670,11 +685,12 @@ constexpr int kCountsTiles = 4096;   // single tensors of up to this many tiles 
 // 77-78 % as 128-thread ones and 74-75 % as single waves.
 constexpr int kMergeWaves = 2;                          // waves (segments) per workgroup
 constexpr int kMergeBlock = kMergeWaves * kWave;
-constexpr int kMergeBlocksPerTile = kDecSegs / kMergeWaves;
+template <int E>
+constexpr int kMergeBlocksPerTileOf = kDecSegsOf<E> / kMergeWaves;
 
 template <int E>
 struct DecGeom {
-    static constexpr int kSegElems = Geom<E>::kTileElems / kDecSegs;    // 2048 two-byte or 1024 four-byte elements
+    static constexpr int kSegElems = Geom<E>::kTileElems / kDecSegsOf<E>;    // 2048 two-byte or 1024 four-byte elements
     static constexpr int kPieces = kSegElems / kChunkElems;             // 512-element pieces per segment: 4 or 2
     static constexpr int kSegMaskBytes = kSegElems / 8;
     static constexpr int kVecsPerLane = kSegElems / Geom<E>::kVecElems / kWave;  // 16-byte payload pieces per lane: 4
@@ -686,7 +702,7 @@ __global__ __launch_bounds__(kMergeBlock) void decode_merge_kernel(bitsnap_spars
                                                                  const bitsnap_sparse_item *__restrict__ items,
                                                                  int64_t count, const uint64_t *__restrict__ tile_offset,
                                                                  const uint32_t *__restrict__ tile_count,
-                                                                 const uint32_t *__restrict__ seg_prefix)
+                                                                 const uint16_t *__restrict__ seg_place)
 {
     typedef typename Geom<E>::elem_t elem_t;
     typedef typename Geom<E>::global_elem_t global_elem_t;
@@ -695,6 +711,7 @@ __global__ __launch_bounds__(kMergeBlock) void decode_merge_kernel(bitsnap_spars
     constexpr uint32_t P = Geom<E>::kVecElems;
     __shared__ alignas(16) elem_t regions[kMergeWaves][kSegElems + 4 * P];  // + a shifted segment's end + what the merge reads past it
     const int tid = threadIdx.x, lane = tid & (kWave - 1), local_wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    constexpr int kDecSegs = kDecSegsOf<E>, kMergeBlocksPerTile = kMergeBlocksPerTileOf<E>;
     const int64_t gtile = blockIdx.x / kMergeBlocksPerTile;
     const int wave = (int)(blockIdx.x % kMergeBlocksPerTile) * kMergeWaves + local_wave;  // the segment inside the tile
     const bitsnap_sparse_item &it = kBatched ? items[find_sparse_item(items, count, gtile)] : single;
@@ -718,7 +735,6 @@ __global__ __launch_bounds__(kMergeBlock) void decode_merge_kernel(bitsnap_spars
     // anything else is requested, so that waiting for these few words does not mean waiting for the base as well
     // (loads return in the order they were issued).
     uint64_t known_start = 0;
-    uint32_t known_count = 0;
     if (kSource == kFromWorkspace || kSource == kFromCounts) {
         uint64_t tile_excl;
         if (kSource == kFromCounts) {
@@ -747,10 +763,14 @@ __global__ __launch_bounds__(kMergeBlock) void decode_merge_kernel(bitsnap_spars
         } else {
             tile_excl = uniform64(tile_offset[gtile]);
         }
-        const uint32_t here = __builtin_amdgcn_readfirstlane(seg_prefix[gtile * kDecSegs + wave]);
-        const uint32_t next = __builtin_amdgcn_readfirstlane(wave + 1 < kDecSegs ? seg_prefix[gtile * kDecSegs + wave + 1] : tile_count[gtile]);
-        known_start = tile_excl + here;
-        known_count = next - here;
+        known_start = tile_excl;
+    }
+    uint32_t seg_before = 0, seg_mine = 0;
+    if (kSource == kFromWorkspace || kSource == kFromCounts) {
+        const uint16_t *__restrict__ places = seg_place + gtile * (4 * kSegWordsOf<E>);
+        seg_before = __builtin_amdgcn_readfirstlane(places[seg_slot(wave)]);
+        const uint32_t next = __builtin_amdgcn_readfirstlane(wave + 1 < kDecSegs ? places[seg_slot(wave + 1)] : tile_count[gtile]);
+        seg_mine = next - seg_before;
     }
 
     // base: a 16-byte load whose first element lies at or beyond the end of the tensor reads the segment's first
@@ -806,8 +826,8 @@ __global__ __launch_bounds__(kMergeBlock) void decode_merge_kernel(bitsnap_spars
         }
     };
     if (kSource == kFromWorkspace || kSource == kFromCounts) {
-        start = known_start;
-        seg_count = known_count;
+        start = known_start + seg_before;
+        seg_count = seg_mine;
         request_payload();
     }
     // ranks inside the segment
@@ -889,11 +909,12 @@ __global__ __launch_bounds__(kMergeBlock) void decode_merge_kernel(bitsnap_spars
 
 // Workspace after the header: encode keeps its count and prefix words there (scan_state.hpp: 8 bytes per tile,
 // then, from a 128-byte boundary, 64 bytes per tile); decode keeps the tiles' payload offsets (8 bytes each)
-// followed by their counts (4 bytes each) and the places of their segments (16 x 4 bytes each).
-// A raw offset is below 2^40 and a count or a place below 2^16, so as scan words their flag bits read "not
-// written": a decode never confuses a later encode.
+// followed by their counts (4 bytes each) and the places of their segments (up to 11 words of three 16-bit places).
+// A raw offset is below 2^40, a tile's count at most 2^15 in 32 bits, and the upper 16 bits of a word of places are
+// zero, so as scan words their two flag bits read "not written": a decode never confuses a later encode.
 constexpr size_t kWorkspaceBytesPerTile = kScanBytesPerTile;
-static_assert(kWorkspaceBytesPerTile >= 12 + 4 * kDecSegs, "decode keeps 8 + 4 + 4 * segments bytes per tile");
+static_assert(kWorkspaceBytesPerTile >= 16 + 8 * kSegWordsOf<2> && kWorkspaceBytesPerTile >= 16 + 8 * kSegWordsOf<4>,
+              "decode keeps 8 + 4 (+ 4 once) + 8 * ceil(segments / 3) bytes per tile");
 
 static std::atomic<uint32_t> g_spin_limit{kDefaultSpinLimit};
 
@@ -991,13 +1012,20 @@ static int check_scan_workspace(void *workspace, size_t workspace_bytes, int64_t
     return BITSNAP_OK;
 }
 
+// The segments' places follow the tiles' counts, from the next 8-byte boundary: their words must be words of the scan too.
+static uint16_t *seg_places_of(const uint32_t *tile_count, int64_t num_tiles)
+{
+    return reinterpret_cast<uint16_t *>(const_cast<uint32_t *>(tile_count) + ((num_tiles + 1) & ~(int64_t)1));
+}
+
 template <bool kBatched, bool kDelta, int kSource, int E>
 static void launch_merge(const bitsnap_sparse_item &single, const bitsnap_sparse_item *items, int64_t count,
                          int64_t num_tiles, const uint64_t *tile_offset, hipStream_t s)
 {
     const uint32_t *tile_count = reinterpret_cast<const uint32_t *>(tile_offset + num_tiles);
-    hipLaunchKernelGGL((decode_merge_kernel<kBatched, kDelta, kSource, E>), dim3((unsigned)(num_tiles * kMergeBlocksPerTile)),
-                       dim3(kMergeBlock), 0, s, single, items, count, tile_offset, tile_count, tile_count + num_tiles);
+    hipLaunchKernelGGL((decode_merge_kernel<kBatched, kDelta, kSource, E>), dim3((unsigned)(num_tiles * kMergeBlocksPerTileOf<E>)),
+                       dim3(kMergeBlock), 0, s, single, items, count, tile_offset, tile_count,
+                       seg_places_of(tile_count, num_tiles));
 }
 
 template <bool kBatched, int E>
@@ -1007,7 +1035,7 @@ static int launch_decode_e(const bitsnap_sparse_item &single, const bitsnap_spar
     uint64_t *tile_offset = reinterpret_cast<uint64_t *>(reinterpret_cast<char *>(workspace) + kScanHeaderBytes);
     uint32_t *tile_count = reinterpret_cast<uint32_t *>(tile_offset + num_tiles);
     hipStream_t s = (hipStream_t)stream;
-    if (num_tiles > 0x7FFFFFFF / kMergeBlocksPerTile)
+    if (num_tiles > 0x7FFFFFFF / kMergeBlocksPerTileOf<E>)
         return BITSNAP_E_SIZE;
     if (offsets && num_tiles > 0) {  // the encoder's tile offsets are given: one launch, nothing to count
         if (delta)
@@ -1018,7 +1046,8 @@ static int launch_decode_e(const bitsnap_sparse_item &single, const bitsnap_spar
     }
     if (!kBatched && num_tiles > kSoloTiles && num_tiles <= kCountsTiles) {  // counting kernel, then the merge adds up the counts
         hipLaunchKernelGGL((decode_count_kernel<kBatched, E>), dim3((unsigned)((num_tiles + kCountWaves - 1) / kCountWaves)),
-                           dim3(kCountWaves * kWave), 0, s, single, items, count, num_tiles, tile_count, tile_count + num_tiles);
+                           dim3(kCountWaves * kWave), 0, s, single, items, count, num_tiles, tile_count,
+                           seg_places_of(tile_count, num_tiles));
         if (delta)
             launch_merge<kBatched, true, kFromCounts, E>(single, items, count, num_tiles, tile_offset, s);
         else
@@ -1034,7 +1063,8 @@ static int launch_decode_e(const bitsnap_sparse_item &single, const bitsnap_spar
     }
     if (num_tiles > 0)
         hipLaunchKernelGGL((decode_count_kernel<kBatched, E>), dim3((unsigned)((num_tiles + kCountWaves - 1) / kCountWaves)),
-                           dim3(kCountWaves * kWave), 0, s, single, items, count, num_tiles, tile_count, tile_count + num_tiles);
+                           dim3(kCountWaves * kWave), 0, s, single, items, count, num_tiles, tile_count,
+                           seg_places_of(tile_count, num_tiles));
     // the scan also reports n_changed, for an empty tensor too
     hipLaunchKernelGGL((decode_scan_kernel<kBatched, E>), dim3((unsigned)(kBatched ? count : 1)), dim3(kBlock), 0, s,
                        single, items, tile_count, tile_offset);

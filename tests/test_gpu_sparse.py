@@ -105,6 +105,47 @@ def test_decode_on_both_sides_of_its_launch_plans(tiles, elem_bytes):
     assert int(cnt2.item()) == o_nc and np.array_equal(to_np(inplace).view(dt), cur)
 
 
+@pytest.mark.parametrize("tiles", [9, 1377, 4099])
+@pytest.mark.parametrize("elem_bytes", [2, 4])
+def test_decode_leaves_nothing_the_encoders_scan_could_read_as_written(tiles, elem_bytes):
+    """Decode and encode share a workspace.  The encoder's scan takes a 64-bit word for written only if its two
+    top bits are set and its tag equals the call's; whatever the decoder keeps there (tile offsets, tile counts,
+    the segments' places) must keep those two bits clear, also for tiles whose every element changed, where the
+    places are largest, and for an odd number of tiles, where the places do not start on the counts' last word.
+    An encode that follows with the same workspace, at whatever tag, matches the oracle."""
+    announce("sparse decode leaves scan words unwritten", tiles, elem_bytes)
+    te = B.sparse_tile_elems(elem_bytes)
+    n = (tiles - 1) * te + te // 2 + 3
+    rng = np.random.default_rng(7100 + tiles + elem_bytes)
+    dt = np.uint16 if elem_bytes == 2 else np.uint32
+    base = rng.integers(0, 1 << 16, n, dtype=np.uint16).astype(dt)
+    cur = base ^ dt(1)                                              # every element changed
+    cur[rng.integers(0, n, n // 50)] ^= dt(1)                       # ... but for a few
+    as_dev = lambda a: torch.from_numpy(a.view(np.int16 if elem_bytes == 2 else np.int32)).to(DEV)
+    o_mask, o_pay, o_nc = (oracle.encode_sparse if elem_bytes == 2 else oracle.encode_sparse32)(cur, base)
+    ws = B.new_sparse_workspace(n, DEV, elem_bytes)
+    mask_d = torch.zeros(max(B.sparse_mask_bytes(n), 16), dtype=torch.uint8, device=DEV)
+    mask_d[: o_mask.size] = torch.from_numpy(o_mask).to(DEV)
+    pay_d = as_dev(np.concatenate([o_pay, np.zeros(8, dt)]))
+    out, cnt = B.decode_sparse(as_dev(base), mask_d, pay_d, o_nc, workspace=ws)
+    torch.cuda.synchronize()
+    assert int(cnt.item()) == o_nc and np.array_equal(to_np(out).view(dt), cur)
+    words = to_np(ws[256:256 + (ws.numel() - 256) // 8 * 8]).view(np.uint64)
+    assert words.any() and not (words >> np.uint64(62)).any()
+    hdr = ws[:16].view(torch.int32)
+    tags = sorted({int(w >> np.uint64(40)) for w in words[words != 0][-400:]})
+    for tag in tags[:3] + tags[-3:]:
+        B.decode_sparse(as_dev(base), mask_d, pay_d, o_nc, workspace=ws)
+        torch.cuda.synchronize()
+        hdr[2] = tag                                                # the tag some word of the decode happens to carry
+        torch.cuda.synchronize()
+        enc = B.encode_sparse(as_dev(cur), as_dev(base), workspace=ws)
+        torch.cuda.synchronize()
+        assert int(enc.n_changed.item()) == o_nc
+        assert np.array_equal(to_np(enc.mask)[: o_mask.size], o_mask)
+        assert np.array_equal(to_np(enc.payload).view(dt)[:o_nc], o_pay)
+
+
 def test_decode_in_place_and_special_patterns():
     announce("sparse in-place / -0 / NaN")
     pats = np.array([0x0000, 0x8000, 0x7FC1, 0x7FC2, 0x7F80, 0x0001], np.uint16)
