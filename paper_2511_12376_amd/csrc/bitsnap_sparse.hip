@@ -546,23 +546,29 @@ __device__ __forceinline__ int64_t find_sparse_item(const bitsnap_sparse_item *_
     return lo;
 }
 
-// Segments per tile in the decoder: a wave of the merge owns one (1024 elements: 2 KB of two-byte, 4 KB of four-byte
-// output).  The lighter the waves, the more evenly reads and writes mix: a plain copy streams at 72-76 % of HBM peak
-// with 4 KB per wave, at 75-80 % with 2 KB; with 16 segments of two-byte elements instead of 32 a pass over a list
-// decodes at 73 instead of 77 % where 71 % of the elements changed (74 and 75 % where 6 % did), with 8 segments
-// single tensors lose another 2 to 10 %.
-template <int E>
-constexpr int kDecSegsOf = E == 2 ? 32 : 16;
+// Where a tile's offset in the payload comes from in the merge (see decode_merge_kernel).
+enum { kFromWorkspace = 0, kFromEncoder = 1, kFromMask = 2, kFromCounts = 3 };
+// Segments per tile in the decoder: a wave of the merge owns one.  The lighter the waves, the more evenly reads and
+// writes mix: a plain copy streams at 72-76 % of HBM peak with 4 KB per wave, at 75-80 % with 2 KB; with 16 segments
+// of two-byte elements instead of 32 a pass over a list decodes at 73 instead of 77 % where 71 % of the elements
+// changed (74 and 75 % where 6 % did), with 8 segments single tensors lose another 2 to 10 %.  That holds where a
+// wave is handed its place (kFromWorkspace).  Where it works its place out itself - from the counts of the earlier
+// tiles, from the mask of its own tile or of the tensor before it - twice the waves do twice that work, and 32
+// segments are slower than 16: the 131 M-element tensor decodes in 0.156 instead of 0.120 ms, a list with the
+// encoder's tile offsets at 58 instead of 73 % of peak.
+template <int E, int kSource>
+constexpr int kDecSegsOf = (E == 2 && kSource == kFromWorkspace) ? 32 : 16;
+constexpr int kMaxDecSegs = 32;
 // The segments' places inside their tile are kept as 16-bit numbers, three to a 64-bit word whose upper 16 bits stay
 // zero: whatever a decode leaves in the workspace then reads as "not written" to the encoder's scan (scan_state.hpp).
-template <int E>
-constexpr int kSegWordsOf = (kDecSegsOf<E> + 2) / 3;
+template <int S>
+constexpr int kSegWordsOf = (S + 2) / 3;
 __device__ __forceinline__ int seg_slot(int k) { return (k / 3) * 4 + k % 3; }
 
 // One wave per tile: popcount of the tile's 4 or 2 KB of mask (bits at or beyond n do not count), and the
 // places of the tile's segments inside the tile.
 constexpr int kCountWaves = 2;  // tiles per workgroup of the counting kernel (small workgroups: see kMergeWaves)
-template <bool kBatched, int E>
+template <bool kBatched, int E, int S>  // S: segments per tile
 __global__ __launch_bounds__(kCountWaves * kWave) void decode_count_kernel(bitsnap_sparse_item single,
                                                               const bitsnap_sparse_item *__restrict__ items,
                                                               int64_t count, int64_t num_tiles,
@@ -580,7 +586,7 @@ __global__ __launch_bounds__(kCountWaves * kWave) void decode_count_kernel(bitsn
     static_assert(kPerLane % 8 == 0, "a lane reads whole 8-byte pieces of the mask");
     // Pass q covers 512 consecutive mask bytes, i.e. one or two whole segments (a wave's part of the tile in
     // the merge): the running sums at the segments' last lanes are the segments' places inside the tile.
-    constexpr int kDecSegs = kDecSegsOf<E>;
+    constexpr int kDecSegs = S;
     constexpr int kSegsPerPass = (kWave * 8) / (Geom<E>::kTileElems / kDecSegs / 8);
     // All of the lane's loads are issued before the first is used.  An 8-byte piece that straddles the end of the
     // mask is read whole (the buffer is 16-byte aligned, so the load stays inside the 16-byte block of the mask's
@@ -611,17 +617,17 @@ __global__ __launch_bounds__(kCountWaves * kWave) void decode_count_kernel(bitsn
         for (int sgm = 0; sgm < kSegsPerPass; ++sgm) {
             const uint32_t inside = sgm == 0 ? 0u : read_lane(incl, sgm == 0 ? 0 : sgm * (kWave / kSegsPerPass) - 1);
             if (lane == 0)  // below the tile's 2^15 elements
-                seg_place[gt * (4 * kSegWordsOf<E>) + seg_slot(q * kSegsPerPass + sgm)] = (uint16_t)(run + inside);
+                seg_place[gt * (4 * kSegWordsOf<S>) + seg_slot(q * kSegsPerPass + sgm)] = (uint16_t)(run + inside);
         }
         run += read_lane(incl, kWave - 1);
     }
     if (lane == 0)
         tile_count[gt] = run;
-    if (lane < kSegWordsOf<E>) {  // the upper 16 bits of every word, and what the last word has beyond the last segment
-        seg_place[gt * (4 * kSegWordsOf<E>) + 4 * lane + 3] = 0;
-        if (lane == kSegWordsOf<E> - 1)
-            for (int k = kDecSegs; k < 3 * kSegWordsOf<E>; ++k)
-                seg_place[gt * (4 * kSegWordsOf<E>) + seg_slot(k)] = 0;
+    if (lane < kSegWordsOf<S>) {  // the upper 16 bits of every word, and what the last word has beyond the last segment
+        seg_place[gt * (4 * kSegWordsOf<S>) + 4 * lane + 3] = 0;
+        if (lane == kSegWordsOf<S> - 1)
+            for (int k = kDecSegs; k < 3 * kSegWordsOf<S>; ++k)
+                seg_place[gt * (4 * kSegWordsOf<S>) + seg_slot(k)] = 0;
     }
 }
 
@@ -676,7 +682,6 @@ __global__ __launch_bounds__(kBlock) void decode_scan_kernel(bitsnap_sparse_item
 // tiles itself, a few KB from L2, which saves a single tensor of moderate size the scanning launch), the
 // encoder's tile_offsets (kFromEncoder), or nowhere: the wave counts the tensor's whole mask before its
 // segment itself (kFromMask; tensors of a few tiles, decoded by this one launch).
-enum { kFromWorkspace = 0, kFromEncoder = 1, kFromMask = 2, kFromCounts = 3 };
 constexpr int kSoloTiles = 8;        // single tensors of up to this many tiles take kFromMask
 constexpr int kCountsTiles = 4096;   // single tensors of up to this many tiles take kFromCounts (offsets stay below 2^32)
 // Waves of a tile do not cooperate, so the workgroup is only the unit in which the hardware hands out wave
@@ -685,13 +690,13 @@ constexpr int kCountsTiles = 4096;   // single tensors of up to this many tiles 
 // 77-78 % as 128-thread ones and 74-75 % as single waves.
 constexpr int kMergeWaves = 2;                          // waves (segments) per workgroup
 constexpr int kMergeBlock = kMergeWaves * kWave;
-template <int E>
-constexpr int kMergeBlocksPerTileOf = kDecSegsOf<E> / kMergeWaves;
+template <int E, int kSource>
+constexpr int kMergeBlocksPerTileOf = kDecSegsOf<E, kSource> / kMergeWaves;
 
-template <int E>
+template <int E, int S>
 struct DecGeom {
-    static constexpr int kSegElems = Geom<E>::kTileElems / kDecSegsOf<E>;    // 2048 two-byte or 1024 four-byte elements
-    static constexpr int kPieces = kSegElems / kChunkElems;             // 512-element pieces per segment: 4 or 2
+    static constexpr int kSegElems = Geom<E>::kTileElems / S;           // 1024 or 2048 two-byte, 1024 four-byte elements
+    static constexpr int kPieces = kSegElems / kChunkElems;             // 512-element pieces per segment: 2 or 4
     static constexpr int kSegMaskBytes = kSegElems / 8;
     static constexpr int kVecsPerLane = kSegElems / Geom<E>::kVecElems / kWave;  // 16-byte payload pieces per lane: 4
     static_assert(kPieces % 2 == 0, "counts are scanned two to a word");
@@ -706,12 +711,13 @@ __global__ __launch_bounds__(kMergeBlock) void decode_merge_kernel(bitsnap_spars
 {
     typedef typename Geom<E>::elem_t elem_t;
     typedef typename Geom<E>::global_elem_t global_elem_t;
-    constexpr int kTileElems = Geom<E>::kTileElems, kSegElems = DecGeom<E>::kSegElems, kPieces = DecGeom<E>::kPieces,
-                  kVecs = Geom<E>::kVecs, kVecElems = Geom<E>::kVecElems, kVecsPerLane = DecGeom<E>::kVecsPerLane;
+    constexpr int kDecSegs = kDecSegsOf<E, kSource>, kMergeBlocksPerTile = kMergeBlocksPerTileOf<E, kSource>;
+    typedef DecGeom<E, kDecSegs> SegGeom;
+    constexpr int kTileElems = Geom<E>::kTileElems, kSegElems = SegGeom::kSegElems, kPieces = SegGeom::kPieces,
+                  kVecs = Geom<E>::kVecs, kVecElems = Geom<E>::kVecElems, kVecsPerLane = SegGeom::kVecsPerLane;
     constexpr uint32_t P = Geom<E>::kVecElems;
     __shared__ alignas(16) elem_t regions[kMergeWaves][kSegElems + 4 * P];  // + a shifted segment's end + what the merge reads past it
     const int tid = threadIdx.x, lane = tid & (kWave - 1), local_wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    constexpr int kDecSegs = kDecSegsOf<E>, kMergeBlocksPerTile = kMergeBlocksPerTileOf<E>;
     const int64_t gtile = blockIdx.x / kMergeBlocksPerTile;
     const int wave = (int)(blockIdx.x % kMergeBlocksPerTile) * kMergeWaves + local_wave;  // the segment inside the tile
     const bitsnap_sparse_item &it = kBatched ? items[find_sparse_item(items, count, gtile)] : single;
@@ -767,7 +773,7 @@ __global__ __launch_bounds__(kMergeBlock) void decode_merge_kernel(bitsnap_spars
     }
     uint32_t seg_before = 0, seg_mine = 0;
     if (kSource == kFromWorkspace || kSource == kFromCounts) {
-        const uint16_t *__restrict__ places = seg_place + gtile * (4 * kSegWordsOf<E>);
+        const uint16_t *__restrict__ places = seg_place + gtile * (4 * kSegWordsOf<kDecSegs>);
         seg_before = __builtin_amdgcn_readfirstlane(places[seg_slot(wave)]);
         const uint32_t next = __builtin_amdgcn_readfirstlane(wave + 1 < kDecSegs ? places[seg_slot(wave + 1)] : tile_count[gtile]);
         seg_mine = next - seg_before;
@@ -913,7 +919,7 @@ __global__ __launch_bounds__(kMergeBlock) void decode_merge_kernel(bitsnap_spars
 // A raw offset is below 2^40, a tile's count at most 2^15 in 32 bits, and the upper 16 bits of a word of places are
 // zero, so as scan words their two flag bits read "not written": a decode never confuses a later encode.
 constexpr size_t kWorkspaceBytesPerTile = kScanBytesPerTile;
-static_assert(kWorkspaceBytesPerTile >= 16 + 8 * kSegWordsOf<2> && kWorkspaceBytesPerTile >= 16 + 8 * kSegWordsOf<4>,
+static_assert(kWorkspaceBytesPerTile >= 16 + 8 * kSegWordsOf<kMaxDecSegs>,
               "decode keeps 8 + 4 (+ 4 once) + 8 * ceil(segments / 3) bytes per tile");
 
 static std::atomic<uint32_t> g_spin_limit{kDefaultSpinLimit};
@@ -1023,7 +1029,7 @@ static void launch_merge(const bitsnap_sparse_item &single, const bitsnap_sparse
                          int64_t num_tiles, const uint64_t *tile_offset, hipStream_t s)
 {
     const uint32_t *tile_count = reinterpret_cast<const uint32_t *>(tile_offset + num_tiles);
-    hipLaunchKernelGGL((decode_merge_kernel<kBatched, kDelta, kSource, E>), dim3((unsigned)(num_tiles * kMergeBlocksPerTileOf<E>)),
+    hipLaunchKernelGGL((decode_merge_kernel<kBatched, kDelta, kSource, E>), dim3((unsigned)(num_tiles * kMergeBlocksPerTileOf<E, kSource>)),
                        dim3(kMergeBlock), 0, s, single, items, count, tile_offset, tile_count,
                        seg_places_of(tile_count, num_tiles));
 }
@@ -1035,7 +1041,7 @@ static int launch_decode_e(const bitsnap_sparse_item &single, const bitsnap_spar
     uint64_t *tile_offset = reinterpret_cast<uint64_t *>(reinterpret_cast<char *>(workspace) + kScanHeaderBytes);
     uint32_t *tile_count = reinterpret_cast<uint32_t *>(tile_offset + num_tiles);
     hipStream_t s = (hipStream_t)stream;
-    if (num_tiles > 0x7FFFFFFF / kMergeBlocksPerTileOf<E>)
+    if (num_tiles > 0x7FFFFFFF / (kMaxDecSegs / kMergeWaves))
         return BITSNAP_E_SIZE;
     if (offsets && num_tiles > 0) {  // the encoder's tile offsets are given: one launch, nothing to count
         if (delta)
@@ -1045,7 +1051,7 @@ static int launch_decode_e(const bitsnap_sparse_item &single, const bitsnap_spar
         return launch_status();
     }
     if (!kBatched && num_tiles > kSoloTiles && num_tiles <= kCountsTiles) {  // counting kernel, then the merge adds up the counts
-        hipLaunchKernelGGL((decode_count_kernel<kBatched, E>), dim3((unsigned)((num_tiles + kCountWaves - 1) / kCountWaves)),
+        hipLaunchKernelGGL((decode_count_kernel<kBatched, E, kDecSegsOf<E, kFromCounts>>), dim3((unsigned)((num_tiles + kCountWaves - 1) / kCountWaves)),
                            dim3(kCountWaves * kWave), 0, s, single, items, count, num_tiles, tile_count,
                            seg_places_of(tile_count, num_tiles));
         if (delta)
@@ -1062,7 +1068,7 @@ static int launch_decode_e(const bitsnap_sparse_item &single, const bitsnap_spar
         return launch_status();
     }
     if (num_tiles > 0)
-        hipLaunchKernelGGL((decode_count_kernel<kBatched, E>), dim3((unsigned)((num_tiles + kCountWaves - 1) / kCountWaves)),
+        hipLaunchKernelGGL((decode_count_kernel<kBatched, E, kDecSegsOf<E, kFromWorkspace>>), dim3((unsigned)((num_tiles + kCountWaves - 1) / kCountWaves)),
                            dim3(kCountWaves * kWave), 0, s, single, items, count, num_tiles, tile_count,
                            seg_places_of(tile_count, num_tiles));
     // the scan also reports n_changed, for an empty tensor too
