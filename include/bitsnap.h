@@ -165,9 +165,10 @@ int bitsnap_encode_sparse_ex(const void *cur, const void *base, int64_t n, int e
 /* bitsnap_decode_sparse for a payload written with the same flags:
  * out[i] = bit i of mask ? (DELTA ? base[i] XOR next payload element : next payload element) : base[i].
  *   tile_offsets  nullable; [ceil(n / tile_elems)] uint32 in: the array the encoder wrote for this
- *                 tensor.  With it the decoder does not count the mask first (one launch instead of
- *                 three); n must be below 2^32, and payload_elems must not be below the number of
- *                 changed elements.  Offsets that do not belong to the mask give unspecified output
+ *                 tensor.  With it the decoder need not count the mask first (one launch instead of
+ *                 two or three; it does so for tensors of up to 2048 tiles, where that is faster,
+ *                 and counts as usual beyond); n must be below 2^32, and payload_elems must not be
+ *                 below the number of changed elements.  Offsets that do not belong to the mask give unspecified output
  *                 values, inside out[0..n). */
 int bitsnap_decode_sparse_ex(const void *base, const uint8_t *mask, const void *payload,
                              int64_t payload_elems, int64_t n, int elem_bytes, uint32_t flags,
@@ -338,7 +339,8 @@ int bitsnap_decode_sparse_batched(const bitsnap_sparse_item *items, int64_t coun
  * element width (2 or 4; first_tile and total_tiles count tiles of bitsnap_sparse_tile_elems_for(elem_bytes)
  * elements).  In the encoder an item's `out`, where not NULL, is that tensor's new_base.  The decoder
  * takes BITSNAP_SPARSE_OFFSETS: every item's tile_offsets is the array the encoder wrote (every
- * n < 2^32; the caller sees to that), and the list is decoded in one launch. */
+ * n < 2^32; the caller sees to that), and a list of up to 2048 tiles is decoded in one launch (a longer
+ * one is faster with the counting launches, and its offsets are left unused). */
 int bitsnap_encode_sparse_batched_ex(const bitsnap_sparse_item *items, int64_t count, int64_t total_tiles,
                                      int elem_bytes, uint32_t flags, void *workspace, size_t workspace_bytes,
                                      bitsnap_stream_t stream);

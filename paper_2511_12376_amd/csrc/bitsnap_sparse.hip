@@ -668,7 +668,8 @@ __global__ __launch_bounds__(kBlock) void decode_scan_kernel(bitsnap_sparse_item
         *it.n_changed = carry_s;
 }
 
-// The merge: out = bit ? next payload element : base.  One wavefront per segment (1024 elements), each entirely on its own - no barrier anywhere; kMergeWaves of them make a workgroup.  A wave
+// The merge: out = bit ? next payload element : base.  One wavefront per segment (1024 or 2048 elements, see
+// kDecSegsOf), each entirely on its own - no barrier anywhere; kMergeWaves of them make a workgroup.  A wave
 // requests its base pieces, its own mask bytes and the mask bytes between the start of the
 // tile and its segment at once; the popcount of the latter is the segment's place behind the tile's offset
 // (the other waves of the tile read the same few KB, from L2).  Then it fetches its part of the payload as
@@ -684,6 +685,7 @@ __global__ __launch_bounds__(kBlock) void decode_scan_kernel(bitsnap_sparse_item
 // segment itself (kFromMask; tensors of a few tiles, decoded by this one launch).
 constexpr int kSoloTiles = 8;        // single tensors of up to this many tiles take kFromMask
 constexpr int kCountsTiles = 4096;   // single tensors of up to this many tiles take kFromCounts (offsets stay below 2^32)
+constexpr int kOffsetsTiles = 2048;  // a call with the encoder's tile offsets uses them (kFromEncoder) up to this many tiles
 // Waves of a tile do not cooperate, so the workgroup is only the unit in which the hardware hands out wave
 // slots and LDS: a new workgroup starts when a whole one has left.  With the byte mix of this kernel and no
 // logic, 16 waves per CU stream at 67-70 % of HBM peak as 512-thread workgroups, 72-74 % as 256-thread ones,
@@ -1043,7 +1045,11 @@ static int launch_decode_e(const bitsnap_sparse_item &single, const bitsnap_spar
     hipStream_t s = (hipStream_t)stream;
     if (num_tiles > 0x7FFFFFFF / (kMaxDecSegs / kMergeWaves))
         return BITSNAP_E_SIZE;
-    if (offsets && num_tiles > 0) {  // the encoder's tile offsets are given: one launch, nothing to count
+    // The encoder's tile offsets are given: one launch, in which every wave counts inside its tile.  That saves a
+    // tensor (or a list) of up to a few thousand tiles 2-3 us; beyond, the launches that hand every wave its place
+    // are faster (131 M two-byte elements: 114-133 against 117-140 us, 6.7 G in a list: 6.4 against 6.7 ms), and
+    // the offsets are left unused.
+    if (offsets && num_tiles > 0 && num_tiles <= kOffsetsTiles) {
         if (delta)
             launch_merge<kBatched, true, kFromEncoder, E>(single, items, count, num_tiles, tile_offset, s);
         else

@@ -64,12 +64,13 @@ def test_encode_decode_match_oracle(n, p):
     assert np.array_equal(dev_to_u16(out2), o_out)
 
 
-@pytest.mark.parametrize("tiles", [8, 9, 10, 511, 1376, 2049, 4095, 4096, 4097])
+@pytest.mark.parametrize("tiles", [8, 9, 10, 511, 1376, 2048, 2049, 4095, 4096, 4097])
 @pytest.mark.parametrize("elem_bytes", [2, 4])
 def test_decode_on_both_sides_of_its_launch_plans(tiles, elem_bytes):
     """A single tensor is decoded by one launch up to 8 tiles, by two (counting kernel + merge that adds up the
-    tile counts itself) up to 4096, by three beyond; the last tile is ragged, the changed fraction differs from
-    tile to tile, and the decoder runs on the oracle's bytes, also in place."""
+    tile counts itself) up to 4096, by three beyond; with the encoder's tile offsets by one launch up to 2048
+    tiles and as without them beyond; the last tile is ragged, the changed fraction differs from tile to tile, and
+    the decoder runs on the oracle's bytes, also in place."""
     announce("sparse decode launch plans", tiles, elem_bytes)
     te = B.sparse_tile_elems(elem_bytes)
     n = (tiles - 1) * te + 4097
@@ -103,6 +104,10 @@ def test_decode_on_both_sides_of_its_launch_plans(tiles, elem_bytes):
     out2, cnt2 = B.decode_sparse(inplace, mask_d, pay_d, o_nc, out=inplace)
     torch.cuda.synchronize()
     assert int(cnt2.item()) == o_nc and np.array_equal(to_np(inplace).view(dt), cur)
+    offs = oracle.tile_offsets(o_mask, n, te)[:tiles].astype(np.uint32)
+    out3, cnt3 = B.decode_sparse(base_d, mask_d, pay_d, o_nc, tile_offsets=torch.from_numpy(offs.view(np.int32)).to(DEV))
+    torch.cuda.synchronize()
+    assert int(cnt3.item()) == o_nc and np.array_equal(to_np(out3).view(dt), cur)
 
 
 @pytest.mark.parametrize("tiles", [9, 1377, 4099])
